@@ -1,0 +1,126 @@
+"""CPU oracle for the SAGA-NN layer: test infrastructure only.
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg may import
+this package. It never imports the HIP package, and the HIP package never
+imports it. The arithmetic lives in saga_oracle.c (plain C loops, fp64
+accumulation) and follows Section 2 (SAGA-NN stages, Example 2.1, Figure 2),
+Figures 9 and 10 (CommNet and GCN programs) and Section 3.2 (hoisting) of the
+NGra paper; this file only marshals numpy arrays into it.
+
+Parity pins (tests/test_oracle_pins.py): dense brute force with numpy, the
+sparse-dense product identity of Section 6.1 via scipy.sparse, the in-degree
+invariant, brute-force max over the raw edge list, gated special cases that
+reduce to the other edge functions, a dense broadcast formulation of the gate,
+hoisted == naive, and hand-worked values under tests/golden/.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from .build import LIB, build
+
+EDGE_OPS = {"copy": 0, "mul_weight": 1, "gated": 2}
+AGGS = {"sum": 0, "max": 1}
+ACTS = {"none": 0, "relu": 1}
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            build()
+        L = ctypes.CDLL(LIB)
+        P, I64, I = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.saga_oracle_num_threads.restype = I
+        L.saga_oracle_hoist.restype = I
+        L.saga_oracle_hoist.argtypes = [I64, P, I64, P, P, P, P, P]
+        L.saga_oracle_layer.restype = I
+        L.saga_oracle_layer.argtypes = [I64, P, P, P, I64, I, P, P, P, P, P, P, P, I,
+                                        P, P, I64, I, P, I64, P, P, P, P]
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().saga_oracle_num_threads())
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def hoist(X, W_gate, W_msg=None):
+    """Per-vertex products (Ps, Pd, M) of Section 3.2, fp64 arrays n x F."""
+    X = _f32(X)
+    n, F = X.shape
+    Wg, Wm = _f32(W_gate), _f32(W_msg)
+    assert Wg.shape == (F, 2 * F) and (Wm is None or Wm.shape == (F, F))
+    Ps, Pd, M = (np.empty((n, F), np.float64) for _ in range(3))
+    rc = lib().saga_oracle_hoist(n, _ptr(X), F, _ptr(Wg), _ptr(Wm), _ptr(Ps), _ptr(Pd), _ptr(M))
+    assert rc == 0
+    return Ps, Pd, M
+
+
+def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_gate=None, W_msg=None,
+          agg="sum", W=None, bias=None, act="none", vlist=None, hoisted=None, want_abs=True):
+    """Run one layer on the CPU oracle.
+
+    Returns a dict with fp64 arrays: "A" (Gather output, nv x F), "A_abs",
+    and, when W is given, "Y" (nv x F_out) and "Y_abs". vlist selects the
+    destination vertices (default: all, in order). hoisted = (Ps, Pd, M) from
+    hoist() switches the gated message to the hoisted form.
+    """
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    X = _f32(X)
+    n, F = X.shape
+    assert col_ptr.shape == (n + 1,) and int(col_ptr[-1]) == row_idx.shape[0]
+    w = _f32(edge_weight)
+    Wg, bg, Wm = _f32(W_gate), _f32(b_gate), _f32(W_msg)
+    if Wg is not None:
+        assert Wg.shape == (F, 2 * F)
+    if Wm is not None:
+        assert Wm.shape == (F, F)
+    if bg is not None:
+        assert bg.shape == (F,)
+    if w is not None:
+        assert w.shape == (row_idx.shape[0],)
+    Wv, bv = _f32(W), _f32(bias)
+    F_out = 0
+    if Wv is not None:
+        assert Wv.shape[0] == F
+        F_out = Wv.shape[1]
+        if bv is not None:
+            assert bv.shape == (F_out,)
+    if vlist is None:
+        vl, nv = None, n
+    else:
+        vl = np.ascontiguousarray(np.asarray(vlist, dtype=np.int64))
+        nv = vl.shape[0]
+    Ps = Pd = M = None
+    if hoisted is not None:
+        Ps, Pd, M = (np.ascontiguousarray(a, dtype=np.float64) for a in hoisted)
+    out = {"A": np.empty((nv, F), np.float64)}
+    if want_abs:
+        out["A_abs"] = np.empty((nv, F), np.float64)
+    if Wv is not None:
+        out["Y"] = np.empty((nv, F_out), np.float64)
+        if want_abs:
+            out["Y_abs"] = np.empty((nv, F_out), np.float64)
+    rc = lib().saga_oracle_layer(
+        n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], _ptr(w),
+        _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(Ps), _ptr(Pd), _ptr(M), AGGS[agg],
+        _ptr(Wv), _ptr(bv), F_out, ACTS[act], _ptr(vl), nv,
+        _ptr(out["A"]), _ptr(out.get("A_abs")), _ptr(out.get("Y")), _ptr(out.get("Y_abs")))
+    if rc != 0:
+        raise ValueError("saga_oracle_layer rejected its arguments")
+    return out

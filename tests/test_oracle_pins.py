@@ -1,0 +1,348 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix.
+
+None of these re-types the oracle's loop. They are: hand-worked values, the
+dense matrix form of the layer (the sparse-dense product identity of
+Section 6.1), a library sparse product, closed forms and invariants, and
+special cases in which one edge function must collapse to another.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+import oracle
+import saga_inputs as si
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _np(g):
+    return g.col_ptr.numpy(), g.row_idx.numpy()
+
+
+def _coo(g):
+    return g.row_idx.numpy().astype(np.int64), g.dst_of_edges().numpy()
+
+
+def _random_graph(n, m, seed, self_loops=False, symmetrise=False):
+    s, d = si.uniform_edges(n, m, seed)
+    return si.build_csc(n, s, d, symmetrise=symmetrise, self_loops=self_loops)
+
+
+def _dense_adj(g, w=None):
+    """Adj[v, u] = weight of edge u -> v (1 if unweighted), built from the COO list."""
+    src, dst = _coo(g)
+    A = np.zeros((g.n, g.n))
+    A[dst, src] = 1.0 if w is None else w.astype(np.float64)
+    return A
+
+
+# --------------------------------------------------------------------------
+# hand-worked values (tests/golden/hand_worked_layer.json)
+# --------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def hand():
+    with open(os.path.join(HERE, "golden", "hand_worked_layer.json")) as f:
+        return json.load(f)
+
+
+def test_hand_worked_graph_builds_the_stated_csc(hand):
+    g = si.csc_from_lists(hand["n"], [tuple(e) for e in hand["edges_src_dst"]])
+    assert g.col_ptr.tolist() == hand["csc_col_ptr"] and g.row_idx.tolist() == hand["csc_row_idx"]
+
+
+@pytest.mark.parametrize("op,agg,key", [("copy", "sum", "copy_sum_A"), ("mul_weight", "sum", "mul_weight_sum_A"),
+                                        ("copy", "max", "copy_max_A"), ("mul_weight", "max", "mul_weight_max_A")])
+def test_hand_worked_gather(hand, op, agg, key):
+    o = oracle.layer(hand["csc_col_ptr"], hand["csc_row_idx"], hand["X"], op,
+                     hand["edge_weight_in_csc_order"] if op == "mul_weight" else None, agg=agg)
+    assert np.array_equal(o["A"], np.array(hand[key], float))
+
+
+def test_hand_worked_apply_vertex(hand):
+    args = (hand["csc_col_ptr"], hand["csc_row_idx"], hand["X"], "copy")
+    y = oracle.layer(*args, W=hand["W"], act="relu")["Y"]
+    assert np.array_equal(y, np.array(hand["copy_sum_relu_Y_no_bias"], float))
+    y = oracle.layer(*args, W=hand["W"], bias=hand["bias"], act="relu")["Y"]
+    assert np.array_equal(y, np.array(hand["copy_sum_relu_Y_with_bias"], float))
+    y = oracle.layer(*args, W=hand["W"], bias=hand["bias"], act="none")["Y"]
+    assert np.array_equal(y, np.array(hand["copy_sum_none_Y_with_bias"], float))
+
+
+def test_hand_worked_gate_closed_form():
+    """Example 2.1 with F = 1: x = (L, -L, 2L), L = fp32(ln 3), gate row (2, -1).
+
+    The gate pre-activation is 2 x_src - x_dst, an integer multiple k of L, so
+    sigmoid = 3^k / (1 + 3^k) up to the rounding of L. Swapping the roles of
+    source and destination, or the sign inside the sigmoid, changes every value.
+    """
+    L = float(np.float32(np.log(3.0)))
+    g = si.csc_from_lists(3, [(0, 1), (2, 1), (1, 0), (0, 0), (1, 2)])
+    X = np.array([[L], [-L], [2 * L]], np.float32)
+    o = oracle.layer(*_np(g), X, "gated", W_gate=np.array([[2.0, -1.0]], np.float32))
+    want = np.array([[L * (3 / 4 - 1 / 28)], [L * (27 / 28 + 2 * 243 / 244)], [-L / 82]])
+    assert np.allclose(o["A"], want, rtol=2e-6, atol=0)
+    # and |terms| summed
+    want_abs = np.array([[L * (3 / 4 + 1 / 28)], [L * (27 / 28 + 2 * 243 / 244)], [L / 82]])
+    assert np.allclose(o["A_abs"], want_abs, rtol=2e-6, atol=0)
+
+
+# --------------------------------------------------------------------------
+# dense matrix form: Y = act((Adj o w) X W + bias)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("op", ["copy", "mul_weight"])
+@pytest.mark.parametrize("act", ["relu", "none"])
+def test_sum_layer_equals_dense_matrix_product(op, act):
+    g = _random_graph(150, 1200, seed=21)            # directed: Adj is not symmetric
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((g.n, 7)).astype(np.float32)
+    W = rng.standard_normal((7, 5)).astype(np.float32)   # F_in != F_out: a transposed W cannot pass
+    bias = rng.standard_normal(5).astype(np.float32)
+    w = rng.standard_normal(g.nnz).astype(np.float32) if op == "mul_weight" else None
+    o = oracle.layer(*_np(g), X, op, w, W=W, bias=bias, act=act)
+    if op == "mul_weight":
+        # the per-edge message is the fp32 product; reproduce that rounding term by term
+        src, dst = _coo(g)
+        A = np.zeros((g.n, 7))
+        np.add.at(A, dst, (w[:, None] * X[src]).astype(np.float32).astype(np.float64))
+    else:
+        A = _dense_adj(g) @ X.astype(np.float64)
+    Y = A @ W.astype(np.float64) + bias
+    if act == "relu":
+        Y = np.maximum(Y, 0.0)
+    assert np.allclose(o["A"], A, rtol=1e-12, atol=1e-12)
+    assert np.allclose(o["Y"], Y, rtol=1e-12, atol=1e-12)
+    if op == "mul_weight":   # the exact-product matrix form agrees to fp32 rounding of each term
+        A2 = _dense_adj(g, w) @ X.astype(np.float64)
+        assert np.abs(o["A"] - A2).max() <= 2.0 ** -23 * o["A_abs"].max()
+
+
+def test_gather_equals_scipy_sparse_product_on_config_shapes():
+    for wl in (si.workload(1), si.workload(2, scale=11)):
+        g = wl.graph
+        src, dst = _coo(g)
+        S = sp.csr_matrix((wl.edge_weight.numpy().astype(np.float64), (dst, src)), shape=(g.n, g.n))
+        want = S @ wl.X.numpy().astype(np.float64)
+        o = oracle.layer(*_np(g), wl.X.numpy(), "mul_weight", wl.edge_weight.numpy())
+        assert np.abs(o["A"] - want).max() <= 2.0 ** -23 * np.abs(o["A_abs"]).max()
+        Sabs = sp.csr_matrix((np.abs(wl.edge_weight.numpy()).astype(np.float64), (dst, src)), shape=(g.n, g.n))
+        want_abs = Sabs @ np.abs(wl.X.numpy()).astype(np.float64)
+        assert np.allclose(o["A_abs"], want_abs, rtol=1e-6, atol=1e-30)
+
+
+def test_all_ones_features_give_the_in_degree():
+    wl = si.workload(4, scale=11)                    # directed R-MAT, empty columns included
+    g = wl.graph
+    o = oracle.layer(*_np(g), np.ones((g.n, 3), np.float32), "copy")
+    deg = g.in_degree().numpy().astype(np.float64)
+    assert (deg == 0).any() and np.array_equal(o["A"], np.repeat(deg[:, None], 3, 1))
+    # out-degree would be a different vector on a directed graph
+    out_deg = np.bincount(g.row_idx.numpy(), minlength=g.n)
+    assert not np.array_equal(out_deg, deg)
+
+
+# --------------------------------------------------------------------------
+# max accumulator
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("op", ["copy", "mul_weight"])
+def test_max_gather_equals_brute_force_over_the_edge_list(op):
+    g = _random_graph(60, 500, seed=33)
+    g = si.CSC(g.n + 4, torch.cat([g.col_ptr, g.col_ptr[-1:].repeat(4)]), g.row_idx)  # 4 isolated vertices
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((g.n, 6)).astype(np.float32)
+    w = rng.standard_normal(g.nnz).astype(np.float32)
+    o = oracle.layer(*_np(g), X, op, w if op == "mul_weight" else None, agg="max")
+    src, dst = _coo(g)
+    msg = X[src] * w[:, None] if op == "mul_weight" else X[src]        # float32 arithmetic
+    assert msg.dtype == np.float32
+    for v in range(g.n):
+        sel = msg[dst == v]
+        want = sel.max(axis=0) if len(sel) else np.zeros(6, np.float32)
+        assert np.array_equal(o["A"][v], want.astype(np.float64))
+
+
+def test_max_is_not_sum_and_handles_negative_only_columns():
+    g = si.csc_from_lists(3, [(0, 2), (1, 2)])
+    X = np.array([[-5.0], [-2.0], [9.0]], np.float32)
+    assert oracle.layer(*_np(g), X, "copy", agg="max")["A"].tolist() == [[0.0], [0.0], [-2.0]]
+    assert oracle.layer(*_np(g), X, "copy", agg="sum")["A"].tolist() == [[0.0], [0.0], [-7.0]]
+
+
+# --------------------------------------------------------------------------
+# gated edge function
+# --------------------------------------------------------------------------
+
+def _gated_setup(n=40, m=300, F=5, seed=4):
+    g = _random_graph(n, m, seed=seed)
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    Wg = (0.5 * rng.standard_normal((F, 2 * F))).astype(np.float32)
+    bg = rng.standard_normal(F).astype(np.float32)
+    Wm = rng.standard_normal((F, F)).astype(np.float32)
+    return g, X, Wg, bg, Wm
+
+
+def test_gated_equals_dense_broadcast_form():
+    g, X, Wg, bg, Wm = _gated_setup()
+    F = X.shape[1]
+    Xd = X.astype(np.float64)
+    Ps = Xd @ Wg[:, :F].astype(np.float64).T
+    Pd = Xd @ Wg[:, F:].astype(np.float64).T
+    M = Xd @ Wm.astype(np.float64).T
+    Z = Pd[:, None, :] + Ps[None, :, :] + bg            # Z[v, u, f]
+    G = 1.0 / (1.0 + np.exp(-Z))
+    Adj = _dense_adj(g)
+    want = np.einsum("vu,vuf,uf->vf", Adj, G, M)
+    o = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm)
+    assert np.allclose(o["A"], want, rtol=1e-12, atol=1e-13)
+    want_abs = np.einsum("vu,vuf,uf->vf", Adj, G, np.abs(M))
+    assert np.allclose(o["A_abs"], want_abs, rtol=1e-12, atol=1e-13)
+    # Example 2.1 proper: no bias, no message matrix
+    Z0 = Pd[:, None, :] + Ps[None, :, :]
+    want0 = np.einsum("vu,vuf,uf->vf", Adj, 1.0 / (1.0 + np.exp(-Z0)), Xd)
+    o0 = oracle.layer(*_np(g), X, "gated", W_gate=Wg)
+    assert np.allclose(o0["A"], want0, rtol=1e-12, atol=1e-13)
+
+
+def test_gate_with_zero_weights_is_a_half():
+    g, X, Wg, bg, Wm = _gated_setup()
+    o = oracle.layer(*_np(g), X, "gated", W_gate=np.zeros_like(Wg), W_msg=Wm)
+    want = 0.5 * (_dense_adj(g) @ (X.astype(np.float64) @ Wm.astype(np.float64).T))
+    assert np.allclose(o["A"], want, rtol=1e-12, atol=1e-13)
+
+
+def test_saturated_gate_is_commnet_passthrough():
+    # bias +40 opens the gate to 1 within 1e-17: Figure 9's ApplyEdge (return edge.src)
+    g, X, Wg, bg, Wm = _gated_setup()
+    o = oracle.layer(*_np(g), X, "gated", W_gate=np.zeros_like(Wg), b_gate=np.full_like(bg, 40.0))
+    c = oracle.layer(*_np(g), X, "copy")
+    assert np.allclose(o["A"], c["A"], rtol=1e-15, atol=1e-15)
+    # and bias -40 closes it
+    z = oracle.layer(*_np(g), X, "gated", W_gate=np.zeros_like(Wg), b_gate=np.full_like(bg, -40.0))
+    assert np.abs(z["A"]).max() < 1e-15
+
+
+def test_gate_halves_address_source_and_destination():
+    g, X, Wg, bg, Wm = _gated_setup()
+    F = X.shape[1]
+    Xd, Adj = X.astype(np.float64), _dense_adj(g)
+    M = Xd @ Wm.astype(np.float64).T
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    # only the destination half is non-zero: the gate factors out of the sum
+    Wd = Wg.copy(); Wd[:, :F] = 0
+    o = oracle.layer(*_np(g), X, "gated", W_gate=Wd, b_gate=bg, W_msg=Wm)
+    want = sig(Xd @ Wd[:, F:].astype(np.float64).T + bg) * (Adj @ M)
+    assert np.allclose(o["A"], want, rtol=1e-11, atol=1e-12)
+    # only the source half is non-zero: the gate folds into the source rows
+    Ws = Wg.copy(); Ws[:, F:] = 0
+    o = oracle.layer(*_np(g), X, "gated", W_gate=Ws, b_gate=bg, W_msg=Wm)
+    want = Adj @ (sig(Xd @ Ws[:, :F].astype(np.float64).T + bg) * M)
+    assert np.allclose(o["A"], want, rtol=1e-11, atol=1e-12)
+
+
+def test_hoisted_equals_naive():
+    # Section 3.2: moving the vertex-only products out of ApplyEdge changes nothing
+    g, X, Wg, bg, Wm = _gated_setup(n=80, m=900, F=9, seed=8)
+    W = np.random.default_rng(3).standard_normal((9, 4)).astype(np.float32)
+    for wm in (Wm, None):
+        for b in (bg, None):
+            a = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=b, W_msg=wm, W=W, act="relu")
+            h = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=b, W_msg=wm, W=W, act="relu",
+                             hoisted=oracle.hoist(X, Wg, wm))
+            assert np.allclose(a["A"], h["A"], rtol=1e-12, atol=1e-13)
+            assert np.allclose(a["Y"], h["Y"], rtol=1e-12, atol=1e-13)
+    Ps, Pd, M = oracle.hoist(X, Wg, Wm)
+    Xd = X.astype(np.float64)
+    assert np.allclose(Ps, Xd @ Wg[:, :9].astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    assert np.allclose(Pd, Xd @ Wg[:, 9:].astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    assert np.allclose(M, Xd @ Wm.astype(np.float64).T, rtol=1e-13, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# ApplyVertex alone, invariances, degenerate shapes
+# --------------------------------------------------------------------------
+
+def test_self_loops_only_reduce_the_layer_to_a_dense_product():
+    n = 33
+    g = si.csc_from_lists(n, [(v, v) for v in range(n)])
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((n, 6)).astype(np.float32)
+    W = rng.standard_normal((6, 11)).astype(np.float32)
+    b = rng.standard_normal(11).astype(np.float32)
+    o = oracle.layer(*_np(g), X, "mul_weight", np.ones(n, np.float32), W=W, bias=b, act="relu")
+    want = np.maximum(X.astype(np.float64) @ W.astype(np.float64) + b, 0)
+    assert np.allclose(o["Y"], want, rtol=1e-13, atol=1e-13) and (o["Y"] >= 0).all()
+    want_abs = np.abs(X).astype(np.float64) @ np.abs(W).astype(np.float64) + np.abs(b)
+    assert np.allclose(o["Y_abs"], want_abs, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("agg", ["sum", "max"])
+def test_relabelling_vertices_permutes_the_output(agg):
+    n = 90
+    s, d = si.uniform_edges(n, 700, seed=13)
+    g = si.build_csc(n, s, d)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(2))   # old id -> new id
+    g2 = si.build_csc(n, perm[s], perm[d])
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((n, 4)).astype(np.float32)
+    X2 = np.empty_like(X); X2[perm.numpy()] = X
+    a = oracle.layer(*_np(g), X, "copy", agg=agg)["A"]
+    b = oracle.layer(*_np(g2), X2, "copy", agg=agg)["A"]
+    if agg == "max":
+        assert np.array_equal(b[perm.numpy()], a)
+    else:
+        assert np.allclose(b[perm.numpy()], a, rtol=1e-13, atol=1e-13)
+
+
+def test_sum_layer_without_activation_is_linear():
+    wl = si.workload(1)
+    g = wl.graph
+    Z = si.normal_features(g.n, 64, seed=77).numpy()
+    f = lambda x: oracle.layer(*_np(g), x, "mul_weight", wl.edge_weight.numpy(), W=wl.W.numpy())["Y"]
+    a, b = 0.5, -2.0   # powers of two: a*X + b*Z has no extra rounding beyond one add
+    X = wl.X.numpy()
+    lhs = f((a * X + b * Z).astype(np.float32))
+    rhs = a * f(X) + b * f(Z)
+    assert np.abs(lhs - rhs).max() <= 1e-5 * np.abs(rhs).max()
+
+
+def test_degenerate_graphs():
+    # no edges at all
+    g = si.csc_from_lists(5, [])
+    W = np.array([[1.0, -1.0]], np.float32)
+    o = oracle.layer(*_np(g), np.ones((5, 1), np.float32), "copy", W=W, bias=np.array([0.25, 0.5], np.float32), act="relu")
+    assert np.array_equal(o["A"], np.zeros((5, 1))) and np.array_equal(o["Y"], np.tile([0.25, 0.5], (5, 1)))
+    # a single vertex with a self-loop
+    g = si.csc_from_lists(1, [(0, 0)])
+    assert oracle.layer(*_np(g), np.array([[3.0, 4.0]], np.float32), "copy")["A"].tolist() == [[3.0, 4.0]]
+    # star: every vertex points at vertex 0
+    n = 3000
+    g = si.csc_from_lists(n, [(u, 0) for u in range(n)])
+    X = np.arange(n, dtype=np.float32)[:, None]
+    o = oracle.layer(*_np(g), X, "copy")
+    assert o["A"][0, 0] == n * (n - 1) / 2 and not o["A"][1:].any()
+    # path 0 -> 1 -> 2 -> ... shifts the rows by one
+    g = si.csc_from_lists(50, [(v, v + 1) for v in range(49)])
+    X = np.random.default_rng(0).standard_normal((50, 3)).astype(np.float32)
+    o = oracle.layer(*_np(g), X, "copy")
+    assert np.array_equal(o["A"][1:], X[:-1].astype(np.float64)) and not o["A"][0].any()
+
+
+def test_vertex_list_selects_rows_of_the_full_result():
+    wl = si.workload(4, scale=9, f_in=8, f_out=5)
+    g = wl.graph
+    kw = dict(edge_op="gated", W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy(), W_msg=wl.W_msg.numpy(),
+              W=wl.W.numpy(), act="relu")
+    full = oracle.layer(*_np(g), wl.X.numpy(), **kw)
+    vl = np.array([7, 0, 300, 7, g.n - 1])
+    part = oracle.layer(*_np(g), wl.X.numpy(), vlist=vl, **kw)
+    for k in ("A", "A_abs", "Y", "Y_abs"):
+        assert np.array_equal(part[k], full[k][vl])
+    with pytest.raises(ValueError):
+        oracle.layer(*_np(g), wl.X.numpy(), vlist=[g.n], **kw)
