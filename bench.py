@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of one fused SAGA-NN layer on one MI355X.
+
+A step is one forward layer (hoisted products if gated, fused
+Scatter-ApplyEdge-Gather, combine of split columns, ApplyVertex) over a seeded
+synthetic graph already resident in HBM. Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config3]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
+
+
+def algorithmic_gather_bytes(nnz, n, f_in, elem_bytes, weighted, gated, n_items):
+    """Bytes the fused Scatter-ApplyEdge-Gather launch has to move by the method itself.
+
+    per edge: 4 (source id) + 4 (edge weight, if any) + the source row
+    (F_in * s; gated: two hoisted fp32 rows Ps[u] and M[u]);
+    per work item: 16 (its descriptor); per vertex: one output row
+    (+ one hoisted fp32 row Pd[v] when gated).
+    """
+    if gated:
+        per_edge = 4 + 2 * f_in * 4
+        per_vertex = f_in * 4 + f_in * 4
+    else:
+        per_edge = 4 + (4 if weighted else 0) + f_in * elem_bytes
+        per_vertex = f_in * elem_bytes
+    return nnz * per_edge + n * per_vertex + n_items * 16
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4"])
+    ap.add_argument("--scale", type=int, default=None, help="shrink the graph (testing only)")
+    ap.add_argument("--edge-factor", type=int, default=None)
+    ap.add_argument("--agg", default="sum", choices=["sum", "max"])
+    ap.add_argument("--split", type=int, default=None)
+    ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing here shards across GPUs", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import numpy as np
+    import saga_inputs as si
+    import paper_1810_08403_amd as saga
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda"
+    k = int(args.workload[-1])
+    t0 = time.time()
+    wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+    g = wl.graph
+    n, nnz = g.n, g.nnz
+    f_in, f_out = wl.X.shape[1], wl.W.shape[1]
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    es = 2 if wl.dtype == "bf16" else 4
+
+    ctx = saga.Context(0)
+    if args.split:
+        ctx.set_option("split", args.split)
+    if args.xcd_remap is not None:
+        ctx.set_option("xcd_remap", args.xcd_remap)
+    t0 = time.time()
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    t_ingest = time.time() - t0
+    info = graph.info()
+    X = wl.X.to(tdt).contiguous()
+    W = wl.W.to(tdt).contiguous()
+    Y = torch.empty(n, f_out, device=dev, dtype=tdt)
+    kw = dict(edge_op=wl.edge_op, agg=args.agg, W=W, act=wl.act)
+    if wl.edge_op == "mul_weight":
+        graph.set_edge_data(wl.edge_weight)
+    if wl.edge_op == "gated":
+        kw.update(W_gate=wl.W_gate, b_gate=wl.b_gate, W_msg=wl.W_msg)
+
+    def step():
+        ctx.layer_forward(graph, X, Y, **kw)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.set_profiling(True)
+    ctx.reset_timings()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    tm = ctx.get_timings()           # HIP events recorded by the library on its own stream
+    ctx.set_profiling(False)
+    ms_per_step = wall * 1e3 / args.steps
+    gteps = nnz / (ms_per_step * 1e-3) / 1e9
+
+    ms_gather = tm["ms_gather"] / max(tm["n_calls"], 1)
+    alg_bytes = algorithmic_gather_bytes(nnz, n, f_in, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
+                                         info["n_work_items"])
+    achieved = alg_bytes / (ms_gather * 1e-3) / 1e9 if ms_gather > 0 else 0.0
+    compulsory = n * f_in * es + nnz * (8 if wl.edge_op == "mul_weight" else 4) + info["n_work_items"] * 16 + n * f_in * es
+    out = {
+        "metric": "fused_saga_layer_throughput", "value": round(gteps, 4), "unit": "GTEPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "n_vertices": n, "nnz": nnz, "f_in": f_in, "f_out": f_out,
+                   "edge_op": wl.edge_op, "agg": args.agg, "act": wl.act, "max_in_degree": info["max_in_degree"],
+                   "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"]},
+        "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "algorithmic_bytes_per_launch": alg_bytes,
+                     "compulsory_bytes_per_launch": compulsory,
+                     "compulsory_frac": round(compulsory / (ms_gather * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if ms_gather > 0 else None,
+                     "ms_per_launch": round(ms_gather, 4)},
+        "stages_ms": {"hoist": round(tm["ms_hoist"] / max(tm["n_calls"], 1), 4), "gather": round(ms_gather, 4),
+                      "combine": round(tm["ms_combine"] / max(tm["n_calls"], 1), 4),
+                      "apply_vertex": round(tm["ms_apply_vertex"] / max(tm["n_calls"], 1), 4),
+                      "events_total": round(tm["ms_total"] / max(tm["n_calls"], 1), 4)},
+        "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3)},
+    }
+
+    if args.cpu_seconds > 0:
+        import oracle
+        cp = g.col_ptr.cpu().numpy()
+        ri = g.row_idx.cpu().numpy()
+        Xh = wl.X.float().cpu().numpy()
+        okw = dict(edge_op=wl.edge_op, agg=args.agg, W=wl.W.float().cpu().numpy(), act=wl.act, want_abs=False)
+        if wl.edge_op == "mul_weight":
+            okw["edge_weight"] = wl.edge_weight.cpu().numpy()
+        if wl.edge_op == "gated":
+            okw.update(W_gate=wl.W_gate.cpu().numpy(), b_gate=wl.b_gate.cpu().numpy(), W_msg=wl.W_msg.cpu().numpy())
+        rng = np.random.default_rng(12345)
+        perm = rng.permutation(n)
+        deg = np.diff(cp)
+
+        def timed(vl):
+            t = time.perf_counter()
+            oracle.layer(cp, ri, Xh, vlist=vl, **okw)
+            return time.perf_counter() - t
+
+        # pilot on a small random sample, then size the real sample for the target time
+        pilot = perm[: max(64, n // 2000)]
+        tp = timed(pilot)
+        rate = max(deg[pilot].sum(), 1) / max(tp, 1e-6)
+        want_edges = rate * args.cpu_seconds
+        csum = np.cumsum(deg[perm])
+        m = int(np.searchsorted(csum, want_edges)) + 1
+        sample = perm[: min(max(m, 64), n)]
+        ts = timed(sample)
+        e_s = int(deg[sample].sum())
+        out["cpu_baseline"] = {"value": round(e_s / ts / 1e9, 6), "unit": "GTEPS", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{len(sample)} random destination vertices ({e_s} in-edges) of the same "
+                                         f"graph, full layer incl. ApplyVertex, {ts:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,192 @@
+/*
+ * saga.h - C ABI of the MI355X (gfx950) SAGA-NN layer library.
+ *
+ * One call computes the forward pass of one GNN layer in the SAGA-NN model of
+ * the NGra paper (arXiv 1810.08403, Section 2.1-2.2):
+ *
+ *   Scatter     every edge u -> v receives [src = X[u], dest = X[v], data = w_e]
+ *   ApplyEdge   per-edge function of that tuple (closed set below)
+ *   Gather      per destination vertex, sum or element-wise max of the edge
+ *               outputs ("commutative and associative accumulate", Section 2.2)
+ *   ApplyVertex Y[v] = act(A[v] W + bias)               (Figures 2 and 10)
+ *
+ * Scatter, ApplyEdge and Gather run as one fused propagation kernel (the
+ * fused-gather operator of Section 3.2); vertex-only matrix products inside a
+ * gated ApplyEdge are hoisted to one product per vertex (Section 3.2); graphs
+ * whose data live in host memory are streamed through a fixed device budget
+ * as vertex intervals x edge chunks (Section 3.1).
+ *
+ * The paper does not let users supply Scatter/Gather functions or accumulators
+ * (Section 2.2, last paragraphs); accordingly everything here is a closed enum.
+ *
+ * Conventions
+ *   - Edge direction: u = source, v = destination. The graph is CSC sorted by
+ *     destination (Section 3.1: "edges clustered by destination vertex id"):
+ *     the in-edges of v are row_idx[col_ptr[v] .. col_ptr[v+1]), source ids
+ *     strictly ascending. Duplicate edges are therefore not representable.
+ *   - All matrices are row-major; ld counts elements between rows.
+ *   - Pointers marked "device" must be device memory of the context's GPU;
+ *     "host" pointers are ordinary or pinned host memory. The caller owns every
+ *     buffer it passes; the library never frees or resizes caller memory and
+ *     owns only what its handles allocate (released by the *_destroy calls).
+ *   - Device-path calls enqueue work on the context's stream and return without
+ *     waiting; host-path (streamed) calls return after the output is in host
+ *     memory.
+ *   - No call throws or aborts; every failure is a saga_status, with text in
+ *     saga_last_error().
+ *   - A context and the handles made from it are not thread-safe.
+ */
+#ifndef SAGA_H
+#define SAGA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct saga_ctx saga_ctx;     /* device, stream, workspace, budget, timers */
+typedef struct saga_graph saga_graph; /* validated CSC, degree bins, work list, chunk grid */
+
+typedef enum {
+    SAGA_OK = 0,
+    SAGA_ERR_INVALID_ARG = 1, /* null pointer, shape/dtype/placement mismatch */
+    SAGA_ERR_BAD_GRAPH = 2,   /* malformed CSC */
+    SAGA_ERR_UNSUPPORTED = 3, /* a combination this build does not implement */
+    SAGA_ERR_BUDGET = 4,      /* no chunk plan fits the device-memory budget */
+    SAGA_ERR_HIP = 5,         /* a HIP runtime call failed */
+    SAGA_ERR_INTERNAL = 6
+} saga_status;
+
+typedef enum { SAGA_F32 = 0, SAGA_BF16 = 1 } saga_dtype;
+typedef enum { SAGA_AGG_SUM = 0, SAGA_AGG_MAX = 1 } saga_agg;
+typedef enum { SAGA_ACT_NONE = 0, SAGA_ACT_RELU = 1 } saga_act;
+typedef enum { SAGA_MEM_DEVICE = 0, SAGA_MEM_HOST = 1 } saga_mem;
+
+/*
+ * ApplyEdge functions (m = message of edge u -> v, per feature f):
+ *   COPY        m = x_u                                   (CommNet, Figure 9)
+ *   MUL_WEIGHT  m = w_e * x_u, one fp32 multiply          (GCN, Figure 10)
+ *   GATED       m = sigmoid(Wg [x_u ; x_v] + b) (.) (Wm x_u)
+ *               (Example 2.1 / Figure 2; b and Wm optional, so that b = NULL,
+ *               Wm = NULL is exactly Example 2.1)
+ */
+typedef enum { SAGA_EDGE_COPY = 0, SAGA_EDGE_MUL_WEIGHT = 1, SAGA_EDGE_GATED = 2 } saga_edge_op;
+
+/* Row-major matrix view. dtype is a saga_dtype, mem a saga_mem. */
+typedef struct saga_tensor {
+    void* data;
+    int64_t rows, cols, ld;
+    int32_t dtype;
+    int32_t mem;
+} saga_tensor;
+
+typedef struct saga_edge_params {
+    int32_t op;               /* saga_edge_op */
+    const float* edge_weight; /* MUL_WEIGHT: [nnz] fp32 in CSC edge order, same placement as the
+                                 graph; NULL = use the data attached by saga_graph_set_edge_data */
+    const saga_tensor* W_gate; /* GATED: F x 2F fp32; columns [0,F) act on the source row,
+                                  [F,2F) on the destination row */
+    const saga_tensor* b_gate; /* GATED: 1 x F fp32, nullable */
+    const saga_tensor* W_msg;  /* GATED: F x F fp32 (row = output channel), nullable = identity */
+} saga_edge_params;
+
+typedef struct saga_vertex_params {
+    const saga_tensor* W;    /* F_in x F_out, dtype of X; NULL skips ApplyVertex (Y = Gather output) */
+    const saga_tensor* bias; /* 1 x F_out fp32, nullable */
+    int32_t act;             /* saga_act */
+} saga_vertex_params;
+
+/* Accumulated since saga_reset_timings(); stage times come from events on the context's stream. */
+typedef struct saga_timings {
+    int64_t n_calls;         /* saga_layer_forward calls accumulated */
+    double ms_total;         /* first to last event of each call, summed */
+    double ms_hoist;         /* per-vertex gate/message products (gated only) */
+    double ms_gather;        /* fused Scatter-ApplyEdge-Gather kernels */
+    double ms_combine;       /* combining the partial rows of split heavy vertices */
+    double ms_apply_vertex;  /* ApplyVertex product + activation */
+    int64_t n_gather_launches;
+    int64_t bytes_h2d, bytes_d2h; /* streamed path only */
+    double ms_wall_streamed;      /* host wall time of streamed calls */
+    int32_t plan_dst_intervals, plan_src_intervals; /* last streamed plan (0 = resident) */
+    int32_t reserved;
+    int64_t n_work_items, n_split_vertices; /* of the last graph used */
+} saga_timings;
+
+/*
+ * Create a context on GPU `device`. hip_stream is a hipStream_t to enqueue on
+ * (NULL: the library creates its own, default priority). hbm_budget_bytes caps
+ * every device byte the library holds for streamed calls (0 = no cap).
+ */
+saga_status saga_create(saga_ctx** out, int device, void* hip_stream, size_t hbm_budget_bytes);
+saga_status saga_destroy(saga_ctx* ctx);
+
+/*
+ * Ingest a CSC graph (Section 3.1). col_ptr is int64 [n_vertices + 1], row_idx
+ * int32 [n_edges]; `where` says where both live. The library copies what it
+ * needs, so the caller may free the arrays after return. It validates the
+ * arrays (monotone col_ptr from 0 to n_edges, ids in range, strictly ascending
+ * within a column) and returns SAGA_ERR_BAD_GRAPH otherwise; computes
+ * in-degrees and the work list (light columns whole, heavy columns cut into
+ * consecutive sub-groups as in Section 3.3's Scatter kernel).
+ * SAGA_MEM_DEVICE graphs serve device-resident calls; SAGA_MEM_HOST graphs
+ * serve streamed calls and are tiled into the chunk grid at the first call.
+ * Synchronises the stream.
+ */
+saga_status saga_graph_create_csc(saga_ctx* ctx, int64_t n_vertices, int64_t n_edges,
+                                  const int64_t* col_ptr, const int32_t* row_idx, int32_t where,
+                                  saga_graph** out);
+saga_status saga_graph_destroy(saga_graph* g);
+
+/*
+ * Attach the static edge data (edge.data of Section 2.1, e.g. GCN's degree
+ * weights): [n_edges] fp32 in CSC edge order, same placement as the graph.
+ * Copied. Used when saga_edge_params.edge_weight is NULL; required for
+ * streamed MUL_WEIGHT calls, where it is stored chunk by chunk with the edges.
+ */
+saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
+
+/*
+ * One layer forward. X is n x F_in (SAGA_F32, or SAGA_BF16 for COPY /
+ * MUL_WEIGHT). Y is n x F_out in X's dtype (n x F_in when vp->W is NULL).
+ * accum_out, if given, receives the Gather output A as n x F_in fp32 before
+ * ApplyVertex (device path only).
+ *
+ * Placement selects the path: all tensors SAGA_MEM_DEVICE with a device graph
+ * -> resident; X and Y SAGA_MEM_HOST (pinned recommended) with a host graph ->
+ * streamed through the context's budget, parameters still on the device.
+ *
+ * Arithmetic: fp32 accumulation everywhere. BF16: X, W bf16; A is rounded to
+ * bf16 (nearest even) once before the ApplyVertex product; Y is rounded to
+ * bf16. Gather over an empty in-edge set gives 0 for both accumulators.
+ * max over MUL_WEIGHT / COPY messages is exact (bitwise reproducible);
+ * sums are deterministic run to run (no floating-point atomics).
+ */
+saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,
+                               const saga_edge_params* ep, int32_t agg,
+                               const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out);
+
+/* Stage timers. Off by default (no events recorded). */
+saga_status saga_set_profiling(saga_ctx* ctx, int32_t on);
+saga_status saga_reset_timings(saga_ctx* ctx);
+saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises the stream */
+
+/* Tunables, for measurement: "split" (max edges per work item, default 1024),
+ * "xcd_remap" (0/1, default 1), "dst_intervals"/"src_intervals" (streamed plan
+ * override, 0 = automatic). Returns INVALID_ARG for unknown names or values. */
+saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value);
+
+/* High-water mark of device bytes held by the library (workspace, graph copies, stream buffers). */
+size_t saga_peak_device_bytes(const saga_ctx* ctx);
+/* Text of the last failure on this context; owned by the context, valid until its next call. */
+const char* saga_last_error(const saga_ctx* ctx);
+/* Facts about an ingested graph: *max_in_degree, *n_work_items, *n_split_vertices (any may be NULL). */
+saga_status saga_graph_info(const saga_graph* g, int64_t* max_in_degree, int64_t* n_work_items,
+                            int64_t* n_split_vertices);
+const char* saga_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGA_H */

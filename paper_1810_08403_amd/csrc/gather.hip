@@ -1,0 +1,544 @@
+// Fused Scatter -> ApplyEdge -> Gather kernels for gfx950 (the fused-gather
+// operator of Section 3.2, built on the kernel principle of Section 3.3:
+// parallelise along the feature row of each vertex, one in-edge group per
+// execution unit, accumulate in registers, write one row).
+//
+// What differs from the paper's P100 kernels:
+//   * the execution unit is one 64-lane wavefront per work item, not a thread
+//     block, and a lane moves 16 bytes per load, so a 1 KiB row is one
+//     wave-wide load; narrower rows put several edges side by side in one
+//     wavefront (64 / lanes-per-row edges per load) and finish with a
+//     cross-lane reduction;
+//   * per-edge tuples are never written: Scatter exists only as the loads;
+//   * source ids reach the lanes through wave-uniform loads or one coalesced
+//     64-id load plus lane permutes, not through shared memory;
+//   * several independent row loads are kept in flight per lane to cover HBM
+//     latency;
+//   * heavy columns are cut into items of bounded length whose partial rows
+//     are combined in a fixed order, so sums are reproducible.
+#include <cmath>
+
+#include "saga_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kInFlight = 8;  // independent 16-byte loads per lane
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+
+template <int AGG>
+__device__ __forceinline__ float identity()
+{
+    return AGG == SAGA_AGG_SUM ? 0.0f : neg_inf();
+}
+
+// Gather's accumulate step. For max the message is formed first by a single
+// multiply (no contraction is possible: there is no addition to fuse with).
+template <int AGG>
+__device__ __forceinline__ float accumulate(float acc, float w, float x)
+{
+    if (AGG == SAGA_AGG_SUM) return fmaf(w, x, acc);
+    const float m = w * x;
+    return m > acc ? m : acc;
+}
+template <int AGG>
+__device__ __forceinline__ float combine(float a, float b)
+{
+    if (AGG == SAGA_AGG_SUM) return a + b;
+    return b > a ? b : a;
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t x = __float_as_uint(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x40u);  // NaN stays NaN
+    x += 0x7fffu + ((x >> 16) & 1u);
+    return (uint16_t)(x >> 16);
+}
+
+// ---- 16-byte (or one-element) row fragments --------------------------------
+template <typename T, int VEC>
+struct Frag;
+
+template <>
+struct Frag<float, 4> {
+    uint4 r;
+    __device__ __forceinline__ void load(const float* p) { r = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void zero() { r = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ float get(int j) const
+    {
+        return __uint_as_float(j == 0 ? r.x : j == 1 ? r.y : j == 2 ? r.z : r.w);
+    }
+};
+template <>
+struct Frag<float, 1> {
+    float r;
+    __device__ __forceinline__ void load(const float* p) { r = *p; }
+    __device__ __forceinline__ void zero() { r = 0.f; }
+    __device__ __forceinline__ float get(int) const { return r; }
+};
+template <>
+struct Frag<uint16_t, 8> {
+    uint4 r;
+    __device__ __forceinline__ void load(const uint16_t* p) { r = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void zero() { r = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ float get(int j) const
+    {
+        const uint32_t d = (j >> 1) == 0 ? r.x : (j >> 1) == 1 ? r.y : (j >> 1) == 2 ? r.z : r.w;
+        return __uint_as_float((j & 1) ? (d & 0xffff0000u) : (d << 16));
+    }
+};
+template <>
+struct Frag<uint16_t, 1> {
+    uint16_t r;
+    __device__ __forceinline__ void load(const uint16_t* p) { r = *p; }
+    __device__ __forceinline__ void zero() { r = 0; }
+    __device__ __forceinline__ float get(int) const { return __uint_as_float((uint32_t)r << 16); }
+};
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous
+// range of the work list instead, so that neighbouring columns share one L2.
+__device__ __forceinline__ int64_t logical_block(int remap)
+{
+    const int64_t b = blockIdx.x;
+    if (!remap) return b;
+    const int64_t per = gridDim.x >> 3;  // grid is padded to a multiple of 8
+    return (b & 7) * per + (b >> 3);
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, int col0, const float (&val)[VEC],
+                                          int agg, bool empty_column)
+{
+    // col0: first feature of this lane's fragment
+    if (slot >= 0) {
+        float* p = a.partials + (int64_t)slot * a.F + col0;
+        if constexpr (VEC % 4 == 0) {
+#pragma unroll
+            for (int j = 0; j < VEC; j += 4)
+                *reinterpret_cast<float4*>(p + j) = make_float4(val[j], val[j + 1], val[j + 2], val[j + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) p[j] = val[j];
+        }
+        return;
+    }
+    float outv[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) outv[j] = val[j];
+    if (a.accumulate) {
+        const float* p = a.out + (int64_t)v * a.ld_out + col0;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) outv[j] = agg == SAGA_AGG_SUM ? p[j] + outv[j] : (outv[j] > p[j] ? outv[j] : p[j]);
+    } else if (agg == SAGA_AGG_MAX && empty_column) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) outv[j] = 0.f;
+    }
+    if (a.out) {
+        float* p = a.out + (int64_t)v * a.ld_out + col0;
+        if constexpr (VEC % 4 == 0) {
+#pragma unroll
+            for (int j = 0; j < VEC; j += 4)
+                *reinterpret_cast<float4*>(p + j) = make_float4(outv[j], outv[j + 1], outv[j + 2], outv[j + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) p[j] = outv[j];
+        }
+    }
+    if (a.out16) {
+        uint16_t* p = a.out16 + (int64_t)v * a.ld_out16 + col0;
+        if constexpr (VEC == 8) {
+            uint4 pk;
+            pk.x = f32_to_bf16_rne(outv[0]) | ((uint32_t)f32_to_bf16_rne(outv[1]) << 16);
+            pk.y = f32_to_bf16_rne(outv[2]) | ((uint32_t)f32_to_bf16_rne(outv[3]) << 16);
+            pk.z = f32_to_bf16_rne(outv[4]) | ((uint32_t)f32_to_bf16_rne(outv[5]) << 16);
+            pk.w = f32_to_bf16_rne(outv[6]) | ((uint32_t)f32_to_bf16_rne(outv[7]) << 16);
+            *reinterpret_cast<uint4*>(p) = pk;
+        } else {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) p[j] = f32_to_bf16_rne(outv[j]);
+        }
+    }
+}
+
+// sigmoid(z) with exp2 on the hardware unit; the product z * log2(e) is
+// carried in two parts so the relative error stays ~1e-7 for |z| up to ~80.
+__device__ __forceinline__ float sigmoid_f32(float z)
+{
+    const float nz = -z;
+    const float l2e_hi = 1.44269502162933349609375f, l2e_lo = 1.92596299e-8f;
+    const float t = nz * l2e_hi;
+    const float tl = fmaf(nz, l2e_hi, -t) + nz * l2e_lo;
+    const float e = __builtin_amdgcn_exp2f(t) * fmaf(tl, 0.693147182f, 1.0f);
+    return __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+struct ItemView {
+    int v, e0, e1, slot;
+};
+__device__ __forceinline__ bool fetch_item(const GatherArgs& a, ItemView* it)
+{
+    const int wave = threadIdx.x >> 6;
+    const int64_t id = logical_block(a.xcd_remap) * kWavesPerBlock + wave;
+    if (id >= a.n_items) return false;
+    const int4 raw = *reinterpret_cast<const int4*>(a.items + id);
+    it->v = __builtin_amdgcn_readfirstlane(raw.x);
+    it->e0 = __builtin_amdgcn_readfirstlane(raw.y);
+    it->e1 = __builtin_amdgcn_readfirstlane(raw.z);
+    it->slot = __builtin_amdgcn_readfirstlane(raw.w);
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// rows of >= 64 fragments: every lane owns RC fragments of the row, one edge
+// per wave-wide load, U edges in flight. GATED reads two fragments per edge.
+// ---------------------------------------------------------------------------
+// One group of up to U edges: issue every row load first, then consume.
+// TAIL guards each edge with the wave-uniform predicate j + k < cnt.
+template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
+__device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const int F, const int idx,
+                                           const float wt, const int j, const int cnt, const int (&col)[RC],
+                                           const float (&pd)[RC][VEC], float (&acc)[RC][VEC])
+{
+    Frag<T, VEC> x[U][RC];
+    Frag<T, VEC> m[GATED ? U : 1][GATED ? RC : 1];
+    float w[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        if (TAIL && j + k >= cnt) continue;
+        // ids and weights come out of the 64-entry batch with a wave-uniform
+        // lane read, so the row base address lives in scalar registers
+        const int64_t u = __builtin_amdgcn_readlane(idx, j + k);
+        w[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wt), j + k));
+        const T* row = X + u * ld;
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+            x[k][c].load(row + col[c]);
+            if constexpr (GATED) m[k][c].load(row + F + col[c]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        if (TAIL && j + k >= cnt) continue;
+#pragma unroll
+        for (int c = 0; c < RC; ++c)
+#pragma unroll
+            for (int jj = 0; jj < VEC; ++jj) {
+                if constexpr (GATED)
+                    acc[c][jj] = accumulate<AGG>(acc[c][jj], sigmoid_f32(x[k][c].get(jj) + pd[c][jj]), m[k][c].get(jj));
+                else
+                    acc[c][jj] = accumulate<AGG>(acc[c][jj], w[k], x[k][c].get(jj));
+            }
+    }
+}
+
+template <typename T, int VEC, int RC, int AGG, bool GATED>
+__global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
+{
+    ItemView it;
+    if (!fetch_item(a, &it)) return;
+    const int lane = threadIdx.x & 63;
+    const int F = a.F;
+    const int nvec = (F + VEC - 1) / VEC;
+    constexpr int LOADS_PER_EDGE = RC * (GATED ? 2 : 1);
+    constexpr int U = (kInFlight / LOADS_PER_EDGE) > 0 ? (kInFlight / LOADS_PER_EDGE) : 1;
+    const T* __restrict__ X = static_cast<const T*>(a.src);
+    const int32_t* __restrict__ ridx = a.row_idx;
+    const float* __restrict__ ew = GATED ? nullptr : a.edge_w;
+
+    for (int cb = 0; cb < nvec; cb += 64 * RC) {
+        float acc[RC][VEC];
+        float pd[RC][VEC];
+        bool ok[RC];
+        int col[RC];
+        int ldcol[RC];  // lanes past the end of the row re-read its first fragment and drop the result
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+            col[c] = (cb + lane + 64 * c) * VEC;
+            ok[c] = (cb + lane + 64 * c) < nvec;
+            ldcol[c] = ok[c] ? col[c] : 0;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                acc[c][j] = identity<AGG>();
+                pd[c][j] = 0.f;
+            }
+            if constexpr (GATED) {
+                Frag<float, VEC> f;
+                f.zero();
+                if (ok[c]) f.load(a.dst + (int64_t)it.v * a.ld_dst + col[c]);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) pd[c][j] = f.get(j);
+            }
+        }
+        // ids and weights are fetched 64 edges at a time, one per lane, one batch ahead
+        int idx_next = 0;
+        float w_next = 1.0f;
+        if (it.e0 + lane < it.e1) {
+            idx_next = ridx[it.e0 + lane];
+            if (ew) w_next = ew[it.e0 + lane];
+        }
+        for (int eb = it.e0; eb < it.e1; eb += 64) {
+            const int idx = idx_next;
+            const float wt = w_next;
+            const int nxt = eb + 64 + lane;
+            if (nxt < it.e1) {
+                idx_next = ridx[nxt];
+                if (ew) w_next = ew[nxt];
+            }
+            const int cnt = min(64, it.e1 - eb);
+            int j = 0;
+            for (; j + U <= cnt; j += U)
+                wide_group<T, VEC, RC, AGG, GATED, U, false>(X, a.ld_src, F, idx, wt, j, cnt, ldcol, pd, acc);
+            if (j < cnt) wide_group<T, VEC, RC, AGG, GATED, U, true>(X, a.ld_src, F, idx, wt, j, cnt, ldcol, pd, acc);
+        }
+#pragma unroll
+        for (int c = 0; c < RC; ++c)
+            if (ok[c]) store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.e0 == it.e1);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// rows of <= 32 fragments: lpr = 2^lpr_log2 lanes cover a row, 64 / lpr edges
+// sit side by side in one wave-wide load; a butterfly over the lane groups
+// finishes the reduction.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int AGG, bool GATED>
+__global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const int lpr_log2)
+{
+    ItemView it;
+    if (!fetch_item(a, &it)) return;
+    const int lane = threadIdx.x & 63;
+    const int F = a.F;
+    const int nvec = (F + VEC - 1) / VEC;
+    const int lpr = 1 << lpr_log2;
+    const int sub = lane & (lpr - 1);
+    const int grp = lane >> lpr_log2;
+    const int epw_log2 = 6 - lpr_log2;
+    const int epw = 1 << epw_log2;
+    const bool colok = sub < nvec;
+    const int col = sub * VEC;
+    const int ldcol = colok ? col : 0;
+    constexpr int U = GATED ? kInFlight / 2 : kInFlight;
+    const T* __restrict__ X = static_cast<const T*>(a.src);
+    const int32_t* __restrict__ ridx = a.row_idx;
+    const float* __restrict__ ew = a.edge_w;
+
+    float acc[VEC], pd[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = identity<AGG>();
+    if constexpr (GATED) {
+        Frag<float, VEC> f;
+        f.zero();
+        if (colok) f.load(a.dst + (int64_t)it.v * a.ld_dst + col);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) pd[j] = f.get(j);
+    }
+
+    for (int eb = it.e0; eb < it.e1; eb += 64) {
+        const int my = eb + lane;
+        int idx = 0;
+        float wt = 1.0f;
+        if (my < it.e1) {
+            idx = ridx[my];
+            if (!GATED && ew) wt = ew[my];
+        }
+        const int cnt = min(64, it.e1 - eb);
+        const int nloads = (cnt + epw - 1) >> epw_log2;
+        for (int j0 = 0; j0 < nloads; j0 += U) {
+            Frag<T, VEC> x[U];
+            Frag<T, VEC> m[GATED ? U : 1];
+            float w[U];
+            bool ok[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const int s = ((j0 + k) << epw_log2) + grp;
+                ok[k] = colok && s < cnt;
+                // slots past the end of the batch hold id 0: a valid row, loaded and dropped
+                const int64_t u = __shfl(idx, s & 63);
+                w[k] = __shfl(wt, s & 63);
+                x[k].load(X + u * a.ld_src + ldcol);
+                if constexpr (GATED) m[k].load(X + u * a.ld_src + F + ldcol);
+            }
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float r;
+                    if constexpr (GATED)
+                        r = accumulate<AGG>(acc[j], sigmoid_f32(x[k].get(j) + pd[j]), m[k].get(j));
+                    else
+                        r = accumulate<AGG>(acc[j], w[k], x[k].get(j));
+                    acc[j] = ok[k] ? r : acc[j];
+                }
+        }
+    }
+    for (int off = lpr; off < 64; off <<= 1)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = combine<AGG>(acc[j], __shfl_xor(acc[j], off));
+    if (grp == 0 && colok) store_row<VEC>(a, it.v, it.slot, col, acc, AGG, it.e0 == it.e1);
+}
+
+// ---------------------------------------------------------------------------
+// combine the partial rows of split vertices, in slot order
+// ---------------------------------------------------------------------------
+template <int AGG>
+__global__ __launch_bounds__(256) void k_combine(const CombineArgs a)
+{
+    const HeavyVertex h = a.heavy[blockIdx.x];
+    const int f = blockIdx.y * 256 + threadIdx.x;
+    if (f >= a.F) return;
+    const float* p = a.partials + (int64_t)h.slot0 * a.F + f;
+    float r = p[0];
+    for (int s = 1; s < h.nslots; ++s) r = combine<AGG>(r, p[(int64_t)s * a.F]);
+    if (a.accumulate) r = combine<AGG>(a.out[(int64_t)h.v * a.ld_out + f], r);
+    if (a.out) a.out[(int64_t)h.v * a.ld_out + f] = r;
+    if (a.out16) a.out16[(int64_t)h.v * a.ld_out16 + f] = f32_to_bf16_rne(r);
+}
+
+__global__ __launch_bounds__(256) void k_fill_f32(float* p, int64_t count, float value)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = value;
+}
+__global__ __launch_bounds__(256) void k_neg_inf_to_zero(float* p, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        if (p[i] == neg_inf()) p[i] = 0.f;
+}
+__global__ __launch_bounds__(256) void k_f32_to_bf16(const float* in, uint16_t* out, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        out[i] = f32_to_bf16_rne(in[i]);
+}
+__global__ __launch_bounds__(256) void k_zero_u32(uint32_t* p, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = 0u;
+}
+
+// One wavefront per work item: ids in range and strictly ascending (also
+// across the cut between consecutive items of one column).
+__global__ __launch_bounds__(256) void k_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx,
+                                                        int64_t n_src, int32_t* flag)
+{
+    const int64_t id = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (id >= n_items) return;
+    const WorkItem it = items[id];
+    // the first edge of an item is checked against its predecessor unless the
+    // item starts its column: a whole-column item does, and so does an item
+    // whose predecessor in the list belongs to another vertex
+    bool starts_column = it.slot < 0 || id == 0 || items[id - 1].v != it.v;
+    bool bad = false;
+    for (int e = it.e0 + (threadIdx.x & 63); e < it.e1; e += 64) {
+        const int u = row_idx[e];
+        if (u < 0 || u >= n_src) bad = true;
+        if ((e > it.e0 || !starts_column) && row_idx[e - 1] >= u) bad = true;
+    }
+    if (bad) *flag = 1;
+}
+
+int grid_for(int64_t count) { return (int)std::min<int64_t>((count + 255) / 256, 65535 * 8); }
+
+int ceil_log2(int x)
+{
+    int l = 0;
+    while ((1 << l) < x) ++l;
+    return l;
+}
+
+template <typename T, int VEC, int AGG, bool GATED>
+hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
+{
+    const int nvec = (a.F + VEC - 1) / VEC;
+    int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (a.xcd_remap) blocks = (blocks + 7) / 8 * 8;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (nvec <= 32) {
+        hipLaunchKernelGGL((k_gather_narrow<T, VEC, AGG, GATED>), grid, block, 0, s, a, ceil_log2(nvec));
+    } else if (nvec <= 64) {
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 1, AGG, GATED>), grid, block, 0, s, a);
+    } else if (nvec <= 128) {
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 2, AGG, GATED>), grid, block, 0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 4, AGG, GATED>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t launch_op(const GatherArgs& a, hipStream_t s)
+{
+    if constexpr (sizeof(T) == 4) {  // the gated message is formed from fp32 hoisted rows only
+        if (a.op == SAGA_EDGE_GATED)
+            return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, true>(a, s)
+                                         : launch_shape<T, VEC, SAGA_AGG_MAX, true>(a, s);
+    }
+    return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, false>(a, s)
+                                 : launch_shape<T, VEC, SAGA_AGG_MAX, false>(a, s);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
+{
+    if (a.n_items <= 0) return hipSuccess;
+    const int esize = a.dtype == SAGA_F32 ? 4 : 2;
+    const int vec = 16 / esize;
+    bool vec_ok = a.F % vec == 0 && (a.ld_src * esize) % 16 == 0 && aligned16(a.src);
+    if (a.out) vec_ok = vec_ok && (a.ld_out * 4) % 16 == 0 && aligned16(a.out);
+    if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
+    if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
+    if (a.op == SAGA_EDGE_GATED) vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst);
+    if (a.dtype == SAGA_F32) return vec_ok ? launch_op<float, 4>(a, s) : launch_op<float, 1>(a, s);
+    if (a.op == SAGA_EDGE_GATED) return hipErrorInvalidValue;
+    return vec_ok ? launch_op<uint16_t, 8>(a, s) : launch_op<uint16_t, 1>(a, s);
+}
+
+hipError_t launch_combine(const CombineArgs& a, hipStream_t s)
+{
+    if (a.n_heavy <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.n_heavy, (unsigned)((a.F + 255) / 256)), block(256);
+    if (a.agg == SAGA_AGG_SUM)
+        hipLaunchKernelGGL(k_combine<SAGA_AGG_SUM>, grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL(k_combine<SAGA_AGG_MAX>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_f32, dim3(grid_for(count)), dim3(256), 0, s, p, count, value);
+    return hipGetLastError();
+}
+hipError_t launch_neg_inf_to_zero(float* p, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_neg_inf_to_zero, dim3(grid_for(count)), dim3(256), 0, s, p, count);
+    return hipGetLastError();
+}
+hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_f32_to_bf16, dim3(grid_for(count)), dim3(256), 0, s, in, out, count);
+    return hipGetLastError();
+}
+hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s)
+{
+    // a fill kernel rather than hipMemsetAsync, so the call is safe under graph capture
+    if (bytes == 0) return hipSuccess;
+    if (bytes % 4 != 0 || !((reinterpret_cast<uintptr_t>(p) & 3u) == 0)) return hipErrorInvalidValue;
+    const int64_t count = (int64_t)(bytes / 4);
+    hipLaunchKernelGGL(k_zero_u32, dim3(grid_for(count)), dim3(256), 0, s, static_cast<uint32_t*>(p), count);
+    return hipGetLastError();
+}
+hipError_t launch_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx, int64_t n_src,
+                                 int32_t* flag, hipStream_t s)
+{
+    if (n_items <= 0) return hipSuccess;
+    const int64_t blocks = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(k_validate_items, dim3((unsigned)blocks), dim3(256), 0, s, items, n_items, row_idx, n_src, flag);
+    return hipGetLastError();
+}

@@ -1,0 +1,645 @@
+// C ABI of libsaga: contexts, graph ingest, and the device-resident layer
+// (Scatter-ApplyEdge-Gather fused, then ApplyVertex; Sections 2.2 and 3.2).
+#include <algorithm>
+#include <cstring>
+
+#include "saga_internal.h"
+
+// ---------------------------------------------------------------------------
+// context plumbing
+// ---------------------------------------------------------------------------
+saga_status saga_ctx::fail(saga_status s, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    err = buf;
+    return s;
+}
+
+saga_status saga_ctx::dev_alloc(DevBuf* b, size_t bytes)
+{
+    if (b->p && b->bytes >= bytes) return SAGA_OK;
+    dev_free(b);
+    if (bytes == 0) return SAGA_OK;
+    const size_t rounded = (bytes + 255) / 256 * 256;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, rounded);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(SAGA_ERR_HIP, "hipMalloc(%zu) failed: %s", rounded, hipGetErrorString(e));
+    }
+    b->p = p;
+    b->bytes = rounded;
+    cur_bytes += rounded;
+    peak_bytes = std::max(peak_bytes, cur_bytes);
+    return SAGA_OK;
+}
+
+void saga_ctx::dev_free(DevBuf* b)
+{
+    if (b->p) {
+        (void)hipFree(b->p);
+        cur_bytes -= b->bytes;
+    }
+    b->p = nullptr;
+    b->bytes = 0;
+}
+
+saga_status saga_ctx::drain_events()
+{
+    if (ev_used == 0) return SAGA_OK;
+    HIP_TRY(this, hipStreamSynchronize(stream));
+    for (size_t i = 0; i < ev_used; ++i) {
+        EventSet& es = ev_pool[i];
+        float ms = 0.f;
+        // ev[0] start, ev[1] after hoist, ev[2] after gather, ev[3] after combine, ev[4] after ApplyVertex
+        if (es.has_hoist) {
+            HIP_TRY(this, hipEventElapsedTime(&ms, es.ev[0], es.ev[1]));
+            acc.ms_hoist += ms;
+        }
+        HIP_TRY(this, hipEventElapsedTime(&ms, es.ev[1], es.ev[2]));
+        acc.ms_gather += ms;
+        if (es.has_combine) {
+            HIP_TRY(this, hipEventElapsedTime(&ms, es.ev[2], es.ev[3]));
+            acc.ms_combine += ms;
+        }
+        if (es.has_apply) {
+            HIP_TRY(this, hipEventElapsedTime(&ms, es.ev[3], es.ev[4]));
+            acc.ms_apply_vertex += ms;
+        }
+        HIP_TRY(this, hipEventElapsedTime(&ms, es.ev[0], es.ev[4]));
+        acc.ms_total += ms;
+        acc.n_gather_launches += es.n_gather_launches;
+        acc.n_calls += 1;
+    }
+    ev_used = 0;
+    return SAGA_OK;
+}
+
+void build_work_list(const int64_t* col_ptr, int64_t v_begin, int64_t v_end, int64_t edge_base, int64_t split,
+                     WorkList* out)
+{
+    out->items.clear();
+    out->heavy.clear();
+    out->n_slots = 0;
+    out->max_degree = 0;
+    out->items.reserve((size_t)(v_end - v_begin));
+    for (int64_t v = v_begin; v < v_end; ++v) {
+        const int64_t b = col_ptr[v] - edge_base, e = col_ptr[v + 1] - edge_base;
+        const int64_t deg = e - b;
+        out->max_degree = std::max(out->max_degree, deg);
+        if (deg <= split) {
+            out->items.push_back(WorkItem{(int32_t)(v - v_begin), (int32_t)b, (int32_t)e, -1});
+            continue;
+        }
+        // consecutive sub-groups of near-equal length
+        const int64_t parts = (deg + split - 1) / split;
+        const int64_t len = (deg + parts - 1) / parts;
+        HeavyVertex h{(int32_t)(v - v_begin), (int32_t)out->n_slots, 0, 0};
+        for (int64_t s = b; s < e; s += len) {
+            out->items.push_back(WorkItem{(int32_t)(v - v_begin), (int32_t)s, (int32_t)std::min(e, s + len),
+                                          (int32_t)out->n_slots});
+            ++out->n_slots;
+            ++h.nslots;
+        }
+        out->heavy.push_back(h);
+    }
+}
+
+namespace {
+
+const char* kVersion = "saga-mi355x 0.1 (gfx950)";
+
+bool tensor_ok(const saga_tensor* t)
+{
+    return t && t->data && t->rows >= 0 && t->cols > 0 && t->ld >= t->cols &&
+           (t->dtype == SAGA_F32 || t->dtype == SAGA_BF16) && (t->mem == SAGA_MEM_DEVICE || t->mem == SAGA_MEM_HOST);
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        if (prev != dev) (void)hipSetDevice(dev);
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// ApplyVertex on rows already on the device (used by both paths)
+// ---------------------------------------------------------------------------
+saga_status run_apply_vertex(saga_ctx* ctx, const void* A, int64_t lda, int32_t a_dtype, int64_t rows, int32_t F_in,
+                             const saga_vertex_params* vp, void* Y, int64_t ldy, int32_t y_dtype)
+{
+    const saga_tensor* W = vp->W;
+    const int32_t F_out = (int32_t)W->cols;
+    int64_t n_pad, k_pad;
+    bt_padded_shape(F_out, F_in, a_dtype, &n_pad, &k_pad);
+    const size_t es = a_dtype == SAGA_F32 ? 4 : 2;
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * k_pad) * es)) return st;
+    HIP_TRY(ctx, launch_pack_bt_transpose(W->data, W->ld, F_in, F_out, a_dtype, ctx->ws_bt.p, ctx->stream));
+    GemmArgs g{};
+    g.A = A;
+    g.lda = lda;
+    g.Bt = ctx->ws_bt.p;
+    g.ldbt = k_pad;
+    g.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
+    g.C = Y;
+    g.ldc = ldy;
+    g.M = rows;
+    g.N = F_out;
+    g.K = F_in;
+    g.dtype = a_dtype;
+    g.out_dtype = y_dtype;
+    g.act = vp->act;
+    HIP_TRY(ctx, launch_gemm(g, ctx->stream));
+    return SAGA_OK;
+}
+
+extern "C" {
+
+const char* saga_version(void) { return kVersion; }
+
+saga_status saga_create(saga_ctx** out, int device, void* hip_stream, size_t hbm_budget_bytes)
+{
+    if (!out) return SAGA_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) {
+        (void)hipGetLastError();
+        return SAGA_ERR_HIP;
+    }
+    saga_ctx* c = new (std::nothrow) saga_ctx();
+    if (!c) return SAGA_ERR_INTERNAL;
+    c->device = device;
+    c->budget = hbm_budget_bytes;
+    DeviceGuard guard(device);
+    if (hip_stream) {
+        c->stream = static_cast<hipStream_t>(hip_stream);
+    } else {
+        if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess) {
+            delete c;
+            return SAGA_ERR_HIP;
+        }
+        c->own_stream = true;
+    }
+    *out = c;
+    return SAGA_OK;
+}
+
+saga_status saga_destroy(saga_ctx* ctx)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
+                      &ctx->ws_flag})
+        ctx->dev_free(b);
+    for (auto& es : ctx->ev_pool)
+        for (auto& e : es.ev) (void)hipEventDestroy(e);
+    if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
+    delete ctx;
+    return SAGA_OK;
+}
+
+const char* saga_last_error(const saga_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+size_t saga_peak_device_bytes(const saga_ctx* ctx) { return ctx ? ctx->peak_bytes : 0; }
+
+saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
+{
+    if (!ctx || !name) return SAGA_ERR_INVALID_ARG;
+    if (!strcmp(name, "split")) {
+        if (value < 64 || value > (1 << 24)) return ctx->fail(SAGA_ERR_INVALID_ARG, "split must be in [64, 2^24]");
+        ctx->opt_split = value;
+    } else if (!strcmp(name, "xcd_remap")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "xcd_remap must be 0 or 1");
+        ctx->opt_xcd_remap = (int)value;
+    } else if (!strcmp(name, "dst_intervals")) {
+        if (value < 0 || value > 4096) return ctx->fail(SAGA_ERR_INVALID_ARG, "dst_intervals must be in [0, 4096]");
+        ctx->opt_dst_intervals = (int)value;
+    } else if (!strcmp(name, "src_intervals")) {
+        if (value < 0 || value > 4096) return ctx->fail(SAGA_ERR_INVALID_ARG, "src_intervals must be in [0, 4096]");
+        ctx->opt_src_intervals = (int)value;
+    } else {
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "unknown option '%s'", name);
+    }
+    return SAGA_OK;
+}
+
+saga_status saga_set_profiling(saga_ctx* ctx, int32_t on)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (saga_status st = ctx->drain_events()) return st;
+    ctx->profiling = on != 0;
+    return SAGA_OK;
+}
+
+saga_status saga_reset_timings(saga_ctx* ctx)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (saga_status st = ctx->drain_events()) return st;
+    const saga_timings keep = ctx->acc;
+    ctx->acc = saga_timings{};
+    ctx->acc.n_work_items = keep.n_work_items;
+    ctx->acc.n_split_vertices = keep.n_split_vertices;
+    return SAGA_OK;
+}
+
+saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out)
+{
+    if (!ctx || !out) return SAGA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (saga_status st = ctx->drain_events()) return st;
+    *out = ctx->acc;
+    return SAGA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// graph ingest
+// ---------------------------------------------------------------------------
+saga_status saga_graph_create_csc(saga_ctx* ctx, int64_t n, int64_t nnz, const int64_t* col_ptr, const int32_t* row_idx,
+                                  int32_t where, saga_graph** out)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    if (!out) return ctx->fail(SAGA_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (n < 0 || nnz < 0 || !col_ptr || (nnz > 0 && !row_idx))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "null array or negative size");
+    if (where != SAGA_MEM_DEVICE && where != SAGA_MEM_HOST) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad placement");
+    if (n > 0x7fffffffLL - 1 || nnz > 0x7fffffffLL - 64)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "graph too large for 32-bit vertex ids / edge offsets");
+    DeviceGuard guard(ctx->device);
+
+    saga_graph* g = new (std::nothrow) saga_graph();
+    if (!g) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    g->ctx = ctx;
+    g->n = n;
+    g->nnz = nnz;
+    g->where = where;
+    auto bail = [&](saga_status st) {
+        saga_graph_destroy(g);
+        return st;
+    };
+
+    // column pointers are always examined on the host
+    try {
+        g->h_col_ptr.resize((size_t)n + 1);
+    } catch (...) {
+        return bail(ctx->fail(SAGA_ERR_INTERNAL, "out of host memory"));
+    }
+    if (where == SAGA_MEM_DEVICE) {
+        hipError_t e = hipMemcpyAsync(g->h_col_ptr.data(), col_ptr, sizeof(int64_t) * ((size_t)n + 1), hipMemcpyDeviceToHost,
+                                      ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) return bail(ctx->fail(SAGA_ERR_HIP, "copying col_ptr: %s", hipGetErrorString(e)));
+    } else {
+        memcpy(g->h_col_ptr.data(), col_ptr, sizeof(int64_t) * ((size_t)n + 1));
+    }
+    const int64_t* cp = g->h_col_ptr.data();
+    if (cp[0] != 0) return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "col_ptr[0] = %lld, expected 0", (long long)cp[0]));
+    for (int64_t v = 0; v < n; ++v)
+        if (cp[v + 1] < cp[v])
+            return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "col_ptr decreases at vertex %lld", (long long)v));
+    if (cp[n] != nnz)
+        return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "col_ptr[n] = %lld but n_edges = %lld", (long long)cp[n], (long long)nnz));
+
+    if (where == SAGA_MEM_HOST) {
+        // streamed graphs stay on the host; validate the ids here
+        try {
+            g->h_row_idx.assign(row_idx, row_idx + nnz);
+        } catch (...) {
+            return bail(ctx->fail(SAGA_ERR_INTERNAL, "out of host memory"));
+        }
+        for (int64_t v = 0; v < n; ++v) {
+            for (int64_t e = cp[v]; e < cp[v + 1]; ++e) {
+                const int32_t u = row_idx[e];
+                if (u < 0 || u >= n)
+                    return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "source id %d out of range at edge %lld", u, (long long)e));
+                if (e > cp[v] && row_idx[e - 1] >= u)
+                    return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "column %lld is not strictly ascending at edge %lld",
+                                          (long long)v, (long long)e));
+            }
+        }
+        int64_t maxdeg = 0;
+        for (int64_t v = 0; v < n; ++v) maxdeg = std::max(maxdeg, cp[v + 1] - cp[v]);
+        g->max_degree = maxdeg;
+        *out = g;
+        return SAGA_OK;
+    }
+
+    WorkList wl;
+    build_work_list(cp, 0, n, 0, ctx->opt_split, &wl);
+    g->n_items = (int64_t)wl.items.size();
+    g->n_heavy = (int64_t)wl.heavy.size();
+    g->n_slots = wl.n_slots;
+    g->max_degree = wl.max_degree;
+    saga_status st;
+    if ((st = ctx->dev_alloc(&g->d_row_idx, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1)))) return bail(st);
+    if ((st = ctx->dev_alloc(&g->d_items, sizeof(WorkItem) * std::max<size_t>(wl.items.size(), 1)))) return bail(st);
+    if ((st = ctx->dev_alloc(&g->d_heavy, sizeof(HeavyVertex) * std::max<size_t>(wl.heavy.size(), 1)))) return bail(st);
+    if ((st = ctx->dev_alloc(&ctx->ws_flag, 256))) return bail(st);
+    hipError_t e = hipSuccess;
+    if (nnz > 0) e = hipMemcpyAsync(g->d_row_idx.p, row_idx, sizeof(int32_t) * (size_t)nnz, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e == hipSuccess && !wl.items.empty())
+        e = hipMemcpyAsync(g->d_items.p, wl.items.data(), sizeof(WorkItem) * wl.items.size(), hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess && !wl.heavy.empty())
+        e = hipMemcpyAsync(g->d_heavy.p, wl.heavy.data(), sizeof(HeavyVertex) * wl.heavy.size(), hipMemcpyHostToDevice,
+                           ctx->stream);
+    if (e == hipSuccess) e = launch_zero_bytes(ctx->ws_flag.p, 256, ctx->stream);
+    if (e == hipSuccess)
+        e = launch_validate_items(static_cast<const WorkItem*>(g->d_items.p), g->n_items,
+                                  static_cast<const int32_t*>(g->d_row_idx.p), n, static_cast<int32_t*>(ctx->ws_flag.p),
+                                  ctx->stream);
+    int32_t flag = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&flag, ctx->ws_flag.p, sizeof flag, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // also keeps wl alive until the copies are done
+    if (e != hipSuccess) return bail(ctx->fail(SAGA_ERR_HIP, "graph upload: %s", hipGetErrorString(e)));
+    if (flag) return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "row_idx has an id out of range or a column that is not strictly ascending"));
+    g->h_col_ptr.clear();
+    g->h_col_ptr.shrink_to_fit();
+    *out = g;
+    return SAGA_OK;
+}
+
+saga_status saga_graph_destroy(saga_graph* g)
+{
+    if (!g) return SAGA_ERR_INVALID_ARG;
+    saga_ctx* ctx = g->ctx;
+    DeviceGuard guard(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (DevBuf* b : {&g->d_row_idx, &g->d_items, &g->d_heavy, &g->d_edge_data}) ctx->dev_free(b);
+    if (g->grid) chunk_grid_destroy(ctx, g->grid);
+    delete g;
+    return SAGA_OK;
+}
+
+saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
+{
+    if (!g) return SAGA_ERR_INVALID_ARG;
+    saga_ctx* ctx = g->ctx;
+    if (!w && g->nnz > 0) return ctx->fail(SAGA_ERR_INVALID_ARG, "edge_weight is null");
+    DeviceGuard guard(ctx->device);
+    if (g->where == SAGA_MEM_HOST) {
+        try {
+            g->h_edge_data.assign(w, w + g->nnz);
+        } catch (...) {
+            return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+        }
+        if (g->grid) {  // chunk-ordered copy is rebuilt at the next call
+            chunk_grid_destroy(ctx, g->grid);
+            g->grid = nullptr;
+        }
+        return SAGA_OK;
+    }
+    if (saga_status st = ctx->dev_alloc(&g->d_edge_data, sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1))) return st;
+    if (g->nnz > 0) {
+        HIP_TRY(ctx, hipMemcpyAsync(g->d_edge_data.p, w, sizeof(float) * (size_t)g->nnz, hipMemcpyDeviceToDevice, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    return SAGA_OK;
+}
+
+saga_status saga_graph_info(const saga_graph* g, int64_t* max_in_degree, int64_t* n_work_items, int64_t* n_split_vertices)
+{
+    if (!g) return SAGA_ERR_INVALID_ARG;
+    if (max_in_degree) *max_in_degree = g->max_degree;
+    if (n_work_items) *n_work_items = g->n_items;
+    if (n_split_vertices) *n_split_vertices = g->n_heavy;
+    return SAGA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// one layer, everything resident in HBM
+// ---------------------------------------------------------------------------
+static saga_status resident_forward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
+                                    int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)X->cols;
+    const bool bf16 = X->dtype == SAGA_BF16;
+    const bool has_w = vp && vp->W;
+    hipStream_t s = ctx->stream;
+
+    saga_ctx::EventSet* es = nullptr;
+    if (ctx->profiling) {
+        if (ctx->ev_used == ctx->ev_pool.size()) {
+            if (ctx->ev_pool.size() >= 512) {
+                if (saga_status st = ctx->drain_events()) return st;
+            } else {
+                saga_ctx::EventSet ne{};
+                for (auto& e : ne.ev) HIP_TRY(ctx, hipEventCreate(&e));
+                ctx->ev_pool.push_back(ne);
+            }
+        }
+        es = &ctx->ev_pool[ctx->ev_used];
+        es->has_hoist = es->has_combine = es->has_apply = false;
+        es->n_gather_launches = 1;
+        HIP_TRY(ctx, hipEventRecord(es->ev[0], s));
+    }
+
+    GatherArgs ga{};
+    ga.items = static_cast<const WorkItem*>(g->d_items.p);
+    ga.n_items = g->n_items;
+    ga.row_idx = static_cast<const int32_t*>(g->d_row_idx.p);
+    ga.F = F;
+    ga.agg = agg;
+    ga.op = ep->op;
+    ga.xcd_remap = ctx->opt_xcd_remap;
+    ga.accumulate = 0;
+
+    if (ep->op == SAGA_EDGE_GATED) {
+        // Section 3.2: H = X [Wgs^T | Wm^T | Wgd^T] (+ [0 | 0 | b]) once per vertex
+        int64_t n_pad, k_pad;
+        bt_padded_shape(3 * F, F, SAGA_F32, &n_pad, &k_pad);
+        saga_status st;
+        if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+        if ((st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)(3 * F)))) return st;
+        if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * 3 * F))) return st;
+        float* bt = static_cast<float*>(ctx->ws_bt.p);
+        float* bias = static_cast<float*>(ctx->ws_bias.p);
+        const float* Wg = static_cast<const float*>(ep->W_gate->data);
+        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+        HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)(3 * F), s));
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr,
+                                         ep->W_msg ? ep->W_msg->ld : 0, 0, F, F, bt, k_pad, F, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
+        if (ep->b_gate)
+            HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
+        GemmArgs hg{};
+        hg.A = X->data;
+        hg.lda = X->ld;
+        hg.Bt = bt;
+        hg.ldbt = k_pad;
+        hg.bias = bias;
+        hg.C = ctx->ws_hoist.p;
+        hg.ldc = 3 * (int64_t)F;
+        hg.M = n;
+        hg.N = 3 * F;
+        hg.K = F;
+        hg.dtype = hg.out_dtype = SAGA_F32;
+        hg.act = SAGA_ACT_NONE;
+        HIP_TRY(ctx, launch_gemm(hg, s));
+        ga.src = ctx->ws_hoist.p;
+        ga.ld_src = 3 * (int64_t)F;
+        ga.dst = static_cast<const float*>(ctx->ws_hoist.p) + 2 * F;
+        ga.ld_dst = 3 * (int64_t)F;
+        ga.dtype = SAGA_F32;
+        if (es) es->has_hoist = true;
+    } else {
+        ga.src = X->data;
+        ga.ld_src = X->ld;
+        ga.dtype = X->dtype;
+        if (ep->op == SAGA_EDGE_MUL_WEIGHT)
+            ga.edge_w = ep->edge_weight ? ep->edge_weight : static_cast<const float*>(g->d_edge_data.p);
+    }
+    if (es) HIP_TRY(ctx, hipEventRecord(es->ev[1], s));
+
+    // where the Gather output goes
+    //   fp32: accum_out if given, else Y itself when there is no ApplyVertex, else workspace
+    //   bf16: a bf16 copy feeds the ApplyVertex product (or is Y itself without one);
+    //         the fp32 rows are written only when accum_out asks for them
+    if (!bf16) {
+        if (accum_out) {
+            ga.out = static_cast<float*>(accum_out->data);
+            ga.ld_out = accum_out->ld;
+        } else if (!has_w) {
+            ga.out = static_cast<float*>(Y->data);
+            ga.ld_out = Y->ld;
+        } else {
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)n * F)) return st;
+            ga.out = static_cast<float*>(ctx->ws_accum.p);
+            ga.ld_out = F;
+        }
+    } else {
+        if (accum_out) {
+            ga.out = static_cast<float*>(accum_out->data);
+            ga.ld_out = accum_out->ld;
+        }
+        if (!has_w) {
+            ga.out16 = static_cast<uint16_t*>(Y->data);
+            ga.ld_out16 = Y->ld;
+        } else {
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_accum16, sizeof(uint16_t) * (size_t)n * F)) return st;
+            ga.out16 = static_cast<uint16_t*>(ctx->ws_accum16.p);
+            ga.ld_out16 = F;
+        }
+    }
+    if (g->n_slots > 0) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * F)) return st;
+        ga.partials = static_cast<float*>(ctx->ws_partials.p);
+    }
+    HIP_TRY(ctx, launch_gather(ga, s));
+    if (es) HIP_TRY(ctx, hipEventRecord(es->ev[2], s));
+
+    if (g->n_heavy > 0) {
+        CombineArgs ca{};
+        ca.heavy = static_cast<const HeavyVertex*>(g->d_heavy.p);
+        ca.n_heavy = g->n_heavy;
+        ca.partials = ga.partials;
+        ca.F = F;
+        ca.agg = agg;
+        ca.out = ga.out;
+        ca.ld_out = ga.ld_out;
+        ca.out16 = ga.out16;
+        ca.ld_out16 = ga.ld_out16;
+        ca.accumulate = 0;
+        HIP_TRY(ctx, launch_combine(ca, s));
+        if (es) es->has_combine = true;
+    }
+    if (es) HIP_TRY(ctx, hipEventRecord(es->ev[3], s));
+
+    if (has_w) {
+        const void* A = bf16 ? static_cast<const void*>(ga.out16) : static_cast<const void*>(ga.out);
+        const int64_t lda = bf16 ? ga.ld_out16 : ga.ld_out;
+        if (saga_status st = run_apply_vertex(ctx, A, lda, X->dtype, n, F, vp, Y->data, Y->ld, Y->dtype)) return st;
+        if (es) es->has_apply = true;
+    }
+    if (es) {
+        HIP_TRY(ctx, hipEventRecord(es->ev[4], s));
+        ctx->ev_used += 1;
+    }
+    ctx->acc.n_work_items = g->n_items;
+    ctx->acc.n_split_vertices = g->n_heavy;
+    ctx->acc.plan_dst_intervals = ctx->acc.plan_src_intervals = 0;
+    return SAGA_OK;
+}
+
+saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
+                               int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    if (!g || !X || !ep || !Y) return ctx->fail(SAGA_ERR_INVALID_ARG, "null argument");
+    if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
+    if (!tensor_ok(X) || !tensor_ok(Y)) return ctx->fail(SAGA_ERR_INVALID_ARG, "malformed X or Y tensor");
+    if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
+    if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_GATED) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
+    if (X->rows != g->n || Y->rows != g->n)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "X/Y have %lld/%lld rows, graph has %lld vertices", (long long)X->rows,
+                         (long long)Y->rows, (long long)g->n);
+    if (X->cols > (1 << 20)) return ctx->fail(SAGA_ERR_UNSUPPORTED, "feature width above 2^20");
+    const int64_t F = X->cols;
+    const bool has_w = vp && vp->W;
+    if (vp && vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
+    if (has_w) {
+        const saga_tensor* W = vp->W;
+        if (!tensor_ok(W) || W->mem != SAGA_MEM_DEVICE || W->rows != F || W->dtype != X->dtype)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out tensor of X's dtype");
+        if (vp->bias && (!tensor_ok(vp->bias) || vp->bias->mem != SAGA_MEM_DEVICE || vp->bias->dtype != SAGA_F32 ||
+                         vp->bias->rows * vp->bias->cols != W->cols))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "bias must be F_out fp32 values on the device");
+        if (Y->cols != W->cols) return ctx->fail(SAGA_ERR_INVALID_ARG, "Y has %lld columns, W has %lld", (long long)Y->cols, (long long)W->cols);
+    } else {
+        if (Y->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "without W, Y must be n x F_in");
+        if (vp && (vp->bias || vp->act != SAGA_ACT_NONE))
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "bias/activation without W");
+    }
+    if (Y->dtype != X->dtype) return ctx->fail(SAGA_ERR_INVALID_ARG, "Y must have X's dtype");
+    if (ep->op == SAGA_EDGE_GATED) {
+        if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "gated ApplyEdge is fp32 only");
+        const saga_tensor* Wg = ep->W_gate;
+        if (!tensor_ok(Wg) || Wg->mem != SAGA_MEM_DEVICE || Wg->dtype != SAGA_F32 || Wg->rows != F || Wg->cols != 2 * F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_gate must be a device F x 2F fp32 tensor");
+        if (ep->b_gate && (!tensor_ok(ep->b_gate) || ep->b_gate->mem != SAGA_MEM_DEVICE || ep->b_gate->dtype != SAGA_F32 ||
+                           ep->b_gate->rows * ep->b_gate->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "b_gate must be F fp32 values on the device");
+        if (ep->W_msg && (!tensor_ok(ep->W_msg) || ep->W_msg->mem != SAGA_MEM_DEVICE || ep->W_msg->dtype != SAGA_F32 ||
+                          ep->W_msg->rows != F || ep->W_msg->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_msg must be a device F x F fp32 tensor");
+    }
+    DeviceGuard guard(ctx->device);
+
+    const bool streamed = X->mem == SAGA_MEM_HOST;
+    if (streamed) {
+        if (Y->mem != SAGA_MEM_HOST || g->where != SAGA_MEM_HOST)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need X, Y and the graph in host memory");
+        if (accum_out) return ctx->fail(SAGA_ERR_UNSUPPORTED, "accum_out is not available on the streamed path");
+        if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
+        if (ep->op == SAGA_EDGE_GATED) return ctx->fail(SAGA_ERR_UNSUPPORTED, "gated ApplyEdge is not streamed");
+        if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
+        return streamed_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
+    }
+    if (Y->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "resident calls need X, Y and the graph in device memory");
+    if (accum_out && (!tensor_ok(accum_out) || accum_out->mem != SAGA_MEM_DEVICE || accum_out->dtype != SAGA_F32 ||
+                      accum_out->rows != g->n || accum_out->cols != F))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "accum_out must be a device n x F_in fp32 tensor");
+    if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
+    if (g->n == 0) return SAGA_OK;
+    return resident_forward(ctx, g, X, ep, agg, vp, Y, accum_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,209 @@
+// Internal declarations shared by the translation units of libsaga.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/saga.h"
+
+// ---------------------------------------------------------------------------
+// work list: the unit a wavefront of the propagation kernel processes
+// ---------------------------------------------------------------------------
+// One item is a run of consecutive in-edges of one destination vertex
+// (Section 3.3: a vertex's in-edge group, cut into consecutive sub-groups when
+// the in-degree is large). slot < 0: the item covers the whole column and its
+// result is the vertex's row. slot >= 0: the item writes a partial row
+// `slot`, and a combine pass reduces a vertex's partial rows in slot order.
+struct WorkItem {
+    int32_t v;     // destination vertex (local to the output interval)
+    int32_t e0;    // first edge
+    int32_t e1;    // one past the last edge
+    int32_t slot;  // partial-row index, or -1
+};
+struct HeavyVertex {
+    int32_t v;
+    int32_t slot0;
+    int32_t nslots;
+    int32_t pad;
+};
+
+struct WorkList {
+    std::vector<WorkItem> items;
+    std::vector<HeavyVertex> heavy;
+    int64_t n_slots = 0;
+    int64_t max_degree = 0;
+};
+
+// Build the work list of columns [v_begin, v_end) of a CSC whose col_ptr is on
+// the host. Edge offsets are relative to edge_base; vertex ids relative to
+// v_begin. split = maximum number of edges in one item.
+void build_work_list(const int64_t* col_ptr, int64_t v_begin, int64_t v_end, int64_t edge_base,
+                     int64_t split, WorkList* out);
+
+// ---------------------------------------------------------------------------
+// device buffers with accounting
+// ---------------------------------------------------------------------------
+struct saga_ctx;
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+};
+
+struct saga_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool own_stream = false;
+    size_t budget = 0;
+    size_t cur_bytes = 0, peak_bytes = 0;
+    std::string err;
+
+    // tunables
+    int64_t opt_split = 1024;
+    int opt_xcd_remap = 1;
+    int opt_dst_intervals = 0, opt_src_intervals = 0;
+
+    // reusable workspace (grown on demand, never shrunk until destroy)
+    DevBuf ws_accum;     // Gather output A (fp32 or bf16) when the caller gives no accum_out
+    DevBuf ws_accum16;   // bf16 copy of A for the bf16 ApplyVertex product
+    DevBuf ws_partials;  // partial rows of split vertices
+    DevBuf ws_hoist;     // [Ps | M | Pd] per vertex (gated)
+    DevBuf ws_bt;        // packed, transposed weights
+    DevBuf ws_bias;      // packed bias for the hoisted product
+    DevBuf ws_flag;      // validation flag
+
+    // profiling
+    bool profiling = false;
+    struct EventSet {
+        hipEvent_t ev[5];
+        bool has_hoist, has_combine, has_apply;
+        int n_gather_launches;
+    };
+    std::vector<EventSet> ev_pool;
+    size_t ev_used = 0;
+    saga_timings acc{};
+
+    saga_status fail(saga_status s, const char* fmt, ...);
+    saga_status dev_alloc(DevBuf* b, size_t bytes);  // frees and reallocates when too small
+    void dev_free(DevBuf* b);
+    saga_status drain_events();
+};
+
+struct ChunkGrid;  // streamed representation (chunked.hip)
+
+struct saga_graph {
+    saga_ctx* ctx = nullptr;
+    int64_t n = 0, nnz = 0;
+    int32_t where = SAGA_MEM_DEVICE;
+    // resident form
+    DevBuf d_row_idx, d_items, d_heavy, d_edge_data;
+    int64_t n_items = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
+    // host form (streamed)
+    std::vector<int64_t> h_col_ptr;
+    std::vector<int32_t> h_row_idx;
+    std::vector<float> h_edge_data;
+    ChunkGrid* grid = nullptr;
+};
+
+#define HIP_TRY(ctx, call)                                                                   \
+    do {                                                                                     \
+        hipError_t e__ = (call);                                                             \
+        if (e__ != hipSuccess)                                                               \
+            return (ctx)->fail(SAGA_ERR_HIP, "%s failed: %s (%s:%d)", #call,                \
+                               hipGetErrorString(e__), __FILE__, __LINE__);                  \
+    } while (0)
+
+// ---------------------------------------------------------------------------
+// kernel launchers (each validates nothing: callers check shapes first)
+// ---------------------------------------------------------------------------
+struct GatherArgs {
+    const WorkItem* items;
+    int64_t n_items;
+    const int32_t* row_idx;  // source ids, local to the rows of `src`
+    const float* edge_w;     // nullable (COPY)
+    // LINEAR ops: src = X (dtype), ld_src elements between rows, F features.
+    // GATED: src = hoisted fp32 rows [Ps | M | Pd], ld_src = 3F; the gate's
+    // destination part is read from row (v + dst_row_offset) of `dst`.
+    const void* src;
+    int64_t ld_src;
+    const float* dst;        // GATED only
+    int64_t ld_dst;
+    int32_t F;
+    int32_t dtype;           // saga_dtype of src (GATED: F32)
+    int32_t op;              // saga_edge_op
+    int32_t agg;             // saga_agg
+    float* out;              // fp32 rows of the output interval (nullable if out16 given)
+    int64_t ld_out;
+    uint16_t* out16;         // optional bf16 copy of the rows (nullable)
+    int64_t ld_out16;
+    float* partials;         // n_slots x F fp32
+    int32_t accumulate;      // 1: combine with what `out` already holds (streamed, chunk i > 0)
+    int32_t xcd_remap;
+};
+hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
+
+struct CombineArgs {
+    const HeavyVertex* heavy;
+    int64_t n_heavy;
+    const float* partials;
+    int32_t F;
+    int32_t agg;
+    float* out;
+    int64_t ld_out;
+    uint16_t* out16;
+    int64_t ld_out16;
+    int32_t accumulate;
+};
+hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+
+// rows x cols fp32 fill / max-identity fix-up for streamed max-Gather
+hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t s);
+hipError_t launch_neg_inf_to_zero(float* p, int64_t count, hipStream_t s);
+hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s);
+
+// Validate row_idx against the work list: ids in [0, n_src), strictly ascending inside each
+// column. *flag (device int32, pre-zeroed) is set nonzero on violation.
+hipError_t launch_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx,
+                                 int64_t n_src, int32_t* flag, hipStream_t s);
+
+// C[M x N] = act(A[M x K] * Bt[N x K]^T + bias), fp32 accumulation on MFMA.
+// Bt must be padded: rows to a multiple of 128 and K to a multiple of 16 bytes
+// worth of elements * 4 (see pack_*), zero-filled.
+struct GemmArgs {
+    const void* A;      // M x K, dtype
+    int64_t lda;
+    const void* Bt;     // Npad x Kpad, dtype, row n = column n of the weight matrix
+    int64_t ldbt;       // = Kpad
+    const float* bias;  // [N] fp32, nullable
+    void* C;            // M x N, out_dtype
+    int64_t ldc;
+    int64_t M;
+    int32_t N, K;
+    int32_t dtype;      // of A and Bt
+    int32_t out_dtype;  // of C
+    int32_t act;
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+// Size (elements) of a padded Bt for N x K.
+void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_t* k_pad);
+// Bt[n][k] = W[k][n] (W is K x N row-major with ldw); pads with zeros. dtype in = dtype out.
+hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32_t N, int32_t dtype,
+                                    void* Bt, hipStream_t s);
+// Bt rows [row0, row0 + R) = Wsrc[r][col0 .. col0 + K) (already output-channel major); Wsrc NULL = identity.
+hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int32_t R, int32_t K,
+                               float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
+hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s);
+
+// streamed path (chunked.hip)
+saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
+                             int32_t agg, const saga_vertex_params* vp, saga_tensor* Y);
+void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
+
+// shared by api and chunked: ApplyVertex on a block of rows already on the device
+saga_status run_apply_vertex(saga_ctx* ctx, const void* A, int64_t lda, int32_t a_dtype, int64_t rows,
+                             int32_t F_in, const saga_vertex_params* vp, void* Y, int64_t ldy, int32_t y_dtype);
