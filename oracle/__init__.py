@@ -38,9 +38,9 @@ def lib():
         P, I64, I = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.saga_oracle_num_threads.restype = I
         L.saga_oracle_hoist.restype = I
-        L.saga_oracle_hoist.argtypes = [I64, P, I64, P, P, P, P, P]
+        L.saga_oracle_hoist.argtypes = [I64, P, I64, P, P, P, P, P, P, P, P]
         L.saga_oracle_layer.restype = I
-        L.saga_oracle_layer.argtypes = [I64, P, P, P, I64, I, P, P, P, P, P, P, P, I,
+        L.saga_oracle_layer.argtypes = [I64, P, P, P, I64, I, P, P, P, P, P, P, P, P, P, P, I,
                                         P, P, I64, I, P, I64, P, P, P, P]
         _lib = L
     return _lib
@@ -59,15 +59,16 @@ def _ptr(a):
 
 
 def hoist(X, W_gate, W_msg=None):
-    """Per-vertex products (Ps, Pd, M) of Section 3.2, fp64 arrays n x F."""
+    """Per-vertex products of Section 3.2 as fp64 arrays n x F: (Ps, Pd, M, Ps_abs, Pd_abs, M_abs),
+    the last three being the absolute-term sums of the first three."""
     X = _f32(X)
     n, F = X.shape
     Wg, Wm = _f32(W_gate), _f32(W_msg)
     assert Wg.shape == (F, 2 * F) and (Wm is None or Wm.shape == (F, F))
-    Ps, Pd, M = (np.empty((n, F), np.float64) for _ in range(3))
-    rc = lib().saga_oracle_hoist(n, _ptr(X), F, _ptr(Wg), _ptr(Wm), _ptr(Ps), _ptr(Pd), _ptr(M))
+    out = tuple(np.empty((n, F), np.float64) for _ in range(6))
+    rc = lib().saga_oracle_hoist(n, _ptr(X), F, _ptr(Wg), _ptr(Wm), *[_ptr(a) for a in out])
     assert rc == 0
-    return Ps, Pd, M
+    return out
 
 
 def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_gate=None, W_msg=None,
@@ -76,7 +77,7 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
 
     Returns a dict with fp64 arrays: "A" (Gather output, nv x F), "A_abs",
     and, when W is given, "Y" (nv x F_out) and "Y_abs". vlist selects the
-    destination vertices (default: all, in order). hoisted = (Ps, Pd, M) from
+    destination vertices (default: all, in order). hoisted = the tuple from
     hoist() switches the gated message to the hoisted form.
     """
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
@@ -106,9 +107,10 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
     else:
         vl = np.ascontiguousarray(np.asarray(vlist, dtype=np.int64))
         nv = vl.shape[0]
-    Ps = Pd = M = None
+    H = [None] * 6
     if hoisted is not None:
-        Ps, Pd, M = (np.ascontiguousarray(a, dtype=np.float64) for a in hoisted)
+        H = [np.ascontiguousarray(a, dtype=np.float64) for a in hoisted]
+        assert len(H) == 6
     out = {"A": np.empty((nv, F), np.float64)}
     if want_abs:
         out["A_abs"] = np.empty((nv, F), np.float64)
@@ -118,7 +120,7 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
             out["Y_abs"] = np.empty((nv, F_out), np.float64)
     rc = lib().saga_oracle_layer(
         n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], _ptr(w),
-        _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(Ps), _ptr(Pd), _ptr(M), AGGS[agg],
+        _ptr(Wg), _ptr(bg), _ptr(Wm), *[_ptr(a) for a in H], AGGS[agg],
         _ptr(Wv), _ptr(bv), F_out, ACTS[act], _ptr(vl), nv,
         _ptr(out["A"]), _ptr(out.get("A_abs")), _ptr(out.get("Y")), _ptr(out.get("Y_abs")))
     if rc != 0:

@@ -32,9 +32,14 @@
  * w_e * x (so that max-Gather is reproducible bit for bit).
  * Gather over an empty in-edge set yields 0 for both accumulators.
  *
- * Besides each value the oracle returns the same expression with every term
- * replaced by its absolute value (A_abs, Y_abs): the scale against which a
- * floating-point summation error is measured.
+ * Besides each value the oracle returns the scale against which a
+ * floating-point error of that value is measured (A_abs, Y_abs): the same
+ * expression with every term of every sum replaced by its absolute value.
+ * A gated message g * t (g = sigmoid(z), t = sum_k Wm[f,k] x_u[k]) is itself
+ * built from sums, so its scale is g * (T + |t| (1 - g) Z), where T and Z are
+ * the absolute-term sums of t and of the gate's pre-activation z, and
+ * g (1 - g) is the sigmoid's derivative: a first-order forward error bound
+ * per unit of relative rounding error.
  */
 #include <math.h>
 #include <stdint.h>
@@ -64,28 +69,39 @@ static double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
  * (M = X when W_msg is NULL). Outputs are n x F fp64.
  */
 int saga_oracle_hoist(int64_t n, const float* X, int64_t F, const float* W_gate, const float* W_msg,
-                      double* Ps, double* Pd, double* M)
+                      double* Ps, double* Pd, double* M, double* Ps_abs, double* Pd_abs, double* M_abs)
 {
     if (!X || !W_gate || !Ps || !Pd || !M || n < 0 || F <= 0) return 1;
+    if ((Ps_abs || Pd_abs || M_abs) && !(Ps_abs && Pd_abs && M_abs)) return 1;
 #pragma omp parallel for schedule(static)
     for (int64_t v = 0; v < n; ++v) {
         const float* x = X + v * F;
         for (int64_t f = 0; f < F; ++f) {
             const float* wg = W_gate + f * 2 * F;
-            double s = 0.0, d = 0.0;
+            double s = 0.0, d = 0.0, sa = 0.0, da = 0.0;
             for (int64_t k = 0; k < F; ++k) {
                 s += (double)wg[k] * (double)x[k];
                 d += (double)wg[F + k] * (double)x[k];
+                sa += fabs((double)wg[k] * (double)x[k]);
+                da += fabs((double)wg[F + k] * (double)x[k]);
             }
             Ps[v * F + f] = s;
             Pd[v * F + f] = d;
+            double t = (double)x[f], ta = fabs((double)x[f]);
             if (W_msg) {
                 const float* wm = W_msg + f * F;
-                double t = 0.0;
-                for (int64_t k = 0; k < F; ++k) t += (double)wm[k] * (double)x[k];
-                M[v * F + f] = t;
-            } else {
-                M[v * F + f] = (double)x[f];
+                t = 0.0;
+                ta = 0.0;
+                for (int64_t k = 0; k < F; ++k) {
+                    t += (double)wm[k] * (double)x[k];
+                    ta += fabs((double)wm[k] * (double)x[k]);
+                }
+            }
+            M[v * F + f] = t;
+            if (Ps_abs) {
+                Ps_abs[v * F + f] = sa;
+                Pd_abs[v * F + f] = da;
+                M_abs[v * F + f] = ta;
             }
         }
     }
@@ -99,7 +115,8 @@ int saga_oracle_hoist(int64_t n, const float* X, int64_t F, const float* W_gate,
  *   edge_op    EDGE_COPY / EDGE_MUL_WEIGHT (edge_w[nnz]) / EDGE_GATED
  *   W_gate, b_gate, W_msg   gated parameters (b_gate, W_msg nullable)
  *   Ps, Pd, M  when Ps is non-NULL the gated message is formed from these
- *              hoisted per-vertex products instead of per-edge products
+ *              hoisted per-vertex products instead of per-edge products;
+ *              Ps_abs, Pd_abs, M_abs are their absolute-term sums
  *   agg        AGG_SUM / AGG_MAX
  *   W, bias    ApplyVertex parameters; W NULL skips ApplyVertex
  *   A, A_abs   nv x F   Gather output and its absolute-term sum (nullable)
@@ -111,6 +128,7 @@ int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
                       int edge_op, const float* edge_w,
                       const float* W_gate, const float* b_gate, const float* W_msg,
                       const double* Ps, const double* Pd, const double* M,
+                      const double* Ps_abs, const double* Pd_abs, const double* M_abs,
                       int agg,
                       const float* W, const float* bias, int64_t F_out, int act,
                       const int64_t* vlist, int64_t nv,
@@ -122,14 +140,15 @@ int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
     if (edge_op == EDGE_GATED && !W_gate && !Ps) return 1;
     if (edge_op < 0 || edge_op > 2 || agg < 0 || agg > 1) return 1;
     if (W && (!Y || F_out <= 0)) return 1;
-    if (Ps && (!Pd || !M)) return 1;
+    if (Ps && (!Pd || !M || !Ps_abs || !Pd_abs || !M_abs)) return 1;
     int bad = 0;
 
 #pragma omp parallel
     {
-        double* acc = (double*)malloc(sizeof(double) * (size_t)F * 3);
+        double* acc = (double*)malloc(sizeof(double) * (size_t)F * 4);
         double* aab = acc + F;
         double* msg = acc + 2 * F;
+        double* mab = acc + 3 * F; /* error scale of msg */
 #pragma omp for schedule(dynamic, 16)
         for (int64_t i = 0; i < nv; ++i) {
             const int64_t v = vlist ? vlist[i] : i;
@@ -147,45 +166,60 @@ int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
                 const float* xu = X + u * F;
                 /* ---- Scatter + ApplyEdge: message msg[f] of edge u -> v ---- */
                 if (edge_op == EDGE_COPY) {
-                    for (int64_t f = 0; f < F; ++f) msg[f] = (double)xu[f];
+                    for (int64_t f = 0; f < F; ++f) { msg[f] = (double)xu[f]; mab[f] = fabs(msg[f]); }
                 } else if (edge_op == EDGE_MUL_WEIGHT) {
                     const float w = edge_w[e];
                     for (int64_t f = 0; f < F; ++f) {
                         const float p = w * xu[f]; /* one fp32 multiply */
                         msg[f] = (double)p;
+                        mab[f] = fabs(msg[f]);
                     }
                 } else if (Ps) {
                     for (int64_t f = 0; f < F; ++f) {
-                        double z = Ps[u * F + f] + Pd[v * F + f] + (b_gate ? (double)b_gate[f] : 0.0);
-                        msg[f] = sigmoid(z) * M[u * F + f];
+                        const double b = b_gate ? (double)b_gate[f] : 0.0;
+                        const double z = Ps[u * F + f] + Pd[v * F + f] + b;
+                        const double za = Ps_abs[u * F + f] + Pd_abs[v * F + f] + fabs(b);
+                        const double g = sigmoid(z), t = M[u * F + f];
+                        msg[f] = g * t;
+                        mab[f] = g * (M_abs[u * F + f] + fabs(t) * (1.0 - g) * za);
                     }
                 } else {
                     for (int64_t f = 0; f < F; ++f) {
                         const float* wg = W_gate + f * 2 * F;
                         double z = b_gate ? (double)b_gate[f] : 0.0;
-                        for (int64_t k = 0; k < F; ++k) z += (double)wg[k] * (double)xu[k];
-                        for (int64_t k = 0; k < F; ++k) z += (double)wg[F + k] * (double)xv[k];
-                        double t;
+                        double za = fabs(z);
+                        for (int64_t k = 0; k < F; ++k) {
+                            z += (double)wg[k] * (double)xu[k];
+                            za += fabs((double)wg[k] * (double)xu[k]);
+                        }
+                        for (int64_t k = 0; k < F; ++k) {
+                            z += (double)wg[F + k] * (double)xv[k];
+                            za += fabs((double)wg[F + k] * (double)xv[k]);
+                        }
+                        double t = (double)xu[f], ta = fabs((double)xu[f]);
                         if (W_msg) {
                             const float* wm = W_msg + f * F;
                             t = 0.0;
-                            for (int64_t k = 0; k < F; ++k) t += (double)wm[k] * (double)xu[k];
-                        } else {
-                            t = (double)xu[f];
+                            ta = 0.0;
+                            for (int64_t k = 0; k < F; ++k) {
+                                t += (double)wm[k] * (double)xu[k];
+                                ta += fabs((double)wm[k] * (double)xu[k]);
+                            }
                         }
-                        msg[f] = sigmoid(z) * t;
+                        const double g = sigmoid(z);
+                        msg[f] = g * t;
+                        mab[f] = g * (ta + fabs(t) * (1.0 - g) * za);
                     }
                 }
                 /* ---- Gather ---- */
                 if (agg == AGG_SUM) {
-                    for (int64_t f = 0; f < F; ++f) { acc[f] += msg[f]; aab[f] += fabs(msg[f]); }
+                    for (int64_t f = 0; f < F; ++f) { acc[f] += msg[f]; aab[f] += mab[f]; }
                 } else if (e == e0) {
-                    for (int64_t f = 0; f < F; ++f) acc[f] = msg[f];
+                    for (int64_t f = 0; f < F; ++f) { acc[f] = msg[f]; aab[f] = mab[f]; }
                 } else {
-                    for (int64_t f = 0; f < F; ++f) if (msg[f] > acc[f]) acc[f] = msg[f];
+                    for (int64_t f = 0; f < F; ++f) if (msg[f] > acc[f]) { acc[f] = msg[f]; aab[f] = mab[f]; }
                 }
             }
-            if (agg == AGG_MAX) for (int64_t f = 0; f < F; ++f) aab[f] = fabs(acc[f]);
             if (A) memcpy(A + i * F, acc, sizeof(double) * (size_t)F);
             if (A_abs) memcpy(A_abs + i * F, aab, sizeof(double) * (size_t)F);
 

@@ -86,8 +86,12 @@ def test_hand_worked_gate_closed_form():
     o = oracle.layer(*_np(g), X, "gated", W_gate=np.array([[2.0, -1.0]], np.float32))
     want = np.array([[L * (3 / 4 - 1 / 28)], [L * (27 / 28 + 2 * 243 / 244)], [-L / 82]])
     assert np.allclose(o["A"], want, rtol=2e-6, atol=0)
-    # and |terms| summed
-    want_abs = np.array([[L * (3 / 4 + 1 / 28)], [L * (27 / 28 + 2 * 243 / 244)], [L / 82]])
+    # error scale of each message g t: g (|t| + |t| (1 - g) Z), Z = 2 |x_src| + |x_dst|
+    def s(g, xu, xv):
+        return g * (abs(xu) + abs(xu) * (1 - g) * (2 * abs(xu) + abs(xv)))
+    want_abs = np.array([[s(3 / 4, L, L) + s(1 / 28, -L, L)],
+                         [s(27 / 28, L, -L) + s(243 / 244, 2 * L, -L)],
+                         [s(1 / 82, -L, 2 * L)]])
     assert np.allclose(o["A_abs"], want_abs, rtol=2e-6, atol=0)
 
 
@@ -201,8 +205,16 @@ def test_gated_equals_dense_broadcast_form():
     want = np.einsum("vu,vuf,uf->vf", Adj, G, M)
     o = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm)
     assert np.allclose(o["A"], want, rtol=1e-12, atol=1e-13)
-    want_abs = np.einsum("vu,vuf,uf->vf", Adj, G, np.abs(M))
+    # error scale: every term of the inner sums by absolute value, the gate through its derivative
+    Xa = np.abs(Xd)
+    T_abs = Xa @ np.abs(Wm).astype(np.float64).T
+    Z_abs = (Xa @ np.abs(Wg[:, F:]).astype(np.float64).T)[:, None, :] + \
+        (Xa @ np.abs(Wg[:, :F]).astype(np.float64).T)[None, :, :] + np.abs(bg)
+    S = G * (T_abs[None, :, :] + np.abs(M)[None, :, :] * (1.0 - G) * Z_abs)
+    want_abs = np.einsum("vu,vuf->vf", Adj, S)
     assert np.allclose(o["A_abs"], want_abs, rtol=1e-12, atol=1e-13)
+    h = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, hoisted=oracle.hoist(X, Wg, Wm))
+    assert np.allclose(h["A_abs"], want_abs, rtol=1e-12, atol=1e-13)
     # Example 2.1 proper: no bias, no message matrix
     Z0 = Pd[:, None, :] + Ps[None, :, :]
     want0 = np.einsum("vu,vuf,uf->vf", Adj, 1.0 / (1.0 + np.exp(-Z0)), Xd)
@@ -257,8 +269,11 @@ def test_hoisted_equals_naive():
                              hoisted=oracle.hoist(X, Wg, wm))
             assert np.allclose(a["A"], h["A"], rtol=1e-12, atol=1e-13)
             assert np.allclose(a["Y"], h["Y"], rtol=1e-12, atol=1e-13)
-    Ps, Pd, M = oracle.hoist(X, Wg, Wm)
+    Ps, Pd, M, Ps_abs, Pd_abs, M_abs = oracle.hoist(X, Wg, Wm)
     Xd = X.astype(np.float64)
+    assert np.allclose(Ps_abs, np.abs(Xd) @ np.abs(Wg[:, :9]).astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    assert np.allclose(Pd_abs, np.abs(Xd) @ np.abs(Wg[:, 9:]).astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    assert np.allclose(M_abs, np.abs(Xd) @ np.abs(Wm).astype(np.float64).T, rtol=1e-13, atol=1e-13)
     assert np.allclose(Ps, Xd @ Wg[:, :9].astype(np.float64).T, rtol=1e-13, atol=1e-13)
     assert np.allclose(Pd, Xd @ Wg[:, 9:].astype(np.float64).T, rtol=1e-13, atol=1e-13)
     assert np.allclose(M, Xd @ Wm.astype(np.float64).T, rtol=1e-13, atol=1e-13)
