@@ -45,7 +45,9 @@ def main():
     ap.add_argument("--scale", type=int, default=None, help="shrink the graph (testing only)")
     ap.add_argument("--edge-factor", type=int, default=None)
     ap.add_argument("--agg", default="sum", choices=["sum", "max"])
-    ap.add_argument("--split", type=int, default=None)
+    ap.add_argument("--split", type=int, default=None, help="work-list tunable (see saga_set_option)")
+    ap.add_argument("--cut-degree", type=int, default=None)
+    ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     args = ap.parse_args()
@@ -74,14 +76,13 @@ def main():
     es = 2 if wl.dtype == "bf16" else 4
 
     ctx = saga.Context(0)
-    if args.split:
-        ctx.set_option("split", args.split)
-    if args.xcd_remap is not None:
-        ctx.set_option("xcd_remap", args.xcd_remap)
+    for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
+                      ("xcd_remap", args.xcd_remap)):
+        if val is not None:
+            ctx.set_option(name, val)
     t0 = time.time()
     graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
     t_ingest = time.time() - t0
-    info = graph.info()
     X = wl.X.to(tdt).contiguous()
     W = wl.W.to(tdt).contiguous()
     Y = torch.empty(n, f_out, device=dev, dtype=tdt)
@@ -94,9 +95,10 @@ def main():
     def step():
         ctx.layer_forward(graph, X, Y, **kw)
 
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):   # the first call also builds the work list
         step()
     torch.cuda.synchronize()
+    info = graph.info()
     ctx.set_profiling(True)
     ctx.reset_timings()
     torch.cuda.synchronize()

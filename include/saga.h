@@ -127,9 +127,10 @@ saga_status saga_destroy(saga_ctx* ctx);
  * int32 [n_edges]; `where` says where both live. The library copies what it
  * needs, so the caller may free the arrays after return. It validates the
  * arrays (monotone col_ptr from 0 to n_edges, ids in range, strictly ascending
- * within a column) and returns SAGA_ERR_BAD_GRAPH otherwise; computes
- * in-degrees and the work list (light columns whole, heavy columns cut into
- * consecutive sub-groups as in Section 3.3's Scatter kernel).
+ * within a column) and returns SAGA_ERR_BAD_GRAPH otherwise. The work list
+ * (light columns whole, heavy columns cut into consecutive sub-groups as in
+ * Section 3.3's Scatter kernel) is built at the first call that uses the graph,
+ * because the cuts depend on the width of the rows to gather.
  * SAGA_MEM_DEVICE graphs serve device-resident calls; SAGA_MEM_HOST graphs
  * serve streamed calls and are tiled into the chunk grid at the first call.
  * Synchronises the stream.
@@ -172,18 +173,36 @@ saga_status saga_set_profiling(saga_ctx* ctx, int32_t on);
 saga_status saga_reset_timings(saga_ctx* ctx);
 saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises the stream */
 
-/* Tunables, for measurement: "split" (max edges per work item, default 1024),
- * "xcd_remap" (0/1, default 1), "dst_intervals"/"src_intervals" (streamed plan
- * override, 0 = automatic). Returns INVALID_ARG for unknown names or values. */
+/* Tunables, for measurement. They shape the work list, which is (re)built at the next
+ * saga_layer_forward that finds them changed:
+ *   "split"      minimum edges in one piece of a cut column (default 64)
+ *   "cut_degree" columns with more in-edges than this are cut (default 0 = 2 * split)
+ *   "stripe_kb"  pieces end where the source rows cross a multiple of this many KiB of
+ *                feature rows, and pieces are processed band by band (default 1024;
+ *                0 = cut by edge count only)
+ *   "xcd_remap"  0/1, keep neighbouring work items on one XCD (default 1)
+ *   "dst_intervals" / "src_intervals"  streamed plan override, 0 = automatic
+ * Returns INVALID_ARG for unknown names or values. */
 saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value);
 
 /* High-water mark of device bytes held by the library (workspace, graph copies, stream buffers). */
 size_t saga_peak_device_bytes(const saga_ctx* ctx);
 /* Text of the last failure on this context; owned by the context, valid until its next call. */
 const char* saga_last_error(const saga_ctx* ctx);
-/* Facts about an ingested graph: *max_in_degree, *n_work_items, *n_split_vertices (any may be NULL). */
+/* Facts about an ingested graph: *max_in_degree, and *n_work_items, *n_split_vertices of the
+ * work list built by the last call that used the graph (0 before any). Any may be NULL. */
 saga_status saga_graph_info(const saga_graph* g, int64_t* max_in_degree, int64_t* n_work_items,
                             int64_t* n_split_vertices);
+/*
+ * Host-only planning call (no GPU needed): build the work list of a host CSC the way
+ * saga_layer_forward would for the given parameters, and copy up to `capacity` items into
+ * items_out as (vertex, first edge, one-past-last edge, partial-row slot or -1) int32
+ * quadruples. Counts are always returned. Used to test and to inspect the plan.
+ */
+saga_status saga_plan_work_list(int64_t n_vertices, const int64_t* col_ptr, const int32_t* row_idx,
+                                int64_t min_edges, int64_t cut_degree, int64_t stripe_rows,
+                                int32_t* items_out, int64_t capacity, int64_t* n_items,
+                                int64_t* n_split_vertices, int64_t* n_slots);
 const char* saga_version(void);
 
 #ifdef __cplusplus

@@ -28,7 +28,7 @@ MEM_DEVICE, MEM_HOST = 0, 1
 EXPORTS = ["saga_create", "saga_destroy", "saga_graph_create_csc", "saga_graph_destroy",
            "saga_graph_set_edge_data", "saga_layer_forward", "saga_set_profiling", "saga_reset_timings",
            "saga_get_timings", "saga_set_option", "saga_peak_device_bytes", "saga_last_error",
-           "saga_graph_info", "saga_version"]
+           "saga_graph_info", "saga_plan_work_list", "saga_version"]
 
 
 class SagaError(RuntimeError):
@@ -103,6 +103,9 @@ def load_library() -> ctypes.CDLL:
     L.saga_last_error.argtypes = [P]
     L.saga_graph_info.restype = I32
     L.saga_graph_info.argtypes = [P, ctypes.POINTER(I64), ctypes.POINTER(I64), ctypes.POINTER(I64)]
+    L.saga_plan_work_list.restype = I32
+    L.saga_plan_work_list.argtypes = [I64, P, P, I64, I64, I64, P, I64, ctypes.POINTER(I64), ctypes.POINTER(I64),
+                                      ctypes.POINTER(I64)]
     L.saga_version.restype = ctypes.c_char_p
     L.saga_version.argtypes = []
     _lib = L
@@ -258,6 +261,23 @@ class Context:
             self.destroy()
         except Exception:
             pass
+
+
+def plan_work_list(col_ptr: torch.Tensor, row_idx: torch.Tensor, min_edges=256, cut_degree=512, stripe_rows=1024):
+    """Host-only: the work list the library would build (int32 tensor [n_items, 4]) and its counts."""
+    L = load_library()
+    assert not col_ptr.is_cuda and col_ptr.dtype == torch.int64 and row_idx.dtype == torch.int32
+    n = col_ptr.numel() - 1
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    args = (n, col_ptr.data_ptr(), row_idx.data_ptr(), min_edges, cut_degree, stripe_rows)
+    st = L.saga_plan_work_list(*args, None, 0, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if st != SAGA_OK:
+        raise SagaError(st, "saga_plan_work_list")
+    items = torch.empty(a.value, 4, dtype=torch.int32)
+    st = L.saga_plan_work_list(*args, items.data_ptr(), a.value, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if st != SAGA_OK:
+        raise SagaError(st, "saga_plan_work_list")
+    return items, {"n_items": a.value, "n_split_vertices": b.value, "n_slots": c.value}
 
 
 def version() -> str:

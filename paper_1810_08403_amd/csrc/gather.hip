@@ -97,14 +97,20 @@ struct Frag<uint16_t, 1> {
     __device__ __forceinline__ float get(int) const { return __uint_as_float((uint32_t)r << 16); }
 };
 
-// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous
-// range of the work list instead, so that neighbouring columns share one L2.
+// Workgroups are dealt to the 8 XCDs round-robin. Within every run of
+// 8 * kXcdRun workgroups, hand each XCD kXcdRun consecutive entries of the
+// work list instead of every eighth one, so that the wavefronts resident on
+// one XCD (about 1024) read neighbouring entries through one L2, while all
+// XCDs still advance through the list at the same pace.
+constexpr int kXcdRun = 256;
 __device__ __forceinline__ int64_t logical_block(int remap)
 {
     const int64_t b = blockIdx.x;
     if (!remap) return b;
-    const int64_t per = gridDim.x >> 3;  // grid is padded to a multiple of 8
-    return (b & 7) * per + (b >> 3);
+    const int64_t group = b / (8 * kXcdRun);
+    if (group >= (int64_t)gridDim.x / (8 * kXcdRun)) return b;  // ragged last run: as dealt
+    const int64_t r = b - group * (8 * kXcdRun);
+    return group * (8 * kXcdRun) + (r & 7) * kXcdRun + (r >> 3);
 }
 
 template <int VEC>
@@ -194,33 +200,59 @@ __device__ __forceinline__ bool fetch_item(const GatherArgs& a, ItemView* it)
 // rows of >= 64 fragments: every lane owns RC fragments of the row, one edge
 // per wave-wide load, U edges in flight. GATED reads two fragments per edge.
 // ---------------------------------------------------------------------------
-// One group of up to U edges: issue every row load first, then consume.
-// TAIL guards each edge with the wave-uniform predicate j + k < cnt.
-template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
-__device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const int F, const int idx,
-                                           const float wt, const int j, const int cnt, const int (&col)[RC],
-                                           const float (&pd)[RC][VEC], float (&acc)[RC][VEC])
+// Source ids and edge weights are read through the constant address space with
+// wave-uniform addresses, so they arrive in scalar registers (read-only scalar
+// loads) and the row base address is formed on the scalar unit.
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+typedef const float __attribute__((address_space(4))) * const_f32_ptr;
+
+template <int U, bool TAIL, bool WEIGHTED>
+__device__ __forceinline__ void fetch_ids_w(const_i32_ptr ridx, const_f32_ptr ew, int e, int e1, int (&u)[U], float (&w)[U])
 {
-    Frag<T, VEC> x[U][RC];
-    Frag<T, VEC> m[GATED ? U : 1][GATED ? RC : 1];
-    float w[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-        if (TAIL && j + k >= cnt) continue;
-        // ids and weights come out of the 64-entry batch with a wave-uniform
-        // lane read, so the row base address lives in scalar registers
-        const int64_t u = __builtin_amdgcn_readlane(idx, j + k);
-        w[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wt), j + k));
-        const T* row = X + u * ld;
+        // past the end of the item, re-read its last edge (always a valid address) and ignore it
+        const int ee = TAIL ? min(e + k, e1 - 1) : e + k;
+        u[k] = ridx[ee];
+        w[k] = WEIGHTED ? ew[ee] : 1.0f;
+    }
+}
+template <int U, bool TAIL>
+__device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, int e, int e1, int (&u)[U], float (&w)[U])
+{
+    if (ew)
+        fetch_ids_w<U, TAIL, true>(ridx, ew, e, e1, u, w);
+    else
+        fetch_ids_w<U, TAIL, false>(ridx, ew, e, e1, u, w);
+}
+
+// One group of up to U edges: issue every row load first, then consume.
+// TAIL guards each edge with the wave-uniform predicate e + k < e1.
+template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
+__device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const int F, const int (&u)[U],
+                                           const float (&w)[U], const int e, const int e1, const int (&col)[RC],
+                                           const float (&pd)[RC][VEC], float (&acc)[RC][VEC], Frag<T, VEC> (&x)[U][RC],
+                                           Frag<T, VEC> (&m)[GATED ? U : 1][GATED ? RC : 1])
+{
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+        if (TAIL && e + k >= e1) continue;
+        const T* row = X + (int64_t)u[k] * ld;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
             x[k][c].load(row + col[c]);
             if constexpr (GATED) m[k][c].load(row + F + col[c]);
         }
     }
+}
+template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
+__device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, const int e1, const float (&pd)[RC][VEC],
+                                             float (&acc)[RC][VEC], const Frag<T, VEC> (&x)[U][RC],
+                                             const Frag<T, VEC> (&m)[GATED ? U : 1][GATED ? RC : 1])
+{
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-        if (TAIL && j + k >= cnt) continue;
+        if (TAIL && e + k >= e1) continue;
 #pragma unroll
         for (int c = 0; c < RC; ++c)
 #pragma unroll
@@ -244,8 +276,8 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
     constexpr int LOADS_PER_EDGE = RC * (GATED ? 2 : 1);
     constexpr int U = (kInFlight / LOADS_PER_EDGE) > 0 ? (kInFlight / LOADS_PER_EDGE) : 1;
     const T* __restrict__ X = static_cast<const T*>(a.src);
-    const int32_t* __restrict__ ridx = a.row_idx;
-    const float* __restrict__ ew = GATED ? nullptr : a.edge_w;
+    const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
+    const const_f32_ptr ew = GATED ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
         float acc[RC][VEC];
@@ -271,26 +303,27 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 for (int j = 0; j < VEC; ++j) pd[c][j] = f.get(j);
             }
         }
-        // ids and weights are fetched 64 edges at a time, one per lane, one batch ahead
-        int idx_next = 0;
-        float w_next = 1.0f;
-        if (it.e0 + lane < it.e1) {
-            idx_next = ridx[it.e0 + lane];
-            if (ew) w_next = ew[it.e0 + lane];
-        }
-        for (int eb = it.e0; eb < it.e1; eb += 64) {
-            const int idx = idx_next;
-            const float wt = w_next;
-            const int nxt = eb + 64 + lane;
-            if (nxt < it.e1) {
-                idx_next = ridx[nxt];
-                if (ew) w_next = ew[nxt];
+        Frag<T, VEC> x[U][RC];
+        Frag<T, VEC> m[GATED ? U : 1][GATED ? RC : 1];
+        int u[U], un[U];
+        float w[U], wn[U];
+        int e = it.e0;
+        if (e + U <= it.e1) fetch_ids<U, false>(ridx, ew, e, it.e1, un, wn);
+        for (; e + U <= it.e1; e += U) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                u[k] = un[k];
+                w[k] = wn[k];
             }
-            const int cnt = min(64, it.e1 - eb);
-            int j = 0;
-            for (; j + U <= cnt; j += U)
-                wide_group<T, VEC, RC, AGG, GATED, U, false>(X, a.ld_src, F, idx, wt, j, cnt, ldcol, pd, acc);
-            if (j < cnt) wide_group<T, VEC, RC, AGG, GATED, U, true>(X, a.ld_src, F, idx, wt, j, cnt, ldcol, pd, acc);
+            wide_group<T, VEC, RC, AGG, GATED, U, false>(X, a.ld_src, F, u, w, e, it.e1, ldcol, pd, acc, x, m);
+            // ids of the next full group travel while this group's rows do
+            if (e + 2 * U <= it.e1) fetch_ids<U, false>(ridx, ew, e + U, it.e1, un, wn);
+            wide_consume<T, VEC, RC, AGG, GATED, U, false>(w, e, it.e1, pd, acc, x, m);
+        }
+        if (e < it.e1) {
+            fetch_ids<U, true>(ridx, ew, e, it.e1, u, w);
+            wide_group<T, VEC, RC, AGG, GATED, U, true>(X, a.ld_src, F, u, w, e, it.e1, ldcol, pd, acc, x, m);
+            wide_consume<T, VEC, RC, AGG, GATED, U, true>(w, e, it.e1, pd, acc, x, m);
         }
 #pragma unroll
         for (int c = 0; c < RC; ++c)
@@ -415,23 +448,18 @@ __global__ __launch_bounds__(256) void k_zero_u32(uint32_t* p, int64_t count)
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
-// One wavefront per work item: ids in range and strictly ascending (also
-// across the cut between consecutive items of one column).
-__global__ __launch_bounds__(256) void k_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx,
-                                                        int64_t n_src, int32_t* flag)
+// One wavefront per column: ids in range and strictly ascending.
+__global__ __launch_bounds__(256) void k_validate_columns(const int64_t* col_ptr, int64_t n_cols, const int32_t* row_idx,
+                                                          int64_t n_src, int32_t* flag)
 {
-    const int64_t id = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (id >= n_items) return;
-    const WorkItem it = items[id];
-    // the first edge of an item is checked against its predecessor unless the
-    // item starts its column: a whole-column item does, and so does an item
-    // whose predecessor in the list belongs to another vertex
-    bool starts_column = it.slot < 0 || id == 0 || items[id - 1].v != it.v;
+    const int64_t v = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (v >= n_cols) return;
+    const int64_t e0 = col_ptr[v], e1 = col_ptr[v + 1];
     bool bad = false;
-    for (int e = it.e0 + (threadIdx.x & 63); e < it.e1; e += 64) {
+    for (int64_t e = e0 + (threadIdx.x & 63); e < e1; e += 64) {
         const int u = row_idx[e];
         if (u < 0 || u >= n_src) bad = true;
-        if ((e > it.e0 || !starts_column) && row_idx[e - 1] >= u) bad = true;
+        if (e > e0 && row_idx[e - 1] >= u) bad = true;
     }
     if (bad) *flag = 1;
 }
@@ -449,8 +477,7 @@ template <typename T, int VEC, int AGG, bool GATED>
 hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
 {
     const int nvec = (a.F + VEC - 1) / VEC;
-    int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (a.xcd_remap) blocks = (blocks + 7) / 8 * 8;
+    const int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(256);
     if (nvec <= 32) {
@@ -534,11 +561,11 @@ hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s)
     hipLaunchKernelGGL(k_zero_u32, dim3(grid_for(count)), dim3(256), 0, s, static_cast<uint32_t*>(p), count);
     return hipGetLastError();
 }
-hipError_t launch_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx, int64_t n_src,
-                                 int32_t* flag, hipStream_t s)
+hipError_t launch_validate_columns(const int64_t* col_ptr, int64_t n_cols, const int32_t* row_idx, int64_t n_src,
+                                   int32_t* flag, hipStream_t s)
 {
-    if (n_items <= 0) return hipSuccess;
-    const int64_t blocks = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-    hipLaunchKernelGGL(k_validate_items, dim3((unsigned)blocks), dim3(256), 0, s, items, n_items, row_idx, n_src, flag);
+    if (n_cols <= 0) return hipSuccess;
+    const int64_t blocks = (n_cols + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(k_validate_columns, dim3((unsigned)blocks), dim3(256), 0, s, col_ptr, n_cols, row_idx, n_src, flag);
     return hipGetLastError();
 }

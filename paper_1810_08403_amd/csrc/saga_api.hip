@@ -79,34 +79,65 @@ saga_status saga_ctx::drain_events()
     return SAGA_OK;
 }
 
-void build_work_list(const int64_t* col_ptr, int64_t v_begin, int64_t v_end, int64_t edge_base, int64_t split,
+// Work list of a CSC block (Section 3.3: one in-edge group per execution unit,
+// heavy groups cut into consecutive sub-groups). Columns with more than
+// cut_degree in-edges are cut into pieces that end on multiples of stripe_rows
+// source rows and hold at least min_edges edges (so at most min_edges +
+// stripe_rows); the pieces of all columns are then ordered by source stripe, so
+// that the wavefronts in flight at any time read one narrow band of the
+// source rows: the 2-D tiling of Section 3.1 applied at the level of the L2.
+void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
                      WorkList* out)
 {
     out->items.clear();
     out->heavy.clear();
     out->n_slots = 0;
     out->max_degree = 0;
-    out->items.reserve((size_t)(v_end - v_begin));
-    for (int64_t v = v_begin; v < v_end; ++v) {
-        const int64_t b = col_ptr[v] - edge_base, e = col_ptr[v + 1] - edge_base;
+    std::vector<WorkItem> whole;
+    whole.reserve((size_t)n_cols);
+    struct Piece {
+        int64_t key;  // (first stripe, vertex)
+        WorkItem it;
+    };
+    std::vector<Piece> pieces;
+    const int64_t R = p.stripe_rows > 0 ? p.stripe_rows : 0;
+    for (int64_t v = 0; v < n_cols; ++v) {
+        const int64_t b = col_ptr[v], e = col_ptr[v + 1];
         const int64_t deg = e - b;
         out->max_degree = std::max(out->max_degree, deg);
-        if (deg <= split) {
-            out->items.push_back(WorkItem{(int32_t)(v - v_begin), (int32_t)b, (int32_t)e, -1});
+        if (deg <= p.cut_degree) {
+            whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, -1});
             continue;
         }
-        // consecutive sub-groups of near-equal length
-        const int64_t parts = (deg + split - 1) / split;
-        const int64_t len = (deg + parts - 1) / parts;
-        HeavyVertex h{(int32_t)(v - v_begin), (int32_t)out->n_slots, 0, 0};
-        for (int64_t s = b; s < e; s += len) {
-            out->items.push_back(WorkItem{(int32_t)(v - v_begin), (int32_t)s, (int32_t)std::min(e, s + len),
-                                          (int32_t)out->n_slots});
-            ++out->n_slots;
-            ++h.nslots;
+        const size_t first_piece = pieces.size();
+        int64_t pos = b;
+        while (pos < e) {
+            int64_t q = std::min(e, pos + p.min_edges);
+            if (R > 0 && q < e) {
+                // extend to the end of the stripe that holds the last edge taken
+                const int64_t bound = ((int64_t)row_idx[q - 1] / R + 1) * R;
+                q = std::lower_bound(row_idx + q, row_idx + e, bound,
+                                     [](int32_t a, int64_t bnd) { return (int64_t)a < bnd; }) - row_idx;
+            }
+            if (e - q < p.min_edges / 2) q = e;  // do not leave a sliver behind
+            const int64_t stripe = R > 0 ? (int64_t)row_idx[pos] / R : (pos - b) / std::max<int64_t>(p.min_edges, 1);
+            pieces.push_back(Piece{stripe * n_cols + v, WorkItem{(int32_t)v, (int32_t)pos, (int32_t)q, 0}});
+            pos = q;
         }
+        const size_t n_p = pieces.size() - first_piece;
+        if (n_p == 1) {  // one piece after all: an ordinary whole column
+            whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, -1});
+            pieces.pop_back();
+            continue;
+        }
+        HeavyVertex h{(int32_t)v, (int32_t)out->n_slots, (int32_t)n_p, 0};
+        for (size_t i = 0; i < n_p; ++i) pieces[first_piece + i].it.slot = (int32_t)(out->n_slots++);
         out->heavy.push_back(h);
     }
+    std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.key < b.key; });
+    out->items.reserve(pieces.size() + whole.size());
+    for (const Piece& pc : pieces) out->items.push_back(pc.it);
+    out->items.insert(out->items.end(), whole.begin(), whole.end());
 }
 
 namespace {
@@ -165,9 +196,87 @@ saga_status run_apply_vertex(saga_ctx* ctx, const void* A, int64_t lda, int32_t 
     return SAGA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// work list of a resident graph, built for the width of the rows it will gather
+// ---------------------------------------------------------------------------
+static int64_t pow2_floor(int64_t x)
+{
+    int64_t p = 1;
+    while (p * 2 <= x) p *= 2;
+    return p;
+}
+
+WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes)
+{
+    WorkListParams p;
+    p.min_edges = ctx->opt_split;
+    p.cut_degree = ctx->opt_cut_degree > 0 ? ctx->opt_cut_degree : 2 * ctx->opt_split;
+    p.stripe_rows = 0;
+    if (ctx->opt_stripe_kb > 0) p.stripe_rows = std::max<int64_t>(64, pow2_floor(ctx->opt_stripe_kb * 1024 / std::max<int64_t>(row_bytes, 1)));
+    return p;
+}
+
+static saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+{
+    const WorkListParams p = work_list_params(ctx, row_bytes);
+    if (p.min_edges == g->list_params.min_edges && p.cut_degree == g->list_params.cut_degree &&
+        p.stripe_rows == g->list_params.stripe_rows)
+        return SAGA_OK;
+    std::vector<int32_t> h_row;
+    WorkList wl;
+    try {
+        h_row.resize((size_t)std::max<int64_t>(g->nnz, 1));
+    } catch (...) {
+        return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    }
+    if (g->nnz > 0) {
+        HIP_TRY(ctx, hipMemcpyAsync(h_row.data(), g->d_row_idx.p, sizeof(int32_t) * (size_t)g->nnz, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    try {
+        build_work_list(g->h_col_ptr.data(), h_row.data(), g->n, p, &wl);
+    } catch (...) {
+        return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    }
+    if (saga_status st = ctx->dev_alloc(&g->d_items, sizeof(WorkItem) * std::max<size_t>(wl.items.size(), 1))) return st;
+    if (saga_status st = ctx->dev_alloc(&g->d_heavy, sizeof(HeavyVertex) * std::max<size_t>(wl.heavy.size(), 1))) return st;
+    if (!wl.items.empty())
+        HIP_TRY(ctx, hipMemcpyAsync(g->d_items.p, wl.items.data(), sizeof(WorkItem) * wl.items.size(), hipMemcpyHostToDevice, ctx->stream));
+    if (!wl.heavy.empty())
+        HIP_TRY(ctx, hipMemcpyAsync(g->d_heavy.p, wl.heavy.data(), sizeof(HeavyVertex) * wl.heavy.size(), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // wl goes out of scope below
+    g->n_items = (int64_t)wl.items.size();
+    g->n_heavy = (int64_t)wl.heavy.size();
+    g->n_slots = wl.n_slots;
+    g->list_params = p;
+    return SAGA_OK;
+}
+
 extern "C" {
 
 const char* saga_version(void) { return kVersion; }
+
+saga_status saga_plan_work_list(int64_t n, const int64_t* col_ptr, const int32_t* row_idx, int64_t min_edges,
+                                int64_t cut_degree, int64_t stripe_rows, int32_t* items_out, int64_t capacity,
+                                int64_t* n_items, int64_t* n_split_vertices, int64_t* n_slots)
+{
+    if (n < 0 || !col_ptr || min_edges < 1 || cut_degree < 0 || stripe_rows < 0 || capacity < 0) return SAGA_ERR_INVALID_ARG;
+    if (col_ptr[n] > 0 && !row_idx) return SAGA_ERR_INVALID_ARG;
+    WorkList wl;
+    try {
+        build_work_list(col_ptr, row_idx, n, WorkListParams{min_edges, cut_degree, stripe_rows}, &wl);
+    } catch (...) {
+        return SAGA_ERR_INTERNAL;
+    }
+    if (n_items) *n_items = (int64_t)wl.items.size();
+    if (n_split_vertices) *n_split_vertices = (int64_t)wl.heavy.size();
+    if (n_slots) *n_slots = wl.n_slots;
+    if (items_out) {
+        const int64_t m = std::min<int64_t>(capacity, (int64_t)wl.items.size());
+        memcpy(items_out, wl.items.data(), sizeof(WorkItem) * (size_t)m);
+    }
+    return SAGA_OK;
+}
 
 saga_status saga_create(saga_ctx** out, int device, void* hip_stream, size_t hbm_budget_bytes)
 {
@@ -218,8 +327,14 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
 {
     if (!ctx || !name) return SAGA_ERR_INVALID_ARG;
     if (!strcmp(name, "split")) {
-        if (value < 64 || value > (1 << 24)) return ctx->fail(SAGA_ERR_INVALID_ARG, "split must be in [64, 2^24]");
+        if (value < 16 || value > (1 << 24)) return ctx->fail(SAGA_ERR_INVALID_ARG, "split must be in [16, 2^24]");
         ctx->opt_split = value;
+    } else if (!strcmp(name, "cut_degree")) {
+        if (value < 0 || value > (1LL << 31)) return ctx->fail(SAGA_ERR_INVALID_ARG, "cut_degree must be in [0, 2^31]");
+        ctx->opt_cut_degree = value;
+    } else if (!strcmp(name, "stripe_kb")) {
+        if (value < 0 || value > (1 << 22)) return ctx->fail(SAGA_ERR_INVALID_ARG, "stripe_kb must be in [0, 2^22]");
+        ctx->opt_stripe_kb = value;
     } else if (!strcmp(name, "xcd_remap")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "xcd_remap must be 0 or 1");
         ctx->opt_xcd_remap = (int)value;
@@ -338,36 +453,23 @@ saga_status saga_graph_create_csc(saga_ctx* ctx, int64_t n, int64_t nnz, const i
         return SAGA_OK;
     }
 
-    WorkList wl;
-    build_work_list(cp, 0, n, 0, ctx->opt_split, &wl);
-    g->n_items = (int64_t)wl.items.size();
-    g->n_heavy = (int64_t)wl.heavy.size();
-    g->n_slots = wl.n_slots;
-    g->max_degree = wl.max_degree;
+    int64_t maxdeg = 0;
+    for (int64_t v = 0; v < n; ++v) maxdeg = std::max(maxdeg, cp[v + 1] - cp[v]);
+    g->max_degree = maxdeg;
     saga_status st;
     if ((st = ctx->dev_alloc(&g->d_row_idx, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1)))) return bail(st);
-    if ((st = ctx->dev_alloc(&g->d_items, sizeof(WorkItem) * std::max<size_t>(wl.items.size(), 1)))) return bail(st);
-    if ((st = ctx->dev_alloc(&g->d_heavy, sizeof(HeavyVertex) * std::max<size_t>(wl.heavy.size(), 1)))) return bail(st);
     if ((st = ctx->dev_alloc(&ctx->ws_flag, 256))) return bail(st);
     hipError_t e = hipSuccess;
     if (nnz > 0) e = hipMemcpyAsync(g->d_row_idx.p, row_idx, sizeof(int32_t) * (size_t)nnz, hipMemcpyDeviceToDevice, ctx->stream);
-    if (e == hipSuccess && !wl.items.empty())
-        e = hipMemcpyAsync(g->d_items.p, wl.items.data(), sizeof(WorkItem) * wl.items.size(), hipMemcpyHostToDevice, ctx->stream);
-    if (e == hipSuccess && !wl.heavy.empty())
-        e = hipMemcpyAsync(g->d_heavy.p, wl.heavy.data(), sizeof(HeavyVertex) * wl.heavy.size(), hipMemcpyHostToDevice,
-                           ctx->stream);
     if (e == hipSuccess) e = launch_zero_bytes(ctx->ws_flag.p, 256, ctx->stream);
     if (e == hipSuccess)
-        e = launch_validate_items(static_cast<const WorkItem*>(g->d_items.p), g->n_items,
-                                  static_cast<const int32_t*>(g->d_row_idx.p), n, static_cast<int32_t*>(ctx->ws_flag.p),
-                                  ctx->stream);
+        e = launch_validate_columns(col_ptr, n, static_cast<const int32_t*>(g->d_row_idx.p), n,
+                                    static_cast<int32_t*>(ctx->ws_flag.p), ctx->stream);
     int32_t flag = 0;
     if (e == hipSuccess) e = hipMemcpyAsync(&flag, ctx->ws_flag.p, sizeof flag, hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // also keeps wl alive until the copies are done
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return bail(ctx->fail(SAGA_ERR_HIP, "graph upload: %s", hipGetErrorString(e)));
     if (flag) return bail(ctx->fail(SAGA_ERR_BAD_GRAPH, "row_idx has an id out of range or a column that is not strictly ascending"));
-    g->h_col_ptr.clear();
-    g->h_col_ptr.shrink_to_fit();
     *out = g;
     return SAGA_OK;
 }
@@ -422,7 +524,7 @@ saga_status saga_graph_info(const saga_graph* g, int64_t* max_in_degree, int64_t
 // ---------------------------------------------------------------------------
 // one layer, everything resident in HBM
 // ---------------------------------------------------------------------------
-static saga_status resident_forward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
+static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
                                     int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out)
 {
     const int64_t n = g->n;
@@ -430,6 +532,9 @@ static saga_status resident_forward(saga_ctx* ctx, const saga_graph* g, const sa
     const bool bf16 = X->dtype == SAGA_BF16;
     const bool has_w = vp && vp->W;
     hipStream_t s = ctx->stream;
+    // bytes one edge gathers: the source row, or two hoisted fp32 rows when gated
+    const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)F * (bf16 ? 2 : 4);
+    if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
 
     saga_ctx::EventSet* es = nullptr;
     if (ctx->profiling) {
@@ -639,7 +744,7 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
     if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
     if (g->n == 0) return SAGA_OK;
-    return resident_forward(ctx, g, X, ep, agg, vp, Y, accum_out);
+    return resident_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y, accum_out);
 }
 
 }  // extern "C"

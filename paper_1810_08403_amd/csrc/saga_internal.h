@@ -39,11 +39,17 @@ struct WorkList {
     int64_t max_degree = 0;
 };
 
-// Build the work list of columns [v_begin, v_end) of a CSC whose col_ptr is on
-// the host. Edge offsets are relative to edge_base; vertex ids relative to
-// v_begin. split = maximum number of edges in one item.
-void build_work_list(const int64_t* col_ptr, int64_t v_begin, int64_t v_end, int64_t edge_base,
-                     int64_t split, WorkList* out);
+struct WorkListParams {
+    int64_t min_edges;    // a piece of a cut column holds at least this many edges
+    int64_t cut_degree;   // columns with more in-edges than this are cut
+    int64_t stripe_rows;  // pieces end on multiples of this many source rows (0: cut by count only)
+};
+// Build the work list of a CSC block whose arrays are on the host
+// (col_ptr[0] = 0; vertex ids and edge offsets are local to the block).
+struct saga_ctx;
+WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes);
+void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
+                     WorkList* out);
 
 // ---------------------------------------------------------------------------
 // device buffers with accounting
@@ -64,7 +70,9 @@ struct saga_ctx {
     std::string err;
 
     // tunables
-    int64_t opt_split = 1024;
+    int64_t opt_split = 64;        // minimum edges per piece of a cut column
+    int64_t opt_cut_degree = 0;    // 0 = 2 * split
+    int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
     int opt_xcd_remap = 1;
     int opt_dst_intervals = 0, opt_src_intervals = 0;
 
@@ -100,9 +108,11 @@ struct saga_graph {
     saga_ctx* ctx = nullptr;
     int64_t n = 0, nnz = 0;
     int32_t where = SAGA_MEM_DEVICE;
-    // resident form
+    // resident form; the work list is built at the first call for a given
+    // (split, cut_degree, stripe_rows) and rebuilt when those change
     DevBuf d_row_idx, d_items, d_heavy, d_edge_data;
     int64_t n_items = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
+    WorkListParams list_params{-1, -1, -1};
     // host form (streamed)
     std::vector<int64_t> h_col_ptr;
     std::vector<int32_t> h_row_idx;
@@ -166,10 +176,10 @@ hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t s);
 hipError_t launch_neg_inf_to_zero(float* p, int64_t count, hipStream_t s);
 hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s);
 
-// Validate row_idx against the work list: ids in [0, n_src), strictly ascending inside each
+// Validate row_idx column by column: ids in [0, n_src), strictly ascending inside each
 // column. *flag (device int32, pre-zeroed) is set nonzero on violation.
-hipError_t launch_validate_items(const WorkItem* items, int64_t n_items, const int32_t* row_idx,
-                                 int64_t n_src, int32_t* flag, hipStream_t s);
+hipError_t launch_validate_columns(const int64_t* col_ptr, int64_t n_cols, const int32_t* row_idx,
+                                   int64_t n_src, int32_t* flag, hipStream_t s);
 
 // C[M x N] = act(A[M x K] * Bt[N x K]^T + bias), fp32 accumulation on MFMA.
 // Bt must be padded: rows to a multiple of 128 and K to a multiple of 16 bytes
