@@ -1,12 +1,462 @@
-// Streamed (chunked) layer: placeholder until the scheduler lands.
+// Streamed layer: graphs whose vertex data live in host memory are processed
+// as vertex intervals x edge chunks through a fixed device budget (Section 3.1).
+//
+// The adjacency matrix is tiled into chunks C_ij (sources in interval V_i,
+// destinations in interval V_j), each a destination-major CSC with local ids.
+// Schedule (Section 3.1, the paper's own): for every destination interval j
+// the accumulator A_j stays on the device while the source intervals V_i and
+// their chunks C_ij stream through; fused Scatter-ApplyEdge-Gather adds each
+// chunk into A_j; ApplyVertex consumes A_j while it is still resident; then
+// the next j. Copies run on their own streams, double buffered, so that the
+// transfer of chunk i+1 overlaps the kernels of chunk i, and the transfer of
+// the output overlaps the next ApplyVertex tile.
+//
+// Differences from the paper: the grid may be rectangular (Q destination
+// intervals x P source intervals, Q <= P): every destination interval re-reads
+// all of X over the host link, so the planner takes the fewest destination
+// intervals whose accumulator fits the budget and keeps the streamed source
+// intervals small. Columns without edges in a chunk are left out of its work
+// list. The static edge data travel with the chunk.
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cstring>
+#include <thread>
+
 #include "saga_internal.h"
 
-struct ChunkGrid {};
+struct ChunkMeta {
+    int64_t nnz = 0, n_items = 0, n_heavy = 0, n_slots = 0;
+    size_t off_items = 0, off_heavy = 0, off_ridx = 0, off_w = 0, bytes = 0;
+    char* host = nullptr;  // pinned payload: [items | heavy | row_idx | weights]
+};
 
-void chunk_grid_destroy(saga_ctx*, ChunkGrid* grid) { delete grid; }
+struct ChunkGrid {
+    int Q = 0, P = 0;
+    int64_t Dq = 0, Sp = 0;  // rows per destination / source interval
+    WorkListParams wlp{-1, -1, -1, true};
+    bool weighted = false;
+    std::vector<ChunkMeta> chunks;  // [j * P + i]
+    size_t max_chunk_bytes = 0;
+    int64_t max_slots = 0;
+    // device side
+    DevBuf A, V[2], C[2], Ystage[2], partials;
+    hipStream_t s_in = nullptr, s_out = nullptr;
+    hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+    hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
+    hipEvent_t ev_a_done = nullptr;
+};
 
-saga_status streamed_forward(saga_ctx* ctx, saga_graph*, const saga_tensor*, const saga_edge_params*, int32_t,
-                             const saga_vertex_params*, saga_tensor*)
+void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
 {
-    return ctx->fail(SAGA_ERR_UNSUPPORTED, "streamed path not built yet");
+    if (!g) return;
+    for (auto& c : g->chunks)
+        if (c.host) (void)hipHostFree(c.host);
+    for (DevBuf* b : {&g->A, &g->V[0], &g->V[1], &g->C[0], &g->C[1], &g->Ystage[0], &g->Ystage[1], &g->partials})
+        ctx->dev_free(b);
+    for (hipEvent_t e : {g->ev_ready[0], g->ev_ready[1], g->ev_free[0], g->ev_free[1], g->ev_y_ready[0], g->ev_y_ready[1],
+                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done})
+        if (e) (void)hipEventDestroy(e);
+    if (g->s_in) (void)hipStreamDestroy(g->s_in);
+    if (g->s_out) (void)hipStreamDestroy(g->s_out);
+    delete g;
+}
+
+namespace {
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+template <typename Fn>
+void parallel_for(int64_t n, int max_threads, Fn fn)
+{
+    const int nt = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, max_threads), std::thread::hardware_concurrency()));
+    if (nt <= 1) {
+        for (int64_t i = 0; i < n; ++i) fn(i);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    std::vector<std::thread> th;
+    for (int t = 0; t < nt; ++t)
+        th.emplace_back([&] {
+            for (;;) {
+                const int64_t i = next.fetch_add(1);
+                if (i >= n) break;
+                fn(i);
+            }
+        });
+    for (auto& t : th) t.join();
+}
+
+struct BuiltChunk {
+    std::vector<WorkItem> items;
+    std::vector<HeavyVertex> heavy;
+    std::vector<int32_t> ridx;
+    std::vector<float> w;
+    int64_t n_slots = 0;
+};
+
+// Chunk C_ij of the host CSC: columns [j*Dq, ...), sources in [i*Sp, (i+1)*Sp), local ids.
+void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, const WorkListParams& wlp, bool weighted,
+                 BuiltChunk* out)
+{
+    const int64_t v0 = (int64_t)j * Dq, v1 = std::min(g->n, v0 + Dq);
+    const int64_t s0 = (int64_t)i * Sp, s1 = std::min(g->n, s0 + Sp);
+    const int64_t* cp = g->h_col_ptr.data();
+    const int32_t* ri = g->h_row_idx.data();
+    std::vector<int64_t> lcp((size_t)(v1 - v0) + 1, 0);
+    std::vector<int64_t> lo((size_t)(v1 - v0));
+    for (int64_t v = v0; v < v1; ++v) {
+        const int32_t* b = ri + cp[v];
+        const int32_t* e = ri + cp[v + 1];
+        const int32_t* l = std::lower_bound(b, e, (int32_t)s0);
+        const int32_t* h = std::lower_bound(l, e, (int32_t)std::min<int64_t>(s1, 0x7fffffff));
+        lo[v - v0] = l - ri;
+        lcp[v - v0 + 1] = lcp[v - v0] + (h - l);
+    }
+    const int64_t nnz = lcp.back();
+    out->ridx.resize((size_t)nnz);
+    if (weighted) out->w.resize((size_t)nnz);
+    for (int64_t v = v0; v < v1; ++v) {
+        const int64_t cnt = lcp[v - v0 + 1] - lcp[v - v0];
+        const int64_t src = lo[v - v0], dst = lcp[v - v0];
+        for (int64_t k = 0; k < cnt; ++k) out->ridx[dst + k] = (int32_t)(ri[src + k] - s0);
+        if (weighted) memcpy(out->w.data() + dst, g->h_edge_data.data() + src, sizeof(float) * (size_t)cnt);
+    }
+    WorkList wl;
+    build_work_list(lcp.data(), out->ridx.data(), v1 - v0, wlp, &wl);
+    out->items.swap(wl.items);
+    out->heavy.swap(wl.heavy);
+    out->n_slots = wl.n_slots;
+}
+
+saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkListParams& wlp, bool weighted)
+{
+    if (g->grid) {
+        chunk_grid_destroy(ctx, g->grid);
+        g->grid = nullptr;
+    }
+    ChunkGrid* grid = new (std::nothrow) ChunkGrid();
+    if (!grid) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    g->grid = grid;
+    grid->Q = Q;
+    grid->P = P;
+    grid->Dq = (g->n + Q - 1) / Q;
+    grid->Sp = (g->n + P - 1) / P;
+    grid->wlp = wlp;
+    grid->weighted = weighted;
+    grid->chunks.resize((size_t)Q * P);
+    std::vector<BuiltChunk> built((size_t)Q * P);
+    std::atomic<bool> oom{false};
+    parallel_for((int64_t)Q * P, 16, [&](int64_t c) {
+        try {
+            build_chunk(g, grid->Dq, grid->Sp, (int)(c % P), (int)(c / P), wlp, weighted, &built[(size_t)c]);
+        } catch (...) {
+            oom = true;
+        }
+    });
+    if (oom) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory while tiling the graph");
+    for (size_t c = 0; c < built.size(); ++c) {
+        ChunkMeta& m = grid->chunks[c];
+        const BuiltChunk& b = built[c];
+        m.nnz = (int64_t)b.ridx.size();
+        m.n_items = (int64_t)b.items.size();
+        m.n_heavy = (int64_t)b.heavy.size();
+        m.n_slots = b.n_slots;
+        size_t off = 0;
+        m.off_items = off;
+        off = round_up(off + sizeof(WorkItem) * b.items.size(), 256);
+        m.off_heavy = off;
+        off = round_up(off + sizeof(HeavyVertex) * b.heavy.size(), 256);
+        m.off_ridx = off;
+        off = round_up(off + sizeof(int32_t) * b.ridx.size(), 256);
+        m.off_w = off;
+        off = round_up(off + sizeof(float) * b.w.size(), 256);
+        m.bytes = off;
+        grid->max_chunk_bytes = std::max(grid->max_chunk_bytes, m.bytes);
+        grid->max_slots = std::max(grid->max_slots, m.n_slots);
+        if (m.bytes > 0 && m.nnz > 0) {
+            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&m.host), m.bytes, hipHostMallocDefault));
+        }
+    }
+    parallel_for((int64_t)built.size(), 8, [&](int64_t c) {
+        ChunkMeta& m = grid->chunks[(size_t)c];
+        BuiltChunk& b = built[(size_t)c];
+        if (!m.host) return;
+        memcpy(m.host + m.off_items, b.items.data(), sizeof(WorkItem) * b.items.size());
+        memcpy(m.host + m.off_heavy, b.heavy.data(), sizeof(HeavyVertex) * b.heavy.size());
+        memcpy(m.host + m.off_ridx, b.ridx.data(), sizeof(int32_t) * b.ridx.size());
+        memcpy(m.host + m.off_w, b.w.data(), sizeof(float) * b.w.size());
+        BuiltChunk().items.swap(b.items);
+        std::vector<int32_t>().swap(b.ridx);
+        std::vector<float>().swap(b.w);
+    });
+    HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_in, hipStreamNonBlocking));
+    HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_out, hipStreamNonBlocking));
+    for (hipEvent_t* e : {&grid->ev_ready[0], &grid->ev_ready[1], &grid->ev_free[0], &grid->ev_free[1], &grid->ev_y_ready[0],
+                          &grid->ev_y_ready[1], &grid->ev_y_free[0], &grid->ev_y_free[1], &grid->ev_a_done})
+        HIP_TRY(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
+    return SAGA_OK;
+}
+
+// Edge counts of a Q x P tiling with equal intervals, from one pass over the columns.
+void count_grid(const saga_graph* g, int Q, int P, std::vector<int64_t>* nnz, std::vector<int64_t>* pairs)
+{
+    const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
+    nnz->assign((size_t)Q * P, 0);
+    pairs->assign((size_t)Q * P, 0);
+    const int64_t* cp = g->h_col_ptr.data();
+    const int32_t* ri = g->h_row_idx.data();
+    const int nt = 16;
+    std::vector<std::vector<int64_t>> part((size_t)nt, std::vector<int64_t>((size_t)Q * P * 2, 0));
+    parallel_for(nt, nt, [&](int64_t t) {
+        std::vector<int64_t>& acc = part[(size_t)t];
+        const int64_t a = g->n * t / nt, b = g->n * (t + 1) / nt;
+        for (int64_t v = a; v < b; ++v) {
+            const int64_t j = v / Dq;
+            int64_t prev = -1;
+            for (int64_t e = cp[v]; e < cp[v + 1]; ++e) {
+                const int64_t i = ri[e] / Sp;
+                acc[(size_t)(j * P + i) * 2] += 1;
+                if (i != prev) acc[(size_t)(j * P + i) * 2 + 1] += 1;
+                prev = i;
+            }
+        }
+    });
+    for (int t = 0; t < nt; ++t)
+        for (size_t c = 0; c < (size_t)Q * P; ++c) {
+            (*nnz)[c] += part[(size_t)t][c * 2];
+            (*pairs)[c] += part[(size_t)t][c * 2 + 1];
+        }
+}
+
+struct Plan {
+    int Q, P;
+    int64_t y_tile_rows;
+    size_t bytes;
+};
+
+// Device bytes a Q x P plan needs (upper bound on the chunk payload from the edge counts).
+size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t F_out, bool has_w, bool weighted, int64_t min_edges,
+                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs)
+{
+    const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
+    size_t max_chunk = 0, max_slots = 0;
+    for (size_t c = 0; c < nnz.size(); ++c) {
+        const size_t pieces = (size_t)(pairs[c] + nnz[c] / std::max<int64_t>(min_edges, 1));
+        const size_t b = 16 * pieces + 16 * (pieces / 2 + 1) + (weighted ? 8 : 4) * (size_t)nnz[c] + 4 * 256;
+        max_chunk = std::max(max_chunk, b);
+        max_slots = std::max(max_slots, (size_t)(nnz[c] / std::max<int64_t>(min_edges, 1)) + 1);
+    }
+    size_t total = (size_t)Dq * F * 4;                 // A_j
+    total += 2 * (size_t)Sp * F * 4;                   // V_i, double buffered
+    total += 2 * max_chunk;                            // C_ij, double buffered
+    total += max_slots * (size_t)F * 4;                // partial rows of cut columns
+    if (has_w) total += 2 * (size_t)y_tile_rows * F_out * 4 + (size_t)(F_out + 128) * (F + 64) * 4;  // Y tiles + packed W
+    return total + (1 << 20);
+}
+
+}  // namespace
+
+saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
+                             const saga_vertex_params* vp, saga_tensor* Y)
+{
+    const auto t_begin = std::chrono::steady_clock::now();
+    const int64_t n = g->n;
+    const int64_t F = X->cols;
+    const bool has_w = vp && vp->W;
+    const int64_t F_out = has_w ? vp->W->cols : F;
+    const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
+    if (n == 0) return SAGA_OK;
+
+    WorkListParams wlp = work_list_params(ctx, F * 4);
+    wlp.skip_empty = true;
+
+    // ---- plan: fewest destination intervals, then the fewest source intervals, that fit the budget ----
+    int Q = ctx->opt_dst_intervals, P = ctx->opt_src_intervals;
+    int64_t y_tile_rows = 0;
+    auto tile_rows_for = [&](int q) {
+        const int64_t Dq = (n + q - 1) / q;
+        return std::min<int64_t>(Dq, std::max<int64_t>(4096, (64 << 20) / (F_out * 4)));  // about 64 MiB per tile
+    };
+    const bool same_grid = g->grid && g->grid->wlp.min_edges == wlp.min_edges && g->grid->wlp.cut_degree == wlp.cut_degree &&
+                           g->grid->wlp.stripe_rows == wlp.stripe_rows && g->grid->weighted == weighted;
+    if (same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P)) {
+        Q = g->grid->Q;
+        P = g->grid->P;
+    } else if (Q > 0 && P > 0) {
+        if (Q > n || P > n) return ctx->fail(SAGA_ERR_INVALID_ARG, "more intervals than vertices");
+    } else {
+        bool found = false;
+        std::vector<int64_t> nnz, pairs;
+        const int qs[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 256, 512, 1024};
+        const int ps[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
+        for (int q : qs) {
+            if ((Q > 0 && q != Q) || q > n) continue;
+            for (int p : ps) {
+                if ((P > 0 && p != P) || p > n || p < q) continue;
+                // without a cap, stop growing P once a source interval is below 1 GiB
+                count_grid(g, q, p, &nnz, &pairs);
+                const size_t need = plan_bytes(g, q, p, F, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs);
+                const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
+                if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need <= ctx->budget)) {
+                    Q = q;
+                    P = p;
+                    found = true;
+                    break;
+                }
+            }
+            if (found) break;
+        }
+        if (!found)
+            return ctx->fail(SAGA_ERR_BUDGET, "no vertex-interval x edge-chunk plan fits %zu bytes of device memory", ctx->budget);
+    }
+    y_tile_rows = tile_rows_for(Q);
+    if (!(same_grid && g->grid->Q == Q && g->grid->P == P))
+        if (saga_status st = build_grid(ctx, g, Q, P, wlp, weighted)) return st;
+    ChunkGrid* grid = g->grid;
+    const int64_t Dq = grid->Dq, Sp = grid->Sp;
+
+    // ---- device buffers, all counted against the budget ----
+    saga_status st;
+    if ((st = ctx->dev_alloc(&grid->A, (size_t)Dq * F * 4))) return st;
+    for (int b = 0; b < 2; ++b) {
+        if ((st = ctx->dev_alloc(&grid->V[b], (size_t)Sp * F * 4))) return st;
+        if ((st = ctx->dev_alloc(&grid->C[b], std::max<size_t>(grid->max_chunk_bytes, 256)))) return st;
+        if (has_w && (st = ctx->dev_alloc(&grid->Ystage[b], (size_t)y_tile_rows * F_out * 4))) return st;
+    }
+    if (grid->max_slots > 0 && (st = ctx->dev_alloc(&grid->partials, (size_t)grid->max_slots * F * 4))) return st;
+    if (ctx->budget > 0 && ctx->cur_bytes > ctx->budget)
+        return ctx->fail(SAGA_ERR_BUDGET, "plan %d x %d needs %zu bytes of device memory, budget is %zu", Q, P, ctx->cur_bytes,
+                         ctx->budget);
+
+    hipStream_t sc = ctx->stream, sin = grid->s_in, sout = grid->s_out;
+    const float* Xh = static_cast<const float*>(X->data);
+    float* Yh = static_cast<float*>(Y->data);
+    int64_t bytes_h2d = 0, bytes_d2h = 0;
+    int64_t step = 0, ystep = 0;
+    bool used[2] = {false, false}, yused[2] = {false, false};
+
+    // pack W^T once (on the compute stream)
+    int64_t n_pad = 0, k_pad = 0;
+    if (has_w) {
+        bt_padded_shape((int32_t)F_out, (int32_t)F, SAGA_F32, &n_pad, &k_pad);
+        if ((st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * k_pad) * 4))) return st;
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)F, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, sc));
+    }
+
+    for (int j = 0; j < Q; ++j) {
+        const int64_t v0 = (int64_t)j * Dq, rows = std::min(n, v0 + Dq) - v0;
+        if (rows <= 0) break;
+        float* A = static_cast<float*>(grid->A.p);
+        // A_j <- identity of the accumulator (after the previous interval's readers are done)
+        if (j > 0) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
+        HIP_TRY(ctx, launch_fill_f32(A, rows * F, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
+        for (int i = 0; i < P; ++i) {
+            const ChunkMeta& m = grid->chunks[(size_t)j * P + i];
+            if (m.nnz == 0) continue;  // nothing to add from this source interval
+            const int b = (int)(step & 1);
+            const int64_t s0 = (int64_t)i * Sp, srows = std::min(n, s0 + Sp) - s0;
+            // copy stream: wait until the kernels that last read this buffer pair are done
+            if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
+            HIP_TRY(ctx, hipMemcpy2DAsync(grid->V[b].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
+                                          (size_t)srows, hipMemcpyHostToDevice, sin));
+            HIP_TRY(ctx, hipMemcpyAsync(grid->C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
+            HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
+            bytes_h2d += srows * F * 4 + (int64_t)m.bytes;
+            // compute stream
+            HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_ready[b], 0));
+            const char* cb = static_cast<const char*>(grid->C[b].p);
+            GatherArgs ga{};
+            ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
+            ga.n_items = m.n_items;
+            ga.row_idx = reinterpret_cast<const int32_t*>(cb + m.off_ridx);
+            ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
+            ga.src = grid->V[b].p;
+            ga.ld_src = F;
+            ga.F = (int32_t)F;
+            ga.dtype = SAGA_F32;
+            ga.op = ep->op;
+            ga.agg = agg;
+            ga.out = A;
+            ga.ld_out = F;
+            ga.partials = static_cast<float*>(grid->partials.p);
+            ga.accumulate = 1;
+            ga.xcd_remap = ctx->opt_xcd_remap;
+            HIP_TRY(ctx, launch_gather(ga, sc));
+            if (m.n_heavy > 0) {
+                CombineArgs ca{};
+                ca.heavy = reinterpret_cast<const HeavyVertex*>(cb + m.off_heavy);
+                ca.n_heavy = m.n_heavy;
+                ca.partials = ga.partials;
+                ca.F = (int32_t)F;
+                ca.agg = agg;
+                ca.out = A;
+                ca.ld_out = F;
+                ca.accumulate = 1;
+                HIP_TRY(ctx, launch_combine(ca, sc));
+            }
+            HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sc));
+            used[b] = true;
+            ++step;
+        }
+        if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * F, sc));
+        if (!has_w) {
+            // Y_j = A_j straight to the host
+            HIP_TRY(ctx, hipEventRecord(grid->ev_y_ready[0], sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_y_ready[0], 0));
+            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)F * 4, (size_t)F * 4, (size_t)rows,
+                                          hipMemcpyDeviceToHost, sout));
+            bytes_d2h += rows * F * 4;
+            HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
+            continue;
+        }
+        // ApplyVertex while A_j is resident, tile by tile into a staging pair that drains to the host
+        for (int64_t r0 = 0; r0 < rows; r0 += y_tile_rows) {
+            const int64_t tr = std::min(y_tile_rows, rows - r0);
+            const int b = (int)(ystep & 1);
+            if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_y_free[b], 0));
+            GemmArgs ge{};
+            ge.A = A + r0 * F;
+            ge.lda = F;
+            ge.Bt = ctx->ws_bt.p;
+            ge.ldbt = k_pad;
+            ge.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
+            ge.C = grid->Ystage[b].p;
+            ge.ldc = F_out;
+            ge.M = tr;
+            ge.N = (int32_t)F_out;
+            ge.K = (int32_t)F;
+            ge.dtype = ge.out_dtype = SAGA_F32;
+            ge.act = vp->act;
+            HIP_TRY(ctx, launch_gemm(ge, sc));
+            HIP_TRY(ctx, hipEventRecord(grid->ev_y_ready[b], sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_y_ready[b], 0));
+            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + (v0 + r0) * Y->ld, (size_t)Y->ld * 4, grid->Ystage[b].p, (size_t)F_out * 4,
+                                          (size_t)F_out * 4, (size_t)tr, hipMemcpyDeviceToHost, sout));
+            HIP_TRY(ctx, hipEventRecord(grid->ev_y_free[b], sout));
+            bytes_d2h += tr * F_out * 4;
+            yused[b] = true;
+            ++ystep;
+        }
+        HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(sin));
+    HIP_TRY(ctx, hipStreamSynchronize(sc));
+    HIP_TRY(ctx, hipStreamSynchronize(sout));
+
+    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+    ctx->acc.ms_wall_streamed += ms;
+    ctx->acc.bytes_h2d += bytes_h2d;
+    ctx->acc.bytes_d2h += bytes_d2h;
+    ctx->acc.plan_dst_intervals = Q;
+    ctx->acc.plan_src_intervals = P;
+    int64_t items = 0, heavy = 0;
+    for (const auto& m : grid->chunks) {
+        items += m.n_items;
+        heavy += m.n_heavy;
+    }
+    ctx->acc.n_work_items = items;
+    ctx->acc.n_split_vertices = heavy;
+    ctx->acc.n_calls += 1;
+    return SAGA_OK;
 }

