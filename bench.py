@@ -36,12 +36,27 @@ def algorithmic_gather_bytes(nnz, n, f_in, elem_bytes, weighted, gated, n_items)
     return nnz * per_edge + n * per_vertex + n_items * 16
 
 
+def measured_traffic(workload_key, nnz, work_items, agg):
+    """HBM-side bytes per gather launch from the committed rocprofv3 counter summary, if it was
+    taken on this very workload and work list (else None: counters cannot be read from here)."""
+    path = os.path.join(ROOT, "profiles", f"{workload_key}_traffic.json")
+    try:
+        with open(path) as f:
+            d = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if d.get("nnz") == nnz and d.get("work_items") == work_items and d.get("agg") == agg:
+        return int(d["traffic_bytes_per_launch"])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4"])
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5"],
+                    help="config5 is streamed from pinned host memory under a 16 GiB device budget")
     ap.add_argument("--scale", type=int, default=None, help="shrink the graph (testing only)")
     ap.add_argument("--edge-factor", type=int, default=None)
     ap.add_argument("--agg", default="sum", choices=["sum", "max"])
@@ -49,6 +64,8 @@ def main():
     ap.add_argument("--cut-degree", type=int, default=None)
     ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 3 plain 1 GiB device copies (k_copy_u128), to scale memory-traffic counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -65,6 +82,8 @@ def main():
         sys.exit(1)
     dev = "cuda"
     k = int(args.workload[-1])
+    if k == 5:
+        return bench_streamed(args)
     t0 = time.time()
     wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
     torch.cuda.synchronize()
@@ -111,6 +130,14 @@ def main():
     ctx.set_profiling(False)
     ms_per_step = wall * 1e3 / args.steps
     gteps = nnz / (ms_per_step * 1e-3) / 1e9
+    if args.calibrate_copy:
+        a = torch.full((1 << 28,), 1.0, device=dev)     # 1 GiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            ctx.copy_bytes(b, a)
+        torch.cuda.synchronize()
+        assert torch.equal(a[:1024], b[:1024]) and torch.equal(a[-1024:], b[-1024:])
+        del a, b
 
     ms_gather = tm["ms_gather"] / max(tm["n_calls"], 1)
     alg_bytes = algorithmic_gather_bytes(nnz, n, f_in, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
@@ -127,7 +154,8 @@ def main():
                    "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"]},
         "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "algorithmic_bytes_per_launch": alg_bytes,
+                     "traffic": measured_traffic(args.workload, nnz, info["n_work_items"], args.agg),
+                     "algorithmic_bytes_per_launch": alg_bytes,
                      "compulsory_bytes_per_launch": compulsory,
                      "compulsory_frac": round(compulsory / (ms_gather * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if ms_gather > 0 else None,
                      "ms_per_launch": round(ms_gather, 4)},
@@ -157,20 +185,78 @@ def main():
             oracle.layer(cp, ri, Xh, vlist=vl, **okw)
             return time.perf_counter() - t
 
-        # pilot on a small random sample, then size the real sample for the target time
-        pilot = perm[: max(64, n // 2000)]
-        tp = timed(pilot)
-        rate = max(deg[pilot].sum(), 1) / max(tp, 1e-6)
-        want_edges = rate * args.cpu_seconds
+        # two pilots (the first also warms the threads up), then size the sample for the target time
         csum = np.cumsum(deg[perm])
-        m = int(np.searchsorted(csum, want_edges)) + 1
-        sample = perm[: min(max(m, 64), n)]
+        m = max(64, n // 2000)
+        for _ in range(2):
+            tp = timed(perm[:m])
+            rate = max(int(csum[m - 1]), 1) / max(tp, 1e-6)
+            m = min(max(int(np.searchsorted(csum, rate * min(2.0, args.cpu_seconds))) + 1, 64), n)
+        tp = timed(perm[:m])
+        rate = max(int(csum[m - 1]), 1) / max(tp, 1e-6)
+        m = min(max(int(np.searchsorted(csum, rate * args.cpu_seconds)) + 1, 64), n)
+        sample = perm[:m]
         ts = timed(sample)
         e_s = int(deg[sample].sum())
         out["cpu_baseline"] = {"value": round(e_s / ts / 1e9, 6), "unit": "GTEPS", "cores": oracle.num_threads(),
                                "kind": "oracle",
                                "sample": f"{len(sample)} random destination vertices ({e_s} in-edges) of the same "
                                          f"graph, full layer incl. ApplyVertex, {ts:.1f} s"}
+    print(json.dumps(out))
+
+
+def bench_streamed(args):
+    """Configuration 5: X and Y in pinned host memory, 16 GiB device budget; every transfer is timed."""
+    import numpy as np
+    import torch
+    import saga_inputs as si
+    import paper_1810_08403_amd as saga
+
+    t0 = time.time()
+    wl = si.workload(5, device="cuda", scale=args.scale, edge_factor=args.edge_factor)
+    g = wl.graph
+    n, nnz = g.n, g.nnz
+    X = wl.X.cpu().pin_memory()
+    W = wl.W.clone()
+    w = wl.edge_weight.cpu()
+    hg = si.CSC(n, g.col_ptr.cpu(), g.row_idx.cpu())
+    del wl, g
+    torch.cuda.empty_cache()
+    t_gen = time.time() - t0
+    budget = 16 << 30
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    t0 = time.time()
+    graph = ctx.graph_create_csc(n, hg.col_ptr, hg.row_idx)
+    graph.set_edge_data(w)
+    t_ingest = time.time() - t0
+    Y = torch.empty(n, W.shape[1]).pin_memory()
+    steps, warmup = min(args.steps, 5), max(1, min(args.warmup, 2))
+    t0 = time.time()
+    for _ in range(warmup):      # the first call plans the grid and tiles the graph
+        ctx.layer_forward(graph, X, Y, edge_op="mul_weight", agg=args.agg, W=W, act="relu")
+    t_first = time.time() - t0
+    ctx.reset_timings()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.layer_forward(graph, X, Y, edge_op="mul_weight", agg=args.agg, W=W, act="relu")
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    tm = ctx.get_timings()
+    ms = wall * 1e3 / steps
+    link = (tm["bytes_h2d"] + tm["bytes_d2h"]) / steps / (ms * 1e-3) / 1e9
+    out = {"metric": "fused_saga_layer_throughput", "value": round(nnz / (ms * 1e-3) / 1e9, 4), "unit": "GTEPS",
+           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 2), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "config5_rmat23_gcn_f32_streamed", "n_vertices": n, "nnz": nnz, "f_in": X.shape[1],
+                      "f_out": W.shape[1], "agg": args.agg, "device_budget_bytes": budget,
+                      "plan": [tm["plan_dst_intervals"], tm["plan_src_intervals"]],
+                      "peak_device_bytes": ctx.peak_device_bytes(), "inputs": "pinned host memory, transfers timed"},
+           "roofline": {"bound": "host_link", "achieved": round(link, 2), "peak": 128.0, "unit": "GB/s",
+                        "frac": round(link / 128.0, 4), "traffic": None,
+                        "note": "H2D + D2H bytes per second against 2 x 64 GB/s (PCIe Gen5 x16, both directions)",
+                        "h2d_bytes_per_step": tm["bytes_h2d"] // steps, "d2h_bytes_per_step": tm["bytes_d2h"] // steps},
+           "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 2), "first_calls": round(t_first, 2)}}
     print(json.dumps(out))
 
 

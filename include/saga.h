@@ -194,6 +194,14 @@ const char* saga_last_error(const saga_ctx* ctx);
 saga_status saga_graph_info(const saga_graph* g, int64_t* max_in_degree, int64_t* n_work_items,
                             int64_t* n_split_vertices);
 /*
+ * Plain device-to-device copy kernel (16 bytes per lane, each byte read once and written
+ * once), enqueued on the context's stream. It exists to calibrate memory-traffic counters:
+ * what a profiler reads for a copy of known size is the scale for what it reads for the
+ * layer's kernels. bytes must be a multiple of 16, pointers 16-byte aligned device memory.
+ */
+saga_status saga_copy_bytes(saga_ctx* ctx, void* dst, const void* src, size_t bytes);
+
+/*
  * Host-only planning call (no GPU needed): build the work list of a host CSC the way
  * saga_layer_forward would for the given parameters, and copy up to `capacity` items into
  * items_out as (vertex, first edge, one-past-last edge, partial-row slot or -1) int32

@@ -28,7 +28,7 @@ MEM_DEVICE, MEM_HOST = 0, 1
 EXPORTS = ["saga_create", "saga_destroy", "saga_graph_create_csc", "saga_graph_destroy",
            "saga_graph_set_edge_data", "saga_layer_forward", "saga_set_profiling", "saga_reset_timings",
            "saga_get_timings", "saga_set_option", "saga_peak_device_bytes", "saga_last_error",
-           "saga_graph_info", "saga_plan_work_list", "saga_version"]
+           "saga_graph_info", "saga_plan_work_list", "saga_copy_bytes", "saga_version"]
 
 
 class SagaError(RuntimeError):
@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     L.saga_plan_work_list.restype = I32
     L.saga_plan_work_list.argtypes = [I64, P, P, I64, I64, I64, P, I64, ctypes.POINTER(I64), ctypes.POINTER(I64),
                                       ctypes.POINTER(I64)]
+    L.saga_copy_bytes.restype = I32
+    L.saga_copy_bytes.argtypes = [P, P, P, SZ]
     L.saga_version.restype = ctypes.c_char_p
     L.saga_version.argtypes = []
     _lib = L
@@ -234,6 +236,15 @@ class Context:
         if cur != self.stream:
             cur.wait_stream(self.stream)
         return Y
+
+    def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor):
+        """Plain copy kernel on the library's stream (counter calibration)."""
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() == nbytes and dst.is_cuda and src.is_cuda
+        cur = torch.cuda.current_stream(self.device)
+        self.stream.wait_stream(cur)
+        self._check(self.lib.saga_copy_bytes(self._h, dst.data_ptr(), src.data_ptr(), nbytes))
+        cur.wait_stream(self.stream)
 
     def set_profiling(self, on: bool):
         self._check(self.lib.saga_set_profiling(self._h, 1 if on else 0))

@@ -443,6 +443,10 @@ __global__ __launch_bounds__(256) void k_f32_to_bf16(const float* in, uint16_t* 
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
         out[i] = f32_to_bf16_rne(in[i]);
 }
+__global__ __launch_bounds__(256) void k_copy_u128(uint4* dst, const uint4* src, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
 __global__ __launch_bounds__(256) void k_zero_u32(uint32_t* p, int64_t count)
 {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = 0u;
@@ -559,6 +563,16 @@ hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s)
     if (bytes % 4 != 0 || !((reinterpret_cast<uintptr_t>(p) & 3u) == 0)) return hipErrorInvalidValue;
     const int64_t count = (int64_t)(bytes / 4);
     hipLaunchKernelGGL(k_zero_u32, dim3(grid_for(count)), dim3(256), 0, s, static_cast<uint32_t*>(p), count);
+    return hipGetLastError();
+}
+hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    if (bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))
+        return hipErrorInvalidValue;
+    const int64_t count = (int64_t)(bytes / 16);
+    hipLaunchKernelGGL(k_copy_u128, dim3(grid_for(count)), dim3(256), 0, s, static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src), count);
     return hipGetLastError();
 }
 hipError_t launch_validate_columns(const int64_t* col_ptr, int64_t n_cols, const int32_t* row_idx, int64_t n_src,

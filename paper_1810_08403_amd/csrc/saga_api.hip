@@ -351,6 +351,17 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     return SAGA_OK;
 }
 
+saga_status saga_copy_bytes(saga_ctx* ctx, void* dst, const void* src, size_t bytes)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    if (!dst || !src) return ctx->fail(SAGA_ERR_INVALID_ARG, "null pointer");
+    DeviceGuard guard(ctx->device);
+    hipError_t e = launch_copy_bytes(dst, src, bytes, ctx->stream);
+    if (e == hipErrorInvalidValue) return ctx->fail(SAGA_ERR_INVALID_ARG, "copy needs 16-byte aligned pointers and size");
+    if (e != hipSuccess) return ctx->fail(SAGA_ERR_HIP, "copy kernel: %s", hipGetErrorString(e));
+    return SAGA_OK;
+}
+
 saga_status saga_set_profiling(saga_ctx* ctx, int32_t on)
 {
     if (!ctx) return SAGA_ERR_INVALID_ARG;

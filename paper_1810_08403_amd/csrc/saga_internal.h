@@ -209,6 +209,7 @@ hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32
 hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int32_t R, int32_t K,
                                float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
 hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // streamed path (chunked.hip)
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
