@@ -17,6 +17,7 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte fragment as a first-class vector value
 
 constexpr int kRowBytes = 64;    // bytes of K per tile row
 constexpr int kLdsStride = 80;   // LDS bytes per tile row
@@ -31,10 +32,10 @@ __device__ __forceinline__ uint16_t to_bf16(float f)
 }
 
 template <typename T>
-__device__ __forceinline__ void mma_step(const uint4& a, const uint4& b, floatx16& acc);
+__device__ __forceinline__ void mma_step(const u32x4& a, const u32x4& b, floatx16& acc);
 
 template <>
-__device__ __forceinline__ void mma_step<float>(const uint4& a, const uint4& b, floatx16& acc)
+__device__ __forceinline__ void mma_step<float>(const u32x4& a, const u32x4& b, floatx16& acc)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
@@ -42,22 +43,107 @@ __device__ __forceinline__ void mma_step<float>(const uint4& a, const uint4& b, 
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 template <>
-__device__ __forceinline__ void mma_step<uint16_t>(const uint4& a, const uint4& b, floatx16& acc)
+__device__ __forceinline__ void mma_step<uint16_t>(const u32x4& a, const u32x4& b, floatx16& acc)
 {
-    union {
-        uint4 u;
-        bf16x8 v;
-    } ua, ub;
-    ua.u = a;
-    ub.u = b;
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua.v, ub.v, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+// Global -> registers of one K tile (64 bytes per row) of the A and Bt blocks: thread t owns
+// 16-byte chunks t, t + 256, ... A chunk past the end of K is loaded from k = 0 and zeroed
+// on its way to LDS, so that the prefetched registers are not touched before the MFMAs of
+// the current tile have issued.
+template <typename T, int BM, int BN, bool ALIGNED, int ACH, int BCH>
+__device__ __forceinline__ void tile_load(const GemmArgs& a, const T* __restrict__ A, const T* __restrict__ Bt, int64_t m0,
+                                          int n0, int kt, int tid, u32x4 (&ra)[ACH], u32x4 (&rb)[BCH], unsigned& ka)
+{
+    constexpr int KT = kRowBytes / (int)sizeof(T), EPC = 16 / (int)sizeof(T);
+    ka = 0;
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+        const int c = tid + 256 * i;
+        const int row = (c >> 2) < BM ? (c >> 2) : 0, kc = c & 3;
+        int64_t gr = m0 + row;
+        if (gr >= a.M) gr = a.M - 1;
+        const int k = kt * KT + kc * EPC;
+        const bool in = k < a.K;
+        ka |= in ? (1u << i) : 0u;
+        const T* p = A + gr * a.lda + (ALIGNED && !in ? 0 : k);
+        if (ALIGNED) {
+            ra[i] = *reinterpret_cast<const u32x4*>(p);
+        } else {
+            uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < EPC; ++j) {
+                const uint32_t e = (k + j < a.K) ? (sizeof(T) == 4 ? __float_as_uint(*reinterpret_cast<const float*>(p + j))
+                                                                   : (uint32_t) * reinterpret_cast<const uint16_t*>(p + j))
+                                                 : 0u;
+                if (sizeof(T) == 4)
+                    w[j] = e;
+                else
+                    w[j >> 1] |= e << (16 * (j & 1));
+            }
+            ra[i] = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) {
+        const int c = tid + 256 * i;
+        const int row = (c >> 2) < BN ? (c >> 2) : 0, kc = c & 3;
+        rb[i] = *reinterpret_cast<const u32x4*>(Bt + (int64_t)(n0 + row) * a.ldbt + kt * KT + kc * EPC);
+    }
+}
+template <int BM, int BN, bool ALIGNED, int ACH, int BCH>
+__device__ __forceinline__ void tile_store(unsigned char* buf, int tid, const u32x4 (&ra)[ACH], const u32x4 (&rb)[BCH],
+                                           unsigned ka)
+{
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+        const int c = tid + 256 * i;
+        const bool in = !ALIGNED || ((ka >> i) & 1u);
+        const u32x4 v = in ? ra[i] : u32x4{0u, 0u, 0u, 0u};
+        if (BM * 4 % 256 == 0 || c < BM * 4) *reinterpret_cast<u32x4*>(buf + (c >> 2) * kLdsStride + (c & 3) * 16) = v;
+    }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) {
+        const int c = tid + 256 * i;
+        if (BN * 4 % 256 == 0 || c < BN * 4)
+            *reinterpret_cast<u32x4*>(buf + (BM + (c >> 2)) * kLdsStride + (c & 3) * 16) = rb[i];
+    }
+}
+
+// Bias, activation, rounding and store of one wave's accumulators. row0 / col0: first row
+// and the column this lane holds. CHECK guards the ragged edge tiles only.
+template <typename TO, int TM, int TN, bool CHECK>
+__device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&acc)[TM][TN], int64_t row0, int col0)
+{
+    TO* __restrict__ C = static_cast<TO*>(a.C);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = col0 + j * 32;
+        if (CHECK && col >= a.N) continue;
+        const float bias = a.bias ? a.bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            TO* p = C + (row0 + i * 32) * a.ldc + col;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = (r >> 2) * 8 + (r & 3);
+                if (CHECK && row0 + i * 32 + dr >= a.M) continue;
+                float y = acc[i][j][r] + bias;
+                if (a.act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
+                if (sizeof(TO) == 4)
+                    reinterpret_cast<float*>(p)[dr * a.ldc] = y;
+                else
+                    reinterpret_cast<uint16_t*>(p)[dr * a.ldc] = to_bf16(y);
+            }
+        }
+    }
 }
 
 template <typename T, int BM, int BN, int WM, int WN, bool ALIGNED, typename TO>
-__global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs a, const int n_tiles_n, const int64_t n_tiles)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) void k_gemm_nt(const GemmArgs a, const int n_tiles_n, const int64_t n_tiles)
 {
     constexpr int KT = kRowBytes / (int)sizeof(T);  // elements of K per tile
-    constexpr int EPC = 16 / (int)sizeof(T);        // elements per 16-byte chunk
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * kLdsStride];
@@ -80,49 +166,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs a, const int n_t
     const int nk = (K + KT - 1) / KT;
 
     constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;
-    uint4 ra[ACH], rb[BCH];
-
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            const int c = tid + 256 * i;
-            if (BM * 4 % 256 != 0 && c >= BM * 4) break;
-            const int row = c >> 2, kc = c & 3;
-            int64_t gr = m0 + row;
-            if (gr >= a.M) gr = a.M - 1;
-            const int k = kt * KT + kc * EPC;
-            const T* p = A + gr * a.lda + k;
-            if (ALIGNED) {
-                ra[i] = k < K ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-            } else {
-                T tmp[EPC];
-#pragma unroll
-                for (int j = 0; j < EPC; ++j) tmp[j] = (k + j < K) ? p[j] : T(0);
-                ra[i] = *reinterpret_cast<const uint4*>(tmp);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            const int c = tid + 256 * i;
-            if (BN * 4 % 256 != 0 && c >= BN * 4) break;
-            const int row = c >> 2, kc = c & 3;
-            rb[i] = *reinterpret_cast<const uint4*>(Bt + (int64_t)(n0 + row) * a.ldbt + kt * KT + kc * EPC);
-        }
-    };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            const int c = tid + 256 * i;
-            if (BM * 4 % 256 != 0 && c >= BM * 4) break;
-            *reinterpret_cast<uint4*>(&lds[buf][(c >> 2) * kLdsStride + (c & 3) * 16]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            const int c = tid + 256 * i;
-            if (BN * 4 % 256 != 0 && c >= BN * 4) break;
-            *reinterpret_cast<uint4*>(&lds[buf][(BM + (c >> 2)) * kLdsStride + (c & 3) * 16]) = rb[i];
-        }
-    };
+    u32x4 ra[ACH], rb[BCH];
+    unsigned ka = 0;  // bit i: chunk i of this thread lies inside K
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -132,54 +177,39 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs a, const int n_t
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    gload(0);
-    lstore(0);
+    tile_load<T, BM, BN, ALIGNED>(a, A, Bt, m0, n0, 0, tid, ra, rb, ka);
+    tile_store<BM, BN, ALIGNED>(lds[0], tid, ra, rb, ka);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
+        // the last iteration re-reads its own tile: no branch around the prefetch
+        tile_load<T, BM, BN, ALIGNED>(a, A, Bt, m0, n0, kt + 1 < nk ? kt + 1 : kt, tid, ra, rb, ka);
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs it is meant to overlap
         const unsigned char* base = lds[kt & 1];
 #pragma unroll
         for (int step = 0; step < 2; ++step) {
-            uint4 fa[TM], fb[TN];
+            u32x4 fa[TM], fb[TN];
             const int chunk = (step * 2 + (lane >> 5)) * 16;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4*>(base + ((wm * TM + i) * 32 + (lane & 31)) * kLdsStride + chunk);
+                fa[i] = *reinterpret_cast<const u32x4*>(base + ((wm * TM + i) * 32 + (lane & 31)) * kLdsStride + chunk);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4*>(base + (BM + (wn * TN + j) * 32 + (lane & 31)) * kLdsStride + chunk);
+                fb[j] = *reinterpret_cast<const u32x4*>(base + (BM + (wn * TN + j) * 32 + (lane & 31)) * kLdsStride + chunk);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) mma_step<T>(fa[i], fb[j], acc[i][j]);
         }
-        if (kt + 1 < nk) lstore((kt + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);  // ... and the wait for it behind them
+        tile_store<BM, BN, ALIGNED>(lds[(kt + 1) & 1], tid, ra, rb, ka);
         __syncthreads();
     }
 
     // epilogue: lane holds column (lane & 31) of 16 rows of each 32 x 32 tile
-    TO* __restrict__ C = static_cast<TO*>(a.C);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-        if (col >= a.N) continue;
-        const float bias = a.bias ? a.bias[col] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t rbase = m0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = rbase + (r >> 2) * 8 + (r & 3);
-                if (row >= a.M) continue;
-                float y = acc[i][j][r] + bias;
-                if (a.act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
-                if (sizeof(TO) == 4)
-                    reinterpret_cast<float*>(C)[row * a.ldc + col] = y;
-                else
-                    reinterpret_cast<uint16_t*>(C)[row * a.ldc + col] = to_bf16(y);
-            }
-        }
-    }
+    if (m0 + BM <= a.M && n0 + BN <= a.N)
+        store_tile<TO, TM, TN, false>(a, acc, m0 + wm * TM * 32 + (lane >> 5) * 4, n0 + wn * TN * 32 + (lane & 31));
+    else
+        store_tile<TO, TM, TN, true>(a, acc, m0 + wm * TM * 32 + (lane >> 5) * 4, n0 + wn * TN * 32 + (lane & 31));
 }
 
 template <typename T>
