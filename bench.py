@@ -55,8 +55,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5"],
-                    help="config5 is streamed from pinned host memory under a 16 GiB device budget")
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5", "spmm"],
+                    help="config5 is streamed from pinned host memory under a 16 GiB device budget; spmm is the "
+                         "10,000 x 10,000 sparse times 10,000 x 128 dense micro-benchmark of the paper's Section 6.1")
+    ap.add_argument("--density", type=float, default=0.01, help="spmm only: fraction of non-zero cells")
     ap.add_argument("--scale", type=int, default=None, help="shrink the graph (testing only)")
     ap.add_argument("--edge-factor", type=int, default=None)
     ap.add_argument("--agg", default="sum", choices=["sum", "max"])
@@ -81,16 +83,20 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda"
-    k = int(args.workload[-1])
+    k = 0 if args.workload == "spmm" else int(args.workload[-1])
     if k == 5:
         return bench_streamed(args)
     t0 = time.time()
-    wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
+    if k == 0:
+        wl = si.spmm_workload(args.density, device=dev)
+    else:
+        wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
     g = wl.graph
     n, nnz = g.n, g.nnz
-    f_in, f_out = wl.X.shape[1], wl.W.shape[1]
+    has_w = wl.W.numel() > 0
+    f_in, f_out = wl.X.shape[1], (wl.W.shape[1] if has_w else wl.X.shape[1])
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     es = 2 if wl.dtype == "bf16" else 4
 
@@ -103,9 +109,10 @@ def main():
     graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
     t_ingest = time.time() - t0
     X = wl.X.to(tdt).contiguous()
-    W = wl.W.to(tdt).contiguous()
     Y = torch.empty(n, f_out, device=dev, dtype=tdt)
-    kw = dict(edge_op=wl.edge_op, agg=args.agg, W=W, act=wl.act)
+    kw = dict(edge_op=wl.edge_op, agg=args.agg)
+    if has_w:
+        kw.update(W=wl.W.to(tdt).contiguous(), act=wl.act)
     if wl.edge_op == "mul_weight":
         graph.set_edge_data(wl.edge_weight)
     if wl.edge_op == "gated":
@@ -154,7 +161,7 @@ def main():
                    "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"]},
         "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(args.workload, nnz, info["n_work_items"], args.agg),
+                     "traffic": measured_traffic(args.workload if k else f"spmm_d{args.density:g}", nnz, info["n_work_items"], args.agg),
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "compulsory_bytes_per_launch": compulsory,
                      "compulsory_frac": round(compulsory / (ms_gather * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if ms_gather > 0 else None,
@@ -163,6 +170,7 @@ def main():
                       "combine": round(tm["ms_combine"] / max(tm["n_calls"], 1), 4),
                       "apply_vertex": round(tm["ms_apply_vertex"] / max(tm["n_calls"], 1), 4),
                       "events_total": round(tm["ms_total"] / max(tm["n_calls"], 1), 4)},
+        "gather_gflops": round(2.0 * nnz * f_in / (ms_gather * 1e-3) / 1e9, 1) if ms_gather > 0 else None,
         "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3)},
     }
 
@@ -171,7 +179,9 @@ def main():
         cp = g.col_ptr.cpu().numpy()
         ri = g.row_idx.cpu().numpy()
         Xh = wl.X.float().cpu().numpy()
-        okw = dict(edge_op=wl.edge_op, agg=args.agg, W=wl.W.float().cpu().numpy(), act=wl.act, want_abs=False)
+        okw = dict(edge_op=wl.edge_op, agg=args.agg, want_abs=False)
+        if has_w:
+            okw.update(W=wl.W.float().cpu().numpy(), act=wl.act)
         if wl.edge_op == "mul_weight":
             okw["edge_weight"] = wl.edge_weight.cpu().numpy()
         if wl.edge_op == "gated":

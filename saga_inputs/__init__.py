@@ -253,6 +253,25 @@ def bf16_bits(x: torch.Tensor) -> torch.Tensor:
     return x.to(torch.bfloat16).view(torch.int16)
 
 
+def bernoulli_graph(n: int, density: float, seed: int, device="cpu") -> CSC:
+    """n x n adjacency in which every cell (dst, src) is an edge independently with
+    probability `density` (the uniformly sparse matrices of the paper's Section 6.1)."""
+    thr = int(density * (1 << 53))
+    keys = []
+    cells = n * n
+    for s in range(0, cells, _CHUNK):
+        c = min(_CHUNK, cells - s)
+        h = _lsr(rand_u64(seed, 7, s, c, device), 11)           # 53 uniform bits
+        idx = torch.nonzero(h < thr).flatten() + s                # cell index = dst * n + src
+        keys.append(idx)
+    key = torch.cat(keys) if keys else torch.zeros(0, dtype=torch.int64, device=device)
+    d = torch.div(key, n, rounding_mode="floor")
+    row_idx = (key - d * n).to(torch.int32)
+    col_ptr = torch.zeros(n + 1, dtype=torch.int64, device=device)
+    torch.cumsum(torch.bincount(d, minlength=n), 0, out=col_ptr[1:])
+    return CSC(n, col_ptr, row_idx)
+
+
 # ----------------------------------------------------------------------------
 # the five workloads
 # ----------------------------------------------------------------------------
@@ -330,3 +349,14 @@ def workload(k: int, device="cpu", scale: Optional[int] = None, edge_factor: Opt
         return Workload("config5_rmat23_gcn_f32_streamed", g, X, "mul_weight", gcn_edge_weights(g),
                         glorot_uniform(fi, fo, wseed, device), "relu", "f32")
     raise ValueError(f"no configuration {k}")
+
+
+def spmm_workload(density: float, n: int = 10000, f: int = 128, device="cpu") -> Workload:
+    """Sparse-dense product of Section 6.1's micro-benchmark: an n x n sparse matrix of the
+    given density (values N(0,1)) times an n x f dense matrix, expressed as a layer whose
+    ApplyEdge multiplies by the edge value, Gather sums, and there is no ApplyVertex."""
+    seed = 7000 + int(round(density * 1e6))
+    g = bernoulli_graph(n, density, seed, device)
+    X = normal_features(n, f, seed + 1, device)
+    w = normal(seed + 2, 8, g.nnz, device)
+    return Workload(f"spmm_{n}x{n}_d{density:g}_x{f}", g, X, "mul_weight", w, torch.zeros(f, 0), "none", "f32")

@@ -254,3 +254,16 @@ def test_malformed_graphs_and_arguments_are_rejected(ctx):
     assert status(lambda: ctx.layer_forward(g, X, torch.zeros(2, 4, device="cuda"), W=torch.zeros(5, 4, device="cuda"))) == INVALID
     assert status(lambda: ctx.layer_forward(g, X, torch.zeros(2, 4, device="cuda", dtype=torch.bfloat16))) == INVALID
     g.destroy()
+
+
+@pytest.mark.parametrize("density", [1e-4, 1e-3, 1e-2, 1e-1])
+def test_spmm_microbenchmark_shapes(ctx, density):
+    """Section 6.1: 10,000 x 10,000 sparse (density 0.01 % .. 10 %) times 10,000 x 128 dense."""
+    wl = si.spmm_workload(density)
+    assert wl.graph.n == 10000 and wl.X.shape == (10000, 128)
+    assert abs(wl.graph.nnz / 1e8 - density) < 0.05 * density + 2e-6
+    graph = make_graph(ctx, wl.graph)
+    Y, _ = run_gpu(ctx, wl, graph, with_vertex=False, want_accum=False)
+    ref = run_oracle(wl, with_vertex=False)
+    assert_sum_close(Y, ref["A"], ref["A_abs"], TOL_F32, f"SpMM density {density}")
+    graph.destroy()
