@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5", "spmm"],
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5", "spmm", "commnet", "mpgcn"],
                     help="config5 is streamed from pinned host memory under a 16 GiB device budget; spmm is the "
                          "10,000 x 10,000 sparse times 10,000 x 128 dense micro-benchmark of the paper's Section 6.1")
     ap.add_argument("--density", type=float, default=0.01, help="spmm only: fraction of non-zero cells")
@@ -83,12 +83,19 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda"
-    k = 0 if args.workload == "spmm" else int(args.workload[-1])
+    k = int(args.workload[-1]) if args.workload.startswith("config") else 0
     if k == 5:
         return bench_streamed(args)
     t0 = time.time()
-    if k == 0:
+    if args.workload == "spmm":
         wl = si.spmm_workload(args.density, device=dev)
+    elif args.workload == "commnet":      # Figure 9 on R-MAT 20, 128 -> 128
+        wl = si.commnet_workload(scale=args.scale or 20, edge_factor=args.edge_factor or 16, f_in=128, f_out=128, device=dev)
+    elif args.workload == "mpgcn":        # Figure 11 on R-MAT 20, 128 -> pool 128 -> 128
+        wl = si.mpgcn_workload(scale=args.scale or 20, edge_factor=args.edge_factor or 32, f_in=128, f_pool=128, f_out=128,
+                               device=dev)
+        if args.agg == "sum":
+            args.agg = "max"
     else:
         wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
     torch.cuda.synchronize()
@@ -97,6 +104,7 @@ def main():
     n, nnz = g.n, g.nnz
     has_w = wl.W.numel() > 0
     f_in, f_out = wl.X.shape[1], (wl.W.shape[1] if has_w else wl.X.shape[1])
+    f_msg = wl.W_pool.shape[0] if wl.edge_op == "pool" else f_in
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     es = 2 if wl.dtype == "bf16" else 4
 
@@ -117,6 +125,10 @@ def main():
         graph.set_edge_data(wl.edge_weight)
     if wl.edge_op == "gated":
         kw.update(W_gate=wl.W_gate, b_gate=wl.b_gate, W_msg=wl.W_msg)
+    if wl.edge_op == "pool":
+        kw.update(W_pool=wl.W_pool, b_pool=wl.b_pool)
+    if wl.W_self is not None:
+        kw["W_self"] = wl.W_self.to(tdt).contiguous()
 
     def step():
         ctx.layer_forward(graph, X, Y, **kw)
@@ -147,10 +159,10 @@ def main():
         del a, b
 
     ms_gather = tm["ms_gather"] / max(tm["n_calls"], 1)
-    alg_bytes = algorithmic_gather_bytes(nnz, n, f_in, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
+    alg_bytes = algorithmic_gather_bytes(nnz, n, f_msg, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
                                          info["n_work_items"])
     achieved = alg_bytes / (ms_gather * 1e-3) / 1e9 if ms_gather > 0 else 0.0
-    compulsory = n * f_in * es + nnz * (8 if wl.edge_op == "mul_weight" else 4) + info["n_work_items"] * 16 + n * f_in * es
+    compulsory = n * f_msg * es + nnz * (8 if wl.edge_op == "mul_weight" else 4) + info["n_work_items"] * 16 + n * f_msg * es
     out = {
         "metric": "fused_saga_layer_throughput", "value": round(gteps, 4), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -161,7 +173,7 @@ def main():
                    "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"]},
         "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(args.workload if k else f"spmm_d{args.density:g}", nnz, info["n_work_items"], args.agg),
+                     "traffic": measured_traffic(f"spmm_d{args.density:g}" if args.workload == "spmm" else args.workload, nnz, info["n_work_items"], args.agg),
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "compulsory_bytes_per_launch": compulsory,
                      "compulsory_frac": round(compulsory / (ms_gather * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if ms_gather > 0 else None,
@@ -186,6 +198,10 @@ def main():
             okw["edge_weight"] = wl.edge_weight.cpu().numpy()
         if wl.edge_op == "gated":
             okw.update(W_gate=wl.W_gate.cpu().numpy(), b_gate=wl.b_gate.cpu().numpy(), W_msg=wl.W_msg.cpu().numpy())
+        if wl.edge_op == "pool":
+            okw["hoisted"] = oracle.hoist_pool(Xh, wl.W_pool.cpu().numpy(), wl.b_pool.cpu().numpy())
+        if wl.W_self is not None:
+            okw["W_self"] = wl.W_self.float().cpu().numpy()
         rng = np.random.default_rng(12345)
         perm = rng.permutation(n)
         deg = np.diff(cp)

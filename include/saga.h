@@ -8,7 +8,7 @@
  *   ApplyEdge   per-edge function of that tuple (closed set below)
  *   Gather      per destination vertex, sum or element-wise max of the edge
  *               outputs ("commutative and associative accumulate", Section 2.2)
- *   ApplyVertex Y[v] = act(A[v] W + bias)               (Figures 2 and 10)
+ *   ApplyVertex Y[v] = act(A[v] W [+ X[v] W_self] + bias)   (Figures 2, 9 and 10)
  *
  * Scatter, ApplyEdge and Gather run as one fused propagation kernel (the
  * fused-gather operator of Section 3.2); vertex-only matrix products inside a
@@ -61,7 +61,7 @@ typedef enum {
 
 typedef enum { SAGA_F32 = 0, SAGA_BF16 = 1 } saga_dtype;
 typedef enum { SAGA_AGG_SUM = 0, SAGA_AGG_MAX = 1 } saga_agg;
-typedef enum { SAGA_ACT_NONE = 0, SAGA_ACT_RELU = 1 } saga_act;
+typedef enum { SAGA_ACT_NONE = 0, SAGA_ACT_RELU = 1, SAGA_ACT_SIGMOID = 2 } saga_act;
 typedef enum { SAGA_MEM_DEVICE = 0, SAGA_MEM_HOST = 1 } saga_mem;
 
 /*
@@ -71,8 +71,13 @@ typedef enum { SAGA_MEM_DEVICE = 0, SAGA_MEM_HOST = 1 } saga_mem;
  *   GATED       m = sigmoid(Wg [x_u ; x_v] + b) (.) (Wm x_u)
  *               (Example 2.1 / Figure 2; b and Wm optional, so that b = NULL,
  *               Wm = NULL is exactly Example 2.1)
+ *   POOL        m = sigmoid(Wp x_u + bp), F_pool values per edge (max-pooling GCN,
+ *               Figure 11, whose sigma is read as the logistic sigmoid); it depends on
+ *               the source only, so it is computed once per vertex (Section 3.2)
+ * The message width Fm is F_pool for POOL and F_in otherwise: Gather output, accum_out and
+ * the rows of W have that width.
  */
-typedef enum { SAGA_EDGE_COPY = 0, SAGA_EDGE_MUL_WEIGHT = 1, SAGA_EDGE_GATED = 2 } saga_edge_op;
+typedef enum { SAGA_EDGE_COPY = 0, SAGA_EDGE_MUL_WEIGHT = 1, SAGA_EDGE_GATED = 2, SAGA_EDGE_POOL = 3 } saga_edge_op;
 
 /* Row-major matrix view. dtype is a saga_dtype, mem a saga_mem. */
 typedef struct saga_tensor {
@@ -90,12 +95,18 @@ typedef struct saga_edge_params {
                                   [F,2F) on the destination row */
     const saga_tensor* b_gate; /* GATED: 1 x F fp32, nullable */
     const saga_tensor* W_msg;  /* GATED: F x F fp32 (row = output channel), nullable = identity */
+    const saga_tensor* W_pool; /* POOL: F_pool x F fp32 (row = output channel) */
+    const saga_tensor* b_pool; /* POOL: 1 x F_pool fp32, nullable */
 } saga_edge_params;
 
 typedef struct saga_vertex_params {
-    const saga_tensor* W;    /* F_in x F_out, dtype of X; NULL skips ApplyVertex (Y = Gather output) */
+    const saga_tensor* W;    /* Fm x F_out, dtype of X; NULL skips ApplyVertex (Y = Gather output) */
     const saga_tensor* bias; /* 1 x F_out fp32, nullable */
     int32_t act;             /* saga_act */
+    int32_t reserved;
+    const saga_tensor* W_self; /* F_in x F_out, dtype of X, nullable: Y = act(A W + X W_self + bias), the
+                                  ApplyVertex of CommNet, ReLU(W_H (x) vertex + W_C (x) accum) (Figure 9),
+                                  with W_self = W_H and W = W_C; device-resident calls only */
 } saga_vertex_params;
 
 /* Accumulated since saga_reset_timings(); stage times come from events on the context's stream. */
@@ -150,8 +161,8 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
 
 /*
  * One layer forward. X is n x F_in (SAGA_F32, or SAGA_BF16 for COPY /
- * MUL_WEIGHT). Y is n x F_out in X's dtype (n x F_in when vp->W is NULL).
- * accum_out, if given, receives the Gather output A as n x F_in fp32 before
+ * MUL_WEIGHT). Y is n x F_out in X's dtype (n x Fm when vp->W is NULL).
+ * accum_out, if given, receives the Gather output A as n x Fm fp32 before
  * ApplyVertex (device path only).
  *
  * Placement selects the path: all tensors SAGA_MEM_DEVICE with a device graph

@@ -11,7 +11,8 @@ Parity pins (tests/test_oracle_pins.py): dense brute force with numpy, the
 sparse-dense product identity of Section 6.1 via scipy.sparse, the in-degree
 invariant, brute-force max over the raw edge list, gated special cases that
 reduce to the other edge functions, a dense broadcast formulation of the gate,
-hoisted == naive, and hand-worked values under tests/golden/.
+hoisted == naive, dense forms of the CommNet and max-pooling layers (Figures 9,
+11), and hand-worked values under tests/golden/.
 """
 from __future__ import annotations
 
@@ -22,11 +23,24 @@ import numpy as np
 
 from .build import LIB, build
 
-EDGE_OPS = {"copy": 0, "mul_weight": 1, "gated": 2}
+EDGE_OPS = {"copy": 0, "mul_weight": 1, "gated": 2, "pool": 3}
 AGGS = {"sum": 0, "max": 1}
-ACTS = {"none": 0, "relu": 1}
+ACTS = {"none": 0, "relu": 1, "sigmoid": 2}
 
 _lib = None
+_P, _I64, _I32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+
+
+class _Args(ctypes.Structure):
+    """Mirror of saga_oracle_args in saga_oracle.c."""
+    _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
+                ("edge_op", _I32), ("agg", _I32), ("edge_w", _P),
+                ("W_gate", _P), ("b_gate", _P), ("W_msg", _P),
+                ("W_pool", _P), ("b_pool", _P), ("F_pool", _I64),
+                ("Ps", _P), ("Pd", _P), ("M", _P), ("Ps_abs", _P), ("Pd_abs", _P), ("M_abs", _P),
+                ("H", _P), ("H_abs", _P),
+                ("W", _P), ("bias", _P), ("W_self", _P), ("F_out", _I64), ("act", _I32), ("pad", _I32),
+                ("vlist", _P), ("nv", _I64), ("A", _P), ("A_abs", _P), ("Y", _P), ("Y_abs", _P)]
 
 
 def lib():
@@ -35,13 +49,13 @@ def lib():
         if not os.path.exists(LIB):
             build()
         L = ctypes.CDLL(LIB)
-        P, I64, I = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
-        L.saga_oracle_num_threads.restype = I
-        L.saga_oracle_hoist.restype = I
-        L.saga_oracle_hoist.argtypes = [I64, P, I64, P, P, P, P, P, P, P, P]
-        L.saga_oracle_layer.restype = I
-        L.saga_oracle_layer.argtypes = [I64, P, P, P, I64, I, P, P, P, P, P, P, P, P, P, P, I,
-                                        P, P, I64, I, P, I64, P, P, P, P]
+        L.saga_oracle_num_threads.restype = ctypes.c_int
+        L.saga_oracle_hoist.restype = ctypes.c_int
+        L.saga_oracle_hoist.argtypes = [_I64, _P, _I64, _P, _P, _P, _P, _P, _P, _P, _P]
+        L.saga_oracle_hoist_pool.restype = ctypes.c_int
+        L.saga_oracle_hoist_pool.argtypes = [_I64, _P, _I64, _P, _P, _I64, _P, _P]
+        L.saga_oracle_layer.restype = ctypes.c_int
+        L.saga_oracle_layer.argtypes = [ctypes.POINTER(_Args)]
         _lib = L
     return _lib
 
@@ -71,14 +85,28 @@ def hoist(X, W_gate, W_msg=None):
     return out
 
 
+def hoist_pool(X, W_pool, b_pool=None):
+    """H = sigmoid(X W_pool^T + b) per vertex (Figure 11's ApplyEdge, hoisted) and its error scale."""
+    X = _f32(X)
+    n, F = X.shape
+    Wp, bp = _f32(W_pool), _f32(b_pool)
+    Fp = Wp.shape[0]
+    assert Wp.shape == (Fp, F) and (bp is None or bp.shape == (Fp,))
+    H, Ha = np.empty((n, Fp), np.float64), np.empty((n, Fp), np.float64)
+    rc = lib().saga_oracle_hoist_pool(n, _ptr(X), F, _ptr(Wp), _ptr(bp), Fp, _ptr(H), _ptr(Ha))
+    assert rc == 0
+    return H, Ha
+
+
 def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_gate=None, W_msg=None,
-          agg="sum", W=None, bias=None, act="none", vlist=None, hoisted=None, want_abs=True):
+          W_pool=None, b_pool=None, agg="sum", W=None, bias=None, W_self=None, act="none", vlist=None,
+          hoisted=None, want_abs=True):
     """Run one layer on the CPU oracle.
 
-    Returns a dict with fp64 arrays: "A" (Gather output, nv x F), "A_abs",
-    and, when W is given, "Y" (nv x F_out) and "Y_abs". vlist selects the
-    destination vertices (default: all, in order). hoisted = the tuple from
-    hoist() switches the gated message to the hoisted form.
+    Returns a dict with fp64 arrays: "A" (Gather output, nv x Fm), "A_abs" (its error scale),
+    and, when W is given, "Y" (nv x F_out) and "Y_abs". vlist selects the destination vertices
+    (default: all, in order). hoisted = the tuple from hoist() (gated) or hoist_pool() (pool)
+    switches the message to its hoisted form.
     """
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
@@ -87,6 +115,7 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
     assert col_ptr.shape == (n + 1,) and int(col_ptr[-1]) == row_idx.shape[0]
     w = _f32(edge_weight)
     Wg, bg, Wm = _f32(W_gate), _f32(b_gate), _f32(W_msg)
+    Wp, bp = _f32(W_pool), _f32(b_pool)
     if Wg is not None:
         assert Wg.shape == (F, 2 * F)
     if Wm is not None:
@@ -95,34 +124,51 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
         assert bg.shape == (F,)
     if w is not None:
         assert w.shape == (row_idx.shape[0],)
-    Wv, bv = _f32(W), _f32(bias)
+    Fm, Fp = F, 0
+    if edge_op == "pool":
+        if hoisted is not None:
+            Fp = np.asarray(hoisted[0]).shape[1]
+        else:
+            Fp = Wp.shape[0]
+            assert Wp.shape == (Fp, F) and (bp is None or bp.shape == (Fp,))
+        Fm = Fp
+    Wv, bv, Ws = _f32(W), _f32(bias), _f32(W_self)
     F_out = 0
     if Wv is not None:
-        assert Wv.shape[0] == F
+        assert Wv.shape[0] == Fm
         F_out = Wv.shape[1]
         if bv is not None:
             assert bv.shape == (F_out,)
+        if Ws is not None:
+            assert Ws.shape == (F, F_out)
     if vlist is None:
         vl, nv = None, n
     else:
         vl = np.ascontiguousarray(np.asarray(vlist, dtype=np.int64))
         nv = vl.shape[0]
-    H = [None] * 6
+    G = [None] * 6
+    H = [None] * 2
     if hoisted is not None:
-        H = [np.ascontiguousarray(a, dtype=np.float64) for a in hoisted]
-        assert len(H) == 6
-    out = {"A": np.empty((nv, F), np.float64)}
+        hs = [np.ascontiguousarray(a, dtype=np.float64) for a in hoisted]
+        if edge_op == "pool":
+            assert len(hs) == 2
+            H = hs
+        else:
+            assert len(hs) == 6
+            G = hs
+    out = {"A": np.empty((nv, Fm), np.float64)}
     if want_abs:
-        out["A_abs"] = np.empty((nv, F), np.float64)
+        out["A_abs"] = np.empty((nv, Fm), np.float64)
     if Wv is not None:
         out["Y"] = np.empty((nv, F_out), np.float64)
         if want_abs:
             out["Y_abs"] = np.empty((nv, F_out), np.float64)
-    rc = lib().saga_oracle_layer(
-        n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], _ptr(w),
-        _ptr(Wg), _ptr(bg), _ptr(Wm), *[_ptr(a) for a in H], AGGS[agg],
-        _ptr(Wv), _ptr(bv), F_out, ACTS[act], _ptr(vl), nv,
-        _ptr(out["A"]), _ptr(out.get("A_abs")), _ptr(out.get("Y")), _ptr(out.get("Y_abs")))
+    a = _Args(n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], AGGS[agg], _ptr(w),
+              _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(Wp), _ptr(bp), Fp,
+              *[_ptr(x) for x in G], *[_ptr(x) for x in H],
+              _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, ACTS[act], 0,
+              _ptr(vl), nv, _ptr(out["A"]), _ptr(out.get("A_abs")), _ptr(out.get("Y")), _ptr(out.get("Y_abs")))
+    rc = lib().saga_oracle_layer(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_layer rejected its arguments")
     return out

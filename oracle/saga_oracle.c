@@ -14,7 +14,10 @@
  *   - accumulators sum and max: Section 2.2, last paragraph;
  *   - GCN layer: Figure 10 (ApplyEdge = src x edge.data, Gather = sum,
  *     ApplyVertex = ReLU(W (x) accum));
- *   - CommNet's pass-through ApplyEdge: Figure 9;
+ *   - CommNet's pass-through ApplyEdge and its two-term ApplyVertex
+ *     ReLU(W_H (x) vertex + W_C (x) accum): Figure 9;
+ *   - max-pooling GCN: ApplyEdge sigma(W_pool (x) src + b), Gather max: Figure 11
+ *     (sigma is not specified there; the logistic sigmoid is used);
  *   - gated layer: Example 2.1 and Figure 2 (gate = sigmoid of a linear map of
  *     source and destination data, message = gate (.) source data), widened
  *     with an optional bias and an optional message matrix;
@@ -109,56 +112,110 @@ int saga_oracle_hoist(int64_t n, const float* X, int64_t F, const float* W_gate,
 }
 
 /*
- * One layer for the destination vertices in vlist (all vertices when vlist is
- * NULL, then nv must equal n).
- *
- *   edge_op    EDGE_COPY / EDGE_MUL_WEIGHT (edge_w[nnz]) / EDGE_GATED
- *   W_gate, b_gate, W_msg   gated parameters (b_gate, W_msg nullable)
- *   Ps, Pd, M  when Ps is non-NULL the gated message is formed from these
- *              hoisted per-vertex products instead of per-edge products;
- *              Ps_abs, Pd_abs, M_abs are their absolute-term sums
- *   agg        AGG_SUM / AGG_MAX
- *   W, bias    ApplyVertex parameters; W NULL skips ApplyVertex
- *   A, A_abs   nv x F   Gather output and its absolute-term sum (nullable)
- *   Y, Y_abs   nv x F_out ApplyVertex output and its scale (nullable iff W NULL)
- * Returns 0, or nonzero on a bad argument.
+ * Max-pooling ApplyEdge of Figure 11 (MP-GCN), hoisted: it depends on the
+ * source only, so H[u] = sigmoid(W_pool x_u + b) is one product per vertex
+ * (Section 3.2). W_pool is Fp x F row-major (row = output channel), b is Fp
+ * (nullable). H and its error scale H_abs are n x Fp fp64.
  */
-int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
-                      const float* X, int64_t F,
-                      int edge_op, const float* edge_w,
-                      const float* W_gate, const float* b_gate, const float* W_msg,
-                      const double* Ps, const double* Pd, const double* M,
-                      const double* Ps_abs, const double* Pd_abs, const double* M_abs,
-                      int agg,
-                      const float* W, const float* bias, int64_t F_out, int act,
-                      const int64_t* vlist, int64_t nv,
-                      double* A, double* A_abs, double* Y, double* Y_abs)
+int saga_oracle_hoist_pool(int64_t n, const float* X, int64_t F, const float* W_pool, const float* b_pool, int64_t Fp,
+                           double* H, double* H_abs)
 {
-    if (!col_ptr || !X || F <= 0 || n < 0 || nv < 0) return 1;
-    if (!vlist && nv != n) return 1;
-    if (edge_op == EDGE_MUL_WEIGHT && !edge_w) return 1;
-    if (edge_op == EDGE_GATED && !W_gate && !Ps) return 1;
-    if (edge_op < 0 || edge_op > 2 || agg < 0 || agg > 1) return 1;
-    if (W && (!Y || F_out <= 0)) return 1;
-    if (Ps && (!Pd || !M || !Ps_abs || !Pd_abs || !M_abs)) return 1;
+    if (!X || !W_pool || !H || n < 0 || F <= 0 || Fp <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; ++v) {
+        const float* x = X + v * F;
+        for (int64_t c = 0; c < Fp; ++c) {
+            const float* wp = W_pool + c * F;
+            double z = b_pool ? (double)b_pool[c] : 0.0, za = fabs(z);
+            for (int64_t k = 0; k < F; ++k) {
+                z += (double)wp[k] * (double)x[k];
+                za += fabs((double)wp[k] * (double)x[k]);
+            }
+            const double g = sigmoid(z);
+            H[v * Fp + c] = g;
+            if (H_abs) H_abs[v * Fp + c] = g * (1.0 + (1.0 - g) * za);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Arguments of one layer. Message width Fm = F_pool for EDGE_POOL, else F.
+ *
+ *   edge_op    EDGE_COPY / EDGE_MUL_WEIGHT (edge_w[nnz]) / EDGE_GATED / EDGE_POOL
+ *   W_gate, b_gate, W_msg   gated parameters (b_gate, W_msg nullable)
+ *   W_pool, b_pool, F_pool  max-pooling parameters (Figure 11; b_pool nullable)
+ *   Ps, Pd, M (+ _abs)      when Ps is non-NULL the gated message is formed from these hoisted
+ *                           per-vertex products instead of per-edge products
+ *   H, H_abs   when H is non-NULL the pooled message is read from this hoisted array
+ *   agg        AGG_SUM / AGG_MAX
+ *   W, bias    ApplyVertex parameters, W is Fm x F_out; W NULL skips ApplyVertex
+ *   W_self     F x F_out, nullable: adds vertex (x) W_self, CommNet's ApplyVertex (Figure 9)
+ *   vlist, nv  destination vertices to compute (vlist NULL: all, nv must equal n)
+ *   A, A_abs   nv x Fm  Gather output and its error scale (nullable)
+ *   Y, Y_abs   nv x F_out ApplyVertex output and its scale (Y required iff W)
+ */
+typedef struct saga_oracle_args {
+    int64_t n;
+    const int64_t* col_ptr;
+    const int32_t* row_idx;
+    const float* X;
+    int64_t F;
+    int32_t edge_op, agg;
+    const float* edge_w;
+    const float *W_gate, *b_gate, *W_msg;
+    const float *W_pool, *b_pool;
+    int64_t F_pool;
+    const double *Ps, *Pd, *M, *Ps_abs, *Pd_abs, *M_abs;
+    const double *H, *H_abs;
+    const float *W, *bias, *W_self;
+    int64_t F_out;
+    int32_t act, pad;
+    const int64_t* vlist;
+    int64_t nv;
+    double *A, *A_abs, *Y, *Y_abs;
+} saga_oracle_args;
+
+enum { EDGE_POOL = 3 };
+enum { ACT_SIGMOID = 2 };
+
+int saga_oracle_layer(const saga_oracle_args* p)
+{
+    if (!p || !p->col_ptr || !p->X || p->F <= 0 || p->n < 0 || p->nv < 0) return 1;
+    const int64_t n = p->n, F = p->F, nv = p->nv, F_out = p->F_out;
+    const int edge_op = p->edge_op, agg = p->agg, act = p->act;
+    if (!p->vlist && nv != n) return 1;
+    if (edge_op < 0 || edge_op > 3 || agg < 0 || agg > 1) return 1;
+    if (edge_op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
+    if (edge_op == EDGE_GATED && !p->W_gate && !p->Ps) return 1;
+    if (edge_op == EDGE_POOL && ((!p->W_pool && !p->H) || p->F_pool <= 0)) return 1;
+    if (p->W && (!p->Y || F_out <= 0)) return 1;
+    if (p->W_self && !p->W) return 1;
+    if (p->Ps && (!p->Pd || !p->M || !p->Ps_abs || !p->Pd_abs || !p->M_abs)) return 1;
+    if (p->H && !p->H_abs) return 1;
+    const int64_t Fm = edge_op == EDGE_POOL ? p->F_pool : F;
+    const int64_t* col_ptr = p->col_ptr;
+    const int32_t* row_idx = p->row_idx;
+    const float* X = p->X;
+    const float *W_gate = p->W_gate, *b_gate = p->b_gate, *W_msg = p->W_msg;
     int bad = 0;
 
 #pragma omp parallel
     {
-        double* acc = (double*)malloc(sizeof(double) * (size_t)F * 4);
-        double* aab = acc + F;
-        double* msg = acc + 2 * F;
-        double* mab = acc + 3 * F; /* error scale of msg */
+        double* acc = (double*)malloc(sizeof(double) * (size_t)Fm * 4);
+        double* aab = acc + Fm;
+        double* msg = acc + 2 * Fm;
+        double* mab = acc + 3 * Fm; /* error scale of msg */
 #pragma omp for schedule(dynamic, 16)
         for (int64_t i = 0; i < nv; ++i) {
-            const int64_t v = vlist ? vlist[i] : i;
+            const int64_t v = p->vlist ? p->vlist[i] : i;
             if (v < 0 || v >= n) {
 #pragma omp atomic write
                 bad = 1;
                 continue;
             }
             const int64_t e0 = col_ptr[v], e1 = col_ptr[v + 1];
-            for (int64_t f = 0; f < F; ++f) { acc[f] = 0.0; aab[f] = 0.0; }
+            for (int64_t f = 0; f < Fm; ++f) { acc[f] = 0.0; aab[f] = 0.0; }
             const float* xv = X + v * F;
 
             for (int64_t e = e0; e < e1; ++e) {
@@ -168,20 +225,36 @@ int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
                 if (edge_op == EDGE_COPY) {
                     for (int64_t f = 0; f < F; ++f) { msg[f] = (double)xu[f]; mab[f] = fabs(msg[f]); }
                 } else if (edge_op == EDGE_MUL_WEIGHT) {
-                    const float w = edge_w[e];
+                    const float w = p->edge_w[e];
                     for (int64_t f = 0; f < F; ++f) {
-                        const float p = w * xu[f]; /* one fp32 multiply */
-                        msg[f] = (double)p;
+                        const float pr = w * xu[f]; /* one fp32 multiply */
+                        msg[f] = (double)pr;
                         mab[f] = fabs(msg[f]);
                     }
-                } else if (Ps) {
+                } else if (edge_op == EDGE_POOL) {
+                    if (p->H) {
+                        for (int64_t c = 0; c < Fm; ++c) { msg[c] = p->H[u * Fm + c]; mab[c] = p->H_abs[u * Fm + c]; }
+                    } else {
+                        for (int64_t c = 0; c < Fm; ++c) {
+                            const float* wp = p->W_pool + c * F;
+                            double z = p->b_pool ? (double)p->b_pool[c] : 0.0, za = fabs(z);
+                            for (int64_t k = 0; k < F; ++k) {
+                                z += (double)wp[k] * (double)xu[k];
+                                za += fabs((double)wp[k] * (double)xu[k]);
+                            }
+                            const double g = sigmoid(z);
+                            msg[c] = g;
+                            mab[c] = g * (1.0 + (1.0 - g) * za);
+                        }
+                    }
+                } else if (p->Ps) {
                     for (int64_t f = 0; f < F; ++f) {
                         const double b = b_gate ? (double)b_gate[f] : 0.0;
-                        const double z = Ps[u * F + f] + Pd[v * F + f] + b;
-                        const double za = Ps_abs[u * F + f] + Pd_abs[v * F + f] + fabs(b);
-                        const double g = sigmoid(z), t = M[u * F + f];
+                        const double z = p->Ps[u * F + f] + p->Pd[v * F + f] + b;
+                        const double za = p->Ps_abs[u * F + f] + p->Pd_abs[v * F + f] + fabs(b);
+                        const double g = sigmoid(z), t = p->M[u * F + f];
                         msg[f] = g * t;
-                        mab[f] = g * (M_abs[u * F + f] + fabs(t) * (1.0 - g) * za);
+                        mab[f] = g * (p->M_abs[u * F + f] + fabs(t) * (1.0 - g) * za);
                     }
                 } else {
                     for (int64_t f = 0; f < F; ++f) {
@@ -213,29 +286,41 @@ int saga_oracle_layer(int64_t n, const int64_t* col_ptr, const int32_t* row_idx,
                 }
                 /* ---- Gather ---- */
                 if (agg == AGG_SUM) {
-                    for (int64_t f = 0; f < F; ++f) { acc[f] += msg[f]; aab[f] += mab[f]; }
+                    for (int64_t f = 0; f < Fm; ++f) { acc[f] += msg[f]; aab[f] += mab[f]; }
                 } else if (e == e0) {
-                    for (int64_t f = 0; f < F; ++f) { acc[f] = msg[f]; aab[f] = mab[f]; }
+                    for (int64_t f = 0; f < Fm; ++f) { acc[f] = msg[f]; aab[f] = mab[f]; }
                 } else {
-                    for (int64_t f = 0; f < F; ++f) if (msg[f] > acc[f]) { acc[f] = msg[f]; aab[f] = mab[f]; }
+                    /* the maximum moves by no more than the largest error among its candidates */
+                    for (int64_t f = 0; f < Fm; ++f) {
+                        if (msg[f] > acc[f]) acc[f] = msg[f];
+                        if (mab[f] > aab[f]) aab[f] = mab[f];
+                    }
                 }
             }
-            if (A) memcpy(A + i * F, acc, sizeof(double) * (size_t)F);
-            if (A_abs) memcpy(A_abs + i * F, aab, sizeof(double) * (size_t)F);
+            if (p->A) memcpy(p->A + i * Fm, acc, sizeof(double) * (size_t)Fm);
+            if (p->A_abs) memcpy(p->A_abs + i * Fm, aab, sizeof(double) * (size_t)Fm);
 
-            /* ---- ApplyVertex: Y = act(bias + A W) ---- */
-            if (W) {
+            /* ---- ApplyVertex: Y = act(bias + A W [+ x_v W_self]) ---- */
+            if (p->W) {
                 for (int64_t o = 0; o < F_out; ++o) {
-                    double y = bias ? (double)bias[o] : 0.0;
+                    double y = p->bias ? (double)p->bias[o] : 0.0;
                     double ya = fabs(y);
-                    for (int64_t f = 0; f < F; ++f) {
-                        const double w = (double)W[f * F_out + o];
+                    for (int64_t f = 0; f < Fm; ++f) {
+                        const double w = (double)p->W[f * F_out + o];
                         y += acc[f] * w;
                         ya += aab[f] * fabs(w);
                     }
+                    if (p->W_self) {
+                        for (int64_t k = 0; k < F; ++k) {
+                            const double t = (double)xv[k] * (double)p->W_self[k * F_out + o];
+                            y += t;
+                            ya += fabs(t);
+                        }
+                    }
                     if (act == ACT_RELU && y < 0.0) y = 0.0;
-                    Y[i * F_out + o] = y;
-                    if (Y_abs) Y_abs[i * F_out + o] = ya;
+                    if (act == ACT_SIGMOID) { const double g = sigmoid(y); ya = g * (1.0 + (1.0 - g) * ya); y = g; }
+                    p->Y[i * F_out + o] = y;
+                    if (p->Y_abs) p->Y_abs[i * F_out + o] = ya;
                 }
             }
         }

@@ -20,8 +20,8 @@ SAGA_OK = 0
 STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "BAD_GRAPH", 3: "UNSUPPORTED", 4: "BUDGET", 5: "HIP", 6: "INTERNAL"}
 F32, BF16 = 0, 1
 AGG = {"sum": 0, "max": 1}
-ACT = {"none": 0, "relu": 1}
-EDGE_OP = {"copy": 0, "mul_weight": 1, "gated": 2}
+ACT = {"none": 0, "relu": 1, "sigmoid": 2}
+EDGE_OP = {"copy": 0, "mul_weight": 1, "gated": 2, "pool": 3}
 MEM_DEVICE, MEM_HOST = 0, 1
 
 # every entry point include/saga.h declares
@@ -44,11 +44,13 @@ class Tensor(ctypes.Structure):
 
 class EdgeParams(ctypes.Structure):
     _fields_ = [("op", ctypes.c_int32), ("edge_weight", ctypes.c_void_p), ("W_gate", ctypes.POINTER(Tensor)),
-                ("b_gate", ctypes.POINTER(Tensor)), ("W_msg", ctypes.POINTER(Tensor))]
+                ("b_gate", ctypes.POINTER(Tensor)), ("W_msg", ctypes.POINTER(Tensor)),
+                ("W_pool", ctypes.POINTER(Tensor)), ("b_pool", ctypes.POINTER(Tensor))]
 
 
 class VertexParams(ctypes.Structure):
-    _fields_ = [("W", ctypes.POINTER(Tensor)), ("bias", ctypes.POINTER(Tensor)), ("act", ctypes.c_int32)]
+    _fields_ = [("W", ctypes.POINTER(Tensor)), ("bias", ctypes.POINTER(Tensor)), ("act", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("W_self", ctypes.POINTER(Tensor))]
 
 
 class Timings(ctypes.Structure):
@@ -215,9 +217,11 @@ class Context:
 
     def layer_forward(self, g: Graph, X: torch.Tensor, Y: torch.Tensor, edge_op: str = "copy",
                       edge_weight: Optional[torch.Tensor] = None, W_gate=None, b_gate=None, W_msg=None,
-                      agg: str = "sum", W=None, bias=None, act: str = "none", accum_out=None):
+                      W_pool=None, b_pool=None, agg: str = "sum", W=None, bias=None, W_self=None, act: str = "none",
+                      accum_out=None):
         tx, ty = as_tensor(X), as_tensor(Y)
         twg, tbg, twm = as_tensor(W_gate), as_tensor(b_gate), as_tensor(W_msg)
+        twp, tbp, tws = as_tensor(W_pool), as_tensor(b_pool), as_tensor(W_self)
         tw, tb, tacc = as_tensor(W), as_tensor(bias), as_tensor(accum_out)
         if edge_weight is not None:
             assert edge_weight.dtype == torch.float32 and edge_weight.is_contiguous()
@@ -225,9 +229,12 @@ class Context:
         ep = EdgeParams(EDGE_OP[edge_op], edge_weight.data_ptr() if edge_weight is not None else None,
                         ctypes.pointer(twg) if twg is not None else None,
                         ctypes.pointer(tbg) if tbg is not None else None,
-                        ctypes.pointer(twm) if twm is not None else None)
+                        ctypes.pointer(twm) if twm is not None else None,
+                        ctypes.pointer(twp) if twp is not None else None,
+                        ctypes.pointer(tbp) if tbp is not None else None)
         vp = VertexParams(ctypes.pointer(tw) if tw is not None else None,
-                          ctypes.pointer(tb) if tb is not None else None, ACT[act])
+                          ctypes.pointer(tb) if tb is not None else None, ACT[act], 0,
+                          ctypes.pointer(tws) if tws is not None else None)
         cur = torch.cuda.current_stream(self.device)
         if cur != self.stream:
             self.stream.wait_stream(cur)

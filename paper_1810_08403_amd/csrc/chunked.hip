@@ -341,7 +341,9 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     if (has_w) {
         bt_padded_shape((int32_t)F_out, (int32_t)F, SAGA_F32, &n_pad, &k_pad);
         if ((st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * k_pad) * 4))) return st;
-        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)F, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, sc));
+        HIP_TRY(ctx, launch_zero_bytes(ctx->ws_bt.p, (size_t)(n_pad * k_pad) * 4, sc));
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)F, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, k_pad, 0,
+                                              sc));
     }
 
     for (int j = 0; j < Q; ++j) {

@@ -11,6 +11,7 @@
 // 32x32x16 MFMA operand; for fp32 it feeds four 32x32x2 MFMAs (lane halves
 // supply k and k+4 instead of k and k+1, the same on both operands, which
 // only permutes the order of the K sum).
+#include "device_math.h"
 #include "saga_internal.h"
 
 namespace {
@@ -58,23 +59,30 @@ __device__ __forceinline__ void tile_load(const GemmArgs& a, const T* __restrict
 {
     constexpr int KT = kRowBytes / (int)sizeof(T), EPC = 16 / (int)sizeof(T);
     ka = 0;
+    // K tiles [0, nk1) come from A, the rest from the optional second operand A2
+    const int nk1 = (a.K + KT - 1) / KT;
+    const bool second = kt >= nk1;
+    const T* __restrict__ Asrc = second ? static_cast<const T*>(a.A2) : A;
+    const int64_t ld = second ? a.lda2 : a.lda;
+    const int Klim = second ? a.K2 : a.K;
+    const int k0 = (second ? kt - nk1 : kt) * KT;
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         const int c = tid + 256 * i;
         const int row = (c >> 2) < BM ? (c >> 2) : 0, kc = c & 3;
         int64_t gr = m0 + row;
         if (gr >= a.M) gr = a.M - 1;
-        const int k = kt * KT + kc * EPC;
-        const bool in = k < a.K;
+        const int k = k0 + kc * EPC;
+        const bool in = k < Klim;
         ka |= in ? (1u << i) : 0u;
-        const T* p = A + gr * a.lda + (ALIGNED && !in ? 0 : k);
+        const T* p = Asrc + gr * ld + (ALIGNED && !in ? 0 : k);
         if (ALIGNED) {
             ra[i] = *reinterpret_cast<const u32x4*>(p);
         } else {
             uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
             for (int j = 0; j < EPC; ++j) {
-                const uint32_t e = (k + j < a.K) ? (sizeof(T) == 4 ? __float_as_uint(*reinterpret_cast<const float*>(p + j))
+                const uint32_t e = (k + j < Klim) ? (sizeof(T) == 4 ? __float_as_uint(*reinterpret_cast<const float*>(p + j))
                                                                    : (uint32_t) * reinterpret_cast<const uint16_t*>(p + j))
                                                  : 0u;
                 if (sizeof(T) == 4)
@@ -131,6 +139,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&a
                 if (CHECK && row0 + i * 32 + dr >= a.M) continue;
                 float y = acc[i][j][r] + bias;
                 if (a.act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
+                if (a.act == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
                 if (sizeof(TO) == 4)
                     reinterpret_cast<float*>(p)[dr * a.ldc] = y;
                 else
@@ -162,8 +171,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) voi
     const int wm = wave % WM, wn = wave / WM;
     const T* __restrict__ A = static_cast<const T*>(a.A);
     const T* __restrict__ Bt = static_cast<const T*>(a.Bt);
-    const int K = a.K;
-    const int nk = (K + KT - 1) / KT;
+    const int nk = (a.K + KT - 1) / KT + (a.A2 ? (a.K2 + KT - 1) / KT : 0);
 
     constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;
     u32x4 ra[ACH], rb[BCH];
@@ -213,13 +221,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) voi
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_pack_bt_transpose(const T* W, int64_t ldw, int K, int N, T* Bt, int64_t n_pad,
-                                                           int64_t k_pad)
+__global__ __launch_bounds__(256) void k_pack_bt_transpose(const T* W, int64_t ldw, int K, int N, T* Bt, int64_t ldbt, int64_t col0)
 {
-    const int64_t total = n_pad * k_pad;
+    const int64_t total = (int64_t)N * K;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-        const int64_t n = i / k_pad, k = i % k_pad;
-        Bt[i] = (n < N && k < K) ? W[k * ldw + n] : T(0);
+        const int64_t k = i / N, n = i % N;  // consecutive threads read consecutive elements of a row of W
+        Bt[n * ldbt + col0 + k] = W[k * ldw + n];
     }
 }
 
@@ -252,8 +259,11 @@ hipError_t launch_cfg(const GemmArgs& a, bool aligned, hipStream_t s)
 template <typename T, typename TO>
 hipError_t launch_typed(const GemmArgs& a, hipStream_t s)
 {
-    const bool aligned = (a.K * sizeof(T)) % 16 == 0 && (a.lda * sizeof(T)) % 16 == 0 &&
-                         (reinterpret_cast<uintptr_t>(a.A) & 15u) == 0;
+    bool aligned = (a.K * sizeof(T)) % 16 == 0 && (a.lda * sizeof(T)) % 16 == 0 &&
+                   (reinterpret_cast<uintptr_t>(a.A) & 15u) == 0;
+    if (a.A2)
+        aligned = aligned && (a.K2 * sizeof(T)) % 16 == 0 && (a.lda2 * sizeof(T)) % 16 == 0 &&
+                  (reinterpret_cast<uintptr_t>(a.A2) & 15u) == 0;
     if (a.N > 64) return launch_cfg<T, 128, 128, 2, 2, TO>(a, aligned, s);
     if (a.N > 32) return launch_cfg<T, 128, 64, 4, 1, TO>(a, aligned, s);
     return launch_cfg<T, 256, 32, 4, 1, TO>(a, aligned, s);
@@ -271,7 +281,7 @@ void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (a.K <= 0) return hipErrorInvalidValue;
+    if (a.K <= 0 || (a.A2 && a.K2 <= 0)) return hipErrorInvalidValue;
     if (a.dtype == SAGA_F32) {
         if (a.out_dtype != SAGA_F32) return hipErrorInvalidValue;
         return launch_typed<float, float>(a, s);
@@ -280,18 +290,18 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     return launch_typed<uint16_t, uint16_t>(a, s);
 }
 
-hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32_t N, int32_t dtype, void* Bt, hipStream_t s)
+hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32_t N, int32_t dtype, void* Bt, int64_t ldbt,
+                                    int64_t col0, hipStream_t s)
 {
-    int64_t n_pad, k_pad;
-    bt_padded_shape(N, K, dtype, &n_pad, &k_pad);
-    const int64_t total = n_pad * k_pad;
+    const int64_t total = (int64_t)N * K;
+    if (total <= 0) return hipSuccess;
     const int grid = (int)std::min<int64_t>((total + 255) / 256, 65535);
     if (dtype == SAGA_F32)
         hipLaunchKernelGGL(k_pack_bt_transpose<float>, dim3(grid), dim3(256), 0, s, static_cast<const float*>(W), ldw, K, N,
-                           static_cast<float*>(Bt), n_pad, k_pad);
+                           static_cast<float*>(Bt), ldbt, col0);
     else
         hipLaunchKernelGGL(k_pack_bt_transpose<uint16_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint16_t*>(W), ldw, K,
-                           N, static_cast<uint16_t*>(Bt), n_pad, k_pad);
+                           N, static_cast<uint16_t*>(Bt), ldbt, col0);
     return hipGetLastError();
 }
 

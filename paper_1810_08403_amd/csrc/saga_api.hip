@@ -170,20 +170,33 @@ struct DeviceGuard {
 // ApplyVertex on rows already on the device (used by both paths)
 // ---------------------------------------------------------------------------
 saga_status run_apply_vertex(saga_ctx* ctx, const void* A, int64_t lda, int32_t a_dtype, int64_t rows, int32_t F_in,
-                             const saga_vertex_params* vp, void* Y, int64_t ldy, int32_t y_dtype)
+                             const saga_vertex_params* vp, const void* Xself, int64_t ld_self, int32_t F_self, void* Y,
+                             int64_t ldy, int32_t y_dtype)
 {
     const saga_tensor* W = vp->W;
     const int32_t F_out = (int32_t)W->cols;
-    int64_t n_pad, k_pad;
+    const bool self = vp->W_self != nullptr;
+    int64_t n_pad, k_pad, n_pad2 = 0, k_pad2 = 0;
     bt_padded_shape(F_out, F_in, a_dtype, &n_pad, &k_pad);
+    if (self) bt_padded_shape(F_out, F_self, a_dtype, &n_pad2, &k_pad2);
+    const int64_t ldbt = k_pad + k_pad2;
     const size_t es = a_dtype == SAGA_F32 ? 4 : 2;
-    if (saga_status st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * k_pad) * es)) return st;
-    HIP_TRY(ctx, launch_pack_bt_transpose(W->data, W->ld, F_in, F_out, a_dtype, ctx->ws_bt.p, ctx->stream));
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * ldbt) * es)) return st;
+    HIP_TRY(ctx, launch_zero_bytes(ctx->ws_bt.p, (size_t)(n_pad * ldbt) * es, ctx->stream));
+    HIP_TRY(ctx, launch_pack_bt_transpose(W->data, W->ld, F_in, F_out, a_dtype, ctx->ws_bt.p, ldbt, 0, ctx->stream));
+    if (self)
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, F_self, F_out, a_dtype, ctx->ws_bt.p, ldbt,
+                                              k_pad, ctx->stream));
     GemmArgs g{};
     g.A = A;
     g.lda = lda;
+    if (self) {
+        g.A2 = Xself;
+        g.lda2 = ld_self;
+        g.K2 = F_self;
+    }
     g.Bt = ctx->ws_bt.p;
-    g.ldbt = k_pad;
+    g.ldbt = ldbt;
     g.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
     g.C = Y;
     g.ldc = ldy;
@@ -541,11 +554,13 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)X->cols;
+    const bool pool = ep->op == SAGA_EDGE_POOL;
+    const int32_t Fm = pool ? (int32_t)ep->W_pool->rows : F;  // message width
     const bool bf16 = X->dtype == SAGA_BF16;
     const bool has_w = vp && vp->W;
     hipStream_t s = ctx->stream;
     // bytes one edge gathers: the source row, or two hoisted fp32 rows when gated
-    const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)F * (bf16 ? 2 : 4);
+    const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)Fm * (bf16 ? 2 : 4);
     if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
 
     saga_ctx::EventSet* es = nullptr;
@@ -569,9 +584,9 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ga.items = static_cast<const WorkItem*>(g->d_items.p);
     ga.n_items = g->n_items;
     ga.row_idx = static_cast<const int32_t*>(g->d_row_idx.p);
-    ga.F = F;
+    ga.F = Fm;
     ga.agg = agg;
-    ga.op = ep->op;
+    ga.op = pool ? (int32_t)SAGA_EDGE_COPY : ep->op;
     ga.xcd_remap = ctx->opt_xcd_remap;
     ga.accumulate = 0;
 
@@ -614,6 +629,35 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ga.ld_dst = 3 * (int64_t)F;
         ga.dtype = SAGA_F32;
         if (es) es->has_hoist = true;
+    } else if (pool) {
+        // Figure 11's ApplyEdge depends on the source only: H = sigmoid(X Wp^T + bp) once per vertex (Section 3.2),
+        // then the propagation kernel gathers rows of H
+        int64_t n_pad, k_pad;
+        bt_padded_shape(Fm, F, SAGA_F32, &n_pad, &k_pad);
+        saga_status st;
+        if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+        if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * Fm))) return st;
+        float* bt = static_cast<float*>(ctx->ws_bt.p);
+        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, Fm, F, bt, k_pad, 0, s));
+        GemmArgs hg{};
+        hg.A = X->data;
+        hg.lda = X->ld;
+        hg.Bt = bt;
+        hg.ldbt = k_pad;
+        hg.bias = ep->b_pool ? static_cast<const float*>(ep->b_pool->data) : nullptr;
+        hg.C = ctx->ws_hoist.p;
+        hg.ldc = Fm;
+        hg.M = n;
+        hg.N = Fm;
+        hg.K = F;
+        hg.dtype = hg.out_dtype = SAGA_F32;
+        hg.act = SAGA_ACT_SIGMOID;
+        HIP_TRY(ctx, launch_gemm(hg, s));
+        ga.src = ctx->ws_hoist.p;
+        ga.ld_src = Fm;
+        ga.dtype = SAGA_F32;
+        if (es) es->has_hoist = true;
     } else {
         ga.src = X->data;
         ga.ld_src = X->ld;
@@ -635,9 +679,9 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
             ga.out = static_cast<float*>(Y->data);
             ga.ld_out = Y->ld;
         } else {
-            if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)n * F)) return st;
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)n * Fm)) return st;
             ga.out = static_cast<float*>(ctx->ws_accum.p);
-            ga.ld_out = F;
+            ga.ld_out = Fm;
         }
     } else {
         if (accum_out) {
@@ -654,7 +698,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         }
     }
     if (g->n_slots > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * F)) return st;
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * Fm)) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
     }
     HIP_TRY(ctx, launch_gather(ga, s));
@@ -665,7 +709,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ca.heavy = static_cast<const HeavyVertex*>(g->d_heavy.p);
         ca.n_heavy = g->n_heavy;
         ca.partials = ga.partials;
-        ca.F = F;
+        ca.F = Fm;
         ca.agg = agg;
         ca.out = ga.out;
         ca.ld_out = ga.ld_out;
@@ -680,7 +724,8 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     if (has_w) {
         const void* A = bf16 ? static_cast<const void*>(ga.out16) : static_cast<const void*>(ga.out);
         const int64_t lda = bf16 ? ga.ld_out16 : ga.ld_out;
-        if (saga_status st = run_apply_vertex(ctx, A, lda, X->dtype, n, F, vp, Y->data, Y->ld, Y->dtype)) return st;
+        if (saga_status st = run_apply_vertex(ctx, A, lda, X->dtype, n, Fm, vp, X->data, X->ld, F, Y->data, Y->ld, Y->dtype))
+            return st;
         if (es) es->has_apply = true;
     }
     if (es) {
@@ -701,26 +746,41 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
     if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
     if (!tensor_ok(X) || !tensor_ok(Y)) return ctx->fail(SAGA_ERR_INVALID_ARG, "malformed X or Y tensor");
     if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
-    if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_GATED) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
+    if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
     if (X->rows != g->n || Y->rows != g->n)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "X/Y have %lld/%lld rows, graph has %lld vertices", (long long)X->rows,
                          (long long)Y->rows, (long long)g->n);
     if (X->cols > (1 << 20)) return ctx->fail(SAGA_ERR_UNSUPPORTED, "feature width above 2^20");
     const int64_t F = X->cols;
     const bool has_w = vp && vp->W;
-    if (vp && vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
+    if (vp && (vp->act < SAGA_ACT_NONE || vp->act > SAGA_ACT_SIGMOID)) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
+    int64_t Fm = F;  // message width
+    if (ep->op == SAGA_EDGE_POOL) {
+        if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "max-pooling ApplyEdge is fp32 only");
+        const saga_tensor* Wp = ep->W_pool;
+        if (!tensor_ok(Wp) || Wp->mem != SAGA_MEM_DEVICE || Wp->dtype != SAGA_F32 || Wp->cols != F || Wp->rows < 1 ||
+            Wp->rows > (1 << 20))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_pool must be a device F_pool x F fp32 tensor");
+        if (ep->b_pool && (!tensor_ok(ep->b_pool) || ep->b_pool->mem != SAGA_MEM_DEVICE || ep->b_pool->dtype != SAGA_F32 ||
+                           ep->b_pool->rows * ep->b_pool->cols != Wp->rows))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "b_pool must be F_pool fp32 values on the device");
+        Fm = Wp->rows;
+    }
     if (has_w) {
         const saga_tensor* W = vp->W;
-        if (!tensor_ok(W) || W->mem != SAGA_MEM_DEVICE || W->rows != F || W->dtype != X->dtype)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out tensor of X's dtype");
+        if (!tensor_ok(W) || W->mem != SAGA_MEM_DEVICE || W->rows != Fm || W->dtype != X->dtype)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device Fm x F_out tensor of X's dtype");
+        if (vp->W_self && (!tensor_ok(vp->W_self) || vp->W_self->mem != SAGA_MEM_DEVICE || vp->W_self->rows != F ||
+                           vp->W_self->cols != W->cols || vp->W_self->dtype != X->dtype))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out tensor of X's dtype");
         if (vp->bias && (!tensor_ok(vp->bias) || vp->bias->mem != SAGA_MEM_DEVICE || vp->bias->dtype != SAGA_F32 ||
                          vp->bias->rows * vp->bias->cols != W->cols))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bias must be F_out fp32 values on the device");
         if (Y->cols != W->cols) return ctx->fail(SAGA_ERR_INVALID_ARG, "Y has %lld columns, W has %lld", (long long)Y->cols, (long long)W->cols);
     } else {
-        if (Y->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "without W, Y must be n x F_in");
-        if (vp && (vp->bias || vp->act != SAGA_ACT_NONE))
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "bias/activation without W");
+        if (Y->cols != Fm) return ctx->fail(SAGA_ERR_INVALID_ARG, "without W, Y must be n x Fm");
+        if (vp && (vp->bias || vp->act != SAGA_ACT_NONE || vp->W_self))
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "bias, activation or W_self without W");
     }
     if (Y->dtype != X->dtype) return ctx->fail(SAGA_ERR_INVALID_ARG, "Y must have X's dtype");
     if (ep->op == SAGA_EDGE_GATED) {
@@ -743,7 +803,9 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need X, Y and the graph in host memory");
         if (accum_out) return ctx->fail(SAGA_ERR_UNSUPPORTED, "accum_out is not available on the streamed path");
         if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
-        if (ep->op == SAGA_EDGE_GATED) return ctx->fail(SAGA_ERR_UNSUPPORTED, "gated ApplyEdge is not streamed");
+        if (ep->op == SAGA_EDGE_GATED || ep->op == SAGA_EDGE_POOL)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "gated and max-pooling ApplyEdge are not streamed");
+        if (vp && vp->W_self) return ctx->fail(SAGA_ERR_UNSUPPORTED, "W_self is not streamed");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         return streamed_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
@@ -751,8 +813,8 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
     if (Y->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "resident calls need X, Y and the graph in device memory");
     if (accum_out && (!tensor_ok(accum_out) || accum_out->mem != SAGA_MEM_DEVICE || accum_out->dtype != SAGA_F32 ||
-                      accum_out->rows != g->n || accum_out->cols != F))
-        return ctx->fail(SAGA_ERR_INVALID_ARG, "accum_out must be a device n x F_in fp32 tensor");
+                      accum_out->rows != g->n || accum_out->cols != Fm))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "accum_out must be a device n x Fm fp32 tensor");
     if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
     if (g->n == 0) return SAGA_OK;

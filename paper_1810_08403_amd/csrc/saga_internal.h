@@ -188,6 +188,10 @@ hipError_t launch_validate_columns(const int64_t* col_ptr, int64_t n_cols, const
 struct GemmArgs {
     const void* A;      // M x K, dtype
     int64_t lda;
+    const void* A2;     // optional second operand, M x K2: C = act(A Bt[:, :Kp]^T + A2 Bt[:, Kp:]^T + bias),
+    int64_t lda2;       // Kp = K padded to the K tile (bt_padded_shape)
+    int32_t K2;
+    int32_t pad_;
     const void* Bt;     // Npad x Kpad, dtype, row n = column n of the weight matrix
     int64_t ldbt;       // = Kpad
     const float* bias;  // [N] fp32, nullable
@@ -202,9 +206,10 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 // Size (elements) of a padded Bt for N x K.
 void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_t* k_pad);
-// Bt[n][k] = W[k][n] (W is K x N row-major with ldw); pads with zeros. dtype in = dtype out.
+// Bt[n][col0 + k] = W[k][n] for n < N, k < K (W is K x N row-major with ldw). Writes only those
+// entries: zero the padded Bt first. dtype in = dtype out.
 hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32_t N, int32_t dtype,
-                                    void* Bt, hipStream_t s);
+                                    void* Bt, int64_t ldbt, int64_t col0, hipStream_t s);
 // Bt rows [row0, row0 + R) = Wsrc[r][col0 .. col0 + K) (already output-channel major); Wsrc NULL = identity.
 hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int32_t R, int32_t K,
                                float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
@@ -217,5 +222,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device
+// Xself / ld_self / F_self: the vertices' own rows for vp->W_self (ignored when that is NULL)
 saga_status run_apply_vertex(saga_ctx* ctx, const void* A, int64_t lda, int32_t a_dtype, int64_t rows,
-                             int32_t F_in, const saga_vertex_params* vp, void* Y, int64_t ldy, int32_t y_dtype);
+                             int32_t F_in, const saga_vertex_params* vp, const void* Xself, int64_t ld_self,
+                             int32_t F_self, void* Y, int64_t ldy, int32_t y_dtype);

@@ -289,6 +289,9 @@ class Workload:
     W_gate: Optional[torch.Tensor] = None  # fp32 [f, 2f]
     b_gate: Optional[torch.Tensor] = None  # fp32 [f]
     W_msg: Optional[torch.Tensor] = None   # fp32 [f, f]
+    W_pool: Optional[torch.Tensor] = None  # fp32 [f_pool, f]   (edge_op "pool")
+    b_pool: Optional[torch.Tensor] = None  # fp32 [f_pool]
+    W_self: Optional[torch.Tensor] = None  # fp32 [f, f_out]    (CommNet's W_H)
     extra: dict = field(default_factory=dict)
 
 
@@ -349,6 +352,31 @@ def workload(k: int, device="cpu", scale: Optional[int] = None, edge_factor: Opt
         return Workload("config5_rmat23_gcn_f32_streamed", g, X, "mul_weight", gcn_edge_weights(g),
                         glorot_uniform(fi, fo, wseed, device), "relu", "f32")
     raise ValueError(f"no configuration {k}")
+
+
+def commnet_workload(scale=12, edge_factor=16, f_in=64, f_out=64, device="cpu") -> Workload:
+    """CommNet layer (Figure 9) on a symmetrised R-MAT graph: pass-through ApplyEdge, sum Gather,
+    ApplyVertex ReLU(W_H (x) vertex + W_C (x) accum)."""
+    n = 1 << scale
+    s, d = rmat_edges(scale, n * edge_factor, 4100 + scale, device=device)
+    g = build_csc(n, s, d, symmetrise=True, self_loops=False)
+    wl = Workload(f"commnet_rmat{scale}", g, normal_features(n, f_in, 4200, device), "copy", None,
+                  glorot_uniform(f_in, f_out, 4300, device), "relu", "f32")
+    wl.W_self = glorot_uniform(f_in, f_out, 4301, device)
+    return wl
+
+
+def mpgcn_workload(scale=12, edge_factor=16, f_in=64, f_pool=32, f_out=16, device="cpu") -> Workload:
+    """Max-pooling GCN layer (Figure 11) on a directed R-MAT graph: ApplyEdge sigmoid(W_pool (x) src + b),
+    max Gather, ApplyVertex ReLU(W (x) accum)."""
+    n = 1 << scale
+    s, d = rmat_edges(scale, n * edge_factor, 4500 + scale, device=device)
+    g = build_csc(n, s, d, symmetrise=False, self_loops=False)
+    wl = Workload(f"mpgcn_rmat{scale}", g, normal_features(n, f_in, 4600, device), "pool", None,
+                  glorot_uniform(f_pool, f_out, 4700, device), "relu", "f32")
+    wl.W_pool = glorot_uniform(f_pool, f_in, 4701, device)
+    wl.b_pool = uniform_pm(f_pool, 0.5, 4702, device)
+    return wl
 
 
 def spmm_workload(density: float, n: int = 10000, f: int = 128, device="cpu") -> Workload:

@@ -50,13 +50,19 @@ def run_gpu(ctx, wl, graph, agg="sum", want_accum=True, with_vertex=True, bias=N
     if wl.edge_op == "gated":
         kw.update(W_gate=wl.W_gate.to(dev), b_gate=None if wl.b_gate is None else wl.b_gate.to(dev),
                   W_msg=None if wl.W_msg is None else wl.W_msg.to(dev))
+    Fm = F
+    if wl.edge_op == "pool":
+        kw.update(W_pool=wl.W_pool.to(dev), b_pool=None if wl.b_pool is None else wl.b_pool.to(dev))
+        Fm = wl.W_pool.shape[0]
     if with_vertex:
         Wd = to_device_dtype(Wt, wl.dtype)
         kw.update(W=Wd, act=wl.act if act is None else act, bias=None if bias is None else bias.to(dev))
+        if wl.W_self is not None:
+            kw["W_self"] = to_device_dtype(wl.W_self, wl.dtype)
         Y = torch.empty(n, Wd.shape[1], device=dev, dtype=Xd.dtype)
     else:
-        Y = torch.empty(n, F, device=dev, dtype=Xd.dtype)
-    A = torch.empty(n, F, device=dev, dtype=torch.float32) if want_accum else None
+        Y = torch.empty(n, Fm, device=dev, dtype=Xd.dtype)
+    A = torch.empty(n, Fm, device=dev, dtype=torch.float32) if want_accum else None
     ctx.layer_forward(graph, Xd, Y, edge_op=wl.edge_op, agg=agg, accum_out=A, **kw)
     torch.cuda.synchronize()
     return Y.float().cpu().numpy(), (None if A is None else A.cpu().numpy())
@@ -73,9 +79,15 @@ def run_oracle(wl, agg="sum", with_vertex=True, bias=None, vlist=None, W=None, a
                   W_msg=None if wl.W_msg is None else wl.W_msg.cpu().numpy())
         if hoisted:
             kw["hoisted"] = oracle.hoist(Xh, kw["W_gate"], kw["W_msg"])
+    if wl.edge_op == "pool":
+        if hoisted:
+            kw["hoisted"] = oracle.hoist_pool(Xh, wl.W_pool.cpu().numpy(), None if wl.b_pool is None else wl.b_pool.cpu().numpy())
+        else:
+            kw.update(W_pool=wl.W_pool.cpu().numpy(), b_pool=None if wl.b_pool is None else wl.b_pool.cpu().numpy())
     if with_vertex:
         kw.update(W=(wl.W if W is None else W).cpu().numpy(), act=wl.act if act is None else act,
-                  bias=None if bias is None else bias.cpu().numpy())
+                  bias=None if bias is None else bias.cpu().numpy(),
+                  W_self=None if wl.W_self is None else wl.W_self.cpu().numpy())
     return oracle.layer(g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), Xh, **kw)
 
 

@@ -1,0 +1,101 @@
+"""The other layer programs of the paper on the same kernels: CommNet (Figure 9) and
+max-pooling GCN (Figure 11), through the C ABI against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import saga_inputs as si
+from helpers import TOL_BF16, TOL_F32, assert_sum_close, make_graph, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1810_08403_amd as saga
+    c = saga.Context(0)
+    yield c
+    c.destroy()
+
+
+@pytest.mark.parametrize("f_in,f_out", [(64, 64), (128, 48), (20, 7), (500, 16)])
+def test_commnet_layer(ctx, f_in, f_out):
+    wl = si.commnet_workload(scale=12, f_in=f_in, f_out=f_out)
+    graph = make_graph(ctx, wl.graph)
+    bias = si.uniform_pm(f_out, 0.3, 77)
+    Y, A = run_gpu(ctx, wl, graph, bias=bias)
+    ref = run_oracle(wl, bias=bias)
+    assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, "CommNet Gather")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, "CommNet layer")
+    # the self term really is there: without it the result differs
+    wl2 = si.commnet_workload(scale=12, f_in=f_in, f_out=f_out)
+    wl2.W_self = None
+    Y2, _ = run_gpu(ctx, wl2, graph, bias=bias)
+    assert np.abs(Y - Y2).max() > 1e-3
+    graph.destroy()
+
+
+def test_commnet_layer_bf16(ctx):
+    wl = si.commnet_workload(scale=12, f_in=128, f_out=64)
+    wl.dtype = "bf16"
+    wl.X, wl.W, wl.W_self = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W), si.round_to_bf16(wl.W_self)
+    graph = make_graph(ctx, wl.graph)
+    Y, A = run_gpu(ctx, wl, graph)
+    ref = run_oracle(wl)
+    assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, "CommNet bf16 Gather")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_BF16, "CommNet bf16 layer")
+    graph.destroy()
+
+
+@pytest.mark.parametrize("f_in,f_pool,f_out", [(64, 32, 16), (128, 128, 128), (30, 9, 5), (16, 256, 8)])
+def test_max_pooling_gcn_layer(ctx, f_in, f_pool, f_out):
+    wl = si.mpgcn_workload(scale=12, f_in=f_in, f_pool=f_pool, f_out=f_out)
+    deg = wl.graph.in_degree()
+    assert (deg == 0).any() and deg.max().item() > 128          # empty columns and cut columns
+    graph = make_graph(ctx, wl.graph)
+    Y, A = run_gpu(ctx, wl, graph, agg="max")
+    ref = run_oracle(wl, agg="max", hoisted=True)
+    assert A.shape == (wl.graph.n, f_pool)
+    # the messages are sigmoids evaluated in fp32, so the maximum is compared to tolerance, not bit for bit
+    assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, "MP-GCN max Gather")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, "MP-GCN layer")
+    assert not A[(deg == 0).numpy()].any() and (A[(deg > 0).numpy()] > 0).all()
+    # naive per-edge oracle on a sample agrees too
+    vl = np.arange(0, wl.graph.n, 37)
+    refn = run_oracle(wl, agg="max", vlist=vl)
+    assert_sum_close(Y[vl], refn["Y"], refn["Y_abs"], TOL_F32, "MP-GCN layer vs naive oracle")
+    graph.destroy()
+
+
+def test_pool_with_sum_and_sigmoid_vertex_activation(ctx):
+    wl = si.mpgcn_workload(scale=11, f_in=32, f_pool=16, f_out=8)
+    wl.act = "sigmoid"
+    graph = make_graph(ctx, wl.graph)
+    Y, A = run_gpu(ctx, wl, graph, agg="sum")
+    ref = run_oracle(wl, agg="sum", hoisted=True)
+    assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, "pool + sum Gather")
+    assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, "sigmoid ApplyVertex")
+    graph.destroy()
+
+
+def test_new_parameters_are_validated(ctx):
+    import paper_1810_08403_amd as saga
+    wl = si.mpgcn_workload(scale=9, f_in=16, f_pool=8, f_out=4)
+    graph = make_graph(ctx, wl.graph)
+    X = wl.X.cuda()
+    n = wl.graph.n
+    def status(fn):
+        with pytest.raises(saga.SagaError) as e:
+            fn()
+        return e.value.status
+    Y8 = torch.empty(n, 8, device="cuda")
+    assert status(lambda: ctx.layer_forward(graph, X, Y8, edge_op="pool")) == 1                       # no W_pool
+    assert status(lambda: ctx.layer_forward(graph, X, Y8, edge_op="pool", W_pool=torch.zeros(8, 15, device="cuda"))) == 1
+    assert status(lambda: ctx.layer_forward(graph, X, torch.empty(n, 16, device="cuda"), edge_op="pool",
+                                            W_pool=wl.W_pool.cuda())) == 1                              # Y must be n x F_pool
+    Y4 = torch.empty(n, 4, device="cuda")
+    assert status(lambda: ctx.layer_forward(graph, X, Y4, edge_op="copy", W=torch.zeros(16, 4, device="cuda"),
+                                            W_self=torch.zeros(15, 4, device="cuda"))) == 1
+    assert status(lambda: ctx.layer_forward(graph, X, torch.empty(n, 16, device="cuda"), edge_op="copy",
+                                            W_self=torch.zeros(16, 16, device="cuda"))) == 3            # W_self without W
+    graph.destroy()

@@ -361,3 +361,83 @@ def test_vertex_list_selects_rows_of_the_full_result():
         assert np.array_equal(part[k], full[k][vl])
     with pytest.raises(ValueError):
         oracle.layer(*_np(g), wl.X.numpy(), vlist=[g.n], **kw)
+
+
+# --------------------------------------------------------------------------
+# CommNet's two-term ApplyVertex (Figure 9) and the max-pooling layer (Figure 11)
+# --------------------------------------------------------------------------
+
+def test_hand_worked_commnet_apply_vertex(hand):
+    y = oracle.layer(hand["csc_col_ptr"], hand["csc_row_idx"], hand["X"], "copy", W=hand["W"], W_self=hand["W_self"],
+                     act="relu")["Y"]
+    assert np.array_equal(y, np.array(hand["commnet_relu_Y_no_bias"], float))
+
+
+def test_commnet_layer_equals_dense_form():
+    g = _random_graph(120, 900, seed=41)
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((g.n, 6)).astype(np.float32)
+    Wc = rng.standard_normal((6, 4)).astype(np.float32)
+    Wh = rng.standard_normal((6, 4)).astype(np.float32)
+    b = rng.standard_normal(4).astype(np.float32)
+    o = oracle.layer(*_np(g), X, "copy", W=Wc, W_self=Wh, bias=b, act="relu")
+    Xd = X.astype(np.float64)
+    want = np.maximum(Xd @ Wh.astype(np.float64) + (_dense_adj(g) @ Xd) @ Wc.astype(np.float64) + b, 0)
+    assert np.allclose(o["Y"], want, rtol=1e-12, atol=1e-12)
+    want_abs = np.abs(Xd) @ np.abs(Wh).astype(np.float64) + (_dense_adj(g) @ np.abs(Xd)) @ np.abs(Wc).astype(np.float64) + np.abs(b)
+    assert np.allclose(o["Y_abs"], want_abs, rtol=1e-12, atol=1e-12)
+    # the self term uses the vertex's own row, not a neighbour's: zero W_C isolates it
+    o2 = oracle.layer(*_np(g), X, "copy", W=np.zeros_like(Wc), W_self=Wh, act="none")
+    assert np.allclose(o2["Y"], Xd @ Wh.astype(np.float64), rtol=1e-13, atol=1e-13)
+
+
+def _pool_setup(n=50, m=90, F=6, Fp=4, seed=9):
+    g = _random_graph(n, m, seed=seed)
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    Wp = rng.standard_normal((Fp, F)).astype(np.float32)
+    bp = rng.standard_normal(Fp).astype(np.float32)
+    return g, X, Wp, bp
+
+
+def test_max_pooling_layer_equals_dense_form():
+    g, X, Wp, bp = _pool_setup()
+    H = 1.0 / (1.0 + np.exp(-(X.astype(np.float64) @ Wp.astype(np.float64).T + bp)))
+    Adj = _dense_adj(g)
+    masked = np.where(Adj[:, :, None] > 0, H[None, :, :], -np.inf).max(axis=1)
+    want = np.where(np.isfinite(masked), masked, 0.0)           # empty columns give 0
+    assert (Adj.sum(1) == 0).any()
+    W = np.random.default_rng(4).standard_normal((4, 3)).astype(np.float32)
+    o = oracle.layer(*_np(g), X, "pool", W_pool=Wp, b_pool=bp, agg="max", W=W, act="relu")
+    assert np.allclose(o["A"], want, rtol=1e-13, atol=1e-14)
+    assert np.allclose(o["Y"], np.maximum(want @ W.astype(np.float64), 0), rtol=1e-12, atol=1e-13)
+    # the sum accumulator over the same messages is a plain product with the adjacency matrix
+    s = oracle.layer(*_np(g), X, "pool", W_pool=Wp, b_pool=bp, agg="sum")
+    assert np.allclose(s["A"], Adj @ H, rtol=1e-12, atol=1e-13)
+    # message uses the source row: pooling the destination's own row would give H[v] for every v with edges
+    assert not np.allclose(o["A"][Adj.sum(1) > 0], H[Adj.sum(1) > 0])
+
+
+def test_max_pooling_closed_forms_and_hoisting():
+    g, X, Wp, bp = _pool_setup()
+    deg = np.diff(g.col_ptr.numpy())
+    # zero weights: every message is sigmoid(b); with b = ln 3 that is 3/4
+    b = np.full(4, np.log(3.0), np.float32)
+    o = oracle.layer(*_np(g), X, "pool", W_pool=np.zeros_like(Wp), b_pool=b, agg="max")
+    assert np.allclose(o["A"][deg > 0], 0.75, rtol=1e-7) and not o["A"][deg == 0].any()
+    # hoisting (Section 3.2) changes nothing
+    a = oracle.layer(*_np(g), X, "pool", W_pool=Wp, b_pool=bp, agg="max")
+    h = oracle.layer(*_np(g), X, "pool", agg="max", hoisted=oracle.hoist_pool(X, Wp, bp))
+    assert np.array_equal(a["A"], h["A"]) and np.allclose(a["A_abs"], h["A_abs"], rtol=1e-13)
+    H, Ha = oracle.hoist_pool(X, Wp, bp)
+    Z = X.astype(np.float64) @ Wp.astype(np.float64).T + bp
+    Za = np.abs(X).astype(np.float64) @ np.abs(Wp).astype(np.float64).T + np.abs(bp)
+    G = 1.0 / (1.0 + np.exp(-Z))
+    assert np.allclose(H, G, rtol=1e-13) and np.allclose(Ha, G * (1 + (1 - G) * Za), rtol=1e-12)
+
+
+def test_sigmoid_activation_in_apply_vertex():
+    g = si.csc_from_lists(4, [(v, v) for v in range(4)])
+    X = np.array([[0.0], [np.log(3.0)], [-np.log(3.0)], [40.0]], np.float32)
+    o = oracle.layer(*_np(g), X, "copy", W=np.array([[1.0]], np.float32), act="sigmoid")
+    assert np.allclose(o["Y"][:, 0], [0.5, 0.75, 0.25, 1.0], rtol=1e-7)
