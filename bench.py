@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--cut-degree", type=int, default=None)
     ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--team", type=int, default=None)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain 1 GiB device copies (k_copy_u128), to scale memory-traffic counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
@@ -110,7 +111,7 @@ def main():
 
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
-                      ("xcd_remap", args.xcd_remap)):
+                      ("xcd_remap", args.xcd_remap), ("team", args.team)):
         if val is not None:
             ctx.set_option(name, val)
     t0 = time.time()

@@ -191,6 +191,9 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *   "stripe_kb"  pieces end where the source rows cross a multiple of this many KiB of
  *                feature rows, and pieces are processed band by band (default 1024;
  *                0 = cut by edge count only)
+ *   "team"       0/1, a piece of a cut column is worked by a whole workgroup whose four
+ *                wavefronts reduce through LDS, and holds at least 4 * split edges (default 0:
+ *                fewer partial rows, but measured slower than one wavefront per piece)
  *   "xcd_remap"  0/1, keep neighbouring work items on one XCD (default 1)
  *   "dst_intervals" / "src_intervals"  streamed plan override, 0 = automatic
  * Returns INVALID_ARG for unknown names or values. */
@@ -216,12 +219,14 @@ saga_status saga_copy_bytes(saga_ctx* ctx, void* dst, const void* src, size_t by
  * Host-only planning call (no GPU needed): build the work list of a host CSC the way
  * saga_layer_forward would for the given parameters, and copy up to `capacity` items into
  * items_out as (vertex, first edge, one-past-last edge, partial-row slot or -1) int32
- * quadruples. Counts are always returned. Used to test and to inspect the plan.
+ * quadruples. team = 4: the first *n_team_items items are pieces of cut columns, each worked
+ * by the four wavefronts of one workgroup; team = 1: every item is worked by one wavefront.
+ * Counts are always returned. Used to test and to inspect the plan.
  */
 saga_status saga_plan_work_list(int64_t n_vertices, const int64_t* col_ptr, const int32_t* row_idx,
-                                int64_t min_edges, int64_t cut_degree, int64_t stripe_rows,
+                                int64_t min_edges, int64_t cut_degree, int64_t stripe_rows, int32_t team,
                                 int32_t* items_out, int64_t capacity, int64_t* n_items,
-                                int64_t* n_split_vertices, int64_t* n_slots);
+                                int64_t* n_team_items, int64_t* n_split_vertices, int64_t* n_slots);
 const char* saga_version(void);
 
 #ifdef __cplusplus

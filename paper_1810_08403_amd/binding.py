@@ -6,8 +6,10 @@ library is missing: there is no CPU fallback.
 """
 from __future__ import annotations
 
+import atexit
 import ctypes
 import os
+import sys
 import weakref
 from typing import Optional
 
@@ -66,6 +68,18 @@ class Timings(ctypes.Structure):
 
 
 _lib = None
+_live_contexts = weakref.WeakSet()
+
+
+@atexit.register
+def _destroy_live_contexts():
+    # Contexts still alive at interpreter exit are released here, while the HIP runtime is
+    # still up; a destructor running during finalisation must not call into it any more.
+    for c in list(_live_contexts):
+        try:
+            c.destroy()
+        except Exception:
+            pass
 
 
 def load_library() -> ctypes.CDLL:
@@ -106,8 +120,8 @@ def load_library() -> ctypes.CDLL:
     L.saga_graph_info.restype = I32
     L.saga_graph_info.argtypes = [P, ctypes.POINTER(I64), ctypes.POINTER(I64), ctypes.POINTER(I64)]
     L.saga_plan_work_list.restype = I32
-    L.saga_plan_work_list.argtypes = [I64, P, P, I64, I64, I64, P, I64, ctypes.POINTER(I64), ctypes.POINTER(I64),
-                                      ctypes.POINTER(I64)]
+    L.saga_plan_work_list.argtypes = [I64, P, P, I64, I64, I64, I32, P, I64, ctypes.POINTER(I64), ctypes.POINTER(I64),
+                                      ctypes.POINTER(I64), ctypes.POINTER(I64)]
     L.saga_copy_bytes.restype = I32
     L.saga_copy_bytes.argtypes = [P, P, P, SZ]
     L.saga_version.restype = ctypes.c_char_p
@@ -163,6 +177,8 @@ class Graph:
             self._h = None
 
     def __del__(self):
+        if sys.is_finalizing():
+            return
         try:
             self.destroy()
         except Exception:
@@ -190,6 +206,7 @@ class Context:
         self._h = h
         self.device = device
         self._graphs = weakref.WeakSet()
+        _live_contexts.add(self)
 
     def synchronize(self):
         self.stream.synchronize()
@@ -275,27 +292,30 @@ class Context:
             self._h = None
 
     def __del__(self):
+        if sys.is_finalizing():
+            return
         try:
             self.destroy()
         except Exception:
             pass
 
 
-def plan_work_list(col_ptr: torch.Tensor, row_idx: torch.Tensor, min_edges=256, cut_degree=512, stripe_rows=1024):
+def plan_work_list(col_ptr: torch.Tensor, row_idx: torch.Tensor, min_edges=64, cut_degree=128, stripe_rows=1024, team=1):
     """Host-only: the work list the library would build (int32 tensor [n_items, 4]) and its counts."""
     L = load_library()
     assert not col_ptr.is_cuda and col_ptr.dtype == torch.int64 and row_idx.dtype == torch.int32
     n = col_ptr.numel() - 1
-    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
-    args = (n, col_ptr.data_ptr(), row_idx.data_ptr(), min_edges, cut_degree, stripe_rows)
-    st = L.saga_plan_work_list(*args, None, 0, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    a, t, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    args = (n, col_ptr.data_ptr(), row_idx.data_ptr(), min_edges, cut_degree, stripe_rows, team)
+    refs = (ctypes.byref(a), ctypes.byref(t), ctypes.byref(b), ctypes.byref(c))
+    st = L.saga_plan_work_list(*args, None, 0, *refs)
     if st != SAGA_OK:
         raise SagaError(st, "saga_plan_work_list")
     items = torch.empty(a.value, 4, dtype=torch.int32)
-    st = L.saga_plan_work_list(*args, items.data_ptr(), a.value, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    st = L.saga_plan_work_list(*args, items.data_ptr(), a.value, *refs)
     if st != SAGA_OK:
         raise SagaError(st, "saga_plan_work_list")
-    return items, {"n_items": a.value, "n_split_vertices": b.value, "n_slots": c.value}
+    return items, {"n_items": a.value, "n_team_items": t.value, "n_split_vertices": b.value, "n_slots": c.value}
 
 
 def version() -> str:

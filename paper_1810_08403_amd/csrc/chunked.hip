@@ -26,7 +26,7 @@
 #include "saga_internal.h"
 
 struct ChunkMeta {
-    int64_t nnz = 0, n_items = 0, n_heavy = 0, n_slots = 0;
+    int64_t nnz = 0, n_items = 0, n_team = 0, n_heavy = 0, n_slots = 0;
     size_t off_items = 0, off_heavy = 0, off_ridx = 0, off_w = 0, bytes = 0;
     char* host = nullptr;  // pinned payload: [items | heavy | row_idx | weights]
 };
@@ -34,7 +34,7 @@ struct ChunkMeta {
 struct ChunkGrid {
     int Q = 0, P = 0;
     int64_t Dq = 0, Sp = 0;  // rows per destination / source interval
-    WorkListParams wlp{-1, -1, -1, true};
+    WorkListParams wlp{-1, -1, -1, true, 1};
     bool weighted = false;
     std::vector<ChunkMeta> chunks;  // [j * P + i]
     size_t max_chunk_bytes = 0;
@@ -92,7 +92,7 @@ struct BuiltChunk {
     std::vector<HeavyVertex> heavy;
     std::vector<int32_t> ridx;
     std::vector<float> w;
-    int64_t n_slots = 0;
+    int64_t n_slots = 0, n_team = 0;
 };
 
 // Chunk C_ij of the host CSC: columns [j*Dq, ...), sources in [i*Sp, (i+1)*Sp), local ids.
@@ -127,6 +127,7 @@ void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, cons
     out->items.swap(wl.items);
     out->heavy.swap(wl.heavy);
     out->n_slots = wl.n_slots;
+    out->n_team = wl.n_team;
 }
 
 saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkListParams& wlp, bool weighted)
@@ -162,6 +163,7 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
         m.n_items = (int64_t)b.items.size();
         m.n_heavy = (int64_t)b.heavy.size();
         m.n_slots = b.n_slots;
+        m.n_team = b.n_team;
         size_t off = 0;
         m.off_items = off;
         off = round_up(off + sizeof(WorkItem) * b.items.size(), 256);
@@ -279,7 +281,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         return std::min<int64_t>(Dq, std::max<int64_t>(4096, (64 << 20) / (F_out * 4)));  // about 64 MiB per tile
     };
     const bool same_grid = g->grid && g->grid->wlp.min_edges == wlp.min_edges && g->grid->wlp.cut_degree == wlp.cut_degree &&
-                           g->grid->wlp.stripe_rows == wlp.stripe_rows && g->grid->weighted == weighted;
+                           g->grid->wlp.stripe_rows == wlp.stripe_rows && g->grid->wlp.team == wlp.team &&
+                           g->grid->weighted == weighted;
     if (same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P)) {
         Q = g->grid->Q;
         P = g->grid->P;
@@ -371,6 +374,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             GatherArgs ga{};
             ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
             ga.n_items = m.n_items;
+            ga.n_team = m.n_team;
             ga.row_idx = reinterpret_cast<const int32_t*>(cb + m.off_ridx);
             ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
             ga.src = grid->V[b].p;

@@ -169,20 +169,59 @@ __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, 
     }
 }
 
+// A wavefront's share of the work list. Blocks [0, n_team) take one team item each: the four
+// wavefronts of the block split its edges and reduce their rows through LDS (fixed order), so a
+// long column costs one partial row per team item, not one per wavefront. Later blocks take
+// four solo items, one per wavefront.
 struct ItemView {
-    int v, e0, e1, slot;
+    int v, e0, e1, slot;  // e0..e1: this wavefront's edges
+    bool team;
+    bool empty_item;      // the whole item has no edges (only a solo item can)
 };
 __device__ __forceinline__ bool fetch_item(const GatherArgs& a, ItemView* it)
 {
     const int wave = threadIdx.x >> 6;
-    const int64_t id = logical_block(a.xcd_remap) * kWavesPerBlock + wave;
-    if (id >= a.n_items) return false;
+    const int64_t blk = logical_block(a.xcd_remap);
+    const bool team = blk < a.n_team;
+    const int64_t id = team ? blk : a.n_team + (blk - a.n_team) * kWavesPerBlock + wave;
+    if (id >= a.n_items) return false;  // only in the last solo block, where no barrier follows
     const int4 raw = *reinterpret_cast<const int4*>(a.items + id);
     it->v = __builtin_amdgcn_readfirstlane(raw.x);
-    it->e0 = __builtin_amdgcn_readfirstlane(raw.y);
-    it->e1 = __builtin_amdgcn_readfirstlane(raw.z);
+    int e0 = __builtin_amdgcn_readfirstlane(raw.y);
+    int e1 = __builtin_amdgcn_readfirstlane(raw.z);
     it->slot = __builtin_amdgcn_readfirstlane(raw.w);
+    it->team = team;
+    it->empty_item = e0 == e1;
+    if (team) {
+        // equal shares, rounded up to the unroll width of the edge loop
+        const int per = (((e1 - e0 + kWavesPerBlock - 1) / kWavesPerBlock) + 7) & ~7;
+        const int w = __builtin_amdgcn_readfirstlane(wave);
+        e0 = min(e1, e0 + w * per);
+        e1 = min(e1, e0 + per);
+    }
+    it->e0 = e0;
+    it->e1 = e1;
     return true;
+}
+
+// Team reduction: wavefronts 1..3 park their row fragments in LDS (team_park), the block
+// synchronises once, and wavefront 0 adds them in wavefront order (team_collect) and stores.
+template <int NV>
+__device__ __forceinline__ void team_park(float* red, int per_wave, int slot_in_wave, bool active, const float (&val)[NV])
+{
+    const int wave = threadIdx.x >> 6;
+    if (wave > 0 && active) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) red[(wave - 1) * per_wave + slot_in_wave * NV + j] = val[j];
+    }
+}
+template <int AGG, int NV>
+__device__ __forceinline__ void team_collect(const float* red, int per_wave, int slot_in_wave, float (&val)[NV])
+{
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock - 1; ++w)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) val[j] = combine<AGG>(val[j], red[w * per_wave + slot_in_wave * NV + j]);
 }
 
 // ---------------------------------------------------------------------------
@@ -267,6 +306,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
     const T* __restrict__ X = static_cast<const T*>(a.src);
     const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
     const const_f32_ptr ew = GATED ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
+    __shared__ float red[(kWavesPerBlock - 1) * 64 * RC * VEC];
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
         float acc[RC][VEC];
@@ -314,9 +354,24 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
             wide_group<T, VEC, RC, AGG, GATED, U, true>(X, a.ld_src, F, u, w, e, it.e1, ldcol, pd, acc, x, m);
             wide_consume<T, VEC, RC, AGG, GATED, U, true>(w, e, it.e1, pd, acc, x, m);
         }
+        if (it.team) {  // the same for every wavefront of the block, so the barriers are uniform
 #pragma unroll
-        for (int c = 0; c < RC; ++c)
-            if (ok[c]) store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.e0 == it.e1);
+            for (int c = 0; c < RC; ++c) team_park<VEC>(red, 64 * RC * VEC, c * 64 + lane, ok[c], acc[c]);
+            __syncthreads();
+            if ((threadIdx.x >> 6) == 0) {
+#pragma unroll
+                for (int c = 0; c < RC; ++c)
+                    if (ok[c]) {
+                        team_collect<AGG, VEC>(red, 64 * RC * VEC, c * 64 + lane, acc[c]);
+                        store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, false);
+                    }
+            }
+            if (cb + 64 * RC < nvec) __syncthreads();  // LDS is reused by the next block of columns
+        } else {
+#pragma unroll
+            for (int c = 0; c < RC; ++c)
+                if (ok[c]) store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.empty_item);
+        }
     }
 }
 
@@ -398,7 +453,17 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
     for (int off = lpr; off < 64; off <<= 1)
 #pragma unroll
         for (int j = 0; j < VEC; ++j) acc[j] = combine<AGG>(acc[j], __shfl_xor(acc[j], off));
-    if (grp == 0 && colok) store_row<VEC>(a, it.v, it.slot, col, acc, AGG, it.e0 == it.e1);
+    if (it.team) {
+        __shared__ float red[(kWavesPerBlock - 1) * 32 * VEC];
+        team_park<VEC>(red, 32 * VEC, sub, grp == 0 && colok, acc);
+        __syncthreads();
+        if ((threadIdx.x >> 6) == 0 && grp == 0 && colok) {
+            team_collect<AGG, VEC>(red, 32 * VEC, sub, acc);
+            store_row<VEC>(a, it.v, it.slot, col, acc, AGG, false);
+        }
+    } else if (grp == 0 && colok) {
+        store_row<VEC>(a, it.v, it.slot, col, acc, AGG, it.empty_item);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -470,7 +535,7 @@ template <typename T, int VEC, int AGG, bool GATED>
 hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
 {
     const int nvec = (a.F + VEC - 1) / VEC;
-    const int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t blocks = a.n_team + (a.n_items - a.n_team + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(256);
     if (nvec <= 32) {

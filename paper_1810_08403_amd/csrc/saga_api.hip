@@ -82,16 +82,19 @@ saga_status saga_ctx::drain_events()
 // Work list of a CSC block (Section 3.3: one in-edge group per execution unit,
 // heavy groups cut into consecutive sub-groups). Columns with more than
 // cut_degree in-edges are cut into pieces that end on multiples of stripe_rows
-// source rows and hold at least min_edges edges (so at most min_edges +
-// stripe_rows); the pieces of all columns are then ordered by source stripe, so
-// that the wavefronts in flight at any time read one narrow band of the
-// source rows: the 2-D tiling of Section 3.1 applied at the level of the L2.
+// source rows and hold at least team * min_edges edges; the pieces of all
+// columns are then ordered by source stripe, so that the wavefronts in flight
+// at any time read one narrow band of the source rows: the 2-D tiling of
+// Section 3.1 applied at the level of the L2. With team = 4 a piece is
+// processed by the four wavefronts of one workgroup (team items come first in
+// the list); with team = 1 by one wavefront like a whole light column.
 void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
                      WorkList* out)
 {
     out->items.clear();
     out->heavy.clear();
     out->n_slots = 0;
+    out->n_team = 0;
     out->max_degree = 0;
     std::vector<WorkItem> whole;
     whole.reserve((size_t)n_cols);
@@ -101,6 +104,8 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
     };
     std::vector<Piece> pieces;
     const int64_t R = p.stripe_rows > 0 ? p.stripe_rows : 0;
+    const int64_t team = p.team > 1 ? p.team : 1;
+    const int64_t min_piece = std::max<int64_t>(1, p.min_edges * team);
     for (int64_t v = 0; v < n_cols; ++v) {
         const int64_t b = col_ptr[v], e = col_ptr[v + 1];
         const int64_t deg = e - b;
@@ -113,22 +118,26 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
         const size_t first_piece = pieces.size();
         int64_t pos = b;
         while (pos < e) {
-            int64_t q = std::min(e, pos + p.min_edges);
+            int64_t q = std::min(e, pos + min_piece);
             if (R > 0 && q < e) {
                 // extend to the end of the stripe that holds the last edge taken
                 const int64_t bound = ((int64_t)row_idx[q - 1] / R + 1) * R;
                 q = std::lower_bound(row_idx + q, row_idx + e, bound,
                                      [](int32_t a, int64_t bnd) { return (int64_t)a < bnd; }) - row_idx;
             }
-            if (e - q < p.min_edges / 2) q = e;  // do not leave a sliver behind
-            const int64_t stripe = R > 0 ? (int64_t)row_idx[pos] / R : (pos - b) / std::max<int64_t>(p.min_edges, 1);
-            pieces.push_back(Piece{stripe * n_cols + v, WorkItem{(int32_t)v, (int32_t)pos, (int32_t)q, 0}});
+            if (e - q < min_piece / 2) q = e;  // do not leave a sliver behind
+            const int64_t stripe = R > 0 ? (int64_t)row_idx[pos] / R : (pos - b) / min_piece;
+            pieces.push_back(Piece{stripe * n_cols + v, WorkItem{(int32_t)v, (int32_t)pos, (int32_t)q, -1}});
             pos = q;
         }
         const size_t n_p = pieces.size() - first_piece;
-        if (n_p == 1) {  // one piece after all: an ordinary whole column
-            whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, -1});
-            pieces.pop_back();
+        if (n_p == 1) {
+            // one piece after all: its result is the vertex's row. A team still takes it
+            // (four wavefronts share the edges); without teams it is an ordinary whole column.
+            if (team == 1) {
+                whole.push_back(pieces.back().it);
+                pieces.pop_back();
+            }
             continue;
         }
         HeavyVertex h{(int32_t)v, (int32_t)out->n_slots, (int32_t)n_p, 0};
@@ -138,6 +147,7 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
     std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.key < b.key; });
     out->items.reserve(pieces.size() + whole.size());
     for (const Piece& pc : pieces) out->items.push_back(pc.it);
+    out->n_team = team > 1 ? (int64_t)pieces.size() : 0;
     out->items.insert(out->items.end(), whole.begin(), whole.end());
 }
 
@@ -227,6 +237,7 @@ WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes)
     p.cut_degree = ctx->opt_cut_degree > 0 ? ctx->opt_cut_degree : 2 * ctx->opt_split;
     p.stripe_rows = 0;
     if (ctx->opt_stripe_kb > 0) p.stripe_rows = std::max<int64_t>(64, pow2_floor(ctx->opt_stripe_kb * 1024 / std::max<int64_t>(row_bytes, 1)));
+    p.team = ctx->opt_team ? 4 : 1;
     return p;
 }
 
@@ -234,7 +245,7 @@ static saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_by
 {
     const WorkListParams p = work_list_params(ctx, row_bytes);
     if (p.min_edges == g->list_params.min_edges && p.cut_degree == g->list_params.cut_degree &&
-        p.stripe_rows == g->list_params.stripe_rows)
+        p.stripe_rows == g->list_params.stripe_rows && p.team == g->list_params.team)
         return SAGA_OK;
     std::vector<int32_t> h_row;
     WorkList wl;
@@ -260,6 +271,7 @@ static saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_by
         HIP_TRY(ctx, hipMemcpyAsync(g->d_heavy.p, wl.heavy.data(), sizeof(HeavyVertex) * wl.heavy.size(), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // wl goes out of scope below
     g->n_items = (int64_t)wl.items.size();
+    g->n_team = wl.n_team;
     g->n_heavy = (int64_t)wl.heavy.size();
     g->n_slots = wl.n_slots;
     g->list_params = p;
@@ -271,18 +283,20 @@ extern "C" {
 const char* saga_version(void) { return kVersion; }
 
 saga_status saga_plan_work_list(int64_t n, const int64_t* col_ptr, const int32_t* row_idx, int64_t min_edges,
-                                int64_t cut_degree, int64_t stripe_rows, int32_t* items_out, int64_t capacity,
-                                int64_t* n_items, int64_t* n_split_vertices, int64_t* n_slots)
+                                int64_t cut_degree, int64_t stripe_rows, int32_t team, int32_t* items_out, int64_t capacity,
+                                int64_t* n_items, int64_t* n_team_items, int64_t* n_split_vertices, int64_t* n_slots)
 {
-    if (n < 0 || !col_ptr || min_edges < 1 || cut_degree < 0 || stripe_rows < 0 || capacity < 0) return SAGA_ERR_INVALID_ARG;
+    if (n < 0 || !col_ptr || min_edges < 1 || cut_degree < 0 || stripe_rows < 0 || capacity < 0 || (team != 1 && team != 4))
+        return SAGA_ERR_INVALID_ARG;
     if (col_ptr[n] > 0 && !row_idx) return SAGA_ERR_INVALID_ARG;
     WorkList wl;
     try {
-        build_work_list(col_ptr, row_idx, n, WorkListParams{min_edges, cut_degree, stripe_rows, false}, &wl);
+        build_work_list(col_ptr, row_idx, n, WorkListParams{min_edges, cut_degree, stripe_rows, false, team}, &wl);
     } catch (...) {
         return SAGA_ERR_INTERNAL;
     }
     if (n_items) *n_items = (int64_t)wl.items.size();
+    if (n_team_items) *n_team_items = wl.n_team;
     if (n_split_vertices) *n_split_vertices = (int64_t)wl.heavy.size();
     if (n_slots) *n_slots = wl.n_slots;
     if (items_out) {
@@ -349,6 +363,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "stripe_kb")) {
         if (value < 0 || value > (1 << 22)) return ctx->fail(SAGA_ERR_INVALID_ARG, "stripe_kb must be in [0, 2^22]");
         ctx->opt_stripe_kb = value;
+    } else if (!strcmp(name, "team")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "team must be 0 or 1");
+        ctx->opt_team = (int)value;
     } else if (!strcmp(name, "xcd_remap")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "xcd_remap must be 0 or 1");
         ctx->opt_xcd_remap = (int)value;
@@ -583,6 +600,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     GatherArgs ga{};
     ga.items = static_cast<const WorkItem*>(g->d_items.p);
     ga.n_items = g->n_items;
+    ga.n_team = g->n_team;
     ga.row_idx = static_cast<const int32_t*>(g->d_row_idx.p);
     ga.F = Fm;
     ga.agg = agg;

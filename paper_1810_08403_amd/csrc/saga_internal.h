@@ -33,8 +33,9 @@ struct HeavyVertex {
 };
 
 struct WorkList {
-    std::vector<WorkItem> items;
+    std::vector<WorkItem> items;  // team items first (one workgroup each), then solo items (one wavefront each)
     std::vector<HeavyVertex> heavy;
+    int64_t n_team = 0;
     int64_t n_slots = 0;
     int64_t max_degree = 0;
 };
@@ -44,6 +45,7 @@ struct WorkListParams {
     int64_t cut_degree;   // columns with more in-edges than this are cut
     int64_t stripe_rows;  // pieces end on multiples of this many source rows (0: cut by count only)
     bool skip_empty = false;  // leave columns without edges out (streamed chunks: nothing to add)
+    int32_t team = 1;         // wavefronts that share one piece of a cut column (1 or 4)
 };
 // Build the work list of a CSC block whose arrays are on the host
 // (col_ptr[0] = 0; vertex ids and edge offsets are local to the block).
@@ -75,6 +77,7 @@ struct saga_ctx {
     int64_t opt_cut_degree = 0;    // 0 = 2 * split
     int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
     int opt_xcd_remap = 1;
+    int opt_team = 0;              // 1: a piece of a cut column is worked by a whole workgroup (measured slower)
     int opt_dst_intervals = 0, opt_src_intervals = 0;
 
     // reusable workspace (grown on demand, never shrunk until destroy)
@@ -112,8 +115,8 @@ struct saga_graph {
     // resident form; the work list is built at the first call for a given
     // (split, cut_degree, stripe_rows) and rebuilt when those change
     DevBuf d_row_idx, d_items, d_heavy, d_edge_data;
-    int64_t n_items = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
-    WorkListParams list_params{-1, -1, -1, false};
+    int64_t n_items = 0, n_team = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
+    WorkListParams list_params{-1, -1, -1, false, 1};
     // host form (streamed)
     std::vector<int64_t> h_col_ptr;
     std::vector<int32_t> h_row_idx;
@@ -135,6 +138,7 @@ struct saga_graph {
 struct GatherArgs {
     const WorkItem* items;
     int64_t n_items;
+    int64_t n_team;          // items [0, n_team) are processed by a whole workgroup each
     const int32_t* row_idx;  // source ids, local to the rows of `src`
     const float* edge_w;     // nullable (COPY)
     // LINEAR ops: src = X (dtype), ld_src elements between rows, F features.

@@ -1,5 +1,7 @@
 """Shared pieces of the GPU parity tests: run a workload through the C ABI and
 through the CPU oracle, and the comparison rules."""
+import contextlib
+
 import numpy as np
 import torch
 
@@ -94,3 +96,17 @@ def run_oracle(wl, agg="sum", with_vertex=True, bias=None, vlist=None, W=None, a
 def make_graph(ctx, g: si.CSC, device="cuda"):
     gd = g.to(device)
     return ctx.graph_create_csc(g.n, gd.col_ptr, gd.row_idx)
+
+
+@contextlib.contextmanager
+def new_context(budget=0, **options):
+    """A library context that is destroyed when the block ends, also when an assertion fails
+    (a context left to the interpreter's shutdown would call into a HIP runtime that is gone)."""
+    import paper_1810_08403_amd as saga
+    c = saga.Context(0, hbm_budget_bytes=budget)
+    try:
+        for k, v in options.items():
+            c.set_option(k, v)
+        yield c
+    finally:
+        c.destroy()

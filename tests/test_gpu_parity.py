@@ -4,7 +4,8 @@ import pytest
 import torch
 
 import saga_inputs as si
-from helpers import (TOL_BF16, TOL_F32, assert_bit_equal, assert_sum_close, make_graph, run_gpu, run_oracle)
+from helpers import (TOL_BF16, TOL_F32, assert_bit_equal, assert_sum_close, make_graph, new_context, run_gpu,
+                     run_oracle)
 
 pytestmark = pytest.mark.gpu
 
@@ -144,20 +145,17 @@ def test_runs_are_bitwise_reproducible(ctx):
 
 
 def test_split_threshold_and_xcd_remap_do_not_change_max(ctx):
-    import paper_1810_08403_amd as saga
     wl = si.workload(5, scale=11, edge_factor=32, f_in=32, f_out=8)
     ref = run_oracle(wl, agg="max", with_vertex=False)
     refs = run_oracle(wl, agg="sum", with_vertex=False)
-    for split, remap in ((64, 1), (300, 0), (1 << 20, 1)):
-        c = saga.Context(0)
-        c.set_option("split", split)
-        c.set_option("xcd_remap", remap)
-        graph = make_graph(c, wl.graph)
-        _, A = run_gpu(c, wl, graph, agg="max", with_vertex=False)
-        assert_bit_equal(A, ref["A"], f"split={split}")
-        _, A = run_gpu(c, wl, graph, agg="sum", with_vertex=False)
-        assert_sum_close(A, refs["A"], refs["A_abs"], TOL_F32, f"split={split}")
-        c.destroy()
+    for split, remap, team, stripe in ((64, 1, 1, 1024), (300, 0, 0, 0), (1 << 20, 1, 1, 64), (16, 1, 1, 16), (32, 0, 0, 256),
+                                       (16, 1, 0, 1024)):
+        with new_context(split=split, xcd_remap=remap, team=team, stripe_kb=stripe) as c:
+            graph = make_graph(c, wl.graph)
+            _, A = run_gpu(c, wl, graph, agg="max", with_vertex=False)
+            assert_bit_equal(A, ref["A"], f"split={split}")
+            _, A = run_gpu(c, wl, graph, agg="sum", with_vertex=False)
+            assert_sum_close(A, refs["A"], refs["A_abs"], TOL_F32, f"split={split}")
 
 
 def test_degenerate_graphs(ctx):
@@ -267,3 +265,34 @@ def test_spmm_microbenchmark_shapes(ctx, density):
     ref = run_oracle(wl, with_vertex=False)
     assert_sum_close(Y, ref["A"], ref["A_abs"], TOL_F32, f"SpMM density {density}")
     graph.destroy()
+
+
+@pytest.mark.parametrize("F,dtype", [(512, "bf16"), (64, "f32"), (500, "f32"), (1028, "f32"), (3, "f32"), (2056, "bf16")])
+def test_team_mode_matches_the_oracle(F, dtype):
+    """Option "team": pieces of cut columns worked by whole workgroups (LDS reduction)."""
+    wl = si.workload(5, scale=11, edge_factor=32, f_in=F, f_out=8)
+    wl.dtype = dtype
+    if dtype == "bf16":
+        wl.X, wl.W = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W)
+    with new_context(team=1, split=16, stripe_kb=16) as c:      # narrow bands, so that columns really are cut
+        graph = make_graph(c, wl.graph)
+        for agg in ("sum", "max"):
+            _, A = run_gpu(c, wl, graph, agg=agg)
+            ref = run_oracle(wl, agg=agg, with_vertex=False)
+            if agg == "max":
+                assert_bit_equal(A, ref["A"], f"team max F={F}")
+            else:
+                assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, f"team sum F={F}")
+        assert graph.info()["n_split_vertices"] > 0
+
+
+def test_team_mode_gated():
+    with new_context(team=1, split=16) as c:
+        for F in (128, 256, 20):
+            wl = si.workload(4, scale=11, edge_factor=48, f_in=F, f_out=8)
+            graph = make_graph(c, wl.graph)
+            Y, A = run_gpu(c, wl, graph)
+            ref = run_oracle(wl, hoisted=True)
+            assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, f"team gated F={F}")
+            assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"team gated layer F={F}")
+            graph.destroy()

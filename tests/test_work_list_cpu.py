@@ -13,11 +13,13 @@ def _plan(g, **kw):
     return items.numpy(), info
 
 
-@pytest.mark.parametrize("kw", [dict(min_edges=64, cut_degree=128, stripe_rows=256),
-                                dict(min_edges=16, cut_degree=16, stripe_rows=64),
-                                dict(min_edges=100, cut_degree=300, stripe_rows=0),
-                                dict(min_edges=256, cut_degree=512, stripe_rows=1024),
-                                dict(min_edges=64, cut_degree=1 << 30, stripe_rows=256)])
+@pytest.mark.parametrize("kw", [dict(min_edges=64, cut_degree=128, stripe_rows=256, team=1),
+                                dict(min_edges=16, cut_degree=16, stripe_rows=64, team=1),
+                                dict(min_edges=100, cut_degree=300, stripe_rows=0, team=1),
+                                dict(min_edges=64, cut_degree=128, stripe_rows=1024, team=4),
+                                dict(min_edges=16, cut_degree=32, stripe_rows=128, team=4),
+                                dict(min_edges=50, cut_degree=100, stripe_rows=0, team=4),
+                                dict(min_edges=64, cut_degree=1 << 30, stripe_rows=256, team=4)])
 def test_work_list_partitions_the_edges(kw):
     g = si.workload(3, scale=12, edge_factor=60).graph
     cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
@@ -29,12 +31,23 @@ def test_work_list_partitions_the_edges(kw):
     assert (np.cumsum(cover)[:-1] == 1).all()                  # each edge in exactly one item
     v, e0, e1, slot = items.T
     assert (e0 >= cp[v]).all() and (e1 <= cp[v + 1]).all() and (e0 <= e1).all()
+    nt = info["n_team_items"]
+    assert nt == (0 if kw["team"] == 1 else nt) and (kw["team"] == 4 or nt == 0)
+    is_team = np.arange(len(items)) < nt
     whole = slot < 0
     assert (e0[whole] == cp[v[whole]]).all() and (e1[whole] == cp[v[whole] + 1]).all()
-    # a column above cut_degree stays whole only if cutting it would give a single piece
-    one_piece = kw["min_edges"] + kw["stripe_rows"] + kw["min_edges"] // 2
-    assert ((e1 - e0)[whole] <= max(kw["cut_degree"], one_piece)).all()
-    assert set(v[whole]).isdisjoint(set(v[~whole])) and len(set(v)) == g.n   # every vertex has an item
+    assert len(set(v)) == g.n                                   # every vertex has an item
+    assert set(v[whole]).isdisjoint(set(v[~whole]))
+    # solo items are whole columns at or below cut_degree (or, without teams, columns that gave one piece)
+    min_piece = kw["min_edges"] * kw["team"]
+    one_piece = min_piece + kw["stripe_rows"] + min_piece // 2
+    solo = ~is_team
+    if kw["team"] == 4:
+        assert whole[solo].all() and ((e1 - e0)[solo] <= kw["cut_degree"]).all()
+        assert ((e1 - e0)[is_team] > 0).all()
+        assert ((cp[v[is_team] + 1] - cp[v[is_team]]) > kw["cut_degree"]).all()    # teams only work cut columns
+    else:
+        assert ((e1 - e0)[whole] <= max(kw["cut_degree"], one_piece)).all()
     # slots: 0..n_slots-1, each once; per vertex contiguous and in edge order
     s = slot[~whole]
     assert sorted(s.tolist()) == list(range(info["n_slots"]))
@@ -46,23 +59,31 @@ def test_work_list_partitions_the_edges(kw):
     assert info["n_split_vertices"] == len(set(vs.tolist()))
     # piece sizes and stripe alignment
     ln = (e1 - e0)[~whole]
-    R, m = kw["stripe_rows"], kw["min_edges"]
+    R = kw["stripe_rows"]
     last = e1[~whole] == cp[v[~whole] + 1]
-    assert (ln[~last] >= m).all()
+    assert (ln[~last] >= min_piece).all()
     if R > 0:
-        assert (ln <= m + R + m // 2).all()
+        assert (ln <= min_piece + R + min_piece // 2).all()
         inner_end = e1[~whole][~last]
         assert (ri[inner_end] // R > ri[inner_end - 1] // R).all()     # a cut sits on a stripe boundary
-        first_stripe = ri[e0[~whole]] // R
+        pieces = is_team if kw["team"] == 4 else ~whole
+        first_stripe = ri[e0[pieces]] // R
         assert (np.diff(first_stripe) >= 0).all()                       # pieces come stripe by stripe
-    assert whole[np.argmax(whole):].all()                               # whole columns follow the pieces
+    if kw["team"] == 1:
+        assert whole[np.argmax(whole):].all()                           # whole columns follow the pieces
 
 
 def test_work_list_of_degenerate_graphs():
     g = si.csc_from_lists(5, [])
     items, info = _plan(g)
-    assert info == {"n_items": 5, "n_split_vertices": 0, "n_slots": 0} and (items[:, 3] == -1).all()
+    assert info == {"n_items": 5, "n_team_items": 0, "n_split_vertices": 0, "n_slots": 0} and (items[:, 3] == -1).all()
     g = si.csc_from_lists(3000, [(u, 7) for u in range(3000)])
-    items, info = _plan(g, min_edges=100, cut_degree=200, stripe_rows=128)
-    assert info["n_split_vertices"] == 1 and info["n_slots"] == info["n_items"] - 2999
-    assert (items[items[:, 3] >= 0][:, 0] == 7).all()
+    for team in (1, 4):
+        items, info = _plan(g, min_edges=100, cut_degree=200, stripe_rows=128, team=team)
+        assert info["n_split_vertices"] == 1 and info["n_slots"] == info["n_items"] - 2999
+        assert (items[items[:, 3] >= 0][:, 0] == 7).all()
+        assert info["n_team_items"] == (info["n_slots"] if team == 4 else 0)
+    # a column just above cut_degree is one team item that writes its row directly
+    g = si.csc_from_lists(400, [(u, 3) for u in range(300)])
+    items, info = _plan(g, min_edges=64, cut_degree=128, stripe_rows=1024, team=4)
+    assert info["n_team_items"] == 1 and info["n_slots"] == 0 and items[0].tolist() == [3, 0, 300, -1]
