@@ -244,9 +244,35 @@ WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes)
 static saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
 {
     const WorkListParams p = work_list_params(ctx, row_bytes);
-    if (p.min_edges == g->list_params.min_edges && p.cut_degree == g->list_params.cut_degree &&
-        p.stripe_rows == g->list_params.stripe_rows && p.team == g->list_params.team)
+    auto same = [](const WorkListParams& a, const WorkListParams& b) {
+        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team;
+    };
+    if (same(p, g->list_params)) return SAGA_OK;
+    // park the current list, then look for one built earlier with these parameters
+    if (g->list_params.min_edges >= 0) {
+        if (g->saved_lists.size() >= 8) {
+            ctx->dev_free(&g->saved_lists.front().items);
+            ctx->dev_free(&g->saved_lists.front().heavy);
+            g->saved_lists.erase(g->saved_lists.begin());
+        }
+        g->saved_lists.push_back(saga_graph::SavedList{g->list_params, g->d_items, g->d_heavy, g->n_items, g->n_team, g->n_heavy, g->n_slots});
+        g->d_items = DevBuf{};
+        g->d_heavy = DevBuf{};
+        g->list_params = WorkListParams{-1, -1, -1, false, 1};
+    }
+    for (size_t i = 0; i < g->saved_lists.size(); ++i) {
+        if (!same(p, g->saved_lists[i].params)) continue;
+        const saga_graph::SavedList sl = g->saved_lists[i];
+        g->saved_lists.erase(g->saved_lists.begin() + (long)i);
+        g->d_items = sl.items;
+        g->d_heavy = sl.heavy;
+        g->n_items = sl.n_items;
+        g->n_team = sl.n_team;
+        g->n_heavy = sl.n_heavy;
+        g->n_slots = sl.n_slots;
+        g->list_params = sl.params;
         return SAGA_OK;
+    }
     std::vector<int32_t> h_row;
     WorkList wl;
     try {
@@ -523,6 +549,10 @@ saga_status saga_graph_destroy(saga_graph* g)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&g->d_row_idx, &g->d_items, &g->d_heavy, &g->d_edge_data}) ctx->dev_free(b);
+    for (auto& sl : g->saved_lists) {
+        ctx->dev_free(&sl.items);
+        ctx->dev_free(&sl.heavy);
+    }
     if (g->grid) chunk_grid_destroy(ctx, g->grid);
     delete g;
     return SAGA_OK;

@@ -117,6 +117,13 @@ struct saga_graph {
     DevBuf d_row_idx, d_items, d_heavy, d_edge_data;
     int64_t n_items = 0, n_team = 0, n_heavy = 0, n_slots = 0, max_degree = 0;
     WorkListParams list_params{-1, -1, -1, false, 1};
+    // work lists built earlier for other row widths (layers of different width alternate between them)
+    struct SavedList {
+        WorkListParams params;
+        DevBuf items, heavy;
+        int64_t n_items, n_team, n_heavy, n_slots;
+    };
+    std::vector<SavedList> saved_lists;
     // host form (streamed)
     std::vector<int64_t> h_col_ptr;
     std::vector<int32_t> h_row_idx;
