@@ -67,6 +67,11 @@ def main():
     ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--team", type=int, default=None)
+    ap.add_argument("--budget-gib", type=float, default=16.0, help="config5 only: device-memory budget")
+    ap.add_argument("--dst-intervals", type=int, default=None, help="config5 only: force the plan")
+    ap.add_argument("--src-intervals", type=int, default=None)
+    ap.add_argument("--schedule", type=int, default=None, help="config5 only: 0 paper, 1 stage by stage, 2 destination order")
+    ap.add_argument("--overlap", type=int, default=None, help="config5 only: 0 = streaming off")
     ap.add_argument("--hip-graph", action="store_true",
                     help="time replays of the layer recorded into a HIP graph (small, launch-bound workloads)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -266,8 +271,13 @@ def bench_streamed(args):
     del wl, g
     torch.cuda.empty_cache()
     t_gen = time.time() - t0
-    budget = 16 << 30
+    budget = int(args.budget_gib * (1 << 30))
     ctx = saga.Context(0, hbm_budget_bytes=budget)
+    for name, val in (("schedule", args.schedule), ("overlap", args.overlap), ("split", args.split),
+                      ("stripe_kb", args.stripe_kb), ("dst_intervals", args.dst_intervals),
+                      ("src_intervals", args.src_intervals)):
+        if val is not None:
+            ctx.set_option(name, val)
     t0 = time.time()
     graph = ctx.graph_create_csc(n, hg.col_ptr, hg.row_idx)
     graph.set_edge_data(w)
@@ -294,7 +304,8 @@ def bench_streamed(args):
            "config": {"workload": "config5_rmat23_gcn_f32_streamed", "n_vertices": n, "nnz": nnz, "f_in": X.shape[1],
                       "f_out": W.shape[1], "agg": args.agg, "device_budget_bytes": budget,
                       "plan": [tm["plan_dst_intervals"], tm["plan_src_intervals"]],
-                      "peak_device_bytes": ctx.peak_device_bytes(), "inputs": "pinned host memory, transfers timed"},
+                      "peak_device_bytes": ctx.peak_device_bytes(), "inputs": "pinned host memory, transfers timed",
+                      "schedule": args.schedule or 0, "overlap": 1 if args.overlap is None else args.overlap},
            "roofline": {"bound": "host_link", "achieved": round(link, 2), "peak": 128.0, "unit": "GB/s",
                         "frac": round(link / 128.0, 4), "traffic": None,
                         "note": "H2D + D2H bytes per second against 2 x 64 GB/s (PCIe Gen5 x16, both directions)",

@@ -196,6 +196,14 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                fewer partial rows, but measured slower than one wavefront per piece)
  *   "xcd_remap"  0/1, keep neighbouring work items on one XCD (default 1)
  *   "dst_intervals" / "src_intervals"  streamed plan override, 0 = automatic
+ *   "schedule"   streamed calls: 0 = the paper's schedule (Section 3.1: an accumulator chunk
+ *                stays on the device until its ApplyVertex has consumed it); the two baselines
+ *                the paper measures against (Section 6.2): 1 = stage by stage (all Gather
+ *                first, accumulators swapped out to the host and back for ApplyVertex),
+ *                2 = destination order innermost (a source chunk stays, accumulators are
+ *                swapped in and out around every edge chunk)
+ *   "overlap"    streamed calls: 1 = copies on their own streams, overlapping the kernels
+ *                (default); 0 = everything on one stream (streaming off)
  * Returns INVALID_ARG for unknown names or values. */
 saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value);
 

@@ -44,7 +44,9 @@ struct ChunkGrid {
     hipStream_t s_in = nullptr, s_out = nullptr;
     hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
-    hipEvent_t ev_a_done = nullptr;
+    hipEvent_t ev_a_done = nullptr, ev_a_ready = nullptr, ev_a_in = nullptr;
+    float* a_host = nullptr;  // pinned home of the accumulators for the swapping baselines
+    size_t a_host_bytes = 0;
 };
 
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
@@ -55,8 +57,9 @@ void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
     for (DevBuf* b : {&g->A, &g->V[0], &g->V[1], &g->C[0], &g->C[1], &g->Ystage[0], &g->Ystage[1], &g->partials})
         ctx->dev_free(b);
     for (hipEvent_t e : {g->ev_ready[0], g->ev_ready[1], g->ev_free[0], g->ev_free[1], g->ev_y_ready[0], g->ev_y_ready[1],
-                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done})
+                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done, g->ev_a_ready, g->ev_a_in})
         if (e) (void)hipEventDestroy(e);
+    if (g->a_host) (void)hipHostFree(g->a_host);
     if (g->s_in) (void)hipStreamDestroy(g->s_in);
     if (g->s_out) (void)hipStreamDestroy(g->s_out);
     delete g;
@@ -195,7 +198,8 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
     HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_in, hipStreamNonBlocking));
     HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_out, hipStreamNonBlocking));
     for (hipEvent_t* e : {&grid->ev_ready[0], &grid->ev_ready[1], &grid->ev_free[0], &grid->ev_free[1], &grid->ev_y_ready[0],
-                          &grid->ev_y_ready[1], &grid->ev_y_free[0], &grid->ev_y_free[1], &grid->ev_a_done})
+                          &grid->ev_y_ready[1], &grid->ev_y_free[0], &grid->ev_y_free[1], &grid->ev_a_done, &grid->ev_a_ready,
+                          &grid->ev_a_in})
         HIP_TRY(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
     return SAGA_OK;
 }
@@ -332,12 +336,25 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         return ctx->fail(SAGA_ERR_BUDGET, "plan %d x %d needs %zu bytes of device memory, budget is %zu", Q, P, ctx->cur_bytes,
                          ctx->budget);
 
-    hipStream_t sc = ctx->stream, sin = grid->s_in, sout = grid->s_out;
+    // "overlap" 0 puts every copy on the compute stream: nothing overlaps (the streaming-off baseline)
+    hipStream_t sc = ctx->stream;
+    hipStream_t sin = ctx->opt_overlap ? grid->s_in : sc, sout = ctx->opt_overlap ? grid->s_out : sc;
+    const int schedule = has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0;
     const float* Xh = static_cast<const float*>(X->data);
     float* Yh = static_cast<float*>(Y->data);
+    float* A = static_cast<float*>(grid->A.p);
     int64_t bytes_h2d = 0, bytes_d2h = 0;
     int64_t step = 0, ystep = 0;
     bool used[2] = {false, false}, yused[2] = {false, false};
+    bool a_busy = false;  // ev_a_done guards the accumulator buffer
+
+    if (schedule != 0 && grid->a_host_bytes < (size_t)n * F * 4) {  // host home of the swapped accumulators
+        if (grid->a_host) (void)hipHostFree(grid->a_host);
+        grid->a_host = nullptr;
+        grid->a_host_bytes = 0;
+        HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&grid->a_host), (size_t)n * F * 4, hipHostMallocDefault));
+        grid->a_host_bytes = (size_t)n * F * 4;
+    }
 
     // pack W^T once (on the compute stream)
     int64_t n_pad = 0, k_pad = 0;
@@ -349,74 +366,82 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                                               sc));
     }
 
-    for (int j = 0; j < Q; ++j) {
-        const int64_t v0 = (int64_t)j * Dq, rows = std::min(n, v0 + Dq) - v0;
-        if (rows <= 0) break;
-        float* A = static_cast<float*>(grid->A.p);
-        // A_j <- identity of the accumulator (after the previous interval's readers are done)
-        if (j > 0) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
-        HIP_TRY(ctx, launch_fill_f32(A, rows * F, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
-        for (int i = 0; i < P; ++i) {
-            const ChunkMeta& m = grid->chunks[(size_t)j * P + i];
-            if (m.nnz == 0) continue;  // nothing to add from this source interval
-            const int b = (int)(step & 1);
-            const int64_t s0 = (int64_t)i * Sp, srows = std::min(n, s0 + Sp) - s0;
-            // copy stream: wait until the kernels that last read this buffer pair are done
-            if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(grid->V[b].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
+    auto rows_of = [&](int j) { return std::min(n, ((int64_t)j + 1) * Dq) - (int64_t)j * Dq; };
+
+    // A_j <- identity of the accumulator, once nobody reads the buffer any more
+    auto fill_a = [&](int j) -> saga_status {
+        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
+        HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * F, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
+        return SAGA_OK;
+    };
+    // stream V_i (unless it already sits in V[vbuf]) and C_ij in, then add the chunk into A_j
+    auto load_and_gather = [&](int i, int j, int vbuf, bool load_v) -> saga_status {
+        const ChunkMeta& m = grid->chunks[(size_t)j * P + i];
+        const int b = (int)(step & 1);
+        const int vb = vbuf >= 0 ? vbuf : b;
+        const int64_t s0 = (int64_t)i * Sp, srows = std::min(n, s0 + Sp) - s0;
+        // copy stream: wait until the kernels that last read this buffer pair are done
+        if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
+        if (load_v) {
+            if (vb != b && used[vb]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[vb], 0));
+            HIP_TRY(ctx, hipMemcpy2DAsync(grid->V[vb].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
                                           (size_t)srows, hipMemcpyHostToDevice, sin));
-            HIP_TRY(ctx, hipMemcpyAsync(grid->C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
-            HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
-            bytes_h2d += srows * F * 4 + (int64_t)m.bytes;
-            // compute stream
-            HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_ready[b], 0));
-            const char* cb = static_cast<const char*>(grid->C[b].p);
-            GatherArgs ga{};
-            ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
-            ga.n_items = m.n_items;
-            ga.n_team = m.n_team;
-            ga.row_idx = reinterpret_cast<const int32_t*>(cb + m.off_ridx);
-            ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
-            ga.src = grid->V[b].p;
-            ga.ld_src = F;
-            ga.F = (int32_t)F;
-            ga.dtype = SAGA_F32;
-            ga.op = ep->op;
-            ga.agg = agg;
-            ga.out = A;
-            ga.ld_out = F;
-            ga.partials = static_cast<float*>(grid->partials.p);
-            ga.accumulate = 1;
-            ga.xcd_remap = ctx->opt_xcd_remap;
-            HIP_TRY(ctx, launch_gather(ga, sc));
-            if (m.n_heavy > 0) {
-                CombineArgs ca{};
-                ca.heavy = reinterpret_cast<const HeavyVertex*>(cb + m.off_heavy);
-                ca.n_heavy = m.n_heavy;
-                ca.partials = ga.partials;
-                ca.F = (int32_t)F;
-                ca.agg = agg;
-                ca.out = A;
-                ca.ld_out = F;
-                ca.accumulate = 1;
-                HIP_TRY(ctx, launch_combine(ca, sc));
-            }
-            HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sc));
-            used[b] = true;
-            ++step;
+            bytes_h2d += srows * F * 4;
         }
+        HIP_TRY(ctx, hipMemcpyAsync(grid->C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
+        HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
+        bytes_h2d += (int64_t)m.bytes;
+        HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_ready[b], 0));
+        const char* cb = static_cast<const char*>(grid->C[b].p);
+        GatherArgs ga{};
+        ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
+        ga.n_items = m.n_items;
+        ga.n_team = m.n_team;
+        ga.row_idx = reinterpret_cast<const int32_t*>(cb + m.off_ridx);
+        ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
+        ga.src = grid->V[vb].p;
+        ga.ld_src = F;
+        ga.F = (int32_t)F;
+        ga.dtype = SAGA_F32;
+        ga.op = ep->op;
+        ga.agg = agg;
+        ga.out = A;
+        ga.ld_out = F;
+        ga.partials = static_cast<float*>(grid->partials.p);
+        ga.accumulate = 1;
+        ga.xcd_remap = ctx->opt_xcd_remap;
+        HIP_TRY(ctx, launch_gather(ga, sc));
+        if (m.n_heavy > 0) {
+            CombineArgs ca{};
+            ca.heavy = reinterpret_cast<const HeavyVertex*>(cb + m.off_heavy);
+            ca.n_heavy = m.n_heavy;
+            ca.partials = ga.partials;
+            ca.F = (int32_t)F;
+            ca.agg = agg;
+            ca.out = A;
+            ca.ld_out = F;
+            ca.accumulate = 1;
+            HIP_TRY(ctx, launch_combine(ca, sc));
+        }
+        HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sc));
+        used[b] = true;
+        ++step;
+        return SAGA_OK;
+    };
+    // ApplyVertex on the resident A_j (or A_j itself when there is none) and its way back to the host
+    auto apply_and_drain = [&](int j) -> saga_status {
+        const int64_t v0 = (int64_t)j * Dq, rows = rows_of(j);
         if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * F, sc));
         if (!has_w) {
-            // Y_j = A_j straight to the host
-            HIP_TRY(ctx, hipEventRecord(grid->ev_y_ready[0], sc));
-            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_y_ready[0], 0));
+            HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
             HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)F * 4, (size_t)F * 4, (size_t)rows,
                                           hipMemcpyDeviceToHost, sout));
             bytes_d2h += rows * F * 4;
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
-            continue;
+            a_busy = true;
+            return SAGA_OK;
         }
-        // ApplyVertex while A_j is resident, tile by tile into a staging pair that drains to the host
         for (int64_t r0 = 0; r0 < rows; r0 += y_tile_rows) {
             const int64_t tr = std::min(y_tile_rows, rows - r0);
             const int b = (int)(ystep & 1);
@@ -445,7 +470,75 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ++ystep;
         }
         HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
+        a_busy = true;
+        return SAGA_OK;
+    };
+    // the baselines swap the accumulator of interval j between the device and its host home
+    auto swap_out = [&](int j) -> saga_status {
+        HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
+        HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
+        HIP_TRY(ctx, hipMemcpyAsync(grid->a_host + (int64_t)j * Dq * F, A, (size_t)rows_of(j) * F * 4, hipMemcpyDeviceToHost, sout));
+        HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
+        a_busy = true;
+        bytes_d2h += rows_of(j) * F * 4;
+        return SAGA_OK;
+    };
+    auto swap_in = [&](int j) -> saga_status {
+        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_a_done, 0));
+        HIP_TRY(ctx, hipMemcpyAsync(A, grid->a_host + (int64_t)j * Dq * F, (size_t)rows_of(j) * F * 4, hipMemcpyHostToDevice, sin));
+        HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
+        HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
+        bytes_h2d += rows_of(j) * F * 4;
+        return SAGA_OK;
+    };
+    auto has_edges = [&](int i, int j) { return grid->chunks[(size_t)j * P + i].nnz > 0; };
+#define SAGA_STEP(call)                       \
+    do {                                      \
+        if (saga_status st__ = (call)) return st__; \
+    } while (0)
+
+    if (schedule == 0) {
+        // the paper's schedule: A_j stays resident until its ApplyVertex has consumed it
+        for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+            SAGA_STEP(fill_a(j));
+            for (int i = 0; i < P; ++i)
+                if (has_edges(i, j)) SAGA_STEP(load_and_gather(i, j, -1, true));
+            SAGA_STEP(apply_and_drain(j));
+        }
+    } else if (schedule == 1) {
+        // stage by stage: the whole Gather stage first (accumulators swapped out), then ApplyVertex
+        for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+            SAGA_STEP(fill_a(j));
+            for (int i = 0; i < P; ++i)
+                if (has_edges(i, j)) SAGA_STEP(load_and_gather(i, j, -1, true));
+            SAGA_STEP(swap_out(j));
+        }
+        for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+            SAGA_STEP(swap_in(j));
+            SAGA_STEP(apply_and_drain(j));
+        }
+    } else {
+        // destination order innermost: a source interval stays, the accumulators are swapped per chunk
+        for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+            SAGA_STEP(fill_a(j));
+            SAGA_STEP(swap_out(j));
+        }
+        for (int i = 0; i < P; ++i) {
+            bool first = true;
+            for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+                if (!has_edges(i, j)) continue;
+                SAGA_STEP(swap_in(j));
+                SAGA_STEP(load_and_gather(i, j, i & 1, first));
+                first = false;
+                SAGA_STEP(swap_out(j));
+            }
+        }
+        for (int j = 0; j < Q && rows_of(j) > 0; ++j) {
+            SAGA_STEP(swap_in(j));
+            SAGA_STEP(apply_and_drain(j));
+        }
     }
+#undef SAGA_STEP
     HIP_TRY(ctx, hipStreamSynchronize(sin));
     HIP_TRY(ctx, hipStreamSynchronize(sc));
     HIP_TRY(ctx, hipStreamSynchronize(sout));

@@ -398,6 +398,12 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "dst_intervals")) {
         if (value < 0 || value > 4096) return ctx->fail(SAGA_ERR_INVALID_ARG, "dst_intervals must be in [0, 4096]");
         ctx->opt_dst_intervals = (int)value;
+    } else if (!strcmp(name, "schedule")) {
+        if (value < 0 || value > 2) return ctx->fail(SAGA_ERR_INVALID_ARG, "schedule must be 0, 1 or 2");
+        ctx->opt_schedule = (int)value;
+    } else if (!strcmp(name, "overlap")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "overlap must be 0 or 1");
+        ctx->opt_overlap = (int)value;
     } else if (!strcmp(name, "src_intervals")) {
         if (value < 0 || value > 4096) return ctx->fail(SAGA_ERR_INVALID_ARG, "src_intervals must be in [0, 4096]");
         ctx->opt_src_intervals = (int)value;

@@ -79,6 +79,8 @@ struct saga_ctx {
     int opt_xcd_remap = 1;
     int opt_team = 0;              // 1: a piece of a cut column is worked by a whole workgroup (measured slower)
     int opt_dst_intervals = 0, opt_src_intervals = 0;
+    int opt_schedule = 0;  // streamed path: 0 the paper's schedule, 1 stage by stage, 2 destination order innermost
+    int opt_overlap = 1;   // streamed path: copies on their own streams
 
     // reusable workspace (grown on demand, never shrunk until destroy)
     DevBuf ws_accum;     // Gather output A (fp32 or bf16) when the caller gives no accum_out

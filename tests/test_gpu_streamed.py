@@ -115,3 +115,28 @@ def test_streamed_needs_attached_edge_data_and_rejects_mixed_placement(wl):
         ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, bad)
     assert e.value.status == 2
     ctx.destroy()
+
+
+@pytest.mark.parametrize("schedule,overlap", [(0, 0), (1, 1), (1, 0), (2, 1), (2, 0)])
+def test_baseline_schedules_give_the_same_result(wl, schedule, overlap):
+    """Stage-by-stage and destination-order schedules and streaming off (the baselines of the
+    paper's Section 6.2) move data differently but must compute the same layer."""
+    from helpers import new_context
+    with new_context(dst_intervals=3, src_intervals=4, schedule=schedule, overlap=overlap) as ctx:
+        graph = ctx.graph_create_csc(wl.graph.n, wl.graph.col_ptr, wl.graph.row_idx)
+        graph.set_edge_data(wl.edge_weight)
+        ref_max = run_oracle(wl, agg="max", with_vertex=False)
+        A = _streamed(ctx, wl, graph, "max", with_vertex=False)
+        assert_bit_equal(A, ref_max["A"], f"max Gather, schedule {schedule}")
+        ref = run_oracle(wl, agg="sum")
+        Y = _streamed(ctx, wl, graph, "sum")
+        assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"sum layer, schedule {schedule}")
+        refm = run_oracle(wl, agg="max")
+        Y = _streamed(ctx, wl, graph, "max")
+        assert_sum_close(Y, refm["Y"], refm["Y_abs"], TOL_F32, f"max layer, schedule {schedule}")
+        t = ctx.get_timings()
+        x_bytes = wl.X.numel() * 4
+        if schedule == 0:
+            assert t["bytes_h2d"] < 3 * 3 * x_bytes + 3 * 2 ** 26        # X three times per call + chunks
+        if schedule == 2:
+            assert t["bytes_d2h"] > 3 * x_bytes                            # accumulators swapped per chunk
