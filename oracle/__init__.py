@@ -43,6 +43,14 @@ class _Args(ctypes.Structure):
                 ("vlist", _P), ("nv", _I64), ("A", _P), ("A_abs", _P), ("Y", _P), ("Y_abs", _P)]
 
 
+class _BwdArgs(ctypes.Structure):
+    """Mirror of saga_oracle_bwd_args in saga_oracle.c."""
+    _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
+                ("edge_op", _I32), ("act", _I32), ("edge_w", _P), ("A", _P),
+                ("W", _P), ("bias", _P), ("W_self", _P), ("F_out", _I64), ("dY", _P),
+                ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dW_self", _P), ("dbias", _P), ("dA", _P)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -56,6 +64,8 @@ def lib():
         L.saga_oracle_hoist_pool.argtypes = [_I64, _P, _I64, _P, _P, _I64, _P, _P]
         L.saga_oracle_layer.restype = ctypes.c_int
         L.saga_oracle_layer.argtypes = [ctypes.POINTER(_Args)]
+        L.saga_oracle_layer_backward.restype = ctypes.c_int
+        L.saga_oracle_layer_backward.argtypes = [ctypes.POINTER(_BwdArgs)]
         _lib = L
     return _lib
 
@@ -171,4 +181,32 @@ def layer(col_ptr, row_idx, X, edge_op="copy", edge_weight=None, W_gate=None, b_
     rc = lib().saga_oracle_layer(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_layer rejected its arguments")
+    return out
+
+
+def layer_backward(col_ptr, row_idx, X, A, dY, W, edge_op="copy", edge_weight=None, bias=None, W_self=None, act="none"):
+    """Gradients of one sum-accumulator layer with a linear ApplyEdge (Section 2.2's backward stages).
+
+    A is the forward Gather output (fp64, from layer()); dY the gradient of the layer's output.
+    Returns fp64 arrays: dX, dX_abs, dW, dW_abs, dbias, dA, and dW_self when W_self is given.
+    """
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    X, Wv, dYv = _f32(X), _f32(W), _f32(dY)
+    A = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
+    n, F = X.shape
+    F_out = Wv.shape[1]
+    assert A.shape == (n, F) and Wv.shape == (F, F_out) and dYv.shape == (n, F_out)
+    w, bv, Ws = _f32(edge_weight), _f32(bias), _f32(W_self)
+    out = {"dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((F, F_out)), "dW_abs": np.empty((F, F_out)),
+           "dbias": np.empty(F_out), "dA": np.empty((n, F))}
+    if Ws is not None:
+        assert Ws.shape == (F, F_out)
+        out["dW_self"] = np.empty((F, F_out))
+    a = _BwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(A),
+                 _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]),
+                 _ptr(out["dW_abs"]), _ptr(out.get("dW_self")), _ptr(out["dbias"]), _ptr(out["dA"]))
+    rc = lib().saga_oracle_layer_backward(ctypes.byref(a))
+    if rc != 0:
+        raise ValueError("saga_oracle_layer_backward rejected its arguments")
     return out

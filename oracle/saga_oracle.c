@@ -328,3 +328,130 @@ int saga_oracle_layer(const saga_oracle_args* p)
     }
     return bad;
 }
+
+/*
+ * Backward pass of one layer with the sum accumulator and a linear ApplyEdge
+ * (EDGE_COPY or EDGE_MUL_WEIGHT), following the reverse stage order of
+ * Section 2.2: backward-ApplyVertex (parameter gradients, gradient of accum and
+ * the vertex's own partial gradient), backward-Gather (sum: every in-edge of v
+ * receives the gradient of accum[v]), backward-ApplyEdge (times the edge
+ * weight), backward-Scatter (every vertex adds up the partial gradients that
+ * arrive over its out-edges and its own).
+ *
+ *   Z = A W + X W_self + bias,  Y = act(Z),  act in {none, ReLU}
+ *   dZ = dY (.) act'(Z)                 (ReLU: 1 where Z > 0)
+ *   dW = A^T dZ,  dW_self = X^T dZ,  dbias = sum_v dZ[v]
+ *   dA = dZ W^T
+ *   dX[u] = sum_{e: u -> v} w_e dA[v]  +  dZ[u] W_self^T
+ *
+ * A (n x F, fp64) is the Gather output of the forward oracle; everything is
+ * accumulated in fp64. Outputs may be NULL except where marked. The *_abs
+ * outputs hold the same sums with every term replaced by its absolute value.
+ */
+typedef struct saga_oracle_bwd_args {
+    int64_t n;
+    const int64_t* col_ptr;
+    const int32_t* row_idx;
+    const float* X;      /* n x F, needed for dW_self only */
+    int64_t F;
+    int32_t edge_op, act;
+    const float* edge_w;
+    const double* A;     /* n x F */
+    const float *W, *bias, *W_self;
+    int64_t F_out;
+    const float* dY;     /* n x F_out */
+    double *dX, *dX_abs; /* n x F */
+    double *dW, *dW_abs; /* F x F_out */
+    double *dW_self;     /* F x F_out */
+    double *dbias;       /* F_out */
+    double *dA;          /* n x F, nullable: gradient of the Gather output */
+} saga_oracle_bwd_args;
+
+int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
+{
+    if (!p || !p->col_ptr || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (p->edge_op != EDGE_COPY && p->edge_op != EDGE_MUL_WEIGHT) return 1;
+    if (p->edge_op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if ((p->W_self || p->dW_self) && !p->X) return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out;
+    double* dZ = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)Fo);
+    double* dA = (double*)calloc((size_t)(n > 0 ? n : 1) * (size_t)F, sizeof(double));
+    double* dAa = (double*)calloc((size_t)(n > 0 ? n : 1) * (size_t)F, sizeof(double));
+    if (!dZ || !dA || !dAa) { free(dZ); free(dA); free(dAa); return 2; }
+
+    /* backward-ApplyVertex, per vertex: recompute Z for the activation's derivative */
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t o = 0; o < Fo; ++o) {
+            double z = p->bias ? (double)p->bias[o] : 0.0;
+            for (int64_t f = 0; f < F; ++f) z += p->A[v * F + f] * (double)p->W[f * Fo + o];
+            if (p->W_self)
+                for (int64_t k = 0; k < F; ++k) z += (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
+            const double g = (double)p->dY[v * Fo + o];
+            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+        }
+        for (int64_t f = 0; f < F; ++f) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t o = 0; o < Fo; ++o) {
+                const double t = dZ[v * Fo + o] * (double)p->W[f * Fo + o];
+                s += t;
+                sa += fabs(t);
+            }
+            dA[v * F + f] = s;
+            dAa[v * F + f] = sa;
+        }
+    }
+    /* parameter gradients: one (f, o) entry per iteration, a sum over all vertices */
+#pragma omp parallel for schedule(static)
+    for (int64_t fo = 0; fo < F * Fo; ++fo) {
+        const int64_t f = fo / Fo, o = fo % Fo;
+        double s = 0.0, sa = 0.0, ss = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            const double t = p->A[v * F + f] * dZ[v * Fo + o];
+            s += t;
+            sa += fabs(t);
+            if (p->dW_self) ss += (double)p->X[v * F + f] * dZ[v * Fo + o];
+        }
+        if (p->dW) p->dW[fo] = s;
+        if (p->dW_abs) p->dW_abs[fo] = sa;
+        if (p->dW_self) p->dW_self[fo] = ss;
+    }
+    if (p->dbias)
+        for (int64_t o = 0; o < Fo; ++o) {
+            double s = 0.0;
+            for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+            p->dbias[o] = s;
+        }
+    if (p->dA) memcpy(p->dA, dA, sizeof(double) * (size_t)n * (size_t)F);
+
+    /* backward-Gather, backward-ApplyEdge, backward-Scatter: feature slices in parallel,
+     * the edge list walked in order inside each slice (no two threads touch one entry) */
+    if (p->dX) {
+#pragma omp parallel for schedule(static)
+        for (int64_t f = 0; f < F; ++f) {
+            for (int64_t u = 0; u < n; ++u) {
+                double s = 0.0, sa = 0.0;
+                if (p->W_self)
+                    for (int64_t o = 0; o < Fo; ++o) {
+                        const double t = dZ[u * Fo + o] * (double)p->W_self[f * Fo + o];
+                        s += t;
+                        sa += fabs(t);
+                    }
+                p->dX[u * F + f] = s;
+                if (p->dX_abs) p->dX_abs[u * F + f] = sa;
+            }
+            for (int64_t v = 0; v < n; ++v)
+                for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                    const int64_t u = p->row_idx[e];
+                    const double w = p->edge_op == EDGE_MUL_WEIGHT ? (double)p->edge_w[e] : 1.0;
+                    p->dX[u * F + f] += w * dA[v * F + f];
+                    if (p->dX_abs) p->dX_abs[u * F + f] += fabs(w) * dAa[v * F + f];
+                }
+        }
+    }
+    free(dZ);
+    free(dA);
+    free(dAa);
+    return 0;
+}

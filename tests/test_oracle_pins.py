@@ -441,3 +441,85 @@ def test_sigmoid_activation_in_apply_vertex():
     X = np.array([[0.0], [np.log(3.0)], [-np.log(3.0)], [40.0]], np.float32)
     o = oracle.layer(*_np(g), X, "copy", W=np.array([[1.0]], np.float32), act="sigmoid")
     assert np.allclose(o["Y"][:, 0], [0.5, 0.75, 0.25, 1.0], rtol=1e-7)
+
+
+# --------------------------------------------------------------------------
+# backward stages (Section 2.2): pinned by the dense form and by finite differences of the
+# (already pinned) forward oracle
+# --------------------------------------------------------------------------
+
+def _bwd_setup(seed=12, n=40, m=260, F=5, Fo=4):
+    g = _random_graph(n, m, seed=seed)
+    rng = np.random.default_rng(seed)
+    # coarse values: X +- h stays exactly representable in fp32 for h = 2^-10
+    X = (np.round(rng.standard_normal((n, F)) * 32) / 32).astype(np.float32)
+    W = (np.round(rng.standard_normal((F, Fo)) * 32) / 32).astype(np.float32)
+    Ws = (np.round(rng.standard_normal((F, Fo)) * 32) / 32).astype(np.float32)
+    b = (np.round(rng.standard_normal(Fo) * 32) / 32).astype(np.float32)
+    w = (np.round(rng.standard_normal(g.nnz) * 16) / 16).astype(np.float32)
+    dY = rng.standard_normal((n, Fo)).astype(np.float32)
+    return g, X, W, Ws, b, w, dY
+
+
+@pytest.mark.parametrize("act", ["none", "relu"])
+@pytest.mark.parametrize("with_self", [False, True])
+def test_backward_equals_dense_matrix_form(act, with_self):
+    g, X, W, Ws, b, w, dY = _bwd_setup()
+    Ws_ = Ws if with_self else None
+    fwd = oracle.layer(*_np(g), X, "mul_weight", w, W=W, W_self=Ws_, bias=b, act="none")
+    bwd = oracle.layer_backward(*_np(g), X, fwd["A"], dY, W, "mul_weight", w, bias=b, W_self=Ws_, act=act)
+    Adj = _dense_adj(g, w)                                   # Adj[v, u] = w(u -> v)
+    Xd, Wd, dYd = X.astype(np.float64), W.astype(np.float64), dY.astype(np.float64)
+    A = Adj @ Xd
+    Z = A @ Wd + b + (Xd @ Ws.astype(np.float64) if with_self else 0.0)
+    dZ = dYd * (Z > 0) if act == "relu" else dYd
+    assert np.allclose(bwd["dW"], A.T @ dZ, rtol=1e-12, atol=1e-12)
+    assert np.allclose(bwd["dbias"], dZ.sum(0), rtol=1e-12, atol=1e-12)
+    assert np.allclose(bwd["dA"], dZ @ Wd.T, rtol=1e-12, atol=1e-12)
+    dX = Adj.T @ (dZ @ Wd.T) + (dZ @ Ws.astype(np.float64).T if with_self else 0.0)
+    assert np.allclose(bwd["dX"], dX, rtol=1e-12, atol=1e-12)
+    if with_self:
+        assert np.allclose(bwd["dW_self"], Xd.T @ dZ, rtol=1e-12, atol=1e-12)
+    assert np.allclose(bwd["dW_abs"], np.abs(A).T @ np.abs(dZ), rtol=1e-12, atol=1e-12)
+    dXa = np.abs(Adj).T @ (np.abs(dZ) @ np.abs(Wd).T) + (np.abs(dZ) @ np.abs(Ws).astype(np.float64).T if with_self else 0.0)
+    assert np.allclose(bwd["dX_abs"], dXa, rtol=1e-12, atol=1e-12)
+
+
+def test_backward_matches_finite_differences_of_the_forward_oracle():
+    g, X, W, Ws, b, w, dY = _bwd_setup(seed=5, n=25, m=120, F=3, Fo=3)
+    R = dY.astype(np.float64)                                # loss L = sum(R * Y)
+    def loss(Xp, Wp, Wsp, bp):
+        y = oracle.layer(*_np(g), Xp, "mul_weight", w, W=Wp, W_self=Wsp, bias=bp, act="none")["Y"]
+        return float((R * y).sum())
+    fwd = oracle.layer(*_np(g), X, "mul_weight", w, W=W, W_self=Ws, bias=b, act="none")
+    bwd = oracle.layer_backward(*_np(g), X, fwd["A"], dY, W, "mul_weight", w, bias=b, W_self=Ws, act="none")
+    h = 2.0 ** -10
+    rng = np.random.default_rng(0)
+    for _ in range(12):                                       # the layer is linear in each argument: differences are exact
+        u, f = rng.integers(g.n), rng.integers(3)
+        Xp, Xm = X.copy(), X.copy(); Xp[u, f] += h; Xm[u, f] -= h
+        num = (loss(Xp, W, Ws, b) - loss(Xm, W, Ws, b)) / (2 * h)
+        assert abs(num - bwd["dX"][u, f]) <= 1e-9 * max(1.0, abs(num))
+        f, o = rng.integers(3), rng.integers(3)
+        Wp, Wm = W.copy(), W.copy(); Wp[f, o] += h; Wm[f, o] -= h
+        num = (loss(X, Wp, Ws, b) - loss(X, Wm, Ws, b)) / (2 * h)
+        assert abs(num - bwd["dW"][f, o]) <= 1e-9 * max(1.0, abs(num))
+        Sp, Sm = Ws.copy(), Ws.copy(); Sp[f, o] += h; Sm[f, o] -= h
+        num = (loss(X, W, Sp, b) - loss(X, W, Sm, b)) / (2 * h)
+        assert abs(num - bwd["dW_self"][f, o]) <= 1e-9 * max(1.0, abs(num))
+        bp, bm = b.copy(), b.copy(); bp[o] += h; bm[o] -= h
+        num = (loss(X, W, Ws, bp) - loss(X, W, Ws, bm)) / (2 * h)
+        assert abs(num - bwd["dbias"][o]) <= 1e-9 * max(1.0, abs(num))
+
+
+def test_backward_relu_mask_and_copy_edges():
+    g, X, W, Ws, b, w, dY = _bwd_setup(seed=21)
+    fwd = oracle.layer(*_np(g), X, "copy", W=W, act="relu")
+    bwd = oracle.layer_backward(*_np(g), X, fwd["A"], dY, W, "copy", act="relu")
+    dead = fwd["Y"] <= 0
+    assert dead.any() and (~dead).any()
+    # a vertex whose outputs are all clipped contributes nothing to dW
+    Adj = _dense_adj(g)
+    dZ = np.where(dead, 0.0, dY.astype(np.float64))
+    assert np.allclose(bwd["dW"], (Adj @ X.astype(np.float64)).T @ dZ, rtol=1e-12, atol=1e-12)
+    assert np.allclose(bwd["dX"], Adj.T @ (dZ @ W.astype(np.float64).T), rtol=1e-12, atol=1e-12)
