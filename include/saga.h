@@ -179,6 +179,44 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
                                const saga_edge_params* ep, int32_t agg,
                                const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out);
 
+/*
+ * Gradients a backward call writes (each overwritten, not added to). All fp32, device.
+ */
+typedef struct saga_layer_grads {
+    saga_tensor* dX;      /* n x F_in: gradient of the layer's input; NULL = not wanted (first layer) */
+    saga_tensor* dW;      /* F_in x F_out: required */
+    saga_tensor* dbias;   /* F_out values; NULL = not wanted */
+    saga_tensor* dW_self; /* F_in x F_out: required exactly when vp->W_self is given */
+} saga_layer_grads;
+
+/*
+ * One layer backward (the backward stages of Section 2.2, run in reverse order of the
+ * forward ones), for the layers whose ApplyEdge is linear in the source row: sum
+ * accumulator, COPY or MUL_WEIGHT, fp32, ApplyVertex Y = act(A W + X W_self + bias) with
+ * act NONE or RELU, everything device-resident. Other layers return SAGA_ERR_UNSUPPORTED.
+ *
+ *   backward-ApplyVertex   dZ = dY (.) act'(Z)  (ReLU: where Y > 0),  dW = A^T dZ,
+ *                          dW_self = X^T dZ,  dbias = column sums of dZ,
+ *                          gradient of accum = dZ W^T, own partial gradient = dZ W_self^T
+ *   backward-Gather, backward-ApplyEdge, backward-Scatter, fused the way the forward
+ *   propagation is: dX[u] = sum over out-edges u -> v of w_e * (gradient of accum)[v]
+ *                           + own partial gradient[u]
+ *
+ * A is the Gather output of the forward call (its accum_out), kept by the caller as the
+ * intermediate feature data back-propagation needs (Section 3.1). X is read only for
+ * dW_self and may be NULL without W_self; Y is read only for RELU and may be NULL otherwise.
+ * The transposed edge order (out-edges grouped by source) and its work list are built at
+ * the first backward call on a graph, which synchronises the stream. Because the
+ * propagation is linear, it runs at the narrower of F_in and F_out: when F_out < F_in the
+ * rows of dZ are propagated first and multiplied by W^T afterwards (the operator motion of
+ * Section 3.2 applied to the backward pass); the result is the same up to rounding order.
+ * Sums are deterministic run to run.
+ */
+saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,
+                                const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                                const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
+                                const saga_layer_grads* grads);
+
 /* Stage timers. Off by default (no events recorded). */
 saga_status saga_set_profiling(saga_ctx* ctx, int32_t on);
 saga_status saga_reset_timings(saga_ctx* ctx);

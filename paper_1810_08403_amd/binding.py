@@ -28,7 +28,7 @@ MEM_DEVICE, MEM_HOST = 0, 1
 
 # every entry point include/saga.h declares
 EXPORTS = ["saga_create", "saga_destroy", "saga_graph_create_csc", "saga_graph_destroy",
-           "saga_graph_set_edge_data", "saga_layer_forward", "saga_set_profiling", "saga_reset_timings",
+           "saga_graph_set_edge_data", "saga_layer_forward", "saga_layer_backward", "saga_set_profiling", "saga_reset_timings",
            "saga_get_timings", "saga_set_option", "saga_peak_device_bytes", "saga_last_error",
            "saga_graph_info", "saga_plan_work_list", "saga_copy_bytes", "saga_version"]
 
@@ -53,6 +53,11 @@ class EdgeParams(ctypes.Structure):
 class VertexParams(ctypes.Structure):
     _fields_ = [("W", ctypes.POINTER(Tensor)), ("bias", ctypes.POINTER(Tensor)), ("act", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("W_self", ctypes.POINTER(Tensor))]
+
+
+class LayerGrads(ctypes.Structure):
+    _fields_ = [("dX", ctypes.POINTER(Tensor)), ("dW", ctypes.POINTER(Tensor)), ("dbias", ctypes.POINTER(Tensor)),
+                ("dW_self", ctypes.POINTER(Tensor))]
 
 
 class Timings(ctypes.Structure):
@@ -105,6 +110,10 @@ def load_library() -> ctypes.CDLL:
     L.saga_layer_forward.restype = I32
     L.saga_layer_forward.argtypes = [P, P, ctypes.POINTER(Tensor), ctypes.POINTER(EdgeParams), I32,
                                      ctypes.POINTER(VertexParams), ctypes.POINTER(Tensor), ctypes.POINTER(Tensor)]
+    L.saga_layer_backward.restype = I32
+    L.saga_layer_backward.argtypes = [P, P, ctypes.POINTER(Tensor), ctypes.POINTER(Tensor), ctypes.POINTER(Tensor),
+                                      ctypes.POINTER(Tensor), ctypes.POINTER(EdgeParams), I32,
+                                      ctypes.POINTER(VertexParams), ctypes.POINTER(LayerGrads)]
     L.saga_set_profiling.restype = I32
     L.saga_set_profiling.argtypes = [P, I32]
     L.saga_reset_timings.restype = I32
@@ -260,6 +269,31 @@ class Context:
         if cur != self.stream:
             cur.wait_stream(self.stream)
         return Y
+
+    def layer_backward(self, g: Graph, A: torch.Tensor, dY: torch.Tensor, W: torch.Tensor, dW: torch.Tensor,
+                       X: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None, edge_op: str = "copy",
+                       edge_weight: Optional[torch.Tensor] = None, agg: str = "sum", bias=None, W_self=None,
+                       act: str = "none", dX=None, dbias=None, dW_self=None):
+        """saga_layer_backward: gradients are written into dW (and dX, dbias, dW_self when given)."""
+        tx, ta, ty, tdy = as_tensor(X), as_tensor(A), as_tensor(Y), as_tensor(dY)
+        tw, tb, tws = as_tensor(W), as_tensor(bias), as_tensor(W_self)
+        tdx, tdw, tdb, tdws = as_tensor(dX), as_tensor(dW), as_tensor(dbias), as_tensor(dW_self)
+        if edge_weight is not None:
+            assert edge_weight.dtype == torch.float32 and edge_weight.is_contiguous()
+            assert edge_weight.numel() == g.nnz
+        ep = EdgeParams(EDGE_OP[edge_op], edge_weight.data_ptr() if edge_weight is not None else None,
+                        None, None, None, None, None)
+        ptr = lambda t: ctypes.pointer(t) if t is not None else None
+        vp = VertexParams(ptr(tw), ptr(tb), ACT[act], 0, ptr(tws))
+        grads = LayerGrads(ptr(tdx), ptr(tdw), ptr(tdb), ptr(tdws))
+        cur = torch.cuda.current_stream(self.device)
+        if cur != self.stream:
+            self.stream.wait_stream(cur)
+        self._check(self.lib.saga_layer_backward(self._h, g._h, _ref(tx), _ref(ta), _ref(ty), _ref(tdy), ctypes.byref(ep),
+                                                 AGG[agg], ctypes.byref(vp), ctypes.byref(grads)))
+        if cur != self.stream:
+            cur.wait_stream(self.stream)
+        return dW
 
     def copy_bytes(self, dst: torch.Tensor, src: torch.Tensor):
         """Plain copy kernel on the library's stream (counter calibration)."""

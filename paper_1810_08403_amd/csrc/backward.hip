@@ -1,0 +1,252 @@
+// Backward pass of one device-resident layer (the backward stages of Section 2.2 in
+// reverse order of the forward ones) for layers whose ApplyEdge is linear in the source
+// row. backward-Gather / backward-ApplyEdge / backward-Scatter fuse exactly like the
+// forward propagation (Section 3.3): vertex u's gradient is the weighted sum, over its
+// out-edges u -> v, of the rows of the gradient at v. That is the forward propagation
+// kernel run on the same edges grouped by source instead of by destination, so this file
+// only builds that second edge order and strings the kernels together.
+#include <cstring>
+
+#include "saga_internal.h"
+
+void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g)
+{
+    ctx->dev_free(&g->d_perm);
+    if (!g->tr) return;
+    saga_graph* t = g->tr;
+    for (DevBuf* b : {&t->d_row_idx, &t->d_items, &t->d_heavy, &t->d_edge_data}) ctx->dev_free(b);
+    for (auto& sl : t->saved_lists) {
+        ctx->dev_free(&sl.items);
+        ctx->dev_free(&sl.heavy);
+    }
+    delete t;
+    g->tr = nullptr;
+    g->tr_edge_data_valid = false;
+}
+
+// Out-edges grouped by source: a counting sort of the CSC edge list by source id. Walking
+// the columns in order keeps every group ascending in destination id, which is the order
+// the propagation kernel and the work-list builder expect.
+static saga_status ensure_transposed(saga_ctx* ctx, saga_graph* g)
+{
+    if (g->tr) return SAGA_OK;
+    const int64_t n = g->n, nnz = g->nnz;
+    saga_graph* t = new (std::nothrow) saga_graph();
+    if (!t) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    t->ctx = ctx;
+    t->n = n;
+    t->nnz = nnz;
+    t->where = SAGA_MEM_DEVICE;
+    g->tr = t;
+    auto bail = [&](saga_status st) {
+        transposed_graph_destroy(ctx, g);
+        return st;
+    };
+    std::vector<int32_t> src, dst, perm;
+    try {
+        src.resize((size_t)std::max<int64_t>(nnz, 1));
+        dst.resize((size_t)std::max<int64_t>(nnz, 1));
+        perm.resize((size_t)std::max<int64_t>(nnz, 1));
+        t->h_col_ptr.assign((size_t)n + 1, 0);
+    } catch (...) {
+        return bail(ctx->fail(SAGA_ERR_INTERNAL, "out of host memory"));
+    }
+    if (nnz > 0) {
+        hipError_t e = hipMemcpyAsync(src.data(), g->d_row_idx.p, sizeof(int32_t) * (size_t)nnz, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) return bail(ctx->fail(SAGA_ERR_HIP, "reading the edge list: %s", hipGetErrorString(e)));
+    }
+    int64_t* rp = t->h_col_ptr.data();
+    for (int64_t e = 0; e < nnz; ++e) ++rp[src[(size_t)e] + 1];
+    int64_t maxdeg = 0;
+    for (int64_t u = 0; u < n; ++u) {
+        maxdeg = std::max(maxdeg, rp[u + 1]);
+        rp[u + 1] += rp[u];
+    }
+    t->max_degree = maxdeg;
+    {
+        std::vector<int64_t> fill(rp, rp + n);
+        const int64_t* cp = g->h_col_ptr.data();
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = cp[v]; e < cp[v + 1]; ++e) {
+                const int64_t pos = fill[(size_t)src[(size_t)e]]++;
+                dst[(size_t)pos] = (int32_t)v;
+                perm[(size_t)pos] = (int32_t)e;
+            }
+    }
+    saga_status st;
+    if ((st = ctx->dev_alloc(&t->d_row_idx, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1)))) return bail(st);
+    if ((st = ctx->dev_alloc(&g->d_perm, sizeof(int32_t) * (size_t)std::max<int64_t>(nnz, 1)))) return bail(st);
+    if (nnz > 0) {
+        hipError_t e = hipMemcpyAsync(t->d_row_idx.p, dst.data(), sizeof(int32_t) * (size_t)nnz, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipMemcpyAsync(g->d_perm.p, perm.data(), sizeof(int32_t) * (size_t)nnz, hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // the host vectors go out of scope below
+        if (e != hipSuccess) return bail(ctx->fail(SAGA_ERR_HIP, "uploading the transposed edge list: %s", hipGetErrorString(e)));
+    }
+    return SAGA_OK;
+}
+
+// rows of `src` (n x F fp32) propagated backwards over the edges into `out`:
+// out[u] (+)= sum over out-edges u -> v of w_e * src[v]
+static saga_status propagate_transposed(saga_ctx* ctx, saga_graph* g, const float* edge_w_t, const float* src, int64_t ld_src,
+                                        int32_t F, float* out, int64_t ld_out, int32_t accumulate)
+{
+    saga_graph* t = g->tr;
+    hipStream_t s = ctx->stream;
+    if (saga_status st = ensure_work_list(ctx, t, (int64_t)F * 4)) return st;
+    GatherArgs ga{};
+    ga.items = static_cast<const WorkItem*>(t->d_items.p);
+    ga.n_items = t->n_items;
+    ga.n_team = t->n_team;
+    ga.row_idx = static_cast<const int32_t*>(t->d_row_idx.p);
+    ga.edge_w = edge_w_t;
+    ga.src = src;
+    ga.ld_src = ld_src;
+    ga.F = F;
+    ga.dtype = SAGA_F32;
+    ga.op = edge_w_t ? SAGA_EDGE_MUL_WEIGHT : SAGA_EDGE_COPY;
+    ga.agg = SAGA_AGG_SUM;
+    ga.out = out;
+    ga.ld_out = ld_out;
+    ga.accumulate = accumulate;
+    ga.xcd_remap = ctx->opt_xcd_remap;
+    if (t->n_slots > 0) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)t->n_slots * F)) return st;
+        ga.partials = static_cast<float*>(ctx->ws_partials.p);
+    }
+    HIP_TRY(ctx, launch_gather(ga, s));
+    if (t->n_heavy > 0) {
+        CombineArgs ca{};
+        ca.heavy = static_cast<const HeavyVertex*>(t->d_heavy.p);
+        ca.n_heavy = t->n_heavy;
+        ca.partials = ga.partials;
+        ca.F = F;
+        ca.agg = SAGA_AGG_SUM;
+        ca.out = out;
+        ca.ld_out = ld_out;
+        ca.accumulate = accumulate;
+        HIP_TRY(ctx, launch_combine(ca, s));
+    }
+    return SAGA_OK;
+}
+
+// C[rows x N] = Arows[rows x K] * Wm[N x K]^T (+ A2 * W2[N x K2]^T): weights given with the output
+// channel as the row, which is how W (F_in x F_out) looks from dA = dZ W^T
+static saga_status rows_times_wt(saga_ctx* ctx, const float* Arows, int64_t lda, int32_t K, const saga_tensor* Wm, const float* A2,
+                                 int64_t lda2, int32_t K2, const saga_tensor* W2, int64_t rows, int32_t N, float* C, int64_t ldc)
+{
+    hipStream_t s = ctx->stream;
+    int64_t n_pad, k_pad, k_pad2 = 0;
+    bt_padded_shape(N, K, SAGA_F32, &n_pad, &k_pad);
+    if (A2) {
+        int64_t np2;
+        bt_padded_shape(N, K2, SAGA_F32, &np2, &k_pad2);
+    }
+    const int64_t ldbt = k_pad + k_pad2;
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * ldbt))) return st;
+    float* bt = static_cast<float*>(ctx->ws_bt.p);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * ldbt), s));
+    HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(Wm->data), Wm->ld, 0, N, K, bt, ldbt, 0, s));
+    if (A2) HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(W2->data), W2->ld, 0, N, K2, bt + k_pad, ldbt, 0, s));
+    GemmArgs ga{};
+    ga.A = Arows;
+    ga.lda = lda;
+    ga.A2 = A2;
+    ga.lda2 = lda2;
+    ga.K2 = K2;
+    ga.Bt = bt;
+    ga.ldbt = ldbt;
+    ga.C = C;
+    ga.ldc = ldc;
+    ga.M = rows;
+    ga.N = N;
+    ga.K = K;
+    ga.dtype = ga.out_dtype = SAGA_F32;
+    ga.act = SAGA_ACT_NONE;
+    HIP_TRY(ctx, launch_gemm(ga, s));
+    return SAGA_OK;
+}
+
+static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_t FP, const float* Q, int64_t ldq, int32_t FQ,
+                              int64_t n, saga_tensor* out)
+{
+    GemmTnArgs ta{};
+    ta.P = P;
+    ta.ldp = ldp;
+    ta.Q = Q;
+    ta.ldq = ldq;
+    ta.n = n;
+    ta.FP = FP;
+    ta.FQ = FQ;
+    gemm_tn_plan(n, FP, FQ, &ta.rows_per_split, &ta.n_split);
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)ta.n_split * FP * FQ)) return st;
+    ta.part = static_cast<float*>(ctx->ws_splitk.p);
+    HIP_TRY(ctx, launch_gemm_tn(ta, static_cast<float*>(out->data), out->ld, ctx->stream));
+    return SAGA_OK;
+}
+
+saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                              const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    hipStream_t s = ctx->stream;
+
+    // backward-ApplyVertex, the activation's derivative
+    const float* dZ = static_cast<const float*>(dY->data);
+    int64_t lddz = dY->ld;
+    if (vp->act == SAGA_ACT_RELU && n > 0) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)n * Fo)) return st;
+        HIP_TRY(ctx, launch_relu_grad(dZ, lddz, static_cast<const float*>(Y->data), Y->ld, static_cast<float*>(ctx->ws_dz.p), n, Fo, s));
+        dZ = static_cast<const float*>(ctx->ws_dz.p);
+        lddz = Fo;
+    }
+
+    // parameter gradients
+    if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, grads->dW)) return st;
+    if (grads->dW_self)
+        if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, grads->dW_self)) return st;
+    if (grads->dbias) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo)) return st;
+        HIP_TRY(ctx, launch_colsum(dZ, lddz, n, Fo, static_cast<float*>(ctx->ws_splitk.p), static_cast<float*>(grads->dbias->data), s));
+    }
+    if (!grads->dX || n == 0) return SAGA_OK;
+
+    // the edges grouped by source, and the edge data in that order
+    if (saga_status st = ensure_transposed(ctx, g)) return st;
+    const float* w_t = nullptr;
+    if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->nnz > 0) {
+        const int32_t* perm = static_cast<const int32_t*>(g->d_perm.p);
+        if (ep->edge_weight) {
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_edge_t, sizeof(float) * (size_t)g->nnz)) return st;
+            HIP_TRY(ctx, launch_permute_f32(ep->edge_weight, perm, static_cast<float*>(ctx->ws_edge_t.p), g->nnz, s));
+            w_t = static_cast<const float*>(ctx->ws_edge_t.p);
+        } else {
+            if (!g->tr_edge_data_valid) {
+                if (saga_status st = ctx->dev_alloc(&g->tr->d_edge_data, sizeof(float) * (size_t)g->nnz)) return st;
+                HIP_TRY(ctx, launch_permute_f32(static_cast<const float*>(g->d_edge_data.p), perm,
+                                                static_cast<float*>(g->tr->d_edge_data.p), g->nnz, s));
+                g->tr_edge_data_valid = true;
+            }
+            w_t = static_cast<const float*>(g->tr->d_edge_data.p);
+        }
+    }
+
+    float* dX = static_cast<float*>(grads->dX->data);
+    const int64_t lddx = grads->dX->ld;
+    if (Fo < F) {
+        // propagate the narrower rows first: dX = (T dZ) W^T + dZ W_self^T, one product with two operands
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)n * Fo)) return st;
+        float* G = static_cast<float*>(ctx->ws_grad.p);
+        if (saga_status st = propagate_transposed(ctx, g, w_t, dZ, lddz, Fo, G, Fo, 0)) return st;
+        return rows_times_wt(ctx, G, Fo, Fo, vp->W, vp->W_self ? dZ : nullptr, lddz, Fo, vp->W_self, n, F, dX, lddx);
+    }
+    // gradient of accum = dZ W^T, then propagate it; the vertex's own partial gradient goes into dX first
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)n * F)) return st;
+    float* dA = static_cast<float*>(ctx->ws_grad.p);
+    if (saga_status st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W, nullptr, 0, 0, nullptr, n, F, dA, F)) return st;
+    if (vp->W_self)
+        if (saga_status st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W_self, nullptr, 0, 0, nullptr, n, F, dX, lddx)) return st;
+    return propagate_transposed(ctx, g, w_t, dA, F, F, dX, lddx, vp->W_self ? 1 : 0);
+}

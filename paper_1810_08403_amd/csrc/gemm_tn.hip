@@ -1,0 +1,272 @@
+// Parameter gradients of backward-ApplyVertex (Section 2.2): C[FP x FQ] = P^T Q, a
+// contraction over all vertices of two row-major fp32 matrices (P = the Gather output or
+// the vertices' own features, Q = the gradient of the pre-activation). Both operands are
+// read the way they are stored, a vertex's features contiguous, so neither is transposed:
+// for the 32x32x2 MFMA a lane's operand is one element (feature l % 32, vertex l / 32),
+// which is a row-contiguous read of a K tile staged in LDS as [vertex][feature].
+//
+// The vertex range is divided over gridDim splits (the output is tiny, the contraction
+// long); every split writes its own FP x FQ partial and a second kernel adds the partials
+// in split order, so the result does not depend on scheduling. The same file holds the
+// two small reductions beside it: the activation's derivative applied to the incoming
+// gradient, and the column sums that give the bias gradient.
+#include "saga_internal.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kKT = 16;       // vertices per K tile
+constexpr int kPadCols = 32;  // LDS row padding (floats): consecutive vertices start 32 banks apart
+
+// One K tile, global -> registers. Thread t owns 4-float chunks t, t + 256, ... of the
+// [kKT][BM + BN] tile. Rows past the split's end and columns past the matrix are zero.
+template <int BM, int BN, bool ALIGNED, int CH>
+__device__ __forceinline__ void tn_load(const GemmTnArgs& a, int64_t v0, int64_t v_end, int i0, int j0, int tid, f32x4 (&r)[CH])
+{
+    constexpr int CPR = (BM + BN) / 4;  // chunks per tile row
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int id = tid + 256 * c;
+        const int k = id / CPR, cc = id % CPR;
+        const bool isq = cc >= BM / 4;
+        const int col = isq ? j0 + (cc - BM / 4) * 4 : i0 + cc * 4;
+        const int lim = isq ? a.FQ : a.FP;
+        const float* base = isq ? a.Q : a.P;
+        const int64_t ld = isq ? a.ldq : a.ldp;
+        const int64_t v = v0 + k;
+        f32x4 x = {0.f, 0.f, 0.f, 0.f};
+        if (id < kKT * CPR && v < v_end) {
+            const float* p = base + v * ld + col;
+            if (ALIGNED) {
+                if (col + 4 <= lim) x = *reinterpret_cast<const f32x4*>(p);  // lim % 4 == 0: a chunk is inside or outside
+            } else {
+                if (col + 0 < lim) x.x = p[0];
+                if (col + 1 < lim) x.y = p[1];
+                if (col + 2 < lim) x.z = p[2];
+                if (col + 3 < lim) x.w = p[3];
+            }
+        }
+        r[c] = x;
+    }
+}
+
+template <int BM, int BN, int CH>
+__device__ __forceinline__ void tn_store(float* buf, int tid, const f32x4 (&r)[CH])
+{
+    constexpr int CPR = (BM + BN) / 4, LD = BM + BN + kPadCols;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int id = tid + 256 * c;
+        if (kKT * CPR % 256 == 0 || id < kKT * CPR) *reinterpret_cast<f32x4*>(buf + (id / CPR) * LD + (id % CPR) * 4) = r[c];
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool ALIGNED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) void k_gemm_tn(const GemmTnArgs a, const int tiles_m, const int tiles_n)
+{
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32, LD = BM + BN + kPadCols;
+    constexpr int CH = (kKT * (BM + BN) / 4 + 255) / 256;
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+    __shared__ __attribute__((aligned(16))) float lds[2][kKT * LD];
+
+    // blocks b, b + 8, b + 16, ... run on one XCD: give them the tiles of one split, which
+    // read the same vertex rows
+    const int T = tiles_m * tiles_n;
+    const int64_t b = blockIdx.x;
+    const int64_t grp = b / (8 * (int64_t)T);
+    const int within = (int)(b % (8 * (int64_t)T));
+    const int64_t split = grp * 8 + (within & 7);
+    const int tile = within >> 3;
+    if (split >= a.n_split) return;
+    const int i0 = (tile / tiles_n) * BM, j0 = (tile % tiles_n) * BN;
+    const int64_t v_begin = split * a.rows_per_split;
+    const int64_t v_end = v_begin + a.rows_per_split < a.n ? v_begin + a.rows_per_split : a.n;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    f32x4 regs[CH];
+    const int64_t nk = (v_end - v_begin + kKT - 1) / kKT;
+    if (nk > 0) {
+        tn_load<BM, BN, ALIGNED>(a, v_begin, v_end, i0, j0, tid, regs);
+        tn_store<BM, BN>(lds[0], tid, regs);
+    }
+    __syncthreads();
+    for (int64_t kt = 0; kt < nk; ++kt) {
+        // the last iteration loads past the end of the split: all zeros, never used
+        tn_load<BM, BN, ALIGNED>(a, v_begin + (kt + 1) * kKT, kt + 1 < nk ? v_end : 0, i0, j0, tid, regs);
+        __builtin_amdgcn_sched_barrier(0);
+        const float* base = lds[kt & 1] + (lane >> 5) * LD + (lane & 31);
+#pragma unroll
+        for (int kk = 0; kk < kKT / 2; ++kk) {
+            float fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = base[kk * 2 * LD + (wm * TM + i) * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = base[kk * 2 * LD + BM + (wn * TN + j) * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        tn_store<BM, BN>(lds[(kt + 1) & 1], tid, regs);
+        __syncthreads();
+    }
+
+    // this split's partial: lane holds column (lane & 31) of 16 rows of each 32 x 32 block
+    float* __restrict__ out = a.part + split * (int64_t)a.FP * a.FQ;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = j0 + (wn * TN + j) * 32 + (lane & 31);
+        if (col >= a.FQ) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = i0 + (wm * TM + i) * 32 + (lane >> 5) * 4;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + (r >> 2) * 8 + (r & 3);
+                if (row < a.FP) out[(int64_t)row * a.FQ + col] = acc[i][j][r];
+            }
+        }
+    }
+}
+
+// C[r][c] = sum over splits, in split order
+__global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ part, int64_t count, int n_split, int FQ, float* __restrict__ C,
+                                                    int64_t ldc)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+        float s = 0.f;
+        for (int k = 0; k < n_split; ++k) s += part[(int64_t)k * count + i];
+        C[(i / FQ) * ldc + (i % FQ)] = s;
+    }
+}
+
+// dZ = dY where Y > 0, else 0 (ReLU's derivative taken from the layer's output)
+__global__ __launch_bounds__(256) void k_relu_grad(const float* __restrict__ dY, int64_t lddy, const float* __restrict__ Y, int64_t ldy,
+                                                   float* __restrict__ dZ, int64_t rows, int F)
+{
+    const int64_t total = rows * F;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / F;
+        const int c = (int)(i % F);
+        dZ[i] = Y[r * ldy + c] > 0.f ? dY[r * lddy + c] : 0.f;
+    }
+}
+
+// part[slab][c] = sum of rows [slab * R, (slab + 1) * R) of column c, rows in order
+__global__ __launch_bounds__(256) void k_colsum_slabs(const float* __restrict__ Z, int64_t ldz, int64_t rows, int F, int64_t R,
+                                                      float* __restrict__ part)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * R;
+    const int64_t r1 = r0 + R < rows ? r0 + R : rows;
+    for (int c = threadIdx.x; c < F; c += 256) {
+        float s = 0.f;
+        for (int64_t r = r0; r < r1; ++r) s += Z[r * ldz + c];
+        part[(int64_t)blockIdx.x * F + c] = s;
+    }
+}
+
+// out[i] = in[perm[i]]
+__global__ __launch_bounds__(256) void k_permute_f32(const float* __restrict__ in, const int32_t* __restrict__ perm, float* __restrict__ out,
+                                                     int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) out[i] = in[perm[i]];
+}
+
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_tn_cfg(const GemmTnArgs& a, bool aligned, hipStream_t s)
+{
+    const int tiles_m = (a.FP + BM - 1) / BM, tiles_n = (a.FQ + BN - 1) / BN;
+    const int64_t groups = (a.n_split + 7) / 8;
+    const int64_t blocks = groups * 8 * tiles_m * tiles_n;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (aligned)
+        hipLaunchKernelGGL((k_gemm_tn<BM, BN, WM, WN, true>), dim3((unsigned)blocks), dim3(256), 0, s, a, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((k_gemm_tn<BM, BN, WM, WN, false>), dim3((unsigned)blocks), dim3(256), 0, s, a, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, int32_t* n_split)
+{
+    const int BN = FQ > 64 ? 128 : (FQ > 32 ? 64 : 32);
+    const int BM = FQ > 64 ? 128 : (FQ > 32 ? 128 : 256);
+    const int64_t tiles = (int64_t)((FP + BM - 1) / BM) * ((FQ + BN - 1) / BN);
+    // enough blocks to fill the chip a few times over, but at least 256 vertices per split
+    int64_t want = std::max<int64_t>(1, 2048 / std::max<int64_t>(tiles, 1));
+    want = std::min<int64_t>(want, std::max<int64_t>(1, n / 256));
+    want = std::min<int64_t>(want, 1024);
+    int64_t rows = (std::max<int64_t>(n, 1) + want - 1) / want;
+    rows = (rows + kKT - 1) / kKT * kKT;
+    *rows_per_split = rows;
+    *n_split = (int32_t)std::max<int64_t>(1, (n + rows - 1) / rows);
+}
+
+hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_t s)
+{
+    if (a.FP <= 0 || a.FQ <= 0) return hipSuccess;
+    if (a.n_split < 1 || a.rows_per_split < 1 || a.rows_per_split % kKT != 0 || !a.part) return hipErrorInvalidValue;
+    if ((int64_t)a.n_split * a.rows_per_split < a.n) return hipErrorInvalidValue;
+    const bool aligned = a.FP % 4 == 0 && a.FQ % 4 == 0 && a.ldp % 4 == 0 && a.ldq % 4 == 0 &&
+                         (reinterpret_cast<uintptr_t>(a.P) & 15u) == 0 && (reinterpret_cast<uintptr_t>(a.Q) & 15u) == 0;
+    hipError_t e;
+    if (a.FQ > 64)
+        e = launch_tn_cfg<128, 128, 2, 2>(a, aligned, s);
+    else if (a.FQ > 32)
+        e = launch_tn_cfg<128, 64, 4, 1>(a, aligned, s);
+    else
+        e = launch_tn_cfg<256, 32, 4, 1>(a, aligned, s);
+    if (e != hipSuccess) return e;
+    const int64_t count = (int64_t)a.FP * a.FQ;
+    const int grid = (int)std::min<int64_t>((count + 255) / 256, 65535);
+    hipLaunchKernelGGL(k_sum_splits, dim3(grid), dim3(256), 0, s, a.part, count, a.n_split, a.FQ, C, ldc);
+    return hipGetLastError();
+}
+
+hipError_t launch_relu_grad(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
+                            hipStream_t s)
+{
+    const int64_t total = rows * F;
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
+    hipLaunchKernelGGL(k_relu_grad, dim3(grid), dim3(256), 0, s, dY, lddy, Y, ldy, dZ, rows, F);
+    return hipGetLastError();
+}
+
+int64_t colsum_slabs(int64_t rows) { return std::max<int64_t>(1, std::min<int64_t>(2048, (rows + 255) / 256)); }
+
+hipError_t launch_colsum(const float* Z, int64_t ldz, int64_t rows, int32_t F, float* part, float* out, hipStream_t s)
+{
+    if (F <= 0) return hipSuccess;
+    const int64_t slabs = colsum_slabs(rows);
+    const int64_t R = (std::max<int64_t>(rows, 1) + slabs - 1) / slabs;
+    hipLaunchKernelGGL(k_colsum_slabs, dim3((unsigned)slabs), dim3(256), 0, s, Z, ldz, rows, F, R, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int grid = (int)std::min<int64_t>((F + 255) / 256, 65535);
+    hipLaunchKernelGGL(k_sum_splits, dim3(grid), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, out, (int64_t)F);
+    return hipGetLastError();
+}
+
+hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((count + 255) / 256, 1 << 20);
+    hipLaunchKernelGGL(k_permute_f32, dim3(grid), dim3(256), 0, s, in, perm, out, count);
+    return hipGetLastError();
+}

@@ -241,7 +241,7 @@ WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes)
     return p;
 }
 
-static saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
 {
     const WorkListParams p = work_list_params(ctx, row_bytes);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
@@ -365,7 +365,7 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag})
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t})
         ctx->dev_free(b);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
@@ -560,6 +560,7 @@ saga_status saga_graph_destroy(saga_graph* g)
         ctx->dev_free(&sl.heavy);
     }
     if (g->grid) chunk_grid_destroy(ctx, g->grid);
+    transposed_graph_destroy(ctx, g);
     delete g;
     return SAGA_OK;
 }
@@ -582,6 +583,7 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
         }
         return SAGA_OK;
     }
+    g->tr_edge_data_valid = false;
     if (saga_status st = ctx->dev_alloc(&g->d_edge_data, sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1))) return st;
     if (g->nnz > 0) {
         HIP_TRY(ctx, hipMemcpyAsync(g->d_edge_data.p, w, sizeof(float) * (size_t)g->nnz, hipMemcpyDeviceToDevice, ctx->stream));
@@ -873,6 +875,53 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
     if (g->n == 0) return SAGA_OK;
     return resident_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y, accum_out);
+}
+
+saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_tensor* A,
+                                const saga_tensor* Y, const saga_tensor* dY, const saga_edge_params* ep, int32_t agg,
+                                const saga_vertex_params* vp, const saga_layer_grads* grads)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    if (!g || !A || !dY || !ep || !vp || !grads) return ctx->fail(SAGA_ERR_INVALID_ARG, "null argument");
+    if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
+    if (g->where != SAGA_MEM_DEVICE) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs a device-resident graph");
+    if (agg != SAGA_AGG_SUM) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers the sum accumulator only");
+    if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers COPY and MUL_WEIGHT ApplyEdge only");
+    if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
+    auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };
+    const saga_tensor* W = vp->W;
+    if (!W) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs an ApplyVertex product (vp->W)");
+    if (!dev_f32(W) || W->rows > (1 << 20) || W->cols > (1 << 20))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out fp32 tensor");
+    const int64_t n = g->n, F = W->rows, Fo = W->cols;
+    if (!dev_f32(A) || A->rows != n || A->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x F_in fp32 tensor");
+    if (!dev_f32(dY) || dY->rows != n || dY->cols != Fo)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "dY must be a device n x F_out fp32 tensor");
+    if (vp->act == SAGA_ACT_RELU && (!Y || !dev_f32(Y) || Y->rows != n || Y->cols != Fo))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a device n x F_out fp32 tensor");
+    if (vp->W_self) {
+        if (!dev_f32(vp->W_self) || vp->W_self->rows != F || vp->W_self->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out fp32 tensor");
+        if (!X || !dev_f32(X) || X->rows != n || X->cols != F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self needs X as a device n x F_in fp32 tensor");
+        if (!grads->dW_self) return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self is given but grads->dW_self is not");
+    } else if (grads->dW_self) {
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
+    }
+    if (!grads->dW || !dev_f32(grads->dW) || grads->dW->rows != F || grads->dW->cols != Fo)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
+    if (grads->dW_self && (!dev_f32(grads->dW_self) || grads->dW_self->rows != F || grads->dW_self->cols != Fo))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self must be a device F_in x F_out fp32 tensor");
+    if (grads->dbias && (!dev_f32(grads->dbias) || grads->dbias->rows * grads->dbias->cols != Fo))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
+    if (grads->dX && (!dev_f32(grads->dX) || grads->dX->rows != n || grads->dX->cols != F))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F_in fp32 tensor");
+    if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
+    DeviceGuard guard(ctx->device);
+    return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
 }
 
 }  // extern "C"

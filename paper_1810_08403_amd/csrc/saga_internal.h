@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -90,6 +91,11 @@ struct saga_ctx {
     DevBuf ws_bt;        // packed, transposed weights
     DevBuf ws_bias;      // packed bias for the hoisted product
     DevBuf ws_flag;      // validation flag
+    // backward pass
+    DevBuf ws_dz;        // gradient of the pre-activation (ReLU layers)
+    DevBuf ws_grad;      // gradient rows between the dense product and the propagation kernel
+    DevBuf ws_splitk;    // per-split partials of the parameter gradients and of the bias column sums
+    DevBuf ws_edge_t;    // per-call edge weights in the order of the transposed graph
 
     // profiling
     bool profiling = false;
@@ -131,6 +137,12 @@ struct saga_graph {
     std::vector<int32_t> h_row_idx;
     std::vector<float> h_edge_data;
     ChunkGrid* grid = nullptr;
+    // the same edges grouped by source (backward-Scatter gathers over out-edges): built at the
+    // first backward call. tr's columns are this graph's sources; perm[e'] is the position in
+    // this graph's edge order of the transposed graph's edge e'.
+    saga_graph* tr = nullptr;
+    DevBuf d_perm;
+    bool tr_edge_data_valid = false;  // tr->d_edge_data holds d_edge_data permuted
 };
 
 #define HIP_TRY(ctx, call)                                                                   \
@@ -227,7 +239,40 @@ hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32
 hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int32_t R, int32_t K,
                                float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
 hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s);
+
+// C[FP x FQ] = P^T Q over n rows (fp32), the rows divided over n_split ranges of
+// rows_per_split (a multiple of 16) whose partials land in `part` (n_split x FP x FQ floats)
+// and are then added in order into C. gemm_tn_plan picks the division.
+struct GemmTnArgs {
+    const float* P;
+    int64_t ldp;
+    const float* Q;
+    int64_t ldq;
+    int64_t n;
+    int64_t rows_per_split;
+    float* part;
+    int32_t FP, FQ;
+    int32_t n_split;
+    int32_t pad_;
+};
+void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, int32_t* n_split);
+hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_t s);
+// dZ (rows x F, compact) = dY where Y > 0, else 0
+hipError_t launch_relu_grad(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
+                            hipStream_t s);
+// out[c] = sum over rows of Z[r][c]; part holds colsum_slabs(rows) x F floats
+int64_t colsum_slabs(int64_t rows);
+hipError_t launch_colsum(const float* Z, int64_t ldz, int64_t rows, int32_t F, float* part, float* out, hipStream_t s);
+hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s);
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
+
+// resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
+saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes);
+// backward pass of a resident layer (backward.hip)
+saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                              const saga_layer_grads* grads);
+void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,

@@ -1,0 +1,174 @@
+"""Backward pass of a layer (Section 2.2's backward stages) through the C ABI against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import saga_inputs as si
+from helpers import TOL_F32, assert_sum_close, make_graph, new_context
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1810_08403_amd as saga
+    c = saga.Context(0)
+    yield c
+    c.destroy()
+
+
+def _oracle_pair(wl, act, bias, with_self, dY):
+    g = wl.graph
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    w = wl.edge_weight.numpy() if wl.edge_op == "mul_weight" else None
+    Ws = wl.W_self.numpy() if with_self else None
+    b = None if bias is None else bias.numpy()
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op=wl.edge_op, edge_weight=w, W=wl.W.numpy(), bias=b, W_self=Ws, act=act)
+    bwd = oracle.layer_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), wl.edge_op, w, bias=b, W_self=Ws, act=act)
+    return fwd, bwd
+
+
+def _run_backward(ctx, graph, wl, A, Y, dY, act, bias, with_self, attach=False, want_dx=True, pad=0):
+    """GPU backward on host arrays; returns dict of numpy gradients. pad > 0 gives every matrix a row stride
+    that many elements longer than its width."""
+    dev = "cuda"
+    def up(a):
+        t = torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32)
+        if pad and t.dim() == 2:
+            buf = torch.zeros(t.shape[0], t.shape[1] + pad, device=dev)
+            buf[:, :t.shape[1]] = t.to(dev)
+            return buf[:, :t.shape[1]]
+        return t.to(dev)
+    def out(r, c):
+        return torch.full((r, c + pad), float("nan"), device=dev)[:, :c] if pad else torch.full((r, c), float("nan"), device=dev)
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    kw = {}
+    if wl.edge_op == "mul_weight":
+        if attach:
+            graph.set_edge_data(wl.edge_weight.to(dev))
+        else:
+            kw["edge_weight"] = wl.edge_weight.to(dev)
+    dW, dX = out(F, Fo), (out(n, F) if want_dx else None)
+    db = torch.full((Fo,), float("nan"), device=dev)
+    dWs = out(F, Fo) if with_self else None
+    ctx.layer_backward(graph, up(A), up(dY), up(wl.W), dW, X=up(wl.X), Y=up(Y), edge_op=wl.edge_op, bias=None if bias is None else bias.to(dev),
+                       W_self=up(wl.W_self) if with_self else None, act=act, dX=dX, dbias=db, dW_self=dWs, **kw)
+    torch.cuda.synchronize()
+    res = {"dW": dW.cpu().numpy(), "dbias": db.cpu().numpy()}
+    if want_dx:
+        res["dX"] = dX.cpu().numpy()
+    if with_self:
+        res["dW_self"] = dWs.cpu().numpy()
+    return res
+
+
+def _check(res, bwd, dY, X, with_self, what):
+    assert_sum_close(res["dW"], bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+    # dbias and dW_self: sums of n terms each; scale by the absolute-term sums written out here
+    dZ_abs_colsum = np.abs(dY.numpy().astype(np.float64)).sum(0)
+    assert_sum_close(res["dbias"], bwd["dbias"], np.maximum(dZ_abs_colsum, 1e-30), TOL_F32, what + " dbias")
+    if "dX" in res:
+        assert_sum_close(res["dX"], bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    if with_self:
+        scale = np.abs(X.numpy().astype(np.float64)).T @ np.abs(dY.numpy().astype(np.float64))
+        assert_sum_close(res["dW_self"], bwd["dW_self"], np.maximum(scale, 1e-30), TOL_F32, what + " dW_self")
+
+
+CASES = [
+    # f_in, f_out, edge_op, act, with_self, with_bias
+    (64, 64, "mul_weight", "relu", False, True),
+    (128, 48, "copy", "relu", True, True),        # F_out < F_in: propagate dZ first, two-operand product
+    (48, 128, "copy", "none", True, False),       # F_out > F_in: dA first, own partial gradient accumulated into
+    (500, 16, "mul_weight", "relu", False, True), # GCN layer 1 shape
+    (16, 3, "mul_weight", "none", False, True),   # GCN layer 2 shape, unaligned width
+    (20, 7, "copy", "relu", True, True),          # nothing aligned
+    (7, 20, "mul_weight", "relu", True, False),
+    (256, 256, "mul_weight", "relu", False, False),
+]
+
+
+@pytest.mark.parametrize("f_in,f_out,edge_op,act,with_self,with_bias", CASES)
+def test_backward_matches_oracle(ctx, f_in, f_out, edge_op, act, with_self, with_bias):
+    wl = si.commnet_workload(scale=11, f_in=f_in, f_out=f_out)   # R-MAT: heavy sources and heavy destinations
+    wl.edge_op = edge_op
+    if edge_op == "mul_weight":
+        wl.edge_weight = si.gcn_edge_weights(wl.graph)
+    n = wl.graph.n
+    out_deg = torch.bincount(wl.graph.row_idx.long(), minlength=n)
+    assert out_deg.max().item() > 128 and (out_deg == 0).any()    # cut groups and empty groups in the transposed order
+    bias = si.uniform_pm(f_out, 0.3, 5) if with_bias else None
+    dY = si.normal_features(n, f_out, 99)
+    fwd, bwd = _oracle_pair(wl, act, bias, with_self, dY)
+    graph = make_graph(ctx, wl.graph)
+    # the oracle's A and Y rounded to fp32 go in, so that the ReLU decisions are the same on both sides
+    res = _run_backward(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_self)
+    dZ = dY * torch.as_tensor(fwd["Y"] > 0) if act == "relu" else dY
+    _check(res, bwd, dZ, wl.X, with_self, f"{f_in}->{f_out} {edge_op} {act}")
+    graph.destroy()
+
+
+def test_backward_after_gpu_forward_with_attached_edge_data_and_strided_tensors(ctx):
+    wl = si.workload(2, scale=12, f_in=96, f_out=40)
+    wl.act = "none"
+    n = wl.graph.n
+    graph = make_graph(ctx, wl.graph)
+    graph.set_edge_data(wl.edge_weight.cuda())
+    Xd, Wd = wl.X.cuda(), wl.W.cuda()
+    Y = torch.empty(n, 40, device="cuda")
+    A = torch.empty(n, 96, device="cuda")
+    ctx.layer_forward(graph, Xd, Y, edge_op="mul_weight", W=Wd, act="none", accum_out=A)
+    dY = si.normal_features(n, 40, 3)
+    fwd, bwd = _oracle_pair(wl, "none", None, False, dY)
+    res = _run_backward(ctx, graph, wl, A.cpu().numpy(), Y.cpu().numpy(), dY, "none", None, False, attach=True, pad=4)
+    _check(res, bwd, dY, wl.X, False, "after GPU forward")
+    # a second call reuses the transposed edge order and gives the same bits
+    res2 = _run_backward(ctx, graph, wl, A.cpu().numpy(), Y.cpu().numpy(), dY, "none", None, False, attach=True, pad=4)
+    assert np.array_equal(res["dX"], res2["dX"]) and np.array_equal(res["dW"], res2["dW"])
+    graph.destroy()
+
+
+def test_backward_without_dx_and_on_a_graph_without_edges(ctx):
+    n, F, Fo = 300, 24, 12
+    g = si.csc_from_lists(n, [])
+    X, W, Ws = si.normal_features(n, F, 1), si.glorot_uniform(F, Fo, 2), si.glorot_uniform(F, Fo, 4)
+    dY = si.normal_features(n, Fo, 3)
+    wl = si.Workload(name="empty", graph=g, X=X, edge_op="copy", edge_weight=None, W=W, act="relu", dtype="f32", W_self=Ws)
+    fwd, bwd = _oracle_pair(wl, "relu", None, True, dY)
+    graph = make_graph(ctx, g)
+    res = _run_backward(ctx, graph, wl, fwd["A"], fwd["Y"], dY, "relu", None, True)
+    dZ = dY * torch.as_tensor(fwd["Y"] > 0)
+    _check(res, bwd, dZ, X, True, "no edges")
+    assert not res["dW"].any()                                   # A is all zero
+    res = _run_backward(ctx, graph, wl, fwd["A"], fwd["Y"], dY, "relu", None, True, want_dx=False)
+    _check(res, bwd, dZ, X, True, "no dX")
+    graph.destroy()
+
+
+def test_backward_rejects_what_it_does_not_cover(ctx):
+    import paper_1810_08403_amd as saga
+    wl = si.workload(1)
+    graph = make_graph(ctx, wl.graph)
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    A, dY, W, dW = (torch.zeros(n, F, device="cuda"), torch.zeros(n, Fo, device="cuda"), wl.W.cuda(), torch.zeros(F, Fo, device="cuda"))
+    with pytest.raises(saga.SagaError) as e:
+        ctx.layer_backward(graph, A, dY, W, dW, agg="max")
+    assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:
+        ctx.layer_backward(graph, A, dY, W, dW, act="sigmoid")
+    assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:
+        ctx.layer_backward(graph, A, dY, W, dW, edge_op="gated")
+    assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:                      # RELU without Y
+        ctx.layer_backward(graph, A, dY, W, dW, act="relu")
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # wrong gradient shape
+        ctx.layer_backward(graph, A, dY, W, torch.zeros(F, Fo + 1, device="cuda"))
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # MUL_WEIGHT without weights
+        ctx.layer_backward(graph, A, dY, W, dW, edge_op="mul_weight")
+    assert e.value.status == 1
+    graph.destroy()
