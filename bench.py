@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--overlap", type=int, default=None, help="config5 only: 0 = streaming off")
     ap.add_argument("--hip-graph", action="store_true",
                     help="time replays of the layer recorded into a HIP graph (small, launch-bound workloads)")
+    ap.add_argument("--f32", action="store_true", help="run a bf16 workload in fp32 instead")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time saga_layer_backward (fp32 sum layers with COPY / MUL_WEIGHT edges) after the forward measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain 1 GiB device copies (k_copy_u128), to scale memory-traffic counters")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
@@ -108,6 +111,8 @@ def main():
         wl = si.workload(k, device=dev, scale=args.scale, edge_factor=args.edge_factor)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
+    if args.f32:
+        wl.dtype = "f32"
     g = wl.graph
     n, nnz = g.n, g.nnz
     has_w = wl.W.numel() > 0
@@ -207,6 +212,32 @@ def main():
         "gather_gflops": round(2.0 * nnz * f_in / (ms_gather * 1e-3) / 1e9, 1) if ms_gather > 0 else None,
         "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3)},
     }
+
+    if args.backward:
+        if wl.dtype != "f32" or args.agg != "sum" or wl.edge_op not in ("copy", "mul_weight") or not has_w or wl.act not in ("none", "relu"):
+            print("bench.py: --backward needs an fp32 sum layer with COPY / MUL_WEIGHT edges and ApplyVertex (try --f32)", file=sys.stderr)
+            sys.exit(2)
+        A = torch.empty(n, f_in, device=dev)
+        dY = si.normal_features(n, f_out, 4242, device=dev)
+        dX, dW, db = torch.empty(n, f_in, device=dev), torch.empty(f_in, f_out, device=dev), torch.empty(f_out, device=dev)
+        dWs = torch.empty(f_in, f_out, device=dev) if wl.W_self is not None else None
+        bkw = dict(X=X, Y=Y, edge_op=wl.edge_op, act=wl.act, W_self=kw.get("W_self"), dX=dX, dbias=db, dW_self=dWs)
+        ctx.layer_forward(graph, X, Y, accum_out=A, **kw)
+
+        def bstep():
+            ctx.layer_backward(graph, A, dY, kw["W"], dW, **bkw)
+
+        for _ in range(max(args.warmup, 1)):   # the first call builds the edge order grouped by source
+            bstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            bstep()
+        torch.cuda.synchronize()
+        ms_b = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["backward"] = {"ms_per_step": round(ms_b, 4), "propagated_width": min(f_in, f_out),
+                           "gteps": round(nnz / (ms_b * 1e-3) / 1e9, 4),
+                           "forward_plus_backward_ms": round(ms_b + ms_per_step, 4)}
 
     if args.cpu_seconds > 0:
         import oracle

@@ -207,7 +207,7 @@ typedef struct saga_layer_grads {
  * dW_self and may be NULL without W_self; Y is read only for RELU and may be NULL otherwise.
  * The transposed edge order (out-edges grouped by source) and its work list are built at
  * the first backward call on a graph, which synchronises the stream. Because the
- * propagation is linear, it runs at the narrower of F_in and F_out: when F_out < F_in the
+ * propagation is linear, it runs at the narrower of F_in and F_out: when F_out <= F_in the
  * rows of dZ are propagated first and multiplied by W^T afterwards (the operator motion of
  * Section 3.2 applied to the backward pass); the result is the same up to rounding order.
  * Sums are deterministic run to run.

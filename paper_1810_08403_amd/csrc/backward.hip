@@ -193,24 +193,31 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
     hipStream_t s = ctx->stream;
 
-    // backward-ApplyVertex, the activation's derivative
+    // backward-ApplyVertex: the activation's derivative and the bias gradient in one pass over the rows
     const float* dZ = static_cast<const float*>(dY->data);
     int64_t lddz = dY->ld;
-    if (vp->act == SAGA_ACT_RELU && n > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)n * Fo)) return st;
-        HIP_TRY(ctx, launch_relu_grad(dZ, lddz, static_cast<const float*>(Y->data), Y->ld, static_cast<float*>(ctx->ws_dz.p), n, Fo, s));
-        dZ = static_cast<const float*>(ctx->ws_dz.p);
-        lddz = Fo;
+    const bool relu = vp->act == SAGA_ACT_RELU;
+    if (relu || grads->dbias) {
+        float* part = nullptr;
+        if (grads->dbias) {
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo)) return st;
+            part = static_cast<float*>(ctx->ws_splitk.p);
+        }
+        if (relu)
+            if (saga_status st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fo)) return st;
+        HIP_TRY(ctx, launch_dz_colsum(dZ, lddz, relu ? static_cast<const float*>(Y->data) : nullptr, relu ? Y->ld : 0,
+                                      static_cast<float*>(ctx->ws_dz.p), n, Fo, part,
+                                      grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, s));
+        if (relu) {
+            dZ = static_cast<const float*>(ctx->ws_dz.p);
+            lddz = Fo;
+        }
     }
 
     // parameter gradients
     if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, grads->dW)) return st;
     if (grads->dW_self)
         if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, grads->dW_self)) return st;
-    if (grads->dbias) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo)) return st;
-        HIP_TRY(ctx, launch_colsum(dZ, lddz, n, Fo, static_cast<float*>(ctx->ws_splitk.p), static_cast<float*>(grads->dbias->data), s));
-    }
     if (!grads->dX || n == 0) return SAGA_OK;
 
     // the edges grouped by source, and the edge data in that order
@@ -235,7 +242,7 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 
     float* dX = static_cast<float*>(grads->dX->data);
     const int64_t lddx = grads->dX->ld;
-    if (Fo < F) {
+    if (Fo <= F) {
         // propagate the narrower rows first: dX = (T dZ) W^T + dZ W_self^T, one product with two operands
         if (saga_status st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)n * Fo)) return st;
         float* G = static_cast<float*>(ctx->ws_grad.p);

@@ -143,39 +143,82 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) voi
     }
 }
 
-// C[r][c] = sum over splits, in split order
+// C[r][c] = sum over splits. A block owns 64 consecutive elements; its four wavefronts each add
+// every fourth split in order, and wavefront 0 adds the four sums in order: the grouping is fixed
+// by n_split alone.
 __global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ part, int64_t count, int n_split, int FQ, float* __restrict__ C,
                                                     int64_t ldc)
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
-        float s = 0.f;
-        for (int k = 0; k < n_split; ++k) s += part[(int64_t)k * count + i];
-        C[(i / FQ) * ldc + (i % FQ)] = s;
-    }
+    __shared__ float red[4][64];
+    const int e = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + e;
+    float s = 0.f;
+    if (i < count)
+        for (int k = q; k < n_split; k += 4) s += part[(int64_t)k * count + i];
+    red[q][e] = s;
+    __syncthreads();
+    if (q == 0 && i < count) C[(i / FQ) * ldc + (i % FQ)] = ((red[0][e] + red[1][e]) + red[2][e]) + red[3][e];
 }
 
-// dZ = dY where Y > 0, else 0 (ReLU's derivative taken from the layer's output)
-__global__ __launch_bounds__(256) void k_relu_grad(const float* __restrict__ dY, int64_t lddy, const float* __restrict__ Y, int64_t ldy,
-                                                   float* __restrict__ dZ, int64_t rows, int F)
+// backward-ApplyVertex's elementwise part over a slab of rows: dZ = dY where Y > 0, else 0 (ReLU's
+// derivative taken from the layer's output; MASK = false: dZ is dY itself and nothing is stored),
+// and the slab's column sums of dZ for the bias gradient. A thread owns VEC consecutive columns
+// and every RL-th row of the slab (RL row lanes when the matrix is narrower than the block); the
+// row lanes' sums are added in lane order.
+template <int VEC, bool MASK>
+__global__ __launch_bounds__(256) void k_dz_colsum(const float* __restrict__ dY, int64_t lddy, const float* __restrict__ Y, int64_t ldy,
+                                                   float* __restrict__ dZ, int64_t rows, int F, int64_t R, float* __restrict__ part)
 {
-    const int64_t total = rows * F;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-        const int64_t r = i / F;
-        const int c = (int)(i % F);
-        dZ[i] = Y[r * ldy + c] > 0.f ? dY[r * lddy + c] : 0.f;
-    }
-}
-
-// part[slab][c] = sum of rows [slab * R, (slab + 1) * R) of column c, rows in order
-__global__ __launch_bounds__(256) void k_colsum_slabs(const float* __restrict__ Z, int64_t ldz, int64_t rows, int F, int64_t R,
-                                                      float* __restrict__ part)
-{
+    __shared__ float red[256 * VEC];
+    const int ncg = (F + VEC - 1) / VEC;                  // column groups
+    const int RL = ncg >= 256 ? 1 : 256 / ncg;            // row lanes
     const int64_t r0 = (int64_t)blockIdx.x * R;
     const int64_t r1 = r0 + R < rows ? r0 + R : rows;
-    for (int c = threadIdx.x; c < F; c += 256) {
-        float s = 0.f;
-        for (int64_t r = r0; r < r1; ++r) s += Z[r * ldz + c];
-        part[(int64_t)blockIdx.x * F + c] = s;
+    for (int cg0 = 0; cg0 < ncg; cg0 += 256) {            // one pass unless the matrix is wider than 256 groups
+        const int t = threadIdx.x;
+        const int cg = cg0 + (RL == 1 ? t : t % ncg), rl = RL == 1 ? 0 : t / ncg;
+        const bool live = cg < ncg && rl < RL;
+        float sum[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) sum[j] = 0.f;
+        if (live) {
+            const int c = cg * VEC;
+            for (int64_t r = r0 + rl; r < r1; r += RL) {
+                float g[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 a = *reinterpret_cast<const float4*>(dY + r * lddy + c);
+                    g[0] = a.x, g[1] = a.y, g[2] = a.z, g[3] = a.w;
+                    if (MASK) {
+                        const float4 y = *reinterpret_cast<const float4*>(Y + r * ldy + c);
+                        g[0] = y.x > 0.f ? g[0] : 0.f, g[1] = y.y > 0.f ? g[1] : 0.f;
+                        g[2] = y.z > 0.f ? g[2] : 0.f, g[3] = y.w > 0.f ? g[3] : 0.f;
+                        *reinterpret_cast<float4*>(dZ + r * F + c) = make_float4(g[0], g[1], g[2], g[3]);
+                    }
+                } else {
+                    g[0] = dY[r * lddy + c];
+                    if (MASK) {
+                        g[0] = Y[r * ldy + c] > 0.f ? g[0] : 0.f;
+                        dZ[r * F + c] = g[0];
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) sum[j] += g[j];
+            }
+        }
+        if (part) {
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) red[t * VEC + j] = sum[j];
+            __syncthreads();
+            if (live && rl == 0) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float s = 0.f;
+                    for (int l = 0; l < RL; ++l) s += red[(RL == 1 ? t : l * ncg + (cg - cg0)) * VEC + j];
+                    if (cg * VEC + j < F) part[(int64_t)blockIdx.x * F + cg * VEC + j] = s;
+                }
+            }
+        }
     }
 }
 
@@ -233,33 +276,34 @@ hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_
         e = launch_tn_cfg<256, 32, 4, 1>(a, aligned, s);
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)a.FP * a.FQ;
-    const int grid = (int)std::min<int64_t>((count + 255) / 256, 65535);
-    hipLaunchKernelGGL(k_sum_splits, dim3(grid), dim3(256), 0, s, a.part, count, a.n_split, a.FQ, C, ldc);
+    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.part, count, a.n_split, a.FQ, C, ldc);
     return hipGetLastError();
 }
 
-hipError_t launch_relu_grad(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
-                            hipStream_t s)
-{
-    const int64_t total = rows * F;
-    if (total <= 0) return hipSuccess;
-    const int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
-    hipLaunchKernelGGL(k_relu_grad, dim3(grid), dim3(256), 0, s, dY, lddy, Y, ldy, dZ, rows, F);
-    return hipGetLastError();
-}
+int64_t colsum_slabs(int64_t rows) { return std::max<int64_t>(1, std::min<int64_t>(1024, (rows + 127) / 128)); }
 
-int64_t colsum_slabs(int64_t rows) { return std::max<int64_t>(1, std::min<int64_t>(2048, (rows + 255) / 256)); }
-
-hipError_t launch_colsum(const float* Z, int64_t ldz, int64_t rows, int32_t F, float* part, float* out, hipStream_t s)
+hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
+                            float* part, float* dbias, hipStream_t s)
 {
     if (F <= 0) return hipSuccess;
+    if (!Y && !part) return hipSuccess;  // nothing to mask, nothing to sum
     const int64_t slabs = colsum_slabs(rows);
     const int64_t R = (std::max<int64_t>(rows, 1) + slabs - 1) / slabs;
-    hipLaunchKernelGGL(k_colsum_slabs, dim3((unsigned)slabs), dim3(256), 0, s, Z, ldz, rows, F, R, part);
+    const bool mask = Y != nullptr;
+    const bool vec4 = F % 4 == 0 && lddy % 4 == 0 && (!mask || ldy % 4 == 0) && (reinterpret_cast<uintptr_t>(dY) & 15u) == 0 &&
+                      (!mask || ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (reinterpret_cast<uintptr_t>(dZ) & 15u) == 0));
+    const dim3 grid((unsigned)slabs), block(256);
+    if (vec4 && mask)
+        hipLaunchKernelGGL((k_dz_colsum<4, true>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+    else if (vec4)
+        hipLaunchKernelGGL((k_dz_colsum<4, false>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+    else if (mask)
+        hipLaunchKernelGGL((k_dz_colsum<1, true>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+    else
+        hipLaunchKernelGGL((k_dz_colsum<1, false>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const int grid = (int)std::min<int64_t>((F + 255) / 256, 65535);
-    hipLaunchKernelGGL(k_sum_splits, dim3(grid), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, out, (int64_t)F);
+    if (e != hipSuccess || !part) return e;
+    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((F + 63) / 64)), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, dbias, (int64_t)F);
     return hipGetLastError();
 }
 

@@ -257,12 +257,11 @@ struct GemmTnArgs {
 };
 void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, int32_t* n_split);
 hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_t s);
-// dZ (rows x F, compact) = dY where Y > 0, else 0
-hipError_t launch_relu_grad(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
-                            hipStream_t s);
-// out[c] = sum over rows of Z[r][c]; part holds colsum_slabs(rows) x F floats
+// One pass over the gradient rows: with Y, dZ (rows x F, compact) = dY where Y > 0, else 0 (without Y
+// nothing is stored: dZ is dY); with part (colsum_slabs(rows) x F floats), dbias[c] = sum over rows of dZ[r][c].
 int64_t colsum_slabs(int64_t rows);
-hipError_t launch_colsum(const float* Z, int64_t ldz, int64_t rows, int32_t F, float* part, float* out, hipStream_t s);
+hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
+                            float* part, float* dbias, hipStream_t s);
 hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s);
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
