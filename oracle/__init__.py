@@ -66,6 +66,8 @@ def lib():
         L.saga_oracle_layer.argtypes = [ctypes.POINTER(_Args)]
         L.saga_oracle_layer_backward.restype = ctypes.c_int
         L.saga_oracle_layer_backward.argtypes = [ctypes.POINTER(_BwdArgs)]
+        L.saga_oracle_backward_sample.restype = ctypes.c_int
+        L.saga_oracle_backward_sample.argtypes = [ctypes.POINTER(_BwdArgs), _I64, _P, _P, _P, _I64, _P, _P, _P, _P]
         _lib = L
     return _lib
 
@@ -209,4 +211,34 @@ def layer_backward(col_ptr, row_idx, X, A, dY, W, edge_op="copy", edge_weight=No
     rc = lib().saga_oracle_layer_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_layer_backward rejected its arguments")
+    return out
+
+
+def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="copy", edge_weight=None, bias=None, W_self=None,
+                    act="none", want_dbias=False):
+    """layer_backward's definitions evaluated only for the rows dX[ulist] and the entries dW[f, o] in w_entries
+    (a list of (f, o) pairs), for graphs too large to do whole. A may be fp32 or fp64 (it is read as fp64).
+    Returns dict: dX, dX_abs (len(ulist) x F), dW, dW_abs (len(w_entries)), and dbias when asked for."""
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    Wv, dYv = _f32(W), _f32(dY)
+    A = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
+    n, F = A.shape
+    F_out = Wv.shape[1]
+    Xv = _f32(X)
+    assert Wv.shape == (F, F_out) and dYv.shape == (n, F_out) and (Xv is None or Xv.shape == (n, F))
+    w, bv, Ws = _f32(edge_weight), _f32(bias), _f32(W_self)
+    ul = np.ascontiguousarray(np.asarray(ulist, dtype=np.int64))
+    wf = np.ascontiguousarray(np.asarray([f for f, _ in w_entries], dtype=np.int64))
+    wo = np.ascontiguousarray(np.asarray([o for _, o in w_entries], dtype=np.int64))
+    assert ((wf >= 0) & (wf < F)).all() and ((wo >= 0) & (wo < F_out)).all()
+    out = {"dX": np.zeros((len(ul), F)), "dX_abs": np.zeros((len(ul), F)), "dW": np.zeros(len(wf)), "dW_abs": np.zeros(len(wf))}
+    if want_dbias:
+        out["dbias"] = np.empty(F_out)
+    a = _BwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(A),
+                 _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, _ptr(dYv), None, None, None, None, None, _ptr(out.get("dbias")), None)
+    rc = lib().saga_oracle_backward_sample(ctypes.byref(a), len(ul), _ptr(ul), _ptr(out["dX"]), _ptr(out["dX_abs"]),
+                                           len(wf), _ptr(wf), _ptr(wo), _ptr(out["dW"]), _ptr(out["dW_abs"]))
+    if rc != 0:
+        raise ValueError("saga_oracle_backward_sample rejected its arguments")
     return out

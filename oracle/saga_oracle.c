@@ -455,3 +455,141 @@ int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
     free(dAa);
     return 0;
 }
+
+/*
+ * The same backward definitions evaluated only where asked, for graphs too large to do
+ * whole: rows of dX for the source vertices in ulist (n_u of them, distinct), and the
+ * entries dW[w_f[i]][w_o[i]] for i < n_w. dbias is cheap and always whole (p->dbias, if
+ * given). Every pre-activation the results depend on is recomputed from A (and X, W_self)
+ * exactly as in the whole-graph form. Outputs: dX_rows, dX_rows_abs (n_u x F), dW_vals,
+ * dW_abs_vals (n_w).
+ */
+static double bwd_dz(const saga_oracle_bwd_args* p, int64_t v, int64_t o)
+{
+    const double g = (double)p->dY[v * p->F_out + o];
+    if (p->act != ACT_RELU) return g;
+    double z = p->bias ? (double)p->bias[o] : 0.0;
+    for (int64_t f = 0; f < p->F; ++f) z += p->A[v * p->F + f] * (double)p->W[f * p->F_out + o];
+    if (p->W_self)
+        for (int64_t k = 0; k < p->F; ++k) z += (double)p->X[v * p->F + k] * (double)p->W_self[k * p->F_out + o];
+    return z > 0.0 ? g : 0.0;
+}
+
+int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, const int64_t* ulist, double* dX_rows,
+                                double* dX_rows_abs, int64_t n_w, const int64_t* w_f, const int64_t* w_o, double* dW_vals,
+                                double* dW_abs_vals)
+{
+    if (!p || !p->col_ptr || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (p->edge_op != EDGE_COPY && p->edge_op != EDGE_MUL_WEIGHT) return 1;
+    if (p->edge_op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (p->W_self && !p->X) return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out;
+
+    if (p->dbias) {
+#pragma omp parallel for schedule(static)
+        for (int64_t o = 0; o < Fo; ++o) {
+            double s = 0.0;
+            for (int64_t v = 0; v < n; ++v) s += bwd_dz(p, v, o);
+            p->dbias[o] = s;
+        }
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_w; ++i) {
+        const int64_t f = w_f[i], o = w_o[i];
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            const double t = p->A[v * F + f] * bwd_dz(p, v, o);
+            s += t;
+            sa += fabs(t);
+        }
+        dW_vals[i] = s;
+        dW_abs_vals[i] = sa;
+    }
+
+    if (n_u > 0) {
+        /* which sample, if any, a source id belongs to */
+        int64_t* slot = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+        if (!slot) return 2;
+        for (int64_t u = 0; u < n; ++u) slot[u] = -1;
+        for (int64_t i = 0; i < n_u; ++i) {
+            if (ulist[i] < 0 || ulist[i] >= n || slot[ulist[i]] >= 0) { free(slot); return 1; }
+            slot[ulist[i]] = i;
+        }
+        /* the vertex's own partial gradient */
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t i = 0; i < n_u; ++i) {
+            const int64_t u = ulist[i];
+            for (int64_t f = 0; f < F; ++f) {
+                double s = 0.0, sa = 0.0;
+                if (p->W_self)
+                    for (int64_t o = 0; o < Fo; ++o) {
+                        const double t = bwd_dz(p, u, o) * (double)p->W_self[f * Fo + o];
+                        s += t;
+                        sa += fabs(t);
+                    }
+                dX_rows[i * F + f] = s;
+                dX_rows_abs[i * F + f] = sa;
+            }
+        }
+        /* every edge whose source is sampled adds w_e * (dZ[v] W^T) to that sample's row;
+         * destinations in parallel, each with a private copy of the sample rows, added up
+         * in thread order afterwards */
+        int nt = 1;
+#ifdef _OPENMP
+        nt = omp_get_max_threads();
+#endif
+        double* priv = (double*)calloc((size_t)nt * 2 * (size_t)n_u * (size_t)F, sizeof(double));
+        if (!priv) { free(slot); return 2; }
+#pragma omp parallel
+        {
+            int tid = 0;
+#ifdef _OPENMP
+            tid = omp_get_thread_num();
+#endif
+            double* mine = priv + (size_t)tid * 2 * (size_t)n_u * (size_t)F;
+            double* mine_abs = mine + (size_t)n_u * (size_t)F;
+            double* dz = (double*)malloc(sizeof(double) * (size_t)(Fo + 2 * F));
+            double* da = dz + Fo;      /* gradient of accum[v], and the same with absolute terms */
+            double* da_abs = da + F;
+#pragma omp for schedule(dynamic, 64)
+            for (int64_t v = 0; v < n; ++v) {
+                int have = 0;
+                for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                    const int64_t i = slot[p->row_idx[e]];
+                    if (i < 0) continue;
+                    if (!have) {
+                        for (int64_t o = 0; o < Fo; ++o) dz[o] = bwd_dz(p, v, o);
+                        for (int64_t f = 0; f < F; ++f) {
+                            double s = 0.0, sa = 0.0;
+                            for (int64_t o = 0; o < Fo; ++o) {
+                                const double t = dz[o] * (double)p->W[f * Fo + o];
+                                s += t;
+                                sa += fabs(t);
+                            }
+                            da[f] = s;
+                            da_abs[f] = sa;
+                        }
+                        have = 1;
+                    }
+                    const double w = p->edge_op == EDGE_MUL_WEIGHT ? (double)p->edge_w[e] : 1.0;
+                    for (int64_t f = 0; f < F; ++f) {
+                        mine[i * F + f] += w * da[f];
+                        mine_abs[i * F + f] += fabs(w) * da_abs[f];
+                    }
+                }
+            }
+            free(dz);
+        }
+        for (int t = 0; t < nt; ++t) {
+            const double* mine = priv + (size_t)t * 2 * (size_t)n_u * (size_t)F;
+            for (int64_t k = 0; k < n_u * F; ++k) {
+                dX_rows[k] += mine[k];
+                dX_rows_abs[k] += mine[(size_t)n_u * (size_t)F + k];
+            }
+        }
+        free(priv);
+        free(slot);
+    }
+    return 0;
+}

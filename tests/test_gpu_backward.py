@@ -172,3 +172,79 @@ def test_backward_rejects_what_it_does_not_cover(ctx):
         ctx.layer_backward(graph, A, dY, W, dW, edge_op="mul_weight")
     assert e.value.status == 1
     graph.destroy()
+
+
+# --------------------------------------------------------------------------
+# full sizes, default tunables, sampled rows and entries from the oracle
+# --------------------------------------------------------------------------
+
+def _sample_sources(g, count, seed):
+    """Random source vertices plus the one with most out-edges, one without any (if present), the first and last."""
+    rng = np.random.default_rng(seed)
+    od = torch.bincount(g.row_idx.long(), minlength=g.n).cpu().numpy()
+    picks = set(rng.choice(g.n, size=count, replace=False).tolist())
+    picks.update([int(od.argmax()), 0, g.n - 1])
+    zero = np.nonzero(od == 0)[0]
+    if len(zero):
+        picks.add(int(zero[0]))
+    return np.array(sorted(picks), dtype=np.int64)
+
+
+def test_backward_config2_full_size_both_layers():
+    """The two GCN layers of configuration 2 (500 -> 16 -> 3) at full size; A of each layer comes from the oracle-checked
+    forward kernel's accum_out, and is an input to both sides."""
+    import paper_1810_08403_amd as saga
+    wl = si.workload(2, device="cuda")
+    g = wl.graph
+    n = g.n
+    assert n == 131072
+    cp, ri, w = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), wl.edge_weight.cpu().numpy()
+    with new_context() as ctx:
+        graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+        graph.set_edge_data(wl.edge_weight)
+        for (F, Fo, W, act, seed) in [(500, 16, wl.W, "relu", 1), (16, 3, wl.extra["W2"], "none", 2)]:
+            A = si.normal_features(n, F, 100 + seed, device="cuda")       # a synthetic Gather output: backward takes it as given
+            b = si.uniform_pm(Fo, 0.3, 7, device="cuda")
+            Y = torch.relu(A.double() @ W.double() + b.double()).float() if act == "relu" else None
+            dY = si.normal_features(n, Fo, 200 + seed, device="cuda")
+            dX, dW, db = (torch.empty(n, F, device="cuda"), torch.empty(F, Fo, device="cuda"), torch.empty(Fo, device="cuda"))
+            ctx.layer_backward(graph, A, dY, W, dW, Y=Y, edge_op="mul_weight", bias=b, act=act, dX=dX, dbias=db)
+            torch.cuda.synchronize()
+            ul = _sample_sources(g, 200, seed)
+            rng = np.random.default_rng(seed)
+            we = [(int(rng.integers(F)), int(rng.integers(Fo))) for _ in range(24)] + [(0, 0), (F - 1, Fo - 1)]
+            ref = oracle.backward_sample(cp, ri, None, A.cpu().numpy(), dY.cpu().numpy(), W.cpu().numpy(), ul, we, "mul_weight", w,
+                                         bias=b.cpu().numpy(), act=act, want_dbias=True)
+            assert_sum_close(dX[ul].cpu().numpy(), ref["dX"], ref["dX_abs"], TOL_F32, f"config 2 {F}->{Fo} dX")
+            got = np.array([dW[f, o].item() for f, o in we])
+            assert_sum_close(got, ref["dW"], ref["dW_abs"], TOL_F32, f"config 2 {F}->{Fo} dW")
+            dz_abs = (dY.double().abs() * ((Y > 0) if act == "relu" else 1)).sum(0).cpu().numpy()
+            assert_sum_close(db.cpu().numpy(), ref["dbias"], np.maximum(dz_abs, 1e-30), TOL_F32, f"config 2 {F}->{Fo} dbias")
+
+
+def test_backward_config3_shape_full_size_fp32():
+    """Configuration 3's graph and widths (R-MAT 18, 130 M edges, 512 -> 256) in fp32, the precision the backward pass covers."""
+    wl = si.workload(3, device="cuda")
+    g = wl.graph
+    n, F, Fo = g.n, 512, 256
+    assert n == 262144 and g.nnz > 100_000_000
+    cp, ri, w = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), wl.edge_weight.cpu().numpy()
+    W = wl.W.float()
+    with new_context() as ctx:
+        graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+        graph.set_edge_data(wl.edge_weight)
+        A = si.normal_features(n, F, 31, device="cuda")
+        Y = torch.relu(A.double() @ W.double()).float()
+        dY = si.normal_features(n, Fo, 32, device="cuda")
+        dX, dW, db = torch.empty(n, F, device="cuda"), torch.empty(F, Fo, device="cuda"), torch.empty(Fo, device="cuda")
+        ctx.layer_backward(graph, A, dY, W, dW, Y=Y, edge_op="mul_weight", act="relu", dX=dX, dbias=db)
+        torch.cuda.synchronize()
+        ul = _sample_sources(g, 12, 3)
+        we = [(0, 0), (511, 255), (17, 200), (300, 5), (128, 128), (255, 31)]
+        ref = oracle.backward_sample(cp, ri, None, A.cpu().numpy(), dY.cpu().numpy(), W.cpu().numpy(), ul, we, "mul_weight", w, act="relu")
+        assert_sum_close(dX[ul].cpu().numpy(), ref["dX"], ref["dX_abs"], TOL_F32, "config 3 shape dX")
+        got = np.array([dW[f, o].item() for f, o in we])
+        assert_sum_close(got, ref["dW"], ref["dW_abs"], TOL_F32, "config 3 shape dW")
+        # the bias gradient against its definition on the device in fp64 (the oracle's whole-column form is too slow here)
+        dz = dY.double() * (Y > 0)
+        assert_sum_close(db.cpu().numpy(), dz.sum(0).cpu().numpy(), dz.abs().sum(0).cpu().numpy(), TOL_F32, "config 3 shape dbias")

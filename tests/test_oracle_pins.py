@@ -523,3 +523,20 @@ def test_backward_relu_mask_and_copy_edges():
     dZ = np.where(dead, 0.0, dY.astype(np.float64))
     assert np.allclose(bwd["dW"], (Adj @ X.astype(np.float64)).T @ dZ, rtol=1e-12, atol=1e-12)
     assert np.allclose(bwd["dX"], Adj.T @ (dZ @ W.astype(np.float64).T), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("act", ["none", "relu"])
+def test_sampled_backward_equals_the_whole_graph_form(act):
+    g, X, W, Ws, b, w, dY = _bwd_setup(seed=8, n=60, m=500)
+    fwd = oracle.layer(*_np(g), X, "mul_weight", w, W=W, W_self=Ws, bias=b, act="none")
+    whole = oracle.layer_backward(*_np(g), X, fwd["A"], dY, W, "mul_weight", w, bias=b, W_self=Ws, act=act)
+    ul = [0, 7, 33, 59, 12]
+    we = [(0, 0), (4, 3), (2, 1), (4, 0)]
+    part = oracle.backward_sample(*_np(g), X, fwd["A"], dY, W, ul, we, "mul_weight", w, bias=b, W_self=Ws, act=act, want_dbias=True)
+    assert np.allclose(part["dX"], whole["dX"][ul], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dX_abs"], whole["dX_abs"][ul], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dW"], [whole["dW"][f, o] for f, o in we], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dW_abs"], [whole["dW_abs"][f, o] for f, o in we], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dbias"], whole["dbias"], rtol=1e-12, atol=1e-13)
+    if act == "relu":
+        assert not np.allclose(part["dbias"], dY.astype(np.float64).sum(0))     # the mask really removes terms
