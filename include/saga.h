@@ -273,6 +273,22 @@ saga_status saga_plan_work_list(int64_t n_vertices, const int64_t* col_ptr, cons
                                 int64_t min_edges, int64_t cut_degree, int64_t stripe_rows, int32_t team,
                                 int32_t* items_out, int64_t capacity, int64_t* n_items,
                                 int64_t* n_team_items, int64_t* n_split_vertices, int64_t* n_slots);
+/*
+ * Host-only planning call (no GPU needed): a re-encoding of the vertex ids that evens out the
+ * numbers of edges in the edge chunks of a dst_intervals x src_intervals tiling (Section 3.1
+ * re-encodes ids, best effort, for that purpose; it does not say how). Here: vertices are ranked
+ * by in-degree + out-degree, heaviest first, ties in an order drawn from `seed`, and dealt to the
+ * src_intervals id intervals in alternating (boustrophedon) order, so that every interval
+ * receives about the same total degree and the runs of heavy vertices that a skewed graph has at
+ * neighbouring ids are spread over all intervals. new_id[v] (int32 [n], a permutation of 0..n-1)
+ * is the id vertex v gets; the caller relabels its graph, features and edge data. before / after
+ * (int64 [3] each, nullable) receive the largest and smallest chunk edge counts and the number of
+ * chunks of the tiling with equal intervals, for the given and for the re-encoded ids.
+ * Requires 1 <= dst_intervals <= src_intervals <= n.
+ */
+saga_status saga_plan_reencoding(int64_t n_vertices, const int64_t* col_ptr, const int32_t* row_idx,
+                                 int32_t dst_intervals, int32_t src_intervals, uint64_t seed,
+                                 int32_t* new_id, int64_t* before, int64_t* after);
 const char* saga_version(void);
 
 #ifdef __cplusplus

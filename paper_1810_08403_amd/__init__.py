@@ -6,7 +6,7 @@ does not load the library; the first call does, and fails loudly if it has
 not been built.
 """
 from .binding import (ACT, AGG, BF16, EDGE_OP, EXPORTS, F32, LIB_PATH, Context, Graph, SagaError, Timings,
-                      load_library, plan_work_list, version)
+                      load_library, plan_reencoding, plan_work_list, version)
 
 __all__ = ["ACT", "AGG", "BF16", "EDGE_OP", "EXPORTS", "F32", "LIB_PATH", "Context", "Graph", "SagaError",
-           "Timings", "load_library", "plan_work_list", "version"]
+           "Timings", "load_library", "plan_reencoding", "plan_work_list", "version"]

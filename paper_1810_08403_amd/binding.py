@@ -30,7 +30,7 @@ MEM_DEVICE, MEM_HOST = 0, 1
 EXPORTS = ["saga_create", "saga_destroy", "saga_graph_create_csc", "saga_graph_destroy",
            "saga_graph_set_edge_data", "saga_layer_forward", "saga_layer_backward", "saga_set_profiling", "saga_reset_timings",
            "saga_get_timings", "saga_set_option", "saga_peak_device_bytes", "saga_last_error",
-           "saga_graph_info", "saga_plan_work_list", "saga_copy_bytes", "saga_version"]
+           "saga_graph_info", "saga_plan_work_list", "saga_plan_reencoding", "saga_copy_bytes", "saga_version"]
 
 
 class SagaError(RuntimeError):
@@ -350,6 +350,25 @@ def plan_work_list(col_ptr: torch.Tensor, row_idx: torch.Tensor, min_edges=64, c
     if st != SAGA_OK:
         raise SagaError(st, "saga_plan_work_list")
     return items, {"n_items": a.value, "n_team_items": t.value, "n_split_vertices": b.value, "n_slots": c.value}
+
+
+def plan_reencoding(col_ptr: torch.Tensor, row_idx: torch.Tensor, dst_intervals: int, src_intervals: int, seed: int = 0):
+    """Host-only: new_id (int32 tensor [n]) that evens out the chunk edge counts of the tiling, and
+    (max, min, chunks) of the chunk edge counts before and after."""
+    L = load_library()
+    assert not col_ptr.is_cuda and col_ptr.dtype == torch.int64 and row_idx.dtype == torch.int32
+    L.saga_plan_reencoding.restype = ctypes.c_int32
+    L.saga_plan_reencoding.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    n = col_ptr.numel() - 1
+    new_id = torch.empty(n, dtype=torch.int32)
+    before, after = (ctypes.c_int64 * 3)(), (ctypes.c_int64 * 3)()
+    st = L.saga_plan_reencoding(n, col_ptr.data_ptr(), row_idx.data_ptr(), dst_intervals, src_intervals, seed,
+                                new_id.data_ptr(), before, after)
+    if st != SAGA_OK:
+        raise SagaError(st, "saga_plan_reencoding")
+    keys = ("max_chunk_edges", "min_chunk_edges", "chunks")
+    return new_id, {"before": dict(zip(keys, before)), "after": dict(zip(keys, after))}
 
 
 def version() -> str:

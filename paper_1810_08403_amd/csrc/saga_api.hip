@@ -332,6 +332,70 @@ saga_status saga_plan_work_list(int64_t n, const int64_t* col_ptr, const int32_t
     return SAGA_OK;
 }
 
+saga_status saga_plan_reencoding(int64_t n, const int64_t* col_ptr, const int32_t* row_idx, int32_t Q, int32_t P, uint64_t seed,
+                                 int32_t* new_id, int64_t* before, int64_t* after)
+{
+    if (n < 1 || n > 0x7fffffffLL - 1 || !col_ptr || !new_id || Q < 1 || P < Q || P > n) return SAGA_ERR_INVALID_ARG;
+    const int64_t nnz = col_ptr[n];
+    if (nnz > 0 && !row_idx) return SAGA_ERR_INVALID_ARG;
+    try {
+        // rank by total degree, ties by a hash of (seed, id)
+        std::vector<int64_t> deg((size_t)n, 0);
+        for (int64_t v = 0; v < n; ++v) {
+            deg[(size_t)v] += col_ptr[v + 1] - col_ptr[v];
+            for (int64_t e = col_ptr[v]; e < col_ptr[v + 1]; ++e) {
+                if (row_idx[e] < 0 || row_idx[e] >= n) return SAGA_ERR_BAD_GRAPH;
+                ++deg[(size_t)row_idx[e]];
+            }
+        }
+        auto mix = [](uint64_t x) {
+            x += 0x9e3779b97f4a7c15ULL;
+            x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ULL;
+            x = (x ^ (x >> 27)) * 0x94d049bb133111ebULL;
+            return x ^ (x >> 31);
+        };
+        std::vector<int32_t> order((size_t)n);
+        for (int64_t v = 0; v < n; ++v) order[(size_t)v] = (int32_t)v;
+        std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+            if (deg[(size_t)a] != deg[(size_t)b]) return deg[(size_t)a] > deg[(size_t)b];
+            const uint64_t ha = mix(seed ^ mix((uint64_t)a)), hb = mix(seed ^ mix((uint64_t)b));
+            return ha != hb ? ha < hb : a < b;
+        });
+        // deal to the P intervals of ceil(n / P) ids, forwards and backwards in turn, skipping full ones
+        const int64_t Sp = (n + P - 1) / P;
+        std::vector<int64_t> fill((size_t)P, 0);
+        auto cap = [&](int64_t g) { return std::max<int64_t>(0, std::min<int64_t>(Sp, n - g * Sp)); };
+        int64_t r = 0;
+        for (int64_t round = 0; r < n; ++round) {
+            for (int64_t k = 0; k < P && r < n; ++k) {
+                const int64_t g = (round & 1) ? P - 1 - k : k;
+                if (fill[(size_t)g] >= cap(g)) continue;
+                new_id[(size_t)order[(size_t)r++]] = (int32_t)(g * Sp + fill[(size_t)g]++);
+            }
+        }
+        // chunk edge counts of the tiling, before and after
+        const int64_t Dq = (n + Q - 1) / Q;
+        for (int pass = 0; pass < 2; ++pass) {
+            int64_t* res = pass == 0 ? before : after;
+            if (!res) continue;
+            std::vector<int64_t> cnt((size_t)Q * P, 0);
+            for (int64_t v = 0; v < n; ++v) {
+                const int64_t j = (pass == 0 ? v : (int64_t)new_id[(size_t)v]) / Dq;
+                for (int64_t e = col_ptr[v]; e < col_ptr[v + 1]; ++e) {
+                    const int64_t u = row_idx[e];
+                    ++cnt[(size_t)(j * P + (pass == 0 ? u : (int64_t)new_id[(size_t)u]) / Sp)];
+                }
+            }
+            res[0] = *std::max_element(cnt.begin(), cnt.end());
+            res[1] = *std::min_element(cnt.begin(), cnt.end());
+            res[2] = (int64_t)cnt.size();
+        }
+    } catch (...) {
+        return SAGA_ERR_INTERNAL;
+    }
+    return SAGA_OK;
+}
+
 saga_status saga_create(saga_ctx** out, int device, void* hip_stream, size_t hbm_budget_bytes)
 {
     if (!out) return SAGA_ERR_INVALID_ARG;

@@ -204,6 +204,14 @@ def csc_from_lists(n: int, edges) -> CSC:
     return build_csc(n, e[:, 0].contiguous(), e[:, 1].contiguous())
 
 
+def relabel_csc(g: CSC, new_id: torch.Tensor) -> CSC:
+    """The same graph with vertex v renamed new_id[v] (a permutation), columns sorted again."""
+    new_id = new_id.to(device=g.col_ptr.device, dtype=torch.int64)
+    deg = g.col_ptr[1:] - g.col_ptr[:-1]
+    dst = torch.repeat_interleave(torch.arange(g.n, device=g.col_ptr.device), deg)
+    return build_csc(g.n, new_id[g.row_idx.long()], new_id[dst])
+
+
 def gcn_edge_weights(g: CSC) -> torch.Tensor:
     """Static GCN edge data w_e = 1/sqrt(d_src * d_dst), d = in-degree in g.
 

@@ -140,3 +140,30 @@ def test_baseline_schedules_give_the_same_result(wl, schedule, overlap):
             assert t["bytes_h2d"] < 3 * 3 * x_bytes + 3 * 2 ** 26        # X three times per call + chunks
         if schedule == 2:
             assert t["bytes_d2h"] > 3 * x_bytes                            # accumulators swapped per chunk
+
+
+def test_reencoded_graph_gives_the_permuted_oracle_result(wl):
+    """Section 3.1's id re-encoding for chunk balance: the layer on the relabelled graph, features and edge data is the
+    layer on the original ones with its rows renamed (max: bit for bit; sum: to tolerance), and the chunks are more even."""
+    import copy
+    import paper_1810_08403_amd as saga
+    Q, P = 2, 8
+    new_id, stats = saga.plan_reencoding(wl.graph.col_ptr, wl.graph.row_idx, Q, P, seed=4)
+    assert stats["after"]["max_chunk_edges"] < stats["before"]["max_chunk_edges"]
+    w2 = copy.copy(wl)
+    w2.graph = si.relabel_csc(wl.graph, new_id)
+    w2.X = torch.empty_like(wl.X)
+    w2.X[new_id.long()] = wl.X
+    w2.edge_weight = si.gcn_edge_weights(w2.graph)
+    ctx = saga.Context(0)
+    ctx.set_option("dst_intervals", Q)
+    ctx.set_option("src_intervals", P)
+    graph = ctx.graph_create_csc(w2.graph.n, w2.graph.col_ptr, w2.graph.row_idx)
+    graph.set_edge_data(w2.edge_weight)
+    ref_max = run_oracle(wl, agg="max", with_vertex=False)        # the oracle on the ORIGINAL ids
+    A = _streamed(ctx, w2, graph, "max", with_vertex=False)
+    assert_bit_equal(A[new_id.long().numpy()], ref_max["A"], "max Gather on re-encoded ids")
+    ref = run_oracle(wl, agg="sum")
+    Y = _streamed(ctx, w2, graph, "sum")
+    assert_sum_close(Y[new_id.long().numpy()], ref["Y"], ref["Y_abs"], TOL_F32, "sum layer on re-encoded ids")
+    ctx.destroy()

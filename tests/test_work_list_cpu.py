@@ -87,3 +87,48 @@ def test_work_list_of_degenerate_graphs():
     g = si.csc_from_lists(400, [(u, 3) for u in range(300)])
     items, info = _plan(g, min_edges=64, cut_degree=128, stripe_rows=1024, team=4)
     assert info["n_team_items"] == 1 and info["n_slots"] == 0 and items[0].tolist() == [3, 0, 300, -1]
+
+
+# --------------------------------------------------------------------------
+# vertex id re-encoding for chunk balance (Section 3.1)
+# --------------------------------------------------------------------------
+
+def _chunk_counts(g, Q, P):
+    n = g.n
+    Dq, Sp = -(-n // Q), -(-n // P)
+    deg = (g.col_ptr[1:] - g.col_ptr[:-1])
+    dst = torch.repeat_interleave(torch.arange(n), deg)
+    cell = (dst // Dq) * P + g.row_idx.long() // Sp
+    return torch.bincount(cell, minlength=Q * P)
+
+
+@pytest.mark.parametrize("Q,P", [(4, 4), (1, 16), (2, 8), (3, 7)])
+def test_reencoding_is_a_permutation_that_evens_out_the_chunks(Q, P):
+    import paper_1810_08403_amd as saga
+    src, dst = si.rmat_edges(13, 16 << 13, seed=5)
+    g = si.build_csc(1 << 13, src, dst, self_loops=True)
+    new_id, stats = saga.plan_reencoding(g.col_ptr, g.row_idx, Q, P, seed=3)
+    assert torch.equal(torch.sort(new_id.long()).values, torch.arange(g.n))
+    before = _chunk_counts(g, Q, P)
+    g2 = si.relabel_csc(g, new_id)
+    after = _chunk_counts(g2, Q, P)
+    assert g2.nnz == g.nnz
+    assert stats["before"] == {"max_chunk_edges": int(before.max()), "min_chunk_edges": int(before.min()), "chunks": Q * P}
+    assert stats["after"] == {"max_chunk_edges": int(after.max()), "min_chunk_edges": int(after.min()), "chunks": Q * P}
+    mean = g.nnz / (Q * P)
+    assert before.max() > 2.0 * mean                    # R-MAT without permutation: a few chunks hold most edges
+    assert after.max() < 1.5 * mean and after.max() < 0.7 * before.max()   # what is left is the heaviest vertices themselves
+    # degrees travel with the vertices
+    assert torch.equal(g2.in_degree()[new_id.long()], g.in_degree())
+
+
+def test_reencoding_is_deterministic_in_the_seed_and_rejects_bad_tilings():
+    import paper_1810_08403_amd as saga
+    g = si.build_csc(1000, *si.uniform_edges(1000, 8000, seed=2))
+    a, _ = saga.plan_reencoding(g.col_ptr, g.row_idx, 2, 5, seed=1)
+    b, _ = saga.plan_reencoding(g.col_ptr, g.row_idx, 2, 5, seed=1)
+    c, _ = saga.plan_reencoding(g.col_ptr, g.row_idx, 2, 5, seed=2)
+    assert torch.equal(a, b) and not torch.equal(a, c)
+    for Q, P in [(0, 4), (5, 4), (1, 1001)]:
+        with pytest.raises(saga.SagaError):
+            saga.plan_reencoding(g.col_ptr, g.row_idx, Q, P)
