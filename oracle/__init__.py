@@ -51,6 +51,16 @@ class _BwdArgs(ctypes.Structure):
                 ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dW_self", _P), ("dbias", _P), ("dA", _P)]
 
 
+class _GBwdArgs(ctypes.Structure):
+    """Mirror of saga_oracle_gbwd_args in saga_oracle.c."""
+    _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
+                ("W_gate", _P), ("b_gate", _P), ("W_msg", _P), ("A", _P), ("W", _P), ("bias", _P),
+                ("F_out", _I64), ("act", _I32), ("pad_", _I32), ("dY", _P),
+                ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dbias", _P),
+                ("dW_gate", _P), ("dW_gate_abs", _P), ("db_gate", _P), ("db_gate_abs", _P),
+                ("dW_msg", _P), ("dW_msg_abs", _P)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -66,6 +76,8 @@ def lib():
         L.saga_oracle_layer.argtypes = [ctypes.POINTER(_Args)]
         L.saga_oracle_layer_backward.restype = ctypes.c_int
         L.saga_oracle_layer_backward.argtypes = [ctypes.POINTER(_BwdArgs)]
+        L.saga_oracle_gated_backward.restype = ctypes.c_int
+        L.saga_oracle_gated_backward.argtypes = [ctypes.POINTER(_GBwdArgs)]
         L.saga_oracle_backward_sample.restype = ctypes.c_int
         L.saga_oracle_backward_sample.argtypes = [ctypes.POINTER(_BwdArgs), _I64, _P, _P, _P, _I64, _P, _P, _P, _P]
         _lib = L
@@ -241,4 +253,31 @@ def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="co
                                            len(wf), _ptr(wf), _ptr(wo), _ptr(out["dW"]), _ptr(out["dW_abs"]))
     if rc != 0:
         raise ValueError("saga_oracle_backward_sample rejected its arguments")
+    return out
+
+
+def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=None, bias=None, act="none"):
+    """Gradients of one gated layer with the sum accumulator (Example 2.1 / Figure 2, Section 2.2's backward stages).
+
+    A is the forward Gather output (fp64). Returns fp64 arrays dX, dW, dbias, dW_gate (F x 2F), db_gate, dW_msg
+    (with respect to an explicit identity when W_msg is None) and the *_abs error scales of all but dbias."""
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    Xv, Wv, dYv, Wg = _f32(X), _f32(W), _f32(dY), _f32(W_gate)
+    A = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
+    n, F = Xv.shape
+    F_out = Wv.shape[1]
+    assert A.shape == (n, F) and Wv.shape == (F, F_out) and dYv.shape == (n, F_out) and Wg.shape == (F, 2 * F)
+    bg, Wm, bv = _f32(b_gate), _f32(W_msg), _f32(bias)
+    assert Wm is None or Wm.shape == (F, F)
+    out = {"dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((F, F_out)), "dW_abs": np.empty((F, F_out)),
+           "dbias": np.empty(F_out), "dW_gate": np.empty((F, 2 * F)), "dW_gate_abs": np.empty((F, 2 * F)),
+           "db_gate": np.empty(F), "db_gate_abs": np.empty(F), "dW_msg": np.empty((F, F)), "dW_msg_abs": np.empty((F, F))}
+    a = _GBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(A), _ptr(Wv), _ptr(bv),
+                  F_out, ACTS[act], 0, _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]), _ptr(out["dW_abs"]),
+                  _ptr(out["dbias"]), _ptr(out["dW_gate"]), _ptr(out["dW_gate_abs"]), _ptr(out["db_gate"]),
+                  _ptr(out["db_gate_abs"]), _ptr(out["dW_msg"]), _ptr(out["dW_msg_abs"]))
+    rc = lib().saga_oracle_gated_backward(ctypes.byref(a))
+    if rc != 0:
+        raise ValueError("saga_oracle_gated_backward rejected its arguments")
     return out

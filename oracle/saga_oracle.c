@@ -593,3 +593,165 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
     }
     return 0;
 }
+
+/*
+ * Backward pass of a gated layer (Example 2.1 / Figure 2 with the optional bias b and message
+ * matrix W_m), sum accumulator, following the backward stages of Section 2.2:
+ *
+ *   forward   s_e = W_gs x_u + W_gd x_v + b,  g_e = sigmoid(s_e),  t_u = W_m x_u,
+ *             m_e = g_e (.) t_u,  A[v] = sum of m_e over in-edges,  Y = act(A W + bias)
+ *   backward-ApplyVertex   dZ = dY (.) act'(Z), dW = A^T dZ, dbias = sum_v dZ, dA = dZ W^T
+ *   backward-Gather        every in-edge e of v receives dm_e = dA[v]
+ *   backward-ApplyEdge     dt_e = g_e (.) dm_e,  ds_e = dm_e (.) t_u (.) g_e (.) (1 - g_e);
+ *                          the source receives (ds_e through W_gs, dt_e through W_m), the destination ds_e
+ *                          through W_gd; parameters: dW_gs += ds_e x_u^T, dW_gd += ds_e x_v^T, db += ds_e,
+ *                          dW_m += dt_e x_u^T
+ *   backward-Scatter       dX[u] = sum over out-edges (W_gs^T ds_e + W_m^T dt_e) + sum over in-edges W_gd^T ds_e
+ *
+ * The per-vertex products (Section 3.2) are formed once in fp64; the per-edge sums are first
+ * collected per vertex (dPs[u], dM[u] over out-edges, dPd[v] over in-edges), which is the same
+ * sum regrouped. W_gate is F x 2F (row = output channel, columns [0,F) source, [F,2F)
+ * destination); W_msg F x F (row = output channel) or NULL for the identity, in which case
+ * dW_msg is the gradient with respect to an explicit identity matrix.
+ * Every *_abs output is the first-order error scale of its value: all sums with absolute
+ * terms, and for each use of g the rounding of its argument propagated through g' = g (1 - g).
+ */
+typedef struct saga_oracle_gbwd_args {
+    int64_t n;
+    const int64_t* col_ptr;
+    const int32_t* row_idx;
+    const float* X;
+    int64_t F;
+    const float *W_gate, *b_gate, *W_msg;
+    const double* A;
+    const float *W, *bias;
+    int64_t F_out;
+    int32_t act, pad_;
+    const float* dY;
+    double *dX, *dX_abs, *dW, *dW_abs, *dbias;
+    double *dW_gate, *dW_gate_abs, *db_gate, *db_gate_abs, *dW_msg, *dW_msg_abs;
+} saga_oracle_gbwd_args;
+
+int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
+{
+    if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (!p->dX || !p->dX_abs || !p->dW || !p->dW_abs || !p->dbias || !p->dW_gate || !p->dW_gate_abs || !p->db_gate ||
+        !p->db_gate_abs || !p->dW_msg || !p->dW_msg_abs)
+        return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out;
+    const size_t nf = (size_t)(n > 0 ? n : 1) * (size_t)F;
+    double* buf = (double*)calloc(14 * nf + (size_t)(n > 0 ? n : 1) * (size_t)Fo, sizeof(double));
+    if (!buf) return 2;
+    double *Ps = buf, *Pd = Ps + nf, *M = Pd + nf, *Psa = M + nf, *Pda = Psa + nf, *Ma = Pda + nf;
+    double *dA = Ma + nf, *dAa = dA + nf, *dPs = dAa + nf, *dPd = dPs + nf, *dM = dPd + nf;
+    double *dPsa = dM + nf, *dPda = dPsa + nf, *dMa = dPda + nf, *dZ = dMa + nf;
+    if (saga_oracle_hoist(n, p->X, F, p->W_gate, p->W_msg, Ps, Pd, M, Psa, Pda, Ma)) { free(buf); return 1; }
+
+    /* backward-ApplyVertex */
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t o = 0; o < Fo; ++o) {
+            double z = p->bias ? (double)p->bias[o] : 0.0;
+            for (int64_t f = 0; f < F; ++f) z += p->A[v * F + f] * (double)p->W[f * Fo + o];
+            const double g = (double)p->dY[v * Fo + o];
+            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+        }
+        for (int64_t f = 0; f < F; ++f) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t o = 0; o < Fo; ++o) {
+                const double t = dZ[v * Fo + o] * (double)p->W[f * Fo + o];
+                s += t;
+                sa += fabs(t);
+            }
+            dA[v * F + f] = s;
+            dAa[v * F + f] = sa;
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t fo = 0; fo < F * Fo; ++fo) {
+        const int64_t f = fo / Fo, o = fo % Fo;
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            const double t = p->A[v * F + f] * dZ[v * Fo + o];
+            s += t;
+            sa += fabs(t);
+        }
+        p->dW[fo] = s;
+        p->dW_abs[fo] = sa;
+    }
+    for (int64_t o = 0; o < Fo; ++o) {
+        double s = 0.0;
+        for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+        p->dbias[o] = s;
+    }
+
+    /* backward-Gather and backward-ApplyEdge: one feature per thread, the edges in order */
+#pragma omp parallel for schedule(static)
+    for (int64_t f = 0; f < F; ++f) {
+        const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                const int64_t u = p->row_idx[e];
+                const double s = Ps[u * F + f] + Pd[v * F + f] + b;
+                const double Za = Psa[u * F + f] + Pda[v * F + f] + fabs(b);
+                const double g = sigmoid(s), t = M[u * F + f], Ta = Ma[u * F + f];
+                const double da = dA[v * F + f], daa = dAa[v * F + f];
+                dM[u * F + f] += g * da;
+                dMa[u * F + f] += g * (daa + fabs(da) * (1.0 - g) * Za);
+                const double ds = da * t * g * (1.0 - g);
+                const double dsa = g * (1.0 - g) * (daa * fabs(t) + fabs(da) * Ta + fabs(da * t) * fabs(1.0 - 2.0 * g) * Za);
+                dPs[u * F + f] += ds;
+                dPd[v * F + f] += ds;
+                dPsa[u * F + f] += dsa;
+                dPda[v * F + f] += dsa;
+            }
+    }
+
+    /* backward-Scatter: the three per-vertex gradients through their matrices */
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < n; ++u)
+        for (int64_t k = 0; k < F; ++k) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t f = 0; f < F; ++f) {
+                const double wgs = (double)p->W_gate[f * 2 * F + k], wgd = (double)p->W_gate[f * 2 * F + F + k];
+                const double wm = p->W_msg ? (double)p->W_msg[f * F + k] : (f == k ? 1.0 : 0.0);
+                s += dPs[u * F + f] * wgs + dM[u * F + f] * wm + dPd[u * F + f] * wgd;
+                sa += dPsa[u * F + f] * fabs(wgs) + dMa[u * F + f] * fabs(wm) + dPda[u * F + f] * fabs(wgd);
+            }
+            p->dX[u * F + k] = s;
+            p->dX_abs[u * F + k] = sa;
+        }
+    /* parameter gradients of ApplyEdge */
+#pragma omp parallel for schedule(static)
+    for (int64_t fk = 0; fk < F * F; ++fk) {
+        const int64_t f = fk / F, k = fk % F;
+        double gs = 0.0, gsa = 0.0, gd = 0.0, gda = 0.0, gm = 0.0, gma = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            const double x = (double)p->X[v * F + k];
+            gs += dPs[v * F + f] * x;
+            gsa += dPsa[v * F + f] * fabs(x);
+            gd += dPd[v * F + f] * x;
+            gda += dPda[v * F + f] * fabs(x);
+            gm += dM[v * F + f] * x;
+            gma += dMa[v * F + f] * fabs(x);
+        }
+        p->dW_gate[f * 2 * F + k] = gs;
+        p->dW_gate_abs[f * 2 * F + k] = gsa;
+        p->dW_gate[f * 2 * F + F + k] = gd;
+        p->dW_gate_abs[f * 2 * F + F + k] = gda;
+        p->dW_msg[fk] = gm;
+        p->dW_msg_abs[fk] = gma;
+    }
+    for (int64_t f = 0; f < F; ++f) {
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            s += dPd[v * F + f];
+            sa += dPda[v * F + f];
+        }
+        p->db_gate[f] = s;
+        p->db_gate_abs[f] = sa;
+    }
+    free(buf);
+    return 0;
+}

@@ -226,7 +226,7 @@ __device__ __forceinline__ void team_collect(const float* red, int per_wave, int
 
 // ---------------------------------------------------------------------------
 // rows of >= 64 fragments: every lane owns RC fragments of the row, one edge
-// per wave-wide load, U edges in flight. GATED reads two fragments per edge.
+// per wave-wide load, U edges in flight. The gated forms read two fragments per edge.
 // ---------------------------------------------------------------------------
 // Source ids and edge weights are read through the constant address space with
 // wave-uniform addresses, so they arrive in scalar registers (read-only scalar
@@ -254,29 +254,48 @@ __device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, 
         fetch_ids_w<U, TAIL, false>(ridx, ew, e, e1, u, w);
 }
 
+// The per-edge function (template parameter EF). The gated forms read two rows per edge, x from
+// `src` and m from `src2`, and per-item constant rows c1 (from `dst`) and, for the gradient form, c2
+// (from `dst2`):
+//   kEfLinear    acc (+)= w_e * x
+//   kEfGate      acc (+)= sigmoid(x + c1) * m                      (forward message, and the message-part gradient)
+//   kEfGateGrad  acc  += g (1 - g) * (c2 * m),  g = sigmoid(x + c1)  (gradient with respect to the gate's argument)
+constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2;
+
+template <int AGG, int EF>
+__device__ __forceinline__ float edge_step(float acc, float w, float x, float m, float c1, float c2)
+{
+    if constexpr (EF == kEfGate) return accumulate<AGG>(acc, sigmoid_f32(x + c1), m);
+    if constexpr (EF == kEfGateGrad) {
+        const float g = sigmoid_f32(x + c1);
+        return fmaf(g * (1.0f - g), c2 * m, acc);
+    }
+    return accumulate<AGG>(acc, w, x);
+}
+
 // One group of up to U edges: issue every row load first, then consume.
 // TAIL guards each edge with the wave-uniform predicate e + k < e1.
-template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
-__device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const int F, const int (&u)[U],
-                                           const float (&w)[U], const int e, const int e1, const int (&col)[RC],
-                                           const float (&pd)[RC][VEC], float (&acc)[RC][VEC], Frag<T, VEC> (&x)[U][RC],
-                                           Frag<T, VEC> (&m)[GATED ? U : 1][GATED ? RC : 1])
+template <typename T, int VEC, int RC, int AGG, int EF, int U, bool TAIL>
+__device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const T* __restrict__ X2, const int64_t ld2,
+                                           const int (&u)[U], const int e, const int e1, const int (&col)[RC],
+                                           Frag<T, VEC> (&x)[U][RC], Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1])
 {
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         if (TAIL && e + k >= e1) continue;
         const T* row = X + (int64_t)u[k] * ld;
+        const T* row2 = X2 + (int64_t)u[k] * ld2;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
             x[k][c].load(row + col[c]);
-            if constexpr (GATED) m[k][c].load(row + F + col[c]);
+            if constexpr (EF != kEfLinear) m[k][c].load(row2 + col[c]);
         }
     }
 }
-template <typename T, int VEC, int RC, int AGG, bool GATED, int U, bool TAIL>
-__device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, const int e1, const float (&pd)[RC][VEC],
-                                             float (&acc)[RC][VEC], const Frag<T, VEC> (&x)[U][RC],
-                                             const Frag<T, VEC> (&m)[GATED ? U : 1][GATED ? RC : 1])
+template <typename T, int VEC, int RC, int AGG, int EF, int U, bool TAIL>
+__device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, const int e1, const float (&c1)[RC][VEC],
+                                             const float (&c2)[RC][VEC], float (&acc)[RC][VEC], const Frag<T, VEC> (&x)[U][RC],
+                                             const Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1])
 {
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -285,15 +304,14 @@ __device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, c
         for (int c = 0; c < RC; ++c)
 #pragma unroll
             for (int jj = 0; jj < VEC; ++jj) {
-                if constexpr (GATED)
-                    acc[c][jj] = accumulate<AGG>(acc[c][jj], sigmoid_f32(x[k][c].get(jj) + pd[c][jj]), m[k][c].get(jj));
-                else
-                    acc[c][jj] = accumulate<AGG>(acc[c][jj], w[k], x[k][c].get(jj));
+                float mv = 0.f;
+                if constexpr (EF != kEfLinear) mv = m[k][c].get(jj);
+                acc[c][jj] = edge_step<AGG, EF>(acc[c][jj], w[k], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
             }
     }
 }
 
-template <typename T, int VEC, int RC, int AGG, bool GATED>
+template <typename T, int VEC, int RC, int AGG, int EF>
 __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
 {
     ItemView it;
@@ -301,16 +319,19 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
     const int lane = threadIdx.x & 63;
     const int F = a.F;
     const int nvec = (F + VEC - 1) / VEC;
+    constexpr bool GATED = EF != kEfLinear;
     constexpr int LOADS_PER_EDGE = RC * (GATED ? 2 : 1);
     constexpr int U = (kInFlight / LOADS_PER_EDGE) > 0 ? (kInFlight / LOADS_PER_EDGE) : 1;
     const T* __restrict__ X = static_cast<const T*>(a.src);
+    const T* __restrict__ X2 = GATED ? static_cast<const T*>(a.src2) : X;
+    const int64_t ld2 = GATED ? a.ld_src2 : 0;
     const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
     const const_f32_ptr ew = GATED ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
     __shared__ float red[(kWavesPerBlock - 1) * 64 * RC * VEC];
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
         float acc[RC][VEC];
-        float pd[RC][VEC];
+        float pd[RC][VEC], c2[RC][VEC];
         bool ok[RC];
         int col[RC];
         int ldcol[RC];  // lanes past the end of the row re-read its first fragment and drop the result
@@ -323,6 +344,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
             for (int j = 0; j < VEC; ++j) {
                 acc[c][j] = identity<AGG>();
                 pd[c][j] = 0.f;
+                c2[c][j] = 0.f;
             }
             if constexpr (GATED) {
                 Frag<float, VEC> f;
@@ -330,6 +352,13 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 if (ok[c]) f.load(a.dst + (int64_t)it.v * a.ld_dst + col[c]);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) pd[c][j] = f.get(j);
+            }
+            if constexpr (EF == kEfGateGrad) {
+                Frag<float, VEC> f;
+                f.zero();
+                if (ok[c]) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col[c]);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) c2[c][j] = f.get(j);
             }
         }
         Frag<T, VEC> x[U][RC];
@@ -344,15 +373,15 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 u[k] = un[k];
                 w[k] = wn[k];
             }
-            wide_group<T, VEC, RC, AGG, GATED, U, false>(X, a.ld_src, F, u, w, e, it.e1, ldcol, pd, acc, x, m);
+            wide_group<T, VEC, RC, AGG, EF, U, false>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
             // ids of the next full group travel while this group's rows do
             if (e + 2 * U <= it.e1) fetch_ids<U, false>(ridx, ew, e + U, it.e1, un, wn);
-            wide_consume<T, VEC, RC, AGG, GATED, U, false>(w, e, it.e1, pd, acc, x, m);
+            wide_consume<T, VEC, RC, AGG, EF, U, false>(w, e, it.e1, pd, c2, acc, x, m);
         }
         if (e < it.e1) {
             fetch_ids<U, true>(ridx, ew, e, it.e1, u, w);
-            wide_group<T, VEC, RC, AGG, GATED, U, true>(X, a.ld_src, F, u, w, e, it.e1, ldcol, pd, acc, x, m);
-            wide_consume<T, VEC, RC, AGG, GATED, U, true>(w, e, it.e1, pd, acc, x, m);
+            wide_group<T, VEC, RC, AGG, EF, U, true>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
+            wide_consume<T, VEC, RC, AGG, EF, U, true>(w, e, it.e1, pd, c2, acc, x, m);
         }
         if (it.team) {  // the same for every wavefront of the block, so the barriers are uniform
 #pragma unroll
@@ -380,9 +409,10 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
 // sit side by side in one wave-wide load; a butterfly over the lane groups
 // finishes the reduction.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int AGG, bool GATED>
+template <typename T, int VEC, int AGG, int EF>
 __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const int lpr_log2)
 {
+    constexpr bool GATED = EF != kEfLinear;
     ItemView it;
     if (!fetch_item(a, &it)) return;
     const int lane = threadIdx.x & 63;
@@ -398,18 +428,31 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
     const int ldcol = colok ? col : 0;
     constexpr int U = GATED ? kInFlight / 2 : kInFlight;
     const T* __restrict__ X = static_cast<const T*>(a.src);
+    const T* __restrict__ X2 = GATED ? static_cast<const T*>(a.src2) : X;
+    const int64_t ld2 = GATED ? a.ld_src2 : 0;
     const int32_t* __restrict__ ridx = a.row_idx;
     const float* __restrict__ ew = a.edge_w;
 
-    float acc[VEC], pd[VEC];
+    float acc[VEC], pd[VEC], c2[VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = identity<AGG>();
+    for (int j = 0; j < VEC; ++j) {
+        acc[j] = identity<AGG>();
+        pd[j] = 0.f;
+        c2[j] = 0.f;
+    }
     if constexpr (GATED) {
         Frag<float, VEC> f;
         f.zero();
         if (colok) f.load(a.dst + (int64_t)it.v * a.ld_dst + col);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) pd[j] = f.get(j);
+    }
+    if constexpr (EF == kEfGateGrad) {
+        Frag<float, VEC> f;
+        f.zero();
+        if (colok) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) c2[j] = f.get(j);
     }
 
     for (int eb = it.e0; eb < it.e1; eb += 64) {
@@ -435,17 +478,15 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                 const int64_t u = __shfl(idx, s & 63);
                 w[k] = __shfl(wt, s & 63);
                 x[k].load(X + u * a.ld_src + ldcol);
-                if constexpr (GATED) m[k].load(X + u * a.ld_src + F + ldcol);
+                if constexpr (GATED) m[k].load(X2 + u * ld2 + ldcol);
             }
 #pragma unroll
             for (int k = 0; k < U; ++k)
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
-                    float r;
-                    if constexpr (GATED)
-                        r = accumulate<AGG>(acc[j], sigmoid_f32(x[k].get(j) + pd[j]), m[k].get(j));
-                    else
-                        r = accumulate<AGG>(acc[j], w[k], x[k].get(j));
+                    float mv = 0.f;
+                    if constexpr (GATED) mv = m[k].get(j);
+                    const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
                     acc[j] = ok[k] ? r : acc[j];
                 }
         }
@@ -531,7 +572,7 @@ int ceil_log2(int x)
     return l;
 }
 
-template <typename T, int VEC, int AGG, bool GATED>
+template <typename T, int VEC, int AGG, int EF>
 hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
 {
     const int nvec = (a.F + VEC - 1) / VEC;
@@ -539,13 +580,13 @@ hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(256);
     if (nvec <= 32) {
-        hipLaunchKernelGGL((k_gather_narrow<T, VEC, AGG, GATED>), grid, block, 0, s, a, ceil_log2(nvec));
+        hipLaunchKernelGGL((k_gather_narrow<T, VEC, AGG, EF>), grid, block, 0, s, a, ceil_log2(nvec));
     } else if (nvec <= 64) {
-        hipLaunchKernelGGL((k_gather_wide<T, VEC, 1, AGG, GATED>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 1, AGG, EF>), grid, block, 0, s, a);
     } else if (nvec <= 128) {
-        hipLaunchKernelGGL((k_gather_wide<T, VEC, 2, AGG, GATED>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 2, AGG, EF>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((k_gather_wide<T, VEC, 4, AGG, GATED>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_gather_wide<T, VEC, 4, AGG, EF>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }
@@ -553,13 +594,14 @@ hipError_t launch_shape(const GatherArgs& a, hipStream_t s)
 template <typename T, int VEC>
 hipError_t launch_op(const GatherArgs& a, hipStream_t s)
 {
-    if constexpr (sizeof(T) == 4) {  // the gated message is formed from fp32 hoisted rows only
+    if constexpr (sizeof(T) == 4) {  // the gated forms work on fp32 hoisted rows only
         if (a.op == SAGA_EDGE_GATED)
-            return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, true>(a, s)
-                                         : launch_shape<T, VEC, SAGA_AGG_MAX, true>(a, s);
+            return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfGate>(a, s)
+                                         : launch_shape<T, VEC, SAGA_AGG_MAX, kEfGate>(a, s);
+        if (a.op == kGatherOpGateGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateGrad>(a, s);
     }
-    return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, false>(a, s)
-                                 : launch_shape<T, VEC, SAGA_AGG_MAX, false>(a, s);
+    return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfLinear>(a, s)
+                                 : launch_shape<T, VEC, SAGA_AGG_MAX, kEfLinear>(a, s);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -575,9 +617,14 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.out) vec_ok = vec_ok && (a.ld_out * 4) % 16 == 0 && aligned16(a.out);
     if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
     if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
-    if (a.op == SAGA_EDGE_GATED) vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst);
+    const bool gated = a.op == SAGA_EDGE_GATED || a.op == kGatherOpGateGrad;
+    if (gated) {
+        if (!a.src2 || !a.dst || (a.op == kGatherOpGateGrad && (!a.dst2 || a.agg != SAGA_AGG_SUM))) return hipErrorInvalidValue;
+        vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst) && (a.ld_src2 * 4) % 16 == 0 && aligned16(a.src2);
+        if (a.op == kGatherOpGateGrad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);
+    }
     if (a.dtype == SAGA_F32) return vec_ok ? launch_op<float, 4>(a, s) : launch_op<float, 1>(a, s);
-    if (a.op == SAGA_EDGE_GATED) return hipErrorInvalidValue;
+    if (gated) return hipErrorInvalidValue;
     return vec_ok ? launch_op<uint16_t, 8>(a, s) : launch_op<uint16_t, 1>(a, s);
 }
 

@@ -745,6 +745,8 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         HIP_TRY(ctx, launch_gemm(hg, s));
         ga.src = ctx->ws_hoist.p;
         ga.ld_src = 3 * (int64_t)F;
+        ga.src2 = static_cast<const float*>(ctx->ws_hoist.p) + F;
+        ga.ld_src2 = 3 * (int64_t)F;
         ga.dst = static_cast<const float*>(ctx->ws_hoist.p) + 2 * F;
         ga.ld_dst = 3 * (int64_t)F;
         ga.dtype = SAGA_F32;

@@ -156,6 +156,10 @@ struct saga_graph {
 // ---------------------------------------------------------------------------
 // kernel launchers (each validates nothing: callers check shapes first)
 // ---------------------------------------------------------------------------
+// internal ApplyEdge code beside the public saga_edge_op values: the gradient of a gated message with
+// respect to the gate's argument (see the edge functions in gather.hip)
+constexpr int32_t kGatherOpGateGrad = 100;
+
 struct GatherArgs {
     const WorkItem* items;
     int64_t n_items;
@@ -163,12 +167,17 @@ struct GatherArgs {
     const int32_t* row_idx;  // source ids, local to the rows of `src`
     const float* edge_w;     // nullable (COPY)
     // LINEAR ops: src = X (dtype), ld_src elements between rows, F features.
-    // GATED: src = hoisted fp32 rows [Ps | M | Pd], ld_src = 3F; the gate's
-    // destination part is read from row (v + dst_row_offset) of `dst`.
+    // Gated forms (fp32): per edge, row u of `src` (x) and of `src2` (m); per item, row v of `dst` (c1)
+    // and, for kGatherOpGateGrad, of `dst2` (c2). Forward: src = Ps, src2 = M, dst = Pd, all inside the
+    // hoisted rows [Ps | M | Pd] with ld 3F.
     const void* src;
     int64_t ld_src;
-    const float* dst;        // GATED only
+    const void* src2;        // gated forms only
+    int64_t ld_src2;
+    const float* dst;        // gated forms only
     int64_t ld_dst;
+    const float* dst2;       // kGatherOpGateGrad only
+    int64_t ld_dst2;
     int32_t F;
     int32_t dtype;           // saga_dtype of src (GATED: F32)
     int32_t op;              // saga_edge_op

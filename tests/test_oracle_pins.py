@@ -540,3 +540,70 @@ def test_sampled_backward_equals_the_whole_graph_form(act):
     assert np.allclose(part["dbias"], whole["dbias"], rtol=1e-12, atol=1e-13)
     if act == "relu":
         assert not np.allclose(part["dbias"], dY.astype(np.float64).sum(0))     # the mask really removes terms
+
+
+# --------------------------------------------------------------------------
+# gated backward (Example 2.1 / Figure 2 through Section 2.2's backward stages)
+# --------------------------------------------------------------------------
+
+def _gated_setup(seed=3, n=30, m=170, F=4, Fo=3, with_msg=True, with_b=True):
+    g = _random_graph(n, m, seed=seed)
+    rng = np.random.default_rng(seed)
+    q = lambda a, s: (np.round(a * s) / s).astype(np.float32)          # coarse values: +- 2^-10 stays exact in fp32
+    X = q(rng.standard_normal((n, F)), 32)
+    Wg = q(rng.standard_normal((F, 2 * F)) * 0.7, 32)
+    bg = q(rng.standard_normal(F) * 0.5, 32) if with_b else None
+    Wm = q(rng.standard_normal((F, F)) * 0.7, 32) if with_msg else None
+    W = q(rng.standard_normal((F, Fo)), 32)
+    b = q(rng.standard_normal(Fo) * 0.5, 32)
+    dY = rng.standard_normal((n, Fo)).astype(np.float32)
+    return g, X, Wg, bg, Wm, W, b, dY
+
+
+@pytest.mark.parametrize("act", ["none", "relu"])
+@pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
+def test_gated_backward_equals_autograd_of_the_dense_form(act, with_msg, with_b):
+    import torch
+    g, X, Wg, bg, Wm, W, b, dY = _gated_setup(with_msg=with_msg, with_b=with_b)
+    n, F = X.shape
+    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act)
+    bwd = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act)
+    t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
+    Xt, Wgt, Wt, bt = t(X), t(Wg), t(W), t(b)
+    bgt = t(bg if with_b else np.zeros(F))
+    Wmt = t(Wm if with_msg else np.eye(F))
+    Adj = torch.tensor(_dense_adj(g))                                    # Adj[v, u] = 1 for an edge u -> v
+    Ps, Pd, M = Xt @ Wgt[:, :F].T, Xt @ Wgt[:, F:].T, Xt @ Wmt.T
+    gate = torch.sigmoid(Ps[None, :, :] + Pd[:, None, :] + bgt)           # [v, u, f]
+    A = (Adj[:, :, None] * gate * M[None, :, :]).sum(1)
+    Z = A @ Wt + bt
+    Y = torch.relu(Z) if act == "relu" else Z
+    assert np.allclose(Y.detach().numpy(), fwd["Y"], rtol=1e-12, atol=1e-12)
+    (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
+    for name, ref in [("dX", Xt.grad), ("dW", Wt.grad), ("dbias", bt.grad), ("dW_gate", Wgt.grad), ("db_gate", bgt.grad),
+                      ("dW_msg", Wmt.grad)]:
+        assert np.allclose(bwd[name], ref.numpy(), rtol=1e-10, atol=1e-11), name
+    for name in ["dX", "dW", "dW_gate", "db_gate", "dW_msg"]:
+        assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name    # a scale bounds its value
+
+
+def test_gated_backward_matches_finite_differences_of_the_naive_forward_oracle():
+    g, X, Wg, bg, Wm, W, b, dY = _gated_setup(seed=9, n=20, m=90, F=3, Fo=2)
+    R = dY.astype(np.float64)
+    def loss(X_=X, Wg_=Wg, bg_=bg, Wm_=Wm, W_=W, b_=b):
+        return float((R * oracle.layer(*_np(g), X_, "gated", W_gate=Wg_, b_gate=bg_, W_msg=Wm_, W=W_, bias=b_, act="none")["Y"]).sum())
+    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act="none")
+    bwd = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act="none")
+    h = 2.0 ** -10
+    rng = np.random.default_rng(1)
+    def fd(name, arr, idx):
+        p, m = arr.copy(), arr.copy()
+        p[idx] += h
+        m[idx] -= h
+        return (loss(**{name: p}) - loss(**{name: m})) / (2 * h)
+    for _ in range(10):
+        u, k, f, k2 = rng.integers(g.n), rng.integers(3), rng.integers(3), rng.integers(6)
+        checks = [(fd("X_", X, (u, k)), bwd["dX"][u, k]), (fd("Wg_", Wg, (f, k2)), bwd["dW_gate"][f, k2]),
+                  (fd("bg_", bg, (f,)), bwd["db_gate"][f]), (fd("Wm_", Wm, (f, k)), bwd["dW_msg"][f, k])]
+        for num, ana in checks:                                   # central differences: error O(h^2)
+            assert abs(num - ana) <= 2e-5 * max(1.0, abs(ana)), (num, ana)
