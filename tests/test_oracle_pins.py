@@ -546,7 +546,7 @@ def test_sampled_backward_equals_the_whole_graph_form(act):
 # gated backward (Example 2.1 / Figure 2 through Section 2.2's backward stages)
 # --------------------------------------------------------------------------
 
-def _gated_setup(seed=3, n=30, m=170, F=4, Fo=3, with_msg=True, with_b=True):
+def _gated_bwd_setup(seed=3, n=30, m=170, F=4, Fo=3, with_msg=True, with_b=True):
     g = _random_graph(n, m, seed=seed)
     rng = np.random.default_rng(seed)
     q = lambda a, s: (np.round(a * s) / s).astype(np.float32)          # coarse values: +- 2^-10 stays exact in fp32
@@ -564,7 +564,7 @@ def _gated_setup(seed=3, n=30, m=170, F=4, Fo=3, with_msg=True, with_b=True):
 @pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
 def test_gated_backward_equals_autograd_of_the_dense_form(act, with_msg, with_b):
     import torch
-    g, X, Wg, bg, Wm, W, b, dY = _gated_setup(with_msg=with_msg, with_b=with_b)
+    g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(with_msg=with_msg, with_b=with_b)
     n, F = X.shape
     fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act)
     bwd = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act)
@@ -588,7 +588,7 @@ def test_gated_backward_equals_autograd_of_the_dense_form(act, with_msg, with_b)
 
 
 def test_gated_backward_matches_finite_differences_of_the_naive_forward_oracle():
-    g, X, Wg, bg, Wm, W, b, dY = _gated_setup(seed=9, n=20, m=90, F=3, Fo=2)
+    g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(seed=9, n=20, m=90, F=3, Fo=2)
     R = dY.astype(np.float64)
     def loss(X_=X, Wg_=Wg, bg_=bg, Wm_=Wm, W_=W, b_=b):
         return float((R * oracle.layer(*_np(g), X_, "gated", W_gate=Wg_, b_gate=bg_, W_msg=Wm_, W=W_, bias=b_, act="none")["Y"]).sum())
