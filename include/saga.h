@@ -187,13 +187,17 @@ typedef struct saga_layer_grads {
     saga_tensor* dW;      /* F_in x F_out: required */
     saga_tensor* dbias;   /* F_out values; NULL = not wanted */
     saga_tensor* dW_self; /* F_in x F_out: required exactly when vp->W_self is given */
+    /* GATED layers only (NULL otherwise) */
+    saga_tensor* dW_gate; /* F x 2F, laid out like W_gate: required */
+    saga_tensor* db_gate; /* F values; NULL = not wanted */
+    saga_tensor* dW_msg;  /* F x F, laid out like W_msg; NULL = not wanted; only when W_msg is given */
 } saga_layer_grads;
 
 /*
  * One layer backward (the backward stages of Section 2.2, run in reverse order of the
- * forward ones), for the layers whose ApplyEdge is linear in the source row: sum
- * accumulator, COPY or MUL_WEIGHT, fp32, ApplyVertex Y = act(A W + X W_self + bias) with
- * act NONE or RELU, everything device-resident. Other layers return SAGA_ERR_UNSUPPORTED.
+ * forward ones): sum accumulator, fp32, ApplyVertex Y = act(A W + X W_self + bias) with act
+ * NONE or RELU, everything device-resident, ApplyEdge COPY, MUL_WEIGHT or GATED (GATED
+ * without W_self). Other layers return SAGA_ERR_UNSUPPORTED.
  *
  *   backward-ApplyVertex   dZ = dY (.) act'(Z)  (ReLU: where Y > 0),  dW = A^T dZ,
  *                          dW_self = X^T dZ,  dbias = column sums of dZ,
@@ -210,6 +214,15 @@ typedef struct saga_layer_grads {
  * propagation is linear, it runs at the narrower of F_in and F_out: when F_out <= F_in the
  * rows of dZ are propagated first and multiplied by W^T afterwards (the operator motion of
  * Section 3.2 applied to the backward pass); the result is the same up to rounding order.
+ *
+ * GATED (Example 2.1 / Figure 2): with s_e = W_gs x_u + W_gd x_v + b, g_e = sigmoid(s_e),
+ * t_u = W_m x_u, backward-ApplyEdge gives every edge dt_e = g_e (.) dA[v] and
+ * ds_e = dA[v] (.) t_u (.) g_e (.) (1 - g_e). The gates are recomputed from the hoisted
+ * per-vertex products (Section 3.2), not stored per edge. Three propagation passes collect
+ * them per vertex: sum of ds_e over in-edges (destination part), sum of ds_e and of dt_e over
+ * out-edges (source parts); dense products then give dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd],
+ * dW_gate = [dPs^T X | dPd^T X], db_gate = column sums of dPd, dW_msg = dM^T X.
+ * X is required.
  * Sums are deterministic run to run.
  */
 saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,

@@ -86,48 +86,56 @@ static saga_status ensure_transposed(saga_ctx* ctx, saga_graph* g)
     return SAGA_OK;
 }
 
+// Run the propagation kernel (and the combine pass for cut groups) over one edge order of the graph:
+// `view` is the graph itself (edges grouped by destination) or its transposed twin (grouped by source).
+// ga carries the sources, constants, edge function, width and output; the work list, ids, partial rows
+// and launch options are filled in here.
+static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs ga, int64_t row_bytes)
+{
+    hipStream_t s = ctx->stream;
+    if (saga_status st = ensure_work_list(ctx, view, row_bytes)) return st;
+    ga.items = static_cast<const WorkItem*>(view->d_items.p);
+    ga.n_items = view->n_items;
+    ga.n_team = view->n_team;
+    ga.row_idx = static_cast<const int32_t*>(view->d_row_idx.p);
+    ga.dtype = SAGA_F32;
+    ga.agg = SAGA_AGG_SUM;
+    ga.xcd_remap = ctx->opt_xcd_remap;
+    if (view->n_slots > 0) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * ga.F)) return st;
+        ga.partials = static_cast<float*>(ctx->ws_partials.p);
+    }
+    HIP_TRY(ctx, launch_gather(ga, s));
+    if (view->n_heavy > 0) {
+        CombineArgs ca{};
+        ca.heavy = static_cast<const HeavyVertex*>(view->d_heavy.p);
+        ca.n_heavy = view->n_heavy;
+        ca.partials = ga.partials;
+        ca.F = ga.F;
+        ca.agg = SAGA_AGG_SUM;
+        ca.out = ga.out;
+        ca.ld_out = ga.ld_out;
+        ca.accumulate = ga.accumulate;
+        HIP_TRY(ctx, launch_combine(ca, s));
+    }
+    return SAGA_OK;
+}
+
 // rows of `src` (n x F fp32) propagated backwards over the edges into `out`:
 // out[u] (+)= sum over out-edges u -> v of w_e * src[v]
 static saga_status propagate_transposed(saga_ctx* ctx, saga_graph* g, const float* edge_w_t, const float* src, int64_t ld_src,
                                         int32_t F, float* out, int64_t ld_out, int32_t accumulate)
 {
-    saga_graph* t = g->tr;
-    hipStream_t s = ctx->stream;
-    if (saga_status st = ensure_work_list(ctx, t, (int64_t)F * 4)) return st;
     GatherArgs ga{};
-    ga.items = static_cast<const WorkItem*>(t->d_items.p);
-    ga.n_items = t->n_items;
-    ga.n_team = t->n_team;
-    ga.row_idx = static_cast<const int32_t*>(t->d_row_idx.p);
     ga.edge_w = edge_w_t;
     ga.src = src;
     ga.ld_src = ld_src;
     ga.F = F;
-    ga.dtype = SAGA_F32;
     ga.op = edge_w_t ? SAGA_EDGE_MUL_WEIGHT : SAGA_EDGE_COPY;
-    ga.agg = SAGA_AGG_SUM;
     ga.out = out;
     ga.ld_out = ld_out;
     ga.accumulate = accumulate;
-    ga.xcd_remap = ctx->opt_xcd_remap;
-    if (t->n_slots > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)t->n_slots * F)) return st;
-        ga.partials = static_cast<float*>(ctx->ws_partials.p);
-    }
-    HIP_TRY(ctx, launch_gather(ga, s));
-    if (t->n_heavy > 0) {
-        CombineArgs ca{};
-        ca.heavy = static_cast<const HeavyVertex*>(t->d_heavy.p);
-        ca.n_heavy = t->n_heavy;
-        ca.partials = ga.partials;
-        ca.F = F;
-        ca.agg = SAGA_AGG_SUM;
-        ca.out = out;
-        ca.ld_out = ld_out;
-        ca.accumulate = accumulate;
-        HIP_TRY(ctx, launch_combine(ca, s));
-    }
-    return SAGA_OK;
+    return run_propagation(ctx, g->tr, ga, (int64_t)F * 4);
 }
 
 // C[rows x N] = Arows[rows x K] * Wm[N x K]^T (+ A2 * W2[N x K2]^T): weights given with the output
@@ -168,7 +176,7 @@ static saga_status rows_times_wt(saga_ctx* ctx, const float* Arows, int64_t lda,
 }
 
 static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_t FP, const float* Q, int64_t ldq, int32_t FQ,
-                              int64_t n, saga_tensor* out)
+                              int64_t n, float* C, int64_t ldc)
 {
     GemmTnArgs ta{};
     ta.P = P;
@@ -181,7 +189,112 @@ static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_
     gemm_tn_plan(n, FP, FQ, &ta.rows_per_split, &ta.n_split);
     if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)ta.n_split * FP * FQ)) return st;
     ta.part = static_cast<float*>(ctx->ws_splitk.p);
-    HIP_TRY(ctx, launch_gemm_tn(ta, static_cast<float*>(out->data), out->ld, ctx->stream));
+    HIP_TRY(ctx, launch_gemm_tn(ta, C, ldc, ctx->stream));
+    return SAGA_OK;
+}
+
+// Everything of a gated layer's backward pass after backward-ApplyVertex's parameter gradients: the gradient of
+// accum, the three per-vertex sums of backward-ApplyEdge (gates recomputed from the hoisted products), and the dense
+// products that turn them into dX and the ApplyEdge parameter gradients.
+static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const float* dZ, int64_t lddz,
+                                       const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    hipStream_t s = ctx->stream;
+    if (n == 0) {  // sums over nothing: the parameter gradients are zero (the products below write them for zero rows)
+        float* dWg0 = static_cast<float*>(grads->dW_gate->data);
+        if (saga_status st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg0, grads->dW_gate->ld)) return st;
+        if (saga_status st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg0 + F, grads->dW_gate->ld)) return st;
+        if (grads->dW_msg)
+            if (saga_status st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, static_cast<float*>(grads->dW_msg->data),
+                                            grads->dW_msg->ld))
+                return st;
+        if (grads->db_gate) HIP_TRY(ctx, launch_fill_f32(static_cast<float*>(grads->db_gate->data), F, 0.f, s));
+        return SAGA_OK;
+    }
+    saga_status st;
+    // gradient of accum
+    if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)n * F))) return st;
+    float* dA = static_cast<float*>(ctx->ws_grad.p);
+    if ((st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W, nullptr, 0, 0, nullptr, n, F, dA, F))) return st;
+    // the per-vertex products the gates are made of
+    if ((st = hoist_gated(ctx, X, ep, n, F))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)n * 3 * F))) return st;
+    const float* H = static_cast<const float*>(ctx->ws_hoist.p);
+    float* dH = static_cast<float*>(ctx->ws_dh.p);
+    const int64_t ldh = 3 * (int64_t)F;
+    const int64_t row_bytes = 2 * (int64_t)F * 4;
+    if ((st = ensure_transposed(ctx, g))) return st;
+
+    GatherArgs ga{};
+    ga.F = F;
+    ga.ld_src = ga.ld_dst = ga.ld_out = ldh;
+    // destination part: dPd[v] = sum over in-edges of dA[v] (.) M[u] (.) g (1 - g), g = sigmoid(Ps[u] + Pd[v])
+    ga.op = kGatherOpGateGrad;
+    ga.src = H;
+    ga.src2 = H + F;
+    ga.ld_src2 = ldh;
+    ga.dst = H + 2 * F;
+    ga.dst2 = dA;
+    ga.ld_dst2 = F;
+    ga.out = dH + 2 * F;
+    if ((st = run_propagation(ctx, g, ga, row_bytes))) return st;
+    // source part of the gate: dPs[u] = sum over out-edges of dA[v] (.) M[u] (.) g (1 - g), g = sigmoid(Pd[v] + Ps[u])
+    ga.src = H + 2 * F;
+    ga.src2 = dA;
+    ga.ld_src2 = F;
+    ga.dst = H;
+    ga.dst2 = H + F;
+    ga.ld_dst2 = ldh;
+    ga.out = dH;
+    if ((st = run_propagation(ctx, g->tr, ga, row_bytes))) return st;
+    // message part: dM[u] = sum over out-edges of g (.) dA[v]
+    ga.op = SAGA_EDGE_GATED;
+    ga.dst2 = nullptr;
+    ga.out = dH + F;
+    if ((st = run_propagation(ctx, g->tr, ga, row_bytes))) return st;
+
+    // ApplyEdge parameter gradients
+    const float* Xp = static_cast<const float*>(X->data);
+    float* dWg = static_cast<float*>(grads->dW_gate->data);
+    if ((st = param_grad(ctx, dH, ldh, F, Xp, X->ld, F, n, dWg, grads->dW_gate->ld))) return st;
+    if ((st = param_grad(ctx, dH + 2 * F, ldh, F, Xp, X->ld, F, n, dWg + F, grads->dW_gate->ld))) return st;
+    if (grads->dW_msg)
+        if ((st = param_grad(ctx, dH + F, ldh, F, Xp, X->ld, F, n, static_cast<float*>(grads->dW_msg->data), grads->dW_msg->ld))) return st;
+    if (grads->db_gate) {
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * F))) return st;
+        HIP_TRY(ctx, launch_dz_colsum(dH + 2 * F, ldh, nullptr, 0, nullptr, n, F, static_cast<float*>(ctx->ws_splitk.p),
+                                      static_cast<float*>(grads->db_gate->data), s));
+    }
+    if (!grads->dX) return SAGA_OK;
+
+    // dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd]: one product over 3F
+    int64_t n_pad, k_pad;
+    bt_padded_shape(F, 3 * F, SAGA_F32, &n_pad, &k_pad);
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    float* bt = static_cast<float*>(ctx->ws_bt.p);
+    const float* Wg = static_cast<const float*>(ep->W_gate->data);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(Wg, ep->W_gate->ld, F, F, SAGA_F32, bt, k_pad, 0, s));
+    if (ep->W_msg)
+        HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_msg->data, ep->W_msg->ld, F, F, SAGA_F32, bt, k_pad, F, s));
+    else
+        HIP_TRY(ctx, launch_pack_bt_rows(nullptr, 0, 0, F, F, bt + F, k_pad, 0, s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(Wg + F, ep->W_gate->ld, F, F, SAGA_F32, bt, k_pad, 2 * (int64_t)F, s));
+    GemmArgs gm{};
+    gm.A = dH;
+    gm.lda = ldh;
+    gm.Bt = bt;
+    gm.ldbt = k_pad;
+    gm.C = grads->dX->data;
+    gm.ldc = grads->dX->ld;
+    gm.M = n;
+    gm.N = F;
+    gm.K = 3 * F;
+    gm.dtype = gm.out_dtype = SAGA_F32;
+    gm.act = SAGA_ACT_NONE;
+    HIP_TRY(ctx, launch_gemm(gm, s));
     return SAGA_OK;
 }
 
@@ -215,9 +328,10 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     }
 
     // parameter gradients
-    if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, grads->dW)) return st;
+    if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW->data), grads->dW->ld)) return st;
     if (grads->dW_self)
-        if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, grads->dW_self)) return st;
+        if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld)) return st;
+    if (ep->op == SAGA_EDGE_GATED) return gated_backward_rest(ctx, g, X, dZ, lddz, ep, vp, grads);
     if (!grads->dX || n == 0) return SAGA_OK;
 
     // the edges grouped by source, and the edge data in that order

@@ -304,6 +304,44 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
     return SAGA_OK;
 }
 
+// Section 3.2: H = X [Wgs^T | Wm^T | Wgd^T] (+ [0 | 0 | b]) once per vertex, into ctx->ws_hoist (n x 3F fp32)
+saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F)
+{
+    hipStream_t s = ctx->stream;
+    int64_t n_pad, k_pad;
+    bt_padded_shape(3 * F, F, SAGA_F32, &n_pad, &k_pad);
+    saga_status st;
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)(3 * F)))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * 3 * F))) return st;
+    float* bt = static_cast<float*>(ctx->ws_bt.p);
+    float* bias = static_cast<float*>(ctx->ws_bias.p);
+    const float* Wg = static_cast<const float*>(ep->W_gate->data);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)(3 * F), s));
+    HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
+    HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr,
+                                     ep->W_msg ? ep->W_msg->ld : 0, 0, F, F, bt, k_pad, F, s));
+    HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
+    if (ep->b_gate)
+        HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
+    GemmArgs hg{};
+    hg.A = X->data;
+    hg.lda = X->ld;
+    hg.Bt = bt;
+    hg.ldbt = k_pad;
+    hg.bias = bias;
+    hg.C = ctx->ws_hoist.p;
+    hg.ldc = 3 * (int64_t)F;
+    hg.M = n;
+    hg.N = 3 * F;
+    hg.K = F;
+    hg.dtype = hg.out_dtype = SAGA_F32;
+    hg.act = SAGA_ACT_NONE;
+    HIP_TRY(ctx, launch_gemm(hg, s));
+    return SAGA_OK;
+}
+
 extern "C" {
 
 const char* saga_version(void) { return kVersion; }
@@ -429,7 +467,7 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t})
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh})
         ctx->dev_free(b);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
@@ -711,38 +749,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ga.accumulate = 0;
 
     if (ep->op == SAGA_EDGE_GATED) {
-        // Section 3.2: H = X [Wgs^T | Wm^T | Wgd^T] (+ [0 | 0 | b]) once per vertex
-        int64_t n_pad, k_pad;
-        bt_padded_shape(3 * F, F, SAGA_F32, &n_pad, &k_pad);
-        saga_status st;
-        if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
-        if ((st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)(3 * F)))) return st;
-        if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * 3 * F))) return st;
-        float* bt = static_cast<float*>(ctx->ws_bt.p);
-        float* bias = static_cast<float*>(ctx->ws_bias.p);
-        const float* Wg = static_cast<const float*>(ep->W_gate->data);
-        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
-        HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)(3 * F), s));
-        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
-        HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr,
-                                         ep->W_msg ? ep->W_msg->ld : 0, 0, F, F, bt, k_pad, F, s));
-        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
-        if (ep->b_gate)
-            HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
-        GemmArgs hg{};
-        hg.A = X->data;
-        hg.lda = X->ld;
-        hg.Bt = bt;
-        hg.ldbt = k_pad;
-        hg.bias = bias;
-        hg.C = ctx->ws_hoist.p;
-        hg.ldc = 3 * (int64_t)F;
-        hg.M = n;
-        hg.N = 3 * F;
-        hg.K = F;
-        hg.dtype = hg.out_dtype = SAGA_F32;
-        hg.act = SAGA_ACT_NONE;
-        HIP_TRY(ctx, launch_gemm(hg, s));
+        if (saga_status st = hoist_gated(ctx, X, ep, n, F)) return st;
         ga.src = ctx->ws_hoist.p;
         ga.ld_src = 3 * (int64_t)F;
         ga.src2 = static_cast<const float*>(ctx->ws_hoist.p) + F;
@@ -952,8 +959,9 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
     if (g->where != SAGA_MEM_DEVICE) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs a device-resident graph");
     if (agg != SAGA_AGG_SUM) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers the sum accumulator only");
-    if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT)
-        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers COPY and MUL_WEIGHT ApplyEdge only");
+    const bool gated = ep->op == SAGA_EDGE_GATED;
+    if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT && !gated)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers COPY, MUL_WEIGHT and GATED ApplyEdge only");
     if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
         return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
     auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };
@@ -986,6 +994,25 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F_in fp32 tensor");
     if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
+    if (gated) {
+        if (vp->W_self) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the gated backward pass does not cover W_self");
+        if (!X || !dev_f32(X) || X->rows != n || X->cols != F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "GATED needs X as a device n x F fp32 tensor");
+        if (!ep->W_gate || !dev_f32(ep->W_gate) || ep->W_gate->rows != F || ep->W_gate->cols != 2 * F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_gate must be a device F x 2F fp32 tensor");
+        if (ep->b_gate && (!dev_f32(ep->b_gate) || ep->b_gate->rows * ep->b_gate->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "b_gate must be F fp32 values on the device");
+        if (ep->W_msg && (!dev_f32(ep->W_msg) || ep->W_msg->rows != F || ep->W_msg->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_msg must be a device F x F fp32 tensor");
+        if (!grads->dW_gate || !dev_f32(grads->dW_gate) || grads->dW_gate->rows != F || grads->dW_gate->cols != 2 * F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_gate must be a device F x 2F fp32 tensor");
+        if (grads->db_gate && (!dev_f32(grads->db_gate) || grads->db_gate->rows * grads->db_gate->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->db_gate must be F fp32 values on the device");
+        if (grads->dW_msg && (!ep->W_msg || !dev_f32(grads->dW_msg) || grads->dW_msg->rows != F || grads->dW_msg->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_msg must be a device F x F fp32 tensor, and needs W_msg");
+    } else if (grads->dW_gate || grads->db_gate || grads->dW_msg) {
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "gate gradients are for GATED layers only");
+    }
     DeviceGuard guard(ctx->device);
     return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
 }

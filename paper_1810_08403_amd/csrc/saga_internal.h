@@ -96,6 +96,7 @@ struct saga_ctx {
     DevBuf ws_grad;      // gradient rows between the dense product and the propagation kernel
     DevBuf ws_splitk;    // per-split partials of the parameter gradients and of the bias column sums
     DevBuf ws_edge_t;    // per-call edge weights in the order of the transposed graph
+    DevBuf ws_dh;        // gated layers: per-vertex gradients [dPs | dM | dPd]
 
     // profiling
     bool profiling = false;
@@ -276,6 +277,8 @@ hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream
 
 // resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
 saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes);
+// per-vertex products of a gated ApplyEdge into ctx->ws_hoist, rows [Ps | M | Pd (+ b)] (saga_api.hip)
+saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F);
 // backward pass of a resident layer (backward.hip)
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,

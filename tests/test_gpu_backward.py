@@ -160,7 +160,7 @@ def test_backward_rejects_what_it_does_not_cover(ctx):
         ctx.layer_backward(graph, A, dY, W, dW, act="sigmoid")
     assert e.value.status == 3
     with pytest.raises(saga.SagaError) as e:
-        ctx.layer_backward(graph, A, dY, W, dW, edge_op="gated")
+        ctx.layer_backward(graph, A, dY, W, dW, edge_op="pool")
     assert e.value.status == 3
     with pytest.raises(saga.SagaError) as e:                      # RELU without Y
         ctx.layer_backward(graph, A, dY, W, dW, act="relu")
@@ -248,3 +248,87 @@ def test_backward_config3_shape_full_size_fp32():
         # the bias gradient against its definition on the device in fp64 (the oracle's whole-column form is too slow here)
         dz = dY.double() * (Y > 0)
         assert_sum_close(db.cpu().numpy(), dz.sum(0).cpu().numpy(), dz.abs().sum(0).cpu().numpy(), TOL_F32, "config 3 shape dbias")
+
+
+# --------------------------------------------------------------------------
+# gated layers (Example 2.1 / Figure 2)
+# --------------------------------------------------------------------------
+
+def _gated_backward_gpu(ctx, graph, wl, A, Y, dY, act, bias, with_b, with_msg, want_dx=True):
+    dev = "cuda"
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    nan = lambda *shape: torch.full(shape, float("nan"), device=dev)
+    f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev)
+    dW, dX, db = nan(F, Fo), (nan(n, F) if want_dx else None), nan(Fo)
+    dWg, dbg, dWm = nan(F, 2 * F), (nan(F) if with_b else None), (nan(F, F) if with_msg else None)
+    ctx.layer_backward(graph, f32(A), f32(dY), wl.W.to(dev), dW, X=wl.X.to(dev), Y=f32(Y), edge_op="gated", act=act,
+                       bias=None if bias is None else bias.to(dev), dX=dX, dbias=db,
+                       W_gate=wl.W_gate.to(dev), b_gate=wl.b_gate.to(dev) if with_b else None,
+                       W_msg=wl.W_msg.to(dev) if with_msg else None, dW_gate=dWg, db_gate=dbg, dW_msg=dWm)
+    torch.cuda.synchronize()
+    res = {"dW": dW, "dbias": db, "dW_gate": dWg}
+    if want_dx:
+        res["dX"] = dX
+    if with_b:
+        res["db_gate"] = dbg
+    if with_msg:
+        res["dW_msg"] = dWm
+    return {k: v.cpu().numpy() for k, v in res.items()}
+
+
+@pytest.mark.parametrize("F,Fo,act,with_b,with_msg", [
+    (8, 8, "relu", True, True),
+    (64, 32, "relu", True, True),
+    (128, 128, "none", True, True),       # configuration 4's widths
+    (260, 16, "relu", False, True),       # wide kernel, two fragments per lane
+    (20, 12, "relu", True, False),        # Example 2.1 exactly plus a bias: identity message matrix
+    (7, 5, "none", False, False),         # nothing aligned
+])
+def test_gated_backward_matches_oracle(ctx, F, Fo, act, with_b, with_msg):
+    wl = si.workload(4, scale=10, f_in=F, f_out=Fo)
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    bias = si.uniform_pm(Fo, 0.3, 5)
+    dY = si.normal_features(n, Fo, 99)
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy() if with_b else None, W_msg=wl.W_msg.numpy() if with_msg else None)
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
+    bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
+    graph = make_graph(ctx, g)
+    res = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg)
+    what = f"gated {F}->{Fo} {act}"
+    assert_sum_close(res["dW"], bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+    assert_sum_close(res["dX"], bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    assert_sum_close(res["dW_gate"], bwd["dW_gate"], bwd["dW_gate_abs"], TOL_F32, what + " dW_gate")
+    if with_b:
+        assert_sum_close(res["db_gate"], bwd["db_gate"], bwd["db_gate_abs"], TOL_F32, what + " db_gate")
+    if with_msg:
+        assert_sum_close(res["dW_msg"], bwd["dW_msg"], bwd["dW_msg_abs"], TOL_F32, what + " dW_msg")
+    # without dX the parameter gradients are the same bits
+    res2 = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg, want_dx=False)
+    assert np.array_equal(res2["dW_gate"], res["dW_gate"]) and np.array_equal(res2["dW"], res["dW"])
+    graph.destroy()
+
+
+def test_gated_backward_rejects_what_it_does_not_cover(ctx):
+    import paper_1810_08403_amd as saga
+    wl = si.workload(4, scale=8, f_in=16, f_out=16)
+    graph = make_graph(ctx, wl.graph)
+    n, F = wl.X.shape
+    z = lambda *s: torch.zeros(*s, device="cuda")
+    kw = dict(X=wl.X.cuda(), edge_op="gated", W_gate=wl.W_gate.cuda(), dW_gate=z(F, 2 * F))
+    with pytest.raises(saga.SagaError) as e:                      # dW_msg without W_msg
+        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), dW_msg=z(F, F), **kw)
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # W_self is not covered
+        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), W_self=z(F, 16), dW_self=z(F, 16), **kw)
+    assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:                      # gate gradients on a linear layer
+        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), dW_gate=z(F, 2 * F))
+    assert e.value.status == 1
+    kw.pop("dW_gate")
+    with pytest.raises(saga.SagaError) as e:                      # dW_gate is required
+        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), **kw)
+    assert e.value.status == 1
+    graph.destroy()
