@@ -101,9 +101,11 @@ static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs g
     ga.dtype = SAGA_F32;
     ga.agg = SAGA_AGG_SUM;
     ga.xcd_remap = ctx->opt_xcd_remap;
+    const bool two = ga.op == kGatherOpGateBoth;
     if (view->n_slots > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * ga.F)) return st;
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * ga.F * (two ? 2 : 1))) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
+        if (two) ga.partials2 = ga.partials + (size_t)view->n_slots * ga.F;
     }
     HIP_TRY(ctx, launch_gather(ga, s));
     if (view->n_heavy > 0) {
@@ -117,6 +119,12 @@ static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs g
         ca.ld_out = ga.ld_out;
         ca.accumulate = ga.accumulate;
         HIP_TRY(ctx, launch_combine(ca, s));
+        if (two) {
+            ca.partials = ga.partials2;
+            ca.out = ga.out2;
+            ca.ld_out = ga.ld_out2;
+            HIP_TRY(ctx, launch_combine(ca, s));
+        }
     }
     return SAGA_OK;
 }
@@ -240,7 +248,9 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     ga.ld_dst2 = F;
     ga.out = dH + 2 * F;
     if ((st = run_propagation(ctx, g, ga, row_bytes))) return st;
-    // source part of the gate: dPs[u] = sum over out-edges of dA[v] (.) M[u] (.) g (1 - g), g = sigmoid(Pd[v] + Ps[u])
+    // source parts, both from one pass over the out-edges (the same two rows are loaded per edge):
+    //   dPs[u] = sum of dA[v] (.) M[u] (.) g (1 - g),  dM[u] = sum of g (.) dA[v],  g = sigmoid(Pd[v] + Ps[u])
+    ga.op = kGatherOpGateBoth;
     ga.src = H + 2 * F;
     ga.src2 = dA;
     ga.ld_src2 = F;
@@ -248,11 +258,8 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     ga.dst2 = H + F;
     ga.ld_dst2 = ldh;
     ga.out = dH;
-    if ((st = run_propagation(ctx, g->tr, ga, row_bytes))) return st;
-    // message part: dM[u] = sum over out-edges of g (.) dA[v]
-    ga.op = SAGA_EDGE_GATED;
-    ga.dst2 = nullptr;
-    ga.out = dH + F;
+    ga.out2 = dH + F;
+    ga.ld_out2 = ldh;
     if ((st = run_propagation(ctx, g->tr, ga, row_bytes))) return st;
 
     // ApplyEdge parameter gradients

@@ -116,6 +116,22 @@ __device__ __forceinline__ int64_t logical_block(int remap)
 
 template <int VEC>
 __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, int col0, const float (&val)[VEC],
+                                          int agg, bool empty_column);
+
+// The second row of the two-output edge function: same rules, its own destinations, fp32 only.
+template <int VEC>
+__device__ __forceinline__ void store_row2(const GatherArgs& a, int v, int slot, int col0, const float (&val)[VEC])
+{
+    GatherArgs b = a;
+    b.out = a.out2;
+    b.ld_out = a.ld_out2;
+    b.partials = a.partials2;
+    b.out16 = nullptr;
+    store_row<VEC>(b, v, slot, col0, val, SAGA_AGG_SUM, false);
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, int col0, const float (&val)[VEC],
                                           int agg, bool empty_column)
 {
     // col0: first feature of this lane's fragment
@@ -260,7 +276,8 @@ __device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, 
 //   kEfLinear    acc (+)= w_e * x
 //   kEfGate      acc (+)= sigmoid(x + c1) * m                      (forward message, and the message-part gradient)
 //   kEfGateGrad  acc  += g (1 - g) * (c2 * m),  g = sigmoid(x + c1)  (gradient with respect to the gate's argument)
-constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2;
+//   kEfGateBoth  both of the above at once from the same loads: acc += g (1 - g) * (c2 * m), acc2 += g * m
+constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3;
 
 template <int AGG, int EF>
 __device__ __forceinline__ float edge_step(float acc, float w, float x, float m, float c1, float c2)
@@ -271,6 +288,12 @@ __device__ __forceinline__ float edge_step(float acc, float w, float x, float m,
         return fmaf(g * (1.0f - g), c2 * m, acc);
     }
     return accumulate<AGG>(acc, w, x);
+}
+__device__ __forceinline__ void edge_step_both(float& acc, float& acc2, float x, float m, float c1, float c2)
+{
+    const float g = sigmoid_f32(x + c1);
+    acc = fmaf(g * (1.0f - g), c2 * m, acc);
+    acc2 = fmaf(g, m, acc2);
 }
 
 // One group of up to U edges: issue every row load first, then consume.
@@ -294,7 +317,8 @@ __device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_
 }
 template <typename T, int VEC, int RC, int AGG, int EF, int U, bool TAIL>
 __device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, const int e1, const float (&c1)[RC][VEC],
-                                             const float (&c2)[RC][VEC], float (&acc)[RC][VEC], const Frag<T, VEC> (&x)[U][RC],
+                                             const float (&c2)[RC][VEC], float (&acc)[RC][VEC],
+                                             float (&acc2)[EF == kEfGateBoth ? RC : 1][VEC], const Frag<T, VEC> (&x)[U][RC],
                                              const Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1])
 {
 #pragma unroll
@@ -306,7 +330,10 @@ __device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, c
             for (int jj = 0; jj < VEC; ++jj) {
                 float mv = 0.f;
                 if constexpr (EF != kEfLinear) mv = m[k][c].get(jj);
-                acc[c][jj] = edge_step<AGG, EF>(acc[c][jj], w[k], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
+                if constexpr (EF == kEfGateBoth)
+                    edge_step_both(acc[c][jj], acc2[c][jj], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
+                else
+                    acc[c][jj] = edge_step<AGG, EF>(acc[c][jj], w[k], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
             }
     }
 }
@@ -331,8 +358,13 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
         float acc[RC][VEC];
+        float acc2[EF == kEfGateBoth ? RC : 1][VEC];
         float pd[RC][VEC], c2[RC][VEC];
         bool ok[RC];
+#pragma unroll
+        for (int c = 0; c < (EF == kEfGateBoth ? RC : 1); ++c)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc2[c][j] = 0.f;
         int col[RC];
         int ldcol[RC];  // lanes past the end of the row re-read its first fragment and drop the result
 #pragma unroll
@@ -353,7 +385,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) pd[c][j] = f.get(j);
             }
-            if constexpr (EF == kEfGateGrad) {
+            if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
                 Frag<float, VEC> f;
                 f.zero();
                 if (ok[c]) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col[c]);
@@ -376,12 +408,12 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
             wide_group<T, VEC, RC, AGG, EF, U, false>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
             // ids of the next full group travel while this group's rows do
             if (e + 2 * U <= it.e1) fetch_ids<U, false>(ridx, ew, e + U, it.e1, un, wn);
-            wide_consume<T, VEC, RC, AGG, EF, U, false>(w, e, it.e1, pd, c2, acc, x, m);
+            wide_consume<T, VEC, RC, AGG, EF, U, false>(w, e, it.e1, pd, c2, acc, acc2, x, m);
         }
         if (e < it.e1) {
             fetch_ids<U, true>(ridx, ew, e, it.e1, u, w);
             wide_group<T, VEC, RC, AGG, EF, U, true>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
-            wide_consume<T, VEC, RC, AGG, EF, U, true>(w, e, it.e1, pd, c2, acc, x, m);
+            wide_consume<T, VEC, RC, AGG, EF, U, true>(w, e, it.e1, pd, c2, acc, acc2, x, m);
         }
         if (it.team) {  // the same for every wavefront of the block, so the barriers are uniform
 #pragma unroll
@@ -395,11 +427,28 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                         store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, false);
                     }
             }
+            if constexpr (EF == kEfGateBoth) {  // the second row through the same LDS space
+                __syncthreads();
+#pragma unroll
+                for (int c = 0; c < RC; ++c) team_park<VEC>(red, 64 * RC * VEC, c * 64 + lane, ok[c], acc2[c]);
+                __syncthreads();
+                if ((threadIdx.x >> 6) == 0) {
+#pragma unroll
+                    for (int c = 0; c < RC; ++c)
+                        if (ok[c]) {
+                            team_collect<AGG, VEC>(red, 64 * RC * VEC, c * 64 + lane, acc2[c]);
+                            store_row2<VEC>(a, it.v, it.slot, col[c], acc2[c]);
+                        }
+                }
+            }
             if (cb + 64 * RC < nvec) __syncthreads();  // LDS is reused by the next block of columns
         } else {
 #pragma unroll
             for (int c = 0; c < RC; ++c)
-                if (ok[c]) store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.empty_item);
+                if (ok[c]) {
+                    store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.empty_item);
+                    if constexpr (EF == kEfGateBoth) store_row2<VEC>(a, it.v, it.slot, col[c], acc2[c]);
+                }
         }
     }
 }
@@ -433,10 +482,11 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
     const int32_t* __restrict__ ridx = a.row_idx;
     const float* __restrict__ ew = a.edge_w;
 
-    float acc[VEC], pd[VEC], c2[VEC];
+    float acc[VEC], acc2[VEC], pd[VEC], c2[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
         acc[j] = identity<AGG>();
+        acc2[j] = 0.f;
         pd[j] = 0.f;
         c2[j] = 0.f;
     }
@@ -447,7 +497,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
 #pragma unroll
         for (int j = 0; j < VEC; ++j) pd[j] = f.get(j);
     }
-    if constexpr (EF == kEfGateGrad) {
+    if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
         Frag<float, VEC> f;
         f.zero();
         if (colok) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col);
@@ -486,14 +536,24 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                 for (int j = 0; j < VEC; ++j) {
                     float mv = 0.f;
                     if constexpr (GATED) mv = m[k].get(j);
-                    const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
-                    acc[j] = ok[k] ? r : acc[j];
+                    if constexpr (EF == kEfGateBoth) {
+                        float r = acc[j], r2 = acc2[j];
+                        edge_step_both(r, r2, x[k].get(j), mv, pd[j], c2[j]);
+                        acc[j] = ok[k] ? r : acc[j];
+                        acc2[j] = ok[k] ? r2 : acc2[j];
+                    } else {
+                        const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
+                        acc[j] = ok[k] ? r : acc[j];
+                    }
                 }
         }
     }
     for (int off = lpr; off < 64; off <<= 1)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] = combine<AGG>(acc[j], __shfl_xor(acc[j], off));
+        for (int j = 0; j < VEC; ++j) {
+            acc[j] = combine<AGG>(acc[j], __shfl_xor(acc[j], off));
+            if constexpr (EF == kEfGateBoth) acc2[j] += __shfl_xor(acc2[j], off);
+        }
     if (it.team) {
         __shared__ float red[(kWavesPerBlock - 1) * 32 * VEC];
         team_park<VEC>(red, 32 * VEC, sub, grp == 0 && colok, acc);
@@ -502,8 +562,18 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
             team_collect<AGG, VEC>(red, 32 * VEC, sub, acc);
             store_row<VEC>(a, it.v, it.slot, col, acc, AGG, false);
         }
+        if constexpr (EF == kEfGateBoth) {
+            __syncthreads();
+            team_park<VEC>(red, 32 * VEC, sub, grp == 0 && colok, acc2);
+            __syncthreads();
+            if ((threadIdx.x >> 6) == 0 && grp == 0 && colok) {
+                team_collect<AGG, VEC>(red, 32 * VEC, sub, acc2);
+                store_row2<VEC>(a, it.v, it.slot, col, acc2);
+            }
+        }
     } else if (grp == 0 && colok) {
         store_row<VEC>(a, it.v, it.slot, col, acc, AGG, it.empty_item);
+        if constexpr (EF == kEfGateBoth) store_row2<VEC>(a, it.v, it.slot, col, acc2);
     }
 }
 
@@ -599,6 +669,7 @@ hipError_t launch_op(const GatherArgs& a, hipStream_t s)
             return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfGate>(a, s)
                                          : launch_shape<T, VEC, SAGA_AGG_MAX, kEfGate>(a, s);
         if (a.op == kGatherOpGateGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateGrad>(a, s);
+        if (a.op == kGatherOpGateBoth) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateBoth>(a, s);
     }
     return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfLinear>(a, s)
                                  : launch_shape<T, VEC, SAGA_AGG_MAX, kEfLinear>(a, s);
@@ -617,11 +688,16 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.out) vec_ok = vec_ok && (a.ld_out * 4) % 16 == 0 && aligned16(a.out);
     if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
     if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
-    const bool gated = a.op == SAGA_EDGE_GATED || a.op == kGatherOpGateGrad;
+    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
+    const bool gated = a.op == SAGA_EDGE_GATED || grad;
     if (gated) {
-        if (!a.src2 || !a.dst || (a.op == kGatherOpGateGrad && (!a.dst2 || a.agg != SAGA_AGG_SUM))) return hipErrorInvalidValue;
+        if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM || a.accumulate))) return hipErrorInvalidValue;
         vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst) && (a.ld_src2 * 4) % 16 == 0 && aligned16(a.src2);
-        if (a.op == kGatherOpGateGrad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);
+        if (grad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);
+        if (a.op == kGatherOpGateBoth) {
+            if (!a.out || !a.out2 || a.out16 || (a.partials && !a.partials2)) return hipErrorInvalidValue;
+            vec_ok = vec_ok && (a.ld_out2 * 4) % 16 == 0 && aligned16(a.out2) && (!a.partials2 || aligned16(a.partials2));
+        }
     }
     if (a.dtype == SAGA_F32) return vec_ok ? launch_op<float, 4>(a, s) : launch_op<float, 1>(a, s);
     if (gated) return hipErrorInvalidValue;

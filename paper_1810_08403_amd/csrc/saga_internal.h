@@ -160,6 +160,8 @@ struct saga_graph {
 // internal ApplyEdge code beside the public saga_edge_op values: the gradient of a gated message with
 // respect to the gate's argument (see the edge functions in gather.hip)
 constexpr int32_t kGatherOpGateGrad = 100;
+// ... and that gradient together with the message-part gradient, from one pass, into out / out2
+constexpr int32_t kGatherOpGateBoth = 101;
 
 struct GatherArgs {
     const WorkItem* items;
@@ -187,6 +189,9 @@ struct GatherArgs {
     int64_t ld_out;
     uint16_t* out16;         // optional bf16 copy of the rows (nullable)
     int64_t ld_out16;
+    float* out2;             // kGatherOpGateBoth only: the second row (fp32), with its own partial rows
+    int64_t ld_out2;
+    float* partials2;
     float* partials;         // n_slots x F fp32
     int32_t accumulate;      // 1: combine with what `out` already holds (streamed, chunk i > 0)
     int32_t xcd_remap;
