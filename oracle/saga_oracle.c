@@ -668,17 +668,27 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
             dAa[v * F + f] = sa;
         }
     }
-#pragma omp parallel for schedule(static)
-    for (int64_t fo = 0; fo < F * Fo; ++fo) {
-        const int64_t f = fo / Fo, o = fo % Fo;
-        double s = 0.0, sa = 0.0;
-        for (int64_t v = 0; v < n; ++v) {
-            const double t = p->A[v * F + f] * dZ[v * Fo + o];
-            s += t;
-            sa += fabs(t);
+    /* dW: one row of W per thread, every entry a sum over the vertices in order */
+#pragma omp parallel
+    {
+        double* row = (double*)malloc(sizeof(double) * 2 * (size_t)Fo);
+#pragma omp for schedule(static)
+        for (int64_t f = 0; f < F; ++f) {
+            for (int64_t o = 0; o < 2 * Fo; ++o) row[o] = 0.0;
+            for (int64_t v = 0; v < n; ++v) {
+                const double a = p->A[v * F + f];
+                for (int64_t o = 0; o < Fo; ++o) {
+                    const double t = a * dZ[v * Fo + o];
+                    row[o] += t;
+                    row[Fo + o] += fabs(t);
+                }
+            }
+            for (int64_t o = 0; o < Fo; ++o) {
+                p->dW[f * Fo + o] = row[o];
+                p->dW_abs[f * Fo + o] = row[Fo + o];
+            }
         }
-        p->dW[fo] = s;
-        p->dW_abs[fo] = sa;
+        free(row);
     }
     for (int64_t o = 0; o < Fo; ++o) {
         double s = 0.0;
@@ -686,25 +696,29 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
         p->dbias[o] = s;
     }
 
-    /* backward-Gather and backward-ApplyEdge: one feature per thread, the edges in order */
-#pragma omp parallel for schedule(static)
-    for (int64_t f = 0; f < F; ++f) {
-        const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+    /* backward-Gather and backward-ApplyEdge: a block of features per thread, the edges in order */
+    const int64_t FB = 8, nfb = (F + FB - 1) / FB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t fb = 0; fb < nfb; ++fb) {
+        const int64_t f0 = fb * FB, f1 = f0 + FB < F ? f0 + FB : F;
         for (int64_t v = 0; v < n; ++v)
             for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
                 const int64_t u = p->row_idx[e];
-                const double s = Ps[u * F + f] + Pd[v * F + f] + b;
-                const double Za = Psa[u * F + f] + Pda[v * F + f] + fabs(b);
-                const double g = sigmoid(s), t = M[u * F + f], Ta = Ma[u * F + f];
-                const double da = dA[v * F + f], daa = dAa[v * F + f];
-                dM[u * F + f] += g * da;
-                dMa[u * F + f] += g * (daa + fabs(da) * (1.0 - g) * Za);
-                const double ds = da * t * g * (1.0 - g);
-                const double dsa = g * (1.0 - g) * (daa * fabs(t) + fabs(da) * Ta + fabs(da * t) * fabs(1.0 - 2.0 * g) * Za);
-                dPs[u * F + f] += ds;
-                dPd[v * F + f] += ds;
-                dPsa[u * F + f] += dsa;
-                dPda[v * F + f] += dsa;
+                for (int64_t f = f0; f < f1; ++f) {
+                    const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+                    const double s = Ps[u * F + f] + Pd[v * F + f] + b;
+                    const double Za = Psa[u * F + f] + Pda[v * F + f] + fabs(b);
+                    const double g = sigmoid(s), t = M[u * F + f], Ta = Ma[u * F + f];
+                    const double da = dA[v * F + f], daa = dAa[v * F + f];
+                    dM[u * F + f] += g * da;
+                    dMa[u * F + f] += g * (daa + fabs(da) * (1.0 - g) * Za);
+                    const double ds = da * t * g * (1.0 - g);
+                    const double dsa = g * (1.0 - g) * (daa * fabs(t) + fabs(da) * Ta + fabs(da * t) * fabs(1.0 - 2.0 * g) * Za);
+                    dPs[u * F + f] += ds;
+                    dPd[v * F + f] += ds;
+                    dPsa[u * F + f] += dsa;
+                    dPda[v * F + f] += dsa;
+                }
             }
     }
 
@@ -722,26 +736,37 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
             p->dX[u * F + k] = s;
             p->dX_abs[u * F + k] = sa;
         }
-    /* parameter gradients of ApplyEdge */
-#pragma omp parallel for schedule(static)
-    for (int64_t fk = 0; fk < F * F; ++fk) {
-        const int64_t f = fk / F, k = fk % F;
-        double gs = 0.0, gsa = 0.0, gd = 0.0, gda = 0.0, gm = 0.0, gma = 0.0;
-        for (int64_t v = 0; v < n; ++v) {
-            const double x = (double)p->X[v * F + k];
-            gs += dPs[v * F + f] * x;
-            gsa += dPsa[v * F + f] * fabs(x);
-            gd += dPd[v * F + f] * x;
-            gda += dPda[v * F + f] * fabs(x);
-            gm += dM[v * F + f] * x;
-            gma += dMa[v * F + f] * fabs(x);
+    /* parameter gradients of ApplyEdge: one output channel per thread, every entry a sum over the vertices in order */
+#pragma omp parallel
+    {
+        double* row = (double*)malloc(sizeof(double) * 6 * (size_t)F);
+#pragma omp for schedule(static)
+        for (int64_t f = 0; f < F; ++f) {
+            for (int64_t k = 0; k < 6 * F; ++k) row[k] = 0.0;
+            double *gs = row, *gsa = row + F, *gd = row + 2 * F, *gda = row + 3 * F, *gm = row + 4 * F, *gma = row + 5 * F;
+            for (int64_t v = 0; v < n; ++v) {
+                const double a = dPs[v * F + f], aa = dPsa[v * F + f], d = dPd[v * F + f], da = dPda[v * F + f];
+                const double mm = dM[v * F + f], ma = dMa[v * F + f];
+                for (int64_t k = 0; k < F; ++k) {
+                    const double x = (double)p->X[v * F + k];
+                    gs[k] += a * x;
+                    gsa[k] += aa * fabs(x);
+                    gd[k] += d * x;
+                    gda[k] += da * fabs(x);
+                    gm[k] += mm * x;
+                    gma[k] += ma * fabs(x);
+                }
+            }
+            for (int64_t k = 0; k < F; ++k) {
+                p->dW_gate[f * 2 * F + k] = gs[k];
+                p->dW_gate_abs[f * 2 * F + k] = gsa[k];
+                p->dW_gate[f * 2 * F + F + k] = gd[k];
+                p->dW_gate_abs[f * 2 * F + F + k] = gda[k];
+                p->dW_msg[f * F + k] = gm[k];
+                p->dW_msg_abs[f * F + k] = gma[k];
+            }
         }
-        p->dW_gate[f * 2 * F + k] = gs;
-        p->dW_gate_abs[f * 2 * F + k] = gsa;
-        p->dW_gate[f * 2 * F + F + k] = gd;
-        p->dW_gate_abs[f * 2 * F + F + k] = gda;
-        p->dW_msg[fk] = gm;
-        p->dW_msg_abs[fk] = gma;
+        free(row);
     }
     for (int64_t f = 0; f < F; ++f) {
         double s = 0.0, sa = 0.0;

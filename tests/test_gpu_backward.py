@@ -332,3 +332,24 @@ def test_gated_backward_rejects_what_it_does_not_cover(ctx):
         ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), **kw)
     assert e.value.status == 1
     graph.destroy()
+
+
+def test_gated_backward_configuration_4_at_scale_16(ctx):
+    """Configuration 4's layer (gated, 128 -> 128, bias and message matrix, ReLU) on R-MAT 16 with default tunables: the
+    largest size at which the whole-graph oracle finishes in seconds (the full R-MAT 20 graph would take it minutes)."""
+    wl = si.workload(4, scale=16)
+    g = wl.graph
+    n, F = wl.X.shape
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    dY = si.normal_features(n, 128, 5)
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy(), W_msg=wl.W_msg.numpy())
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), act="relu", b_gate=okw["b_gate"],
+                       hoisted=oracle.hoist(wl.X.numpy(), okw["W_gate"], okw["W_msg"]))
+    bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), act="relu", **okw)
+    graph = make_graph(ctx, g)
+    res = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, "relu", None, True, True)
+    info = graph.info()
+    assert info["n_split_vertices"] > 0
+    for name in ["dW", "dX", "dW_gate", "db_gate", "dW_msg"]:
+        assert_sum_close(res[name], bwd[name], bwd[name + "_abs"], TOL_F32, "configuration 4 at scale 16, " + name)
+    graph.destroy()
