@@ -61,6 +61,15 @@ class _GBwdArgs(ctypes.Structure):
                 ("dW_msg", _P), ("dW_msg_abs", _P)]
 
 
+class _MBwdArgs(ctypes.Structure):
+    """Mirror of saga_oracle_mbwd_args in saga_oracle.c."""
+    _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
+                ("edge_op", _I32), ("act", _I32), ("edge_w", _P), ("W_pool", _P), ("b_pool", _P), ("F_pool", _I64),
+                ("W", _P), ("bias", _P), ("F_out", _I64), ("dY", _P), ("A", _P),
+                ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dbias", _P),
+                ("dW_pool", _P), ("dW_pool_abs", _P), ("db_pool", _P), ("db_pool_abs", _P)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -76,6 +85,8 @@ def lib():
         L.saga_oracle_layer.argtypes = [ctypes.POINTER(_Args)]
         L.saga_oracle_layer_backward.restype = ctypes.c_int
         L.saga_oracle_layer_backward.argtypes = [ctypes.POINTER(_BwdArgs)]
+        L.saga_oracle_max_backward.restype = ctypes.c_int
+        L.saga_oracle_max_backward.argtypes = [ctypes.POINTER(_MBwdArgs)]
         L.saga_oracle_gated_backward.restype = ctypes.c_int
         L.saga_oracle_gated_backward.argtypes = [ctypes.POINTER(_GBwdArgs)]
         L.saga_oracle_backward_sample.restype = ctypes.c_int
@@ -280,4 +291,32 @@ def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=Non
     rc = lib().saga_oracle_gated_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_gated_backward rejected its arguments")
+    return out
+
+
+def max_backward(col_ptr, row_idx, X, dY, W, edge_op="copy", edge_weight=None, W_pool=None, b_pool=None, bias=None, act="none"):
+    """Gradients of one max-accumulator layer (COPY, MUL_WEIGHT or POOL messages; Figure 11 and Section 2.2's backward
+    stages). Returns fp64 arrays A (the recomputed Gather output), dX, dW, dbias and, for POOL, dW_pool, db_pool, plus
+    *_abs error scales."""
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    Xv, Wv, dYv = _f32(X), _f32(W), _f32(dY)
+    n, F = Xv.shape
+    Wp, bp, w, bv = _f32(W_pool), _f32(b_pool), _f32(edge_weight), _f32(bias)
+    Fp = Wp.shape[0] if edge_op == "pool" else 0
+    Fm = Fp if edge_op == "pool" else F
+    F_out = Wv.shape[1]
+    assert Wv.shape == (Fm, F_out) and dYv.shape == (n, F_out)
+    out = {"A": np.empty((n, Fm)), "dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((Fm, F_out)),
+           "dW_abs": np.empty((Fm, F_out)), "dbias": np.empty(F_out)}
+    if edge_op == "pool":
+        assert Wp.shape == (Fp, F)
+        out.update(dW_pool=np.empty((Fp, F)), dW_pool_abs=np.empty((Fp, F)), db_pool=np.empty(Fp), db_pool_abs=np.empty(Fp))
+    a = _MBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(Wp), _ptr(bp), Fp,
+                  _ptr(Wv), _ptr(bv), F_out, _ptr(dYv), _ptr(out["A"]), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]),
+                  _ptr(out["dW_abs"]), _ptr(out["dbias"]), _ptr(out.get("dW_pool")), _ptr(out.get("dW_pool_abs")),
+                  _ptr(out.get("db_pool")), _ptr(out.get("db_pool_abs")))
+    rc = lib().saga_oracle_max_backward(ctypes.byref(a))
+    if rc != 0:
+        raise ValueError("saga_oracle_max_backward rejected its arguments")
     return out

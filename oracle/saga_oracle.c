@@ -780,3 +780,192 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
     free(buf);
     return 0;
 }
+
+/*
+ * Backward pass of a layer with the max accumulator (the max-pooling GCN of Figure 11, and max
+ * over COPY / MUL_WEIGHT messages), through the backward stages of Section 2.2.
+ *
+ *   forward   m_e = x_u (COPY), w_e x_u (MUL_WEIGHT, one fp32 multiply), sigmoid(W_p x_u + b_p) (POOL);
+ *             A[v][f] = max over in-edges of m_e[f] (0 without in-edges);  Y = act(A W + bias)
+ *   backward-ApplyVertex   dZ, dW = A^T dZ, dbias, dA = dZ W^T as for the sum layers
+ *   backward-Gather        the gradient of A[v][f] goes to every in-edge whose message equals the
+ *                          maximum (the paper does not say what happens on ties; here every
+ *                          maximal edge receives the whole gradient, nothing is divided)
+ *   backward-ApplyEdge     times w_e (MUL_WEIGHT); POOL: through the sigmoid, per vertex because the
+ *                          message depends on the source only: dPre[u] = dS[u] (.) h_u (.) (1 - h_u)
+ *   backward-Scatter       dS[u] = sum over out-edges of what they received; COPY / MUL_WEIGHT: dX = dS;
+ *                          POOL: dX = dPre W_p, dW_pool = dPre^T X, db_pool = sum_u dPre[u]
+ *
+ * A is recomputed here from the same definitions as the forward oracle (max decisions in the
+ * precision of the messages: fp32 products for MUL_WEIGHT, fp64 sigmoids for POOL).
+ * *_abs: error scales (sums of absolute terms; for POOL the rounding of the sigmoid's argument
+ * carried through h' and h'').
+ */
+typedef struct saga_oracle_mbwd_args {
+    int64_t n;
+    const int64_t* col_ptr;
+    const int32_t* row_idx;
+    const float* X;
+    int64_t F;
+    int32_t edge_op, act;
+    const float* edge_w;
+    const float *W_pool, *b_pool;
+    int64_t F_pool;
+    const float *W, *bias;
+    int64_t F_out;
+    const float* dY;
+    double *A;                       /* n x Fm out (nullable): the recomputed Gather output */
+    double *dX, *dX_abs;             /* n x F */
+    double *dW, *dW_abs, *dbias;     /* Fm x F_out, F_out */
+    double *dW_pool, *dW_pool_abs;   /* F_pool x F (POOL) */
+    double *db_pool, *db_pool_abs;   /* F_pool (POOL) */
+} saga_oracle_mbwd_args;
+
+int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
+{
+    if (!p || !p->col_ptr || !p->X || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    const int op = p->edge_op;
+    if (op != EDGE_COPY && op != EDGE_MUL_WEIGHT && op != EDGE_POOL) return 1;
+    if (op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
+    if (op == EDGE_POOL && (!p->W_pool || p->F_pool <= 0 || !p->dW_pool || !p->dW_pool_abs || !p->db_pool || !p->db_pool_abs)) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (!p->dX || !p->dX_abs || !p->dW || !p->dW_abs || !p->dbias) return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out, Fm = op == EDGE_POOL ? p->F_pool : F;
+    const size_t nm = (size_t)(n > 0 ? n : 1) * (size_t)Fm;
+    double* buf = (double*)calloc(8 * nm + (size_t)(n > 0 ? n : 1) * (size_t)Fo, sizeof(double));
+    if (!buf) return 2;
+    double *S = buf, *Sz = S + nm, *A = Sz + nm, *dA = A + nm, *dAa = dA + nm, *dS = dAa + nm, *dSa = dS + nm, *spare = dSa + nm;
+    double* dZ = spare + nm;
+
+    /* the per-vertex part of the message: x_u, or h_u = sigmoid(W_p x_u + b_p) with the absolute-term sum of its argument */
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < n; ++u)
+        for (int64_t c = 0; c < Fm; ++c) {
+            if (op == EDGE_POOL) {
+                double z = p->b_pool ? (double)p->b_pool[c] : 0.0, za = fabs(z);
+                for (int64_t k = 0; k < F; ++k) {
+                    const double t = (double)p->W_pool[c * F + k] * (double)p->X[u * F + k];
+                    z += t;
+                    za += fabs(t);
+                }
+                S[u * Fm + c] = sigmoid(z);
+                Sz[u * Fm + c] = za;
+            } else {
+                S[u * Fm + c] = (double)p->X[u * F + c];
+            }
+        }
+    /* Gather */
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t c = 0; c < Fm; ++c) {
+            double best = 0.0;
+            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                const int64_t u = p->row_idx[e];
+                double m = S[u * Fm + c];
+                if (op == EDGE_MUL_WEIGHT) { const float pr = p->edge_w[e] * p->X[u * F + c]; m = (double)pr; }
+                if (e == p->col_ptr[v] || m > best) best = m;
+            }
+            A[v * Fm + c] = best;
+        }
+    if (p->A) memcpy(p->A, A, sizeof(double) * (size_t)n * (size_t)Fm);
+
+    /* backward-ApplyVertex */
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t o = 0; o < Fo; ++o) {
+            double z = p->bias ? (double)p->bias[o] : 0.0;
+            for (int64_t c = 0; c < Fm; ++c) z += A[v * Fm + c] * (double)p->W[c * Fo + o];
+            const double g = (double)p->dY[v * Fo + o];
+            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+        }
+        for (int64_t c = 0; c < Fm; ++c) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t o = 0; o < Fo; ++o) {
+                const double t = dZ[v * Fo + o] * (double)p->W[c * Fo + o];
+                s += t;
+                sa += fabs(t);
+            }
+            dA[v * Fm + c] = s;
+            dAa[v * Fm + c] = sa;
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t co = 0; co < Fm * Fo; ++co) {
+        const int64_t c = co / Fo, o = co % Fo;
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            const double t = A[v * Fm + c] * dZ[v * Fo + o];
+            s += t;
+            sa += fabs(t);
+        }
+        p->dW[co] = s;
+        p->dW_abs[co] = sa;
+    }
+    for (int64_t o = 0; o < Fo; ++o) {
+        double s = 0.0;
+        for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+        p->dbias[o] = s;
+    }
+
+    /* backward-Gather, backward-ApplyEdge's edge factor and backward-Scatter: a block of features per thread, edges in order */
+    const int64_t FB = 8, nfb = (Fm + FB - 1) / FB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t fb = 0; fb < nfb; ++fb) {
+        const int64_t c0 = fb * FB, c1 = c0 + FB < Fm ? c0 + FB : Fm;
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                const int64_t u = p->row_idx[e];
+                for (int64_t c = c0; c < c1; ++c) {
+                    double m = S[u * Fm + c], w = 1.0;
+                    if (op == EDGE_MUL_WEIGHT) { const float pr = p->edge_w[e] * p->X[u * F + c]; m = (double)pr; w = (double)p->edge_w[e]; }
+                    if (m == A[v * Fm + c]) {
+                        dS[u * Fm + c] += w * dA[v * Fm + c];
+                        dSa[u * Fm + c] += fabs(w) * dAa[v * Fm + c];
+                    }
+                }
+            }
+    }
+
+    if (op != EDGE_POOL) {
+        memcpy(p->dX, dS, sizeof(double) * (size_t)n * (size_t)F);
+        memcpy(p->dX_abs, dSa, sizeof(double) * (size_t)n * (size_t)F);
+        free(buf);
+        return 0;
+    }
+    /* POOL: through the sigmoid (dPre overwrites dS), then the per-vertex product */
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n * Fm; ++i) {
+        const double h = S[i], d1 = h * (1.0 - h);
+        dSa[i] = dSa[i] * d1 + fabs(dS[i]) * d1 * fabs(1.0 - 2.0 * h) * Sz[i];
+        dS[i] = dS[i] * d1;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < n; ++u)
+        for (int64_t k = 0; k < F; ++k) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t c = 0; c < Fm; ++c) {
+                s += dS[u * Fm + c] * (double)p->W_pool[c * F + k];
+                sa += dSa[u * Fm + c] * fabs((double)p->W_pool[c * F + k]);
+            }
+            p->dX[u * F + k] = s;
+            p->dX_abs[u * F + k] = sa;
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < Fm; ++c) {
+        double bs = 0.0, bsa = 0.0;
+        for (int64_t k = 0; k < F; ++k) p->dW_pool[c * F + k] = p->dW_pool_abs[c * F + k] = 0.0;
+        for (int64_t u = 0; u < n; ++u) {
+            const double d = dS[u * Fm + c], da = dSa[u * Fm + c];
+            bs += d;
+            bsa += da;
+            for (int64_t k = 0; k < F; ++k) {
+                p->dW_pool[c * F + k] += d * (double)p->X[u * F + k];
+                p->dW_pool_abs[c * F + k] += da * fabs((double)p->X[u * F + k]);
+            }
+        }
+        p->db_pool[c] = bs;
+        p->db_pool_abs[c] = bsa;
+    }
+    free(buf);
+    return 0;
+}

@@ -277,7 +277,10 @@ __device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, 
 //   kEfGate      acc (+)= sigmoid(x + c1) * m                      (forward message, and the message-part gradient)
 //   kEfGateGrad  acc  += g (1 - g) * (c2 * m),  g = sigmoid(x + c1)  (gradient with respect to the gate's argument)
 //   kEfGateBoth  both of the above at once from the same loads: acc += g (1 - g) * (c2 * m), acc2 += g * m
-constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3;
+//   kEfMaxGrad   acc += w_e * m where w_e * c1 == x, else nothing   (gradient of a max Gather: x is the maximum that
+//                was gathered at the other end of the edge, c1 this vertex's own row, so the test says "this vertex
+//                supplied the maximum"; the product is the same single fp32 multiply that formed the message)
+constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3, kEfMaxGrad = 4;
 
 template <int AGG, int EF>
 __device__ __forceinline__ float edge_step(float acc, float w, float x, float m, float c1, float c2)
@@ -286,6 +289,10 @@ __device__ __forceinline__ float edge_step(float acc, float w, float x, float m,
     if constexpr (EF == kEfGateGrad) {
         const float g = sigmoid_f32(x + c1);
         return fmaf(g * (1.0f - g), c2 * m, acc);
+    }
+    if constexpr (EF == kEfMaxGrad) {
+        const float msg = w * c1;
+        return msg == x ? fmaf(w, m, acc) : acc;
     }
     return accumulate<AGG>(acc, w, x);
 }
@@ -353,7 +360,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
     const T* __restrict__ X2 = GATED ? static_cast<const T*>(a.src2) : X;
     const int64_t ld2 = GATED ? a.ld_src2 : 0;
     const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
-    const const_f32_ptr ew = GATED ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
+    const const_f32_ptr ew = (GATED && EF != kEfMaxGrad) ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
     __shared__ float red[(kWavesPerBlock - 1) * 64 * RC * VEC];
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
@@ -511,7 +518,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
         float wt = 1.0f;
         if (my < it.e1) {
             idx = ridx[my];
-            if (!GATED && ew) wt = ew[my];
+            if ((!GATED || EF == kEfMaxGrad) && ew) wt = ew[my];
         }
         const int cnt = min(64, it.e1 - eb);
         const int nloads = (cnt + epw - 1) >> epw_log2;
@@ -670,6 +677,7 @@ hipError_t launch_op(const GatherArgs& a, hipStream_t s)
                                          : launch_shape<T, VEC, SAGA_AGG_MAX, kEfGate>(a, s);
         if (a.op == kGatherOpGateGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateGrad>(a, s);
         if (a.op == kGatherOpGateBoth) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateBoth>(a, s);
+        if (a.op == kGatherOpMaxGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfMaxGrad>(a, s);
     }
     return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfLinear>(a, s)
                                  : launch_shape<T, VEC, SAGA_AGG_MAX, kEfLinear>(a, s);
@@ -689,9 +697,10 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
     if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
     const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
-    const bool gated = a.op == SAGA_EDGE_GATED || grad;
+    const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {
         if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM || a.accumulate))) return hipErrorInvalidValue;
+        if (a.op == kGatherOpMaxGrad && a.agg != SAGA_AGG_SUM) return hipErrorInvalidValue;
         vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst) && (a.ld_src2 * 4) % 16 == 0 && aligned16(a.src2);
         if (grad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);
         if (a.op == kGatherOpGateBoth) {

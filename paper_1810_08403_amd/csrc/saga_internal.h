@@ -162,6 +162,8 @@ struct saga_graph {
 constexpr int32_t kGatherOpGateGrad = 100;
 // ... and that gradient together with the message-part gradient, from one pass, into out / out2
 constexpr int32_t kGatherOpGateBoth = 101;
+// gradient of a max Gather: a vertex receives w_e * (gradient at the other end) over the edges whose maximum it supplied
+constexpr int32_t kGatherOpMaxGrad = 102;
 
 struct GatherArgs {
     const WorkItem* items;

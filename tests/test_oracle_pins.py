@@ -607,3 +607,72 @@ def test_gated_backward_matches_finite_differences_of_the_naive_forward_oracle()
                   (fd("bg_", bg, (f,)), bwd["db_gate"][f]), (fd("Wm_", Wm, (f, k)), bwd["dW_msg"][f, k])]
         for num, ana in checks:                                   # central differences: error O(h^2)
             assert abs(num - ana) <= 2e-5 * max(1.0, abs(ana)), (num, ana)
+
+
+# --------------------------------------------------------------------------
+# max-accumulator backward (Figure 11's layer, and max over COPY / MUL_WEIGHT messages)
+# --------------------------------------------------------------------------
+
+def _max_bwd_setup(seed=4, n=40, m=70, F=5, Fp=4, Fo=3):
+    g = _random_graph(n, m, seed=seed)
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    w = (rng.standard_normal(g.nnz) * 0.8).astype(np.float32)        # both signs: a negative weight flips the order
+    Wp = (rng.standard_normal((Fp, F)) * 0.6).astype(np.float32)
+    bp = (rng.standard_normal(Fp) * 0.3).astype(np.float32)
+    b = (rng.standard_normal(Fo) * 0.3).astype(np.float32)
+    return g, X, w, Wp, bp, b, rng
+
+
+@pytest.mark.parametrize("edge_op", ["copy", "mul_weight", "pool"])
+@pytest.mark.parametrize("act", ["none", "relu"])
+def test_max_backward_equals_autograd_of_the_dense_form(edge_op, act):
+    import torch
+    g, X, w, Wp, bp, b, rng = _max_bwd_setup()
+    n, F = X.shape
+    Fm = Wp.shape[0] if edge_op == "pool" else F
+    W = rng.standard_normal((Fm, 3)).astype(np.float32)
+    dY = rng.standard_normal((n, 3)).astype(np.float32)
+    deg = np.diff(g.col_ptr.numpy())
+    assert (deg == 0).any() and (deg > 1).any()
+    kw = dict(edge_weight=w) if edge_op == "mul_weight" else (dict(W_pool=Wp, b_pool=bp) if edge_op == "pool" else {})
+    fwd = oracle.layer(*_np(g), X, edge_op, agg="max", W=W, bias=b, act=act, **kw)
+    bwd = oracle.max_backward(*_np(g), X, dY, W, edge_op, bias=b, act=act, **kw)
+    assert np.array_equal(bwd["A"], fwd["A"])                             # the Gather it differentiates is the pinned one
+    t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
+    Xt, Wt, bt, Wpt, bpt = t(X), t(W), t(b), t(Wp), t(bp)
+    Adj = torch.tensor(_dense_adj(g)) > 0                                  # [v, u]
+    if edge_op == "pool":
+        S = torch.sigmoid(Xt @ Wpt.T + bpt)[None, :, :].expand(n, n, Fm)
+    elif edge_op == "mul_weight":
+        # the message is one fp32 multiply: form it in fp32, differentiate through the fp64 product, which agrees to rounding
+        Wd = torch.tensor(_dense_adj(g, w))
+        S = Wd[:, :, None] * Xt[None, :, :]
+    else:
+        S = Xt[None, :, :].expand(n, n, F)
+    masked = torch.where(Adj[:, :, None], S, torch.tensor(-np.inf, dtype=torch.float64))
+    A = torch.where(Adj.any(1)[:, None], masked.amax(1), torch.zeros(n, Fm, dtype=torch.float64))
+    Z = A @ Wt + bt
+    Y = torch.relu(Z) if act == "relu" else Z
+    (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
+    tol = dict(rtol=1e-6, atol=1e-7) if edge_op == "mul_weight" else dict(rtol=1e-10, atol=1e-11)
+    assert np.allclose(bwd["dX"], Xt.grad.numpy(), **tol)
+    assert np.allclose(bwd["dW"], Wt.grad.numpy(), **tol)
+    assert np.allclose(bwd["dbias"], bt.grad.numpy(), **tol)
+    if edge_op == "pool":
+        assert np.allclose(bwd["dW_pool"], Wpt.grad.numpy(), **tol)
+        assert np.allclose(bwd["db_pool"], bpt.grad.numpy(), **tol)
+    for name in ["dX", "dW"] + (["dW_pool", "db_pool"] if edge_op == "pool" else []):
+        assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name
+
+
+def test_max_backward_sends_the_whole_gradient_to_every_tied_source():
+    # vertex 2 has in-edges from 0 and 1 with equal features in column 0 and distinct ones in column 1
+    g = si.csc_from_lists(3, [(0, 2), (1, 2)])
+    X = np.array([[2.0, 1.0], [2.0, 5.0], [0.0, 0.0]], np.float32)
+    W = np.eye(2, dtype=np.float32)
+    dY = np.array([[0, 0], [0, 0], [3.0, 7.0]], np.float32)
+    bwd = oracle.max_backward(*_np(g), X, dY, W, "copy")
+    assert np.array_equal(bwd["A"], [[0, 0], [0, 0], [2, 5]])
+    assert np.array_equal(bwd["dX"], [[3, 0], [3, 7], [0, 0]])            # the tie in column 0: both get 3
+    assert np.array_equal(bwd["dW"], [[6, 14], [15, 35]])                  # A^T dZ
