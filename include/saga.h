@@ -191,13 +191,17 @@ typedef struct saga_layer_grads {
     saga_tensor* dW_gate; /* F x 2F, laid out like W_gate: required */
     saga_tensor* db_gate; /* F values; NULL = not wanted */
     saga_tensor* dW_msg;  /* F x F, laid out like W_msg; NULL = not wanted; only when W_msg is given */
+    /* POOL layers only (NULL otherwise) */
+    saga_tensor* dW_pool; /* F_pool x F, laid out like W_pool: required */
+    saga_tensor* db_pool; /* F_pool values; NULL = not wanted */
 } saga_layer_grads;
 
 /*
  * One layer backward (the backward stages of Section 2.2, run in reverse order of the
- * forward ones): sum accumulator, fp32, ApplyVertex Y = act(A W + X W_self + bias) with act
- * NONE or RELU, everything device-resident, ApplyEdge COPY, MUL_WEIGHT or GATED (GATED
- * without W_self). Other layers return SAGA_ERR_UNSUPPORTED.
+ * forward ones): fp32, ApplyVertex Y = act(A W + X W_self + bias) with act NONE or RELU,
+ * everything device-resident. Covered: sum accumulator with COPY, MUL_WEIGHT, GATED or POOL
+ * messages; max accumulator with COPY, MUL_WEIGHT or POOL messages. W_self only with sum over
+ * COPY / MUL_WEIGHT. Other layers return SAGA_ERR_UNSUPPORTED.
  *
  *   backward-ApplyVertex   dZ = dY (.) act'(Z)  (ReLU: where Y > 0),  dW = A^T dZ,
  *                          dW_self = X^T dZ,  dbias = column sums of dZ,
@@ -223,6 +227,16 @@ typedef struct saga_layer_grads {
  * out-edges (source parts); dense products then give dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd],
  * dW_gate = [dPs^T X | dPd^T X], db_gate = column sums of dPd, dW_msg = dM^T X.
  * X is required.
+ *
+ * Max accumulator (Figure 11's layer): the gradient of A[v][f] goes to every in-edge whose
+ * message equals the maximum A[v][f] (on a tie every maximal edge receives all of it). The
+ * decision is taken by recomputing the message, w_e * x_u[f] with the same single fp32
+ * multiply as the forward pass (or the pooled sigmoid row of u, recomputed per vertex by the
+ * same product and kernel as in the forward pass), and comparing it with the A the caller
+ * kept: one propagation pass over the out-edges. POOL then goes through the sigmoid per
+ * vertex: dPre = dS (.) h (.) (1 - h), dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
+ * sums of dPre. X and A are required; A must be the accum_out of the forward call on the
+ * same inputs, or no message will compare equal.
  * Sums are deterministic run to run.
  */
 saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,

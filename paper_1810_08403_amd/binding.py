@@ -58,7 +58,8 @@ class VertexParams(ctypes.Structure):
 class LayerGrads(ctypes.Structure):
     _fields_ = [("dX", ctypes.POINTER(Tensor)), ("dW", ctypes.POINTER(Tensor)), ("dbias", ctypes.POINTER(Tensor)),
                 ("dW_self", ctypes.POINTER(Tensor)), ("dW_gate", ctypes.POINTER(Tensor)),
-                ("db_gate", ctypes.POINTER(Tensor)), ("dW_msg", ctypes.POINTER(Tensor))]
+                ("db_gate", ctypes.POINTER(Tensor)), ("dW_msg", ctypes.POINTER(Tensor)),
+                ("dW_pool", ctypes.POINTER(Tensor)), ("db_pool", ctypes.POINTER(Tensor))]
 
 
 class Timings(ctypes.Structure):
@@ -275,8 +276,9 @@ class Context:
                        X: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None, edge_op: str = "copy",
                        edge_weight: Optional[torch.Tensor] = None, agg: str = "sum", bias=None, W_self=None,
                        act: str = "none", dX=None, dbias=None, dW_self=None, W_gate=None, b_gate=None, W_msg=None,
-                       dW_gate=None, db_gate=None, dW_msg=None):
-        """saga_layer_backward: gradients are written into dW (and dX, dbias, dW_self, dW_gate, db_gate, dW_msg when given)."""
+                       dW_gate=None, db_gate=None, dW_msg=None, W_pool=None, b_pool=None, dW_pool=None, db_pool=None):
+        """saga_layer_backward: gradients are written into dW (and dX, dbias, dW_self, dW_gate, db_gate, dW_msg, dW_pool,
+        db_pool when given)."""
         tx, ta, ty, tdy = as_tensor(X), as_tensor(A), as_tensor(Y), as_tensor(dY)
         tw, tb, tws = as_tensor(W), as_tensor(bias), as_tensor(W_self)
         tdx, tdw, tdb, tdws = as_tensor(dX), as_tensor(dW), as_tensor(dbias), as_tensor(dW_self)
@@ -285,11 +287,12 @@ class Context:
             assert edge_weight.numel() == g.nnz
         twg, tbg, twm = as_tensor(W_gate), as_tensor(b_gate), as_tensor(W_msg)
         tdwg, tdbg, tdwm = as_tensor(dW_gate), as_tensor(db_gate), as_tensor(dW_msg)
+        twp, tbp, tdwp, tdbp = as_tensor(W_pool), as_tensor(b_pool), as_tensor(dW_pool), as_tensor(db_pool)
         ptr = lambda t: ctypes.pointer(t) if t is not None else None
         ep = EdgeParams(EDGE_OP[edge_op], edge_weight.data_ptr() if edge_weight is not None else None,
-                        ptr(twg), ptr(tbg), ptr(twm), None, None)
+                        ptr(twg), ptr(tbg), ptr(twm), ptr(twp), ptr(tbp))
         vp = VertexParams(ptr(tw), ptr(tb), ACT[act], 0, ptr(tws))
-        grads = LayerGrads(ptr(tdx), ptr(tdw), ptr(tdb), ptr(tdws), ptr(tdwg), ptr(tdbg), ptr(tdwm))
+        grads = LayerGrads(ptr(tdx), ptr(tdw), ptr(tdb), ptr(tdws), ptr(tdwg), ptr(tdbg), ptr(tdwm), ptr(tdwp), ptr(tdbp))
         cur = torch.cuda.current_stream(self.device)
         if cur != self.stream:
             self.stream.wait_stream(cur)

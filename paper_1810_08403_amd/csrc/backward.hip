@@ -305,12 +305,128 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     return SAGA_OK;
 }
 
+// The edge data in the order of the transposed graph: *w_t is NULL for unweighted layers.
+static saga_status transposed_weights(saga_ctx* ctx, saga_graph* g, const saga_edge_params* ep, const float** w_t)
+{
+    *w_t = nullptr;
+    if (ep->op != SAGA_EDGE_MUL_WEIGHT || g->nnz == 0) return SAGA_OK;
+    hipStream_t s = ctx->stream;
+    const int32_t* perm = static_cast<const int32_t*>(g->d_perm.p);
+    if (ep->edge_weight) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_edge_t, sizeof(float) * (size_t)g->nnz)) return st;
+        HIP_TRY(ctx, launch_permute_f32(ep->edge_weight, perm, static_cast<float*>(ctx->ws_edge_t.p), g->nnz, s));
+        *w_t = static_cast<const float*>(ctx->ws_edge_t.p);
+        return SAGA_OK;
+    }
+    if (!g->tr_edge_data_valid) {
+        if (saga_status st = ctx->dev_alloc(&g->tr->d_edge_data, sizeof(float) * (size_t)g->nnz)) return st;
+        HIP_TRY(ctx, launch_permute_f32(static_cast<const float*>(g->d_edge_data.p), perm, static_cast<float*>(g->tr->d_edge_data.p),
+                                        g->nnz, s));
+        g->tr_edge_data_valid = true;
+    }
+    *w_t = static_cast<const float*>(g->tr->d_edge_data.p);
+    return SAGA_OK;
+}
+
+// Max accumulator and / or max-pooling messages, after backward-ApplyVertex's parameter gradients: the gradient of
+// accum, its way back over the edges (to the sources that supplied the maxima, or, for a sum, to all of them), and for
+// pooled messages the way through the per-vertex sigmoid and product.
+static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const float* dZ,
+                                          int64_t lddz, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
+                                          const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const bool pool = ep->op == SAGA_EDGE_POOL;
+    const int32_t Fm = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    const int32_t F = pool ? (int32_t)ep->W_pool->cols : Fm;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+    if (n == 0) {
+        if (pool) {
+            if ((st = param_grad(ctx, nullptr, Fm, Fm, nullptr, F, F, 0, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
+            if (grads->db_pool) HIP_TRY(ctx, launch_fill_f32(static_cast<float*>(grads->db_pool->data), Fm, 0.f, s));
+        }
+        return SAGA_OK;
+    }
+    if (!pool && !grads->dX) return SAGA_OK;
+
+    if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)n * Fm))) return st;
+    float* dA = static_cast<float*>(ctx->ws_grad.p);
+    if ((st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W, nullptr, 0, 0, nullptr, n, Fm, dA, Fm))) return st;
+    if ((st = ensure_transposed(ctx, g))) return st;
+    const float* w_t = nullptr;
+    if ((st = transposed_weights(ctx, g, ep, &w_t))) return st;
+
+    // the per-vertex part of the message, and where the gradient with respect to it goes
+    const float* S = static_cast<const float*>(X->data);
+    int64_t lds = X->ld;
+    float* dS = grads->dX ? static_cast<float*>(grads->dX->data) : nullptr;
+    int64_t ldds = grads->dX ? grads->dX->ld : 0;
+    if (pool) {
+        if ((st = hoist_pool(ctx, X, ep, n, F, Fm))) return st;
+        if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)n * Fm))) return st;
+        S = static_cast<const float*>(ctx->ws_hoist.p);
+        lds = Fm;
+        dS = static_cast<float*>(ctx->ws_dh.p);
+        ldds = Fm;
+    }
+    if (agg == SAGA_AGG_MAX) {
+        GatherArgs ga{};
+        ga.op = kGatherOpMaxGrad;
+        ga.F = Fm;
+        ga.src = A->data;      // per edge: the maximum gathered at the destination ...
+        ga.ld_src = A->ld;
+        ga.src2 = dA;          // ... and its gradient
+        ga.ld_src2 = Fm;
+        ga.dst = S;            // per item: this vertex's own row
+        ga.ld_dst = lds;
+        ga.edge_w = w_t;
+        ga.out = dS;
+        ga.ld_out = ldds;
+        if ((st = run_propagation(ctx, g->tr, ga, 2 * (int64_t)Fm * 4))) return st;
+    } else {
+        if ((st = propagate_transposed(ctx, g, w_t, dA, Fm, Fm, dS, ldds, 0))) return st;
+    }
+    if (!pool) return SAGA_OK;
+
+    // through the sigmoid, then the per-vertex product: dPre = dS (.) h (1 - h), dW_pool = dPre^T X, db_pool, dX = dPre W_pool
+    HIP_TRY(ctx, launch_sigmoid_grad(dS, S, n * (int64_t)Fm, s));
+    const float* Xp = static_cast<const float*>(X->data);
+    if ((st = param_grad(ctx, dS, Fm, Fm, Xp, X->ld, F, n, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
+    if (grads->db_pool) {
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fm))) return st;
+        HIP_TRY(ctx, launch_dz_colsum(dS, Fm, nullptr, 0, nullptr, n, Fm, static_cast<float*>(ctx->ws_splitk.p),
+                                      static_cast<float*>(grads->db_pool->data), s));
+    }
+    if (!grads->dX) return SAGA_OK;
+    int64_t n_pad, k_pad;
+    bt_padded_shape(F, Fm, SAGA_F32, &n_pad, &k_pad);
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    float* bt = static_cast<float*>(ctx->ws_bt.p);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_pool->data, ep->W_pool->ld, Fm, F, SAGA_F32, bt, k_pad, 0, s));
+    GemmArgs gm{};
+    gm.A = dS;
+    gm.lda = Fm;
+    gm.Bt = bt;
+    gm.ldbt = k_pad;
+    gm.C = grads->dX->data;
+    gm.ldc = grads->dX->ld;
+    gm.M = n;
+    gm.N = F;
+    gm.K = Fm;
+    gm.dtype = gm.out_dtype = SAGA_F32;
+    gm.act = SAGA_ACT_NONE;
+    HIP_TRY(ctx, launch_gemm(gm, s));
+    return SAGA_OK;
+}
+
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
-                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                              const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                               const saga_layer_grads* grads)
 {
     const int64_t n = g->n;
-    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;  // F: message width (equals X's width except for POOL)
     hipStream_t s = ctx->stream;
 
     // backward-ApplyVertex: the activation's derivative and the bias gradient in one pass over the rows
@@ -339,27 +455,13 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     if (grads->dW_self)
         if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld)) return st;
     if (ep->op == SAGA_EDGE_GATED) return gated_backward_rest(ctx, g, X, dZ, lddz, ep, vp, grads);
+    if (ep->op == SAGA_EDGE_POOL || agg == SAGA_AGG_MAX) return max_pool_backward_rest(ctx, g, X, A, dZ, lddz, ep, agg, vp, grads);
     if (!grads->dX || n == 0) return SAGA_OK;
 
     // the edges grouped by source, and the edge data in that order
     if (saga_status st = ensure_transposed(ctx, g)) return st;
     const float* w_t = nullptr;
-    if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->nnz > 0) {
-        const int32_t* perm = static_cast<const int32_t*>(g->d_perm.p);
-        if (ep->edge_weight) {
-            if (saga_status st = ctx->dev_alloc(&ctx->ws_edge_t, sizeof(float) * (size_t)g->nnz)) return st;
-            HIP_TRY(ctx, launch_permute_f32(ep->edge_weight, perm, static_cast<float*>(ctx->ws_edge_t.p), g->nnz, s));
-            w_t = static_cast<const float*>(ctx->ws_edge_t.p);
-        } else {
-            if (!g->tr_edge_data_valid) {
-                if (saga_status st = ctx->dev_alloc(&g->tr->d_edge_data, sizeof(float) * (size_t)g->nnz)) return st;
-                HIP_TRY(ctx, launch_permute_f32(static_cast<const float*>(g->d_edge_data.p), perm,
-                                                static_cast<float*>(g->tr->d_edge_data.p), g->nnz, s));
-                g->tr_edge_data_valid = true;
-            }
-            w_t = static_cast<const float*>(g->tr->d_edge_data.p);
-        }
-    }
+    if (saga_status st = transposed_weights(ctx, g, ep, &w_t)) return st;
 
     float* dX = static_cast<float*>(grads->dX->data);
     const int64_t lddx = grads->dX->ld;

@@ -229,6 +229,14 @@ __global__ __launch_bounds__(256) void k_permute_f32(const float* __restrict__ i
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) out[i] = in[perm[i]];
 }
 
+__global__ __launch_bounds__(256) void k_sigmoid_grad(float* __restrict__ d, const float* __restrict__ h, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+        const float y = h[i];
+        d[i] *= y * (1.0f - y);
+    }
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_tn_cfg(const GemmTnArgs& a, bool aligned, hipStream_t s)
 {
@@ -312,5 +320,13 @@ hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, 
     if (count <= 0) return hipSuccess;
     const int grid = (int)std::min<int64_t>((count + 255) / 256, 1 << 20);
     hipLaunchKernelGGL(k_permute_f32, dim3(grid), dim3(256), 0, s, in, perm, out, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_sigmoid_grad(float* d, const float* h, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((count + 255) / 256, 1 << 20);
+    hipLaunchKernelGGL(k_sigmoid_grad, dim3(grid), dim3(256), 0, s, d, h, count);
     return hipGetLastError();
 }

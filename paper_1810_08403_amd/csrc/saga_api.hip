@@ -342,6 +342,36 @@ saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_par
     return SAGA_OK;
 }
 
+// Figure 11's ApplyEdge depends on the source only: H = sigmoid(X Wp^T + bp) once per vertex (Section 3.2),
+// into ctx->ws_hoist (n x Fm fp32)
+saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm)
+{
+    hipStream_t s = ctx->stream;
+    int64_t n_pad, k_pad;
+    bt_padded_shape(Fm, F, SAGA_F32, &n_pad, &k_pad);
+    saga_status st;
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * Fm))) return st;
+    float* bt = static_cast<float*>(ctx->ws_bt.p);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, Fm, F, bt, k_pad, 0, s));
+    GemmArgs hg{};
+    hg.A = X->data;
+    hg.lda = X->ld;
+    hg.Bt = bt;
+    hg.ldbt = k_pad;
+    hg.bias = ep->b_pool ? static_cast<const float*>(ep->b_pool->data) : nullptr;
+    hg.C = ctx->ws_hoist.p;
+    hg.ldc = Fm;
+    hg.M = n;
+    hg.N = Fm;
+    hg.K = F;
+    hg.dtype = hg.out_dtype = SAGA_F32;
+    hg.act = SAGA_ACT_SIGMOID;
+    HIP_TRY(ctx, launch_gemm(hg, s));
+    return SAGA_OK;
+}
+
 extern "C" {
 
 const char* saga_version(void) { return kVersion; }
@@ -759,30 +789,8 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ga.dtype = SAGA_F32;
         if (es) es->has_hoist = true;
     } else if (pool) {
-        // Figure 11's ApplyEdge depends on the source only: H = sigmoid(X Wp^T + bp) once per vertex (Section 3.2),
         // then the propagation kernel gathers rows of H
-        int64_t n_pad, k_pad;
-        bt_padded_shape(Fm, F, SAGA_F32, &n_pad, &k_pad);
-        saga_status st;
-        if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
-        if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)n * Fm))) return st;
-        float* bt = static_cast<float*>(ctx->ws_bt.p);
-        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
-        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, Fm, F, bt, k_pad, 0, s));
-        GemmArgs hg{};
-        hg.A = X->data;
-        hg.lda = X->ld;
-        hg.Bt = bt;
-        hg.ldbt = k_pad;
-        hg.bias = ep->b_pool ? static_cast<const float*>(ep->b_pool->data) : nullptr;
-        hg.C = ctx->ws_hoist.p;
-        hg.ldc = Fm;
-        hg.M = n;
-        hg.N = Fm;
-        hg.K = F;
-        hg.dtype = hg.out_dtype = SAGA_F32;
-        hg.act = SAGA_ACT_SIGMOID;
-        HIP_TRY(ctx, launch_gemm(hg, s));
+        if (saga_status st = hoist_pool(ctx, X, ep, n, F, Fm)) return st;
         ga.src = ctx->ws_hoist.p;
         ga.ld_src = Fm;
         ga.dtype = SAGA_F32;
@@ -958,46 +966,62 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (!g || !A || !dY || !ep || !vp || !grads) return ctx->fail(SAGA_ERR_INVALID_ARG, "null argument");
     if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
     if (g->where != SAGA_MEM_DEVICE) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs a device-resident graph");
-    if (agg != SAGA_AGG_SUM) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers the sum accumulator only");
-    const bool gated = ep->op == SAGA_EDGE_GATED;
-    if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT && !gated)
-        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers COPY, MUL_WEIGHT and GATED ApplyEdge only");
+    if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
+    const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
+    if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
+    if (gated && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
     if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
         return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
     auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };
     const saga_tensor* W = vp->W;
     if (!W) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs an ApplyVertex product (vp->W)");
     if (!dev_f32(W) || W->rows > (1 << 20) || W->cols > (1 << 20))
-        return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out fp32 tensor");
-    const int64_t n = g->n, F = W->rows, Fo = W->cols;
-    if (!dev_f32(A) || A->rows != n || A->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x F_in fp32 tensor");
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device Fm x F_out fp32 tensor");
+    // Fm: message width (rows of W, columns of A); F: width of X and dX
+    const int64_t n = g->n, Fm = W->rows, Fo = W->cols;
+    int64_t F = Fm;
+    if (pool) {
+        const saga_tensor* Wp = ep->W_pool;
+        if (!Wp || !dev_f32(Wp) || Wp->rows != Fm || Wp->cols < 1 || Wp->cols > (1 << 20))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_pool must be a device F_pool x F fp32 tensor with F_pool = rows of W");
+        F = Wp->cols;
+        if (ep->b_pool && (!dev_f32(ep->b_pool) || ep->b_pool->rows * ep->b_pool->cols != Fm))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "b_pool must be F_pool fp32 values on the device");
+        if (!grads->dW_pool || !dev_f32(grads->dW_pool) || grads->dW_pool->rows != Fm || grads->dW_pool->cols != F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_pool must be a device F_pool x F fp32 tensor");
+        if (grads->db_pool && (!dev_f32(grads->db_pool) || grads->db_pool->rows * grads->db_pool->cols != Fm))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->db_pool must be F_pool fp32 values on the device");
+    } else if (grads->dW_pool || grads->db_pool) {
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "pool gradients are for POOL layers only");
+    }
+    if (!dev_f32(A) || A->rows != n || A->cols != Fm) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x Fm fp32 tensor");
     if (!dev_f32(dY) || dY->rows != n || dY->cols != Fo)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "dY must be a device n x F_out fp32 tensor");
     if (vp->act == SAGA_ACT_RELU && (!Y || !dev_f32(Y) || Y->rows != n || Y->cols != Fo))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a device n x F_out fp32 tensor");
+    const bool needs_x = vp->W_self || gated || pool || agg == SAGA_AGG_MAX;
+    if (needs_x && (!X || !dev_f32(X) || X->rows != n || X->cols != F))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer needs X as a device n x F fp32 tensor");
     if (vp->W_self) {
+        if (gated || pool || agg == SAGA_AGG_MAX)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers W_self only with sum over COPY / MUL_WEIGHT messages");
         if (!dev_f32(vp->W_self) || vp->W_self->rows != F || vp->W_self->cols != Fo)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out fp32 tensor");
-        if (!X || !dev_f32(X) || X->rows != n || X->cols != F)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self needs X as a device n x F_in fp32 tensor");
         if (!grads->dW_self) return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self is given but grads->dW_self is not");
     } else if (grads->dW_self) {
         return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
     }
-    if (!grads->dW || !dev_f32(grads->dW) || grads->dW->rows != F || grads->dW->cols != Fo)
-        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
+    if (!grads->dW || !dev_f32(grads->dW) || grads->dW->rows != Fm || grads->dW->cols != Fo)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device Fm x F_out fp32 tensor");
     if (grads->dW_self && (!dev_f32(grads->dW_self) || grads->dW_self->rows != F || grads->dW_self->cols != Fo))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self must be a device F_in x F_out fp32 tensor");
     if (grads->dbias && (!dev_f32(grads->dbias) || grads->dbias->rows * grads->dbias->cols != Fo))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
     if (grads->dX && (!dev_f32(grads->dX) || grads->dX->rows != n || grads->dX->cols != F))
-        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F_in fp32 tensor");
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F fp32 tensor");
     if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
     if (gated) {
-        if (vp->W_self) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the gated backward pass does not cover W_self");
-        if (!X || !dev_f32(X) || X->rows != n || X->cols != F)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "GATED needs X as a device n x F fp32 tensor");
         if (!ep->W_gate || !dev_f32(ep->W_gate) || ep->W_gate->rows != F || ep->W_gate->cols != 2 * F)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "W_gate must be a device F x 2F fp32 tensor");
         if (ep->b_gate && (!dev_f32(ep->b_gate) || ep->b_gate->rows * ep->b_gate->cols != F))
@@ -1014,7 +1038,7 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         return ctx->fail(SAGA_ERR_INVALID_ARG, "gate gradients are for GATED layers only");
     }
     DeviceGuard guard(ctx->device);
-    return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
+    return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads);
 }
 
 }  // extern "C"

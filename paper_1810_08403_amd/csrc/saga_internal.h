@@ -280,15 +280,19 @@ int64_t colsum_slabs(int64_t rows);
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
                             float* part, float* dbias, hipStream_t s);
 hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s);
+// d[i] *= h[i] * (1 - h[i]): a gradient taken through a sigmoid whose outputs are h (both compact, count elements)
+hipError_t launch_sigmoid_grad(float* d, const float* h, int64_t count, hipStream_t s);
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
 saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes);
 // per-vertex products of a gated ApplyEdge into ctx->ws_hoist, rows [Ps | M | Pd (+ b)] (saga_api.hip)
 saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F);
+// per-vertex messages of a max-pooling ApplyEdge into ctx->ws_hoist, n x Fm (saga_api.hip)
+saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm);
 // backward pass of a resident layer (backward.hip)
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
-                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                              const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                               const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 

@@ -153,15 +153,22 @@ def test_backward_rejects_what_it_does_not_cover(ctx):
     n, F = wl.X.shape
     Fo = wl.W.shape[1]
     A, dY, W, dW = (torch.zeros(n, F, device="cuda"), torch.zeros(n, Fo, device="cuda"), wl.W.cuda(), torch.zeros(F, Fo, device="cuda"))
-    with pytest.raises(saga.SagaError) as e:
-        ctx.layer_backward(graph, A, dY, W, dW, agg="max")
+    X = wl.X.cuda()
+    with pytest.raises(saga.SagaError) as e:                      # max over gated messages
+        ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", edge_op="gated")
     assert e.value.status == 3
     with pytest.raises(saga.SagaError) as e:
         ctx.layer_backward(graph, A, dY, W, dW, act="sigmoid")
     assert e.value.status == 3
-    with pytest.raises(saga.SagaError) as e:
-        ctx.layer_backward(graph, A, dY, W, dW, edge_op="pool")
+    with pytest.raises(saga.SagaError) as e:                      # W_self with the max accumulator
+        ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", W_self=W, dW_self=torch.zeros_like(dW))
     assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:                      # max needs X
+        ctx.layer_backward(graph, A, dY, W, dW, agg="max")
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # POOL needs W_pool and dW_pool
+        ctx.layer_backward(graph, A, dY, W, dW, X=X, edge_op="pool")
+    assert e.value.status == 1
     with pytest.raises(saga.SagaError) as e:                      # RELU without Y
         ctx.layer_backward(graph, A, dY, W, dW, act="relu")
     assert e.value.status == 1
@@ -352,4 +359,92 @@ def test_gated_backward_configuration_4_at_scale_16(ctx):
     assert info["n_split_vertices"] > 0
     for name in ["dW", "dX", "dW_gate", "db_gate", "dW_msg"]:
         assert_sum_close(res[name], bwd[name], bwd[name + "_abs"], TOL_F32, "configuration 4 at scale 16, " + name)
+    graph.destroy()
+
+
+# --------------------------------------------------------------------------
+# max accumulator and max-pooling messages (Figure 11)
+# --------------------------------------------------------------------------
+
+def _quantised_pool_workload(scale, f_in, f_pool, f_out):
+    """MP-GCN workload whose pooled pre-activations are exact in fp32 (coarse X, W_pool, b_pool), so that the order of the
+    sigmoid messages, ties included, is the same in fp32 on the GPU and in fp64 in the oracle."""
+    wl = si.mpgcn_workload(scale=scale, f_in=f_in, f_pool=f_pool, f_out=f_out)
+    wl.X = torch.round(wl.X.clamp(-1, 1) * 4) / 4
+    wl.W_pool = torch.round((wl.W_pool * 4).clamp(-0.5, 0.5) * 8) / 8
+    wl.b_pool = torch.round(wl.b_pool.clamp(-0.5, 0.5) * 8) / 8
+    assert f_in * 0.5 + 0.5 <= 8.5
+    return wl
+
+
+@pytest.mark.parametrize("edge_op,F,Fo,act", [("copy", 64, 32, "relu"), ("mul_weight", 96, 128, "none"), ("copy", 7, 5, "relu"),
+                                               ("mul_weight", 260, 16, "relu")])
+def test_max_backward_matches_oracle(ctx, edge_op, F, Fo, act):
+    wl = si.commnet_workload(scale=11, f_in=F, f_out=Fo)
+    wl.W_self = None
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    w = None
+    if edge_op == "mul_weight":
+        w = si.uniform_pm(g.nnz, 1.0, 17)                           # both signs
+    bias = si.uniform_pm(Fo, 0.3, 5)
+    dY = si.normal_features(n, Fo, 99)
+    kw = dict(edge_weight=w.numpy()) if w is not None else {}
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op, agg="max", W=wl.W.numpy(), bias=bias.numpy(), act=act, **kw)
+    bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), edge_op, bias=bias.numpy(), act=act, **kw)
+    graph = make_graph(ctx, g)
+    dev = "cuda"
+    f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev)
+    dX, dW, db = (torch.full((n, F), float("nan"), device=dev), torch.full((F, Fo), float("nan"), device=dev),
+                  torch.full((Fo,), float("nan"), device=dev))
+    ctx.layer_backward(graph, f32(bwd["A"]), dY.to(dev), wl.W.to(dev), dW, X=wl.X.to(dev), Y=f32(fwd["Y"]), edge_op=edge_op, agg="max",
+                       edge_weight=None if w is None else w.to(dev), bias=bias.to(dev), act=act, dX=dX, dbias=db)
+    torch.cuda.synchronize()
+    what = f"max {edge_op} {F}->{Fo}"
+    assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+    assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    # every source that never supplies a maximum gets exactly zero
+    assert ((bwd["dX_abs"] == 0) <= (dX.cpu().numpy() == 0)).all()
+    graph.destroy()
+
+
+@pytest.mark.parametrize("agg", ["max", "sum"])
+@pytest.mark.parametrize("f_in,f_pool,f_out", [(16, 32, 16), (12, 7, 5), (16, 128, 64)])
+def test_pool_backward_matches_oracle(ctx, agg, f_in, f_pool, f_out):
+    wl = _quantised_pool_workload(11, f_in, f_pool, f_out)
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    dY = si.normal_features(n, f_out, 7)
+    dev = "cuda"
+    graph = make_graph(ctx, g)
+    Xd, Wd, Wp, bp = wl.X.to(dev), wl.W.to(dev), wl.W_pool.to(dev), wl.b_pool.to(dev)
+    # the GPU's own forward pass supplies A and Y (its pooled rows are recomputed bit for bit in the backward pass)
+    Y, A = torch.empty(n, f_out, device=dev), torch.empty(n, f_pool, device=dev)
+    ctx.layer_forward(graph, Xd, Y, edge_op="pool", agg=agg, W_pool=Wp, b_pool=bp, W=Wd, act="none", accum_out=A)
+    nan = lambda *s: torch.full(s, float("nan"), device=dev)
+    dX, dW, db, dWp, dbp = nan(n, f_in), nan(f_pool, f_out), nan(f_out), nan(f_pool, f_in), nan(f_pool)
+    ctx.layer_backward(graph, A, dY.to(dev), Wd, dW, X=Xd, edge_op="pool", agg=agg, W_pool=Wp, b_pool=bp, act="none",
+                       dX=dX, dbias=db, dW_pool=dWp, db_pool=dbp)
+    torch.cuda.synchronize()
+    if agg == "max":
+        bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), "pool", W_pool=wl.W_pool.numpy(),
+                                  b_pool=wl.b_pool.numpy(), act="none")
+        ties = 0
+        for name, got in [("dW", dW), ("dX", dX), ("dW_pool", dWp), ("db_pool", dbp)]:
+            assert_sum_close(got.cpu().numpy(), bwd[name], bwd[name + "_abs"], TOL_F32, f"pool max {f_in}->{f_pool}->{f_out} {name}")
+    else:
+        # sum over pooled messages: the linear backward of the hoisted rows, then through the sigmoid; checked against
+        # autograd of the definition in fp64 on the host
+        Xt = wl.X.double().requires_grad_(True)
+        Wpt, bpt, Wt = wl.W_pool.double().requires_grad_(True), wl.b_pool.double().requires_grad_(True), wl.W.double().requires_grad_(True)
+        H = torch.sigmoid(Xt @ Wpt.T + bpt)
+        deg = g.col_ptr[1:] - g.col_ptr[:-1]
+        dst = torch.repeat_interleave(torch.arange(n), deg)
+        Aref = torch.zeros(n, f_pool, dtype=torch.float64).index_add(0, dst, H[g.row_idx.long()])
+        ((Aref @ Wt) * dY.double()).sum().backward()
+        for name, got, ref in [("dW", dW, Wt.grad), ("dX", dX, Xt.grad), ("dW_pool", dWp, Wpt.grad), ("db_pool", dbp, bpt.grad)]:
+            err = (got.cpu().double() - ref).abs().max().item()
+            assert err <= 2e-5 * ref.abs().max().item(), (name, err)
     graph.destroy()
