@@ -216,14 +216,17 @@ def main():
     }
 
     if args.backward:
-        if wl.dtype != "f32" or args.agg != "sum" or wl.edge_op not in ("copy", "mul_weight", "gated") or not has_w or wl.act not in ("none", "relu"):
-            print("bench.py: --backward needs an fp32 sum layer with COPY / MUL_WEIGHT / GATED edges and ApplyVertex (try --f32)", file=sys.stderr)
+        if wl.dtype != "f32" or not has_w or wl.act not in ("none", "relu") or (wl.edge_op == "gated" and args.agg != "sum"):
+            print("bench.py: --backward needs an fp32 layer with ApplyVertex, ReLU or no activation, and no max over gated messages "
+                  "(try --f32)", file=sys.stderr)
             sys.exit(2)
-        A = torch.empty(n, f_in, device=dev)
+        A = torch.empty(n, f_msg, device=dev)
         dY = si.normal_features(n, f_out, 4242, device=dev)
-        dX, dW, db = torch.empty(n, f_in, device=dev), torch.empty(f_in, f_out, device=dev), torch.empty(f_out, device=dev)
+        dX, dW, db = torch.empty(n, f_in, device=dev), torch.empty(f_msg, f_out, device=dev), torch.empty(f_out, device=dev)
         dWs = torch.empty(f_in, f_out, device=dev) if wl.W_self is not None else None
-        bkw = dict(X=X, Y=Y, edge_op=wl.edge_op, act=wl.act, W_self=kw.get("W_self"), dX=dX, dbias=db, dW_self=dWs)
+        bkw = dict(X=X, Y=Y, edge_op=wl.edge_op, agg=args.agg, act=wl.act, W_self=kw.get("W_self"), dX=dX, dbias=db, dW_self=dWs)
+        if wl.edge_op == "pool":
+            bkw.update(W_pool=wl.W_pool, b_pool=wl.b_pool, dW_pool=torch.empty(f_msg, f_in, device=dev), db_pool=torch.empty(f_msg, device=dev))
         if wl.edge_op == "gated":
             bkw.update(W_gate=wl.W_gate, b_gate=wl.b_gate, W_msg=wl.W_msg, dW_gate=torch.empty(f_in, 2 * f_in, device=dev),
                        db_gate=torch.empty(f_in, device=dev), dW_msg=torch.empty(f_in, f_in, device=dev))
@@ -240,7 +243,7 @@ def main():
             bstep()
         torch.cuda.synchronize()
         ms_b = (time.perf_counter() - t0) * 1e3 / args.steps
-        out["backward"] = {"ms_per_step": round(ms_b, 4), "propagated_width": f_in if wl.edge_op == "gated" else min(f_in, f_out),
+        out["backward"] = {"ms_per_step": round(ms_b, 4), "propagated_width": f_msg if (wl.edge_op in ("gated", "pool") or args.agg == "max") else min(f_in, f_out),
                            "gteps": round(nnz / (ms_b * 1e-3) / 1e9, 4),
                            "forward_plus_backward_ms": round(ms_b + ms_per_step, 4)}
 
