@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--team", type=int, default=None)
+    ap.add_argument("--transform-first", type=int, default=None,
+                    help="1: run the ApplyVertex product before the propagation where the layer narrows the rows (see saga_set_option)")
     ap.add_argument("--budget-gib", type=float, default=16.0, help="config5 only: device-memory budget")
     ap.add_argument("--dst-intervals", type=int, default=None, help="config5 only: force the plan")
     ap.add_argument("--src-intervals", type=int, default=None)
@@ -125,7 +127,7 @@ def main():
 
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
-                      ("xcd_remap", args.xcd_remap), ("team", args.team)):
+                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("transform_first", args.transform_first)):
         if val is not None:
             ctx.set_option(name, val)
     t0 = time.time()
@@ -187,6 +189,9 @@ def main():
         del a, b
 
     ms_gather = tm["ms_gather"] / max(tm["n_calls"], 1)
+    if (args.transform_first and has_w and wl.W_self is None and args.agg == "sum" and wl.edge_op in ("copy", "mul_weight")
+            and f_out < f_in):
+        f_msg = f_out          # the propagation moves rows of X W
     alg_bytes = algorithmic_gather_bytes(nnz, n, f_msg, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
                                          info["n_work_items"])
     achieved = alg_bytes / (ms_gather * 1e-3) / 1e9 if ms_gather > 0 else 0.0
@@ -199,7 +204,7 @@ def main():
         "config": {"workload": wl.name, "n_vertices": n, "nnz": nnz, "f_in": f_in, "f_out": f_out,
                    "edge_op": wl.edge_op, "agg": args.agg, "act": wl.act, "max_in_degree": info["max_in_degree"],
                    "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"],
-                   "hip_graph": bool(args.hip_graph)},
+                   "hip_graph": bool(args.hip_graph), "transform_first": int(args.transform_first or 0)},
         "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(f"spmm_d{args.density:g}" if args.workload == "spmm" else args.workload, nnz, info["n_work_items"], args.agg),

@@ -267,6 +267,12 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                first, accumulators swapped out to the host and back for ApplyVertex),
  *                2 = destination order innermost (a source chunk stays, accumulators are
  *                swapped in and out around every edge chunk)
+ *   "transform_first"  0/1 (default 0): device-resident layers with a linear ApplyEdge (COPY, MUL_WEIGHT), the
+ *                sum accumulator, an ApplyVertex product that narrows the rows (F_out < F_in), no W_self and no
+ *                accum_out compute Y = act(sum_e w_e (x_u W) + bias): the product first, then the propagation
+ *                at F_out values per edge. The same function (the linear stages commute; the operator motion
+ *                of Section 3.2 taken one step further), with a different rounding order: sums are taken over
+ *                rows of X W rounded to X's dtype. Off by default because it leaves the paper's stage order.
  *   "overlap"    streamed calls: 1 = copies on their own streams, overlapping the kernels
  *                (default); 0 = everything on one stream (streaming off)
  * Returns INVALID_ARG for unknown names or values. */

@@ -58,6 +58,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(x >> 16);
 }
 
+// ApplyVertex's bias and activation on a finished row element (transform-first layers)
+__device__ __forceinline__ float finish_vertex(float y, float bias, int act)
+{
+    y += bias;
+    if (act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
+    if (act == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
+    return y;
+}
+
 // ---- 16-byte (or one-element) row fragments --------------------------------
 template <typename T, int VEC>
 struct Frag;
@@ -157,6 +166,10 @@ __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, 
     } else if (agg == SAGA_AGG_MAX && empty_column) {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) outv[j] = 0.f;
+    }
+    if (a.bias || a.act != SAGA_ACT_NONE) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) outv[j] = finish_vertex(outv[j], a.bias ? a.bias[col0 + j] : 0.f, a.act);
     }
     if (a.out) {
         float* p = a.out + (int64_t)v * a.ld_out + col0;
@@ -597,6 +610,7 @@ __global__ __launch_bounds__(256) void k_combine(const CombineArgs a)
     float r = p[0];
     for (int s = 1; s < h.nslots; ++s) r = combine<AGG>(r, p[(int64_t)s * a.F]);
     if (a.accumulate) r = combine<AGG>(a.out[(int64_t)h.v * a.ld_out + f], r);
+    if (a.bias || a.act != SAGA_ACT_NONE) r = finish_vertex(r, a.bias ? a.bias[f] : 0.f, a.act);
     if (a.out) a.out[(int64_t)h.v * a.ld_out + f] = r;
     if (a.out16) a.out16[(int64_t)h.v * a.ld_out16 + f] = f32_to_bf16_rne(r);
 }
@@ -696,6 +710,7 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.out) vec_ok = vec_ok && (a.ld_out * 4) % 16 == 0 && aligned16(a.out);
     if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
     if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
+    if ((a.bias || a.act != SAGA_ACT_NONE) && a.accumulate) return hipErrorInvalidValue;
     const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {

@@ -536,6 +536,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "overlap")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "overlap must be 0 or 1");
         ctx->opt_overlap = (int)value;
+    } else if (!strcmp(name, "transform_first")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "transform_first must be 0 or 1");
+        ctx->opt_transform_first = (int)value;
     } else if (!strcmp(name, "src_intervals")) {
         if (value < 0 || value > 4096) return ctx->fail(SAGA_ERR_INVALID_ARG, "src_intervals must be in [0, 4096]");
         ctx->opt_src_intervals = (int)value;
@@ -746,8 +749,14 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     const bool bf16 = X->dtype == SAGA_BF16;
     const bool has_w = vp && vp->W;
     hipStream_t s = ctx->stream;
+    // Transform first (option): for a linear ApplyEdge under the sum accumulator, W (.) sum_e w_e x_u = sum_e w_e (W (.) x_u),
+    // so when the layer narrows the rows the product runs first and the propagation moves F_out values per edge
+    // instead of F_in. The Gather output of the paper's order then never exists, so accum_out keeps the usual order.
+    const bool tf = ctx->opt_transform_first && has_w && !vp->W_self && !accum_out && agg == SAGA_AGG_SUM &&
+                    (ep->op == SAGA_EDGE_COPY || ep->op == SAGA_EDGE_MUL_WEIGHT) && vp->W->cols < F;
+    const int32_t Fo_tf = tf ? (int32_t)vp->W->cols : 0;
     // bytes one edge gathers: the source row, or two hoisted fp32 rows when gated
-    const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)Fm * (bf16 ? 2 : 4);
+    const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)(tf ? Fo_tf : Fm) * (bf16 ? 2 : 4);
     if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
 
     saga_ctx::EventSet* es = nullptr;
@@ -801,6 +810,22 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ga.dtype = X->dtype;
         if (ep->op == SAGA_EDGE_MUL_WEIGHT)
             ga.edge_w = ep->edge_weight ? ep->edge_weight : static_cast<const float*>(g->d_edge_data.p);
+        if (tf) {
+            // Z = X W in X's dtype, no bias, no activation: those follow the sum
+            DevBuf* zb = bf16 ? &ctx->ws_accum16 : &ctx->ws_accum;
+            if (saga_status st = ctx->dev_alloc(zb, (size_t)(bf16 ? 2 : 4) * (size_t)n * Fo_tf)) return st;
+            saga_vertex_params vz{};
+            vz.W = vp->W;
+            vz.act = SAGA_ACT_NONE;
+            if (saga_status st = run_apply_vertex(ctx, X->data, X->ld, X->dtype, n, F, &vz, nullptr, 0, 0, zb->p, Fo_tf, X->dtype))
+                return st;
+            ga.src = zb->p;
+            ga.ld_src = Fo_tf;
+            ga.F = Fo_tf;
+            ga.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
+            ga.act = vp->act;
+            if (es) es->has_hoist = true;  // the product is timed in the slot of the per-vertex products
+        }
     }
     if (es) HIP_TRY(ctx, hipEventRecord(es->ev[1], s));
 
@@ -808,7 +833,15 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     //   fp32: accum_out if given, else Y itself when there is no ApplyVertex, else workspace
     //   bf16: a bf16 copy feeds the ApplyVertex product (or is Y itself without one);
     //         the fp32 rows are written only when accum_out asks for them
-    if (!bf16) {
+    if (tf) {
+        if (bf16) {
+            ga.out16 = static_cast<uint16_t*>(Y->data);
+            ga.ld_out16 = Y->ld;
+        } else {
+            ga.out = static_cast<float*>(Y->data);
+            ga.ld_out = Y->ld;
+        }
+    } else if (!bf16) {
         if (accum_out) {
             ga.out = static_cast<float*>(accum_out->data);
             ga.ld_out = accum_out->ld;
@@ -835,7 +868,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         }
     }
     if (g->n_slots > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * Fm)) return st;
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * ga.F)) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
     }
     HIP_TRY(ctx, launch_gather(ga, s));
@@ -846,19 +879,21 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ca.heavy = static_cast<const HeavyVertex*>(g->d_heavy.p);
         ca.n_heavy = g->n_heavy;
         ca.partials = ga.partials;
-        ca.F = Fm;
+        ca.F = ga.F;
         ca.agg = agg;
         ca.out = ga.out;
         ca.ld_out = ga.ld_out;
         ca.out16 = ga.out16;
         ca.ld_out16 = ga.ld_out16;
         ca.accumulate = 0;
+        ca.bias = ga.bias;
+        ca.act = ga.act;
         HIP_TRY(ctx, launch_combine(ca, s));
         if (es) es->has_combine = true;
     }
     if (es) HIP_TRY(ctx, hipEventRecord(es->ev[3], s));
 
-    if (has_w) {
+    if (has_w && !tf) {
         const void* A = bf16 ? static_cast<const void*>(ga.out16) : static_cast<const void*>(ga.out);
         const int64_t lda = bf16 ? ga.ld_out16 : ga.ld_out;
         if (saga_status st = run_apply_vertex(ctx, A, lda, X->dtype, n, Fm, vp, X->data, X->ld, F, Y->data, Y->ld, Y->dtype))

@@ -82,6 +82,7 @@ struct saga_ctx {
     int opt_dst_intervals = 0, opt_src_intervals = 0;
     int opt_schedule = 0;  // streamed path: 0 the paper's schedule, 1 stage by stage, 2 destination order innermost
     int opt_overlap = 1;   // streamed path: copies on their own streams
+    int opt_transform_first = 0;  // resident linear sum layers with F_out < F_in: Y = act(gather(X W) + bias)
 
     // reusable workspace (grown on demand, never shrunk until destroy)
     DevBuf ws_accum;     // Gather output A (fp32 or bf16) when the caller gives no accum_out
@@ -197,6 +198,10 @@ struct GatherArgs {
     float* partials;         // n_slots x F fp32
     int32_t accumulate;      // 1: combine with what `out` already holds (streamed, chunk i > 0)
     int32_t xcd_remap;
+    // transform-first layers: the gathered rows are already X W, so ApplyVertex's bias and activation are applied
+    // to every finished row (whole-column items here, cut columns in the combine pass); not with `accumulate`
+    const float* bias;       // [F] fp32, nullable
+    int32_t act;             // saga_act
 };
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 
@@ -211,6 +216,8 @@ struct CombineArgs {
     uint16_t* out16;
     int64_t ld_out16;
     int32_t accumulate;
+    const float* bias;       // as in GatherArgs
+    int32_t act;
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 

@@ -99,3 +99,32 @@ def test_new_parameters_are_validated(ctx):
     assert status(lambda: ctx.layer_forward(graph, X, torch.empty(n, 16, device="cuda"), edge_op="copy",
                                             W_self=torch.zeros(16, 16, device="cuda"))) == 3            # W_self without W
     graph.destroy()
+
+
+@pytest.mark.parametrize("dtype,f_in,f_out,edge_op,act", [("f32", 500, 16, "mul_weight", "relu"), ("f32", 64, 3, "copy", "sigmoid"),
+                                                          ("bf16", 512, 64, "mul_weight", "relu"), ("bf16", 96, 40, "copy", "none"),
+                                                          ("f32", 37, 5, "mul_weight", "relu")])
+def test_transform_first_gives_the_same_layer(dtype, f_in, f_out, edge_op, act):
+    """Option transform_first: the product runs before the propagation when the layer narrows the rows. Same function as
+    the paper's order (the oracle's), different rounding order."""
+    from helpers import new_context
+    wl = si.workload(2, scale=12, f_in=f_in, f_out=f_out)
+    wl.edge_op, wl.act, wl.dtype = edge_op, act, dtype
+    if edge_op == "copy":
+        wl.edge_weight = None
+    if dtype == "bf16":
+        wl.X, wl.W = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W)
+    bias = si.uniform_pm(f_out, 0.3, 77)
+    ref = run_oracle(wl, bias=bias)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    with new_context(transform_first=1) as c:
+        graph = make_graph(c, wl.graph)
+        Y, _ = run_gpu(c, wl, graph, bias=bias, want_accum=False)
+        assert_sum_close(Y, ref["Y"], ref["Y_abs"], tol, f"transform-first {dtype} {f_in}->{f_out}")
+        info = graph.info()
+        # with accum_out the paper's order runs (the Gather output has to exist) and gives its usual result
+        Y2, A = run_gpu(c, wl, graph, bias=bias, want_accum=True)
+        assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, "Gather with accum_out")
+        assert_sum_close(Y2, ref["Y"], ref["Y_abs"], tol, "layer with accum_out")
+        graph.destroy()
+    assert info["n_work_items"] > 0
