@@ -17,6 +17,7 @@
 //   * heavy columns are cut into items of bounded length whose partial rows
 //     are combined in a fixed order, so sums are reproducible.
 #include <cmath>
+#include <type_traits>
 
 #include "device_math.h"
 #include "saga_internal.h"
@@ -534,39 +535,53 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
             if ((!GATED || EF == kEfMaxGrad) && ew) wt = ew[my];
         }
         const int cnt = min(64, it.e1 - eb);
-        const int nloads = (cnt + epw - 1) >> epw_log2;
-        for (int j0 = 0; j0 < nloads; j0 += U) {
+        // `count` load steps starting at step j0, all issued before the first is consumed. CHECK: a step may reach past
+        // the batch (only its last step can), so every lane tests its own slot; otherwise nothing is tested per lane.
+        // Lanes past the end of a row (colok false) accumulate what they load from the row's first fragment and are
+        // never stored, and the closing butterfly only mixes lanes of equal `sub`.
+        auto steps = [&](const int j0, const int count, auto check_tag) {
+            constexpr bool CHECK = decltype(check_tag)::value;
             Frag<T, VEC> x[U];
             Frag<T, VEC> m[GATED ? U : 1];
             float w[U];
             bool ok[U];
 #pragma unroll
             for (int k = 0; k < U; ++k) {
-                const int s = ((j0 + k) << epw_log2) + grp;
-                ok[k] = colok && s < cnt;
-                // slots past the end of the batch hold id 0: a valid row, loaded and dropped
-                const int64_t u = __shfl(idx, s & 63);
-                w[k] = __shfl(wt, s & 63);
-                x[k].load(X + u * a.ld_src + ldcol);
-                if constexpr (GATED) m[k].load(X2 + u * ld2 + ldcol);
+                if (k < count) {
+                    const int s = ((j0 + k) << epw_log2) + grp;
+                    ok[k] = !CHECK || s < cnt;
+                    // slots past the end of the batch hold id 0: a valid row, loaded and dropped
+                    const int64_t u = __shfl(idx, s & 63);
+                    w[k] = __shfl(wt, s & 63);
+                    x[k].load(X + u * a.ld_src + ldcol);
+                    if constexpr (GATED) m[k].load(X2 + u * ld2 + ldcol);
+                }
             }
 #pragma unroll
-            for (int k = 0; k < U; ++k)
+            for (int k = 0; k < U; ++k) {
+                if (k < count) {
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    float mv = 0.f;
-                    if constexpr (GATED) mv = m[k].get(j);
-                    if constexpr (EF == kEfGateBoth) {
-                        float r = acc[j], r2 = acc2[j];
-                        edge_step_both(r, r2, x[k].get(j), mv, pd[j], c2[j]);
-                        acc[j] = ok[k] ? r : acc[j];
-                        acc2[j] = ok[k] ? r2 : acc2[j];
-                    } else {
-                        const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
-                        acc[j] = ok[k] ? r : acc[j];
+                    for (int j = 0; j < VEC; ++j) {
+                        float mv = 0.f;
+                        if constexpr (GATED) mv = m[k].get(j);
+                        if constexpr (EF == kEfGateBoth) {
+                            float r = acc[j], r2 = acc2[j];
+                            edge_step_both(r, r2, x[k].get(j), mv, pd[j], c2[j]);
+                            acc[j] = (!CHECK || ok[k]) ? r : acc[j];
+                            acc2[j] = (!CHECK || ok[k]) ? r2 : acc2[j];
+                        } else {
+                            const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
+                            acc[j] = (!CHECK || ok[k]) ? r : acc[j];
+                        }
                     }
                 }
-        }
+            }
+        };
+        const int nfull = cnt >> epw_log2;  // steps whose slots all lie inside the batch
+        int j0 = 0;
+        for (; j0 + U <= nfull; j0 += U) steps(j0, U, std::false_type{});
+        if (j0 < nfull) steps(j0, nfull - j0, std::false_type{});
+        if (cnt & (epw - 1)) steps(nfull, 1, std::true_type{});
     }
     for (int off = lpr; off < 64; off <<= 1)
 #pragma unroll
