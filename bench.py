@@ -220,6 +220,22 @@ def main():
         "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3)},
     }
 
+    if (not args.transform_first and not args.hip_graph and has_w and wl.W_self is None and args.agg == "sum"
+            and wl.edge_op in ("copy", "mul_weight") and f_out < f_in):
+        # the same layer with the product before the propagation (option transform_first), timed beside the headline
+        ctx.set_option("transform_first", 1)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms_tf = (time.perf_counter() - t0) * 1e3 / args.steps
+        ctx.set_option("transform_first", 0)
+        out["variants"] = {"transform_first": {"ms_per_step": round(ms_tf, 4), "value": round(nnz / (ms_tf * 1e-3) / 1e9, 4),
+                                               "note": "same layer, ApplyVertex product before the propagation; not the headline"}}
+
     if args.backward:
         if wl.dtype != "f32" or not has_w or wl.act not in ("none", "relu") or (wl.edge_op == "gated" and args.agg != "sum"):
             print("bench.py: --backward needs an fp32 layer with ApplyVertex, ReLU or no activation, and no max over gated messages "
