@@ -526,14 +526,23 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
         for (int j = 0; j < VEC; ++j) c2[j] = f.get(j);
     }
 
-    for (int eb = it.e0; eb < it.e1; eb += 64) {
+    // ids and weights of a batch of 64 edges, one per lane; the next batch's travel while this one's rows do
+    auto fetch_batch = [&](const int eb, int& id_out, float& w_out) {
         const int my = eb + lane;
-        int idx = 0;
-        float wt = 1.0f;
+        id_out = 0;
+        w_out = 1.0f;
         if (my < it.e1) {
-            idx = ridx[my];
-            if ((!GATED || EF == kEfMaxGrad) && ew) wt = ew[my];
+            id_out = ridx[my];
+            if ((!GATED || EF == kEfMaxGrad) && ew) w_out = ew[my];
         }
+    };
+    int idx_next;
+    float wt_next;
+    fetch_batch(it.e0, idx_next, wt_next);
+    for (int eb = it.e0; eb < it.e1; eb += 64) {
+        const int idx = idx_next;
+        const float wt = wt_next;
+        if (eb + 64 < it.e1) fetch_batch(eb + 64, idx_next, wt_next);
         const int cnt = min(64, it.e1 - eb);
         // `count` load steps starting at step j0, all issued before the first is consumed. CHECK: a step may reach past
         // the batch (only its last step can), so every lane tests its own slot; otherwise nothing is tested per lane.
