@@ -237,13 +237,14 @@ def main():
                                                "note": "same layer, ApplyVertex product before the propagation; not the headline"}}
 
     if args.backward:
-        if wl.dtype != "f32" or not has_w or wl.act not in ("none", "relu") or (wl.edge_op == "gated" and args.agg != "sum"):
-            print("bench.py: --backward needs an fp32 layer with ApplyVertex, ReLU or no activation, and no max over gated messages "
-                  "(try --f32)", file=sys.stderr)
+        bf16_ok = wl.dtype == "bf16" and args.agg == "sum" and wl.edge_op in ("copy", "mul_weight") and wl.W_self is None
+        if (wl.dtype != "f32" and not bf16_ok) or not has_w or wl.act not in ("none", "relu") or (wl.edge_op == "gated" and args.agg != "sum"):
+            print("bench.py: --backward needs an fp32 layer (or a bf16 sum layer with COPY / MUL_WEIGHT edges) with ApplyVertex, "
+                  "ReLU or no activation, and no max over gated messages (try --f32)", file=sys.stderr)
             sys.exit(2)
         A = torch.empty(n, f_msg, device=dev)
-        dY = si.normal_features(n, f_out, 4242, device=dev)
-        dX, dW, db = torch.empty(n, f_in, device=dev), torch.empty(f_msg, f_out, device=dev), torch.empty(f_out, device=dev)
+        dY = si.normal_features(n, f_out, 4242, device=dev).to(tdt)
+        dX, dW, db = torch.empty(n, f_in, device=dev, dtype=tdt), torch.empty(f_msg, f_out, device=dev), torch.empty(f_out, device=dev)
         dWs = torch.empty(f_in, f_out, device=dev) if wl.W_self is not None else None
         bkw = dict(X=X, Y=Y, edge_op=wl.edge_op, agg=args.agg, act=wl.act, W_self=kw.get("W_self"), dX=dX, dbias=db, dW_self=dWs)
         if wl.edge_op == "pool":

@@ -237,6 +237,12 @@ typedef struct saga_layer_grads {
  * vertex: dPre = dS (.) h (.) (1 - h), dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
  * sums of dPre. X and A are required; A must be the accum_out of the forward call on the
  * same inputs, or no message will compare equal.
+ *
+ * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self): X is not
+ * needed, Y, dY and grads->dX are bf16 like W, A stays the fp32 accum_out of the forward
+ * call, parameter gradients are fp32. dZ's bf16 values are used as they are; the rows that
+ * travel over the edges and the product that makes dX are bf16 with fp32 accumulation and
+ * one rounding to bf16 each, like the forward pass; dW and dbias are fp32 products and sums.
  * Sums are deterministic run to run.
  */
 saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,

@@ -480,3 +480,108 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
         if (saga_status st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W_self, nullptr, 0, 0, nullptr, n, F, dX, lddx)) return st;
     return propagate_transposed(ctx, g, w_t, dA, F, F, dX, lddx, vp->W_self ? 1 : 0);
 }
+
+// bf16 layers (sum over COPY / MUL_WEIGHT messages): the rows that travel over the edges and through the dX product
+// are bf16 with fp32 accumulation, like the forward pass; the parameter gradients are fp32 products of the fp32 Gather
+// output with dZ (whose bf16 values are exact in fp32).
+saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                                   const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+    const size_t nz = (size_t)std::max<int64_t>(n, 1) * Fo;
+    if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * nz))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_dz16, sizeof(uint16_t) * nz))) return st;
+    float* dZ32 = static_cast<float*>(ctx->ws_dz.p);
+    uint16_t* dZ16 = static_cast<uint16_t*>(ctx->ws_dz16.p);
+    const bool relu = vp->act == SAGA_ACT_RELU;
+    HIP_TRY(ctx, launch_dz_bf16(static_cast<const uint16_t*>(dY->data), dY->ld, relu ? static_cast<const uint16_t*>(Y->data) : nullptr,
+                                relu ? Y->ld : 0, dZ32, dZ16, n, Fo, s));
+    if (grads->dbias) {
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo))) return st;
+        HIP_TRY(ctx, launch_dz_colsum(dZ32, Fo, nullptr, 0, nullptr, n, Fo, static_cast<float*>(ctx->ws_splitk.p),
+                                      static_cast<float*>(grads->dbias->data), s));
+    }
+    if ((st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ32, Fo, Fo, n, static_cast<float*>(grads->dW->data),
+                         grads->dW->ld)))
+        return st;
+    if (!grads->dX || n == 0) return SAGA_OK;
+    if ((st = ensure_transposed(ctx, g))) return st;
+    const float* w_t = nullptr;
+    if ((st = transposed_weights(ctx, g, ep, &w_t))) return st;
+
+    // rows x K (bf16) times W^T, W given as F x F_out: C[rows x F] bf16
+    auto times_wt16 = [&](const uint16_t* rows16, int64_t ld, uint16_t* C, int64_t ldc) -> saga_status {
+        int64_t n_pad, k_pad;
+        bt_padded_shape(F, Fo, SAGA_BF16, &n_pad, &k_pad);
+        if (saga_status e = ctx->dev_alloc(&ctx->ws_bt, sizeof(uint16_t) * (size_t)(n_pad * k_pad))) return e;
+        uint16_t* bt = static_cast<uint16_t*>(ctx->ws_bt.p);
+        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(uint16_t) * (size_t)(n_pad * k_pad), s));
+        HIP_TRY(ctx, launch_pack_bt_rows_bf16(static_cast<const uint16_t*>(vp->W->data), vp->W->ld, F, Fo, bt, k_pad, s));
+        GemmArgs gm{};
+        gm.A = rows16;
+        gm.lda = ld;
+        gm.Bt = bt;
+        gm.ldbt = k_pad;
+        gm.C = C;
+        gm.ldc = ldc;
+        gm.M = n;
+        gm.N = F;
+        gm.K = Fo;
+        gm.dtype = gm.out_dtype = SAGA_BF16;
+        gm.act = SAGA_ACT_NONE;
+        HIP_TRY(ctx, launch_gemm(gm, s));
+        return SAGA_OK;
+    };
+    auto propagate16 = [&](const uint16_t* src, int64_t ld, int32_t width, uint16_t* out16, int64_t ld_out) -> saga_status {
+        GatherArgs ga{};
+        ga.edge_w = w_t;
+        ga.src = src;
+        ga.ld_src = ld;
+        ga.F = width;
+        ga.op = w_t ? SAGA_EDGE_MUL_WEIGHT : SAGA_EDGE_COPY;
+        ga.out16 = out16;
+        ga.ld_out16 = ld_out;
+        // run_propagation sets dtype to fp32: give the bf16 view its own few lines
+        saga_graph* view = g->tr;
+        if (saga_status e = ensure_work_list(ctx, view, (int64_t)width * 2)) return e;
+        ga.items = static_cast<const WorkItem*>(view->d_items.p);
+        ga.n_items = view->n_items;
+        ga.n_team = view->n_team;
+        ga.row_idx = static_cast<const int32_t*>(view->d_row_idx.p);
+        ga.dtype = SAGA_BF16;
+        ga.agg = SAGA_AGG_SUM;
+        ga.xcd_remap = ctx->opt_xcd_remap;
+        if (view->n_slots > 0) {
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * width)) return e;
+            ga.partials = static_cast<float*>(ctx->ws_partials.p);
+        }
+        HIP_TRY(ctx, launch_gather(ga, s));
+        if (view->n_heavy > 0) {
+            CombineArgs ca{};
+            ca.heavy = static_cast<const HeavyVertex*>(view->d_heavy.p);
+            ca.n_heavy = view->n_heavy;
+            ca.partials = ga.partials;
+            ca.F = width;
+            ca.agg = SAGA_AGG_SUM;
+            ca.out16 = out16;
+            ca.ld_out16 = ld_out;
+            HIP_TRY(ctx, launch_combine(ca, s));
+        }
+        return SAGA_OK;
+    };
+
+    uint16_t* dX = static_cast<uint16_t*>(grads->dX->data);
+    const int64_t lddx = grads->dX->ld;
+    const int32_t wmid = Fo <= F ? Fo : F;
+    if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(uint16_t) * (size_t)n * wmid))) return st;
+    uint16_t* mid = static_cast<uint16_t*>(ctx->ws_grad.p);
+    if (Fo <= F) {
+        if ((st = propagate16(dZ16, Fo, Fo, mid, Fo))) return st;   // the narrower rows travel
+        return times_wt16(mid, Fo, dX, lddx);
+    }
+    if ((st = times_wt16(dZ16, Fo, mid, F))) return st;
+    return propagate16(mid, F, F, dX, lddx);
+}

@@ -239,6 +239,14 @@ __global__ __launch_bounds__(256) void k_pack_bt_rows(const float* Wsrc, int64_t
         Bt[(row0 + r) * ldbt + k] = Wsrc ? Wsrc[r * ldw + col0 + k] : (r == k ? 1.f : 0.f);
     }
 }
+__global__ __launch_bounds__(256) void k_pack_bt_rows16(const uint16_t* Wsrc, int64_t ldw, int R, int K, uint16_t* Bt, int64_t ldbt)
+{
+    const int64_t total = (int64_t)R * K;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / K, k = i % K;
+        Bt[r * ldbt + k] = Wsrc[r * ldw + k];
+    }
+}
 
 template <typename T, int BM, int BN, int WM, int WN, typename TO>
 hipError_t launch_cfg(const GemmArgs& a, bool aligned, hipStream_t s)
@@ -312,5 +320,14 @@ hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int
     if (total <= 0) return hipSuccess;
     const int grid = (int)std::min<int64_t>((total + 255) / 256, 65535);
     hipLaunchKernelGGL(k_pack_bt_rows, dim3(grid), dim3(256), 0, s, Wsrc, ldw, col0, R, K, Bt, ldbt, row0);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_bt_rows_bf16(const uint16_t* Wsrc, int64_t ldw, int32_t R, int32_t K, uint16_t* Bt, int64_t ldbt, hipStream_t s)
+{
+    const int64_t total = (int64_t)R * K;
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((total + 255) / 256, 65535);
+    hipLaunchKernelGGL(k_pack_bt_rows16, dim3(grid), dim3(256), 0, s, Wsrc, ldw, R, K, Bt, ldbt);
     return hipGetLastError();
 }

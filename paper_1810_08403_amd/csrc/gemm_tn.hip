@@ -222,6 +222,26 @@ __global__ __launch_bounds__(256) void k_dz_colsum(const float* __restrict__ dY,
     }
 }
 
+// bf16 layers: dZ = dY where Y > 0 (or dY itself without Y), written twice, as fp32 for the parameter-gradient product
+// and the bias sums, and as bf16 (the same values) for the propagation and the products that run in bf16
+__global__ __launch_bounds__(256) void k_dz_bf16(const uint16_t* __restrict__ dY, int64_t lddy, const uint16_t* __restrict__ Y, int64_t ldy,
+                                                 float* __restrict__ dZ32, uint16_t* __restrict__ dZ16, int64_t rows, int F)
+{
+    const int64_t total = rows * F;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / F;
+        const int c = (int)(i % F);
+        uint16_t g = dY[r * lddy + c];
+        if (Y) {
+            const uint16_t y = Y[r * ldy + c];
+            const bool pos = (y & 0x7fffu) != 0 && (y & 0x8000u) == 0 && (y & 0x7fffu) <= 0x7f80u;  // y > 0, not NaN
+            g = pos ? g : (uint16_t)0;
+        }
+        dZ16[i] = g;
+        dZ32[i] = __uint_as_float((uint32_t)g << 16);
+    }
+}
+
 // out[i] = in[perm[i]]
 __global__ __launch_bounds__(256) void k_permute_f32(const float* __restrict__ in, const int32_t* __restrict__ perm, float* __restrict__ out,
                                                      int64_t count)
@@ -328,5 +348,15 @@ hipError_t launch_sigmoid_grad(float* d, const float* h, int64_t count, hipStrea
     if (count <= 0) return hipSuccess;
     const int grid = (int)std::min<int64_t>((count + 255) / 256, 1 << 20);
     hipLaunchKernelGGL(k_sigmoid_grad, dim3(grid), dim3(256), 0, s, d, h, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_dz_bf16(const uint16_t* dY, int64_t lddy, const uint16_t* Y, int64_t ldy, float* dZ32, uint16_t* dZ16, int64_t rows,
+                          int32_t F, hipStream_t s)
+{
+    const int64_t total = rows * F;
+    if (total <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 20);
+    hipLaunchKernelGGL(k_dz_bf16, dim3(grid), dim3(256), 0, s, dY, lddy, Y, ldy, dZ32, dZ16, rows, F);
     return hipGetLastError();
 }

@@ -497,7 +497,7 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh})
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16})
         ctx->dev_free(b);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
@@ -1010,6 +1010,31 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };
     const saga_tensor* W = vp->W;
     if (!W) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs an ApplyVertex product (vp->W)");
+    if (tensor_ok(W) && W->dtype == SAGA_BF16) {
+        // bf16 layers: X, W, Y, dY, dX in bf16; A and the parameter gradients in fp32
+        auto dev_bf16 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_BF16; };
+        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
+        if (!dev_bf16(W) || W->rows > (1 << 20) || W->cols > (1 << 20)) return ctx->fail(SAGA_ERR_INVALID_ARG, "malformed W");
+        const int64_t n = g->n, F = W->rows, Fo = W->cols;
+        if (!dev_f32(A) || A->rows != n || A->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x F_in fp32 tensor");
+        if (!dev_bf16(dY) || dY->rows != n || dY->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "dY must be a device n x F_out bf16 tensor, like W");
+        if (vp->act == SAGA_ACT_RELU && (!Y || !dev_bf16(Y) || Y->rows != n || Y->cols != Fo))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a device n x F_out bf16 tensor");
+        if (!grads->dW || !dev_f32(grads->dW) || grads->dW->rows != F || grads->dW->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
+        if (grads->dbias && (!dev_f32(grads->dbias) || grads->dbias->rows * grads->dbias->cols != Fo))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
+        if (grads->dX && (!dev_bf16(grads->dX) || grads->dX->rows != n || grads->dX->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F_in bf16 tensor");
+        if (grads->dW_self || grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
+        if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
+        DeviceGuard guard16(ctx->device);
+        return resident_backward_bf16(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+    }
     if (!dev_f32(W) || W->rows > (1 << 20) || W->cols > (1 << 20))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device Fm x F_out fp32 tensor");
     // Fm: message width (rows of W, columns of A); F: width of X and dX

@@ -98,6 +98,7 @@ struct saga_ctx {
     DevBuf ws_splitk;    // per-split partials of the parameter gradients and of the bias column sums
     DevBuf ws_edge_t;    // per-call edge weights in the order of the transposed graph
     DevBuf ws_dh;        // gated layers: per-vertex gradients [dPs | dM | dPd]
+    DevBuf ws_dz16;      // bf16 layers: the gradient of the pre-activation in bf16
 
     // profiling
     bool profiling = false;
@@ -262,6 +263,8 @@ hipError_t launch_pack_bt_transpose(const void* W, int64_t ldw, int32_t K, int32
 // Bt rows [row0, row0 + R) = Wsrc[r][col0 .. col0 + K) (already output-channel major); Wsrc NULL = identity.
 hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int32_t R, int32_t K,
                                float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
+// Bt rows [0, R) = Wsrc[r][0 .. K), bf16
+hipError_t launch_pack_bt_rows_bf16(const uint16_t* Wsrc, int64_t ldw, int32_t R, int32_t K, uint16_t* Bt, int64_t ldbt, hipStream_t s);
 hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s);
 
 // C[FP x FQ] = P^T Q over n rows (fp32), the rows divided over n_split ranges of
@@ -286,6 +289,9 @@ hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_
 int64_t colsum_slabs(int64_t rows);
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
                             float* part, float* dbias, hipStream_t s);
+// bf16 layers: dZ (rows x F, compact) = dY where Y > 0 (Y NULL: dY), as fp32 and as bf16
+hipError_t launch_dz_bf16(const uint16_t* dY, int64_t lddy, const uint16_t* Y, int64_t ldy, float* dZ32, uint16_t* dZ16, int64_t rows,
+                          int32_t F, hipStream_t s);
 hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s);
 // d[i] *= h[i] * (1 - h[i]): a gradient taken through a sigmoid whose outputs are h (both compact, count elements)
 hipError_t launch_sigmoid_grad(float* d, const float* h, int64_t count, hipStream_t s);
@@ -301,6 +307,8 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                               const saga_layer_grads* grads);
+saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                                   const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)

@@ -448,3 +448,57 @@ def test_pool_backward_matches_oracle(ctx, agg, f_in, f_pool, f_out):
             err = (got.cpu().double() - ref).abs().max().item()
             assert err <= 2e-5 * ref.abs().max().item(), (name, err)
     graph.destroy()
+
+
+# --------------------------------------------------------------------------
+# bf16 layers
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("f_in,f_out,edge_op,act", [(128, 48, "mul_weight", "relu"), (48, 128, "copy", "none"), (512, 256, "mul_weight", "relu"),
+                                                    (20, 7, "copy", "relu"), (64, 64, "mul_weight", "none")])
+def test_bf16_backward_matches_oracle(ctx, f_in, f_out, edge_op, act):
+    from helpers import TOL_BF16
+    wl = si.commnet_workload(scale=11, f_in=f_in, f_out=f_out)
+    wl.edge_op, wl.W_self = edge_op, None
+    if edge_op == "mul_weight":
+        wl.edge_weight = si.gcn_edge_weights(wl.graph)
+    wl.X, wl.W = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W)
+    n = wl.graph.n
+    dY = si.round_to_bf16(si.normal_features(n, f_out, 99))
+    fwd, bwd = _oracle_pair(wl, act, None, False, dY)
+    graph = make_graph(ctx, wl.graph)
+    dev = "cuda"
+    b16 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev).to(torch.bfloat16)
+    A = torch.as_tensor(fwd["A"], dtype=torch.float32).to(dev)
+    dW, db = torch.full((f_in, f_out), float("nan"), device=dev), torch.full((f_out,), float("nan"), device=dev)
+    dX = torch.full((n, f_in), float("nan"), device=dev, dtype=torch.bfloat16)
+    kw = dict(edge_weight=wl.edge_weight.to(dev)) if edge_op == "mul_weight" else {}
+    ctx.layer_backward(graph, A, b16(dY), b16(wl.W), dW, Y=b16(fwd["Y"]), edge_op=edge_op, act=act, dX=dX, dbias=db, **kw)
+    torch.cuda.synchronize()
+    what = f"bf16 {f_in}->{f_out} {edge_op} {act}"
+    # the parameter gradients are fp32 products of exactly representable inputs: the fp32 bar applies
+    assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+    dZ = dY * torch.as_tensor(fwd["Y"] > 0) if act == "relu" else dY
+    assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(np.abs(dZ.numpy().astype(np.float64)).sum(0), 1e-30), TOL_F32, what + " dbias")
+    assert_sum_close(dX.float().cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_BF16, what + " dX")
+    graph.destroy()
+
+
+def test_bf16_backward_rejects_mixed_dtypes(ctx):
+    import paper_1810_08403_amd as saga
+    wl = si.workload(1)
+    graph = make_graph(ctx, wl.graph)
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    bf = torch.bfloat16
+    A, W16, dW = torch.zeros(n, F, device="cuda"), wl.W.cuda().to(bf), torch.zeros(F, Fo, device="cuda")
+    with pytest.raises(saga.SagaError) as e:                      # fp32 dY with bf16 W
+        ctx.layer_backward(graph, A, torch.zeros(n, Fo, device="cuda"), W16, dW)
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # fp32 dX with bf16 W
+        ctx.layer_backward(graph, A, torch.zeros(n, Fo, device="cuda", dtype=bf), W16, dW, dX=torch.zeros(n, F, device="cuda"))
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # gated layers are fp32 only
+        ctx.layer_backward(graph, A, torch.zeros(n, Fo, device="cuda", dtype=bf), W16, dW, edge_op="gated")
+    assert e.value.status == 3
+    graph.destroy()
