@@ -238,6 +238,16 @@ typedef struct saga_layer_grads {
  * sums of dPre. X and A are required; A must be the accum_out of the forward call on the
  * same inputs, or no message will compare equal.
  *
+ * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, no W_self):
+ * A, Y, dY and grads->dX are SAGA_MEM_HOST tensors (pinned recommended), W and the parameter
+ * gradients stay on the device. backward-ApplyVertex runs over tiles of rows (dW and dbias
+ * accumulate tile by tile in a fixed order; for RELU dZ is written to pinned host memory held
+ * by the context). The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is the forward
+ * chunk schedule of Section 3.1 run on the chunks of edges clustered by source (the CSR side
+ * of the paper's chunk layout), with dZ as the vertex data and W^T as the ApplyVertex matrix;
+ * the transposed chunk grid is built at the first such call. Every transfer goes through the
+ * context's device budget like in saga_layer_forward.
+ *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self): X is not
  * needed, Y, dY and grads->dX are bf16 like W, A stays the fp32 accum_out of the forward
  * call, parameter gradients are fp32. dZ's bf16 values are used as they are; the rows that
@@ -279,6 +289,8 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                at F_out values per edge. The same function (the linear stages commute; the operator motion
  *                of Section 3.2 taken one step further), with a different rounding order: sums are taken over
  *                rows of X W rounded to X's dtype. Off by default because it leaves the paper's stage order.
+ *   "bwd_tile_rows"  streamed backward calls: rows per tile of the backward-ApplyVertex pass (default 0 = as
+ *                many as make the widest tile about 64 MiB)
  *   "overlap"    streamed calls: 1 = copies on their own streams, overlapping the kernels
  *                (default); 0 = everything on one stream (streaming off)
  * Returns INVALID_ARG for unknown names or values. */

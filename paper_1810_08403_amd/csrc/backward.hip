@@ -14,6 +14,7 @@ void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g)
     ctx->dev_free(&g->d_perm);
     if (!g->tr) return;
     saga_graph* t = g->tr;
+    if (t->grid) chunk_grid_destroy(ctx, t->grid);
     for (DevBuf* b : {&t->d_row_idx, &t->d_items, &t->d_heavy, &t->d_edge_data}) ctx->dev_free(b);
     for (auto& sl : t->saved_lists) {
         ctx->dev_free(&sl.items);
@@ -184,7 +185,7 @@ static saga_status rows_times_wt(saga_ctx* ctx, const float* Arows, int64_t lda,
 }
 
 static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_t FP, const float* Q, int64_t ldq, int32_t FQ,
-                              int64_t n, float* C, int64_t ldc)
+                              int64_t n, float* C, int64_t ldc, int accumulate = 0)
 {
     GemmTnArgs ta{};
     ta.P = P;
@@ -197,7 +198,7 @@ static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_
     gemm_tn_plan(n, FP, FQ, &ta.rows_per_split, &ta.n_split);
     if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)ta.n_split * FP * FQ)) return st;
     ta.part = static_cast<float*>(ctx->ws_splitk.p);
-    HIP_TRY(ctx, launch_gemm_tn(ta, C, ldc, ctx->stream));
+    HIP_TRY(ctx, launch_gemm_tn(ta, C, ldc, accumulate, ctx->stream));
     return SAGA_OK;
 }
 
@@ -272,7 +273,7 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     if (grads->db_gate) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * F))) return st;
         HIP_TRY(ctx, launch_dz_colsum(dH + 2 * F, ldh, nullptr, 0, nullptr, n, F, static_cast<float*>(ctx->ws_splitk.p),
-                                      static_cast<float*>(grads->db_gate->data), s));
+                                      static_cast<float*>(grads->db_gate->data), 0, s));
     }
     if (!grads->dX) return SAGA_OK;
 
@@ -396,7 +397,7 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     if (grads->db_pool) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fm))) return st;
         HIP_TRY(ctx, launch_dz_colsum(dS, Fm, nullptr, 0, nullptr, n, Fm, static_cast<float*>(ctx->ws_splitk.p),
-                                      static_cast<float*>(grads->db_pool->data), s));
+                                      static_cast<float*>(grads->db_pool->data), 0, s));
     }
     if (!grads->dX) return SAGA_OK;
     int64_t n_pad, k_pad;
@@ -443,7 +444,7 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
             if (saga_status st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fo)) return st;
         HIP_TRY(ctx, launch_dz_colsum(dZ, lddz, relu ? static_cast<const float*>(Y->data) : nullptr, relu ? Y->ld : 0,
                                       static_cast<float*>(ctx->ws_dz.p), n, Fo, part,
-                                      grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, s));
+                                      grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, 0, s));
         if (relu) {
             dZ = static_cast<const float*>(ctx->ws_dz.p);
             lddz = Fo;
@@ -502,7 +503,7 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
     if (grads->dbias) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo))) return st;
         HIP_TRY(ctx, launch_dz_colsum(dZ32, Fo, nullptr, 0, nullptr, n, Fo, static_cast<float*>(ctx->ws_splitk.p),
-                                      static_cast<float*>(grads->dbias->data), s));
+                                      static_cast<float*>(grads->dbias->data), 0, s));
     }
     if ((st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ32, Fo, Fo, n, static_cast<float*>(grads->dW->data),
                          grads->dW->ld)))
@@ -584,4 +585,142 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
     }
     if ((st = times_wt16(dZ16, Fo, mid, F))) return st;
     return propagate16(mid, F, F, dX, lddx);
+}
+
+// ---------------------------------------------------------------------------
+// streamed layers (Section 3.1): tensors in host memory, host graph
+// ---------------------------------------------------------------------------
+// The edge order by source of a host graph, with its edge data: the chunk grid the backward propagation streams is
+// built from it the way the forward one is built from the graph itself (chunks of edges clustered by source).
+static saga_status ensure_transposed_host(saga_ctx* ctx, saga_graph* g)
+{
+    if (g->tr) return SAGA_OK;
+    const int64_t n = g->n, nnz = g->nnz;
+    saga_graph* t = new (std::nothrow) saga_graph();
+    if (!t) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    t->ctx = ctx;
+    t->n = n;
+    t->nnz = nnz;
+    t->where = SAGA_MEM_HOST;
+    g->tr = t;
+    const bool weighted = !g->h_edge_data.empty();
+    try {
+        t->h_col_ptr.assign((size_t)n + 1, 0);
+        t->h_row_idx.resize((size_t)nnz);
+        if (weighted) t->h_edge_data.resize((size_t)nnz);
+        int64_t* rp = t->h_col_ptr.data();
+        const int32_t* src = g->h_row_idx.data();
+        for (int64_t e = 0; e < nnz; ++e) ++rp[src[e] + 1];
+        int64_t maxdeg = 0;
+        for (int64_t u = 0; u < n; ++u) {
+            maxdeg = std::max(maxdeg, rp[u + 1]);
+            rp[u + 1] += rp[u];
+        }
+        t->max_degree = maxdeg;
+        std::vector<int64_t> fill(rp, rp + n);
+        const int64_t* cp = g->h_col_ptr.data();
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = cp[v]; e < cp[v + 1]; ++e) {
+                const int64_t pos = fill[(size_t)src[e]]++;
+                t->h_row_idx[(size_t)pos] = (int32_t)v;
+                if (weighted) t->h_edge_data[(size_t)pos] = g->h_edge_data[(size_t)e];
+            }
+    } catch (...) {
+        transposed_graph_destroy(ctx, g);
+        return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    }
+    return SAGA_OK;
+}
+
+saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    const bool relu = vp->act == SAGA_ACT_RELU;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+
+    // ---- backward-ApplyVertex, a tile of rows at a time: dZ, the bias sums, dW += A^T dZ ----
+    const int64_t t_auto = std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)std::max(F, Fo)));
+    const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), ctx->opt_bwd_tile_rows > 0 ? ctx->opt_bwd_tile_rows : t_auto));
+    if ((st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F))) return st;   // A tile
+    if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)T * Fo))) return st;   // dY tile
+    if (relu) {
+        if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)T * Fo))) return st;  // Y tile
+        if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)T * Fo))) return st;     // dZ tile
+        const size_t need = sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fo;
+        if (ctx->h_dz_bytes < need) {
+            if (ctx->h_dz) (void)hipHostFree(ctx->h_dz);
+            ctx->h_dz = nullptr;
+            ctx->h_dz_bytes = 0;
+            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_dz), need, hipHostMallocDefault));
+            ctx->h_dz_bytes = need;
+        }
+    }
+    if (grads->dbias)
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(T) * Fo))) return st;
+    float* tA = static_cast<float*>(ctx->ws_accum.p);
+    float* tdY = static_cast<float*>(ctx->ws_grad.p);
+    float* tY = static_cast<float*>(ctx->ws_hoist.p);
+    float* tdZ = relu ? static_cast<float*>(ctx->ws_dz.p) : tdY;
+    int64_t h2d = 0, d2h = 0;
+    auto rows_at = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
+    for (int64_t r0 = 0; r0 < std::max<int64_t>(n, 1); r0 += T) {
+        const int64_t rows = std::min(T, n - r0);
+        const int acc = r0 > 0;
+        if (rows > 0) {
+            HIP_TRY(ctx, hipMemcpy2DAsync(tA, sizeof(float) * (size_t)F, rows_at(A, r0), sizeof(float) * (size_t)A->ld,
+                                          sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, s));
+            HIP_TRY(ctx, hipMemcpy2DAsync(tdY, sizeof(float) * (size_t)Fo, rows_at(dY, r0), sizeof(float) * (size_t)dY->ld,
+                                          sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, s));
+            h2d += rows * (int64_t)(F + Fo) * 4;
+            if (relu) {
+                HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_at(Y, r0), sizeof(float) * (size_t)Y->ld,
+                                              sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, s));
+                h2d += rows * (int64_t)Fo * 4;
+            }
+        }
+        if (relu || grads->dbias)
+            HIP_TRY(ctx, launch_dz_colsum(tdY, Fo, relu ? tY : nullptr, Fo, tdZ, rows, Fo,
+                                          grads->dbias ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
+                                          grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, acc, s));
+        if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
+        if (relu && rows > 0 && grads->dX) {
+            HIP_TRY(ctx, hipMemcpyAsync(ctx->h_dz + r0 * Fo, tdZ, sizeof(float) * (size_t)rows * Fo, hipMemcpyDeviceToHost, s));
+            d2h += rows * (int64_t)Fo * 4;
+        }
+        // one stream: the next tile's copies queue behind this tile's kernels
+    }
+    ctx->acc.bytes_h2d += h2d;
+    ctx->acc.bytes_d2h += d2h;
+    if (!grads->dX || n == 0) return SAGA_OK;
+
+    // ---- backward-Gather / ApplyEdge / Scatter: dX = (T dZ) W^T is the streamed forward schedule run on the edges
+    // grouped by source, with dZ as the vertex data and W^T as the ApplyVertex matrix (no bias, no activation) ----
+    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)F * Fo))) return st;
+    HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, F, Fo, SAGA_F32, ctx->ws_wt.p, F, 0, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));  // dZ has to be in host memory before the streamed schedule reads it
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz}) ctx->dev_free(b);  // make room under the budget
+    if ((st = ensure_transposed_host(ctx, g))) return st;
+    saga_tensor dz_t{};
+    dz_t.data = relu ? static_cast<void*>(ctx->h_dz) : dY->data;
+    dz_t.rows = n;
+    dz_t.cols = Fo;
+    dz_t.ld = relu ? Fo : dY->ld;
+    dz_t.dtype = SAGA_F32;
+    dz_t.mem = SAGA_MEM_HOST;
+    saga_tensor wt{};
+    wt.data = ctx->ws_wt.p;
+    wt.rows = Fo;
+    wt.cols = F;
+    wt.ld = F;
+    wt.dtype = SAGA_F32;
+    wt.mem = SAGA_MEM_DEVICE;
+    saga_vertex_params vt{};
+    vt.W = &wt;
+    vt.act = SAGA_ACT_NONE;
+    saga_edge_params et{};
+    et.op = ep->op;
+    return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX);
 }

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 3))) voi
 // every fourth split in order, and wavefront 0 adds the four sums in order: the grouping is fixed
 // by n_split alone.
 __global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ part, int64_t count, int n_split, int FQ, float* __restrict__ C,
-                                                    int64_t ldc)
+                                                    int64_t ldc, int accumulate)
 {
     __shared__ float red[4][64];
     const int e = threadIdx.x & 63, q = threadIdx.x >> 6;
@@ -157,7 +157,11 @@ __global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ pa
         for (int k = q; k < n_split; k += 4) s += part[(int64_t)k * count + i];
     red[q][e] = s;
     __syncthreads();
-    if (q == 0 && i < count) C[(i / FQ) * ldc + (i % FQ)] = ((red[0][e] + red[1][e]) + red[2][e]) + red[3][e];
+    if (q == 0 && i < count) {
+        float* c = C + (i / FQ) * ldc + (i % FQ);
+        const float r = ((red[0][e] + red[1][e]) + red[2][e]) + red[3][e];
+        *c = accumulate ? *c + r : r;  // accumulate: a later tile of rows adds to what earlier tiles left (streamed calls)
+    }
 }
 
 // backward-ApplyVertex's elementwise part over a slab of rows: dZ = dY where Y > 0, else 0 (ReLU's
@@ -288,7 +292,7 @@ void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, in
     *n_split = (int32_t)std::max<int64_t>(1, (n + rows - 1) / rows);
 }
 
-hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_t s)
+hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, int accumulate, hipStream_t s)
 {
     if (a.FP <= 0 || a.FQ <= 0) return hipSuccess;
     if (a.n_split < 1 || a.rows_per_split < 1 || a.rows_per_split % kKT != 0 || !a.part) return hipErrorInvalidValue;
@@ -304,14 +308,14 @@ hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_
         e = launch_tn_cfg<256, 32, 4, 1>(a, aligned, s);
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)a.FP * a.FQ;
-    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.part, count, a.n_split, a.FQ, C, ldc);
+    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.part, count, a.n_split, a.FQ, C, ldc, accumulate);
     return hipGetLastError();
 }
 
 int64_t colsum_slabs(int64_t rows) { return std::max<int64_t>(1, std::min<int64_t>(1024, (rows + 127) / 128)); }
 
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
-                            float* part, float* dbias, hipStream_t s)
+                            float* part, float* dbias, int accumulate, hipStream_t s)
 {
     if (F <= 0) return hipSuccess;
     if (!Y && !part) return hipSuccess;  // nothing to mask, nothing to sum
@@ -331,7 +335,7 @@ hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64
         hipLaunchKernelGGL((k_dz_colsum<1, false>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !part) return e;
-    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((F + 63) / 64)), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, dbias, (int64_t)F);
+    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((F + 63) / 64)), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, dbias, (int64_t)F, accumulate);
     return hipGetLastError();
 }
 

@@ -497,8 +497,9 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16})
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt})
         ctx->dev_free(b);
+    if (ctx->h_dz) (void)hipHostFree(ctx->h_dz);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
@@ -536,6 +537,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "overlap")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "overlap must be 0 or 1");
         ctx->opt_overlap = (int)value;
+    } else if (!strcmp(name, "bwd_tile_rows")) {
+        if (value < 0 || value > (1LL << 31)) return ctx->fail(SAGA_ERR_INVALID_ARG, "bwd_tile_rows must be in [0, 2^31]");
+        ctx->opt_bwd_tile_rows = value;
     } else if (!strcmp(name, "transform_first")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "transform_first must be 0 or 1");
         ctx->opt_transform_first = (int)value;
@@ -716,6 +720,7 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
             chunk_grid_destroy(ctx, g->grid);
             g->grid = nullptr;
         }
+        transposed_graph_destroy(ctx, g);  // its copy of the edge data, too
         return SAGA_OK;
     }
     g->tr_edge_data_valid = false;
@@ -1000,7 +1005,36 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (!ctx) return SAGA_ERR_INVALID_ARG;
     if (!g || !A || !dY || !ep || !vp || !grads) return ctx->fail(SAGA_ERR_INVALID_ARG, "null argument");
     if (g->ctx != ctx) return ctx->fail(SAGA_ERR_INVALID_ARG, "graph belongs to another context");
-    if (g->where != SAGA_MEM_DEVICE) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs a device-resident graph");
+    if (g->where == SAGA_MEM_HOST) {
+        // streamed: the layer's tensors live in host memory, parameters and their gradients on the device
+        auto f32_at = [](const saga_tensor* t, int32_t mem) { return tensor_ok(t) && t->mem == mem && t->dtype == SAGA_F32; };
+        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
+        if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
+        const saga_tensor* W = vp->W;
+        if (!W || !f32_at(W, SAGA_MEM_DEVICE) || W->rows > (1 << 20) || W->cols > (1 << 20))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out fp32 tensor");
+        const int64_t n = g->n, F = W->rows, Fo = W->cols;
+        if (!f32_at(A, SAGA_MEM_HOST) || A->rows != n || A->cols != F)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need A as a host n x F_in fp32 tensor");
+        if (!f32_at(dY, SAGA_MEM_HOST) || dY->rows != n || dY->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need dY as a host n x F_out fp32 tensor");
+        if (vp->act == SAGA_ACT_RELU && (!Y || !f32_at(Y, SAGA_MEM_HOST) || Y->rows != n || Y->cols != Fo))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a host n x F_out fp32 tensor");
+        if (!grads->dW || !f32_at(grads->dW, SAGA_MEM_DEVICE) || grads->dW->rows != F || grads->dW->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
+        if (grads->dbias && (!f32_at(grads->dbias, SAGA_MEM_DEVICE) || grads->dbias->rows * grads->dbias->cols != Fo))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
+        if (grads->dX && (!f32_at(grads->dX, SAGA_MEM_HOST) || grads->dX->rows != n || grads->dX->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need grads->dX as a host n x F_in fp32 tensor");
+        if (grads->dW_self || grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
+        if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
+        DeviceGuard guard_h(ctx->device);
+        return streamed_backward(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+    }
     if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
     const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
     if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");

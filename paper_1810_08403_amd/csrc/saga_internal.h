@@ -82,6 +82,7 @@ struct saga_ctx {
     int opt_dst_intervals = 0, opt_src_intervals = 0;
     int opt_schedule = 0;  // streamed path: 0 the paper's schedule, 1 stage by stage, 2 destination order innermost
     int opt_overlap = 1;   // streamed path: copies on their own streams
+    int64_t opt_bwd_tile_rows = 0;  // streamed backward: rows per tile of backward-ApplyVertex (0 = about 64 MiB)
     int opt_transform_first = 0;  // resident linear sum layers with F_out < F_in: Y = act(gather(X W) + bias)
 
     // reusable workspace (grown on demand, never shrunk until destroy)
@@ -99,6 +100,9 @@ struct saga_ctx {
     DevBuf ws_edge_t;    // per-call edge weights in the order of the transposed graph
     DevBuf ws_dh;        // gated layers: per-vertex gradients [dPs | dM | dPd]
     DevBuf ws_dz16;      // bf16 layers: the gradient of the pre-activation in bf16
+    DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
+    float* h_dz = nullptr;  // streamed backward: dZ of all vertices in pinned host memory (ReLU layers)
+    size_t h_dz_bytes = 0;
 
     // profiling
     bool profiling = false;
@@ -283,12 +287,12 @@ struct GemmTnArgs {
     int32_t pad_;
 };
 void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, int32_t* n_split);
-hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, hipStream_t s);
+hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, int accumulate, hipStream_t s);  // accumulate: C += P^T Q
 // One pass over the gradient rows: with Y, dZ (rows x F, compact) = dY where Y > 0, else 0 (without Y
 // nothing is stored: dZ is dY); with part (colsum_slabs(rows) x F floats), dbias[c] = sum over rows of dZ[r][c].
 int64_t colsum_slabs(int64_t rows);
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, float* dZ, int64_t rows, int32_t F,
-                            float* part, float* dbias, hipStream_t s);
+                            float* part, float* dbias, int accumulate, hipStream_t s);  // accumulate: dbias += the sums
 // bf16 layers: dZ (rows x F, compact) = dY where Y > 0 (Y NULL: dY), as fp32 and as bf16
 hipError_t launch_dz_bf16(const uint16_t* dY, int64_t lddy, const uint16_t* Y, int64_t ldy, float* dZ32, uint16_t* dZ16, int64_t rows,
                           int32_t F, hipStream_t s);
@@ -309,6 +313,9 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
                               const saga_layer_grads* grads);
 saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
+// backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
+saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)

@@ -167,3 +167,46 @@ def test_reencoded_graph_gives_the_permuted_oracle_result(wl):
     Y = _streamed(ctx, w2, graph, "sum")
     assert_sum_close(Y[new_id.long().numpy()], ref["Y"], ref["Y_abs"], TOL_F32, "sum layer on re-encoded ids")
     ctx.destroy()
+
+
+@pytest.mark.parametrize("act,edge_op,Q,P,tile", [("relu", "mul_weight", 2, 3, 1000), ("none", "mul_weight", 1, 4, 0), ("relu", "copy", 3, 3, 4096),
+                                                  ("none", "copy", 1, 1, 777)])
+def test_streamed_backward_matches_oracle(wl, act, edge_op, Q, P, tile):
+    """Backward pass with everything but the parameters in host memory: tiles of backward-ApplyVertex, then the chunk
+    schedule over the edges clustered by source."""
+    import oracle
+    import paper_1810_08403_amd as saga
+    g = wl.graph
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    w = wl.edge_weight.numpy() if edge_op == "mul_weight" else None
+    dY = si.normal_features(n, Fo, 21)
+    bias = si.uniform_pm(Fo, 0.3, 3)
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op, w, W=wl.W.numpy(), bias=bias.numpy(), act=act)
+    bwd = oracle.layer_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), edge_op, w, bias=bias.numpy(), act=act)
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", Q), ("src_intervals", P), ("bwd_tile_rows", tile)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)        # host graph
+    if edge_op == "mul_weight":
+        graph.set_edge_data(wl.edge_weight)
+    pin = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).pin_memory()
+    A_h, Y_h, dY_h = pin(fwd["A"]), pin(fwd["Y"]), pin(dY.numpy())
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    dW, db = torch.full((F, Fo), float("nan"), device="cuda"), torch.full((Fo,), float("nan"), device="cuda")
+    for rep in range(2):                                           # the second call reuses the transposed chunk grid
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, Y=Y_h, edge_op=edge_op, bias=bias.cuda(), act=act, dX=dX_h, dbias=db)
+        torch.cuda.synchronize()
+        what = f"streamed backward {act} {edge_op} {Q}x{P} tile {tile} call {rep}"
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+        assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+        dZ = dY.numpy().astype(np.float64) * ((fwd["Y"] > 0) if act == "relu" else 1.0)
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(np.abs(dZ).sum(0), 1e-30), TOL_F32, what + " dbias")
+        dX_h.fill_(float("nan"))
+    # a forward call on the same graph still works afterwards (its own chunk grid is untouched)
+    Yf = torch.empty(n, Fo).pin_memory()
+    kw = dict(edge_op=edge_op, W=wl.W.cuda(), act=act, bias=bias.cuda())
+    ctx.layer_forward(graph, wl.X.clone().pin_memory(), Yf, **kw)
+    assert_sum_close(Yf.numpy(), fwd["Y"], fwd["Y_abs"], TOL_F32, "forward after backward")
+    ctx.destroy()
