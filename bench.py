@@ -384,6 +384,31 @@ def bench_streamed(args):
                         "note": "H2D + D2H bytes per second against 2 x 64 GB/s (PCIe Gen5 x16, both directions)",
                         "h2d_bytes_per_step": tm["bytes_h2d"] // steps, "d2h_bytes_per_step": tm["bytes_d2h"] // steps},
            "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 2), "first_calls": round(t_first, 2)}}
+    if args.backward:
+        if args.agg != "sum":
+            print("bench.py: the streamed backward pass covers the sum accumulator", file=sys.stderr)
+            sys.exit(2)
+        A = torch.empty(n, X.shape[1]).pin_memory()
+        A.copy_(X)                                   # any n x F_in matrix serves as the kept Gather output for timing
+        dY = torch.empty(n, W.shape[1]).pin_memory()
+        dY.copy_(Y)
+        dX = torch.empty(n, X.shape[1]).pin_memory()
+        dW, db = torch.empty_like(W), torch.empty(W.shape[1], device="cuda")
+        t0 = time.time()
+        ctx.layer_backward(graph, A, dY, W, dW, Y=Y, edge_op="mul_weight", act="relu", dX=dX, dbias=db)   # builds the transposed grid
+        torch.cuda.synchronize()
+        t_first_b = time.time() - t0
+        ctx.reset_timings()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ctx.layer_backward(graph, A, dY, W, dW, Y=Y, edge_op="mul_weight", act="relu", dX=dX, dbias=db)
+        torch.cuda.synchronize()
+        ms_b = (time.perf_counter() - t0) * 1e3 / steps
+        tb = ctx.get_timings()
+        out["backward"] = {"ms_per_step": round(ms_b, 2), "gteps": round(nnz / (ms_b * 1e-3) / 1e9, 4),
+                           "h2d_bytes_per_step": tb["bytes_h2d"] // steps, "d2h_bytes_per_step": tb["bytes_d2h"] // steps,
+                           "plan": [tb["plan_dst_intervals"], tb["plan_src_intervals"]], "first_call_s": round(t_first_b, 2),
+                           "peak_device_bytes": ctx.peak_device_bytes()}
     print(json.dumps(out))
 
 

@@ -644,6 +644,14 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     // ---- backward-ApplyVertex, a tile of rows at a time: dZ, the bias sums, dW += A^T dZ ----
     const int64_t t_auto = std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)std::max(F, Fo)));
     const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), ctx->opt_bwd_tile_rows > 0 ? ctx->opt_bwd_tile_rows : t_auto));
+    {
+        // the buffers of an earlier streamed call may fill the budget: they are rebuilt by the propagation below anyway
+        const size_t tiles = sizeof(float) * (size_t)T * ((size_t)F + 3 * (size_t)Fo) + sizeof(float) * (size_t)colsum_slabs(T) * Fo;
+        if (ctx->budget > 0 && ctx->cur_bytes + tiles > ctx->budget)
+            for (DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
+                              &ctx->st_partials})
+                ctx->dev_free(b);
+    }
     if ((st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F))) return st;   // A tile
     if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)T * Fo))) return st;   // dY tile
     if (relu) {

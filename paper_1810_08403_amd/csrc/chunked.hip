@@ -39,8 +39,8 @@ struct ChunkGrid {
     std::vector<ChunkMeta> chunks;  // [j * P + i]
     size_t max_chunk_bytes = 0;
     int64_t max_slots = 0;
-    // device side
-    DevBuf A, V[2], C[2], Ystage[2], partials;
+    // device side: the buffers themselves belong to the context (one streamed call runs at a time, and the forward
+    // grid of a graph and the grid of its transposed twin must share one budget)
     hipStream_t s_in = nullptr, s_out = nullptr;
     hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
@@ -54,8 +54,7 @@ void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
     if (!g) return;
     for (auto& c : g->chunks)
         if (c.host) (void)hipHostFree(c.host);
-    for (DevBuf* b : {&g->A, &g->V[0], &g->V[1], &g->C[0], &g->C[1], &g->Ystage[0], &g->Ystage[1], &g->partials})
-        ctx->dev_free(b);
+    (void)ctx;
     for (hipEvent_t e : {g->ev_ready[0], g->ev_ready[1], g->ev_free[0], g->ev_free[1], g->ev_y_ready[0], g->ev_y_ready[1],
                          g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done, g->ev_a_ready, g->ev_a_in})
         if (e) (void)hipEventDestroy(e);
@@ -325,13 +324,22 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
 
     // ---- device buffers, all counted against the budget ----
     saga_status st;
-    if ((st = ctx->dev_alloc(&grid->A, (size_t)Dq * F * 4))) return st;
-    for (int b = 0; b < 2; ++b) {
-        if ((st = ctx->dev_alloc(&grid->V[b], (size_t)Sp * F * 4))) return st;
-        if ((st = ctx->dev_alloc(&grid->C[b], std::max<size_t>(grid->max_chunk_bytes, 256)))) return st;
-        if (has_w && (st = ctx->dev_alloc(&grid->Ystage[b], (size_t)y_tile_rows * F_out * 4))) return st;
+    {
+        DevBuf* bufs[8] = {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
+                           &ctx->st_partials};
+        const size_t c_bytes = std::max<size_t>(grid->max_chunk_bytes, 256);
+        const size_t y_bytes = has_w ? (size_t)y_tile_rows * F_out * 4 : 0;
+        const size_t want[8] = {(size_t)Dq * F * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
+                                grid->max_slots > 0 ? (size_t)grid->max_slots * F * 4 : 0};
+        bool fits = true;
+        for (int b = 0; b < 8; ++b) fits = fits && bufs[b]->bytes >= want[b];
+        if (!fits) {
+            // another plan left its buffers: start from nothing, so that this plan's own sizes are what counts against the budget
+            for (DevBuf* b : bufs) ctx->dev_free(b);
+            for (int b = 0; b < 8; ++b)
+                if (want[b] > 0 && (st = ctx->dev_alloc(bufs[b], want[b]))) return st;
+        }
     }
-    if (grid->max_slots > 0 && (st = ctx->dev_alloc(&grid->partials, (size_t)grid->max_slots * F * 4))) return st;
     if (ctx->budget > 0 && ctx->cur_bytes > ctx->budget)
         return ctx->fail(SAGA_ERR_BUDGET, "plan %d x %d needs %zu bytes of device memory, budget is %zu", Q, P, ctx->cur_bytes,
                          ctx->budget);
@@ -342,7 +350,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const int schedule = has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0;
     const float* Xh = static_cast<const float*>(X->data);
     float* Yh = static_cast<float*>(Y->data);
-    float* A = static_cast<float*>(grid->A.p);
+    float* A = static_cast<float*>(ctx->st_A.p);
     int64_t bytes_h2d = 0, bytes_d2h = 0;
     int64_t step = 0, ystep = 0;
     bool used[2] = {false, false}, yused[2] = {false, false};
@@ -384,22 +392,22 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
         if (load_v) {
             if (vb != b && used[vb]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[vb], 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(grid->V[vb].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
+            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_V[vb].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
                                           (size_t)srows, hipMemcpyHostToDevice, sin));
             bytes_h2d += srows * F * 4;
         }
-        HIP_TRY(ctx, hipMemcpyAsync(grid->C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->st_C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
         HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
         bytes_h2d += (int64_t)m.bytes;
         HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_ready[b], 0));
-        const char* cb = static_cast<const char*>(grid->C[b].p);
+        const char* cb = static_cast<const char*>(ctx->st_C[b].p);
         GatherArgs ga{};
         ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
         ga.n_items = m.n_items;
         ga.n_team = m.n_team;
         ga.row_idx = reinterpret_cast<const int32_t*>(cb + m.off_ridx);
         ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
-        ga.src = grid->V[vb].p;
+        ga.src = ctx->st_V[vb].p;
         ga.ld_src = F;
         ga.F = (int32_t)F;
         ga.dtype = SAGA_F32;
@@ -407,7 +415,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         ga.agg = agg;
         ga.out = A;
         ga.ld_out = F;
-        ga.partials = static_cast<float*>(grid->partials.p);
+        ga.partials = static_cast<float*>(ctx->st_partials.p);
         ga.accumulate = 1;
         ga.xcd_remap = ctx->opt_xcd_remap;
         HIP_TRY(ctx, launch_gather(ga, sc));
@@ -452,7 +460,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ge.Bt = ctx->ws_bt.p;
             ge.ldbt = k_pad;
             ge.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
-            ge.C = grid->Ystage[b].p;
+            ge.C = ctx->st_Y[b].p;
             ge.ldc = F_out;
             ge.M = tr;
             ge.N = (int32_t)F_out;
@@ -462,7 +470,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             HIP_TRY(ctx, launch_gemm(ge, sc));
             HIP_TRY(ctx, hipEventRecord(grid->ev_y_ready[b], sc));
             HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_y_ready[b], 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + (v0 + r0) * Y->ld, (size_t)Y->ld * 4, grid->Ystage[b].p, (size_t)F_out * 4,
+            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + (v0 + r0) * Y->ld, (size_t)Y->ld * 4, ctx->st_Y[b].p, (size_t)F_out * 4,
                                           (size_t)F_out * 4, (size_t)tr, hipMemcpyDeviceToHost, sout));
             HIP_TRY(ctx, hipEventRecord(grid->ev_y_free[b], sout));
             bytes_d2h += tr * F_out * 4;

@@ -100,6 +100,8 @@ struct saga_ctx {
     DevBuf ws_edge_t;    // per-call edge weights in the order of the transposed graph
     DevBuf ws_dh;        // gated layers: per-vertex gradients [dPs | dM | dPd]
     DevBuf ws_dz16;      // bf16 layers: the gradient of the pre-activation in bf16
+    // streamed calls: accumulator interval, two vertex intervals, two chunk payloads, two output tiles, partial rows
+    DevBuf st_A, st_V[2], st_C[2], st_Y[2], st_partials;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
     float* h_dz = nullptr;  // streamed backward: dZ of all vertices in pinned host memory (ReLU layers)
     size_t h_dz_bytes = 0;

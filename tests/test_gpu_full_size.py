@@ -151,3 +151,51 @@ def test_config5_full_streamed_under_16gb(agg):
     ctx.destroy()
     if agg == "max":
         del test_config5_full_streamed_under_16gb.wl
+
+
+def test_config5_full_streamed_backward_under_16gb():
+    """Configuration 5's layer backwards at full size (R-MAT 23, 515 M edges, 256 -> 256, ReLU), everything but the
+    parameters in host memory, 16 GiB device budget; sampled rows of dX and entries of dW from the oracle."""
+    import paper_1810_08403_amd as saga
+    wl = si.workload(5, device="cuda")
+    g = wl.graph
+    n, F, Fo = g.n, 256, 256
+    host = si.CSC(n, g.col_ptr.cpu(), g.row_idx.cpu())
+    W, w = wl.W.clone(), wl.edge_weight.cpu()
+    del wl, g
+    torch.cuda.empty_cache()
+    # a synthetic Gather output (backward takes it as given), Y = ReLU(A W) formed in fp64 so that the signs are the oracle's
+    A_h = torch.empty(n, F).pin_memory()
+    Y_h = torch.empty(n, Fo).pin_memory()
+    dY_h = torch.empty(n, Fo).pin_memory()
+    step = 1 << 20
+    for r0 in range(0, n, step):
+        a = si.normal(311, r0 // step, step * F, device="cuda").view(step, F)
+        A_h[r0:r0 + step] = a.cpu()
+        Y_h[r0:r0 + step] = torch.relu(a.double() @ W.double()).float().cpu()
+        dY_h[r0:r0 + step] = si.normal(312, r0 // step, step * Fo, device="cuda").view(step, Fo).cpu()
+    del a
+    torch.cuda.empty_cache()
+    budget = 16 * (1 << 30)
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    graph = ctx.graph_create_csc(n, host.col_ptr, host.row_idx)
+    graph.set_edge_data(w)
+    dX_h = torch.empty(n, F).pin_memory()
+    dW, db = torch.empty(F, Fo, device="cuda"), torch.empty(Fo, device="cuda")
+    ctx.layer_backward(graph, A_h, dY_h, W, dW, Y=Y_h, edge_op="mul_weight", act="relu", dX=dX_h, dbias=db)
+    torch.cuda.synchronize()
+    t = ctx.get_timings()
+    assert ctx.peak_device_bytes() <= budget
+    print(f"config5 backward: plan {t['plan_dst_intervals']} x {t['plan_src_intervals']}, H2D {t['bytes_h2d'] / 1e9:.1f} GB, "
+          f"D2H {t['bytes_d2h'] / 1e9:.1f} GB, peak device {ctx.peak_device_bytes() / 1e9:.2f} GB")
+    rng = np.random.default_rng(6)
+    ul = np.unique(np.concatenate([rng.choice(n, 120, replace=False), [0, n - 1]])).astype(np.int64)
+    we = [(0, 0), (255, 0), (100, 7), (31, 7)]
+    ref = oracle.backward_sample(host.col_ptr.numpy(), host.row_idx.numpy(), None, A_h.numpy(), dY_h.numpy(), W.cpu().numpy(), ul, we,
+                                 "mul_weight", w.numpy(), act="relu")
+    assert_sum_close(dX_h[ul].numpy(), ref["dX"], ref["dX_abs"], TOL_F32, "config 5 backward dX")
+    got = np.array([dW[f, o].item() for f, o in we])
+    assert_sum_close(got, ref["dW"], ref["dW_abs"], TOL_F32, "config 5 backward dW")
+    dz = dY_h.double() * (Y_h > 0)
+    assert_sum_close(db.cpu().numpy(), dz.sum(0).numpy(), dz.abs().sum(0).numpy(), TOL_F32, "config 5 backward dbias")
+    ctx.destroy()
