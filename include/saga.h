@@ -240,13 +240,15 @@ typedef struct saga_layer_grads {
  *
  * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, no W_self):
  * A, Y, dY and grads->dX are SAGA_MEM_HOST tensors (pinned recommended), W and the parameter
- * gradients stay on the device. backward-ApplyVertex runs over tiles of rows (dW and dbias
- * accumulate tile by tile in a fixed order; for RELU dZ is written to pinned host memory held
- * by the context). The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is the forward
- * chunk schedule of Section 3.1 run on the chunks of edges clustered by source (the CSR side
- * of the paper's chunk layout), with dZ as the vertex data and W^T as the ApplyVertex matrix;
- * the transposed chunk grid is built at the first such call. Every transfer goes through the
- * context's device budget like in saga_layer_forward.
+ * gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
+ * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
+ * (the CSR side of the paper's chunk layout), with dZ as the vertex data and W^T as the
+ * ApplyVertex matrix; the transposed chunk grid is built at the first such call. dZ is formed
+ * on the way in: a vertex interval's rows of dY (and Y for RELU) are copied to the device and
+ * masked in place, and the first time an interval comes by, its rows of A are copied too and
+ * its share of dW and dbias is added (interval by interval in a fixed order). Without
+ * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Every transfer goes
+ * through the context's device budget like in saga_layer_forward.
  *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self): X is not
  * needed, Y, dY and grads->dX are bf16 like W, A stays the fp32 accum_out of the forward

@@ -185,7 +185,7 @@ static saga_status rows_times_wt(saga_ctx* ctx, const float* Arows, int64_t lda,
 }
 
 static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_t FP, const float* Q, int64_t ldq, int32_t FQ,
-                              int64_t n, float* C, int64_t ldc, int accumulate = 0)
+                              int64_t n, float* C, int64_t ldc, int accumulate = 0, hipStream_t on = nullptr, bool grow = true)
 {
     GemmTnArgs ta{};
     ta.P = P;
@@ -196,9 +196,14 @@ static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_
     ta.FP = FP;
     ta.FQ = FQ;
     gemm_tn_plan(n, FP, FQ, &ta.rows_per_split, &ta.n_split);
-    if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)ta.n_split * FP * FQ)) return st;
+    const size_t need = sizeof(float) * (size_t)ta.n_split * FP * FQ;
+    if (grow) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, need)) return st;
+    } else if (ctx->ws_splitk.bytes < need) {  // inside a pipeline: the caller sized the workspace beforehand
+        return ctx->fail(SAGA_ERR_INTERNAL, "split workspace too small");
+    }
     ta.part = static_cast<float*>(ctx->ws_splitk.p);
-    HIP_TRY(ctx, launch_gemm_tn(ta, C, ldc, accumulate, ctx->stream));
+    HIP_TRY(ctx, launch_gemm_tn(ta, C, ldc, accumulate, on ? on : ctx->stream));
     return SAGA_OK;
 }
 
@@ -632,20 +637,19 @@ static saga_status ensure_transposed_host(saga_ctx* ctx, saga_graph* g)
     return SAGA_OK;
 }
 
-saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
-                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+// Parameter gradients of a streamed layer without the propagation: backward-ApplyVertex over tiles of rows copied in
+// from host memory on the context's stream (dZ, the bias sums, dW += A^T dZ, tile after tile in a fixed order).
+static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                                        const saga_vertex_params* vp, const saga_layer_grads* grads)
 {
-    const int64_t n = g->n;
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
     const bool relu = vp->act == SAGA_ACT_RELU;
     hipStream_t s = ctx->stream;
     saga_status st;
-
-    // ---- backward-ApplyVertex, a tile of rows at a time: dZ, the bias sums, dW += A^T dZ ----
     const int64_t t_auto = std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)std::max(F, Fo)));
     const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), ctx->opt_bwd_tile_rows > 0 ? ctx->opt_bwd_tile_rows : t_auto));
     {
-        // the buffers of an earlier streamed call may fill the budget: they are rebuilt by the propagation below anyway
+        // the buffers of an earlier streamed call may fill the budget: the next streamed call rebuilds them
         const size_t tiles = sizeof(float) * (size_t)T * ((size_t)F + 3 * (size_t)Fo) + sizeof(float) * (size_t)colsum_slabs(T) * Fo;
         if (ctx->budget > 0 && ctx->cur_bytes + tiles > ctx->budget)
             for (DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
@@ -657,14 +661,6 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     if (relu) {
         if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)T * Fo))) return st;  // Y tile
         if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)T * Fo))) return st;     // dZ tile
-        const size_t need = sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fo;
-        if (ctx->h_dz_bytes < need) {
-            if (ctx->h_dz) (void)hipHostFree(ctx->h_dz);
-            ctx->h_dz = nullptr;
-            ctx->h_dz_bytes = 0;
-            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_dz), need, hipHostMallocDefault));
-            ctx->h_dz_bytes = need;
-        }
     }
     if (grads->dbias)
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(T) * Fo))) return st;
@@ -694,28 +690,79 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
                                           grads->dbias ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
                                           grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, acc, s));
         if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
-        if (relu && rows > 0 && grads->dX) {
-            HIP_TRY(ctx, hipMemcpyAsync(ctx->h_dz + r0 * Fo, tdZ, sizeof(float) * (size_t)rows * Fo, hipMemcpyDeviceToHost, s));
-            d2h += rows * (int64_t)Fo * 4;
-        }
         // one stream: the next tile's copies queue behind this tile's kernels
     }
     ctx->acc.bytes_h2d += h2d;
     ctx->acc.bytes_d2h += d2h;
-    if (!grads->dX || n == 0) return SAGA_OK;
+    return SAGA_OK;
+}
 
-    // ---- backward-Gather / ApplyEdge / Scatter: dX = (T dZ) W^T is the streamed forward schedule run on the edges
-    // grouped by source, with dZ as the vertex data and W^T as the ApplyVertex matrix (no bias, no activation) ----
+saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    const bool relu = vp->act == SAGA_ACT_RELU;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+
+    if (!grads->dX || n == 0) return streamed_param_grads(ctx, n, A, Y, dY, vp, grads);
+
+    // ---- with dX: one pass. The propagation dX = (T dZ) W^T is the streamed forward schedule run on the edges grouped by
+    // source, with dZ as the vertex data and W^T as the ApplyVertex matrix (no bias, no activation). dZ is not read
+    // from anywhere: a source interval's rows of dY (and Y, A) are copied in, dZ is formed in place in the interval's
+    // buffer, and the first time an interval comes by its share of dW and dbias is added, on the copy-in stream. ----
     if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)F * Fo))) return st;
     HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, F, Fo, SAGA_F32, ctx->ws_wt.p, F, 0, s));
-    HIP_TRY(ctx, hipStreamSynchronize(s));  // dZ has to be in host memory before the streamed schedule reads it
-    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz}) ctx->dev_free(b);  // make room under the budget
+    {
+        // the split workspace for the largest interval there can be, so that nothing is allocated inside the pipeline
+        int64_t rps;
+        int32_t nsp;
+        gemm_tn_plan(n, F, Fo, &rps, &nsp);
+        const size_t need = std::max(sizeof(float) * (size_t)nsp * F * Fo, sizeof(float) * (size_t)colsum_slabs(n) * Fo);
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, need))) return st;
+    }
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist}) ctx->dev_free(b);  // sized per interval below
     if ((st = ensure_transposed_host(ctx, g))) return st;
+    bool any_done = false;
+    VertexFeed feed;
+    feed.bytes_per_row = sizeof(float) * ((size_t)F + (relu ? (size_t)Fo : 0));
+    feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool first_visit, int64_t* h2d) -> saga_status {
+        auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)Fo, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
+                                      sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * (int64_t)Fo * 4;
+        const bool sums = first_visit && grads->dbias;
+        if (relu) {
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fo)) return e;  // grows once: intervals do not grow
+            float* tY = static_cast<float*>(ctx->ws_hoist.p);
+            HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_of_t(Y, row0), sizeof(float) * (size_t)Y->ld,
+                                          sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)Fo * 4;
+        }
+        if (relu || sums)   // in place: every element is read and written by one thread
+            HIP_TRY(ctx, launch_dz_colsum(dst, Fo, relu ? static_cast<const float*>(ctx->ws_hoist.p) : nullptr, Fo, dst, rows, Fo,
+                                          sums ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
+                                          sums ? static_cast<float*>(grads->dbias->data) : nullptr, any_done ? 1 : 0, on));
+        if (first_visit) {
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)rows * F)) return e;
+            float* tA = static_cast<float*>(ctx->ws_accum.p);
+            HIP_TRY(ctx, hipMemcpy2DAsync(tA, sizeof(float) * (size_t)F, rows_of_t(A, row0), sizeof(float) * (size_t)A->ld,
+                                          sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)F * 4;
+            if (saga_status e = param_grad(ctx, tA, F, F, dst, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld,
+                                           any_done ? 1 : 0, on, false))
+                return e;
+            any_done = true;
+        }
+        return SAGA_OK;
+    };
+    HIP_TRY(ctx, hipStreamSynchronize(s));  // W^T is packed on the context's stream, the feed works on the copy-in stream
     saga_tensor dz_t{};
-    dz_t.data = relu ? static_cast<void*>(ctx->h_dz) : dY->data;
+    dz_t.data = nullptr;  // shape only: the feed supplies the rows
     dz_t.rows = n;
     dz_t.cols = Fo;
-    dz_t.ld = relu ? Fo : dY->ld;
+    dz_t.ld = Fo;
     dz_t.dtype = SAGA_F32;
     dz_t.mem = SAGA_MEM_HOST;
     saga_tensor wt{};
@@ -730,5 +777,5 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     vt.act = SAGA_ACT_NONE;
     saga_edge_params et{};
     et.op = ep->op;
-    return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX);
+    return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX, &feed);
 }

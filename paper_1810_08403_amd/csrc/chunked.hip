@@ -263,7 +263,7 @@ size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t F_out, b
 }  // namespace
 
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
-                             const saga_vertex_params* vp, saga_tensor* Y)
+                             const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed)
 {
     const auto t_begin = std::chrono::steady_clock::now();
     const int64_t n = g->n;
@@ -302,7 +302,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 if ((P > 0 && p != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
                 count_grid(g, q, p, &nnz, &pairs);
-                const size_t need = plan_bytes(g, q, p, F, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs);
+                const size_t need = plan_bytes(g, q, p, F, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs) +
+                                    (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
                 if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need <= ctx->budget)) {
                     Q = q;
@@ -347,7 +348,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // "overlap" 0 puts every copy on the compute stream: nothing overlaps (the streaming-off baseline)
     hipStream_t sc = ctx->stream;
     hipStream_t sin = ctx->opt_overlap ? grid->s_in : sc, sout = ctx->opt_overlap ? grid->s_out : sc;
-    const int schedule = has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0;
+    const int schedule = feed ? 0 : (has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0);
+    std::vector<char> seen(feed ? (size_t)P : 0, 0);  // source intervals the feed has been called for
     const float* Xh = static_cast<const float*>(X->data);
     float* Yh = static_cast<float*>(Y->data);
     float* A = static_cast<float*>(ctx->st_A.p);
@@ -392,9 +394,21 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
         if (load_v) {
             if (vb != b && used[vb]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[vb], 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_V[vb].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
-                                          (size_t)srows, hipMemcpyHostToDevice, sin));
-            bytes_h2d += srows * F * 4;
+            if (feed) {
+                if (saga_status fs = feed->fill(s0, srows, static_cast<float*>(ctx->st_V[vb].p), sin, !seen[(size_t)i], &bytes_h2d))
+                    return fs;
+                seen[(size_t)i] = 1;
+            } else {
+                HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_V[vb].p, (size_t)F * 4, Xh + s0 * X->ld, (size_t)X->ld * 4, (size_t)F * 4,
+                                              (size_t)srows, hipMemcpyHostToDevice, sin));
+                bytes_h2d += srows * F * 4;
+            }
+        }
+        if (m.nnz == 0) {  // only a feed brings us here: the interval had to be visited, there is nothing to add
+            HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sin));
+            used[b] = true;
+            ++step;
+            return SAGA_OK;
         }
         HIP_TRY(ctx, hipMemcpyAsync(ctx->st_C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
         HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
@@ -499,7 +513,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         bytes_h2d += rows_of(j) * F * 4;
         return SAGA_OK;
     };
-    auto has_edges = [&](int i, int j) { return grid->chunks[(size_t)j * P + i].nnz > 0; };
+    auto has_edges = [&](int i, int j) { return grid->chunks[(size_t)j * P + i].nnz > 0 || (feed && !seen[(size_t)i]); };
 #define SAGA_STEP(call)                       \
     do {                                      \
         if (saga_status st__ = (call)) return st__; \

@@ -500,7 +500,6 @@ saga_status saga_destroy(saga_ctx* ctx)
                       &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
                       &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials})
         ctx->dev_free(b);
-    if (ctx->h_dz) (void)hipHostFree(ctx->h_dz);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <functional>
 #include <string>
 #include <vector>
 
@@ -103,8 +104,6 @@ struct saga_ctx {
     // streamed calls: accumulator interval, two vertex intervals, two chunk payloads, two output tiles, partial rows
     DevBuf st_A, st_V[2], st_C[2], st_Y[2], st_partials;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
-    float* h_dz = nullptr;  // streamed backward: dZ of all vertices in pinned host memory (ReLU layers)
-    size_t h_dz_bytes = 0;
 
     // profiling
     bool profiling = false;
@@ -321,8 +320,17 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)
+// A VertexFeed replaces the plain host-to-device copy of a source interval's rows: fill() enqueues on `s` whatever leaves
+// rows [row0, row0 + rows) of the vertex data in dst (rows x F, compact). It is called once per (destination interval,
+// source interval) pair in schedule order, also for pairs without edges the first time an interval is seen
+// (first_visit), and adds the bytes it copies to *h2d. bytes_per_row: device bytes it holds per row of an interval,
+// for the planner. With a feed, X only supplies the shape and the paper's schedule is used.
+struct VertexFeed {
+    std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, bool first_visit, int64_t* h2d)> fill;
+    size_t bytes_per_row = 0;
+};
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
-                             int32_t agg, const saga_vertex_params* vp, saga_tensor* Y);
+                             int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr);
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device

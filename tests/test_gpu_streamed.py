@@ -204,6 +204,13 @@ def test_streamed_backward_matches_oracle(wl, act, edge_op, Q, P, tile):
         dZ = dY.numpy().astype(np.float64) * ((fwd["Y"] > 0) if act == "relu" else 1.0)
         assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(np.abs(dZ).sum(0), 1e-30), TOL_F32, what + " dbias")
         dX_h.fill_(float("nan"))
+    # without dX only backward-ApplyVertex runs, over tiles of rows
+    dW.fill_(float("nan"))
+    db.fill_(float("nan"))
+    ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, Y=Y_h, edge_op=edge_op, bias=bias.cuda(), act=act, dbias=db)
+    torch.cuda.synchronize()
+    assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, "parameter gradients only: dW")
+    assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(np.abs(dZ).sum(0), 1e-30), TOL_F32, "parameter gradients only: dbias")
     # a forward call on the same graph still works afterwards (its own chunk grid is untouched)
     Yf = torch.empty(n, Fo).pin_memory()
     kw = dict(edge_op=edge_op, W=wl.W.cuda(), act=act, bias=bias.cuda())
