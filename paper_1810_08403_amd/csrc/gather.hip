@@ -68,6 +68,15 @@ __device__ __forceinline__ float finish_vertex(float y, float bias, int act)
     return y;
 }
 
+// A 16-byte store that is not going to be read again by this kernel (partial rows, finished rows): marked
+// non-temporal so that it does not displace the band of source rows the wavefronts around it are sharing in the L2.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream4(float* p, float a, float b, float c, float d)
+{
+    const f32x4_t v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
+}
+
 // ---- 16-byte (or one-element) row fragments --------------------------------
 template <typename T, int VEC>
 struct Frag;
@@ -150,7 +159,7 @@ __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, 
         if constexpr (VEC % 4 == 0) {
 #pragma unroll
             for (int j = 0; j < VEC; j += 4)
-                *reinterpret_cast<float4*>(p + j) = make_float4(val[j], val[j + 1], val[j + 2], val[j + 3]);
+                store_stream4(p + j, val[j], val[j + 1], val[j + 2], val[j + 3]);
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) p[j] = val[j];
@@ -177,7 +186,7 @@ __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, 
         if constexpr (VEC % 4 == 0) {
 #pragma unroll
             for (int j = 0; j < VEC; j += 4)
-                *reinterpret_cast<float4*>(p + j) = make_float4(outv[j], outv[j + 1], outv[j + 2], outv[j + 3]);
+                store_stream4(p + j, outv[j], outv[j + 1], outv[j + 2], outv[j + 3]);
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) p[j] = outv[j];
@@ -191,7 +200,7 @@ __device__ __forceinline__ void store_row(const GatherArgs& a, int v, int slot, 
             pk.y = f32_to_bf16_rne(outv[2]) | ((uint32_t)f32_to_bf16_rne(outv[3]) << 16);
             pk.z = f32_to_bf16_rne(outv[4]) | ((uint32_t)f32_to_bf16_rne(outv[5]) << 16);
             pk.w = f32_to_bf16_rne(outv[6]) | ((uint32_t)f32_to_bf16_rne(outv[7]) << 16);
-            *reinterpret_cast<uint4*>(p) = pk;
+            store_stream4(reinterpret_cast<float*>(p), __uint_as_float(pk.x), __uint_as_float(pk.y), __uint_as_float(pk.z), __uint_as_float(pk.w));
         } else {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) p[j] = f32_to_bf16_rne(outv[j]);
@@ -531,9 +540,9 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
         const int my = eb + lane;
         id_out = 0;
         w_out = 1.0f;
-        if (my < it.e1) {
-            id_out = ridx[my];
-            if ((!GATED || EF == kEfMaxGrad) && ew) w_out = ew[my];
+        if (my < it.e1) {  // read once: keep them out of the way of the rows in the L2
+            id_out = __builtin_nontemporal_load(ridx + my);
+            if ((!GATED || EF == kEfMaxGrad) && ew) w_out = __builtin_nontemporal_load(ew + my);
         }
     };
     int idx_next;
@@ -631,8 +640,8 @@ __global__ __launch_bounds__(256) void k_combine(const CombineArgs a)
     const int f = blockIdx.y * 256 + threadIdx.x;
     if (f >= a.F) return;
     const float* p = a.partials + (int64_t)h.slot0 * a.F + f;
-    float r = p[0];
-    for (int s = 1; s < h.nslots; ++s) r = combine<AGG>(r, p[(int64_t)s * a.F]);
+    float r = __builtin_nontemporal_load(p);
+    for (int s = 1; s < h.nslots; ++s) r = combine<AGG>(r, __builtin_nontemporal_load(p + (int64_t)s * a.F));
     if (a.accumulate) r = combine<AGG>(a.out[(int64_t)h.v * a.ld_out + f], r);
     if (a.bias || a.act != SAGA_ACT_NONE) r = finish_vertex(r, a.bias ? a.bias[f] : 0.f, a.act);
     if (a.out) a.out[(int64_t)h.v * a.ld_out + f] = r;
