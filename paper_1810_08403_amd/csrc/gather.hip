@@ -633,19 +633,74 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
 // ---------------------------------------------------------------------------
 // combine the partial rows of split vertices, in slot order
 // ---------------------------------------------------------------------------
-template <int AGG>
-__global__ __launch_bounds__(256) void k_combine(const CombineArgs a)
+// One thread per 16-byte fragment of a row (per element when the row does not allow fragments); the rows of as many
+// cut columns as fit share a block. The partial rows are added strictly in slot order; four loads are issued before
+// the first of them is added.
+template <int AGG, int VEC>
+__global__ __launch_bounds__(256) void k_combine(const CombineArgs a, const int tpr, const int rows_per_block)
 {
-    const HeavyVertex h = a.heavy[blockIdx.x];
-    const int f = blockIdx.y * 256 + threadIdx.x;
-    if (f >= a.F) return;
+    int hv, frag;
+    if (rows_per_block == 1) {
+        hv = blockIdx.x;
+        frag = blockIdx.y * 256 + threadIdx.x;
+    } else {
+        hv = blockIdx.x * rows_per_block + threadIdx.x / tpr;
+        frag = threadIdx.x % tpr;
+        if ((int)threadIdx.x >= rows_per_block * tpr) return;
+    }
+    if (hv >= a.n_heavy || frag >= tpr) return;
+    const HeavyVertex h = a.heavy[hv];
+    const int f = frag * VEC;
     const float* p = a.partials + (int64_t)h.slot0 * a.F + f;
-    float r = __builtin_nontemporal_load(p);
-    for (int s = 1; s < h.nslots; ++s) r = combine<AGG>(r, __builtin_nontemporal_load(p + (int64_t)s * a.F));
-    if (a.accumulate) r = combine<AGG>(a.out[(int64_t)h.v * a.ld_out + f], r);
-    if (a.bias || a.act != SAGA_ACT_NONE) r = finish_vertex(r, a.bias ? a.bias[f] : 0.f, a.act);
-    if (a.out) a.out[(int64_t)h.v * a.ld_out + f] = r;
-    if (a.out16) a.out16[(int64_t)h.v * a.ld_out16 + f] = f32_to_bf16_rne(r);
+    auto load = [&](int slot, float (&v)[VEC]) {
+        if constexpr (VEC == 4) {
+            const f32x4_t x = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p + (int64_t)slot * a.F));
+            v[0] = x.x, v[1] = x.y, v[2] = x.z, v[3] = x.w;
+        } else {
+            v[0] = __builtin_nontemporal_load(p + (int64_t)slot * a.F);
+        }
+    };
+    float r[VEC];
+    load(0, r);
+    int s = 1;
+    for (; s + 4 <= h.nslots; s += 4) {
+        float x0[VEC], x1[VEC], x2[VEC], x3[VEC];
+        load(s, x0);
+        load(s + 1, x1);
+        load(s + 2, x2);
+        load(s + 3, x3);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) r[j] = combine<AGG>(combine<AGG>(combine<AGG>(combine<AGG>(r[j], x0[j]), x1[j]), x2[j]), x3[j]);
+    }
+    for (; s < h.nslots; ++s) {
+        float x[VEC];
+        load(s, x);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) r[j] = combine<AGG>(r[j], x[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        if (a.accumulate) r[j] = combine<AGG>(a.out[(int64_t)h.v * a.ld_out + f + j], r[j]);
+        if (a.bias || a.act != SAGA_ACT_NONE) r[j] = finish_vertex(r[j], a.bias ? a.bias[f + j] : 0.f, a.act);
+    }
+    if (a.out) {
+        float* o = a.out + (int64_t)h.v * a.ld_out + f;
+        if constexpr (VEC == 4)
+            store_stream4(o, r[0], r[1], r[2], r[3]);
+        else
+            o[0] = r[0];
+    }
+    if (a.out16) {
+        uint16_t* o = a.out16 + (int64_t)h.v * a.ld_out16 + f;
+        if constexpr (VEC == 4) {
+            uint2 pk;
+            pk.x = f32_to_bf16_rne(r[0]) | ((uint32_t)f32_to_bf16_rne(r[1]) << 16);
+            pk.y = f32_to_bf16_rne(r[2]) | ((uint32_t)f32_to_bf16_rne(r[3]) << 16);
+            *reinterpret_cast<uint2*>(o) = pk;
+        } else {
+            o[0] = f32_to_bf16_rne(r[0]);
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void k_fill_f32(float* p, int64_t count, float value)
@@ -764,11 +819,25 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s)
 {
     if (a.n_heavy <= 0) return hipSuccess;
-    const dim3 grid((unsigned)a.n_heavy, (unsigned)((a.F + 255) / 256)), block(256);
-    if (a.agg == SAGA_AGG_SUM)
-        hipLaunchKernelGGL(k_combine<SAGA_AGG_SUM>, grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL(k_combine<SAGA_AGG_MAX>, grid, block, 0, s, a);
+    bool vec = a.F % 4 == 0 && aligned16(a.partials);
+    if (a.out) vec = vec && a.ld_out % 4 == 0 && aligned16(a.out);
+    if (a.out16) vec = vec && a.ld_out16 % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out16) & 7u) == 0;
+    const int tpr = vec ? a.F / 4 : a.F;  // threads per row
+    const int rows_per_block = tpr >= 256 ? 1 : 256 / tpr;
+    const dim3 grid(rows_per_block == 1 ? (unsigned)a.n_heavy : (unsigned)((a.n_heavy + rows_per_block - 1) / rows_per_block),
+                    rows_per_block == 1 ? (unsigned)((tpr + 255) / 256) : 1u),
+        block(256);
+    if (a.agg == SAGA_AGG_SUM) {
+        if (vec)
+            hipLaunchKernelGGL((k_combine<SAGA_AGG_SUM, 4>), grid, block, 0, s, a, tpr, rows_per_block);
+        else
+            hipLaunchKernelGGL((k_combine<SAGA_AGG_SUM, 1>), grid, block, 0, s, a, tpr, rows_per_block);
+    } else {
+        if (vec)
+            hipLaunchKernelGGL((k_combine<SAGA_AGG_MAX, 4>), grid, block, 0, s, a, tpr, rows_per_block);
+        else
+            hipLaunchKernelGGL((k_combine<SAGA_AGG_MAX, 1>), grid, block, 0, s, a, tpr, rows_per_block);
+    }
     return hipGetLastError();
 }
 
