@@ -1,8 +1,9 @@
 /*
  * saga.h - C ABI of the MI355X (gfx950) SAGA-NN layer library.
  *
- * One call computes the forward pass of one GNN layer in the SAGA-NN model of
- * the NGra paper (arXiv 1810.08403, Section 2.1-2.2):
+ * One call computes the forward pass (saga_layer_forward) or the backward pass
+ * (saga_layer_backward) of one GNN layer in the SAGA-NN model of the NGra paper
+ * (arXiv 1810.08403, Section 2.1-2.2):
  *
  *   Scatter     every edge u -> v receives [src = X[u], dest = X[v], data = w_e]
  *   ApplyEdge   per-edge function of that tuple (closed set below)
@@ -14,7 +15,9 @@
  * fused-gather operator of Section 3.2); vertex-only matrix products inside a
  * gated ApplyEdge are hoisted to one product per vertex (Section 3.2); graphs
  * whose data live in host memory are streamed through a fixed device budget
- * as vertex intervals x edge chunks (Section 3.1).
+ * as vertex intervals x edge chunks (Section 3.1). The backward stages
+ * (backward-ApplyVertex, -Gather, -ApplyEdge, -Scatter, Section 2.2) run the
+ * same propagation kernel over the edges grouped by source.
  *
  * The paper does not let users supply Scatter/Gather functions or accumulators
  * (Section 2.2, last paragraphs); accordingly everything here is a closed enum.
