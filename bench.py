@@ -147,6 +147,12 @@ def main():
     if wl.W_self is not None:
         kw["W_self"] = wl.W_self.to(tdt).contiguous()
 
+    second = None
+    if k == 2 and "W2" in wl.extra:       # configuration 2 is a two-layer model: 500 -> 16 (ReLU) -> 3
+        W2 = wl.extra["W2"].to(tdt).contiguous()
+        Y2 = torch.empty(n, W2.shape[1], device=dev, dtype=tdt)
+        second = dict(edge_op=wl.edge_op, agg=args.agg, W=W2, act="none")
+
     def step():
         ctx.layer_forward(graph, X, Y, **kw)
 
@@ -235,6 +241,33 @@ def main():
         ctx.set_option("transform_first", 0)
         out["variants"] = {"transform_first": {"ms_per_step": round(ms_tf, 4), "value": round(nnz / (ms_tf * 1e-3) / 1e9, 4),
                                                "note": "same layer, ApplyVertex product before the propagation; not the headline"}}
+
+    if second is not None:
+        def both():
+            ctx.layer_forward(graph, X, Y, **kw)
+            ctx.layer_forward(graph, Y, Y2, **second)
+        for _ in range(2):
+            both()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            both()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
+        hg2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hg2):
+            both()
+        for _ in range(2):
+            hg2.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            hg2.replay()
+        torch.cuda.synchronize()
+        ms2g = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["two_layer_model"] = {"ms_per_forward": round(ms2, 4), "ms_per_forward_hip_graph": round(ms2g, 4),
+                                  "gteps": round(2 * nnz / (ms2 * 1e-3) / 1e9, 4),
+                                  "note": "both layers of the model (500 -> 16 ReLU -> 3); the headline above is layer 1"}
 
     if args.backward:
         bf16_ok = wl.dtype == "bf16" and args.agg == "sum" and wl.edge_op in ("copy", "mul_weight") and wl.W_self is None
