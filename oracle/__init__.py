@@ -12,7 +12,10 @@ sparse-dense product identity of Section 6.1 via scipy.sparse, the in-degree
 invariant, brute-force max over the raw edge list, gated special cases that
 reduce to the other edge functions, a dense broadcast formulation of the gate,
 hoisted == naive, dense forms of the CommNet and max-pooling layers (Figures 9,
-11), and hand-worked values under tests/golden/.
+11), and hand-worked values under tests/golden/. The backward functions
+(Section 2.2's backward stages) are pinned by dense matrix forms, finite
+differences of the forward functions and automatic differentiation of dense
+formulations of the layers.
 """
 from __future__ import annotations
 

@@ -21,7 +21,16 @@
  *   - gated layer: Example 2.1 and Figure 2 (gate = sigmoid of a linear map of
  *     source and destination data, message = gate (.) source data), widened
  *     with an optional bias and an optional message matrix;
- *   - hoisting of vertex-only products out of ApplyEdge: Section 3.2.
+ *   - hoisting of vertex-only products out of ApplyEdge: Section 3.2;
+ *   - the backward stages (backward-ApplyVertex, -Gather, -ApplyEdge, -Scatter,
+ *     Section 2.2) as the chain rule of the forward definitions: linear layers
+ *     (whole graph and sampled), the gated layer, the max accumulator with
+ *     COPY / MUL_WEIGHT / max-pooling messages (further down in this file).
+ *
+ * Every function is pinned by tests/test_oracle_pins.py against something
+ * other than itself (dense matrix forms, finite differences of the forward
+ * functions, automatic differentiation of dense formulations, hand-made
+ * cases); none is "parity unpinned".
  *
  * Conventions. An edge goes from source u to destination v. The graph is
  * destination-major CSC: in-edges of v are row_idx[col_ptr[v] .. col_ptr[v+1]).
