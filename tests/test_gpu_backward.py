@@ -502,3 +502,34 @@ def test_bf16_backward_rejects_mixed_dtypes(ctx):
         ctx.layer_backward(graph, A, torch.zeros(n, Fo, device="cuda", dtype=bf), W16, dW, edge_op="gated")
     assert e.value.status == 3
     graph.destroy()
+
+
+@pytest.mark.parametrize("F", [64, 260])
+def test_backward_with_team_mode_and_other_tunables(F):
+    """The optional work-list shapes (a workgroup per piece of a cut group, small pieces and bands) under the backward
+    edge functions: gated (one- and two-output forms) and max gradient."""
+    from helpers import new_context
+    wl = si.workload(4, scale=10, f_in=F, f_out=32)
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    dY = si.normal_features(n, 32, 3)
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy(), W_msg=wl.W_msg.numpy())
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), act="relu", **okw)
+    bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), act="relu", **okw)
+    fwd_m = oracle.layer(cp, ri, wl.X.numpy(), "copy", agg="max", W=wl.W.numpy(), act="relu")
+    bwd_m = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), "copy", act="relu")
+    with new_context(team=1, split=16, cut_degree=32, stripe_kb=16) as c:
+        graph = make_graph(c, g)
+        res = _gated_backward_gpu(c, graph, wl, fwd["A"], fwd["Y"], dY, "relu", None, True, True)
+        for name in ["dW", "dX", "dW_gate", "db_gate", "dW_msg"]:
+            assert_sum_close(res[name], bwd[name], bwd[name + "_abs"], TOL_F32, f"team mode, gated F={F}, {name}")
+        f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda()
+        dX, dW = torch.full((n, F), float("nan"), device="cuda"), torch.full((F, 32), float("nan"), device="cuda")
+        c.layer_backward(graph, f32(bwd_m["A"]), dY.cuda(), wl.W.cuda(), dW, X=wl.X.cuda(), Y=f32(fwd_m["Y"]), edge_op="copy", agg="max",
+                         act="relu", dX=dX)
+        torch.cuda.synchronize()
+        assert_sum_close(dX.cpu().numpy(), bwd_m["dX"], bwd_m["dX_abs"], TOL_F32, f"team mode, max F={F}, dX")
+        assert_sum_close(dW.cpu().numpy(), bwd_m["dW"], bwd_m["dW_abs"], TOL_F32, f"team mode, max F={F}, dW")
+        assert graph.info()["n_split_vertices"] > 0
+        graph.destroy()
