@@ -1,0 +1,129 @@
+"""Seeded random small cases through the C ABI against the oracle: odd widths, empty and heavy columns, every edge
+function, accumulator, activation and dtype the forward pass covers, and the linear backward pass."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import saga_inputs as si
+from helpers import TOL_BF16, TOL_F32, assert_bit_equal, assert_sum_close, new_context
+
+pytestmark = pytest.mark.gpu
+
+import os
+
+# more cases on demand: SAGA_RANDOM_CASES=1000 python -m pytest tests/test_gpu_random_cases.py
+N_CASES = int(os.environ.get("SAGA_RANDOM_CASES", "48"))
+N_BWD_CASES = max(16, N_CASES // 3)
+
+
+def _case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 2, 7, 33, 64, 200, 777, 1500]))
+    kind = rng.choice(["uniform", "star", "powerlaw", "empty"])
+    if kind == "empty" or n == 1:
+        edges = [] if rng.random() < 0.5 else [(0, 0)]
+    elif kind == "star":                       # one destination with (almost) every vertex as a source, plus a few others
+        hub = int(rng.integers(n))
+        edges = [(u, hub) for u in range(n) if rng.random() < 0.9] + [(int(rng.integers(n)), int(rng.integers(n))) for _ in range(n)]
+    elif kind == "powerlaw":
+        m = int(n * rng.integers(2, 40))
+        src = np.minimum((rng.pareto(1.2, m) * 2).astype(np.int64), n - 1)
+        dst = np.minimum((rng.pareto(1.0, m) * 3).astype(np.int64), n - 1)
+        edges = list(zip(src.tolist(), dst.tolist()))
+    else:
+        m = int(n * rng.integers(1, 12))
+        edges = list(zip(rng.integers(n, size=m).tolist(), rng.integers(n, size=m).tolist()))
+    g = si.csc_from_lists(n, sorted(set(edges)))
+    F = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 17, 32, 40, 64, 100, 128, 132, 200, 256, 260, 516]))
+    Fo = int(rng.choice([1, 3, 4, 8, 16, 33, 64, 130]))
+    op = str(rng.choice(["copy", "mul_weight", "gated", "pool"]))
+    agg = str(rng.choice(["sum", "max"]))
+    act = str(rng.choice(["none", "relu", "sigmoid"]))
+    dtype = "bf16" if (op in ("copy", "mul_weight") and rng.random() < 0.3) else "f32"
+    if op == "gated" and F > 132:
+        F = 64
+    if dtype == "bf16" and act == "sigmoid":
+        # rounding the Gather output to bf16 moves the pre-activation by 2^-9 of its magnitude, which a sigmoid turns into
+        # an absolute error of up to a quarter of that: fine against the element-wise error scale, but not against the
+        # normwise bar of assert_sum_close (largest |Y| is 1); keep bf16 to the activations the bf16 workloads use
+        act = "relu"
+    return rng, g, F, Fo, op, agg, act, dtype
+
+
+@pytest.mark.parametrize("seed", range(N_CASES))
+def test_random_forward_case(seed):
+    rng, g, F, Fo, op, agg, act, dtype = _case(seed)
+    n = g.n
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    X, W, bias = t(n, F), t(F, Fo, s=0.3), t(Fo, s=0.2)
+    w = t(g.nnz) if op == "mul_weight" else None
+    kw, okw = {}, {}
+    Fm = F
+    if op == "gated":
+        Wg, bg, Wm = t(F, 2 * F, s=0.3), t(F, s=0.2), (t(F, F, s=0.3) if rng.random() < 0.6 else None)
+        kw = dict(W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=None if Wm is None else Wm.cuda())
+        okw = dict(W_gate=Wg.numpy(), b_gate=bg.numpy(), W_msg=None if Wm is None else Wm.numpy())
+    if op == "pool":
+        Fm = int(rng.choice([2, 8, 20, 64]))
+        Wp, bp = t(Fm, F, s=0.3), t(Fm, s=0.2)
+        W = t(Fm, Fo, s=0.3)
+        kw = dict(W_pool=Wp.cuda(), b_pool=bp.cuda())
+        okw = dict(W_pool=Wp.numpy(), b_pool=bp.numpy())
+    if dtype == "bf16":
+        X, W = si.round_to_bf16(X), si.round_to_bf16(W)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    ref = oracle.layer(g.col_ptr.numpy(), g.row_idx.numpy(), X.numpy(), op, None if w is None else w.numpy(), agg=agg, W=W.numpy(),
+                       bias=bias.numpy(), act=act, **okw)
+    opts = {}
+    if rng.random() < 0.5:
+        opts = dict(split=int(rng.choice([16, 32, 64])), cut_degree=int(rng.choice([16, 64, 256])), stripe_kb=int(rng.choice([0, 4, 64])),
+                    team=int(rng.integers(2)))
+    with new_context(**opts) as c:
+        graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        Y = torch.full((n, Fo), float("nan"), device="cuda", dtype=tdt)
+        A = torch.full((n, Fm), float("nan"), device="cuda")
+        c.layer_forward(graph, X.cuda().to(tdt), Y, edge_op=op, edge_weight=None if w is None else w.cuda(), agg=agg, W=W.cuda().to(tdt),
+                        bias=bias.cuda(), act=act, accum_out=A, **kw)
+        torch.cuda.synchronize()
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} {dtype} {opts}"
+        if agg == "max" and op in ("copy", "mul_weight"):
+            assert_bit_equal(A.cpu().numpy(), ref["A"], what + " max Gather")
+        else:
+            assert_sum_close(A.cpu().numpy(), ref["A"], ref["A_abs"], TOL_F32, what + " Gather")
+        if n > 0:
+            assert_sum_close(Y.float().cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_BF16 if dtype == "bf16" else TOL_F32, what + " layer")
+        graph.destroy()
+
+
+@pytest.mark.parametrize("seed", range(N_BWD_CASES))
+def test_random_linear_backward_case(seed):
+    rng, g, F, Fo, op, agg, act, dtype = _case(500 + seed)
+    n = g.n
+    op = "mul_weight" if seed % 2 else "copy"
+    act = "relu" if seed % 3 else "none"
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    X, W, Ws, bias, dY = t(n, F), t(F, Fo, s=0.3), (t(F, Fo, s=0.3) if seed % 4 == 0 else None), t(Fo, s=0.2), t(n, Fo)
+    w = t(g.nnz) if op == "mul_weight" else None
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    wn = None if w is None else w.numpy()
+    Wsn = None if Ws is None else Ws.numpy()
+    fwd = oracle.layer(cp, ri, X.numpy(), op, wn, W=W.numpy(), W_self=Wsn, bias=bias.numpy(), act=act)
+    bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
+    with new_context() as c:
+        graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda()
+        nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+        dX, dW, db, dWs = nan(n, F), nan(F, Fo), nan(Fo), (nan(F, Fo) if Ws is not None else None)
+        c.layer_backward(graph, f32(fwd["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(fwd["Y"]), edge_op=op,
+                         edge_weight=None if w is None else w.cuda(), bias=bias.cuda(), W_self=None if Ws is None else Ws.cuda(), act=act,
+                         dX=dX, dbias=db, dW_self=dWs)
+        torch.cuda.synchronize()
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} self={Ws is not None}"
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+        assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+        if Ws is not None:
+            dz = dY.numpy().astype(np.float64) * ((fwd["Y"] > 0) if act == "relu" else 1.0)
+            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(np.abs(X.numpy().astype(np.float64)).T @ np.abs(dz), 1e-30),
+                             TOL_F32, what + " dW_self")
+        graph.destroy()
