@@ -310,8 +310,9 @@ __device__ __forceinline__ float edge_step(float acc, float w, float x, float m,
 {
     if constexpr (EF == kEfGate) return accumulate<AGG>(acc, sigmoid_f32(x + c1), m);
     if constexpr (EF == kEfGateGrad) {
-        const float g = sigmoid_f32(x + c1);
-        return fmaf(g * (1.0f - g), c2 * m, acc);
+        float g, slope;
+        sigmoid_and_slope_f32(x + c1, g, slope);
+        return fmaf(slope, c2 * m, acc);
     }
     if constexpr (EF == kEfMaxGrad) {
         const float msg = w * c1;
@@ -321,8 +322,9 @@ __device__ __forceinline__ float edge_step(float acc, float w, float x, float m,
 }
 __device__ __forceinline__ void edge_step_both(float& acc, float& acc2, float x, float m, float c1, float c2)
 {
-    const float g = sigmoid_f32(x + c1);
-    acc = fmaf(g * (1.0f - g), c2 * m, acc);
+    float g, slope;
+    sigmoid_and_slope_f32(x + c1, g, slope);
+    acc = fmaf(slope, c2 * m, acc);
     acc2 = fmaf(g, m, acc2);
 }
 
