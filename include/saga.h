@@ -109,7 +109,7 @@ typedef struct saga_vertex_params {
     int32_t reserved;
     const saga_tensor* W_self; /* F_in x F_out, dtype of X, nullable: Y = act(A W + X W_self + bias), the
                                   ApplyVertex of CommNet, ReLU(W_H (x) vertex + W_C (x) accum) (Figure 9),
-                                  with W_self = W_H and W = W_C; device-resident calls only */
+                                  with W_self = W_H and W = W_C */
 } saga_vertex_params;
 
 /* Accumulated since saga_reset_timings(); stage times come from events on the context's stream. */
@@ -170,7 +170,13 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
  *
  * Placement selects the path: all tensors SAGA_MEM_DEVICE with a device graph
  * -> resident; X and Y SAGA_MEM_HOST (pinned recommended) with a host graph ->
- * streamed through the context's budget, parameters still on the device.
+ * streamed through the context's budget, parameters still on the device. Streamed calls
+ * cover all four layer programs in fp32: GATED and POOL first stream X through their
+ * per-vertex products (Section 3.2) into pinned host memory held by the context, tile by
+ * tile, and then run the chunk schedule on those rows (for GATED the rows [Ps | M] travel
+ * and the destination parts Pd of the resident interval are copied in beside its
+ * accumulator); with W_self the interval's own rows of X are copied in tile by tile for
+ * the second operand of the ApplyVertex product.
  *
  * Arithmetic: fp32 accumulation everywhere. BF16: X, W bf16; A is rounded to
  * bf16 (nearest even) once before the ApplyVertex product; Y is rounded to

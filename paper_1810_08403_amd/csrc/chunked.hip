@@ -45,6 +45,7 @@ struct ChunkGrid {
     hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
     hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
     hipEvent_t ev_a_done = nullptr, ev_a_ready = nullptr, ev_a_in = nullptr;
+    hipEvent_t ev_d_free = nullptr, ev_s_ready[2] = {nullptr, nullptr};  // destination parts / own-row tiles (gated, W_self)
     float* a_host = nullptr;  // pinned home of the accumulators for the swapping baselines
     size_t a_host_bytes = 0;
 };
@@ -56,7 +57,8 @@ void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
         if (c.host) (void)hipHostFree(c.host);
     (void)ctx;
     for (hipEvent_t e : {g->ev_ready[0], g->ev_ready[1], g->ev_free[0], g->ev_free[1], g->ev_y_ready[0], g->ev_y_ready[1],
-                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done, g->ev_a_ready, g->ev_a_in})
+                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done, g->ev_a_ready, g->ev_a_in, g->ev_d_free, g->ev_s_ready[0],
+                         g->ev_s_ready[1]})
         if (e) (void)hipEventDestroy(e);
     if (g->a_host) (void)hipHostFree(g->a_host);
     if (g->s_in) (void)hipStreamDestroy(g->s_in);
@@ -198,7 +200,7 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
     HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_out, hipStreamNonBlocking));
     for (hipEvent_t* e : {&grid->ev_ready[0], &grid->ev_ready[1], &grid->ev_free[0], &grid->ev_free[1], &grid->ev_y_ready[0],
                           &grid->ev_y_ready[1], &grid->ev_y_free[0], &grid->ev_y_free[1], &grid->ev_a_done, &grid->ev_a_ready,
-                          &grid->ev_a_in})
+                          &grid->ev_a_in, &grid->ev_d_free, &grid->ev_s_ready[0], &grid->ev_s_ready[1]})
         HIP_TRY(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
     return SAGA_OK;
 }
@@ -241,8 +243,8 @@ struct Plan {
 };
 
 // Device bytes a Q x P plan needs (upper bound on the chunk payload from the edge counts).
-size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t F_out, bool has_w, bool weighted, int64_t min_edges,
-                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs)
+size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t Fa, int64_t F_out, bool has_w, bool weighted, int64_t min_edges,
+                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs, bool dst_rows, int64_t F_self)
 {
     const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
     size_t max_chunk = 0, max_slots = 0;
@@ -252,26 +254,32 @@ size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t F_out, b
         max_chunk = std::max(max_chunk, b);
         max_slots = std::max(max_slots, (size_t)(nnz[c] / std::max<int64_t>(min_edges, 1)) + 1);
     }
-    size_t total = (size_t)Dq * F * 4;                 // A_j
+    size_t total = (size_t)Dq * Fa * 4;                // A_j
+    if (dst_rows) total += (size_t)Dq * Fa * 4;        // destination parts of the interval (gated)
     total += 2 * (size_t)Sp * F * 4;                   // V_i, double buffered
     total += 2 * max_chunk;                            // C_ij, double buffered
-    total += max_slots * (size_t)F * 4;                // partial rows of cut columns
-    if (has_w) total += 2 * (size_t)y_tile_rows * F_out * 4 + (size_t)(F_out + 128) * (F + 64) * 4;  // Y tiles + packed W
+    total += max_slots * (size_t)Fa * 4;               // partial rows of cut columns
+    if (has_w) total += 2 * (size_t)y_tile_rows * (F_out + F_self) * 4 + (size_t)(F_out + 128) * (Fa + F_self + 128) * 4;  // Y tiles (+ own rows) + packed W
     return total + (1 << 20);
 }
 
 }  // namespace
 
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
-                             const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed)
+                             const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed, const StreamExtras* extras)
 {
     const auto t_begin = std::chrono::steady_clock::now();
     const int64_t n = g->n;
-    const int64_t F = X->cols;
+    const int64_t F = X->cols;                                            // width of the rows that travel over the edges
+    const int64_t Fa = extras && extras->acc_width ? extras->acc_width : F;  // width of the accumulator rows
+    const bool gated = ep->op == SAGA_EDGE_GATED;
     const bool has_w = vp && vp->W;
-    const int64_t F_out = has_w ? vp->W->cols : F;
+    const bool has_self = has_w && extras && extras->self_rows;
+    const int64_t F_self = has_self ? extras->F_self : 0;
+    const int64_t F_out = has_w ? vp->W->cols : Fa;
     const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
     if (n == 0) return SAGA_OK;
+    if (gated && (!extras || !extras->dst_rows || F != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "streamed gated call without its hoisted rows");
 
     WorkListParams wlp = work_list_params(ctx, F * 4);
     wlp.skip_empty = true;
@@ -302,7 +310,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 if ((P > 0 && p != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
                 count_grid(g, q, p, &nnz, &pairs);
-                const size_t need = plan_bytes(g, q, p, F, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs) +
+                const size_t need = plan_bytes(g, q, p, F, Fa, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs, gated,
+                                               F_self) +
                                     (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
                 if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need <= ctx->budget)) {
@@ -326,18 +335,20 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // ---- device buffers, all counted against the budget ----
     saga_status st;
     {
-        DevBuf* bufs[8] = {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
-                           &ctx->st_partials};
+        constexpr int NB = 11;
+        DevBuf* bufs[NB] = {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
+                            &ctx->st_partials, &ctx->st_D, &ctx->st_S[0], &ctx->st_S[1]};
         const size_t c_bytes = std::max<size_t>(grid->max_chunk_bytes, 256);
         const size_t y_bytes = has_w ? (size_t)y_tile_rows * F_out * 4 : 0;
-        const size_t want[8] = {(size_t)Dq * F * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
-                                grid->max_slots > 0 ? (size_t)grid->max_slots * F * 4 : 0};
+        const size_t s_bytes = has_self ? (size_t)y_tile_rows * F_self * 4 : 0;
+        const size_t want[NB] = {(size_t)Dq * Fa * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
+                                 grid->max_slots > 0 ? (size_t)grid->max_slots * Fa * 4 : 0, gated ? (size_t)Dq * Fa * 4 : 0, s_bytes, s_bytes};
         bool fits = true;
-        for (int b = 0; b < 8; ++b) fits = fits && bufs[b]->bytes >= want[b];
+        for (int b = 0; b < NB; ++b) fits = fits && bufs[b]->bytes >= want[b];
         if (!fits) {
             // another plan left its buffers: start from nothing, so that this plan's own sizes are what counts against the budget
             for (DevBuf* b : bufs) ctx->dev_free(b);
-            for (int b = 0; b < 8; ++b)
+            for (int b = 0; b < NB; ++b)
                 if (want[b] > 0 && (st = ctx->dev_alloc(bufs[b], want[b]))) return st;
         }
     }
@@ -348,7 +359,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // "overlap" 0 puts every copy on the compute stream: nothing overlaps (the streaming-off baseline)
     hipStream_t sc = ctx->stream;
     hipStream_t sin = ctx->opt_overlap ? grid->s_in : sc, sout = ctx->opt_overlap ? grid->s_out : sc;
-    const int schedule = feed ? 0 : (has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0);
+    const int schedule = (feed || extras) ? 0 : (has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0);
     std::vector<char> seen(feed ? (size_t)P : 0, 0);  // source intervals the feed has been called for
     const float* Xh = static_cast<const float*>(X->data);
     float* Yh = static_cast<float*>(Y->data);
@@ -358,6 +369,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     bool used[2] = {false, false}, yused[2] = {false, false};
     bool a_busy = false;  // ev_a_done guards the accumulator buffer
 
+    bool d_busy = false;  // ev_d_free guards the destination parts
     if (schedule != 0 && grid->a_host_bytes < (size_t)n * F * 4) {  // host home of the swapped accumulators
         if (grid->a_host) (void)hipHostFree(grid->a_host);
         grid->a_host = nullptr;
@@ -367,13 +379,18 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     }
 
     // pack W^T once (on the compute stream)
-    int64_t n_pad = 0, k_pad = 0;
+    int64_t n_pad = 0, k_pad = 0, ldbt = 0;
     if (has_w) {
-        bt_padded_shape((int32_t)F_out, (int32_t)F, SAGA_F32, &n_pad, &k_pad);
-        if ((st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * k_pad) * 4))) return st;
-        HIP_TRY(ctx, launch_zero_bytes(ctx->ws_bt.p, (size_t)(n_pad * k_pad) * 4, sc));
-        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)F, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, k_pad, 0,
-                                              sc));
+        int64_t n_pad2 = 0, k_pad2 = 0;
+        bt_padded_shape((int32_t)F_out, (int32_t)Fa, SAGA_F32, &n_pad, &k_pad);
+        if (has_self) bt_padded_shape((int32_t)F_out, (int32_t)F_self, SAGA_F32, &n_pad2, &k_pad2);
+        ldbt = k_pad + k_pad2;
+        if ((st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * ldbt) * 4))) return st;
+        HIP_TRY(ctx, launch_zero_bytes(ctx->ws_bt.p, (size_t)(n_pad * ldbt) * 4, sc));
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)Fa, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, ldbt, 0, sc));
+        if (has_self)
+            HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, (int32_t)F_self, (int32_t)F_out, SAGA_F32,
+                                                  ctx->ws_bt.p, ldbt, k_pad, sc));
     }
 
     auto rows_of = [&](int j) { return std::min(n, ((int64_t)j + 1) * Dq) - (int64_t)j * Dq; };
@@ -381,7 +398,15 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // A_j <- identity of the accumulator, once nobody reads the buffer any more
     auto fill_a = [&](int j) -> saga_status {
         if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
-        HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * F, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
+        HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * Fa, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
+        if (gated) {  // the destination parts of this interval, once the previous interval's kernels have let go of the buffer
+            if (d_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_d_free, 0));
+            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_D.p, (size_t)Fa * 4, extras->dst_rows + (int64_t)j * Dq * extras->ld_dst,
+                                          (size_t)extras->ld_dst * 4, (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+            HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
+            HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
+            bytes_h2d += rows_of(j) * Fa * 4;
+        }
         return SAGA_OK;
     };
     // stream V_i (unless it already sits in V[vbuf]) and C_ij in, then add the chunk into A_j
@@ -423,12 +448,18 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         ga.edge_w = weighted ? reinterpret_cast<const float*>(cb + m.off_w) : nullptr;
         ga.src = ctx->st_V[vb].p;
         ga.ld_src = F;
-        ga.F = (int32_t)F;
+        ga.F = (int32_t)Fa;
         ga.dtype = SAGA_F32;
         ga.op = ep->op;
         ga.agg = agg;
         ga.out = A;
-        ga.ld_out = F;
+        ga.ld_out = Fa;
+        if (gated) {  // rows [Ps | M] travel, the destination parts are resident
+            ga.src2 = static_cast<const float*>(ctx->st_V[vb].p) + Fa;
+            ga.ld_src2 = F;
+            ga.dst = static_cast<const float*>(ctx->st_D.p);
+            ga.ld_dst = Fa;
+        }
         ga.partials = static_cast<float*>(ctx->st_partials.p);
         ga.accumulate = 1;
         ga.xcd_remap = ctx->opt_xcd_remap;
@@ -438,10 +469,10 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ca.heavy = reinterpret_cast<const HeavyVertex*>(cb + m.off_heavy);
             ca.n_heavy = m.n_heavy;
             ca.partials = ga.partials;
-            ca.F = (int32_t)F;
+            ca.F = (int32_t)Fa;
             ca.agg = agg;
             ca.out = A;
-            ca.ld_out = F;
+            ca.ld_out = Fa;
             ca.accumulate = 1;
             HIP_TRY(ctx, launch_combine(ca, sc));
         }
@@ -453,13 +484,17 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // ApplyVertex on the resident A_j (or A_j itself when there is none) and its way back to the host
     auto apply_and_drain = [&](int j) -> saga_status {
         const int64_t v0 = (int64_t)j * Dq, rows = rows_of(j);
-        if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * F, sc));
+        if (gated) {  // every kernel that reads the destination parts of this interval has been enqueued
+            HIP_TRY(ctx, hipEventRecord(grid->ev_d_free, sc));
+            d_busy = true;
+        }
+        if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * Fa, sc));
         if (!has_w) {
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
             HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)F * 4, (size_t)F * 4, (size_t)rows,
+            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)Fa * 4, (size_t)Fa * 4, (size_t)rows,
                                           hipMemcpyDeviceToHost, sout));
-            bytes_d2h += rows * F * 4;
+            bytes_d2h += rows * Fa * 4;
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
             a_busy = true;
             return SAGA_OK;
@@ -469,16 +504,29 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             const int b = (int)(ystep & 1);
             if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_y_free[b], 0));
             GemmArgs ge{};
-            ge.A = A + r0 * F;
-            ge.lda = F;
+            if (has_self) {
+                // the tile's own rows of the layer input, for the second operand; the staging buffer is free once the
+                // product that last read it has been followed by its copy-out (ev_y_free)
+                if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_y_free[b], 0));
+                HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_S[b].p, (size_t)F_self * 4, extras->self_rows + (v0 + r0) * extras->ld_self,
+                                              (size_t)extras->ld_self * 4, (size_t)F_self * 4, (size_t)tr, hipMemcpyHostToDevice, sin));
+                HIP_TRY(ctx, hipEventRecord(grid->ev_s_ready[b], sin));
+                HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_s_ready[b], 0));
+                bytes_h2d += tr * F_self * 4;
+                ge.A2 = ctx->st_S[b].p;
+                ge.lda2 = F_self;
+                ge.K2 = (int32_t)F_self;
+            }
+            ge.A = A + r0 * Fa;
+            ge.lda = Fa;
             ge.Bt = ctx->ws_bt.p;
-            ge.ldbt = k_pad;
+            ge.ldbt = ldbt;
             ge.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
             ge.C = ctx->st_Y[b].p;
             ge.ldc = F_out;
             ge.M = tr;
             ge.N = (int32_t)F_out;
-            ge.K = (int32_t)F;
+            ge.K = (int32_t)Fa;
             ge.dtype = ge.out_dtype = SAGA_F32;
             ge.act = vp->act;
             HIP_TRY(ctx, launch_gemm(ge, sc));

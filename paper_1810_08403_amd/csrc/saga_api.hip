@@ -372,6 +372,81 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
     return SAGA_OK;
 }
 
+// A streamed layer of any of the four programs. Linear layers go straight to the chunk schedule. Layers whose ApplyEdge has
+// a per-vertex part (Section 3.2) first stream X through that product, tile by tile, into pinned host memory held by
+// the context (the paper's dataflow does the same when the hoisted products of a big graph do not fit the device:
+// they become vertex data of their own), then run the schedule on those rows.
+static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
+                                  const saga_vertex_params* vp, saga_tensor* Y)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)X->cols;
+    const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
+    StreamExtras ex;
+    bool use_ex = false;
+    if (vp && vp->W_self) {
+        ex.self_rows = static_cast<const float*>(X->data);
+        ex.ld_self = X->ld;
+        ex.F_self = F;
+        use_ex = true;
+    }
+    if (!gated && !pool) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
+
+    const int32_t Fh = gated ? 3 * F : (int32_t)ep->W_pool->rows;  // width of the per-vertex rows
+    const size_t need = sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fh;
+    if (ctx->h_hoist_bytes < need) {
+        if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
+        ctx->h_hoist = nullptr;
+        ctx->h_hoist_bytes = 0;
+        HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_hoist), need, hipHostMallocDefault));
+        ctx->h_hoist_bytes = need;
+    }
+    // tiles of about 64 MiB of per-vertex rows
+    const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)Fh))));
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F)) return st;
+    hipStream_t s = ctx->stream;
+    int64_t h2d = 0, d2h = 0;
+    for (int64_t r0 = 0; r0 < n; r0 += T) {
+        const int64_t rows = std::min(T, n - r0);
+        HIP_TRY(ctx, hipMemcpy2DAsync(ctx->ws_accum.p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + r0 * X->ld,
+                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, s));
+        saga_tensor xt{};
+        xt.data = ctx->ws_accum.p;
+        xt.rows = rows;
+        xt.cols = F;
+        xt.ld = F;
+        xt.dtype = SAGA_F32;
+        xt.mem = SAGA_MEM_DEVICE;
+        if (saga_status st = gated ? hoist_gated(ctx, &xt, ep, rows, F) : hoist_pool(ctx, &xt, ep, rows, F, Fh)) return st;
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->h_hoist + r0 * Fh, ctx->ws_hoist.p, sizeof(float) * (size_t)rows * Fh, hipMemcpyDeviceToHost, s));
+        h2d += rows * (int64_t)F * 4;
+        d2h += rows * (int64_t)Fh * 4;
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    ctx->acc.bytes_h2d += h2d;
+    ctx->acc.bytes_d2h += d2h;
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist}) ctx->dev_free(b);  // make room under the budget
+
+    saga_tensor hx{};
+    hx.data = ctx->h_hoist;
+    hx.rows = n;
+    hx.dtype = SAGA_F32;
+    hx.mem = SAGA_MEM_HOST;
+    hx.ld = Fh;
+    saga_edge_params e2 = *ep;
+    if (pool) {  // the pooled rows are plain vertex data now
+        hx.cols = Fh;
+        e2.op = SAGA_EDGE_COPY;
+    } else {     // rows [Ps | M] travel; the destination parts Pd sit behind them in every row
+        hx.cols = 2 * F;
+        ex.acc_width = F;
+        ex.dst_rows = ctx->h_hoist + 2 * F;
+        ex.ld_dst = Fh;
+        use_ex = true;
+    }
+    return streamed_forward(ctx, g, &hx, &e2, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
+}
+
 extern "C" {
 
 const char* saga_version(void) { return kVersion; }
@@ -498,8 +573,10 @@ saga_status saga_destroy(saga_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
                       &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
-                      &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials})
+                      &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials, &ctx->st_D, &ctx->st_S[0],
+                      &ctx->st_S[1]})
         ctx->dev_free(b);
+    if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
@@ -980,12 +1057,9 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need X, Y and the graph in host memory");
         if (accum_out) return ctx->fail(SAGA_ERR_UNSUPPORTED, "accum_out is not available on the streamed path");
         if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
-        if (ep->op == SAGA_EDGE_GATED || ep->op == SAGA_EDGE_POOL)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "gated and max-pooling ApplyEdge are not streamed");
-        if (vp && vp->W_self) return ctx->fail(SAGA_ERR_UNSUPPORTED, "W_self is not streamed");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
-        return streamed_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
+        return streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
     }
     if (Y->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "resident calls need X, Y and the graph in device memory");

@@ -103,6 +103,9 @@ struct saga_ctx {
     DevBuf ws_dz16;      // bf16 layers: the gradient of the pre-activation in bf16
     // streamed calls: accumulator interval, two vertex intervals, two chunk payloads, two output tiles, partial rows
     DevBuf st_A, st_V[2], st_C[2], st_Y[2], st_partials;
+    DevBuf st_D, st_S[2];  // gated: destination parts of the resident interval; W_self: tiles of the interval's own rows
+    float* h_hoist = nullptr;  // streamed gated / pooled layers: the per-vertex products of all vertices in pinned host memory
+    size_t h_hoist_bytes = 0;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
 
     // profiling
@@ -329,8 +332,21 @@ struct VertexFeed {
     std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, bool first_visit, int64_t* h2d)> fill;
     size_t bytes_per_row = 0;
 };
+// What the streamed schedule needs beyond a linear layer. Gated layers: X is the host array of hoisted rows [Ps | M]
+// (2F wide), the accumulator rows are acc_width = F wide, and the destination parts Pd of every destination interval
+// are made resident from dst_rows while the interval is worked on. W_self layers: the interval's own rows of the
+// layer input are copied in tile by tile for the second operand of the ApplyVertex product.
+struct StreamExtras {
+    int32_t acc_width = 0;             // 0: as wide as X's rows
+    const float* dst_rows = nullptr;   // host, n rows, ld_dst elements apart (gated)
+    int64_t ld_dst = 0;
+    const float* self_rows = nullptr;  // host, n rows of F_self, ld_self elements apart (W_self)
+    int64_t ld_self = 0;
+    int32_t F_self = 0;
+};
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
-                             int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr);
+                             int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,
+                             const StreamExtras* extras = nullptr);
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device

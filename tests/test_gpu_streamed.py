@@ -217,3 +217,58 @@ def test_streamed_backward_matches_oracle(wl, act, edge_op, Q, P, tile):
     ctx.layer_forward(graph, wl.X.clone().pin_memory(), Yf, **kw)
     assert_sum_close(Yf.numpy(), fwd["Y"], fwd["Y_abs"], TOL_F32, "forward after backward")
     ctx.destroy()
+
+
+@pytest.mark.parametrize("Q,P", [(1, 3), (2, 2), (3, 5)])
+@pytest.mark.parametrize("agg", ["sum", "max"])
+def test_streamed_gated_layer(Q, P, agg):
+    """Configuration 4's layer from host memory: hoisted rows through pinned host memory, [Ps | M] streamed, Pd resident."""
+    import paper_1810_08403_amd as saga
+    w = si.workload(4, scale=12, f_in=40, f_out=24)
+    g = w.graph
+    n = g.n
+    ctx = saga.Context(0)
+    ctx.set_option("dst_intervals", Q)
+    ctx.set_option("src_intervals", P)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    bias = si.uniform_pm(24, 0.3, 4)
+    ref = run_oracle(w, agg=agg, bias=bias, hoisted=True)
+    Y = torch.full((n, 24), float("nan")).pin_memory()
+    ctx.layer_forward(graph, w.X.clone().pin_memory(), Y, edge_op="gated", agg=agg, W_gate=w.W_gate.cuda(), b_gate=w.b_gate.cuda(),
+                      W_msg=w.W_msg.cuda(), W=w.W.cuda(), bias=bias.cuda(), act=w.act)
+    assert_sum_close(Y.numpy(), ref["Y"], ref["Y_abs"], TOL_F32, f"streamed gated {agg} {Q}x{P}")
+    # the same call on a device-resident copy gives the same layer
+    with_dev = saga.Context(0)
+    gd = with_dev.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+    Yd = torch.empty(n, 24, device="cuda")
+    with_dev.layer_forward(gd, w.X.cuda(), Yd, edge_op="gated", agg=agg, W_gate=w.W_gate.cuda(), b_gate=w.b_gate.cuda(),
+                           W_msg=w.W_msg.cuda(), W=w.W.cuda(), bias=bias.cuda(), act=w.act)
+    assert_sum_close(Yd.cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_F32, "resident gated")
+    with_dev.destroy()
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("agg", ["max", "sum"])
+def test_streamed_max_pooling_and_commnet_layers(agg):
+    import paper_1810_08403_amd as saga
+    ctx = saga.Context(0)
+    ctx.set_option("dst_intervals", 2)
+    ctx.set_option("src_intervals", 3)
+    # Figure 11: pooled messages, hoisted through host memory, then max (or sum) over them
+    w = si.mpgcn_workload(scale=12, f_in=24, f_pool=40, f_out=16)
+    g = w.graph
+    graph = ctx.graph_create_csc(g.n, g.col_ptr, g.row_idx)
+    ref = run_oracle(w, agg=agg, hoisted=True)
+    Y = torch.full((g.n, 16), float("nan")).pin_memory()
+    ctx.layer_forward(graph, w.X.clone().pin_memory(), Y, edge_op="pool", agg=agg, W_pool=w.W_pool.cuda(), b_pool=w.b_pool.cuda(),
+                      W=w.W.cuda(), act=w.act)
+    assert_sum_close(Y.numpy(), ref["Y"], ref["Y_abs"], TOL_F32, f"streamed pooled layer, {agg}")
+    # Figure 9: the two-term ApplyVertex needs the interval's own rows
+    c = si.commnet_workload(scale=12, f_in=48, f_out=20)
+    gc = c.graph
+    graph2 = ctx.graph_create_csc(gc.n, gc.col_ptr, gc.row_idx)
+    refc = run_oracle(c, agg=agg)
+    Yc = torch.full((gc.n, 20), float("nan")).pin_memory()
+    ctx.layer_forward(graph2, c.X.clone().pin_memory(), Yc, edge_op="copy", agg=agg, W=c.W.cuda(), W_self=c.W_self.cuda(), act=c.act)
+    assert_sum_close(Yc.numpy(), refc["Y"], refc["Y_abs"], TOL_F32, f"streamed CommNet layer, {agg}")
+    ctx.destroy()
