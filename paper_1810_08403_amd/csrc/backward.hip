@@ -647,14 +647,18 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     hipStream_t s = ctx->stream;
     saga_status st;
     const int64_t t_auto = std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)std::max(F, Fo)));
-    const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), ctx->opt_bwd_tile_rows > 0 ? ctx->opt_bwd_tile_rows : t_auto));
-    {
-        // the buffers of an earlier streamed call may fill the budget: the next streamed call rebuilds them
-        const size_t tiles = sizeof(float) * (size_t)T * ((size_t)F + 3 * (size_t)Fo) + sizeof(float) * (size_t)colsum_slabs(T) * Fo;
-        if (ctx->budget > 0 && ctx->cur_bytes + tiles > ctx->budget)
-            for (DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
-                              &ctx->st_partials})
-                ctx->dev_free(b);
+    int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), ctx->opt_bwd_tile_rows > 0 ? ctx->opt_bwd_tile_rows : t_auto));
+    if (ctx->budget > 0) {
+        // the tiles, the split workspace of the parameter-gradient product (at most 1,024 partial F x F_out matrices, usually
+        // far fewer) and the column-sum slabs have to fit beside whatever else the context holds
+        const size_t per_row = sizeof(float) * ((size_t)F + 3 * (size_t)Fo);
+        int64_t rps;
+        int32_t nsp;
+        gemm_tn_plan(T, F, Fo, &rps, &nsp);
+        const size_t fixed = sizeof(float) * (size_t)nsp * F * Fo + sizeof(float) * (size_t)colsum_slabs(T) * Fo + (1 << 20);
+        ctx->make_room(fixed + per_row * (size_t)T);
+        const size_t left = ctx->budget > ctx->cur_bytes + fixed ? ctx->budget - ctx->cur_bytes - fixed : 0;
+        T = std::max<int64_t>(64, std::min<int64_t>(T, (int64_t)(left / per_row)));
     }
     if ((st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F))) return st;   // A tile
     if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)T * Fo))) return st;   // dY tile

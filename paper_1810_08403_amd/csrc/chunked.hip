@@ -302,6 +302,11 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     } else {
         bool found = false;
         std::vector<int64_t> nnz, pairs;
+        // what the context holds apart from the schedule's own buffers (packed weights, other graphs) counts too
+        size_t held = ctx->cur_bytes;
+        for (const DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
+                                &ctx->st_partials, &ctx->st_D, &ctx->st_S[0], &ctx->st_S[1]})
+            held -= std::min(held, b->bytes);
         const int qs[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 256, 512, 1024};
         const int ps[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
         for (int q : qs) {
@@ -314,7 +319,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                                                F_self) +
                                     (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
-                if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need <= ctx->budget)) {
+                if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need + held <= ctx->budget)) {
                     Q = q;
                     P = p;
                     found = true;

@@ -48,6 +48,12 @@ void saga_ctx::dev_free(DevBuf* b)
     b->bytes = 0;
 }
 
+void saga_ctx::make_room(size_t bytes)
+{
+    if (budget == 0 || cur_bytes + bytes <= budget) return;
+    for (DevBuf* b : {&st_A, &st_V[0], &st_V[1], &st_C[0], &st_C[1], &st_Y[0], &st_Y[1], &st_partials, &st_D, &st_S[0], &st_S[1]}) dev_free(b);
+}
+
 saga_status saga_ctx::drain_events()
 {
     if (ev_used == 0) return SAGA_OK;
@@ -401,8 +407,16 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
         HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_hoist), need, hipHostMallocDefault));
         ctx->h_hoist_bytes = need;
     }
-    // tiles of about 64 MiB of per-vertex rows
-    const int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)Fh))));
+    // tiles of about 64 MiB of per-vertex rows; smaller when that is what the budget leaves beside the schedule's
+    // buffers of an earlier call (giving those up and allocating them again costs more than smaller tiles do)
+    int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)Fh))));
+    const size_t fixed = sizeof(float) * (size_t)(Fh + 128) * (F + 64) + (1 << 20);  // packed weights, slack
+    const size_t per_row = sizeof(float) * ((size_t)F + Fh);
+    if (ctx->budget > 0 && ctx->cur_bytes + fixed + per_row * (size_t)T > ctx->budget) {
+        auto left = [&]() { return ctx->budget > ctx->cur_bytes + fixed ? ctx->budget - ctx->cur_bytes - fixed : (size_t)0; };
+        if (left() / per_row < 2048) ctx->make_room(fixed + per_row * (size_t)T);
+        T = std::max<int64_t>(64, std::min<int64_t>(T, (int64_t)(left() / per_row)));
+    }
     if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F)) return st;
     hipStream_t s = ctx->stream;
     int64_t h2d = 0, d2h = 0;

@@ -123,6 +123,9 @@ struct saga_ctx {
     saga_status dev_alloc(DevBuf* b, size_t bytes);  // frees and reallocates when too small
     void dev_free(DevBuf* b);
     saga_status drain_events();
+    // Before `bytes` more device bytes are taken outside the streamed schedule: if they would not fit the budget beside the
+    // schedule's buffers of an earlier call, those are given up (the next streamed call allocates what its plan needs).
+    void make_room(size_t bytes);
 };
 
 struct ChunkGrid;  // streamed representation (chunked.hip)

@@ -272,3 +272,35 @@ def test_streamed_max_pooling_and_commnet_layers(agg):
     ctx.layer_forward(graph2, c.X.clone().pin_memory(), Yc, edge_op="copy", agg=agg, W=c.W.cuda(), W_self=c.W_self.cuda(), act=c.act)
     assert_sum_close(Yc.numpy(), refc["Y"], refc["Y_abs"], TOL_F32, f"streamed CommNet layer, {agg}")
     ctx.destroy()
+
+
+def test_streamed_apps_respect_the_budget_over_repeated_calls():
+    """The per-vertex products of gated and pooled layers are formed outside the chunk schedule; together with the
+    schedule's buffers of the previous call they still have to stay under the budget."""
+    import paper_1810_08403_amd as saga
+    budget = 8 << 20
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    w = si.mpgcn_workload(scale=13, f_in=64, f_pool=96, f_out=32)
+    g = w.graph
+    graph = ctx.graph_create_csc(g.n, g.col_ptr, g.row_idx)
+    ref = run_oracle(w, agg="max", hoisted=True)
+    X = w.X.clone().pin_memory()
+    for rep in range(3):
+        Y = torch.full((g.n, 32), float("nan")).pin_memory()
+        ctx.layer_forward(graph, X, Y, edge_op="pool", agg="max", W_pool=w.W_pool.cuda(), b_pool=w.b_pool.cuda(), W=w.W.cuda(), act=w.act)
+        assert_sum_close(Y.numpy(), ref["Y"], ref["Y_abs"], TOL_F32, f"pooled layer under {budget >> 20} MiB, call {rep}")
+        assert ctx.peak_device_bytes() <= budget, (ctx.peak_device_bytes(), budget)
+    wg = si.workload(4, scale=13, f_in=64, f_out=32)
+    gg = wg.graph
+    graph2 = ctx.graph_create_csc(gg.n, gg.col_ptr, gg.row_idx)
+    refg = run_oracle(wg, agg="sum", hoisted=True)
+    Xg = wg.X.clone().pin_memory()
+    for rep in range(2):
+        Yg = torch.full((gg.n, 32), float("nan")).pin_memory()
+        ctx.layer_forward(graph2, Xg, Yg, edge_op="gated", W_gate=wg.W_gate.cuda(), b_gate=wg.b_gate.cuda(), W_msg=wg.W_msg.cuda(),
+                          W=wg.W.cuda(), act=wg.act)
+        assert_sum_close(Yg.numpy(), refg["Y"], refg["Y_abs"], TOL_F32, f"gated layer under {budget >> 20} MiB, call {rep}")
+        assert ctx.peak_device_bytes() <= budget, (ctx.peak_device_bytes(), budget)
+    t = ctx.get_timings()
+    assert t["plan_dst_intervals"] * t["plan_src_intervals"] > 1
+    ctx.destroy()
