@@ -1,10 +1,17 @@
-// Backward pass of one device-resident layer (the backward stages of Section 2.2 in
-// reverse order of the forward ones) for layers whose ApplyEdge is linear in the source
-// row. backward-Gather / backward-ApplyEdge / backward-Scatter fuse exactly like the
-// forward propagation (Section 3.3): vertex u's gradient is the weighted sum, over its
-// out-edges u -> v, of the rows of the gradient at v. That is the forward propagation
-// kernel run on the same edges grouped by source instead of by destination, so this file
-// only builds that second edge order and strings the kernels together.
+// Backward pass of one layer (the backward stages of Section 2.2 in reverse order of the
+// forward ones). backward-Gather / backward-ApplyEdge / backward-Scatter fuse exactly like
+// the forward propagation (Section 3.3): vertex u's gradient is a sum, over its out-edges
+// u -> v, of rows taken at v. That is the forward propagation kernel run on the same edges
+// grouped by source instead of by destination, so this file builds that second edge order
+// and strings the kernels together:
+//   - linear ApplyEdge (COPY, MUL_WEIGHT) under the sum accumulator, fp32 and bf16: one
+//     propagation at the narrower of the layer's two widths;
+//   - gated ApplyEdge: gates recomputed from the hoisted per-vertex products, one
+//     propagation by destination and one (two outputs) by source;
+//   - max accumulator and pooled messages: the gradient goes to the sources that supplied
+//     the maxima, found by recomputing the messages;
+//   - streamed layers (tensors in host memory): the chunk schedule of Section 3.1 on the
+//     chunks of edges clustered by source, with dZ formed on the way in.
 #include <cstring>
 
 #include "saga_internal.h"
