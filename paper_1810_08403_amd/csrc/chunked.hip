@@ -17,6 +17,14 @@
 // intervals whose accumulator fits the budget and keeps the streamed source
 // intervals small. Columns without edges in a chunk are left out of its work
 // list. The static edge data travel with the chunk.
+//
+// The same schedule serves the other layer programs and the backward pass through
+// two hooks: a vertex feed that produces a source interval's rows instead of copying
+// them (the streamed backward pass forms dZ there), and extras for layers that need
+// more than one kind of row (gated: rows [Ps | M] travel, the destination parts Pd
+// of the resident interval sit beside its accumulator; W_self: the interval's own
+// rows are copied in for ApplyVertex). The device buffers belong to the context, so
+// that the grid of a graph and the grid of its transposed twin share one budget.
 #include <algorithm>
 #include <atomic>
 #include <chrono>

@@ -1,5 +1,7 @@
-// C ABI of libsaga: contexts, graph ingest, and the device-resident layer
-// (Scatter-ApplyEdge-Gather fused, then ApplyVertex; Sections 2.2 and 3.2).
+// C ABI of libsaga: contexts, graph ingest, the host-side work list and id re-encoding,
+// the device-resident layer (Scatter-ApplyEdge-Gather fused, then ApplyVertex; Sections
+// 2.2 and 3.2), the per-vertex products hoisted out of gated and pooled ApplyEdge
+// functions, and argument checking for every entry point.
 #include <algorithm>
 #include <cstring>
 
