@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--stripe-kb", type=int, default=None)
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--team", type=int, default=None)
+    ap.add_argument("--mma", type=int, default=None, help="1: bf16 sums accumulate on the matrix unit (library option mma)")
     ap.add_argument("--transform-first", type=int, default=None,
                     help="1: run the ApplyVertex product before the propagation where the layer narrows the rows (see saga_set_option)")
     ap.add_argument("--budget-gib", type=float, default=16.0, help="config5 only: device-memory budget")
@@ -131,7 +132,7 @@ def main():
 
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
-                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("transform_first", args.transform_first)):
+                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first)):
         if val is not None:
             ctx.set_option(name, val)
     t0 = time.time()

@@ -109,6 +109,7 @@ static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs g
     ga.dtype = SAGA_F32;
     ga.agg = SAGA_AGG_SUM;
     ga.xcd_remap = ctx->opt_xcd_remap;
+    ga.mma = ctx->opt_mma;
     const bool two = ga.op == kGatherOpGateBoth;
     if (view->n_slots > 0) {
         if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * ga.F * (two ? 2 : 1))) return st;
@@ -567,6 +568,7 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
         ga.dtype = SAGA_BF16;
         ga.agg = SAGA_AGG_SUM;
         ga.xcd_remap = ctx->opt_xcd_remap;
+        ga.mma = ctx->opt_mma;
         if (view->n_slots > 0) {
             if (saga_status e = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * width)) return e;
             ga.partials = static_cast<float*>(ctx->ws_partials.p);

@@ -476,6 +476,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         ga.partials = static_cast<float*>(ctx->st_partials.p);
         ga.accumulate = 1;
         ga.xcd_remap = ctx->opt_xcd_remap;
+        ga.mma = ctx->opt_mma;
         HIP_TRY(ctx, launch_gather(ga, sc));
         if (m.n_heavy > 0) {
             CombineArgs ca{};

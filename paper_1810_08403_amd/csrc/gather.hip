@@ -486,6 +486,241 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// bf16 rows, sum over linear messages, with the multiply-accumulate on the matrix unit. The loads are
+// those of k_gather_wide / k_gather_narrow; what changes is who does the arithmetic. Unpacking a bf16
+// and one FMA per element costs two vector-ALU instructions per element (the narrow kernel on 512-byte
+// rows keeps the vector ALUs busy 100 % of the time); here a lane only interleaves the halves of its
+// registers (one byte-permute per two elements) and a 16x16x32 bf16 MFMA forms `acc += w_e * x` for
+// four edges and two features per lane at once:
+//
+//   B (32 x 16, the data): column n = lane % 16, rows k = 8 (lane / 16) + j. A lane supplies, from its
+//     own fragments, j = 0..3: feature 2p of its edges 4h..4h+3, j = 4..7: feature 2p + 1 of the same
+//     edges (p = 0..3 feature pair, h = 0..1 half of a group of eight loads: eight MFMAs per group).
+//   A (16 x 32, the weights): row i serves lane group kg = (i & 7) / 2 and feature 2p + (i & 1); it holds
+//     that group's four edge weights at k = 8 kg + 4 (i & 1) + 0..3 and zero elsewhere, so that a lane
+//     group only ever meets its own rows (and may work on other edges than its neighbours). Rows 0..7
+//     carry the weights rounded to bf16, rows 8..15 the bf16-rounded remainder: w = hi + lo to 2^-18
+//     relative, and the two partial sums are added at the end of the item.
+//   C (16 x 16 fp32): lane (n, g) register r is row 4 g + r: all 256 values are in use.
+//
+// At the end of the item the rows of C go back to the lanes that own the features through a
+// wavefront-private piece of LDS. Products of two bf16 values are exact in fp32 and the accumulation
+// is fp32, as before. A non-finite feature of one source row turns every feature that shares a C
+// column with it into NaN (0 x inf inside the dot product), not only its own.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kPermLowHalves = 0x05040100u;   // (s0.lo16 << 16) | s1.lo16
+constexpr uint32_t kPermHighHalves = 0x07060302u;  // (s0.hi16 << 16) | s1.hi16
+constexpr uint32_t kPermZero = 0x0c0c0c0cu;
+
+// What a lane contributes to the A operand: row i = lane % 16 belongs to lane group (i & 7) / 2, and only the
+// lanes of that group hold its k range. `sel_part` picks this row's part of a weight out of a dword.
+struct MmaLane {
+    uint32_t sel0, sel1;  // byte selectors of the dwords 0..1 and 2..3 of A (zero selectors for lanes that supply nothing)
+    bool low_rows;        // rows 8..15: the remainder part
+};
+__device__ __forceinline__ MmaLane mma_lane(const int lane, const uint32_t sel_hi, const uint32_t sel_lo)
+{
+    const int i = lane & 15, g = lane >> 4;
+    const bool mine = ((i & 7) >> 1) == g;
+    const uint32_t sel = i >= 8 ? sel_lo : sel_hi;
+    return MmaLane{(mine && !(i & 1)) ? sel : kPermZero, (mine && (i & 1)) ? sel : kPermZero, i >= 8};
+}
+
+// Eight fragments (one per load of the group) and the eight weights that go with them, as dwords from which the
+// lane's selectors take its part: acc[p] += sum over the loads of w * (features 2p, 2p + 1 of the fragment).
+__device__ __forceinline__ void mma_consume(const Frag<uint16_t, 8> (&x)[8], const uint32_t (&wv)[8], const MmaLane ml,
+                                            const bool second_half, f32x4_t (&acc)[4])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !second_half) break;  // the same for the whole wavefront
+        u32x4_t av;
+        av.x = __builtin_amdgcn_perm(wv[4 * h + 1], wv[4 * h], ml.sel0);
+        av.y = __builtin_amdgcn_perm(wv[4 * h + 3], wv[4 * h + 2], ml.sel0);
+        av.z = __builtin_amdgcn_perm(wv[4 * h + 1], wv[4 * h], ml.sel1);
+        av.w = __builtin_amdgcn_perm(wv[4 * h + 3], wv[4 * h + 2], ml.sel1);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t d0 = p == 0 ? x[4 * h].r.x : p == 1 ? x[4 * h].r.y : p == 2 ? x[4 * h].r.z : x[4 * h].r.w;
+            const uint32_t d1 = p == 0 ? x[4 * h + 1].r.x : p == 1 ? x[4 * h + 1].r.y : p == 2 ? x[4 * h + 1].r.z : x[4 * h + 1].r.w;
+            const uint32_t d2 = p == 0 ? x[4 * h + 2].r.x : p == 1 ? x[4 * h + 2].r.y : p == 2 ? x[4 * h + 2].r.z : x[4 * h + 2].r.w;
+            const uint32_t d3 = p == 0 ? x[4 * h + 3].r.x : p == 1 ? x[4 * h + 3].r.y : p == 2 ? x[4 * h + 3].r.z : x[4 * h + 3].r.w;
+            u32x4_t bv;
+            bv.x = __builtin_amdgcn_perm(d1, d0, kPermLowHalves);
+            bv.y = __builtin_amdgcn_perm(d3, d2, kPermLowHalves);
+            bv.z = __builtin_amdgcn_perm(d1, d0, kPermHighHalves);
+            bv.w = __builtin_amdgcn_perm(d3, d2, kPermHighHalves);
+            acc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv),
+                                                             acc[p], 0, 0, 0);
+        }
+    }
+}
+
+// End of an item: C row 4 g + r of column n belongs to lane 16 kg + n, feature 2 p + (row & 1), part row / 8.
+// Every lane leaves with the eight sums of its own fragment (both parts added).
+__device__ __forceinline__ void mma_collect(const f32x4_t (&acc)[4], float* const xw, const int lane, float (&val)[8])
+{
+    const int n = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * g + r;
+        const int owner = 16 * ((row & 7) >> 1) + n;
+        float* const q = xw + ((row >> 3) * 64 + owner) * 8 + (row & 1);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) q[2 * p] = acc[p][r];
+    }
+    // the exchange stays inside one wavefront, whose LDS operations complete in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int j = 0; j < 8; ++j) val[j] = xw[lane * 8 + j] + xw[(64 + lane) * 8 + j];
+}
+
+// Rows of 33..64 fragments: one edge per wave-wide load, ids and weights in scalar registers.
+template <bool TAIL>
+__device__ __forceinline__ void mma_wide_group(const uint16_t* __restrict__ X, const int64_t ld, const int (&u)[8], const float (&w)[8],
+                                               const int cnt, const int ldcol, const MmaLane ml, f32x4_t (&acc)[4])
+{
+    Frag<uint16_t, 8> x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (TAIL && k >= cnt)
+            x[k].zero();
+        else
+            x[k].load(X + (int64_t)u[k] * ld + ldcol);
+    }
+    // this lane's part of every weight in the upper half of a dword: hi = bf16(w) for the rows 0..7,
+    // bf16(w - hi) for the rows 8..15 (adding 0x8000 before the truncation rounds)
+    const uint32_t lo_mask = ml.low_rows ? 0xffff0000u : 0u;
+    uint32_t part[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float wk = (TAIL && k >= cnt) ? 0.f : w[k];
+        const uint32_t hi = (__float_as_uint(wk) + 0x8000u) & 0xffff0000u;
+        part[k] = __float_as_uint(wk - __uint_as_float(hi & lo_mask)) + 0x8000u;
+    }
+    mma_consume(x, part, ml, !TAIL || cnt > 4, acc);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7, 8))) void k_gather_wide_mma(const GatherArgs a)
+{
+    ItemView it;
+    if (!fetch_item(a, &it)) return;  // launched without team items
+    const int lane = threadIdx.x & 63;
+    const int nvec = a.F / 8;  // 33..64
+    const bool ok = lane < nvec;
+    const int col = lane * 8;
+    const int ldcol = ok ? col : 0;  // lanes past the end of the row re-read its first fragment and drop the result
+    const uint16_t* __restrict__ X = static_cast<const uint16_t*>(a.src);
+    const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
+    const const_f32_ptr ew = (const_f32_ptr)(uintptr_t)a.edge_w;
+    __shared__ float xch[kWavesPerBlock][2 * 64 * 8];
+    const MmaLane ml = mma_lane(lane, kPermHighHalves, kPermHighHalves);
+
+    f32x4_t acc[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) acc[p] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    int u[8], un[8];
+    float w[8], wn[8];
+    int e = it.e0;
+    if (e + 8 <= it.e1) fetch_ids<8, false>(ridx, ew, e, it.e1, un, wn);
+    for (; e + 8 <= it.e1; e += 8) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            u[k] = un[k];
+            w[k] = wn[k];
+        }
+        // ids of the next full group travel while this group's rows do
+        if (e + 16 <= it.e1) fetch_ids<8, false>(ridx, ew, e + 8, it.e1, un, wn);
+        mma_wide_group<false>(X, a.ld_src, u, w, 8, ldcol, ml, acc);
+    }
+    if (e < it.e1) {
+        fetch_ids<8, true>(ridx, ew, e, it.e1, u, w);
+        mma_wide_group<true>(X, a.ld_src, u, w, it.e1 - e, ldcol, ml, acc);
+    }
+    float val[8];
+    mma_collect(acc, xch[threadIdx.x >> 6], lane, val);
+    if (ok) store_row<8>(a, it.v, it.slot, col, val, SAGA_AGG_SUM, false);
+}
+
+// Rows of 9..32 fragments: 2 or 4 edges side by side in one wave-wide load (lpr = 32 or 16 lanes per row, so a
+// lane group of the MFMA never straddles two edges). Ids and weights of 64 edges are read one per lane and travel
+// by lane permutes.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(6, 8))) void k_gather_narrow_mma(const GatherArgs a, const int lpr_log2)
+{
+    ItemView it;
+    if (!fetch_item(a, &it)) return;  // launched without team items
+    const int lane = threadIdx.x & 63;
+    const int nvec = a.F / 8;
+    const int lpr = 1 << lpr_log2;
+    const int sub = lane & (lpr - 1);
+    const int grp = lane >> lpr_log2;
+    const int epw_log2 = 6 - lpr_log2;
+    const int epw = 1 << epw_log2;
+    const bool colok = sub < nvec;
+    const int col = sub * 8;
+    const int ldcol = colok ? col : 0;
+    const uint16_t* __restrict__ X = static_cast<const uint16_t*>(a.src);
+    const int32_t* __restrict__ ridx = a.row_idx;
+    const float* __restrict__ ew = a.edge_w;
+    const char* const xbase = reinterpret_cast<const char*>(X + ldcol);  // see k_gather_narrow
+    const uint32_t ldb = (uint32_t)(a.ld_src * 2);
+    const int grp4 = grp << 2;  // slot s < 64 of a batch lives in lane s: byte address 4 s of the lane permute
+    __shared__ float xch[kWavesPerBlock][2 * 64 * 8];
+    const MmaLane ml = mma_lane(lane, kPermHighHalves, kPermLowHalves);
+
+    f32x4_t acc[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) acc[p] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // Ids and weights of a batch of 64 edges, one per lane. Slots past the end of the item repeat its last edge with
+    // weight 0, so that every load step can run unguarded. The loaded values are not touched before the batch they
+    // belong to starts: the next batch's are requested right after the first rows of this one.
+    auto fetch_batch = [&](const int eb, int& id_out, float& w_out) {
+        const int my = eb + lane;
+        id_out = __builtin_nontemporal_load(ridx + min(my, it.e1 - 1));  // read once: kept out of the rows' way in the L2
+        w_out = my < it.e1 ? (ew ? __builtin_nontemporal_load(ew + my) : 1.0f) : 0.f;
+    };
+    int idx_next = 0;
+    float wt_next = 0.f;
+    if (it.e0 < it.e1) fetch_batch(it.e0, idx_next, wt_next);
+    for (int eb = it.e0; eb < it.e1; eb += 64) {
+        const int idx = idx_next;
+        // both bf16 parts of the weight in one dword, split once per edge (not once per use)
+        const uint32_t w_hi = f32_to_bf16_rne(wt_next);
+        const uint32_t wt = (w_hi << 16) | f32_to_bf16_rne(wt_next - __uint_as_float(w_hi << 16));
+        const int cnt = min(64, it.e1 - eb);
+        // groups of eight load steps, all issued before the first is consumed
+        for (int j0 = 0; (j0 << epw_log2) < cnt; j0 += 8) {
+            Frag<uint16_t, 8> x[8];
+            uint32_t wv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t u = (uint32_t)__builtin_amdgcn_ds_bpermute(((j0 + k) << (epw_log2 + 2)) + grp4, idx);
+                x[k].load(reinterpret_cast<const uint16_t*>(xbase + (uint64_t)u * ldb));
+            }
+            if (j0 == 0 && eb + 64 < it.e1) fetch_batch(eb + 64, idx_next, wt_next);
+            // the weights are only needed when the rows are there: fetching them after the loads keeps their
+            // registers free while the row addresses are formed
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) wv[k] = (uint32_t)__builtin_amdgcn_ds_bpermute(((j0 + k) << (epw_log2 + 2)) + grp4, (int)wt);
+            mma_consume(x, wv, ml, ((j0 + 4) << epw_log2) < cnt, acc);
+        }
+    }
+    float val[8];
+    mma_collect(acc, xch[threadIdx.x >> 6], lane, val);
+    for (int off = lpr; off < 64; off <<= 1)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) val[j] += __shfl_xor(val[j], off);
+    if (grp == 0 && colok) store_row<8>(a, it.v, it.slot, col, val, SAGA_AGG_SUM, false);
+}
+
+// ---------------------------------------------------------------------------
 // rows of <= 32 fragments: lpr = 2^lpr_log2 lanes cover a row, 64 / lpr edges
 // sit side by side in one wave-wide load; a butterfly over the lane groups
 // finishes the reduction.
@@ -513,6 +748,13 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
     const int64_t ld2 = GATED ? a.ld_src2 : 0;
     const int32_t* __restrict__ ridx = a.row_idx;
     const float* __restrict__ ew = a.edge_w;
+    // row address = this lane's fragment of row 0 + id * bytes per row: one 32 x 32 -> 64-bit multiply-add
+    // (the launcher checks that a row stride fits 32 bits)
+    const char* const xbase = reinterpret_cast<const char*>(X + ldcol);
+    const char* const xbase2 = reinterpret_cast<const char*>(X2 + ldcol);
+    const uint32_t ldb = (uint32_t)(a.ld_src * (int64_t)sizeof(T));
+    const uint32_t ldb2 = (uint32_t)(ld2 * (int64_t)sizeof(T));
+    const int grp4 = grp << 2;
 
     float acc[VEC], acc2[VEC], pd[VEC], c2[VEC];
 #pragma unroll
@@ -571,10 +813,12 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                     const int s = ((j0 + k) << epw_log2) + grp;
                     ok[k] = !CHECK || s < cnt;
                     // slots past the end of the batch hold id 0: a valid row, loaded and dropped
-                    const int64_t u = __shfl(idx, s & 63);
-                    w[k] = __shfl(wt, s & 63);
-                    x[k].load(X + u * a.ld_src + ldcol);
-                    if constexpr (GATED) m[k].load(X2 + u * ld2 + ldcol);
+                    // slot s < 64 of the batch lives in lane s: byte address 4 s of the lane permute
+                    const int from = ((j0 + k) << (epw_log2 + 2)) + grp4;
+                    const uint32_t u = (uint32_t)__builtin_amdgcn_ds_bpermute(from, idx);
+                    w[k] = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(wt)));
+                    x[k].load(reinterpret_cast<const T*>(xbase + (uint64_t)u * ldb));
+                    if constexpr (GATED) m[k].load(reinterpret_cast<const T*>(xbase2 + (uint64_t)u * ldb2));
                 }
             }
 #pragma unroll
@@ -801,6 +1045,8 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.out16) vec_ok = vec_ok && (a.ld_out16 * 2) % 16 == 0 && aligned16(a.out16);
     if (a.partials) vec_ok = vec_ok && aligned16(a.partials);
     if ((a.bias || a.act != SAGA_ACT_NONE) && a.accumulate) return hipErrorInvalidValue;
+    if (a.ld_src < 0 || a.ld_src >= (1LL << 30) || a.ld_src2 < 0 || a.ld_src2 >= (1LL << 30))
+        return hipErrorInvalidValue;  // the kernels form row offsets in bytes with 32-bit row strides
     const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {
@@ -815,6 +1061,16 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     }
     if (a.dtype == SAGA_F32) return vec_ok ? launch_op<float, 4>(a, s) : launch_op<float, 1>(a, s);
     if (gated) return hipErrorInvalidValue;
+    if (a.mma && vec_ok && a.agg == SAGA_AGG_SUM && a.n_team == 0 && a.F > 8 * 8 && a.F <= 64 * 8) {
+        const int64_t blocks = (a.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        const int nvec = a.F / 8;
+        if (nvec > 32)
+            hipLaunchKernelGGL(k_gather_wide_mma, dim3((unsigned)blocks), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL(k_gather_narrow_mma, dim3((unsigned)blocks), dim3(256), 0, s, a, nvec > 16 ? 5 : 4);
+        return hipGetLastError();
+    }
     return vec_ok ? launch_op<uint16_t, 8>(a, s) : launch_op<uint16_t, 1>(a, s);
 }
 

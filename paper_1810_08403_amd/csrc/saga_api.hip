@@ -618,6 +618,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "team")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "team must be 0 or 1");
         ctx->opt_team = (int)value;
+    } else if (!strcmp(name, "mma")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "mma must be 0 or 1");
+        ctx->opt_mma = (int)value;
     } else if (!strcmp(name, "xcd_remap")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "xcd_remap must be 0 or 1");
         ctx->opt_xcd_remap = (int)value;
@@ -883,6 +886,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ga.agg = agg;
     ga.op = pool ? (int32_t)SAGA_EDGE_COPY : ep->op;
     ga.xcd_remap = ctx->opt_xcd_remap;
+    ga.mma = ctx->opt_mma;
     ga.accumulate = 0;
 
     if (ep->op == SAGA_EDGE_GATED) {

@@ -79,6 +79,7 @@ struct saga_ctx {
     int64_t opt_cut_degree = 0;    // 0 = 2 * split
     int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
     int opt_xcd_remap = 1;
+    int opt_mma = 0;               // 1: bf16 sum propagation with the multiply-accumulate on the matrix unit (measured: a tie)
     int opt_team = 0;              // 1: a piece of a cut column is worked by a whole workgroup (measured slower)
     int opt_dst_intervals = 0, opt_src_intervals = 0;
     int opt_schedule = 0;  // streamed path: 0 the paper's schedule, 1 stage by stage, 2 destination order innermost
@@ -210,6 +211,7 @@ struct GatherArgs {
     float* partials;         // n_slots x F fp32
     int32_t accumulate;      // 1: combine with what `out` already holds (streamed, chunk i > 0)
     int32_t xcd_remap;
+    int32_t mma;             // 1: bf16 sums over linear messages may run their multiply-accumulate on the matrix unit
     // transform-first layers: the gathered rows are already X W, so ApplyVertex's bias and activation are applied
     // to every finished row (whole-column items here, cut columns in the combine pass); not with `accumulate`
     const float* bias;       // [F] fp32, nullable

@@ -105,6 +105,28 @@ def test_gather_widths_and_both_accumulators(ctx, F, agg):
     graph.destroy()
 
 
+@pytest.mark.parametrize("F", [72, 128, 136, 200, 256, 264, 384, 512])
+@pytest.mark.parametrize("op", ["copy", "mul_weight"])
+def test_bf16_sums_on_the_matrix_unit_and_on_the_vector_alus(F, op):
+    """bf16 rows of 9..64 fragments (4 or 2 edges side by side in a wavefront, or one): the propagation kernel that accumulates with MFMA (option mma = 1) and the
+    one that accumulates with FMAs (mma = 0), both against the oracle at the fp32 bar (edge weights enter the MFMA
+    as two bf16 parts, 2^-18 relative). Empty columns, cut columns and item tails of every length 1..7 occur."""
+    wl = si.workload(4, scale=12, edge_factor=48, f_in=F, f_out=16)      # no self-loops: empty columns
+    wl.edge_op, wl.dtype = op, "bf16"
+    wl.edge_weight = si.normal(5, 8, wl.graph.nnz) if op == "mul_weight" else None   # signed weights
+    wl.X, wl.W = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W)
+    deg = wl.graph.in_degree()
+    assert (deg == 0).any() and deg.max().item() > 1024 and len(set((deg % 8).tolist())) == 8
+    ref = run_oracle(wl, with_vertex=False)
+    for mma in (1, 0):
+        with new_context(mma=mma) as c:
+            graph = make_graph(c, wl.graph)
+            _, A = run_gpu(c, wl, graph, with_vertex=False)
+            assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, f"bf16 sum F={F} {op} mma={mma}")
+            assert not A[(deg == 0).numpy()].any()
+            graph.destroy()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("op", ["copy", "mul_weight"])
 def test_max_gather_is_bit_exact_with_split_and_empty_columns(ctx, dtype, op):
