@@ -659,8 +659,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(6, 8))) voi
     const int lpr = 1 << lpr_log2;
     const int sub = lane & (lpr - 1);
     const int grp = lane >> lpr_log2;
-    const int epw_log2 = 6 - lpr_log2;
-    const int epw = 1 << epw_log2;
+    const int epw_log2 = 6 - lpr_log2;  // 2 or 4 edges per wave-wide load
     const bool colok = sub < nvec;
     const int col = sub * 8;
     const int ldcol = colok ? col : 0;
