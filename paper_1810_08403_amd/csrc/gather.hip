@@ -16,6 +16,12 @@
 //     latency;
 //   * heavy columns are cut into items of bounded length whose partial rows
 //     are combined in a fixed order, so sums are reproducible.
+//
+// Kernels: k_gather_wide (rows of >= 64 fragments of 16 bytes), k_gather_narrow
+// (fewer: several edges side by side in a wavefront), both templates over the
+// per-edge function; k_gather_wide_mma / k_gather_narrow_mma (optional: bf16
+// sums whose multiply-accumulate runs on the matrix unit); k_combine (partial
+// rows of cut columns); small fill / copy / validation kernels.
 #include <cmath>
 #include <type_traits>
 
