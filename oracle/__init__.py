@@ -51,7 +51,8 @@ class _BwdArgs(ctypes.Structure):
     _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
                 ("edge_op", _I32), ("act", _I32), ("edge_w", _P), ("A", _P),
                 ("W", _P), ("bias", _P), ("W_self", _P), ("F_out", _I64), ("dY", _P),
-                ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dW_self", _P), ("dbias", _P), ("dA", _P)]
+                ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dW_self", _P), ("dbias", _P), ("dA", _P),
+                ("dW_self_abs", _P), ("dbias_abs", _P)]
 
 
 class _GBwdArgs(ctypes.Structure):
@@ -61,7 +62,8 @@ class _GBwdArgs(ctypes.Structure):
                 ("F_out", _I64), ("act", _I32), ("pad_", _I32), ("dY", _P),
                 ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dbias", _P),
                 ("dW_gate", _P), ("dW_gate_abs", _P), ("db_gate", _P), ("db_gate_abs", _P),
-                ("dW_msg", _P), ("dW_msg_abs", _P)]
+                ("dW_msg", _P), ("dW_msg_abs", _P),
+                ("W_self", _P), ("dW_self", _P), ("dW_self_abs", _P), ("dbias_abs", _P)]
 
 
 class _MBwdArgs(ctypes.Structure):
@@ -70,7 +72,8 @@ class _MBwdArgs(ctypes.Structure):
                 ("edge_op", _I32), ("act", _I32), ("edge_w", _P), ("W_pool", _P), ("b_pool", _P), ("F_pool", _I64),
                 ("W", _P), ("bias", _P), ("F_out", _I64), ("dY", _P), ("A", _P),
                 ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dbias", _P),
-                ("dW_pool", _P), ("dW_pool_abs", _P), ("db_pool", _P), ("db_pool_abs", _P)]
+                ("dW_pool", _P), ("dW_pool_abs", _P), ("db_pool", _P), ("db_pool_abs", _P),
+                ("W_self", _P), ("dW_self", _P), ("dW_self_abs", _P), ("dbias_abs", _P)]
 
 
 def lib():
@@ -216,7 +219,7 @@ def layer_backward(col_ptr, row_idx, X, A, dY, W, edge_op="copy", edge_weight=No
     """Gradients of one sum-accumulator layer with a linear ApplyEdge (Section 2.2's backward stages).
 
     A is the forward Gather output (fp64, from layer()); dY the gradient of the layer's output.
-    Returns fp64 arrays: dX, dX_abs, dW, dW_abs, dbias, dA, and dW_self when W_self is given.
+    Returns fp64 arrays: dX, dX_abs, dW, dW_abs, dbias, dbias_abs, dA, and dW_self, dW_self_abs when W_self is given.
     """
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
@@ -227,13 +230,15 @@ def layer_backward(col_ptr, row_idx, X, A, dY, W, edge_op="copy", edge_weight=No
     assert A.shape == (n, F) and Wv.shape == (F, F_out) and dYv.shape == (n, F_out)
     w, bv, Ws = _f32(edge_weight), _f32(bias), _f32(W_self)
     out = {"dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((F, F_out)), "dW_abs": np.empty((F, F_out)),
-           "dbias": np.empty(F_out), "dA": np.empty((n, F))}
+           "dbias": np.empty(F_out), "dbias_abs": np.empty(F_out), "dA": np.empty((n, F))}
     if Ws is not None:
         assert Ws.shape == (F, F_out)
         out["dW_self"] = np.empty((F, F_out))
+        out["dW_self_abs"] = np.empty((F, F_out))
     a = _BwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(X), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(A),
                  _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]),
-                 _ptr(out["dW_abs"]), _ptr(out.get("dW_self")), _ptr(out["dbias"]), _ptr(out["dA"]))
+                 _ptr(out["dW_abs"]), _ptr(out.get("dW_self")), _ptr(out["dbias"]), _ptr(out["dA"]),
+                 _ptr(out.get("dW_self_abs")), _ptr(out["dbias_abs"]))
     rc = lib().saga_oracle_layer_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_layer_backward rejected its arguments")
@@ -244,7 +249,7 @@ def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="co
                     act="none", want_dbias=False):
     """layer_backward's definitions evaluated only for the rows dX[ulist] and the entries dW[f, o] in w_entries
     (a list of (f, o) pairs), for graphs too large to do whole. A may be fp32 or fp64 (it is read as fp64).
-    Returns dict: dX, dX_abs (len(ulist) x F), dW, dW_abs (len(w_entries)), and dbias when asked for."""
+    Returns dict: dX, dX_abs (len(ulist) x F), dW, dW_abs (len(w_entries)), and dbias, dbias_abs when asked for."""
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
     Wv, dYv = _f32(W), _f32(dY)
@@ -261,8 +266,10 @@ def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="co
     out = {"dX": np.zeros((len(ul), F)), "dX_abs": np.zeros((len(ul), F)), "dW": np.zeros(len(wf)), "dW_abs": np.zeros(len(wf))}
     if want_dbias:
         out["dbias"] = np.empty(F_out)
+        out["dbias_abs"] = np.empty(F_out)
     a = _BwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(A),
-                 _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, _ptr(dYv), None, None, None, None, None, _ptr(out.get("dbias")), None)
+                 _ptr(Wv), _ptr(bv), _ptr(Ws), F_out, _ptr(dYv), None, None, None, None, None, _ptr(out.get("dbias")), None,
+                 None, _ptr(out.get("dbias_abs")))
     rc = lib().saga_oracle_backward_sample(ctypes.byref(a), len(ul), _ptr(ul), _ptr(out["dX"]), _ptr(out["dX_abs"]),
                                            len(wf), _ptr(wf), _ptr(wo), _ptr(out["dW"]), _ptr(out["dW_abs"]))
     if rc != 0:
@@ -270,11 +277,12 @@ def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="co
     return out
 
 
-def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=None, bias=None, act="none"):
+def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=None, bias=None, act="none", W_self=None):
     """Gradients of one gated layer with the sum accumulator (Example 2.1 / Figure 2, Section 2.2's backward stages).
 
     A is the forward Gather output (fp64). Returns fp64 arrays dX, dW, dbias, dW_gate (F x 2F), db_gate, dW_msg
-    (with respect to an explicit identity when W_msg is None) and the *_abs error scales of all but dbias."""
+    (with respect to an explicit identity when W_msg is None), dW_self when W_self is given, and their *_abs error
+    scales."""
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
     Xv, Wv, dYv, Wg = _f32(X), _f32(W), _f32(dY), _f32(W_gate)
@@ -282,43 +290,52 @@ def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=Non
     n, F = Xv.shape
     F_out = Wv.shape[1]
     assert A.shape == (n, F) and Wv.shape == (F, F_out) and dYv.shape == (n, F_out) and Wg.shape == (F, 2 * F)
-    bg, Wm, bv = _f32(b_gate), _f32(W_msg), _f32(bias)
+    bg, Wm, bv, Ws = _f32(b_gate), _f32(W_msg), _f32(bias), _f32(W_self)
     assert Wm is None or Wm.shape == (F, F)
     out = {"dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((F, F_out)), "dW_abs": np.empty((F, F_out)),
-           "dbias": np.empty(F_out), "dW_gate": np.empty((F, 2 * F)), "dW_gate_abs": np.empty((F, 2 * F)),
+           "dbias": np.empty(F_out), "dbias_abs": np.empty(F_out), "dW_gate": np.empty((F, 2 * F)), "dW_gate_abs": np.empty((F, 2 * F)),
            "db_gate": np.empty(F), "db_gate_abs": np.empty(F), "dW_msg": np.empty((F, F)), "dW_msg_abs": np.empty((F, F))}
+    if Ws is not None:
+        assert Ws.shape == (F, F_out)
+        out.update(dW_self=np.empty((F, F_out)), dW_self_abs=np.empty((F, F_out)))
     a = _GBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(A), _ptr(Wv), _ptr(bv),
                   F_out, ACTS[act], 0, _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]), _ptr(out["dW_abs"]),
                   _ptr(out["dbias"]), _ptr(out["dW_gate"]), _ptr(out["dW_gate_abs"]), _ptr(out["db_gate"]),
-                  _ptr(out["db_gate_abs"]), _ptr(out["dW_msg"]), _ptr(out["dW_msg_abs"]))
+                  _ptr(out["db_gate_abs"]), _ptr(out["dW_msg"]), _ptr(out["dW_msg_abs"]),
+                  _ptr(Ws), _ptr(out.get("dW_self")), _ptr(out.get("dW_self_abs")), _ptr(out["dbias_abs"]))
     rc = lib().saga_oracle_gated_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_gated_backward rejected its arguments")
     return out
 
 
-def max_backward(col_ptr, row_idx, X, dY, W, edge_op="copy", edge_weight=None, W_pool=None, b_pool=None, bias=None, act="none"):
+def max_backward(col_ptr, row_idx, X, dY, W, edge_op="copy", edge_weight=None, W_pool=None, b_pool=None, bias=None, act="none",
+                 W_self=None):
     """Gradients of one max-accumulator layer (COPY, MUL_WEIGHT or POOL messages; Figure 11 and Section 2.2's backward
-    stages). Returns fp64 arrays A (the recomputed Gather output), dX, dW, dbias and, for POOL, dW_pool, db_pool, plus
-    *_abs error scales."""
+    stages). Returns fp64 arrays A (the recomputed Gather output), dX, dW, dbias and, for POOL, dW_pool, db_pool, with
+    W_self dW_self, plus *_abs error scales."""
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
     Xv, Wv, dYv = _f32(X), _f32(W), _f32(dY)
     n, F = Xv.shape
-    Wp, bp, w, bv = _f32(W_pool), _f32(b_pool), _f32(edge_weight), _f32(bias)
+    Wp, bp, w, bv, Ws = _f32(W_pool), _f32(b_pool), _f32(edge_weight), _f32(bias), _f32(W_self)
     Fp = Wp.shape[0] if edge_op == "pool" else 0
     Fm = Fp if edge_op == "pool" else F
     F_out = Wv.shape[1]
     assert Wv.shape == (Fm, F_out) and dYv.shape == (n, F_out)
     out = {"A": np.empty((n, Fm)), "dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((Fm, F_out)),
-           "dW_abs": np.empty((Fm, F_out)), "dbias": np.empty(F_out)}
+           "dW_abs": np.empty((Fm, F_out)), "dbias": np.empty(F_out), "dbias_abs": np.empty(F_out)}
+    if Ws is not None:
+        assert Ws.shape == (F, F_out)
+        out.update(dW_self=np.empty((F, F_out)), dW_self_abs=np.empty((F, F_out)))
     if edge_op == "pool":
         assert Wp.shape == (Fp, F)
         out.update(dW_pool=np.empty((Fp, F)), dW_pool_abs=np.empty((Fp, F)), db_pool=np.empty(Fp), db_pool_abs=np.empty(Fp))
     a = _MBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(Wp), _ptr(bp), Fp,
                   _ptr(Wv), _ptr(bv), F_out, _ptr(dYv), _ptr(out["A"]), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]),
                   _ptr(out["dW_abs"]), _ptr(out["dbias"]), _ptr(out.get("dW_pool")), _ptr(out.get("dW_pool_abs")),
-                  _ptr(out.get("db_pool")), _ptr(out.get("db_pool_abs")))
+                  _ptr(out.get("db_pool")), _ptr(out.get("db_pool_abs")),
+                  _ptr(Ws), _ptr(out.get("dW_self")), _ptr(out.get("dW_self_abs")), _ptr(out["dbias_abs"]))
     rc = lib().saga_oracle_max_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_max_backward rejected its arguments")

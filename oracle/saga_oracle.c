@@ -347,16 +347,43 @@ int saga_oracle_layer(const saga_oracle_args* p)
  * weight), backward-Scatter (every vertex adds up the partial gradients that
  * arrive over its out-edges and its own).
  *
- *   Z = A W + X W_self + bias,  Y = act(Z),  act in {none, ReLU}
- *   dZ = dY (.) act'(Z)                 (ReLU: 1 where Z > 0)
+ *   Z = A W + X W_self + bias,  Y = act(Z),  act in {none, ReLU, sigmoid}
+ *   dZ = dY (.) act'(Z)                 (ReLU: 1 where Z > 0; sigmoid: Y (1 - Y))
  *   dW = A^T dZ,  dW_self = X^T dZ,  dbias = sum_v dZ[v]
  *   dA = dZ W^T
  *   dX[u] = sum_{e: u -> v} w_e dA[v]  +  dZ[u] W_self^T
  *
  * A (n x F, fp64) is the Gather output of the forward oracle; everything is
  * accumulated in fp64. Outputs may be NULL except where marked. The *_abs
- * outputs hold the same sums with every term replaced by its absolute value.
+ * outputs hold the same sums with every term replaced by its absolute value;
+ * where dZ enters a term, its own error scale (act_backward) takes the place
+ * of |dZ|, which is the same thing for none and ReLU.
  */
+
+/*
+ * dZ = dY * act'(z) for one element, and the scale of dZ's first-order error for a
+ * caller that forms the derivative from the layer's stored fp32 output, as the backward
+ * stage of Section 2.2 does (it is handed the vertex data, not the pre-activation):
+ * none, ReLU: |dZ| (nothing is rounded before the products that use it);
+ * sigmoid: with s = sigmoid(z), d = s (1 - s):  |dY| (d + |1 - 2s| (d za + s)), i.e. the
+ * rounding of the stored s and of z (absolute-term sum za) carried through d' = 1 - 2s,
+ * plus the rounding of the product itself.
+ */
+static void act_backward(int act, double z, double za, double g, double* dz, double* dz_abs)
+{
+    if (act == ACT_RELU) {
+        *dz = z > 0.0 ? g : 0.0;
+        *dz_abs = fabs(*dz);
+    } else if (act == ACT_SIGMOID) {
+        const double s = sigmoid(z), d = s * (1.0 - s), c = fabs(1.0 - 2.0 * s);
+        *dz = g * d;
+        *dz_abs = fabs(g) * (d + c * (d * za + s));
+    } else {
+        *dz = g;
+        *dz_abs = fabs(g);
+    }
+}
+
 typedef struct saga_oracle_bwd_args {
     int64_t n;
     const int64_t* col_ptr;
@@ -374,6 +401,8 @@ typedef struct saga_oracle_bwd_args {
     double *dW_self;     /* F x F_out */
     double *dbias;       /* F_out */
     double *dA;          /* n x F, nullable: gradient of the Gather output */
+    double *dW_self_abs; /* F x F_out, nullable */
+    double *dbias_abs;   /* F_out, nullable */
 } saga_oracle_bwd_args;
 
 int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
@@ -381,31 +410,38 @@ int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
     if (!p || !p->col_ptr || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
     if (p->edge_op != EDGE_COPY && p->edge_op != EDGE_MUL_WEIGHT) return 1;
     if (p->edge_op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
-    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
     if ((p->W_self || p->dW_self) && !p->X) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out;
-    double* dZ = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)Fo);
+    double* dZ = (double*)malloc(sizeof(double) * 2 * (size_t)(n > 0 ? n : 1) * (size_t)Fo);
     double* dA = (double*)calloc((size_t)(n > 0 ? n : 1) * (size_t)F, sizeof(double));
     double* dAa = (double*)calloc((size_t)(n > 0 ? n : 1) * (size_t)F, sizeof(double));
     if (!dZ || !dA || !dAa) { free(dZ); free(dA); free(dAa); return 2; }
+    double* dZa = dZ + (size_t)(n > 0 ? n : 1) * (size_t)Fo;
 
     /* backward-ApplyVertex, per vertex: recompute Z for the activation's derivative */
 #pragma omp parallel for schedule(static)
     for (int64_t v = 0; v < n; ++v) {
         for (int64_t o = 0; o < Fo; ++o) {
-            double z = p->bias ? (double)p->bias[o] : 0.0;
-            for (int64_t f = 0; f < F; ++f) z += p->A[v * F + f] * (double)p->W[f * Fo + o];
+            double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);
+            for (int64_t f = 0; f < F; ++f) {
+                const double t = p->A[v * F + f] * (double)p->W[f * Fo + o];
+                z += t;
+                za += fabs(t);
+            }
             if (p->W_self)
-                for (int64_t k = 0; k < F; ++k) z += (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
-            const double g = (double)p->dY[v * Fo + o];
-            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+                for (int64_t k = 0; k < F; ++k) {
+                    const double t = (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
+                    z += t;
+                    za += fabs(t);
+                }
+            act_backward(p->act, z, za, (double)p->dY[v * Fo + o], &dZ[v * Fo + o], &dZa[v * Fo + o]);
         }
         for (int64_t f = 0; f < F; ++f) {
             double s = 0.0, sa = 0.0;
             for (int64_t o = 0; o < Fo; ++o) {
-                const double t = dZ[v * Fo + o] * (double)p->W[f * Fo + o];
-                s += t;
-                sa += fabs(t);
+                s += dZ[v * Fo + o] * (double)p->W[f * Fo + o];
+                sa += dZa[v * Fo + o] * fabs((double)p->W[f * Fo + o]);
             }
             dA[v * F + f] = s;
             dAa[v * F + f] = sa;
@@ -415,22 +451,29 @@ int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
 #pragma omp parallel for schedule(static)
     for (int64_t fo = 0; fo < F * Fo; ++fo) {
         const int64_t f = fo / Fo, o = fo % Fo;
-        double s = 0.0, sa = 0.0, ss = 0.0;
+        double s = 0.0, sa = 0.0, ss = 0.0, ssa = 0.0;
         for (int64_t v = 0; v < n; ++v) {
-            const double t = p->A[v * F + f] * dZ[v * Fo + o];
-            s += t;
-            sa += fabs(t);
-            if (p->dW_self) ss += (double)p->X[v * F + f] * dZ[v * Fo + o];
+            s += p->A[v * F + f] * dZ[v * Fo + o];
+            sa += fabs(p->A[v * F + f]) * dZa[v * Fo + o];
+            if (p->dW_self) {
+                ss += (double)p->X[v * F + f] * dZ[v * Fo + o];
+                ssa += fabs((double)p->X[v * F + f]) * dZa[v * Fo + o];
+            }
         }
         if (p->dW) p->dW[fo] = s;
         if (p->dW_abs) p->dW_abs[fo] = sa;
         if (p->dW_self) p->dW_self[fo] = ss;
+        if (p->dW_self && p->dW_self_abs) p->dW_self_abs[fo] = ssa;
     }
     if (p->dbias)
         for (int64_t o = 0; o < Fo; ++o) {
-            double s = 0.0;
-            for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+            double s = 0.0, sa = 0.0;
+            for (int64_t v = 0; v < n; ++v) {
+                s += dZ[v * Fo + o];
+                sa += dZa[v * Fo + o];
+            }
             p->dbias[o] = s;
+            if (p->dbias_abs) p->dbias_abs[o] = sa;
         }
     if (p->dA) memcpy(p->dA, dA, sizeof(double) * (size_t)n * (size_t)F);
 
@@ -443,9 +486,8 @@ int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
                 double s = 0.0, sa = 0.0;
                 if (p->W_self)
                     for (int64_t o = 0; o < Fo; ++o) {
-                        const double t = dZ[u * Fo + o] * (double)p->W_self[f * Fo + o];
-                        s += t;
-                        sa += fabs(t);
+                        s += dZ[u * Fo + o] * (double)p->W_self[f * Fo + o];
+                        sa += dZa[u * Fo + o] * fabs((double)p->W_self[f * Fo + o]);
                     }
                 p->dX[u * F + f] = s;
                 if (p->dX_abs) p->dX_abs[u * F + f] = sa;
@@ -473,15 +515,27 @@ int saga_oracle_layer_backward(const saga_oracle_bwd_args* p)
  * exactly as in the whole-graph form. Outputs: dX_rows, dX_rows_abs (n_u x F), dW_vals,
  * dW_abs_vals (n_w).
  */
-static double bwd_dz(const saga_oracle_bwd_args* p, int64_t v, int64_t o)
+static double bwd_dz(const saga_oracle_bwd_args* p, int64_t v, int64_t o, double* dz_abs)
 {
     const double g = (double)p->dY[v * p->F_out + o];
-    if (p->act != ACT_RELU) return g;
-    double z = p->bias ? (double)p->bias[o] : 0.0;
-    for (int64_t f = 0; f < p->F; ++f) z += p->A[v * p->F + f] * (double)p->W[f * p->F_out + o];
-    if (p->W_self)
-        for (int64_t k = 0; k < p->F; ++k) z += (double)p->X[v * p->F + k] * (double)p->W_self[k * p->F_out + o];
-    return z > 0.0 ? g : 0.0;
+    double z = 0.0, za = 0.0, dz;
+    if (p->act != ACT_NONE) {
+        z = p->bias ? (double)p->bias[o] : 0.0;
+        za = fabs(z);
+        for (int64_t f = 0; f < p->F; ++f) {
+            const double t = p->A[v * p->F + f] * (double)p->W[f * p->F_out + o];
+            z += t;
+            za += fabs(t);
+        }
+        if (p->W_self)
+            for (int64_t k = 0; k < p->F; ++k) {
+                const double t = (double)p->X[v * p->F + k] * (double)p->W_self[k * p->F_out + o];
+                z += t;
+                za += fabs(t);
+            }
+    }
+    act_backward(p->act, z, za, g, &dz, dz_abs);
+    return dz;
 }
 
 int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, const int64_t* ulist, double* dX_rows,
@@ -491,26 +545,29 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
     if (!p || !p->col_ptr || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
     if (p->edge_op != EDGE_COPY && p->edge_op != EDGE_MUL_WEIGHT) return 1;
     if (p->edge_op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
-    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
     if (p->W_self && !p->X) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out;
 
     if (p->dbias) {
 #pragma omp parallel for schedule(static)
         for (int64_t o = 0; o < Fo; ++o) {
-            double s = 0.0;
-            for (int64_t v = 0; v < n; ++v) s += bwd_dz(p, v, o);
+            double s = 0.0, sa = 0.0, da;
+            for (int64_t v = 0; v < n; ++v) {
+                s += bwd_dz(p, v, o, &da);
+                sa += da;
+            }
             p->dbias[o] = s;
+            if (p->dbias_abs) p->dbias_abs[o] = sa;
         }
     }
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t i = 0; i < n_w; ++i) {
         const int64_t f = w_f[i], o = w_o[i];
-        double s = 0.0, sa = 0.0;
+        double s = 0.0, sa = 0.0, da;
         for (int64_t v = 0; v < n; ++v) {
-            const double t = p->A[v * F + f] * bwd_dz(p, v, o);
-            s += t;
-            sa += fabs(t);
+            s += p->A[v * F + f] * bwd_dz(p, v, o, &da);
+            sa += fabs(p->A[v * F + f]) * da;
         }
         dW_vals[i] = s;
         dW_abs_vals[i] = sa;
@@ -533,9 +590,9 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
                 double s = 0.0, sa = 0.0;
                 if (p->W_self)
                     for (int64_t o = 0; o < Fo; ++o) {
-                        const double t = bwd_dz(p, u, o) * (double)p->W_self[f * Fo + o];
-                        s += t;
-                        sa += fabs(t);
+                        double da;
+                        s += bwd_dz(p, u, o, &da) * (double)p->W_self[f * Fo + o];
+                        sa += da * fabs((double)p->W_self[f * Fo + o]);
                     }
                 dX_rows[i * F + f] = s;
                 dX_rows_abs[i * F + f] = sa;
@@ -558,8 +615,9 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
 #endif
             double* mine = priv + (size_t)tid * 2 * (size_t)n_u * (size_t)F;
             double* mine_abs = mine + (size_t)n_u * (size_t)F;
-            double* dz = (double*)malloc(sizeof(double) * (size_t)(Fo + 2 * F));
-            double* da = dz + Fo;      /* gradient of accum[v], and the same with absolute terms */
+            double* dz = (double*)malloc(sizeof(double) * (size_t)(2 * Fo + 2 * F));
+            double* dza = dz + Fo;
+            double* da = dza + Fo;     /* gradient of accum[v], and the same with absolute terms */
             double* da_abs = da + F;
 #pragma omp for schedule(dynamic, 64)
             for (int64_t v = 0; v < n; ++v) {
@@ -568,13 +626,12 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
                     const int64_t i = slot[p->row_idx[e]];
                     if (i < 0) continue;
                     if (!have) {
-                        for (int64_t o = 0; o < Fo; ++o) dz[o] = bwd_dz(p, v, o);
+                        for (int64_t o = 0; o < Fo; ++o) dz[o] = bwd_dz(p, v, o, &dza[o]);
                         for (int64_t f = 0; f < F; ++f) {
                             double s = 0.0, sa = 0.0;
                             for (int64_t o = 0; o < Fo; ++o) {
-                                const double t = dz[o] * (double)p->W[f * Fo + o];
-                                s += t;
-                                sa += fabs(t);
+                                s += dz[o] * (double)p->W[f * Fo + o];
+                                sa += dza[o] * fabs((double)p->W[f * Fo + o]);
                             }
                             da[f] = s;
                             da_abs[f] = sa;
@@ -608,8 +665,9 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
  * matrix W_m), sum accumulator, following the backward stages of Section 2.2:
  *
  *   forward   s_e = W_gs x_u + W_gd x_v + b,  g_e = sigmoid(s_e),  t_u = W_m x_u,
- *             m_e = g_e (.) t_u,  A[v] = sum of m_e over in-edges,  Y = act(A W + bias)
+ *             m_e = g_e (.) t_u,  A[v] = sum of m_e over in-edges,  Y = act(A W [+ X W_self] + bias)
  *   backward-ApplyVertex   dZ = dY (.) act'(Z), dW = A^T dZ, dbias = sum_v dZ, dA = dZ W^T
+ *                          [dW_self = X^T dZ, and dZ[u] W_self^T joins dX[u]]
  *   backward-Gather        every in-edge e of v receives dm_e = dA[v]
  *   backward-ApplyEdge     dt_e = g_e (.) dm_e,  ds_e = dm_e (.) t_u (.) g_e (.) (1 - g_e);
  *                          the source receives (ds_e through W_gs, dt_e through W_m), the destination ds_e
@@ -639,70 +697,88 @@ typedef struct saga_oracle_gbwd_args {
     const float* dY;
     double *dX, *dX_abs, *dW, *dW_abs, *dbias;
     double *dW_gate, *dW_gate_abs, *db_gate, *db_gate_abs, *dW_msg, *dW_msg_abs;
+    const float* W_self;                        /* F x F_out, nullable: Z = A W + X W_self + bias */
+    double *dW_self, *dW_self_abs, *dbias_abs;  /* nullable (dW_self with W_self only) */
 } saga_oracle_gbwd_args;
 
 int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
 {
     if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
-    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
     if (!p->dX || !p->dX_abs || !p->dW || !p->dW_abs || !p->dbias || !p->dW_gate || !p->dW_gate_abs || !p->db_gate ||
         !p->db_gate_abs || !p->dW_msg || !p->dW_msg_abs)
         return 1;
+    if (p->dW_self && !p->W_self) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out;
-    const size_t nf = (size_t)(n > 0 ? n : 1) * (size_t)F;
-    double* buf = (double*)calloc(14 * nf + (size_t)(n > 0 ? n : 1) * (size_t)Fo, sizeof(double));
+    const size_t nf = (size_t)(n > 0 ? n : 1) * (size_t)F, nz = (size_t)(n > 0 ? n : 1) * (size_t)Fo;
+    double* buf = (double*)calloc(14 * nf + 2 * nz, sizeof(double));
     if (!buf) return 2;
     double *Ps = buf, *Pd = Ps + nf, *M = Pd + nf, *Psa = M + nf, *Pda = Psa + nf, *Ma = Pda + nf;
     double *dA = Ma + nf, *dAa = dA + nf, *dPs = dAa + nf, *dPd = dPs + nf, *dM = dPd + nf;
-    double *dPsa = dM + nf, *dPda = dPsa + nf, *dMa = dPda + nf, *dZ = dMa + nf;
+    double *dPsa = dM + nf, *dPda = dPsa + nf, *dMa = dPda + nf, *dZ = dMa + nf, *dZa = dZ + nz;
     if (saga_oracle_hoist(n, p->X, F, p->W_gate, p->W_msg, Ps, Pd, M, Psa, Pda, Ma)) { free(buf); return 1; }
 
     /* backward-ApplyVertex */
 #pragma omp parallel for schedule(static)
     for (int64_t v = 0; v < n; ++v) {
         for (int64_t o = 0; o < Fo; ++o) {
-            double z = p->bias ? (double)p->bias[o] : 0.0;
-            for (int64_t f = 0; f < F; ++f) z += p->A[v * F + f] * (double)p->W[f * Fo + o];
-            const double g = (double)p->dY[v * Fo + o];
-            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+            double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);
+            for (int64_t f = 0; f < F; ++f) {
+                const double t = p->A[v * F + f] * (double)p->W[f * Fo + o];
+                z += t;
+                za += fabs(t);
+            }
+            if (p->W_self)
+                for (int64_t k = 0; k < F; ++k) {
+                    const double t = (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
+                    z += t;
+                    za += fabs(t);
+                }
+            act_backward(p->act, z, za, (double)p->dY[v * Fo + o], &dZ[v * Fo + o], &dZa[v * Fo + o]);
         }
         for (int64_t f = 0; f < F; ++f) {
             double s = 0.0, sa = 0.0;
             for (int64_t o = 0; o < Fo; ++o) {
-                const double t = dZ[v * Fo + o] * (double)p->W[f * Fo + o];
-                s += t;
-                sa += fabs(t);
+                s += dZ[v * Fo + o] * (double)p->W[f * Fo + o];
+                sa += dZa[v * Fo + o] * fabs((double)p->W[f * Fo + o]);
             }
             dA[v * F + f] = s;
             dAa[v * F + f] = sa;
         }
     }
-    /* dW: one row of W per thread, every entry a sum over the vertices in order */
+    /* dW (and dW_self): one row of W per thread, every entry a sum over the vertices in order */
 #pragma omp parallel
     {
-        double* row = (double*)malloc(sizeof(double) * 2 * (size_t)Fo);
+        double* row = (double*)malloc(sizeof(double) * 4 * (size_t)Fo);
 #pragma omp for schedule(static)
         for (int64_t f = 0; f < F; ++f) {
-            for (int64_t o = 0; o < 2 * Fo; ++o) row[o] = 0.0;
+            for (int64_t o = 0; o < 4 * Fo; ++o) row[o] = 0.0;
             for (int64_t v = 0; v < n; ++v) {
-                const double a = p->A[v * F + f];
+                const double a = p->A[v * F + f], x = (double)p->X[v * F + f];
                 for (int64_t o = 0; o < Fo; ++o) {
-                    const double t = a * dZ[v * Fo + o];
-                    row[o] += t;
-                    row[Fo + o] += fabs(t);
+                    row[o] += a * dZ[v * Fo + o];
+                    row[Fo + o] += fabs(a) * dZa[v * Fo + o];
+                    row[2 * Fo + o] += x * dZ[v * Fo + o];
+                    row[3 * Fo + o] += fabs(x) * dZa[v * Fo + o];
                 }
             }
             for (int64_t o = 0; o < Fo; ++o) {
                 p->dW[f * Fo + o] = row[o];
                 p->dW_abs[f * Fo + o] = row[Fo + o];
+                if (p->dW_self) p->dW_self[f * Fo + o] = row[2 * Fo + o];
+                if (p->dW_self && p->dW_self_abs) p->dW_self_abs[f * Fo + o] = row[3 * Fo + o];
             }
         }
         free(row);
     }
     for (int64_t o = 0; o < Fo; ++o) {
-        double s = 0.0;
-        for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            s += dZ[v * Fo + o];
+            sa += dZa[v * Fo + o];
+        }
         p->dbias[o] = s;
+        if (p->dbias_abs) p->dbias_abs[o] = sa;
     }
 
     /* backward-Gather and backward-ApplyEdge: a block of features per thread, the edges in order */
@@ -742,6 +818,11 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
                 s += dPs[u * F + f] * wgs + dM[u * F + f] * wm + dPd[u * F + f] * wgd;
                 sa += dPsa[u * F + f] * fabs(wgs) + dMa[u * F + f] * fabs(wm) + dPda[u * F + f] * fabs(wgd);
             }
+            if (p->W_self) /* the vertex's own partial gradient */
+                for (int64_t o = 0; o < Fo; ++o) {
+                    s += dZ[u * Fo + o] * (double)p->W_self[k * Fo + o];
+                    sa += dZa[u * Fo + o] * fabs((double)p->W_self[k * Fo + o]);
+                }
             p->dX[u * F + k] = s;
             p->dX_abs[u * F + k] = sa;
         }
@@ -790,13 +871,31 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
     return 0;
 }
 
+/* the vertex's own partial gradient: dX[u] += dZ[u] W_self^T (and its scale) */
+static void self_gradient(int64_t n, int64_t F, int64_t Fo, const double* dZ, const double* dZa, const float* W_self, double* dX,
+                          double* dX_abs)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t u = 0; u < n; ++u)
+        for (int64_t k = 0; k < F; ++k) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t o = 0; o < Fo; ++o) {
+                s += dZ[u * Fo + o] * (double)W_self[k * Fo + o];
+                sa += dZa[u * Fo + o] * fabs((double)W_self[k * Fo + o]);
+            }
+            dX[u * F + k] += s;
+            dX_abs[u * F + k] += sa;
+        }
+}
+
 /*
  * Backward pass of a layer with the max accumulator (the max-pooling GCN of Figure 11, and max
  * over COPY / MUL_WEIGHT messages), through the backward stages of Section 2.2.
  *
  *   forward   m_e = x_u (COPY), w_e x_u (MUL_WEIGHT, one fp32 multiply), sigmoid(W_p x_u + b_p) (POOL);
- *             A[v][f] = max over in-edges of m_e[f] (0 without in-edges);  Y = act(A W + bias)
- *   backward-ApplyVertex   dZ, dW = A^T dZ, dbias, dA = dZ W^T as for the sum layers
+ *             A[v][f] = max over in-edges of m_e[f] (0 without in-edges);  Y = act(A W [+ X W_self] + bias)
+ *   backward-ApplyVertex   dZ, dW = A^T dZ, dbias, dA = dZ W^T [dW_self = X^T dZ, dZ[u] W_self^T joins dX[u]]
+ *                          as for the sum layers
  *   backward-Gather        the gradient of A[v][f] goes to every in-edge whose message equals the
  *                          maximum (the paper does not say what happens on ties; here every
  *                          maximal edge receives the whole gradient, nothing is divided)
@@ -828,6 +927,8 @@ typedef struct saga_oracle_mbwd_args {
     double *dW, *dW_abs, *dbias;     /* Fm x F_out, F_out */
     double *dW_pool, *dW_pool_abs;   /* F_pool x F (POOL) */
     double *db_pool, *db_pool_abs;   /* F_pool (POOL) */
+    const float* W_self;                        /* F x F_out, nullable: Z = A W + X W_self + bias */
+    double *dW_self, *dW_self_abs, *dbias_abs;  /* nullable (dW_self with W_self only) */
 } saga_oracle_mbwd_args;
 
 int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
@@ -837,14 +938,15 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
     if (op != EDGE_COPY && op != EDGE_MUL_WEIGHT && op != EDGE_POOL) return 1;
     if (op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
     if (op == EDGE_POOL && (!p->W_pool || p->F_pool <= 0 || !p->dW_pool || !p->dW_pool_abs || !p->db_pool || !p->db_pool_abs)) return 1;
-    if (p->act != ACT_NONE && p->act != ACT_RELU) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
     if (!p->dX || !p->dX_abs || !p->dW || !p->dW_abs || !p->dbias) return 1;
+    if (p->dW_self && !p->W_self) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out, Fm = op == EDGE_POOL ? p->F_pool : F;
-    const size_t nm = (size_t)(n > 0 ? n : 1) * (size_t)Fm;
-    double* buf = (double*)calloc(8 * nm + (size_t)(n > 0 ? n : 1) * (size_t)Fo, sizeof(double));
+    const size_t nm = (size_t)(n > 0 ? n : 1) * (size_t)Fm, nz = (size_t)(n > 0 ? n : 1) * (size_t)Fo;
+    double* buf = (double*)calloc(8 * nm + 2 * nz, sizeof(double));
     if (!buf) return 2;
     double *S = buf, *Sz = S + nm, *A = Sz + nm, *dA = A + nm, *dAa = dA + nm, *dS = dAa + nm, *dSa = dS + nm, *spare = dSa + nm;
-    double* dZ = spare + nm;
+    double *dZ = spare + nm, *dZa = dZ + nz;
 
     /* the per-vertex part of the message: x_u, or h_u = sigmoid(W_p x_u + b_p) with the absolute-term sum of its argument */
 #pragma omp parallel for schedule(static)
@@ -882,17 +984,25 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
 #pragma omp parallel for schedule(static)
     for (int64_t v = 0; v < n; ++v) {
         for (int64_t o = 0; o < Fo; ++o) {
-            double z = p->bias ? (double)p->bias[o] : 0.0;
-            for (int64_t c = 0; c < Fm; ++c) z += A[v * Fm + c] * (double)p->W[c * Fo + o];
-            const double g = (double)p->dY[v * Fo + o];
-            dZ[v * Fo + o] = (p->act == ACT_RELU && !(z > 0.0)) ? 0.0 : g;
+            double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);
+            for (int64_t c = 0; c < Fm; ++c) {
+                const double t = A[v * Fm + c] * (double)p->W[c * Fo + o];
+                z += t;
+                za += fabs(t);
+            }
+            if (p->W_self)
+                for (int64_t k = 0; k < F; ++k) {
+                    const double t = (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
+                    z += t;
+                    za += fabs(t);
+                }
+            act_backward(p->act, z, za, (double)p->dY[v * Fo + o], &dZ[v * Fo + o], &dZa[v * Fo + o]);
         }
         for (int64_t c = 0; c < Fm; ++c) {
             double s = 0.0, sa = 0.0;
             for (int64_t o = 0; o < Fo; ++o) {
-                const double t = dZ[v * Fo + o] * (double)p->W[c * Fo + o];
-                s += t;
-                sa += fabs(t);
+                s += dZ[v * Fo + o] * (double)p->W[c * Fo + o];
+                sa += dZa[v * Fo + o] * fabs((double)p->W[c * Fo + o]);
             }
             dA[v * Fm + c] = s;
             dAa[v * Fm + c] = sa;
@@ -903,17 +1013,33 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
         const int64_t c = co / Fo, o = co % Fo;
         double s = 0.0, sa = 0.0;
         for (int64_t v = 0; v < n; ++v) {
-            const double t = A[v * Fm + c] * dZ[v * Fo + o];
-            s += t;
-            sa += fabs(t);
+            s += A[v * Fm + c] * dZ[v * Fo + o];
+            sa += fabs(A[v * Fm + c]) * dZa[v * Fo + o];
         }
         p->dW[co] = s;
         p->dW_abs[co] = sa;
     }
+    if (p->dW_self) {
+#pragma omp parallel for schedule(static)
+        for (int64_t ko = 0; ko < F * Fo; ++ko) {
+            const int64_t k = ko / Fo, o = ko % Fo;
+            double s = 0.0, sa = 0.0;
+            for (int64_t v = 0; v < n; ++v) {
+                s += (double)p->X[v * F + k] * dZ[v * Fo + o];
+                sa += fabs((double)p->X[v * F + k]) * dZa[v * Fo + o];
+            }
+            p->dW_self[ko] = s;
+            if (p->dW_self_abs) p->dW_self_abs[ko] = sa;
+        }
+    }
     for (int64_t o = 0; o < Fo; ++o) {
-        double s = 0.0;
-        for (int64_t v = 0; v < n; ++v) s += dZ[v * Fo + o];
+        double s = 0.0, sa = 0.0;
+        for (int64_t v = 0; v < n; ++v) {
+            s += dZ[v * Fo + o];
+            sa += dZa[v * Fo + o];
+        }
         p->dbias[o] = s;
+        if (p->dbias_abs) p->dbias_abs[o] = sa;
     }
 
     /* backward-Gather, backward-ApplyEdge's edge factor and backward-Scatter: a block of features per thread, edges in order */
@@ -938,6 +1064,7 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
     if (op != EDGE_POOL) {
         memcpy(p->dX, dS, sizeof(double) * (size_t)n * (size_t)F);
         memcpy(p->dX_abs, dSa, sizeof(double) * (size_t)n * (size_t)F);
+        if (p->W_self) self_gradient(n, F, Fo, dZ, dZa, p->W_self, p->dX, p->dX_abs);
         free(buf);
         return 0;
     }
@@ -959,6 +1086,7 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
             p->dX[u * F + k] = s;
             p->dX_abs[u * F + k] = sa;
         }
+    if (p->W_self) self_gradient(n, F, Fo, dZ, dZa, p->W_self, p->dX, p->dX_abs);
 #pragma omp parallel for schedule(static)
     for (int64_t c = 0; c < Fm; ++c) {
         double bs = 0.0, bsa = 0.0;

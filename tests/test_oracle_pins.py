@@ -461,7 +461,7 @@ def _bwd_setup(seed=12, n=40, m=260, F=5, Fo=4):
     return g, X, W, Ws, b, w, dY
 
 
-@pytest.mark.parametrize("act", ["none", "relu"])
+@pytest.mark.parametrize("act", ["none", "relu", "sigmoid"])
 @pytest.mark.parametrize("with_self", [False, True])
 def test_backward_equals_dense_matrix_form(act, with_self):
     g, X, W, Ws, b, w, dY = _bwd_setup()
@@ -472,7 +472,8 @@ def test_backward_equals_dense_matrix_form(act, with_self):
     Xd, Wd, dYd = X.astype(np.float64), W.astype(np.float64), dY.astype(np.float64)
     A = Adj @ Xd
     Z = A @ Wd + b + (Xd @ Ws.astype(np.float64) if with_self else 0.0)
-    dZ = dYd * (Z > 0) if act == "relu" else dYd
+    Sg = 1.0 / (1.0 + np.exp(-Z))
+    dZ = dYd * (Z > 0) if act == "relu" else (dYd * Sg * (1.0 - Sg) if act == "sigmoid" else dYd)
     assert np.allclose(bwd["dW"], A.T @ dZ, rtol=1e-12, atol=1e-12)
     assert np.allclose(bwd["dbias"], dZ.sum(0), rtol=1e-12, atol=1e-12)
     assert np.allclose(bwd["dA"], dZ @ Wd.T, rtol=1e-12, atol=1e-12)
@@ -480,9 +481,37 @@ def test_backward_equals_dense_matrix_form(act, with_self):
     assert np.allclose(bwd["dX"], dX, rtol=1e-12, atol=1e-12)
     if with_self:
         assert np.allclose(bwd["dW_self"], Xd.T @ dZ, rtol=1e-12, atol=1e-12)
-    assert np.allclose(bwd["dW_abs"], np.abs(A).T @ np.abs(dZ), rtol=1e-12, atol=1e-12)
-    dXa = np.abs(Adj).T @ (np.abs(dZ) @ np.abs(Wd).T) + (np.abs(dZ) @ np.abs(Ws).astype(np.float64).T if with_self else 0.0)
+    # the scales: |dZ| for none and ReLU; for the sigmoid the scale of a derivative formed from the stored output
+    dZa = np.abs(dZ)
+    if act == "sigmoid":
+        Za = np.abs(A) @ np.abs(Wd) + np.abs(b) + (np.abs(Xd) @ np.abs(Ws).astype(np.float64) if with_self else 0.0)
+        D, C = Sg * (1.0 - Sg), np.abs(1.0 - 2.0 * Sg)
+        dZa = np.abs(dYd) * (D + C * (D * Za + Sg))
+    assert np.allclose(bwd["dW_abs"], np.abs(A).T @ dZa, rtol=1e-12, atol=1e-12)
+    assert np.allclose(bwd["dbias_abs"], dZa.sum(0), rtol=1e-12, atol=1e-12)
+    if with_self:
+        assert np.allclose(bwd["dW_self_abs"], np.abs(Xd).T @ dZa, rtol=1e-12, atol=1e-12)
+    dXa = np.abs(Adj).T @ (dZa @ np.abs(Wd).T) + (dZa @ np.abs(Ws).astype(np.float64).T if with_self else 0.0)
     assert np.allclose(bwd["dX_abs"], dXa, rtol=1e-12, atol=1e-12)
+
+
+def test_sigmoid_derivative_from_the_stored_output_stays_within_its_scale():
+    """The backward stage forms sigmoid'(z) from the stored fp32 output y as y (1 - y). Whatever z is, the distance of
+    dY y (1 - y), evaluated in fp32, from the exact dZ is at most a few units of 2^-24 of the scale the oracle reports
+    (here through dbias_abs of a one-vertex graph without edges, where za = |b|), also for saturated outputs."""
+    g = si.csc_from_lists(1, [])
+    X = np.zeros((1, 1), np.float32)
+    W = np.zeros((1, 1), np.float32)
+    for z in [-30.0, -17.0, -9.0, -2.5, -0.3, 0.0, 0.4, 3.0, 8.0, 12.5, 16.6, 25.0]:
+        b = np.array([z], np.float32)
+        dY = np.array([[1.7]], np.float32)
+        bwd = oracle.layer_backward(*_np(g), X, np.zeros((1, 1)), dY, W, "copy", bias=b, act="sigmoid")
+        sg = 1.0 / (1.0 + np.exp(-np.float64(b[0])))
+        assert abs(bwd["dbias"][0] - np.float64(dY[0, 0]) * sg * (1.0 - sg)) <= 1e-15
+        y = np.float32(sg)
+        got = np.float32(dY[0, 0]) * (y * (np.float32(1.0) - y))
+        assert abs(np.float64(got) - bwd["dbias"][0]) <= 4 * 2.0 ** -24 * bwd["dbias_abs"][0], z
+        assert bwd["dbias_abs"][0] >= abs(bwd["dbias"][0])
 
 
 def test_backward_matches_finite_differences_of_the_forward_oracle():
@@ -525,7 +554,7 @@ def test_backward_relu_mask_and_copy_edges():
     assert np.allclose(bwd["dX"], Adj.T @ (dZ @ W.astype(np.float64).T), rtol=1e-12, atol=1e-12)
 
 
-@pytest.mark.parametrize("act", ["none", "relu"])
+@pytest.mark.parametrize("act", ["none", "relu", "sigmoid"])
 def test_sampled_backward_equals_the_whole_graph_form(act):
     g, X, W, Ws, b, w, dY = _bwd_setup(seed=8, n=60, m=500)
     fwd = oracle.layer(*_np(g), X, "mul_weight", w, W=W, W_self=Ws, bias=b, act="none")
@@ -538,6 +567,7 @@ def test_sampled_backward_equals_the_whole_graph_form(act):
     assert np.allclose(part["dW"], [whole["dW"][f, o] for f, o in we], rtol=1e-12, atol=1e-13)
     assert np.allclose(part["dW_abs"], [whole["dW_abs"][f, o] for f, o in we], rtol=1e-12, atol=1e-13)
     assert np.allclose(part["dbias"], whole["dbias"], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dbias_abs"], whole["dbias_abs"], rtol=1e-12, atol=1e-13)
     if act == "relu":
         assert not np.allclose(part["dbias"], dY.astype(np.float64).sum(0))     # the mask really removes terms
 
@@ -560,30 +590,32 @@ def _gated_bwd_setup(seed=3, n=30, m=170, F=4, Fo=3, with_msg=True, with_b=True)
     return g, X, Wg, bg, Wm, W, b, dY
 
 
-@pytest.mark.parametrize("act", ["none", "relu"])
+@pytest.mark.parametrize("act,with_self", [("none", False), ("relu", False), ("sigmoid", False), ("relu", True), ("sigmoid", True)])
 @pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
-def test_gated_backward_equals_autograd_of_the_dense_form(act, with_msg, with_b):
+def test_gated_backward_equals_autograd_of_the_dense_form(act, with_self, with_msg, with_b):
     import torch
     g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(with_msg=with_msg, with_b=with_b)
     n, F = X.shape
-    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act)
-    bwd = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act)
+    Ws = (np.round(np.random.default_rng(77).standard_normal(W.shape) * 32) / 32).astype(np.float32) if with_self else None
+    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act, W_self=Ws)
+    bwd = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act, W_self=Ws)
     t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
     Xt, Wgt, Wt, bt = t(X), t(Wg), t(W), t(b)
+    Wst = t(Ws if with_self else np.zeros(W.shape))
     bgt = t(bg if with_b else np.zeros(F))
     Wmt = t(Wm if with_msg else np.eye(F))
     Adj = torch.tensor(_dense_adj(g))                                    # Adj[v, u] = 1 for an edge u -> v
     Ps, Pd, M = Xt @ Wgt[:, :F].T, Xt @ Wgt[:, F:].T, Xt @ Wmt.T
     gate = torch.sigmoid(Ps[None, :, :] + Pd[:, None, :] + bgt)           # [v, u, f]
     A = (Adj[:, :, None] * gate * M[None, :, :]).sum(1)
-    Z = A @ Wt + bt
-    Y = torch.relu(Z) if act == "relu" else Z
+    Z = A @ Wt + Xt @ Wst + bt
+    Y = torch.relu(Z) if act == "relu" else (torch.sigmoid(Z) if act == "sigmoid" else Z)
     assert np.allclose(Y.detach().numpy(), fwd["Y"], rtol=1e-12, atol=1e-12)
     (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
     for name, ref in [("dX", Xt.grad), ("dW", Wt.grad), ("dbias", bt.grad), ("dW_gate", Wgt.grad), ("db_gate", bgt.grad),
-                      ("dW_msg", Wmt.grad)]:
+                      ("dW_msg", Wmt.grad)] + ([("dW_self", Wst.grad)] if with_self else []):
         assert np.allclose(bwd[name], ref.numpy(), rtol=1e-10, atol=1e-11), name
-    for name in ["dX", "dW", "dW_gate", "db_gate", "dW_msg"]:
+    for name in ["dX", "dW", "dW_gate", "db_gate", "dW_msg", "dbias"] + (["dW_self"] if with_self else []):
         assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name    # a scale bounds its value
 
 
@@ -625,22 +657,24 @@ def _max_bwd_setup(seed=4, n=40, m=70, F=5, Fp=4, Fo=3):
 
 
 @pytest.mark.parametrize("edge_op", ["copy", "mul_weight", "pool"])
-@pytest.mark.parametrize("act", ["none", "relu"])
-def test_max_backward_equals_autograd_of_the_dense_form(edge_op, act):
+@pytest.mark.parametrize("act,with_self", [("none", False), ("relu", False), ("sigmoid", False), ("relu", True), ("sigmoid", True)])
+def test_max_backward_equals_autograd_of_the_dense_form(edge_op, act, with_self):
     import torch
     g, X, w, Wp, bp, b, rng = _max_bwd_setup()
     n, F = X.shape
     Fm = Wp.shape[0] if edge_op == "pool" else F
     W = rng.standard_normal((Fm, 3)).astype(np.float32)
     dY = rng.standard_normal((n, 3)).astype(np.float32)
+    Ws = rng.standard_normal((F, 3)).astype(np.float32) if with_self else None
     deg = np.diff(g.col_ptr.numpy())
     assert (deg == 0).any() and (deg > 1).any()
     kw = dict(edge_weight=w) if edge_op == "mul_weight" else (dict(W_pool=Wp, b_pool=bp) if edge_op == "pool" else {})
-    fwd = oracle.layer(*_np(g), X, edge_op, agg="max", W=W, bias=b, act=act, **kw)
-    bwd = oracle.max_backward(*_np(g), X, dY, W, edge_op, bias=b, act=act, **kw)
+    fwd = oracle.layer(*_np(g), X, edge_op, agg="max", W=W, bias=b, act=act, W_self=Ws, **kw)
+    bwd = oracle.max_backward(*_np(g), X, dY, W, edge_op, bias=b, act=act, W_self=Ws, **kw)
     assert np.array_equal(bwd["A"], fwd["A"])                             # the Gather it differentiates is the pinned one
     t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
     Xt, Wt, bt, Wpt, bpt = t(X), t(W), t(b), t(Wp), t(bp)
+    Wst = t(Ws if with_self else np.zeros((F, 3)))
     Adj = torch.tensor(_dense_adj(g)) > 0                                  # [v, u]
     if edge_op == "pool":
         S = torch.sigmoid(Xt @ Wpt.T + bpt)[None, :, :].expand(n, n, Fm)
@@ -652,13 +686,18 @@ def test_max_backward_equals_autograd_of_the_dense_form(edge_op, act):
         S = Xt[None, :, :].expand(n, n, F)
     masked = torch.where(Adj[:, :, None], S, torch.tensor(-np.inf, dtype=torch.float64))
     A = torch.where(Adj.any(1)[:, None], masked.amax(1), torch.zeros(n, Fm, dtype=torch.float64))
-    Z = A @ Wt + bt
-    Y = torch.relu(Z) if act == "relu" else Z
+    Z = A @ Wt + Xt @ Wst + bt
+    Y = torch.relu(Z) if act == "relu" else (torch.sigmoid(Z) if act == "sigmoid" else Z)
+    assert np.allclose(Y.detach().numpy(), fwd["Y"], rtol=1e-6, atol=1e-7)
     (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
     tol = dict(rtol=1e-6, atol=1e-7) if edge_op == "mul_weight" else dict(rtol=1e-10, atol=1e-11)
     assert np.allclose(bwd["dX"], Xt.grad.numpy(), **tol)
     assert np.allclose(bwd["dW"], Wt.grad.numpy(), **tol)
     assert np.allclose(bwd["dbias"], bt.grad.numpy(), **tol)
+    if with_self:
+        assert np.allclose(bwd["dW_self"], Wst.grad.numpy(), **tol)
+        assert (bwd["dW_self_abs"] >= np.abs(bwd["dW_self"]) * (1 - 1e-12)).all()
+    assert (bwd["dbias_abs"] >= np.abs(bwd["dbias"]) * (1 - 1e-12)).all()
     if edge_op == "pool":
         assert np.allclose(bwd["dW_pool"], Wpt.grad.numpy(), **tol)
         assert np.allclose(bwd["db_pool"], bpt.grad.numpy(), **tol)
