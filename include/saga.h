@@ -207,13 +207,15 @@ typedef struct saga_layer_grads {
 
 /*
  * One layer backward (the backward stages of Section 2.2, run in reverse order of the
- * forward ones): fp32, ApplyVertex Y = act(A W + X W_self + bias) with act NONE or RELU,
- * everything device-resident. Covered: sum accumulator with COPY, MUL_WEIGHT, GATED or POOL
- * messages; max accumulator with COPY, MUL_WEIGHT or POOL messages. W_self only with sum over
- * COPY / MUL_WEIGHT. Other layers return SAGA_ERR_UNSUPPORTED.
+ * forward ones): fp32, ApplyVertex Y = act(A W + X W_self + bias) with act NONE, RELU or
+ * SIGMOID, everything device-resident. Covered: sum accumulator with COPY, MUL_WEIGHT, GATED
+ * or POOL messages; max accumulator with COPY, MUL_WEIGHT or POOL messages; each with or
+ * without W_self. Max over GATED messages returns SAGA_ERR_UNSUPPORTED.
  *
- *   backward-ApplyVertex   dZ = dY (.) act'(Z)  (ReLU: where Y > 0),  dW = A^T dZ,
- *                          dW_self = X^T dZ,  dbias = column sums of dZ,
+ *   backward-ApplyVertex   dZ = dY (.) act'(Z), the derivative taken from the stored output
+ *                          (ReLU: 1 where Y > 0; sigmoid: Y (1 - Y), whose error is that of
+ *                          the fp32 Y it is formed from: about 2^-24 |dY| Y |1 - 2Y|),
+ *                          dW = A^T dZ, dW_self = X^T dZ,  dbias = column sums of dZ,
  *                          gradient of accum = dZ W^T, own partial gradient = dZ W_self^T
  *   backward-Gather, backward-ApplyEdge, backward-Scatter, fused the way the forward
  *   propagation is: dX[u] = sum over out-edges u -> v of w_e * (gradient of accum)[v]
@@ -221,7 +223,8 @@ typedef struct saga_layer_grads {
  *
  * A is the Gather output of the forward call (its accum_out), kept by the caller as the
  * intermediate feature data back-propagation needs (Section 3.1). X is read only for
- * dW_self and may be NULL without W_self; Y is read only for RELU and may be NULL otherwise.
+ * dW_self and may be NULL without W_self; Y is read only for the activation's derivative and
+ * may be NULL with SAGA_ACT_NONE.
  * The transposed edge order (out-edges grouped by source) and its work list are built at
  * the first backward call on a graph, which synchronises the stream. Because the
  * propagation is linear, it runs at the narrower of F_in and F_out: when F_out <= F_in the
@@ -235,7 +238,8 @@ typedef struct saga_layer_grads {
  * them per vertex: sum of ds_e over in-edges (destination part), sum of ds_e and of dt_e over
  * out-edges (source parts); dense products then give dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd],
  * dW_gate = [dPs^T X | dPd^T X], db_gate = column sums of dPd, dW_msg = dM^T X.
- * X is required.
+ * With W_self the own partial gradient dZ W_self^T joins dX as a second operand pair of that
+ * product. X is required.
  *
  * Max accumulator (Figure 11's layer): the gradient of A[v][f] goes to every in-edge whose
  * message equals the maximum A[v][f] (on a tie every maximal edge receives all of it). The
@@ -244,8 +248,10 @@ typedef struct saga_layer_grads {
  * same product and kernel as in the forward pass), and comparing it with the A the caller
  * kept: one propagation pass over the out-edges. POOL then goes through the sigmoid per
  * vertex: dPre = dS (.) h (.) (1 - h), dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
- * sums of dPre. X and A are required; A must be the accum_out of the forward call on the
- * same inputs, or no message will compare equal.
+ * sums of dPre. With W_self the own partial gradient dZ W_self^T is written into dX before
+ * the propagation adds to it (COPY, MUL_WEIGHT) or joins the product dPre W_pool (POOL).
+ * X and A are required; A must be the accum_out of the forward call on the same inputs, or
+ * no message will compare equal.
  *
  * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, no W_self):
  * A, Y, dY and grads->dX are SAGA_MEM_HOST tensors (pinned recommended), W and the parameter
@@ -253,13 +259,14 @@ typedef struct saga_layer_grads {
  * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
  * (the CSR side of the paper's chunk layout), with dZ as the vertex data and W^T as the
  * ApplyVertex matrix; the transposed chunk grid is built at the first such call. dZ is formed
- * on the way in: a vertex interval's rows of dY (and Y for RELU) are copied to the device and
- * masked in place, and the first time an interval comes by, its rows of A are copied too and
+ * on the way in: a vertex interval's rows of dY (and Y with an activation) are copied to the
+ * device and turned into dZ in place, and the first time an interval comes by, its rows of A are copied too and
  * its share of dW and dbias is added (interval by interval in a fixed order). Without
  * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Every transfer goes
  * through the context's device budget like in saga_layer_forward.
  *
- * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self): X is not
+ * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self, act NONE or
+ * RELU): X is not
  * needed, Y, dY and grads->dX are bf16 like W, A stays the fp32 accum_out of the forward
  * call, parameter gradients are fp32. dZ's bf16 values are used as they are; the rows that
  * travel over the edges and the product that makes dX are bf16 with fp32 accumulation and

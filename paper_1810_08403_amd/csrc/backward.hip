@@ -285,29 +285,42 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
         if ((st = param_grad(ctx, dH + F, ldh, F, Xp, X->ld, F, n, static_cast<float*>(grads->dW_msg->data), grads->dW_msg->ld))) return st;
     if (grads->db_gate) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * F))) return st;
-        HIP_TRY(ctx, launch_dz_colsum(dH + 2 * F, ldh, nullptr, 0, nullptr, n, F, static_cast<float*>(ctx->ws_splitk.p),
+        HIP_TRY(ctx, launch_dz_colsum(dH + 2 * F, ldh, nullptr, 0, SAGA_ACT_NONE, nullptr, n, F, static_cast<float*>(ctx->ws_splitk.p),
                                       static_cast<float*>(grads->db_gate->data), 0, s));
     }
     if (!grads->dX) return SAGA_OK;
 
-    // dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd]: one product over 3F
-    int64_t n_pad, k_pad;
+    // dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd] (+ dZ W_self^T, the vertex's own partial gradient, as a second operand
+    // pair of the same product): one product over 3F (+ F_out)
+    int64_t n_pad, k_pad, k_pad2 = 0;
     bt_padded_shape(F, 3 * F, SAGA_F32, &n_pad, &k_pad);
-    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    if (vp->W_self) {
+        int64_t np2;
+        bt_padded_shape(F, (int32_t)vp->W->cols, SAGA_F32, &np2, &k_pad2);
+    }
+    const int64_t ldbt = k_pad + k_pad2;
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * ldbt)))) return st;
     float* bt = static_cast<float*>(ctx->ws_bt.p);
     const float* Wg = static_cast<const float*>(ep->W_gate->data);
-    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
-    HIP_TRY(ctx, launch_pack_bt_transpose(Wg, ep->W_gate->ld, F, F, SAGA_F32, bt, k_pad, 0, s));
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * ldbt), s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(Wg, ep->W_gate->ld, F, F, SAGA_F32, bt, ldbt, 0, s));
     if (ep->W_msg)
-        HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_msg->data, ep->W_msg->ld, F, F, SAGA_F32, bt, k_pad, F, s));
+        HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_msg->data, ep->W_msg->ld, F, F, SAGA_F32, bt, ldbt, F, s));
     else
-        HIP_TRY(ctx, launch_pack_bt_rows(nullptr, 0, 0, F, F, bt + F, k_pad, 0, s));
-    HIP_TRY(ctx, launch_pack_bt_transpose(Wg + F, ep->W_gate->ld, F, F, SAGA_F32, bt, k_pad, 2 * (int64_t)F, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(nullptr, 0, 0, F, F, bt + F, ldbt, 0, s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(Wg + F, ep->W_gate->ld, F, F, SAGA_F32, bt, ldbt, 2 * (int64_t)F, s));
     GemmArgs gm{};
+    if (vp->W_self) {
+        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(vp->W_self->data), vp->W_self->ld, 0, F, (int32_t)vp->W->cols, bt + k_pad,
+                                         ldbt, 0, s));
+        gm.A2 = dZ;
+        gm.lda2 = lddz;
+        gm.K2 = (int32_t)vp->W->cols;
+    }
     gm.A = dH;
     gm.lda = ldh;
     gm.Bt = bt;
-    gm.ldbt = k_pad;
+    gm.ldbt = ldbt;
     gm.C = grads->dX->data;
     gm.ldc = grads->dX->ld;
     gm.M = n;
@@ -384,8 +397,13 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
         dS = static_cast<float*>(ctx->ws_dh.p);
         ldds = Fm;
     }
+    // without pooling the propagation writes dX itself: the vertex's own partial gradient dZ W_self^T goes in first
+    const int32_t own_first = (!pool && vp->W_self) ? 1 : 0;
+    if (own_first)
+        if ((st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W_self, nullptr, 0, 0, nullptr, n, F, dS, ldds))) return st;
     if (agg == SAGA_AGG_MAX) {
         GatherArgs ga{};
+        ga.accumulate = own_first;
         ga.op = kGatherOpMaxGrad;
         ga.F = Fm;
         ga.src = A->data;      // per edge: the maximum gathered at the destination ...
@@ -399,7 +417,7 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
         ga.ld_out = ldds;
         if ((st = run_propagation(ctx, g->tr, ga, 2 * (int64_t)Fm * 4))) return st;
     } else {
-        if ((st = propagate_transposed(ctx, g, w_t, dA, Fm, Fm, dS, ldds, 0))) return st;
+        if ((st = propagate_transposed(ctx, g, w_t, dA, Fm, Fm, dS, ldds, own_first))) return st;
     }
     if (!pool) return SAGA_OK;
 
@@ -409,21 +427,33 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     if ((st = param_grad(ctx, dS, Fm, Fm, Xp, X->ld, F, n, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
     if (grads->db_pool) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fm))) return st;
-        HIP_TRY(ctx, launch_dz_colsum(dS, Fm, nullptr, 0, nullptr, n, Fm, static_cast<float*>(ctx->ws_splitk.p),
+        HIP_TRY(ctx, launch_dz_colsum(dS, Fm, nullptr, 0, SAGA_ACT_NONE, nullptr, n, Fm, static_cast<float*>(ctx->ws_splitk.p),
                                       static_cast<float*>(grads->db_pool->data), 0, s));
     }
     if (!grads->dX) return SAGA_OK;
-    int64_t n_pad, k_pad;
+    // dX = dPre W_pool (+ dZ W_self^T as a second operand pair of the same product)
+    int64_t n_pad, k_pad, k_pad2 = 0;
     bt_padded_shape(F, Fm, SAGA_F32, &n_pad, &k_pad);
-    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    if (vp->W_self) {
+        int64_t np2;
+        bt_padded_shape(F, Fo, SAGA_F32, &np2, &k_pad2);
+    }
+    const int64_t ldbt = k_pad + k_pad2;
+    if ((st = ctx->dev_alloc(&ctx->ws_bt, sizeof(float) * (size_t)(n_pad * ldbt)))) return st;
     float* bt = static_cast<float*>(ctx->ws_bt.p);
-    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
-    HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_pool->data, ep->W_pool->ld, Fm, F, SAGA_F32, bt, k_pad, 0, s));
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * ldbt), s));
+    HIP_TRY(ctx, launch_pack_bt_transpose(ep->W_pool->data, ep->W_pool->ld, Fm, F, SAGA_F32, bt, ldbt, 0, s));
     GemmArgs gm{};
+    if (vp->W_self) {
+        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(vp->W_self->data), vp->W_self->ld, 0, F, Fo, bt + k_pad, ldbt, 0, s));
+        gm.A2 = dZ;
+        gm.lda2 = lddz;
+        gm.K2 = Fo;
+    }
     gm.A = dS;
     gm.lda = Fm;
     gm.Bt = bt;
-    gm.ldbt = k_pad;
+    gm.ldbt = ldbt;
     gm.C = grads->dX->data;
     gm.ldc = grads->dX->ld;
     gm.M = n;
@@ -446,19 +476,19 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     // backward-ApplyVertex: the activation's derivative and the bias gradient in one pass over the rows
     const float* dZ = static_cast<const float*>(dY->data);
     int64_t lddz = dY->ld;
-    const bool relu = vp->act == SAGA_ACT_RELU;
-    if (relu || grads->dbias) {
+    const bool use_y = vp->act != SAGA_ACT_NONE;  // the activation's derivative is taken from the layer's output
+    if (use_y || grads->dbias) {
         float* part = nullptr;
         if (grads->dbias) {
             if (saga_status st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo)) return st;
             part = static_cast<float*>(ctx->ws_splitk.p);
         }
-        if (relu)
+        if (use_y)
             if (saga_status st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fo)) return st;
-        HIP_TRY(ctx, launch_dz_colsum(dZ, lddz, relu ? static_cast<const float*>(Y->data) : nullptr, relu ? Y->ld : 0,
+        HIP_TRY(ctx, launch_dz_colsum(dZ, lddz, use_y ? static_cast<const float*>(Y->data) : nullptr, use_y ? Y->ld : 0, vp->act,
                                       static_cast<float*>(ctx->ws_dz.p), n, Fo, part,
                                       grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, 0, s));
-        if (relu) {
+        if (use_y) {
             dZ = static_cast<const float*>(ctx->ws_dz.p);
             lddz = Fo;
         }
@@ -466,8 +496,8 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 
     // parameter gradients
     if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW->data), grads->dW->ld)) return st;
-    if (grads->dW_self)
-        if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld)) return st;
+    if (grads->dW_self)  // X is as wide as the messages except for POOL
+        if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, (int32_t)X->cols, dZ, lddz, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld)) return st;
     if (ep->op == SAGA_EDGE_GATED) return gated_backward_rest(ctx, g, X, dZ, lddz, ep, vp, grads);
     if (ep->op == SAGA_EDGE_POOL || agg == SAGA_AGG_MAX) return max_pool_backward_rest(ctx, g, X, A, dZ, lddz, ep, agg, vp, grads);
     if (!grads->dX || n == 0) return SAGA_OK;
@@ -515,7 +545,7 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
                                 relu ? Y->ld : 0, dZ32, dZ16, n, Fo, s));
     if (grads->dbias) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * Fo))) return st;
-        HIP_TRY(ctx, launch_dz_colsum(dZ32, Fo, nullptr, 0, nullptr, n, Fo, static_cast<float*>(ctx->ws_splitk.p),
+        HIP_TRY(ctx, launch_dz_colsum(dZ32, Fo, nullptr, 0, SAGA_ACT_NONE, nullptr, n, Fo, static_cast<float*>(ctx->ws_splitk.p),
                                       static_cast<float*>(grads->dbias->data), 0, s));
     }
     if ((st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ32, Fo, Fo, n, static_cast<float*>(grads->dW->data),
@@ -652,7 +682,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
                                         const saga_vertex_params* vp, const saga_layer_grads* grads)
 {
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
-    const bool relu = vp->act == SAGA_ACT_RELU;
+    const bool use_y = vp->act != SAGA_ACT_NONE;  // the activation's derivative is taken from the layer's output
     hipStream_t s = ctx->stream;
     saga_status st;
     const int64_t t_auto = std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)std::max(F, Fo)));
@@ -671,7 +701,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     }
     if ((st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F))) return st;   // A tile
     if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(float) * (size_t)T * Fo))) return st;   // dY tile
-    if (relu) {
+    if (use_y) {
         if ((st = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)T * Fo))) return st;  // Y tile
         if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)T * Fo))) return st;     // dZ tile
     }
@@ -680,7 +710,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     float* tA = static_cast<float*>(ctx->ws_accum.p);
     float* tdY = static_cast<float*>(ctx->ws_grad.p);
     float* tY = static_cast<float*>(ctx->ws_hoist.p);
-    float* tdZ = relu ? static_cast<float*>(ctx->ws_dz.p) : tdY;
+    float* tdZ = use_y ? static_cast<float*>(ctx->ws_dz.p) : tdY;
     int64_t h2d = 0, d2h = 0;
     auto rows_at = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
     for (int64_t r0 = 0; r0 < std::max<int64_t>(n, 1); r0 += T) {
@@ -692,14 +722,14 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
             HIP_TRY(ctx, hipMemcpy2DAsync(tdY, sizeof(float) * (size_t)Fo, rows_at(dY, r0), sizeof(float) * (size_t)dY->ld,
                                           sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, s));
             h2d += rows * (int64_t)(F + Fo) * 4;
-            if (relu) {
+            if (use_y) {
                 HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_at(Y, r0), sizeof(float) * (size_t)Y->ld,
                                               sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, s));
                 h2d += rows * (int64_t)Fo * 4;
             }
         }
-        if (relu || grads->dbias)
-            HIP_TRY(ctx, launch_dz_colsum(tdY, Fo, relu ? tY : nullptr, Fo, tdZ, rows, Fo,
+        if (use_y || grads->dbias)
+            HIP_TRY(ctx, launch_dz_colsum(tdY, Fo, use_y ? tY : nullptr, Fo, vp->act, tdZ, rows, Fo,
                                           grads->dbias ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
                                           grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, acc, s));
         if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
@@ -715,7 +745,7 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
-    const bool relu = vp->act == SAGA_ACT_RELU;
+    const bool use_y = vp->act != SAGA_ACT_NONE;  // the activation's derivative is taken from the layer's output
     hipStream_t s = ctx->stream;
     saga_status st;
 
@@ -739,22 +769,22 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     if ((st = ensure_transposed_host(ctx, g))) return st;
     bool any_done = false;
     VertexFeed feed;
-    feed.bytes_per_row = sizeof(float) * ((size_t)F + (relu ? (size_t)Fo : 0));
+    feed.bytes_per_row = sizeof(float) * ((size_t)F + (use_y ? (size_t)Fo : 0));
     feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool first_visit, int64_t* h2d) -> saga_status {
         auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
         HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)Fo, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
                                       sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
         *h2d += rows * (int64_t)Fo * 4;
         const bool sums = first_visit && grads->dbias;
-        if (relu) {
+        if (use_y) {
             if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fo)) return e;  // grows once: intervals do not grow
             float* tY = static_cast<float*>(ctx->ws_hoist.p);
             HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_of_t(Y, row0), sizeof(float) * (size_t)Y->ld,
                                           sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
             *h2d += rows * (int64_t)Fo * 4;
         }
-        if (relu || sums)   // in place: every element is read and written by one thread
-            HIP_TRY(ctx, launch_dz_colsum(dst, Fo, relu ? static_cast<const float*>(ctx->ws_hoist.p) : nullptr, Fo, dst, rows, Fo,
+        if (use_y || sums)   // in place: every element is read and written by one thread
+            HIP_TRY(ctx, launch_dz_colsum(dst, Fo, use_y ? static_cast<const float*>(ctx->ws_hoist.p) : nullptr, Fo, vp->act, dst, rows, Fo,
                                           sums ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
                                           sums ? static_cast<float*>(grads->dbias->data) : nullptr, any_done ? 1 : 0, on));
         if (first_visit) {

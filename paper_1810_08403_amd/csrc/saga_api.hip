@@ -1104,8 +1104,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         auto f32_at = [](const saga_tensor* t, int32_t mem) { return tensor_ok(t) && t->mem == mem && t->dtype == SAGA_F32; };
         if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
             return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
-        if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
+        if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
         const saga_tensor* W = vp->W;
         if (!W || !f32_at(W, SAGA_MEM_DEVICE) || W->rows > (1 << 20) || W->cols > (1 << 20))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out fp32 tensor");
@@ -1114,8 +1114,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need A as a host n x F_in fp32 tensor");
         if (!f32_at(dY, SAGA_MEM_HOST) || dY->rows != n || dY->cols != Fo)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need dY as a host n x F_out fp32 tensor");
-        if (vp->act == SAGA_ACT_RELU && (!Y || !f32_at(Y, SAGA_MEM_HOST) || Y->rows != n || Y->cols != Fo))
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a host n x F_out fp32 tensor");
+        if (vp->act != SAGA_ACT_NONE && (!Y || !f32_at(Y, SAGA_MEM_HOST) || Y->rows != n || Y->cols != Fo))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "an activation needs Y as a host n x F_out fp32 tensor");
         if (!grads->dW || !f32_at(grads->dW, SAGA_MEM_DEVICE) || grads->dW->rows != F || grads->dW->cols != Fo)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
         if (grads->dbias && (!f32_at(grads->dbias, SAGA_MEM_DEVICE) || grads->dbias->rows * grads->dbias->cols != Fo))
@@ -1133,8 +1133,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
     if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
     if (gated && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
-    if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU)
-        return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers activations NONE and RELU only");
+    if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
     auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };
     const saga_tensor* W = vp->W;
     if (!W) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass needs an ApplyVertex product (vp->W)");
@@ -1143,6 +1143,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         auto dev_bf16 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_BF16; };
         if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
             return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
+        if (vp->act == SAGA_ACT_SIGMOID)  // a derivative y (1 - y) from an 8-bit y is not worth having
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers activations NONE and RELU only");
         if (!dev_bf16(W) || W->rows > (1 << 20) || W->cols > (1 << 20)) return ctx->fail(SAGA_ERR_INVALID_ARG, "malformed W");
         const int64_t n = g->n, F = W->rows, Fo = W->cols;
         if (!dev_f32(A) || A->rows != n || A->cols != F) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x F_in fp32 tensor");
@@ -1185,14 +1187,12 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (!dev_f32(A) || A->rows != n || A->cols != Fm) return ctx->fail(SAGA_ERR_INVALID_ARG, "A must be a device n x Fm fp32 tensor");
     if (!dev_f32(dY) || dY->rows != n || dY->cols != Fo)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "dY must be a device n x F_out fp32 tensor");
-    if (vp->act == SAGA_ACT_RELU && (!Y || !dev_f32(Y) || Y->rows != n || Y->cols != Fo))
-        return ctx->fail(SAGA_ERR_INVALID_ARG, "RELU needs Y as a device n x F_out fp32 tensor");
+    if (vp->act != SAGA_ACT_NONE && (!Y || !dev_f32(Y) || Y->rows != n || Y->cols != Fo))
+        return ctx->fail(SAGA_ERR_INVALID_ARG, "an activation needs Y as a device n x F_out fp32 tensor");
     const bool needs_x = vp->W_self || gated || pool || agg == SAGA_AGG_MAX;
     if (needs_x && (!X || !dev_f32(X) || X->rows != n || X->cols != F))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer needs X as a device n x F fp32 tensor");
     if (vp->W_self) {
-        if (gated || pool || agg == SAGA_AGG_MAX)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass covers W_self only with sum over COPY / MUL_WEIGHT messages");
         if (!dev_f32(vp->W_self) || vp->W_self->rows != F || vp->W_self->cols != Fo)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out fp32 tensor");
         if (!grads->dW_self) return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self is given but grads->dW_self is not");

@@ -66,14 +66,11 @@ def _run_backward(ctx, graph, wl, A, Y, dY, act, bias, with_self, attach=False, 
 
 def _check(res, bwd, dY, X, with_self, what):
     assert_sum_close(res["dW"], bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
-    # dbias and dW_self: sums of n terms each; scale by the absolute-term sums written out here
-    dZ_abs_colsum = np.abs(dY.numpy().astype(np.float64)).sum(0)
-    assert_sum_close(res["dbias"], bwd["dbias"], np.maximum(dZ_abs_colsum, 1e-30), TOL_F32, what + " dbias")
+    assert_sum_close(res["dbias"], bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
     if "dX" in res:
         assert_sum_close(res["dX"], bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
     if with_self:
-        scale = np.abs(X.numpy().astype(np.float64)).T @ np.abs(dY.numpy().astype(np.float64))
-        assert_sum_close(res["dW_self"], bwd["dW_self"], np.maximum(scale, 1e-30), TOL_F32, what + " dW_self")
+        assert_sum_close(res["dW_self"], bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self")
 
 
 CASES = [
@@ -86,6 +83,8 @@ CASES = [
     (20, 7, "copy", "relu", True, True),          # nothing aligned
     (7, 20, "mul_weight", "relu", True, False),
     (256, 256, "mul_weight", "relu", False, False),
+    (64, 48, "mul_weight", "sigmoid", True, True),   # the derivative y (1 - y) from the stored output
+    (20, 33, "copy", "sigmoid", False, False),
 ]
 
 
@@ -157,12 +156,12 @@ def test_backward_rejects_what_it_does_not_cover(ctx):
     with pytest.raises(saga.SagaError) as e:                      # max over gated messages
         ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", edge_op="gated")
     assert e.value.status == 3
-    with pytest.raises(saga.SagaError) as e:
+    with pytest.raises(saga.SagaError) as e:                      # an activation without Y
         ctx.layer_backward(graph, A, dY, W, dW, act="sigmoid")
-    assert e.value.status == 3
-    with pytest.raises(saga.SagaError) as e:                      # W_self with the max accumulator
-        ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", W_self=W, dW_self=torch.zeros_like(dW))
-    assert e.value.status == 3
+    assert e.value.status == 1
+    with pytest.raises(saga.SagaError) as e:                      # W_self without dW_self
+        ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", W_self=W)
+    assert e.value.status == 1
     with pytest.raises(saga.SagaError) as e:                      # max needs X
         ctx.layer_backward(graph, A, dY, W, dW, agg="max")
     assert e.value.status == 1
@@ -261,7 +260,7 @@ def test_backward_config3_shape_full_size_fp32():
 # gated layers (Example 2.1 / Figure 2)
 # --------------------------------------------------------------------------
 
-def _gated_backward_gpu(ctx, graph, wl, A, Y, dY, act, bias, with_b, with_msg, want_dx=True):
+def _gated_backward_gpu(ctx, graph, wl, A, Y, dY, act, bias, with_b, with_msg, want_dx=True, W_self=None):
     dev = "cuda"
     n, F = wl.X.shape
     Fo = wl.W.shape[1]
@@ -269,12 +268,16 @@ def _gated_backward_gpu(ctx, graph, wl, A, Y, dY, act, bias, with_b, with_msg, w
     f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev)
     dW, dX, db = nan(F, Fo), (nan(n, F) if want_dx else None), nan(Fo)
     dWg, dbg, dWm = nan(F, 2 * F), (nan(F) if with_b else None), (nan(F, F) if with_msg else None)
+    dWs = nan(F, Fo) if W_self is not None else None
     ctx.layer_backward(graph, f32(A), f32(dY), wl.W.to(dev), dW, X=wl.X.to(dev), Y=f32(Y), edge_op="gated", act=act,
                        bias=None if bias is None else bias.to(dev), dX=dX, dbias=db,
                        W_gate=wl.W_gate.to(dev), b_gate=wl.b_gate.to(dev) if with_b else None,
-                       W_msg=wl.W_msg.to(dev) if with_msg else None, dW_gate=dWg, db_gate=dbg, dW_msg=dWm)
+                       W_msg=wl.W_msg.to(dev) if with_msg else None, dW_gate=dWg, db_gate=dbg, dW_msg=dWm,
+                       W_self=None if W_self is None else W_self.to(dev), dW_self=dWs)
     torch.cuda.synchronize()
     res = {"dW": dW, "dbias": db, "dW_gate": dWg}
+    if W_self is not None:
+        res["dW_self"] = dWs
     if want_dx:
         res["dX"] = dX
     if with_b:
@@ -284,36 +287,43 @@ def _gated_backward_gpu(ctx, graph, wl, A, Y, dY, act, bias, with_b, with_msg, w
     return {k: v.cpu().numpy() for k, v in res.items()}
 
 
-@pytest.mark.parametrize("F,Fo,act,with_b,with_msg", [
-    (8, 8, "relu", True, True),
-    (64, 32, "relu", True, True),
-    (128, 128, "none", True, True),       # configuration 4's widths
-    (260, 16, "relu", False, True),       # wide kernel, two fragments per lane
-    (20, 12, "relu", True, False),        # Example 2.1 exactly plus a bias: identity message matrix
-    (7, 5, "none", False, False),         # nothing aligned
+@pytest.mark.parametrize("F,Fo,act,with_b,with_msg,with_self", [
+    (8, 8, "relu", True, True, False),
+    (64, 32, "relu", True, True, False),
+    (128, 128, "none", True, True, False),       # configuration 4's widths
+    (260, 16, "relu", False, True, False),       # wide kernel, two fragments per lane
+    (20, 12, "relu", True, False, False),        # Example 2.1 exactly plus a bias: identity message matrix
+    (7, 5, "none", False, False, False),         # nothing aligned
+    (64, 48, "sigmoid", True, True, True),       # sigmoid activation and the vertex's own product
+    (20, 12, "relu", True, False, True),
 ])
-def test_gated_backward_matches_oracle(ctx, F, Fo, act, with_b, with_msg):
+def test_gated_backward_matches_oracle(ctx, F, Fo, act, with_b, with_msg, with_self):
     wl = si.workload(4, scale=10, f_in=F, f_out=Fo)
     g = wl.graph
     n = g.n
     cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
     bias = si.uniform_pm(Fo, 0.3, 5)
     dY = si.normal_features(n, Fo, 99)
-    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy() if with_b else None, W_msg=wl.W_msg.numpy() if with_msg else None)
+    Ws = si.glorot_uniform(F, Fo, 41) if with_self else None
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy() if with_b else None, W_msg=wl.W_msg.numpy() if with_msg else None,
+               W_self=None if Ws is None else Ws.numpy())
     fwd = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
     bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
     graph = make_graph(ctx, g)
-    res = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg)
+    res = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg, W_self=Ws)
     what = f"gated {F}->{Fo} {act}"
     assert_sum_close(res["dW"], bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
     assert_sum_close(res["dX"], bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    assert_sum_close(res["dbias"], bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
+    if with_self:
+        assert_sum_close(res["dW_self"], bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self")
     assert_sum_close(res["dW_gate"], bwd["dW_gate"], bwd["dW_gate_abs"], TOL_F32, what + " dW_gate")
     if with_b:
         assert_sum_close(res["db_gate"], bwd["db_gate"], bwd["db_gate_abs"], TOL_F32, what + " db_gate")
     if with_msg:
         assert_sum_close(res["dW_msg"], bwd["dW_msg"], bwd["dW_msg_abs"], TOL_F32, what + " dW_msg")
     # without dX the parameter gradients are the same bits
-    res2 = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg, want_dx=False)
+    res2 = _gated_backward_gpu(ctx, graph, wl, fwd["A"], fwd["Y"], dY, act, bias, with_b, with_msg, want_dx=False, W_self=Ws)
     assert np.array_equal(res2["dW_gate"], res["dW_gate"]) and np.array_equal(res2["dW"], res["dW"])
     graph.destroy()
 
@@ -328,9 +338,9 @@ def test_gated_backward_rejects_what_it_does_not_cover(ctx):
     with pytest.raises(saga.SagaError) as e:                      # dW_msg without W_msg
         ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), dW_msg=z(F, F), **kw)
     assert e.value.status == 1
-    with pytest.raises(saga.SagaError) as e:                      # W_self is not covered
-        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), W_self=z(F, 16), dW_self=z(F, 16), **kw)
-    assert e.value.status == 3
+    with pytest.raises(saga.SagaError) as e:                      # W_self of the wrong shape
+        ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), W_self=z(F, 15), dW_self=z(F, 15), **kw)
+    assert e.value.status == 1
     with pytest.raises(saga.SagaError) as e:                      # gate gradients on a linear layer
         ctx.layer_backward(graph, z(n, F), z(n, 16), wl.W.cuda(), z(F, 16), dW_gate=z(F, 2 * F))
     assert e.value.status == 1
@@ -377,11 +387,12 @@ def _quantised_pool_workload(scale, f_in, f_pool, f_out):
     return wl
 
 
-@pytest.mark.parametrize("edge_op,F,Fo,act", [("copy", 64, 32, "relu"), ("mul_weight", 96, 128, "none"), ("copy", 7, 5, "relu"),
-                                               ("mul_weight", 260, 16, "relu")])
-def test_max_backward_matches_oracle(ctx, edge_op, F, Fo, act):
+@pytest.mark.parametrize("edge_op,F,Fo,act,with_self", [("copy", 64, 32, "relu", False), ("mul_weight", 96, 128, "none", False),
+                                                         ("copy", 7, 5, "relu", False), ("mul_weight", 260, 16, "relu", False),
+                                                         ("mul_weight", 64, 48, "sigmoid", True), ("copy", 20, 12, "relu", True)])
+def test_max_backward_matches_oracle(ctx, edge_op, F, Fo, act, with_self):
     wl = si.commnet_workload(scale=11, f_in=F, f_out=Fo)
-    wl.W_self = None
+    Ws = wl.W_self if with_self else None
     g = wl.graph
     n = g.n
     cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
@@ -391,6 +402,8 @@ def test_max_backward_matches_oracle(ctx, edge_op, F, Fo, act):
     bias = si.uniform_pm(Fo, 0.3, 5)
     dY = si.normal_features(n, Fo, 99)
     kw = dict(edge_weight=w.numpy()) if w is not None else {}
+    if with_self:
+        kw["W_self"] = Ws.numpy()
     fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op, agg="max", W=wl.W.numpy(), bias=bias.numpy(), act=act, **kw)
     bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), edge_op, bias=bias.numpy(), act=act, **kw)
     graph = make_graph(ctx, g)
@@ -398,14 +411,20 @@ def test_max_backward_matches_oracle(ctx, edge_op, F, Fo, act):
     f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev)
     dX, dW, db = (torch.full((n, F), float("nan"), device=dev), torch.full((F, Fo), float("nan"), device=dev),
                   torch.full((Fo,), float("nan"), device=dev))
+    dWs = torch.full((F, Fo), float("nan"), device=dev) if with_self else None
     ctx.layer_backward(graph, f32(bwd["A"]), dY.to(dev), wl.W.to(dev), dW, X=wl.X.to(dev), Y=f32(fwd["Y"]), edge_op=edge_op, agg="max",
-                       edge_weight=None if w is None else w.to(dev), bias=bias.to(dev), act=act, dX=dX, dbias=db)
+                       edge_weight=None if w is None else w.to(dev), bias=bias.to(dev), act=act, dX=dX, dbias=db,
+                       W_self=Ws.to(dev) if with_self else None, dW_self=dWs)
     torch.cuda.synchronize()
     what = f"max {edge_op} {F}->{Fo}"
     assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
     assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
-    # every source that never supplies a maximum gets exactly zero
-    assert ((bwd["dX_abs"] == 0) <= (dX.cpu().numpy() == 0)).all()
+    assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
+    if with_self:
+        assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self")
+    else:
+        # every source that never supplies a maximum gets exactly zero
+        assert ((bwd["dX_abs"] == 0) <= (dX.cpu().numpy() == 0)).all()
     graph.destroy()
 
 
@@ -447,6 +466,33 @@ def test_pool_backward_matches_oracle(ctx, agg, f_in, f_pool, f_out):
         for name, got, ref in [("dW", dW, Wt.grad), ("dX", dX, Xt.grad), ("dW_pool", dWp, Wpt.grad), ("db_pool", dbp, bpt.grad)]:
             err = (got.cpu().double() - ref).abs().max().item()
             assert err <= 2e-5 * ref.abs().max().item(), (name, err)
+    graph.destroy()
+
+
+def test_pool_backward_with_own_product_and_sigmoid_activation(ctx):
+    """Max over pooled messages with ApplyVertex = sigmoid(A W + X W_self + bias): the vertex's own partial gradient joins
+    dX inside the last product, and the activation's derivative comes from the stored output."""
+    f_in, f_pool, f_out = 16, 32, 24
+    wl = _quantised_pool_workload(11, f_in, f_pool, f_out)
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    dY = si.normal_features(n, f_out, 7)
+    Ws, bias = si.glorot_uniform(f_in, f_out, 43), si.uniform_pm(f_out, 0.3, 5)
+    dev = "cuda"
+    graph = make_graph(ctx, g)
+    Xd, Wd, Wp, bp = wl.X.to(dev), wl.W.to(dev), wl.W_pool.to(dev), wl.b_pool.to(dev)
+    Y, A = torch.empty(n, f_out, device=dev), torch.empty(n, f_pool, device=dev)
+    kw = dict(edge_op="pool", agg="max", W_pool=Wp, b_pool=bp, W_self=Ws.to(dev), bias=bias.to(dev), act="sigmoid")
+    ctx.layer_forward(graph, Xd, Y, W=Wd, accum_out=A, **kw)
+    nan = lambda *s: torch.full(s, float("nan"), device=dev)
+    dX, dW, db, dWp, dbp, dWs = nan(n, f_in), nan(f_pool, f_out), nan(f_out), nan(f_pool, f_in), nan(f_pool), nan(f_in, f_out)
+    ctx.layer_backward(graph, A, dY.to(dev), Wd, dW, X=Xd, Y=Y, dX=dX, dbias=db, dW_pool=dWp, db_pool=dbp, dW_self=dWs, **kw)
+    torch.cuda.synchronize()
+    bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), "pool", W_pool=wl.W_pool.numpy(), b_pool=wl.b_pool.numpy(),
+                              bias=bias.numpy(), act="sigmoid", W_self=Ws.numpy())
+    for name, got in [("dW", dW), ("dX", dX), ("dW_pool", dWp), ("db_pool", dbp), ("dW_self", dWs), ("dbias", db)]:
+        assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, f"pool max with W_self, sigmoid: {name}")
     graph.destroy()
 
 
