@@ -101,7 +101,7 @@ def test_random_linear_backward_case(seed):
     rng, g, F, Fo, op, agg, act, dtype = _case(500 + seed)
     n = g.n
     op = "mul_weight" if seed % 2 else "copy"
-    act = "relu" if seed % 3 else "none"
+    act = ["none", "relu", "relu", "sigmoid", "relu"][seed % 5]
     t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
     X, W, Ws, bias, dY = t(n, F), t(F, Fo, s=0.3), (t(F, Fo, s=0.3) if seed % 4 == 0 else None), t(Fo, s=0.2), t(n, Fo)
     w = t(g.nnz) if op == "mul_weight" else None
@@ -122,10 +122,9 @@ def test_random_linear_backward_case(seed):
         what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} self={Ws is not None}"
         assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
         assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
         if Ws is not None:
-            dz = dY.numpy().astype(np.float64) * ((fwd["Y"] > 0) if act == "relu" else 1.0)
-            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(np.abs(X.numpy().astype(np.float64)).T @ np.abs(dz), 1e-30),
-                             TOL_F32, what + " dW_self")
+            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self")
         graph.destroy()
 
 
@@ -134,38 +133,46 @@ def test_random_gated_and_max_backward_case(seed):
     rng, g, F, Fo, _, _, _, _ = _case(900 + seed)
     F = min(F, 132)
     n = g.n
-    act = "relu" if seed % 2 else "none"
+    act = ["none", "relu", "sigmoid", "relu"][seed % 4]
     t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
     X, W, dY = t(n, F), t(F, Fo, s=0.3), t(n, Fo)
+    Ws = t(F, Fo, s=0.3) if seed % 5 < 2 else None             # the vertex's own product, in some cases
+    Wsn, Wsd = (None, None) if Ws is None else (Ws.numpy(), Ws.cuda())
     cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
     f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda()
     nan = lambda *s: torch.full(s, float("nan"), device="cuda")
     with new_context() as c:
         graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
-        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {act}"
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {act} self={Ws is not None}"
+        dWs = nan(F, Fo) if Ws is not None else None
         if seed % 3 != 2:                                        # gated, with and without the message matrix
             Wg, bg, Wm = t(F, 2 * F, s=0.3), t(F, s=0.2), (t(F, F, s=0.3) if seed % 3 == 0 else None)
             okw = dict(W_gate=Wg.numpy(), b_gate=bg.numpy(), W_msg=None if Wm is None else Wm.numpy())
-            fwd = oracle.layer(cp, ri, X.numpy(), "gated", W=W.numpy(), act=act, **okw)
-            bwd = oracle.gated_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), act=act, **okw)
+            fwd = oracle.layer(cp, ri, X.numpy(), "gated", W=W.numpy(), act=act, W_self=Wsn, **okw)
+            bwd = oracle.gated_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), act=act, W_self=Wsn, **okw)
             dX, dW, dWg, dbg = nan(n, F), nan(F, Fo), nan(F, 2 * F), nan(F)
             dWm = nan(F, F) if Wm is not None else None
             c.layer_backward(graph, f32(fwd["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(fwd["Y"]), edge_op="gated", act=act, dX=dX,
-                             W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=None if Wm is None else Wm.cuda(), dW_gate=dWg, db_gate=dbg, dW_msg=dWm)
+                             W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=None if Wm is None else Wm.cuda(), dW_gate=dWg, db_gate=dbg, dW_msg=dWm,
+                             W_self=Wsd, dW_self=dWs)
             torch.cuda.synchronize()
             got = {"dX": dX, "dW": dW, "dW_gate": dWg, "db_gate": dbg}
             if Wm is not None:
                 got["dW_msg"] = dWm
+            if Ws is not None:
+                got["dW_self"] = dWs
             for name, v in got.items():
-                assert_sum_close(v.cpu().numpy(), bwd[name], bwd[name + "_abs"], TOL_F32, what + " gated " + name)
+                assert_sum_close(v.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " gated " + name)
         else:                                                    # max over weighted messages
             w = t(g.nnz)
-            fwd = oracle.layer(cp, ri, X.numpy(), "mul_weight", w.numpy(), agg="max", W=W.numpy(), act=act)
-            bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), "mul_weight", edge_weight=w.numpy(), act=act)
+            fwd = oracle.layer(cp, ri, X.numpy(), "mul_weight", w.numpy(), agg="max", W=W.numpy(), act=act, W_self=Wsn)
+            bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), "mul_weight", edge_weight=w.numpy(), act=act, W_self=Wsn)
             dX, dW = nan(n, F), nan(F, Fo)
             c.layer_backward(graph, f32(bwd["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(fwd["Y"]), edge_op="mul_weight", agg="max",
-                             edge_weight=w.cuda(), act=act, dX=dX)
+                             edge_weight=w.cuda(), act=act, dX=dX, W_self=Wsd, dW_self=dWs)
             torch.cuda.synchronize()
             assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " max dW")
             assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " max dX")
+            if Ws is not None:
+                assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " max dW_self")
         graph.destroy()
