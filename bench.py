@@ -230,6 +230,11 @@ def main():
         "gather_gflops": round(2.0 * nnz * f_in / (ms_gather * 1e-3) / 1e9, 1) if ms_gather > 0 else None,
         "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3)},
     }
+    if out["roofline"]["traffic"] and ms_gather > 0:
+        # the measured bytes below the L2 per launch over the launch time measured here: the "achieved HBM GB/s vs peak" figure
+        tr_gbps = out["roofline"]["traffic"] / (ms_gather * 1e-3) / 1e9
+        out["roofline"]["traffic_GBps"] = round(tr_gbps, 1)
+        out["roofline"]["traffic_frac"] = round(tr_gbps / HBM_PEAK_GBPS, 4)
     copy_gbps = device_copy_ceiling(ctx, torch)
     out["roofline"]["measured_copy_ceiling"] = {"GBps": round(copy_gbps, 1), "frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
                                                 "kernel": "k_copy_u128, 1 GiB read + 1 GiB written"}
