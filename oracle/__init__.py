@@ -95,6 +95,8 @@ def lib():
         L.saga_oracle_max_backward.argtypes = [ctypes.POINTER(_MBwdArgs)]
         L.saga_oracle_gated_backward.restype = ctypes.c_int
         L.saga_oracle_gated_backward.argtypes = [ctypes.POINTER(_GBwdArgs)]
+        L.saga_oracle_gated_backward_sample.restype = ctypes.c_int
+        L.saga_oracle_gated_backward_sample.argtypes = [ctypes.POINTER(_GBwdArgs), _I64, _P, _P, _P]
         L.saga_oracle_backward_sample.restype = ctypes.c_int
         L.saga_oracle_backward_sample.argtypes = [ctypes.POINTER(_BwdArgs), _I64, _P, _P, _P, _I64, _P, _P, _P, _P]
         _lib = L
@@ -306,6 +308,27 @@ def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=Non
     rc = lib().saga_oracle_gated_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_gated_backward rejected its arguments")
+    return out
+
+
+def gated_backward_sample(col_ptr, row_idx, X, dZ, W, W_gate, ulist, b_gate=None, W_msg=None):
+    """gated_backward's definitions (no activation: dZ is given) evaluated only for the rows dX[ulist], from the in- and
+    out-edges of those vertices, for graphs too large to do whole. Returns dict dX, dX_abs (len(ulist) x F)."""
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    Xv, Wv, dZv, Wg = _f32(X), _f32(W), _f32(dZ), _f32(W_gate)
+    n, F = Xv.shape
+    F_out = Wv.shape[1]
+    assert Wv.shape == (F, F_out) and dZv.shape == (n, F_out) and Wg.shape == (F, 2 * F)
+    bg, Wm = _f32(b_gate), _f32(W_msg)
+    ul = np.ascontiguousarray(np.asarray(ulist, dtype=np.int64))
+    assert len(set(ul.tolist())) == len(ul)
+    out = {"dX": np.zeros((len(ul), F)), "dX_abs": np.zeros((len(ul), F))}
+    a = _GBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, _ptr(Wg), _ptr(bg), _ptr(Wm), None, _ptr(Wv), None,
+                  F_out, ACTS["none"], 0, _ptr(dZv), *([None] * 11), None, None, None, None)
+    rc = lib().saga_oracle_gated_backward_sample(ctypes.byref(a), len(ul), _ptr(ul), _ptr(out["dX"]), _ptr(out["dX_abs"]))
+    if rc != 0:
+        raise ValueError("saga_oracle_gated_backward_sample rejected its arguments")
     return out
 
 

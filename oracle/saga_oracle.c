@@ -24,7 +24,8 @@
  *   - hoisting of vertex-only products out of ApplyEdge: Section 3.2;
  *   - the backward stages (backward-ApplyVertex, -Gather, -ApplyEdge, -Scatter,
  *     Section 2.2) as the chain rule of the forward definitions: linear layers
- *     (whole graph and sampled), the gated layer, the max accumulator with
+ *     (whole graph and sampled), the gated layer (whole graph, and sampled
+ *     rows of the input gradient), the max accumulator with
  *     COPY / MUL_WEIGHT / max-pooling messages (further down in this file).
  *
  * Every function is pinned by tests/test_oracle_pins.py against something
@@ -868,6 +869,150 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
         p->db_gate_abs[f] = sa;
     }
     free(buf);
+    return 0;
+}
+
+/*
+ * The gated backward definitions evaluated only for the rows dX[ulist] (n_u distinct vertices), for graphs
+ * too large to do whole. A sampled vertex u needs dPs[u], dM[u] (sums over its out-edges) and dPd[u] (a sum
+ * over its in-edges), hence the per-vertex products of u and of its neighbours only; those are formed here
+ * exactly as in the whole-graph form. No activation and no W_self: p->dY is taken as dZ (p->act must be
+ * ACT_NONE, p->A and the parameter-gradient outputs are not used). Outputs n_u x F.
+ */
+int saga_oracle_gated_backward_sample(const saga_oracle_gbwd_args* p, int64_t n_u, const int64_t* ulist, double* dX_rows,
+                                      double* dX_rows_abs)
+{
+    if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (p->act != ACT_NONE || p->W_self || n_u < 0 || (n_u > 0 && (!ulist || !dX_rows || !dX_rows_abs))) return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out, nnz = p->col_ptr[n];
+    if (n_u == 0) return 0;
+    /* the edges grouped by source */
+    int64_t* optr = (int64_t*)calloc((size_t)n + 2, sizeof(int64_t));
+    int32_t* odst = (int32_t*)malloc(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1));
+    int64_t* as_src = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));  /* compact row of a vertex whose Ps, M are needed */
+    int64_t* as_dst = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));  /* ... whose Pd, dA are needed */
+    if (!optr || !odst || !as_src || !as_dst) { free(optr); free(odst); free(as_src); free(as_dst); return 2; }
+    for (int64_t e = 0; e < nnz; ++e) optr[p->row_idx[e] + 2]++;
+    for (int64_t u = 0; u < n; ++u) optr[u + 2] += optr[u + 1];
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) odst[optr[p->row_idx[e] + 1]++] = (int32_t)v;
+    /* now optr[u] .. optr[u + 1] are u's out-edges */
+    for (int64_t v = 0; v < n; ++v) as_src[v] = as_dst[v] = -1;
+    int64_t ns = 0, nd = 0;
+    for (int64_t i = 0; i < n_u; ++i) {
+        const int64_t u = ulist[i];
+        if (u < 0 || u >= n) { free(optr); free(odst); free(as_src); free(as_dst); return 1; }
+        if (as_src[u] < 0) as_src[u] = ns++;
+        if (as_dst[u] < 0) as_dst[u] = nd++;
+        for (int64_t e = p->col_ptr[u]; e < p->col_ptr[u + 1]; ++e)
+            if (as_src[p->row_idx[e]] < 0) as_src[p->row_idx[e]] = ns++;
+        for (int64_t e = optr[u]; e < optr[u + 1]; ++e)
+            if (as_dst[odst[e]] < 0) as_dst[odst[e]] = nd++;
+    }
+    double* buf = (double*)calloc(4 * (size_t)ns * (size_t)F + 4 * (size_t)nd * (size_t)F, sizeof(double));
+    if (!buf) { free(optr); free(odst); free(as_src); free(as_dst); return 2; }
+    double *Ps = buf, *Psa = Ps + ns * F, *M = Psa + ns * F, *Ma = M + ns * F;
+    double *Pd = Ma + ns * F, *Pda = Pd + nd * F, *dA = Pda + nd * F, *dAa = dA + nd * F;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n; ++v) {
+        const float* x = p->X + v * F;
+        if (as_src[v] >= 0) {
+            const int64_t r = as_src[v];
+            for (int64_t f = 0; f < F; ++f) {
+                const float* wg = p->W_gate + f * 2 * F;
+                double s = 0.0, sa = 0.0, t = (double)x[f], ta = fabs((double)x[f]);
+                for (int64_t k = 0; k < F; ++k) {
+                    s += (double)wg[k] * (double)x[k];
+                    sa += fabs((double)wg[k] * (double)x[k]);
+                }
+                if (p->W_msg) {
+                    const float* wm = p->W_msg + f * F;
+                    t = 0.0;
+                    ta = 0.0;
+                    for (int64_t k = 0; k < F; ++k) {
+                        t += (double)wm[k] * (double)x[k];
+                        ta += fabs((double)wm[k] * (double)x[k]);
+                    }
+                }
+                Ps[r * F + f] = s;
+                Psa[r * F + f] = sa;
+                M[r * F + f] = t;
+                Ma[r * F + f] = ta;
+            }
+        }
+        if (as_dst[v] >= 0) {
+            const int64_t r = as_dst[v];
+            for (int64_t f = 0; f < F; ++f) {
+                const float* wg = p->W_gate + f * 2 * F + F;
+                double d = 0.0, da = 0.0, g = 0.0, ga = 0.0;
+                for (int64_t k = 0; k < F; ++k) {
+                    d += (double)wg[k] * (double)x[k];
+                    da += fabs((double)wg[k] * (double)x[k]);
+                }
+                for (int64_t o = 0; o < Fo; ++o) {
+                    const double t = (double)p->dY[v * Fo + o] * (double)p->W[f * Fo + o];
+                    g += t;
+                    ga += fabs(t);
+                }
+                Pd[r * F + f] = d;
+                Pda[r * F + f] = da;
+                dA[r * F + f] = g;
+                dAa[r * F + f] = ga;
+            }
+        }
+    }
+    /* per sampled vertex: the three sums of backward-ApplyEdge, then backward-Scatter's products */
+#pragma omp parallel
+    {
+        double* acc = (double*)malloc(sizeof(double) * 6 * (size_t)F);
+        double *dPs = acc, *dPsa = acc + F, *dM = acc + 2 * F, *dMa = acc + 3 * F, *dPd = acc + 4 * F, *dPda = acc + 5 * F;
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t i = 0; i < n_u; ++i) {
+            const int64_t u = ulist[i], us = as_src[u], ud = as_dst[u];
+            for (int64_t k = 0; k < 6 * F; ++k) acc[k] = 0.0;
+            for (int64_t e = optr[u]; e < optr[u + 1]; ++e) {          /* u as the source of u -> v */
+                const int64_t vd = as_dst[odst[e]];
+                for (int64_t f = 0; f < F; ++f) {
+                    const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+                    const double z = Ps[us * F + f] + Pd[vd * F + f] + b, Za = Psa[us * F + f] + Pda[vd * F + f] + fabs(b);
+                    const double g = sigmoid(z), t = M[us * F + f], Ta = Ma[us * F + f];
+                    const double da = dA[vd * F + f], daa = dAa[vd * F + f];
+                    dM[f] += g * da;
+                    dMa[f] += g * (daa + fabs(da) * (1.0 - g) * Za);
+                    dPs[f] += da * t * g * (1.0 - g);
+                    dPsa[f] += g * (1.0 - g) * (daa * fabs(t) + fabs(da) * Ta + fabs(da * t) * fabs(1.0 - 2.0 * g) * Za);
+                }
+            }
+            for (int64_t e = p->col_ptr[u]; e < p->col_ptr[u + 1]; ++e) {  /* u as the destination of w -> u */
+                const int64_t ws = as_src[p->row_idx[e]];
+                for (int64_t f = 0; f < F; ++f) {
+                    const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+                    const double z = Ps[ws * F + f] + Pd[ud * F + f] + b, Za = Psa[ws * F + f] + Pda[ud * F + f] + fabs(b);
+                    const double g = sigmoid(z), t = M[ws * F + f], Ta = Ma[ws * F + f];
+                    const double da = dA[ud * F + f], daa = dAa[ud * F + f];
+                    dPd[f] += da * t * g * (1.0 - g);
+                    dPda[f] += g * (1.0 - g) * (daa * fabs(t) + fabs(da) * Ta + fabs(da * t) * fabs(1.0 - 2.0 * g) * Za);
+                }
+            }
+            for (int64_t k = 0; k < F; ++k) {
+                double s = 0.0, sa = 0.0;
+                for (int64_t f = 0; f < F; ++f) {
+                    const double wgs = (double)p->W_gate[f * 2 * F + k], wgd = (double)p->W_gate[f * 2 * F + F + k];
+                    const double wm = p->W_msg ? (double)p->W_msg[f * F + k] : (f == k ? 1.0 : 0.0);
+                    s += dPs[f] * wgs + dM[f] * wm + dPd[f] * wgd;
+                    sa += dPsa[f] * fabs(wgs) + dMa[f] * fabs(wm) + dPda[f] * fabs(wgd);
+                }
+                dX_rows[i * F + k] = s;
+                dX_rows_abs[i * F + k] = sa;
+            }
+        }
+        free(acc);
+    }
+    free(buf);
+    free(optr);
+    free(odst);
+    free(as_src);
+    free(as_dst);
     return 0;
 }
 

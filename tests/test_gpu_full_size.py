@@ -119,6 +119,53 @@ def test_config4_full_gated():
     ctx.destroy()
 
 
+def test_config4_full_gated_backward():
+    """The gated backward pass at configuration 4's full size with default tunables: rows of dX for sampled vertices (the
+    one with most out-edges, the one with most in-edges, one without out-edges, random ones) from the oracle's sampled
+    form, which needs only those vertices' own edges; the parameter gradients, sums over all million vertices the
+    oracle cannot do in seconds, through what holds at any size: they are the same bits whether or not dX is asked for,
+    and doubling dY doubles every gradient exactly."""
+    import paper_1810_08403_amd as saga
+    wl = si.workload(4, device="cuda")
+    g = wl.graph
+    n, F = wl.X.shape
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    Y = torch.empty(n, 128, device="cuda")
+    A = torch.empty(n, 128, device="cuda")
+    kw = dict(edge_op="gated", W_gate=wl.W_gate, b_gate=wl.b_gate, W_msg=wl.W_msg, act="none")
+    ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
+    dY = si.normal_features(n, 128, 31).cuda()
+    z = lambda *s: torch.full(s, float("nan"), device="cuda")
+    def run(dy, want_dx=True):
+        out = dict(dW=z(F, 128), dX=z(n, F) if want_dx else None, dW_gate=z(F, 2 * F), db_gate=z(F), dW_msg=z(F, F))
+        ctx.layer_backward(graph, A, dy, wl.W, out["dW"], X=wl.X, dX=out["dX"], dW_gate=out["dW_gate"], db_gate=out["db_gate"],
+                           dW_msg=out["dW_msg"], **kw)
+        torch.cuda.synchronize()
+        return out
+    r1 = run(dY)
+    od = torch.bincount(g.row_idx.long(), minlength=n).cpu().numpy()
+    ind = g.in_degree().cpu().numpy()
+    rng = np.random.default_rng(12)
+    picks = set(rng.choice(n, size=60, replace=False).tolist()) | {int(od.argmax()), int(ind.argmax()), 0, n - 1}
+    picks.add(int(np.nonzero(od == 0)[0][0]))
+    ul = np.array(sorted(picks), dtype=np.int64)
+    assert od.max() > 10_000
+    ref = oracle.gated_backward_sample(g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), wl.X.cpu().numpy(), dY.cpu().numpy(),
+                                       wl.W.cpu().numpy(), wl.W_gate.cpu().numpy(), ul, b_gate=wl.b_gate.cpu().numpy(),
+                                       W_msg=wl.W_msg.cpu().numpy())
+    assert_sum_close(r1["dX"][ul].cpu().numpy(), ref["dX"], ref["dX_abs"], TOL_F32, "configuration 4 full size, sampled rows of dX")
+    for name in ("dW", "dW_gate", "db_gate", "dW_msg"):
+        assert torch.isfinite(r1[name]).all() and r1[name].abs().max().item() > 0
+    r2 = run(dY, want_dx=False)
+    r3 = run(dY * 2.0)
+    for name in ("dW", "dW_gate", "db_gate", "dW_msg"):
+        assert torch.equal(r1[name], r2[name]), name
+        assert torch.equal(r3[name], r1[name] * 2.0), name
+    assert torch.equal(r3["dX"], r1["dX"] * 2.0)
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("agg", ["sum", "max"])
 def test_config5_full_streamed_under_16gb(agg):
     import paper_1810_08403_amd as saga

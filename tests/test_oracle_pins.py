@@ -619,6 +619,19 @@ def test_gated_backward_equals_autograd_of_the_dense_form(act, with_self, with_m
         assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name    # a scale bounds its value
 
 
+@pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
+def test_sampled_gated_backward_equals_the_whole_graph_form(with_msg, with_b):
+    g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(seed=6, n=70, m=600, F=5, Fo=4, with_msg=with_msg, with_b=with_b)
+    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act="none")
+    whole = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act="none")
+    od = np.bincount(g.row_idx.numpy(), minlength=g.n)
+    ul = sorted({0, 69, 13, 41, int(od.argmax()), int(od.argmin()), int(np.diff(g.col_ptr.numpy()).argmax())})
+    part = oracle.gated_backward_sample(*_np(g), X, dY, W, Wg, ul, b_gate=bg, W_msg=Wm)
+    assert np.allclose(part["dX"], whole["dX"][ul], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dX_abs"], whole["dX_abs"][ul], rtol=1e-12, atol=1e-13)
+    assert np.abs(whole["dX"][ul]).max() > 0.1
+
+
 def test_gated_backward_matches_finite_differences_of_the_naive_forward_oracle():
     g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(seed=9, n=20, m=90, F=3, Fo=2)
     R = dY.astype(np.float64)
