@@ -166,6 +166,124 @@ def test_config4_full_gated_backward():
     ctx.destroy()
 
 
+def test_config3_full_bf16_backward():
+    """Configuration 3 as configured (bf16, 512 -> 256, ReLU) backwards at full size: sampled rows of dX (bf16 bar) and
+    sampled entries of dW (fp32 products of values exact in fp32: fp32 bar) from the oracle's sampled form."""
+    import paper_1810_08403_amd as saga
+    wl = si.workload(3, device="cuda")
+    g = wl.graph
+    n, F, Fo = g.n, 512, 256
+    cp, ri, w = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), wl.edge_weight.cpu().numpy()
+    bf = torch.bfloat16
+    W16 = wl.W.to(bf)
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    graph.set_edge_data(wl.edge_weight)
+    A = si.round_to_bf16(si.normal_features(n, F, 31, device="cuda")).float()     # a synthetic Gather output, taken as given
+    Y16 = torch.relu(A.double() @ W16.double()).to(bf)
+    dY16 = si.normal_features(n, Fo, 32, device="cuda").to(bf)
+    dX = torch.empty(n, F, device="cuda", dtype=bf)
+    dW, db = torch.empty(F, Fo, device="cuda"), torch.empty(Fo, device="cuda")
+    ctx.layer_backward(graph, A, dY16, W16, dW, Y=Y16, edge_op="mul_weight", act="relu", dX=dX, dbias=db)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    od = torch.bincount(g.row_idx.long(), minlength=n).cpu().numpy()
+    ul = np.array(sorted(set(rng.choice(n, size=10, replace=False).tolist()) | {int(od.argmax()), 0, n - 1}), dtype=np.int64)
+    we = [(0, 0), (511, 255), (17, 200), (300, 5)]
+    # the oracle sees the same bf16-valued dZ: dY masked by the stored bf16 output, handed over as dY without activation
+    dZ = (dY16.float() * (Y16.float() > 0)).cpu().numpy()
+    ref = oracle.backward_sample(cp, ri, None, A.cpu().numpy(), dZ, W16.float().cpu().numpy(), ul, we, "mul_weight", w, act="none",
+                                 want_dbias=True)
+    assert_sum_close(dX[ul].float().cpu().numpy(), ref["dX"], ref["dX_abs"], TOL_BF16, "config 3 bf16 backward dX")
+    got = np.array([dW[f, o].item() for f, o in we])
+    assert_sum_close(got, ref["dW"], ref["dW_abs"], TOL_F32, "config 3 bf16 backward dW")
+    assert_sum_close(db.cpu().numpy(), ref["dbias"], np.maximum(ref["dbias_abs"], 1e-30), TOL_F32, "config 3 bf16 backward dbias")
+    ctx.destroy()
+
+
+def test_commnet_rmat20_forward_and_backward():
+    """The CommNet layer bench.py times (R-MAT 20, 128 -> 128, W_self, ReLU): sampled rows of the layer from the oracle,
+    then sampled rows of dX and entries of dW of its backward pass."""
+    import paper_1810_08403_amd as saga
+    wl = si.commnet_workload(scale=20, edge_factor=16, f_in=128, f_out=128, device="cuda")
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy()
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
+    ctx.layer_forward(graph, wl.X, Y, edge_op="copy", W=wl.W, W_self=wl.W_self, act="relu", accum_out=A)
+    torch.cuda.synchronize()
+    vl = _sample(g, 300, 4)
+    Xh, Wh, Wsh = wl.X.cpu().numpy(), wl.W.cpu().numpy(), wl.W_self.cpu().numpy()
+    r = oracle.layer(cp, ri, Xh, "copy", W=Wh, W_self=Wsh, act="relu", vlist=vl)
+    assert_sum_close(A[vl].cpu().numpy(), r["A"], r["A_abs"], TOL_F32, "CommNet R-MAT 20 Gather")
+    assert_sum_close(Y[vl].cpu().numpy(), r["Y"], r["Y_abs"], TOL_F32, "CommNet R-MAT 20 layer")
+    dY = si.normal_features(n, 128, 77, device="cuda")
+    dX, dW, dWs, db = (torch.empty(n, 128, device="cuda"), torch.empty(128, 128, device="cuda"), torch.empty(128, 128, device="cuda"),
+                       torch.empty(128, device="cuda"))
+    ctx.layer_backward(graph, A, dY, wl.W, dW, X=wl.X, Y=Y, edge_op="copy", W_self=wl.W_self, act="relu", dX=dX, dbias=db, dW_self=dWs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    od = torch.bincount(g.row_idx.long(), minlength=n).cpu().numpy()
+    ul = np.array(sorted(set(rng.choice(n, size=40, replace=False).tolist()) | {int(od.argmax()), 0, n - 1}), dtype=np.int64)
+    we = [(0, 0), (127, 127), (5, 99), (64, 3)]
+    # both sides differentiate the layer the GPU computed: its A and its ReLU decisions (dY masked by Y > 0, no activation)
+    dZ = (dY * (Y > 0)).cpu().numpy()
+    ref = oracle.backward_sample(cp, ri, Xh, A.cpu().numpy(), dZ, Wh, ul, we, "copy", W_self=Wsh, act="none", want_dbias=True)
+    assert_sum_close(dX[ul].cpu().numpy(), ref["dX"], ref["dX_abs"], TOL_F32, "CommNet R-MAT 20 dX")
+    assert_sum_close(np.array([dW[f, o].item() for f, o in we]), ref["dW"], ref["dW_abs"], TOL_F32, "CommNet R-MAT 20 dW")
+    assert_sum_close(db.cpu().numpy(), ref["dbias"], np.maximum(ref["dbias_abs"], 1e-30), TOL_F32, "CommNet R-MAT 20 dbias")
+    # dW_self = X^T dZ against the same product in fp64 on the device
+    dz64 = (dY * (Y > 0)).double()
+    assert_sum_close(dWs.cpu().numpy(), (wl.X.double().T @ dz64).cpu().numpy(), (wl.X.double().abs().T @ dz64.abs()).cpu().numpy(), TOL_F32,
+                     "CommNet R-MAT 20 dW_self")
+    ctx.destroy()
+
+
+def test_mpgcn_rmat20_forward_and_backward_properties():
+    """The max-pooling GCN layer bench.py times (R-MAT 20, 128 -> pool 128 -> 128, max): sampled rows from the oracle
+    (max over sigmoids: the Gather output to the fp32 bar, because the sigmoid is evaluated in fp32), and for the
+    backward pass at this size what holds at any size: the same bits with and without dX, exact doubling, and no
+    gradient for a vertex without out-edges."""
+    import paper_1810_08403_amd as saga
+    wl = si.mpgcn_workload(scale=20, edge_factor=32, f_in=128, f_pool=128, f_out=128, device="cuda")
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy()
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
+    kw = dict(edge_op="pool", agg="max", W_pool=wl.W_pool, b_pool=wl.b_pool, act="relu")
+    ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
+    torch.cuda.synchronize()
+    vl = _sample(g, 300, 6)
+    r = oracle.layer(cp, ri, wl.X.cpu().numpy(), "pool", agg="max", W_pool=wl.W_pool.cpu().numpy(), b_pool=wl.b_pool.cpu().numpy(),
+                     W=wl.W.cpu().numpy(), act="relu", vlist=vl)
+    assert_sum_close(A[vl].cpu().numpy(), r["A"], r["A_abs"], TOL_F32, "MP-GCN R-MAT 20 Gather")
+    assert_sum_close(Y[vl].cpu().numpy(), r["Y"], r["Y_abs"], TOL_F32, "MP-GCN R-MAT 20 layer")
+    dY = si.normal_features(n, 128, 78, device="cuda")
+    z = lambda *s: torch.full(s, float("nan"), device="cuda")
+    def run(dy, want_dx=True):
+        out = dict(dW=z(128, 128), dX=z(n, 128) if want_dx else None, dW_pool=z(128, 128), db_pool=z(128), dbias=z(128))
+        ctx.layer_backward(graph, A, dy, wl.W, out["dW"], X=wl.X, Y=Y, dX=out["dX"], dW_pool=out["dW_pool"], db_pool=out["db_pool"],
+                           dbias=out["dbias"], **kw)
+        torch.cuda.synchronize()
+        return out
+    r1, r2, r3 = run(dY), run(dY, want_dx=False), run(dY * 2.0)
+    for name in ("dW", "dW_pool", "db_pool", "dbias"):
+        assert torch.isfinite(r1[name]).all() and r1[name].abs().max().item() > 0
+        assert torch.equal(r1[name], r2[name]), name
+        assert torch.equal(r3[name], r1[name] * 2.0), name
+    assert torch.equal(r3["dX"], r1["dX"] * 2.0)
+    # dW = A^T dZ and dbias against the same sums in fp64 on the device
+    dz64 = (dY * (Y > 0)).double()
+    assert_sum_close(r1["dW"].cpu().numpy(), (A.double().T @ dz64).cpu().numpy(), (A.double().abs().T @ dz64.abs()).cpu().numpy(), TOL_F32,
+                     "MP-GCN R-MAT 20 dW")
+    assert_sum_close(r1["dbias"].cpu().numpy(), dz64.sum(0).cpu().numpy(), dz64.abs().sum(0).cpu().numpy(), TOL_F32, "MP-GCN R-MAT 20 dbias")
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("agg", ["sum", "max"])
 def test_config5_full_streamed_under_16gb(agg):
     import paper_1810_08403_amd as saga
