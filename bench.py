@@ -354,10 +354,21 @@ def main():
         ts = timed(sample)
         e_s = int(deg[sample].sum())
         out["cpu_baseline"] = {"value": round(e_s / ts / 1e9, 6), "unit": "GTEPS", "cores": oracle.num_threads(),
-                               "kind": "oracle",
+                               "kind": "oracle", "cpu_model": cpu_model(),
                                "sample": f"{len(sample)} random destination vertices ({e_s} in-edges) of the same "
                                          f"graph, full layer incl. ApplyVertex, {ts:.1f} s"}
     print(json.dumps(out))
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def device_copy_ceiling(ctx, torch, reps=10):
