@@ -735,6 +735,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
         if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
         // one stream: the next tile's copies queue behind this tile's kernels
     }
+    HIP_TRY(ctx, hipStreamSynchronize(s));  // a streamed call returns when the host tensors are the caller's again
     ctx->acc.bytes_h2d += h2d;
     ctx->acc.bytes_d2h += d2h;
     return SAGA_OK;

@@ -74,6 +74,15 @@ void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
     delete g;
 }
 
+// After a streamed call that failed half-way: nothing it enqueued may still be reading or writing the caller's host
+// tensors when the error is returned. Errors of the waits themselves are ignored (the call has failed already).
+void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* g)
+{
+    if (g && g->s_in) (void)hipStreamSynchronize(g->s_in);
+    if (ctx->stream) (void)hipStreamSynchronize(ctx->stream);
+    if (g && g->s_out) (void)hipStreamSynchronize(g->s_out);
+}
+
 namespace {
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -1079,7 +1079,9 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
         if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
-        return streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
+        const saga_status sst = streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
+        if (sst != SAGA_OK) chunk_grid_drain(ctx, g->grid);  // host tensors are the caller's again when this returns
+        return sst;
     }
     if (Y->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "resident calls need X, Y and the graph in device memory");
@@ -1127,7 +1129,12 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
-        return streamed_backward(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+        const saga_status sst = streamed_backward(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+        if (sst != SAGA_OK) {  // host tensors are the caller's again when this returns
+            chunk_grid_drain(ctx, g->grid);
+            if (g->tr) chunk_grid_drain(ctx, g->tr->grid);
+        }
+        return sst;
     }
     if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
     const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;

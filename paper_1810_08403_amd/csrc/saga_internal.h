@@ -354,6 +354,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                              int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,
                              const StreamExtras* extras = nullptr);
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
+void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device
 // Xself / ld_self / F_self: the vertices' own rows for vp->W_self (ignored when that is NULL)
