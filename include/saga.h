@@ -253,15 +253,17 @@ typedef struct saga_layer_grads {
  * X and A are required; A must be the accum_out of the forward call on the same inputs, or
  * no message will compare equal.
  *
- * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, no W_self):
- * A, Y, dY and grads->dX are SAGA_MEM_HOST tensors (pinned recommended), W and the parameter
- * gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
+ * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, with or
+ * without W_self): A, Y, dY, grads->dX (and X, read only with W_self) are SAGA_MEM_HOST tensors
+ * (pinned recommended), W, W_self and the parameter gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
  * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
  * (the CSR side of the paper's chunk layout), with dZ as the vertex data and W^T as the
  * ApplyVertex matrix; the transposed chunk grid is built at the first such call. dZ is formed
  * on the way in: a vertex interval's rows of dY (and Y with an activation) are copied to the
  * device and turned into dZ in place, and the first time an interval comes by, its rows of A are copied too and
- * its share of dW and dbias is added (interval by interval in a fixed order). Without
+ * its share of dW and dbias is added (interval by interval in a fixed order; with W_self its
+ * rows of X come too, for dW_self, and the own partial gradient dZ W_self^T is the second operand
+ * pair of the schedule's last product, fed by tiles of dZ formed the same way). Without
  * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Every transfer goes
  * through the context's device budget like in saga_layer_forward.
  *

@@ -678,8 +678,8 @@ static saga_status ensure_transposed_host(saga_ctx* ctx, saga_graph* g)
 
 // Parameter gradients of a streamed layer without the propagation: backward-ApplyVertex over tiles of rows copied in
 // from host memory on the context's stream (dZ, the bias sums, dW += A^T dZ, tile after tile in a fixed order).
-static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
-                                        const saga_vertex_params* vp, const saga_layer_grads* grads)
+static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                        const saga_tensor* dY, const saga_vertex_params* vp, const saga_layer_grads* grads)
 {
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
     const bool use_y = vp->act != SAGA_ACT_NONE;  // the activation's derivative is taken from the layer's output
@@ -690,7 +690,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     if (ctx->budget > 0) {
         // the tiles, the split workspace of the parameter-gradient product (at most 1,024 partial F x F_out matrices, usually
         // far fewer) and the column-sum slabs have to fit beside whatever else the context holds
-        const size_t per_row = sizeof(float) * ((size_t)F + 3 * (size_t)Fo);
+        const size_t per_row = sizeof(float) * ((size_t)F + 3 * (size_t)Fo + (grads->dW_self ? (size_t)F : 0));
         int64_t rps;
         int32_t nsp;
         gemm_tn_plan(T, F, Fo, &rps, &nsp);
@@ -707,6 +707,9 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     }
     if (grads->dbias)
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(T) * Fo))) return st;
+    if (grads->dW_self)
+        if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)T * F))) return st;  // X tile (dW_self = X^T dZ)
+    float* tX = static_cast<float*>(ctx->ws_dh.p);
     float* tA = static_cast<float*>(ctx->ws_accum.p);
     float* tdY = static_cast<float*>(ctx->ws_grad.p);
     float* tY = static_cast<float*>(ctx->ws_hoist.p);
@@ -733,6 +736,15 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
                                           grads->dbias ? static_cast<float*>(ctx->ws_splitk.p) : nullptr,
                                           grads->dbias ? static_cast<float*>(grads->dbias->data) : nullptr, acc, s));
         if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
+        if (grads->dW_self) {
+            if (rows > 0) {
+                HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)F, rows_at(X, r0), sizeof(float) * (size_t)X->ld,
+                                              sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, s));
+                h2d += rows * (int64_t)F * 4;
+            }
+            if ((st = param_grad(ctx, tX, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld, acc)))
+                return st;
+        }
         // one stream: the next tile's copies queue behind this tile's kernels
     }
     HIP_TRY(ctx, hipStreamSynchronize(s));  // a streamed call returns when the host tensors are the caller's again
@@ -741,8 +753,8 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     return SAGA_OK;
 }
 
-saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
-                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
@@ -750,14 +762,23 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     hipStream_t s = ctx->stream;
     saga_status st;
 
-    if (!grads->dX || n == 0) return streamed_param_grads(ctx, n, A, Y, dY, vp, grads);
+    if (!grads->dX || n == 0) return streamed_param_grads(ctx, n, X, A, Y, dY, vp, grads);
+    const bool with_self = vp->W_self != nullptr;
 
     // ---- with dX: one pass. The propagation dX = (T dZ) W^T is the streamed forward schedule run on the edges grouped by
     // source, with dZ as the vertex data and W^T as the ApplyVertex matrix (no bias, no activation). dZ is not read
     // from anywhere: a source interval's rows of dY (and Y, A) are copied in, dZ is formed in place in the interval's
     // buffer, and the first time an interval comes by its share of dW and dbias is added, on the copy-in stream. ----
-    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)F * Fo))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)F * Fo * (with_self ? 2 : 1)))) return st;
     HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, F, Fo, SAGA_F32, ctx->ws_wt.p, F, 0, s));
+    float* wst = static_cast<float*>(ctx->ws_wt.p) + (size_t)F * Fo;  // W_self^T, the second matrix of the backward "ApplyVertex"
+    // tiles of the interval's own dZ for that second product: dY and Y of a tile of rows, turned into dZ
+    const int64_t self_tile = std::min<int64_t>(n, std::max<int64_t>(4096, ((int64_t)64 << 20) / ((int64_t)F * 4)));
+    if (with_self) {
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, F, Fo, SAGA_F32, wst, F, 0, s));
+        if (use_y)
+            if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)self_tile * Fo))) return st;
+    }
     {
         // the split workspace for the largest interval there can be, so that nothing is allocated inside the pipeline
         int64_t rps;
@@ -766,11 +787,11 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
         const size_t need = std::max(sizeof(float) * (size_t)nsp * F * Fo, sizeof(float) * (size_t)colsum_slabs(n) * Fo);
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, need))) return st;
     }
-    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist}) ctx->dev_free(b);  // sized per interval below
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist, &ctx->ws_dh}) ctx->dev_free(b);  // sized per interval below
     if ((st = ensure_transposed_host(ctx, g))) return st;
     bool any_done = false;
     VertexFeed feed;
-    feed.bytes_per_row = sizeof(float) * ((size_t)F + (use_y ? (size_t)Fo : 0));
+    feed.bytes_per_row = sizeof(float) * ((size_t)F + (use_y ? (size_t)Fo : 0) + (with_self ? (size_t)F : 0));
     feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool first_visit, int64_t* h2d) -> saga_status {
         auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
         HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)Fo, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
@@ -797,6 +818,16 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
             if (saga_status e = param_grad(ctx, tA, F, F, dst, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld,
                                            any_done ? 1 : 0, on, false))
                 return e;
+            if (with_self) {  // dW_self += X_J^T dZ_J
+                if (saga_status e = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)rows * F)) return e;
+                float* tX = static_cast<float*>(ctx->ws_dh.p);
+                HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)F, rows_of_t(X, row0), sizeof(float) * (size_t)X->ld,
+                                              sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+                *h2d += rows * (int64_t)F * 4;
+                if (saga_status e = param_grad(ctx, tX, F, F, dst, Fo, Fo, rows, static_cast<float*>(grads->dW_self->data),
+                                               grads->dW_self->ld, any_done ? 1 : 0, on, false))
+                    return e;
+            }
             any_done = true;
         }
         return SAGA_OK;
@@ -821,5 +852,29 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A
     vt.act = SAGA_ACT_NONE;
     saga_edge_params et{};
     et.op = ep->op;
-    return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX, &feed);
+    if (!with_self) return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX, &feed);
+
+    // dX_J = (T dZ)_J W^T + dZ_J W_self^T: the vertex's own partial gradient is the second operand pair of the schedule's
+    // ApplyVertex product, and the own rows dZ_J are formed tile by tile like the interval rows above
+    saga_tensor wst_t = wt;
+    wst_t.data = wst;
+    vt.W_self = &wst_t;
+    StreamExtras ex;
+    ex.F_self = Fo;
+    ex.self_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+        auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
+        if (rows > self_tile) return ctx->fail(SAGA_ERR_INTERNAL, "own-row tile larger than planned");
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)Fo, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
+                                      sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * (int64_t)Fo * 4;
+        if (use_y) {
+            float* tY = static_cast<float*>(ctx->ws_dz.p);
+            HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_of_t(Y, row0), sizeof(float) * (size_t)Y->ld,
+                                          sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)Fo * 4;
+            HIP_TRY(ctx, launch_dz_colsum(dst, Fo, tY, Fo, vp->act, dst, rows, Fo, nullptr, nullptr, 0, on));
+        }
+        return SAGA_OK;
+    };
+    return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX, &feed, &ex);
 }

@@ -291,7 +291,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const int64_t Fa = extras && extras->acc_width ? extras->acc_width : F;  // width of the accumulator rows
     const bool gated = ep->op == SAGA_EDGE_GATED;
     const bool has_w = vp && vp->W;
-    const bool has_self = has_w && extras && extras->self_rows;
+    const bool has_self = has_w && extras && (extras->self_rows || extras->self_fill);
     const int64_t F_self = has_self ? extras->F_self : 0;
     const int64_t F_out = has_w ? vp->W->cols : Fa;
     const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
@@ -531,11 +531,15 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 // the tile's own rows of the layer input, for the second operand; the staging buffer is free once the
                 // product that last read it has been followed by its copy-out (ev_y_free)
                 if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_y_free[b], 0));
-                HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_S[b].p, (size_t)F_self * 4, extras->self_rows + (v0 + r0) * extras->ld_self,
-                                              (size_t)extras->ld_self * 4, (size_t)F_self * 4, (size_t)tr, hipMemcpyHostToDevice, sin));
+                if (extras->self_fill) {
+                    if (saga_status fs = extras->self_fill(v0 + r0, tr, static_cast<float*>(ctx->st_S[b].p), sin, &bytes_h2d)) return fs;
+                } else {
+                    HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_S[b].p, (size_t)F_self * 4, extras->self_rows + (v0 + r0) * extras->ld_self,
+                                                  (size_t)extras->ld_self * 4, (size_t)F_self * 4, (size_t)tr, hipMemcpyHostToDevice, sin));
+                    bytes_h2d += tr * F_self * 4;
+                }
                 HIP_TRY(ctx, hipEventRecord(grid->ev_s_ready[b], sin));
                 HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_s_ready[b], 0));
-                bytes_h2d += tr * F_self * 4;
                 ge.A2 = ctx->st_S[b].p;
                 ge.lda2 = F_self;
                 ge.K2 = (int32_t)F_self;

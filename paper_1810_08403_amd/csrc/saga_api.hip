@@ -1104,8 +1104,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (g->where == SAGA_MEM_HOST) {
         // streamed: the layer's tensors live in host memory, parameters and their gradients on the device
         auto f32_at = [](const saga_tensor* t, int32_t mem) { return tensor_ok(t) && t->mem == mem && t->dtype == SAGA_F32; };
-        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
+        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT))
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers sum over COPY / MUL_WEIGHT messages");
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
         const saga_tensor* W = vp->W;
@@ -1124,12 +1124,22 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
         if (grads->dX && (!f32_at(grads->dX, SAGA_MEM_HOST) || grads->dX->rows != n || grads->dX->cols != F))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need grads->dX as a host n x F_in fp32 tensor");
-        if (grads->dW_self || grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
+        if (vp->W_self) {
+            if (!f32_at(vp->W_self, SAGA_MEM_DEVICE) || vp->W_self->rows != F || vp->W_self->cols != Fo)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out fp32 tensor");
+            if (!grads->dW_self || !f32_at(grads->dW_self, SAGA_MEM_DEVICE) || grads->dW_self->rows != F || grads->dW_self->cols != Fo)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self is given: grads->dW_self must be a device F_in x F_out fp32 tensor");
+            if (!X || !f32_at(X, SAGA_MEM_HOST) || X->rows != n || X->cols != F)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self needs X as a host n x F_in fp32 tensor");
+        } else if (grads->dW_self) {
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
+        }
+        if (grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
-        const saga_status sst = streamed_backward(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+        const saga_status sst = streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
         if (sst != SAGA_OK) {  // host tensors are the caller's again when this returns
             chunk_grid_drain(ctx, g->grid);
             if (g->tr) chunk_grid_drain(ctx, g->tr->grid);

@@ -324,8 +324,8 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 // backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
-saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
-                              const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
+saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                              const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)
@@ -349,6 +349,9 @@ struct StreamExtras {
     const float* self_rows = nullptr;  // host, n rows of F_self, ld_self elements apart (W_self)
     int64_t ld_self = 0;
     int32_t F_self = 0;
+    // instead of self_rows: produces rows [row0, row0 + rows) of the second operand (F_self wide, compact) in dst on
+    // stream s and adds the bytes it copies to *h2d (the streamed backward pass forms the interval's own dZ there)
+    std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, int64_t* h2d)> self_fill;
 };
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
                              int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,

@@ -218,6 +218,50 @@ def test_streamed_backward_matches_oracle(wl, act, edge_op, Q, P, tile):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("act,Q,P,tile", [("relu", 2, 3, 1000), ("sigmoid", 1, 4, 0), ("none", 3, 3, 700)])
+def test_streamed_backward_with_own_product(act, Q, P, tile):
+    """The CommNet layer (COPY messages, Y = act(A W + X W_self + b)) backwards with everything but the parameters in
+    host memory: dW_self is added interval by interval from tiles of X, and the vertex's own partial gradient
+    dZ W_self^T joins dX as the second operand pair of the schedule's last product, its rows of dZ formed tile by tile."""
+    import oracle
+    import paper_1810_08403_amd as saga
+    wl = si.commnet_workload(scale=12, f_in=40, f_out=24)
+    g = wl.graph
+    n, F = wl.X.shape
+    Fo = wl.W.shape[1]
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    dY = si.normal_features(n, Fo, 21)
+    bias = si.uniform_pm(Fo, 0.3, 3)
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), "copy", W=wl.W.numpy(), W_self=wl.W_self.numpy(), bias=bias.numpy(), act=act)
+    bwd = oracle.layer_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), "copy", bias=bias.numpy(),
+                                W_self=wl.W_self.numpy(), act=act)
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", Q), ("src_intervals", P), ("bwd_tile_rows", tile)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    pin = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).pin_memory()
+    X_h, A_h, Y_h, dY_h = wl.X.clone().pin_memory(), pin(fwd["A"]), pin(fwd["Y"]), pin(dY.numpy())
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    dW, dWs, db = nan(F, Fo), nan(F, Fo), nan(Fo)
+    kw = dict(X=X_h, Y=Y_h, edge_op="copy", bias=bias.cuda(), act=act, W_self=wl.W_self.cuda(), dbias=db, dW_self=dWs)
+    for rep, want_dx in enumerate([True, True, False]):           # the second call reuses the grid; the third has no dX
+        for t in (dW, dWs, db):
+            t.fill_(float("nan"))
+        dX_h.fill_(float("nan"))
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, dX=dX_h if want_dx else None, **kw)
+        what = f"streamed backward with W_self, {act} {Q}x{P} call {rep}"
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+        assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], bwd["dW_self_abs"], TOL_F32, what + " dW_self")
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
+        if want_dx:
+            assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    with pytest.raises(saga.SagaError) as e:                      # W_self without X
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, Y=Y_h, edge_op="copy", act=act, W_self=wl.W_self.cuda(), dW_self=dWs)
+    assert e.value.status == 1
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("Q,P", [(1, 3), (2, 2), (3, 5)])
 @pytest.mark.parametrize("agg", ["sum", "max"])
 def test_streamed_gated_layer(Q, P, agg):
