@@ -253,9 +253,10 @@ typedef struct saga_layer_grads {
  * X and A are required; A must be the accum_out of the forward call on the same inputs, or
  * no message will compare equal.
  *
- * Streamed calls (a SAGA_MEM_HOST graph; sum over COPY / MUL_WEIGHT messages, fp32, with or
- * without W_self): A, Y, dY, grads->dX (and X, read only with W_self) are SAGA_MEM_HOST tensors
- * (pinned recommended), W, W_self and the parameter gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
+ * Streamed calls (a SAGA_MEM_HOST graph, fp32; sum over COPY / MUL_WEIGHT messages with or
+ * without W_self, max over COPY / MUL_WEIGHT messages, sum or max over POOL messages): A, Y, dY,
+ * grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST tensors (pinned
+ * recommended), the parameters and their gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
  * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
  * (the CSR side of the paper's chunk layout), with dZ as the vertex data and W^T as the
  * ApplyVertex matrix; the transposed chunk grid is built at the first such call. dZ is formed
@@ -264,7 +265,14 @@ typedef struct saga_layer_grads {
  * its share of dW and dbias is added (interval by interval in a fixed order; with W_self its
  * rows of X come too, for dW_self, and the own partial gradient dZ W_self^T is the second operand
  * pair of the schedule's last product, fed by tiles of dZ formed the same way). Without
- * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Every transfer goes
+ * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Max and pooled layers
+ * take three passes: tiles of rows for backward-ApplyVertex, which also send the gradient of accum
+ * out to pinned host memory of the library's own (pooled layers stream X through W_pool as their
+ * forward call does); the chunk schedule over the edges clustered by source, in which rows
+ * [A | gradient of accum] travel and the row of the vertex itself (x_u or its pooled row) sits
+ * beside the accumulator for the max decision (sum over pooled rows: the gradient of accum travels
+ * as plain vertex data); and per interval, while its sums are on the device, the pooled layers'
+ * sigmoid derivative, dW_pool, db_pool and the product dX = dPre W_pool. Every transfer goes
  * through the context's device budget like in saga_layer_forward.
  *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self, act NONE or

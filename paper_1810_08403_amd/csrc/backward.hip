@@ -678,10 +678,13 @@ static saga_status ensure_transposed_host(saga_ctx* ctx, saga_graph* g)
 
 // Parameter gradients of a streamed layer without the propagation: backward-ApplyVertex over tiles of rows copied in
 // from host memory on the context's stream (dZ, the bias sums, dW += A^T dZ, tile after tile in a fixed order).
+// h_dA (optional, pinned host, n x F compact): also receives the gradient of accum, dZ W^T, tile by tile.
 static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
-                                        const saga_tensor* dY, const saga_vertex_params* vp, const saga_layer_grads* grads)
+                                        const saga_tensor* dY, const saga_vertex_params* vp, const saga_layer_grads* grads,
+                                        float* h_dA = nullptr)
 {
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
+    const int32_t Fx = X ? (int32_t)X->cols : F;  // X is as wide as the messages except for POOL
     const bool use_y = vp->act != SAGA_ACT_NONE;  // the activation's derivative is taken from the layer's output
     hipStream_t s = ctx->stream;
     saga_status st;
@@ -690,7 +693,7 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     if (ctx->budget > 0) {
         // the tiles, the split workspace of the parameter-gradient product (at most 1,024 partial F x F_out matrices, usually
         // far fewer) and the column-sum slabs have to fit beside whatever else the context holds
-        const size_t per_row = sizeof(float) * ((size_t)F + 3 * (size_t)Fo + (grads->dW_self ? (size_t)F : 0));
+        const size_t per_row = sizeof(float) * ((size_t)F + 3 * (size_t)Fo + (grads->dW_self ? (size_t)Fx : 0) + (h_dA ? (size_t)F : 0));
         int64_t rps;
         int32_t nsp;
         gemm_tn_plan(T, F, Fo, &rps, &nsp);
@@ -708,7 +711,9 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     if (grads->dbias)
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(T) * Fo))) return st;
     if (grads->dW_self)
-        if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)T * F))) return st;  // X tile (dW_self = X^T dZ)
+        if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)T * Fx))) return st;  // X tile (dW_self = X^T dZ)
+    if (h_dA)
+        if ((st = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * (size_t)T * F))) return st;  // tile of the gradient of accum
     float* tX = static_cast<float*>(ctx->ws_dh.p);
     float* tA = static_cast<float*>(ctx->ws_accum.p);
     float* tdY = static_cast<float*>(ctx->ws_grad.p);
@@ -738,12 +743,18 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
         if ((st = param_grad(ctx, tA, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW->data), grads->dW->ld, acc))) return st;
         if (grads->dW_self) {
             if (rows > 0) {
-                HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)F, rows_at(X, r0), sizeof(float) * (size_t)X->ld,
-                                              sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, s));
-                h2d += rows * (int64_t)F * 4;
+                HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)Fx, rows_at(X, r0), sizeof(float) * (size_t)X->ld,
+                                              sizeof(float) * (size_t)Fx, (size_t)rows, hipMemcpyHostToDevice, s));
+                h2d += rows * (int64_t)Fx * 4;
             }
-            if ((st = param_grad(ctx, tX, F, F, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld, acc)))
+            if ((st = param_grad(ctx, tX, Fx, Fx, tdZ, Fo, Fo, rows, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld, acc)))
                 return st;
+        }
+        if (h_dA && rows > 0) {
+            float* tDA = static_cast<float*>(ctx->ws_tile.p);
+            if ((st = rows_times_wt(ctx, tdZ, Fo, Fo, vp->W, nullptr, 0, 0, nullptr, rows, F, tDA, F))) return st;
+            HIP_TRY(ctx, hipMemcpyAsync(h_dA + r0 * F, tDA, sizeof(float) * (size_t)rows * F, hipMemcpyDeviceToHost, s));
+            d2h += rows * (int64_t)F * 4;
         }
         // one stream: the next tile's copies queue behind this tile's kernels
     }
@@ -751,6 +762,128 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     ctx->acc.bytes_h2d += h2d;
     ctx->acc.bytes_d2h += d2h;
     return SAGA_OK;
+}
+
+// Streamed backward pass of a layer with the max accumulator (COPY, MUL_WEIGHT or POOL messages) or with pooled messages
+// under the sum accumulator; X, A, Y, dY and dX in host memory. Three passes:
+//   1. tiles of rows: dZ, dW += A^T dZ, dbias (dW_self), and the gradient of accum dZ W^T out to pinned host memory;
+//      pooled layers also stream X through their per-vertex product (stream_hoist_to_host);
+//   2. the chunk schedule over the edges clustered by source. Max: rows [A | gradient of accum] of the destination side
+//      travel, the row of the vertex itself (x_u, or its pooled row) sits beside the accumulator, and the edge function
+//      is the max-gradient one of the resident pass; sum over pooled rows: the gradient of accum travels as it is;
+//   3. per interval, while its sums dS are still on the device: pooled layers go through the sigmoid
+//      (dPre = dS (.) h (1 - h)), add dPre^T X and the column sums of dPre to dW_pool and db_pool, and the schedule's
+//      ApplyVertex product is dX = dPre W_pool; otherwise dS is dX.
+saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                       const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
+                                       const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const bool pool = ep->op == SAGA_EDGE_POOL;
+    const int32_t Fm = (int32_t)vp->W->rows, F = (int32_t)X->cols;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+    const bool propagate = n > 0 && (pool || grads->dX);
+    if (propagate) {
+        const size_t need = sizeof(float) * (size_t)n * Fm;
+        if (ctx->h_grad_bytes < need) {
+            if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
+            ctx->h_grad = nullptr;
+            ctx->h_grad_bytes = 0;
+            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_grad), need, hipHostMallocDefault));
+            ctx->h_grad_bytes = need;
+        }
+    }
+    if ((st = streamed_param_grads(ctx, n, X, A, Y, dY, vp, grads, propagate ? ctx->h_grad : nullptr))) return st;
+    if (n == 0) {
+        if (pool) {
+            if ((st = param_grad(ctx, nullptr, Fm, Fm, nullptr, F, F, 0, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
+            if (grads->db_pool) HIP_TRY(ctx, launch_fill_f32(static_cast<float*>(grads->db_pool->data), Fm, 0.f, s));
+            HIP_TRY(ctx, hipStreamSynchronize(s));
+        }
+        return SAGA_OK;
+    }
+    if (!propagate) return SAGA_OK;
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
+    if (pool)
+        if ((st = stream_hoist_to_host(ctx, X, ep, n, F, Fm))) return st;
+    if ((st = ensure_transposed_host(ctx, g))) return st;
+
+    // the per-vertex part of the message: the pooled rows, or X itself
+    const float* S = pool ? ctx->h_hoist : static_cast<const float*>(X->data);
+    const int64_t lds = pool ? Fm : X->ld;
+    const float* h_dA = ctx->h_grad;
+    VertexFeed feed;
+    StreamExtras ex;
+    saga_tensor rows_t{};  // shape of the rows that travel
+    rows_t.rows = n;
+    rows_t.dtype = SAGA_F32;
+    rows_t.mem = SAGA_MEM_HOST;
+    saga_edge_params et{};
+    et.op = pool ? SAGA_EDGE_COPY : ep->op;  // whether the chunks carry edge data
+    if (agg == SAGA_AGG_MAX) {
+        rows_t.cols = rows_t.ld = 2 * Fm;
+        feed.bytes_per_row = 0;
+        feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
+            // [the maximum gathered at the vertex | its gradient], side by side
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * 2 * (size_t)Fm, static_cast<const float*>(A->data) + row0 * A->ld,
+                                          sizeof(float) * (size_t)A->ld, sizeof(float) * (size_t)Fm, (size_t)rows, hipMemcpyHostToDevice, on));
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst + Fm, sizeof(float) * 2 * (size_t)Fm, h_dA + row0 * Fm, sizeof(float) * (size_t)Fm,
+                                          sizeof(float) * (size_t)Fm, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * 2 * (int64_t)Fm * 4;
+            return SAGA_OK;
+        };
+        ex.op = kGatherOpMaxGrad;
+        ex.acc_width = Fm;
+        ex.dst_rows = S;
+        ex.ld_dst = lds;
+    } else {
+        rows_t.data = ctx->h_grad;  // sum over pooled rows: the gradient of accum travels unchanged
+        rows_t.cols = rows_t.ld = Fm;
+    }
+    saga_vertex_params vt{};
+    saga_tensor wp{};
+    if (pool) {
+        // dX = dPre W_pool: W_pool (F_pool x F) is already the "F_in x F_out" matrix of this product
+        wp = *ep->W_pool;
+        vt.W = &wp;
+        vt.act = SAGA_ACT_NONE;
+        ex.bytes_per_dst_row = sizeof(float) * ((size_t)Fm + F);
+        {
+            // the split workspace for the largest interval there can be, so that nothing is allocated inside the pipeline;
+            // the column sums use it after the product's partial sums have been added up (same stream)
+            int64_t rps;
+            int32_t nsp;
+            gemm_tn_plan(n, Fm, F, &rps, &nsp);
+            const size_t need = std::max(sizeof(float) * (size_t)nsp * Fm * F, sizeof(float) * (size_t)colsum_slabs(n) * Fm);
+            if ((st = ctx->dev_alloc(&ctx->ws_splitk, need))) return st;
+        }
+        bool any_done = false;
+        ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
+            // the interval's pooled rows and its rows of X, on the compute stream (its kernels wait for them anyway)
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fm)) return e;  // intervals do not grow
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * (size_t)rows * F)) return e;
+            float* tS = static_cast<float*>(ctx->ws_hoist.p);
+            float* tX = static_cast<float*>(ctx->ws_tile.p);
+            HIP_TRY(ctx, hipMemcpyAsync(tS, ctx->h_hoist + row0 * Fm, sizeof(float) * (size_t)rows * Fm, hipMemcpyHostToDevice, on));
+            HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                          sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)(Fm + F) * 4;
+            HIP_TRY(ctx, launch_sigmoid_grad(acc, tS, rows * (int64_t)Fm, on));
+            if (saga_status e = param_grad(ctx, acc, Fm, Fm, tX, F, F, rows, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld,
+                                           any_done ? 1 : 0, on, false))
+                return e;
+            if (grads->db_pool)
+                HIP_TRY(ctx, launch_dz_colsum(acc, Fm, nullptr, 0, SAGA_ACT_NONE, nullptr, rows, Fm,
+                                              static_cast<float*>(ctx->ws_splitk.p), static_cast<float*>(grads->db_pool->data),
+                                              any_done ? 1 : 0, on));
+            any_done = true;
+            return SAGA_OK;
+        };
+    }
+    saga_tensor no_dx{};  // pooled layers without dX still need the pass for dW_pool: the schedule then writes nothing out
+    return streamed_forward(ctx, g->tr, &rows_t, &et, SAGA_AGG_SUM, pool ? &vt : nullptr, grads->dX ? grads->dX : &no_dx,
+                            agg == SAGA_AGG_MAX ? &feed : nullptr, &ex);
 }
 
 saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,

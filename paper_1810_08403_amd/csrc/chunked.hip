@@ -289,7 +289,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const int64_t n = g->n;
     const int64_t F = X->cols;                                            // width of the rows that travel over the edges
     const int64_t Fa = extras && extras->acc_width ? extras->acc_width : F;  // width of the accumulator rows
-    const bool gated = ep->op == SAGA_EDGE_GATED;
+    const int32_t op = extras && extras->op ? extras->op : (int32_t)ep->op;
+    const bool gated = ep->op == SAGA_EDGE_GATED || (extras && extras->op);  // rows [x | m] travel, constant rows are resident
     const bool has_w = vp && vp->W;
     const bool has_self = has_w && extras && (extras->self_rows || extras->self_fill);
     const int64_t F_self = has_self ? extras->F_self : 0;
@@ -334,7 +335,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 count_grid(g, q, p, &nnz, &pairs);
                 const size_t need = plan_bytes(g, q, p, F, Fa, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs, gated,
                                                F_self) +
-                                    (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0);
+                                    (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0) +
+                                    (extras ? extras->bytes_per_dst_row * (size_t)((n + q - 1) / q) : 0);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
                 if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need + held <= ctx->budget)) {
                     Q = q;
@@ -472,7 +474,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         ga.ld_src = F;
         ga.F = (int32_t)Fa;
         ga.dtype = SAGA_F32;
-        ga.op = ep->op;
+        ga.op = op;
         ga.agg = agg;
         ga.out = A;
         ga.ld_out = Fa;
@@ -512,6 +514,13 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             d_busy = true;
         }
         if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * Fa, sc));
+        if (extras && extras->after_gather)
+            if (saga_status hs = extras->after_gather(v0, rows, A, sc, &bytes_h2d)) return hs;
+        if (!Yh) {  // nobody wants the rows (a backward pass that only needs what after_gather adds up)
+            HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
+            a_busy = true;
+            return SAGA_OK;
+        }
         if (!has_w) {
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
             HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));

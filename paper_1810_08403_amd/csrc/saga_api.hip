@@ -384,23 +384,12 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
 // a per-vertex part (Section 3.2) first stream X through that product, tile by tile, into pinned host memory held by
 // the context (the paper's dataflow does the same when the hoisted products of a big graph do not fit the device:
 // they become vertex data of their own), then run the schedule on those rows.
-static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
-                                  const saga_vertex_params* vp, saga_tensor* Y)
+// The per-vertex products of a gated or pooled layer (Section 3.2) for every vertex of a host-resident X, tile by tile
+// through the device into pinned host memory (ctx->h_hoist, n rows of Fh values): [Ps | M | Pd] (Fh = 3F) or the pooled
+// rows sigmoid(X W_pool^T + b) (Fh = F_pool). Returns after the last copy has arrived.
+saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fh)
 {
-    const int64_t n = g->n;
-    const int32_t F = (int32_t)X->cols;
-    const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
-    StreamExtras ex;
-    bool use_ex = false;
-    if (vp && vp->W_self) {
-        ex.self_rows = static_cast<const float*>(X->data);
-        ex.ld_self = X->ld;
-        ex.F_self = F;
-        use_ex = true;
-    }
-    if (!gated && !pool) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
-
-    const int32_t Fh = gated ? 3 * F : (int32_t)ep->W_pool->rows;  // width of the per-vertex rows
+    const bool gated = ep->op == SAGA_EDGE_GATED;
     const size_t need = sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fh;
     if (ctx->h_hoist_bytes < need) {
         if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
@@ -442,6 +431,27 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
     ctx->acc.bytes_h2d += h2d;
     ctx->acc.bytes_d2h += d2h;
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist}) ctx->dev_free(b);  // make room under the budget
+    return SAGA_OK;
+}
+
+static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
+                                  const saga_vertex_params* vp, saga_tensor* Y)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)X->cols;
+    const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
+    StreamExtras ex;
+    bool use_ex = false;
+    if (vp && vp->W_self) {
+        ex.self_rows = static_cast<const float*>(X->data);
+        ex.ld_self = X->ld;
+        ex.F_self = F;
+        use_ex = true;
+    }
+    if (!gated && !pool) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
+
+    const int32_t Fh = gated ? 3 * F : (int32_t)ep->W_pool->rows;  // width of the per-vertex rows
+    if (saga_status st = stream_hoist_to_host(ctx, X, ep, n, F, Fh)) return st;
 
     saga_tensor hx{};
     hx.data = ctx->h_hoist;
@@ -588,11 +598,12 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->ws_tile, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
                       &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials, &ctx->st_D, &ctx->st_S[0],
                       &ctx->st_S[1]})
         ctx->dev_free(b);
     if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
+    if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
@@ -1104,26 +1115,48 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (g->where == SAGA_MEM_HOST) {
         // streamed: the layer's tensors live in host memory, parameters and their gradients on the device
         auto f32_at = [](const saga_tensor* t, int32_t mem) { return tensor_ok(t) && t->mem == mem && t->dtype == SAGA_F32; };
-        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT))
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers sum over COPY / MUL_WEIGHT messages");
+        if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
+        const bool pool_h = ep->op == SAGA_EDGE_POOL;
+        if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT && !pool_h)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers COPY, MUL_WEIGHT and POOL messages");
+        const bool max_or_pool = pool_h || agg == SAGA_AGG_MAX;
+        if (max_or_pool && vp->W_self)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers W_self only with sum over COPY / MUL_WEIGHT messages");
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
         const saga_tensor* W = vp->W;
         if (!W || !f32_at(W, SAGA_MEM_DEVICE) || W->rows > (1 << 20) || W->cols > (1 << 20))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device F_in x F_out fp32 tensor");
-        const int64_t n = g->n, F = W->rows, Fo = W->cols;
-        if (!f32_at(A, SAGA_MEM_HOST) || A->rows != n || A->cols != F)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need A as a host n x F_in fp32 tensor");
+        const int64_t n = g->n, Fmh = W->rows, Fo = W->cols;  // Fmh: message width (rows of W, columns of A)
+        int64_t F = Fmh;                                       // F: width of X and dX
+        if (pool_h) {
+            const saga_tensor* Wp = ep->W_pool;
+            if (!Wp || !f32_at(Wp, SAGA_MEM_DEVICE) || Wp->rows != Fmh || Wp->cols < 1 || Wp->cols > (1 << 20))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_pool must be a device F_pool x F fp32 tensor with F_pool = rows of W");
+            F = Wp->cols;
+            if (ep->b_pool && (!f32_at(ep->b_pool, SAGA_MEM_DEVICE) || ep->b_pool->rows * ep->b_pool->cols != Fmh))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "b_pool must be F_pool fp32 values on the device");
+            if (!grads->dW_pool || !f32_at(grads->dW_pool, SAGA_MEM_DEVICE) || grads->dW_pool->rows != Fmh || grads->dW_pool->cols != F)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_pool must be a device F_pool x F fp32 tensor");
+            if (grads->db_pool && (!f32_at(grads->db_pool, SAGA_MEM_DEVICE) || grads->db_pool->rows * grads->db_pool->cols != Fmh))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->db_pool must be F_pool fp32 values on the device");
+        } else if (grads->dW_pool || grads->db_pool) {
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "pool gradients are for POOL layers only");
+        }
+        if (max_or_pool && (!X || !f32_at(X, SAGA_MEM_HOST) || X->rows != n || X->cols != F))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer needs X as a host n x F fp32 tensor");
+        if (!f32_at(A, SAGA_MEM_HOST) || A->rows != n || A->cols != Fmh)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need A as a host n x Fm fp32 tensor");
         if (!f32_at(dY, SAGA_MEM_HOST) || dY->rows != n || dY->cols != Fo)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need dY as a host n x F_out fp32 tensor");
         if (vp->act != SAGA_ACT_NONE && (!Y || !f32_at(Y, SAGA_MEM_HOST) || Y->rows != n || Y->cols != Fo))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "an activation needs Y as a host n x F_out fp32 tensor");
-        if (!grads->dW || !f32_at(grads->dW, SAGA_MEM_DEVICE) || grads->dW->rows != F || grads->dW->cols != Fo)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device F_in x F_out fp32 tensor");
+        if (!grads->dW || !f32_at(grads->dW, SAGA_MEM_DEVICE) || grads->dW->rows != Fmh || grads->dW->cols != Fo)
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW must be a device Fm x F_out fp32 tensor");
         if (grads->dbias && (!f32_at(grads->dbias, SAGA_MEM_DEVICE) || grads->dbias->rows * grads->dbias->cols != Fo))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
         if (grads->dX && (!f32_at(grads->dX, SAGA_MEM_HOST) || grads->dX->rows != n || grads->dX->cols != F))
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need grads->dX as a host n x F_in fp32 tensor");
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need grads->dX as a host n x F fp32 tensor");
         if (vp->W_self) {
             if (!f32_at(vp->W_self, SAGA_MEM_DEVICE) || vp->W_self->rows != F || vp->W_self->cols != Fo)
                 return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out fp32 tensor");
@@ -1134,12 +1167,14 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         } else if (grads->dW_self) {
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
         }
-        if (grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
+        if (grads->dW_gate || grads->db_gate || grads->dW_msg)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
-        const saga_status sst = streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
+        const saga_status sst = max_or_pool
+                                    ? streamed_max_pool_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
+                                    : streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
         if (sst != SAGA_OK) {  // host tensors are the caller's again when this returns
             chunk_grid_drain(ctx, g->grid);
             if (g->tr) chunk_grid_drain(ctx, g->tr->grid);

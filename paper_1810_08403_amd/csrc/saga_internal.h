@@ -107,7 +107,10 @@ struct saga_ctx {
     DevBuf st_D, st_S[2];  // gated: destination parts of the resident interval; W_self: tiles of the interval's own rows
     float* h_hoist = nullptr;  // streamed gated / pooled layers: the per-vertex products of all vertices in pinned host memory
     size_t h_hoist_bytes = 0;
+    float* h_grad = nullptr;   // streamed backward of max / pooled layers: the gradient of accum of all vertices, pinned
+    size_t h_grad_bytes = 0;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
+    DevBuf ws_tile;      // streamed backward of max / pooled layers: a tile of the gradient of accum, rows of X of an interval
 
     // profiling
     bool profiling = false;
@@ -324,6 +327,9 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 // backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
+saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                       const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
+                                       const saga_layer_grads* grads);
 saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
@@ -344,8 +350,14 @@ struct VertexFeed {
 // layer input are copied in tile by tile for the second operand of the ApplyVertex product.
 struct StreamExtras {
     int32_t acc_width = 0;             // 0: as wide as X's rows
-    const float* dst_rows = nullptr;   // host, n rows, ld_dst elements apart (gated)
-    int64_t ld_dst = 0;
+    const float* dst_rows = nullptr;   // host, n rows of acc_width values, ld_dst elements apart: per-destination rows kept
+    int64_t ld_dst = 0;                // beside the accumulators of the resident interval (gated; backward of a max Gather)
+    int32_t op = 0;                    // 0: ep->op; else an internal edge function of the propagation kernel whose rows
+                                       // [x | m] travel (2 * acc_width wide) and whose constant row is dst_rows
+    // called once per destination interval after its last chunk, before ApplyVertex, with the interval's accumulator
+    // rows on the device (compute stream s): the backward pass of pooled messages goes through the sigmoid there
+    std::function<saga_status(int64_t row0, int64_t rows, float* acc, hipStream_t s, int64_t* h2d)> after_gather;
+    size_t bytes_per_dst_row = 0;      // device bytes after_gather holds per row of a destination interval, for the planner
     const float* self_rows = nullptr;  // host, n rows of F_self, ld_self elements apart (W_self)
     int64_t ld_self = 0;
     int32_t F_self = 0;
@@ -357,6 +369,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                              int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,
                              const StreamExtras* extras = nullptr);
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
+saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fh);
 void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device

@@ -337,6 +337,52 @@ def test_streamed_applications_under_one_gib_at_full_size(app):
     ctx.destroy()
 
 
+def test_mpgcn_rmat20_streamed_backward_under_two_gib_equals_the_resident_one():
+    """The max-pooling layer's backward pass from host memory through a 2 GiB device budget at R-MAT 20, against the
+    device-resident backward pass of the same layer (whose maxima decisions it must reproduce: both recompute the pooled
+    rows with the same kernels), and the peak stays under the budget."""
+    import paper_1810_08403_amd as saga
+    wl = si.mpgcn_workload(scale=20, edge_factor=32, f_in=128, f_pool=128, f_out=128, device="cuda")
+    g = wl.graph
+    n = g.n
+    kw = dict(edge_op="pool", agg="max", W_pool=wl.W_pool, b_pool=wl.b_pool, act="relu")
+    z = lambda *s: torch.full(s, float("nan"), device="cuda")
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
+    ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
+    dY = si.normal_features(n, 128, 78, device="cuda")
+    ref = dict(dW=z(128, 128), dX=z(n, 128), dW_pool=z(128, 128), db_pool=z(128), dbias=z(128))
+    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y, dX=ref["dX"], dW_pool=ref["dW_pool"], db_pool=ref["db_pool"],
+                       dbias=ref["dbias"], **kw)
+    torch.cuda.synchronize()
+    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y, dY=dY).items()}
+    ref = {k: v.cpu() for k, v in ref.items()}
+    graph.destroy()
+    ctx.destroy()
+    del Y, A, dY
+    torch.cuda.empty_cache()
+    budget = 2 << 30
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    hg = ctx.graph_create_csc(n, g.col_ptr.cpu(), g.row_idx.cpu())
+    pin = lambda t: t.contiguous().pin_memory()
+    dX_h = torch.full((n, 128), float("nan")).pin_memory()
+    got = dict(dW=z(128, 128), dW_pool=z(128, 128), db_pool=z(128), dbias=z(128))
+    ctx.layer_backward(hg, pin(host["A"]), pin(host["dY"]), wl.W, got["dW"], X=pin(host["X"]), Y=pin(host["Y"]), dX=dX_h,
+                       dW_pool=got["dW_pool"], db_pool=got["db_pool"], dbias=got["dbias"], **kw)
+    torch.cuda.synchronize()
+    assert ctx.peak_device_bytes() <= budget
+    # the same sums in another grouping: close in the norm of each tensor
+    for name in ("dW", "dW_pool", "db_pool", "dbias"):
+        err = (got[name].cpu().double() - ref[name].double()).abs().max().item()
+        assert err <= 1e-4 * ref[name].abs().max().item(), (name, err)
+    err = (dX_h.double() - ref["dX"].double()).abs().max().item()
+    assert err <= 1e-4 * ref["dX"].abs().max().item(), ("dX", err)
+    # a vertex gets a gradient exactly where the resident pass gives it one
+    assert torch.equal(dX_h.abs().sum(1) > 0, ref["dX"].abs().sum(1) > 0)
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("agg", ["sum", "max"])
 def test_config5_full_streamed_under_16gb(agg):
     import paper_1810_08403_amd as saga

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import saga_inputs as si
-from helpers import TOL_F32, assert_bit_equal, assert_sum_close, run_oracle
+from helpers import TOL_F32, assert_bit_equal, assert_sum_close, new_context, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -259,6 +259,113 @@ def test_streamed_backward_with_own_product(act, Q, P, tile):
     with pytest.raises(saga.SagaError) as e:                      # W_self without X
         ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, Y=Y_h, edge_op="copy", act=act, W_self=wl.W_self.cuda(), dW_self=dWs)
     assert e.value.status == 1
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("edge_op,act,Q,P", [("copy", "relu", 2, 3), ("mul_weight", "none", 1, 4), ("pool", "relu", 2, 2), ("pool", "sigmoid", 1, 3)])
+def test_streamed_max_backward_matches_oracle(edge_op, act, Q, P):
+    """Backward pass of a max-accumulator layer (plain, weighted or pooled messages) from host memory: the gradient of accum
+    goes out to pinned memory tile by tile, then rows [A | gradient of accum] travel over the chunks of edges clustered
+    by source while the vertex's own row sits beside the accumulator; pooled layers finish per interval on the device."""
+    import oracle
+    import paper_1810_08403_amd as saga
+    pool = edge_op == "pool"
+    wl = si.mpgcn_workload(scale=12, f_in=16, f_pool=32, f_out=24) if pool else si.commnet_workload(scale=12, f_in=40, f_out=24)
+    if pool:   # coarse values: the order of the sigmoids, ties included, is the same in fp32 and fp64
+        wl.X = torch.round(wl.X.clamp(-1, 1) * 4) / 4
+        wl.W_pool = torch.round((wl.W_pool * 4).clamp(-0.5, 0.5) * 8) / 8
+        wl.b_pool = torch.round(wl.b_pool.clamp(-0.5, 0.5) * 8) / 8
+    g = wl.graph
+    n, F = wl.X.shape
+    Fm, Fo = wl.W.shape
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    w = si.uniform_pm(g.nnz, 1.0, 17) if edge_op == "mul_weight" else None     # both signs
+    dY = si.normal_features(n, Fo, 23)
+    bias = si.uniform_pm(Fo, 0.3, 3)
+    okw = {}
+    if w is not None:
+        okw["edge_weight"] = w.numpy()
+    if pool:
+        okw.update(W_pool=wl.W_pool.numpy(), b_pool=wl.b_pool.numpy())
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", Q), ("src_intervals", P), ("bwd_tile_rows", 900)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    if w is not None:
+        graph.set_edge_data(w)
+    kw = dict(edge_op=edge_op, agg="max", act=act, bias=bias.cuda())
+    if pool:
+        kw.update(W_pool=wl.W_pool.cuda(), b_pool=wl.b_pool.cuda())
+    X_h = wl.X.clone().pin_memory()
+    Y_h, A_h = torch.empty(n, Fo).pin_memory(), torch.empty(n, Fm).pin_memory()
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op, agg="max", W=wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
+    bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), edge_op, bias=bias.numpy(), act=act, **okw)
+    if pool:
+        # a forward pass on the device supplies A and Y: its pooled rows are the ones the backward pass recomputes bit for bit
+        with new_context() as c2:
+            g2 = c2.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+            Yd, Ad = torch.empty(n, Fo, device="cuda"), torch.empty(n, Fm, device="cuda")
+            c2.layer_forward(g2, wl.X.cuda(), Yd, W=wl.W.cuda(), accum_out=Ad, **kw)
+            torch.cuda.synchronize()
+            A_h.copy_(Ad.cpu())
+            Y_h.copy_(Yd.cpu())
+            g2.destroy()
+        assert_sum_close(A_h.numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, "pooled Gather of the forward pass")
+    else:
+        A_h.copy_(torch.as_tensor(bwd["A"], dtype=torch.float32))
+        Y_h.copy_(torch.as_tensor(fwd["Y"], dtype=torch.float32))
+    dY_h = dY.clone().pin_memory()
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    dW, db = nan(Fm, Fo), nan(Fo)
+    gk = dict(dW_pool=nan(Fm, F), db_pool=nan(Fm)) if pool else {}
+    for rep, want_dx in enumerate([True, True, False]):
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, X=X_h, Y=Y_h, dX=dX_h if want_dx else None, dbias=db, **kw, **gk)
+        what = f"streamed max backward {edge_op} {act} {Q}x{P} call {rep}"
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
+        if want_dx:
+            assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+        if pool:
+            assert_sum_close(gk["dW_pool"].cpu().numpy(), bwd["dW_pool"], bwd["dW_pool_abs"], TOL_F32, what + " dW_pool")
+            assert_sum_close(gk["db_pool"].cpu().numpy(), bwd["db_pool"], bwd["db_pool_abs"], TOL_F32, what + " db_pool")
+            for t in gk.values():
+                t.fill_(float("nan"))
+        dX_h.fill_(float("nan"))
+        dW.fill_(float("nan"))
+        db.fill_(float("nan"))
+    ctx.destroy()
+
+
+def test_streamed_sum_over_pooled_messages_backward():
+    """Sum over pooled messages from host memory: the gradient of accum travels as plain vertex data, then the same
+    per-interval finish as for the max accumulator; against autograd of the definition in fp64."""
+    import paper_1810_08403_amd as saga
+    wl = si.mpgcn_workload(scale=11, f_in=12, f_pool=20, f_out=8)
+    g = wl.graph
+    n, F = wl.X.shape
+    Fm, Fo = wl.W.shape
+    dY = si.normal_features(n, Fo, 7)
+    Xt = wl.X.double().requires_grad_(True)
+    Wpt, bpt, Wt = wl.W_pool.double().requires_grad_(True), wl.b_pool.double().requires_grad_(True), wl.W.double().requires_grad_(True)
+    H = torch.sigmoid(Xt @ Wpt.T + bpt)
+    deg = g.col_ptr[1:] - g.col_ptr[:-1]
+    dst = torch.repeat_interleave(torch.arange(n), deg)
+    Aref = torch.zeros(n, Fm, dtype=torch.float64).index_add(0, dst, H[g.row_idx.long()])
+    ((Aref @ Wt) * dY.double()).sum().backward()
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", 2), ("src_intervals", 3)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    X_h, A_h, dY_h = wl.X.clone().pin_memory(), Aref.detach().float().pin_memory(), dY.clone().pin_memory()
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    dW, dWp, dbp = nan(Fm, Fo), nan(Fm, F), nan(Fm)
+    ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), dW, X=X_h, edge_op="pool", agg="sum", W_pool=wl.W_pool.cuda(), b_pool=wl.b_pool.cuda(),
+                       act="none", dX=dX_h, dW_pool=dWp, db_pool=dbp)
+    for name, got, ref in [("dW", dW.cpu(), Wt.grad), ("dX", dX_h, Xt.grad), ("dW_pool", dWp.cpu(), Wpt.grad), ("db_pool", dbp.cpu(), bpt.grad)]:
+        err = (got.double() - ref).abs().max().item()
+        assert err <= 2e-5 * ref.abs().max().item(), (name, err)
     ctx.destroy()
 
 
