@@ -11,7 +11,10 @@
 //   - max accumulator and pooled messages: the gradient goes to the sources that supplied
 //     the maxima, found by recomputing the messages;
 //   - streamed layers (tensors in host memory): the chunk schedule of Section 3.1 on the
-//     chunks of edges clustered by source, with dZ formed on the way in.
+//     chunks of edges clustered by source, with dZ formed on the way in (linear ApplyEdge,
+//     with or without W_self), or, for the max accumulator and pooled messages, with the
+//     gradient of accum passing through pinned host memory between a tile pass and the
+//     schedule, and a per-interval finish on the device.
 #include <cstring>
 
 #include "saga_internal.h"

@@ -23,7 +23,9 @@
 // them (the streamed backward pass forms dZ there), and extras for layers that need
 // more than one kind of row (gated: rows [Ps | M] travel, the destination parts Pd
 // of the resident interval sit beside its accumulator; W_self: the interval's own
-// rows are copied in for ApplyVertex). The device buffers belong to the context, so
+// rows are copied in, or produced by a callback, for ApplyVertex; the backward pass
+// of a max Gather: another edge function over rows [x | m], and a callback that works
+// on an interval's sums before ApplyVertex). The device buffers belong to the context, so
 // that the grid of a graph and the grid of its transposed twin share one budget.
 #include <algorithm>
 #include <atomic>
