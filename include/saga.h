@@ -254,7 +254,8 @@ typedef struct saga_layer_grads {
  * no message will compare equal.
  *
  * Streamed calls (a SAGA_MEM_HOST graph, fp32; sum over COPY / MUL_WEIGHT messages with or
- * without W_self, max over COPY / MUL_WEIGHT messages, sum or max over POOL messages): A, Y, dY,
+ * without W_self, max over COPY / MUL_WEIGHT messages, sum or max over POOL messages, sum over
+ * GATED messages): A, Y, dY,
  * grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST tensors (pinned
  * recommended), the parameters and their gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
  * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
@@ -272,8 +273,14 @@ typedef struct saga_layer_grads {
  * [A | gradient of accum] travel and the row of the vertex itself (x_u or its pooled row) sits
  * beside the accumulator for the max decision (sum over pooled rows: the gradient of accum travels
  * as plain vertex data); and per interval, while its sums are on the device, the pooled layers'
- * sigmoid derivative, dW_pool, db_pool and the product dX = dPre W_pool. Every transfer goes
- * through the context's device budget like in saga_layer_forward.
+ * sigmoid derivative, dW_pool, db_pool and the product dX = dPre W_pool. Gated layers take the
+ * tile pass, then the schedule over the in-edges (rows [Ps | M] travel, [Pd | gradient of accum]
+ * of the resident interval are the constants: dPd, and per interval its share of dW_gate's right
+ * half and of db_gate), then the schedule over the edges clustered by source (rows
+ * [Pd | gradient of accum] travel, [Ps | M] are the constants, both source-side sums at once; per
+ * interval the shares of dW_gate's left half and of dW_msg; the last product is
+ * dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd). Every transfer goes through the context's device
+ * budget like in saga_layer_forward.
  *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self, act NONE or
  * RELU): X is not

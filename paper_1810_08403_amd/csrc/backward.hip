@@ -14,7 +14,9 @@
 //     chunks of edges clustered by source, with dZ formed on the way in (linear ApplyEdge,
 //     with or without W_self), or, for the max accumulator and pooled messages, with the
 //     gradient of accum passing through pinned host memory between a tile pass and the
-//     schedule, and a per-interval finish on the device.
+//     schedule, and a per-interval finish on the device; gated layers run the schedule
+//     twice (in-edges, then edges by source), their per-vertex products and gradients
+//     passing through pinned memory as well.
 #include <cstring>
 
 #include "saga_internal.h"
@@ -887,6 +889,176 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
     saga_tensor no_dx{};  // pooled layers without dX still need the pass for dW_pool: the schedule then writes nothing out
     return streamed_forward(ctx, g->tr, &rows_t, &et, SAGA_AGG_SUM, pool ? &vt : nullptr, grads->dX ? grads->dX : &no_dx,
                             agg == SAGA_AGG_MAX ? &feed : nullptr, &ex);
+}
+
+// Streamed backward pass of a gated layer (sum accumulator); X, A, Y, dY and dX in host memory. The per-vertex products
+// [Ps | M | Pd] of all vertices and the per-vertex gradients [dPs | dM | dPd] pass through pinned host memory of the
+// library's own, as the forward call's products do:
+//   1. tiles of rows: dZ, dW += A^T dZ, dbias, and the gradient of accum dZ W^T out to pinned memory; X through the
+//      per-vertex products (stream_hoist_to_host);
+//   2. the chunk schedule over the in-edges: rows [Ps | M] travel, [Pd | gradient of accum] of the resident interval sit
+//      beside its accumulator, edge function "gate gradient": dPd_j. Per interval: dW_gd += dPd_j^T X_j, db += sums;
+//      dPd_j goes out to pinned memory;
+//   3. the chunk schedule over the edges clustered by source: rows [Pd | gradient of accum] travel, [Ps | M] of the
+//      resident interval are the constants, edge function "both gate gradients": [dPs | dM]_J. Per interval:
+//      dW_gs += dPs^T X_J, dW_m += dM^T X_J; the schedule's last product is
+//      dX_J = [dPs | dM] [W_gs ; W_m] + dPd_J W_gd, the second pair fed from what pass 2 left in pinned memory.
+saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                    const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                                    const saga_layer_grads* grads)
+{
+    const int64_t n = g->n;
+    const int32_t F = (int32_t)X->cols;
+    hipStream_t s = ctx->stream;
+    saga_status st;
+    float* dWg = static_cast<float*>(grads->dW_gate->data);
+    const int64_t lddwg = grads->dW_gate->ld;
+    if (n > 0) {
+        const size_t need = sizeof(float) * (size_t)n * 4 * F;  // gradient of accum (n x F), then [dPs | dM | dPd] (n x 3F)
+        if (ctx->h_grad_bytes < need) {
+            if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
+            ctx->h_grad = nullptr;
+            ctx->h_grad_bytes = 0;
+            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_grad), need, hipHostMallocDefault));
+            ctx->h_grad_bytes = need;
+        }
+    }
+    if ((st = streamed_param_grads(ctx, n, nullptr, A, Y, dY, vp, grads, n > 0 ? ctx->h_grad : nullptr))) return st;
+    if (n == 0) {  // sums over nothing
+        if ((st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg, lddwg))) return st;
+        if ((st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg + F, lddwg))) return st;
+        if (grads->dW_msg)
+            if ((st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, static_cast<float*>(grads->dW_msg->data), grads->dW_msg->ld)))
+                return st;
+        if (grads->db_gate) HIP_TRY(ctx, launch_fill_f32(static_cast<float*>(grads->db_gate->data), F, 0.f, s));
+        HIP_TRY(ctx, hipStreamSynchronize(s));
+        return SAGA_OK;
+    }
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
+    if ((st = stream_hoist_to_host(ctx, X, ep, n, F, 3 * F))) return st;
+    if ((st = ensure_transposed_host(ctx, g))) return st;
+    const float* H = ctx->h_hoist;                 // [Ps | M | Pd], 3F per vertex
+    const float* h_dA = ctx->h_grad;               // F per vertex
+    float* h_dH = ctx->h_grad + (size_t)n * F;     // [dPs | dM | dPd], 3F per vertex
+    const int64_t ldh = 3 * (int64_t)F;
+    {
+        // the split workspace for the largest interval there can be, so that nothing is allocated inside the pipeline;
+        // the column sums use it after a product's partial sums have been added up (same stream)
+        int64_t rps;
+        int32_t nsp;
+        gemm_tn_plan(n, F, F, &rps, &nsp);
+        const size_t need = std::max(sizeof(float) * (size_t)nsp * F * F, sizeof(float) * (size_t)colsum_slabs(n) * F);
+        if ((st = ctx->dev_alloc(&ctx->ws_splitk, need))) return st;
+    }
+    // an interval's rows of X on the device, for the parameter gradients both schedules add up per interval
+    auto x_rows = [&](int64_t row0, int64_t rows, hipStream_t on, int64_t* h2d, float** tX) -> saga_status {
+        if (saga_status e = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * (size_t)rows * F)) return e;  // intervals do not grow
+        *tX = static_cast<float*>(ctx->ws_tile.p);
+        HIP_TRY(ctx, hipMemcpy2DAsync(*tX, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * (int64_t)F * 4;
+        return SAGA_OK;
+    };
+    saga_edge_params et{};
+    et.op = SAGA_EDGE_COPY;  // the chunks carry no edge data; the edge function is named in the extras
+
+    // ---- pass 2: destination parts, over the in-edges ----
+    {
+        saga_tensor rows_t{};
+        rows_t.data = const_cast<float*>(H);
+        rows_t.rows = n;
+        rows_t.cols = 2 * F;
+        rows_t.ld = ldh;
+        rows_t.dtype = SAGA_F32;
+        rows_t.mem = SAGA_MEM_HOST;
+        saga_tensor out_t = rows_t;
+        out_t.data = h_dH + 2 * F;
+        out_t.cols = F;
+        StreamExtras ex;
+        ex.op = kGatherOpGateGrad;
+        ex.acc_width = F;
+        ex.dst_width = 2 * F;
+        ex.dst_rows = H + 2 * F;
+        ex.ld_dst = ldh;
+        ex.dst2_rows = h_dA;
+        ex.ld_dst2 = F;
+        ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
+        bool any_done = false;
+        ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
+            float* tX = nullptr;
+            if (saga_status e = x_rows(row0, rows, on, h2d, &tX)) return e;
+            if (saga_status e = param_grad(ctx, acc, F, F, tX, F, F, rows, dWg + F, lddwg, any_done ? 1 : 0, on, false)) return e;
+            if (grads->db_gate)
+                HIP_TRY(ctx, launch_dz_colsum(acc, F, nullptr, 0, SAGA_ACT_NONE, nullptr, rows, F, static_cast<float*>(ctx->ws_splitk.p),
+                                              static_cast<float*>(grads->db_gate->data), any_done ? 1 : 0, on));
+            any_done = true;
+            return SAGA_OK;
+        };
+        if ((st = streamed_forward(ctx, g, &rows_t, &et, SAGA_AGG_SUM, nullptr, &out_t, nullptr, &ex))) return st;
+    }
+
+    // ---- pass 3: source parts and dX, over the edges clustered by source ----
+    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * 2 * (size_t)F * F))) return st;
+    float* M1 = static_cast<float*>(ctx->ws_wt.p);  // [W_gs ; W_m] as a 2F x F matrix: row f of W_gs is W_gate[f][0..F)
+    const float* Wg = static_cast<const float*>(ep->W_gate->data);
+    HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, M1, F, 0, s));
+    HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr, ep->W_msg ? ep->W_msg->ld : 0, 0, F, F,
+                                     M1, F, F, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    saga_tensor rows_t{};
+    rows_t.rows = n;
+    rows_t.cols = rows_t.ld = 2 * F;
+    rows_t.dtype = SAGA_F32;
+    rows_t.mem = SAGA_MEM_HOST;
+    VertexFeed feed;
+    feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
+        // [the destination part of the gate's argument | the gradient of accum] of the vertices at the far end of the out-edges
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * 2 * (size_t)F, H + row0 * ldh + 2 * F, sizeof(float) * (size_t)ldh,
+                                      sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * 2 * (size_t)F, h_dA + row0 * F, sizeof(float) * (size_t)F,
+                                      sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * 2 * (int64_t)F * 4;
+        return SAGA_OK;
+    };
+    StreamExtras ex;
+    ex.op = kGatherOpGateBoth;
+    ex.acc_width = F;
+    ex.n_out = 2;
+    ex.dst_width = 2 * F;
+    ex.dst_rows = H;  // [Ps | M]
+    ex.ld_dst = ldh;
+    ex.self_rows = h_dH + 2 * F;  // dPd, the second operand of the last product
+    ex.ld_self = ldh;
+    ex.F_self = F;
+    ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
+    bool any_done = false;
+    ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
+        float* tX = nullptr;
+        if (saga_status e = x_rows(row0, rows, on, h2d, &tX)) return e;
+        if (saga_status e = param_grad(ctx, acc, 2 * (int64_t)F, F, tX, F, F, rows, dWg, lddwg, any_done ? 1 : 0, on, false)) return e;
+        if (grads->dW_msg)
+            if (saga_status e = param_grad(ctx, acc + F, 2 * (int64_t)F, F, tX, F, F, rows, static_cast<float*>(grads->dW_msg->data),
+                                           grads->dW_msg->ld, any_done ? 1 : 0, on, false))
+                return e;
+        any_done = true;
+        return SAGA_OK;
+    };
+    saga_tensor m1_t{}, wgd_t{};
+    m1_t.data = M1;
+    m1_t.rows = 2 * F;
+    m1_t.cols = F;
+    m1_t.ld = F;
+    m1_t.dtype = SAGA_F32;
+    m1_t.mem = SAGA_MEM_DEVICE;
+    wgd_t = *ep->W_gate;  // W_gd: the right half of W_gate, F x F with W_gate's row stride
+    wgd_t.data = const_cast<float*>(Wg) + F;
+    wgd_t.cols = F;
+    saga_vertex_params vt{};
+    vt.W = &m1_t;
+    vt.W_self = &wgd_t;
+    vt.act = SAGA_ACT_NONE;
+    saga_tensor no_dx{};
+    return streamed_forward(ctx, g->tr, &rows_t, &et, SAGA_AGG_SUM, &vt, grads->dX ? grads->dX : &no_dx, &feed, &ex);
 }
 
 saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,

@@ -263,7 +263,7 @@ struct Plan {
 
 // Device bytes a Q x P plan needs (upper bound on the chunk payload from the edge counts).
 size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t Fa, int64_t F_out, bool has_w, bool weighted, int64_t min_edges,
-                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs, bool dst_rows, int64_t F_self)
+                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs, int64_t Fd, int64_t F_self)
 {
     const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
     size_t max_chunk = 0, max_slots = 0;
@@ -274,7 +274,7 @@ size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t Fa, int6
         max_slots = std::max(max_slots, (size_t)(nnz[c] / std::max<int64_t>(min_edges, 1)) + 1);
     }
     size_t total = (size_t)Dq * Fa * 4;                // A_j
-    if (dst_rows) total += (size_t)Dq * Fa * 4;        // destination parts of the interval (gated)
+    total += (size_t)Dq * Fd * 4;                      // constant rows of the interval's destinations (gated)
     total += 2 * (size_t)Sp * F * 4;                   // V_i, double buffered
     total += 2 * max_chunk;                            // C_ij, double buffered
     total += max_slots * (size_t)Fa * 4;               // partial rows of cut columns
@@ -296,9 +296,13 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const bool has_w = vp && vp->W;
     const bool has_self = has_w && extras && (extras->self_rows || extras->self_fill);
     const int64_t F_self = has_self ? extras->F_self : 0;
-    const int64_t F_out = has_w ? vp->W->cols : Fa;
     const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
+    const int64_t n_out = extras && extras->n_out == 2 ? 2 : 1;            // accumulator rows are n_out * Fa wide
+    const int64_t Fd = extras && extras->dst_width ? extras->dst_width : Fa;  // width of the resident constant rows
+    const int64_t Fw = Fa * n_out;
+    const int64_t F_out = has_w ? vp->W->cols : Fw;
     if (n == 0) return SAGA_OK;
+    if (n_out == 2 && (!extras->op || Fd != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "two outputs need a two-row edge function");
     if (gated && (!extras || !extras->dst_rows || F != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "streamed gated call without its hoisted rows");
 
     WorkListParams wlp = work_list_params(ctx, F * 4);
@@ -335,8 +339,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 if ((P > 0 && p != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
                 count_grid(g, q, p, &nnz, &pairs);
-                const size_t need = plan_bytes(g, q, p, F, Fa, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs, gated,
-                                               F_self) +
+                const size_t need = plan_bytes(g, q, p, F, Fw, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs,
+                                               gated ? Fd : 0, F_self) +
                                     (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0) +
                                     (extras ? extras->bytes_per_dst_row * (size_t)((n + q - 1) / q) : 0);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
@@ -367,8 +371,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         const size_t c_bytes = std::max<size_t>(grid->max_chunk_bytes, 256);
         const size_t y_bytes = has_w ? (size_t)y_tile_rows * F_out * 4 : 0;
         const size_t s_bytes = has_self ? (size_t)y_tile_rows * F_self * 4 : 0;
-        const size_t want[NB] = {(size_t)Dq * Fa * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
-                                 grid->max_slots > 0 ? (size_t)grid->max_slots * Fa * 4 : 0, gated ? (size_t)Dq * Fa * 4 : 0, s_bytes, s_bytes};
+        const size_t want[NB] = {(size_t)Dq * Fw * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
+                                 grid->max_slots > 0 ? (size_t)grid->max_slots * Fw * 4 : 0, gated ? (size_t)Dq * Fd * 4 : 0, s_bytes, s_bytes};
         bool fits = true;
         for (int b = 0; b < NB; ++b) fits = fits && bufs[b]->bytes >= want[b];
         if (!fits) {
@@ -408,12 +412,12 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     int64_t n_pad = 0, k_pad = 0, ldbt = 0;
     if (has_w) {
         int64_t n_pad2 = 0, k_pad2 = 0;
-        bt_padded_shape((int32_t)F_out, (int32_t)Fa, SAGA_F32, &n_pad, &k_pad);
+        bt_padded_shape((int32_t)F_out, (int32_t)Fw, SAGA_F32, &n_pad, &k_pad);
         if (has_self) bt_padded_shape((int32_t)F_out, (int32_t)F_self, SAGA_F32, &n_pad2, &k_pad2);
         ldbt = k_pad + k_pad2;
         if ((st = ctx->dev_alloc(&ctx->ws_bt, (size_t)(n_pad * ldbt) * 4))) return st;
         HIP_TRY(ctx, launch_zero_bytes(ctx->ws_bt.p, (size_t)(n_pad * ldbt) * 4, sc));
-        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)Fa, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, ldbt, 0, sc));
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W->data, vp->W->ld, (int32_t)Fw, (int32_t)F_out, SAGA_F32, ctx->ws_bt.p, ldbt, 0, sc));
         if (has_self)
             HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, (int32_t)F_self, (int32_t)F_out, SAGA_F32,
                                                   ctx->ws_bt.p, ldbt, k_pad, sc));
@@ -424,14 +428,19 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // A_j <- identity of the accumulator, once nobody reads the buffer any more
     auto fill_a = [&](int j) -> saga_status {
         if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
-        HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * Fa, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
+        HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * Fw, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
         if (gated) {  // the destination parts of this interval, once the previous interval's kernels have let go of the buffer
             if (d_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_d_free, 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_D.p, (size_t)Fa * 4, extras->dst_rows + (int64_t)j * Dq * extras->ld_dst,
-                                          (size_t)extras->ld_dst * 4, (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+            const int64_t w1 = extras->dst2_rows ? Fa : Fd;  // columns that come from dst_rows
+            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_D.p, (size_t)Fd * 4, extras->dst_rows + (int64_t)j * Dq * extras->ld_dst,
+                                          (size_t)extras->ld_dst * 4, (size_t)w1 * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+            if (extras->dst2_rows)
+                HIP_TRY(ctx, hipMemcpy2DAsync(static_cast<float*>(ctx->st_D.p) + Fa, (size_t)Fd * 4,
+                                              extras->dst2_rows + (int64_t)j * Dq * extras->ld_dst2, (size_t)extras->ld_dst2 * 4,
+                                              (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
             HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
-            bytes_h2d += rows_of(j) * Fa * 4;
+            bytes_h2d += rows_of(j) * Fd * 4;
         }
         return SAGA_OK;
     };
@@ -479,14 +488,23 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         ga.op = op;
         ga.agg = agg;
         ga.out = A;
-        ga.ld_out = Fa;
+        ga.ld_out = Fw;
         if (gated) {  // rows [Ps | M] travel, the destination parts are resident
             ga.src2 = static_cast<const float*>(ctx->st_V[vb].p) + Fa;
             ga.ld_src2 = F;
             ga.dst = static_cast<const float*>(ctx->st_D.p);
-            ga.ld_dst = Fa;
+            ga.ld_dst = Fd;
+            if (Fd == 2 * Fa) {
+                ga.dst2 = ga.dst + Fa;
+                ga.ld_dst2 = Fd;
+            }
         }
         ga.partials = static_cast<float*>(ctx->st_partials.p);
+        if (n_out == 2) {
+            ga.out2 = A + Fa;
+            ga.ld_out2 = Fw;
+            ga.partials2 = ga.partials + (size_t)m.n_slots * Fa;
+        }
         ga.accumulate = 1;
         ga.xcd_remap = ctx->opt_xcd_remap;
         ga.mma = ctx->opt_mma;
@@ -499,9 +517,14 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ca.F = (int32_t)Fa;
             ca.agg = agg;
             ca.out = A;
-            ca.ld_out = Fa;
+            ca.ld_out = Fw;
             ca.accumulate = 1;
             HIP_TRY(ctx, launch_combine(ca, sc));
+            if (n_out == 2) {
+                ca.partials = ga.partials2;
+                ca.out = ga.out2;
+                HIP_TRY(ctx, launch_combine(ca, sc));
+            }
         }
         HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sc));
         used[b] = true;
@@ -515,7 +538,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             HIP_TRY(ctx, hipEventRecord(grid->ev_d_free, sc));
             d_busy = true;
         }
-        if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * Fa, sc));
+        if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * Fw, sc));
         if (extras && extras->after_gather)
             if (saga_status hs = extras->after_gather(v0, rows, A, sc, &bytes_h2d)) return hs;
         if (!Yh) {  // nobody wants the rows (a backward pass that only needs what after_gather adds up)
@@ -526,9 +549,9 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         if (!has_w) {
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
             HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
-            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)Fa * 4, (size_t)Fa * 4, (size_t)rows,
+            HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)Fw * 4, (size_t)Fw * 4, (size_t)rows,
                                           hipMemcpyDeviceToHost, sout));
-            bytes_d2h += rows * Fa * 4;
+            bytes_d2h += rows * Fw * 4;
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
             a_busy = true;
             return SAGA_OK;
@@ -555,8 +578,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 ge.lda2 = F_self;
                 ge.K2 = (int32_t)F_self;
             }
-            ge.A = A + r0 * Fa;
-            ge.lda = Fa;
+            ge.A = A + r0 * Fw;
+            ge.lda = Fw;
             ge.Bt = ctx->ws_bt.p;
             ge.ldbt = ldbt;
             ge.bias = vp->bias ? static_cast<const float*>(vp->bias->data) : nullptr;
@@ -564,7 +587,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ge.ldc = F_out;
             ge.M = tr;
             ge.N = (int32_t)F_out;
-            ge.K = (int32_t)Fa;
+            ge.K = (int32_t)Fw;
             ge.dtype = ge.out_dtype = SAGA_F32;
             ge.act = vp->act;
             HIP_TRY(ctx, launch_gemm(ge, sc));

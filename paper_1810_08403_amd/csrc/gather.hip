@@ -1055,7 +1055,7 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {
-        if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM || a.accumulate))) return hipErrorInvalidValue;
+        if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM))) return hipErrorInvalidValue;
         if (a.op == kGatherOpMaxGrad && a.agg != SAGA_AGG_SUM) return hipErrorInvalidValue;
         vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst) && (a.ld_src2 * 4) % 16 == 0 && aligned16(a.src2);
         if (grad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);

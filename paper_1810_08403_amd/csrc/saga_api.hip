@@ -1116,11 +1116,11 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         // streamed: the layer's tensors live in host memory, parameters and their gradients on the device
         auto f32_at = [](const saga_tensor* t, int32_t mem) { return tensor_ok(t) && t->mem == mem && t->dtype == SAGA_F32; };
         if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
-        const bool pool_h = ep->op == SAGA_EDGE_POOL;
-        if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT && !pool_h)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers COPY, MUL_WEIGHT and POOL messages");
-        const bool max_or_pool = pool_h || agg == SAGA_AGG_MAX;
-        if (max_or_pool && vp->W_self)
+        const bool pool_h = ep->op == SAGA_EDGE_POOL, gated_h = ep->op == SAGA_EDGE_GATED;
+        if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
+        if (gated_h && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
+        const bool max_or_pool = pool_h || (agg == SAGA_AGG_MAX && !gated_h);
+        if ((max_or_pool || gated_h) && vp->W_self)
             return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers W_self only with sum over COPY / MUL_WEIGHT messages");
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
@@ -1143,8 +1143,24 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         } else if (grads->dW_pool || grads->db_pool) {
             return ctx->fail(SAGA_ERR_INVALID_ARG, "pool gradients are for POOL layers only");
         }
-        if (max_or_pool && (!X || !f32_at(X, SAGA_MEM_HOST) || X->rows != n || X->cols != F))
+        if ((max_or_pool || gated_h) && (!X || !f32_at(X, SAGA_MEM_HOST) || X->rows != n || X->cols != F))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer needs X as a host n x F fp32 tensor");
+        if (gated_h) {
+            if (!ep->W_gate || !f32_at(ep->W_gate, SAGA_MEM_DEVICE) || ep->W_gate->rows != F || ep->W_gate->cols != 2 * F)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_gate must be a device F x 2F fp32 tensor");
+            if (ep->b_gate && (!f32_at(ep->b_gate, SAGA_MEM_DEVICE) || ep->b_gate->rows * ep->b_gate->cols != F))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "b_gate must be F fp32 values on the device");
+            if (ep->W_msg && (!f32_at(ep->W_msg, SAGA_MEM_DEVICE) || ep->W_msg->rows != F || ep->W_msg->cols != F))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_msg must be a device F x F fp32 tensor");
+            if (!grads->dW_gate || !f32_at(grads->dW_gate, SAGA_MEM_DEVICE) || grads->dW_gate->rows != F || grads->dW_gate->cols != 2 * F)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_gate must be a device F x 2F fp32 tensor");
+            if (grads->db_gate && (!f32_at(grads->db_gate, SAGA_MEM_DEVICE) || grads->db_gate->rows * grads->db_gate->cols != F))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->db_gate must be F fp32 values on the device");
+            if (grads->dW_msg && (!ep->W_msg || !f32_at(grads->dW_msg, SAGA_MEM_DEVICE) || grads->dW_msg->rows != F || grads->dW_msg->cols != F))
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_msg must be a device F x F fp32 tensor, and needs W_msg");
+        } else if (grads->dW_gate || grads->db_gate || grads->dW_msg) {
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "gate gradients are for GATED layers only");
+        }
         if (!f32_at(A, SAGA_MEM_HOST) || A->rows != n || A->cols != Fmh)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need A as a host n x Fm fp32 tensor");
         if (!f32_at(dY, SAGA_MEM_HOST) || dY->rows != n || dY->cols != Fo)
@@ -1167,12 +1183,11 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         } else if (grads->dW_self) {
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
         }
-        if (grads->dW_gate || grads->db_gate || grads->dW_msg)
-            return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
-        const saga_status sst = max_or_pool
+        const saga_status sst = gated_h ? streamed_gated_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads)
+                                : max_or_pool
                                     ? streamed_max_pool_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
                                     : streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
         if (sst != SAGA_OK) {  // host tensors are the caller's again when this returns

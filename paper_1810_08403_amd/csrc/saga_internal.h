@@ -327,6 +327,9 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 // backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
+saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                    const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                                    const saga_layer_grads* grads);
 saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                                        const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                                        const saga_layer_grads* grads);
@@ -354,6 +357,13 @@ struct StreamExtras {
     int64_t ld_dst = 0;                // beside the accumulators of the resident interval (gated; backward of a max Gather)
     int32_t op = 0;                    // 0: ep->op; else an internal edge function of the propagation kernel whose rows
                                        // [x | m] travel (2 * acc_width wide) and whose constant row is dst_rows
+    // the gate-gradient edge functions take two constant rows per destination: dst_width = 2 * acc_width makes the
+    // resident rows [c1 | c2]; they come from dst_rows alone (its rows are then 2 * acc_width wide) or, with dst2_rows,
+    // c1 from dst_rows and c2 from dst2_rows
+    int32_t dst_width = 0;             // 0: acc_width
+    const float* dst2_rows = nullptr;  // host, n rows of acc_width values, ld_dst2 elements apart
+    int64_t ld_dst2 = 0;
+    int32_t n_out = 1;                 // 2: the edge function has two outputs; accumulator rows are [out | out2]
     // called once per destination interval after its last chunk, before ApplyVertex, with the interval's accumulator
     // rows on the device (compute stream s): the backward pass of pooled messages goes through the sigmoid there
     std::function<saga_status(int64_t row0, int64_t rows, float* acc, hipStream_t s, int64_t* h2d)> after_gather;

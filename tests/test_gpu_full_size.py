@@ -337,6 +337,52 @@ def test_streamed_applications_under_one_gib_at_full_size(app):
     ctx.destroy()
 
 
+def test_config4_streamed_gated_backward_under_two_gib_equals_the_resident_one():
+    """Configuration 4's gated layer backwards from host memory through a 2 GiB device budget, against the device-resident
+    backward pass of the same layer (itself checked against the oracle's sampled rows above)."""
+    import paper_1810_08403_amd as saga
+    wl = si.workload(4, device="cuda")
+    g = wl.graph
+    n, F = wl.X.shape
+    kw = dict(edge_op="gated", W_gate=wl.W_gate, b_gate=wl.b_gate, W_msg=wl.W_msg, act="relu")
+    z = lambda *s: torch.full(s, float("nan"), device="cuda")
+    names = ("dW", "dbias", "dW_gate", "db_gate", "dW_msg")
+    ctx = saga.Context(0)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
+    ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
+    dY = si.normal_features(n, 128, 31).cuda()
+    ref = dict(dW=z(F, 128), dbias=z(128), dW_gate=z(F, 2 * F), db_gate=z(F), dW_msg=z(F, F), dX=z(n, F))
+    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y, dX=ref["dX"], dbias=ref["dbias"], dW_gate=ref["dW_gate"],
+                       db_gate=ref["db_gate"], dW_msg=ref["dW_msg"], **kw)
+    torch.cuda.synchronize()
+    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y, dY=dY).items()}
+    ref = {k: v.cpu() for k, v in ref.items()}
+    graph.destroy()
+    ctx.destroy()
+    del Y, A, dY
+    torch.cuda.empty_cache()
+    budget = 2 << 30
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    hg = ctx.graph_create_csc(n, g.col_ptr.cpu(), g.row_idx.cpu())
+    pin = lambda t: t.contiguous().pin_memory()
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    got = dict(dW=z(F, 128), dbias=z(128), dW_gate=z(F, 2 * F), db_gate=z(F), dW_msg=z(F, F))
+    ctx.layer_backward(hg, pin(host["A"]), pin(host["dY"]), wl.W, got["dW"], X=pin(host["X"]), Y=pin(host["Y"]), dX=dX_h,
+                       dbias=got["dbias"], dW_gate=got["dW_gate"], db_gate=got["db_gate"], dW_msg=got["dW_msg"], **kw)
+    torch.cuda.synchronize()
+    assert ctx.peak_device_bytes() <= budget
+    for name in names:   # the same sums in another grouping: close in the norm of each tensor
+        err = (got[name].cpu().double() - ref[name].double()).abs().max().item()
+        assert err <= 1e-4 * ref[name].abs().max().item(), (name, err)
+    err = (dX_h.double() - ref["dX"].double()).abs().max().item()
+    assert err <= 1e-4 * ref["dX"].abs().max().item(), ("dX", err)
+    t = ctx.get_timings()
+    print(f"streamed gated backward: {t['ms_wall_streamed']:.0f} ms in the two schedules, H2D {t['bytes_h2d'] / 1e9:.1f} GB, "
+          f"D2H {t['bytes_d2h'] / 1e9:.1f} GB, peak {ctx.peak_device_bytes() / 1e9:.2f} GB")
+    ctx.destroy()
+
+
 def test_mpgcn_rmat20_streamed_backward_under_two_gib_equals_the_resident_one():
     """The max-pooling layer's backward pass from host memory through a 2 GiB device budget at R-MAT 20, against the
     device-resident backward pass of the same layer (whose maxima decisions it must reproduce: both recompute the pooled

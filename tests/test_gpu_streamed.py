@@ -369,6 +369,54 @@ def test_streamed_sum_over_pooled_messages_backward():
     ctx.destroy()
 
 
+@pytest.mark.parametrize("F,Fo,act,with_b,with_msg,Q,P", [(16, 12, "relu", True, True, 2, 3), (20, 8, "none", False, False, 1, 4),
+                                                          (64, 32, "sigmoid", True, True, 3, 3), (7, 5, "relu", True, False, 2, 2)])
+def test_streamed_gated_backward_matches_oracle(F, Fo, act, with_b, with_msg, Q, P):
+    """Backward pass of a gated layer from host memory: tile pass, the chunk schedule over the in-edges (destination
+    parts of the gate gradient), the chunk schedule over the edges clustered by source (source parts, both at once,
+    and dX as its last product), per-vertex products and gradients passing through pinned memory in between."""
+    import oracle
+    import paper_1810_08403_amd as saga
+    wl = si.workload(4, scale=11, f_in=F, f_out=Fo)
+    g = wl.graph
+    n = g.n
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    bias = si.uniform_pm(Fo, 0.3, 5)
+    dY = si.normal_features(n, Fo, 99)
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy() if with_b else None, W_msg=wl.W_msg.numpy() if with_msg else None)
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
+    bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), bias=bias.numpy(), act=act, **okw)
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", Q), ("src_intervals", P), ("bwd_tile_rows", 700)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    pin = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).pin_memory()
+    X_h, A_h, Y_h, dY_h = wl.X.clone().pin_memory(), pin(fwd["A"]), pin(fwd["Y"]), dY.clone().pin_memory()
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    out = dict(dW=nan(F, Fo), dbias=nan(Fo), dW_gate=nan(F, 2 * F), db_gate=nan(F) if with_b else None, dW_msg=nan(F, F) if with_msg else None)
+    kw = dict(X=X_h, Y=Y_h, edge_op="gated", act=act, bias=bias.cuda(), W_gate=wl.W_gate.cuda(),
+              b_gate=wl.b_gate.cuda() if with_b else None, W_msg=wl.W_msg.cuda() if with_msg else None)
+    for rep, want_dx in enumerate([True, True, False]):            # the second call reuses both grids; the third has no dX
+        for t in out.values():
+            if t is not None:
+                t.fill_(float("nan"))
+        dX_h.fill_(float("nan"))
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), out["dW"], dX=dX_h if want_dx else None, dbias=out["dbias"],
+                           dW_gate=out["dW_gate"], db_gate=out["db_gate"], dW_msg=out["dW_msg"], **kw)
+        what = f"streamed gated backward {F}->{Fo} {act} {Q}x{P} call {rep}"
+        for name in ("dW", "dbias", "dW_gate", "db_gate", "dW_msg"):
+            if out[name] is not None:
+                assert_sum_close(out[name].cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " " + name)
+        if want_dx:
+            assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    # a forward call on the same graph still works afterwards
+    Yf = torch.empty(n, Fo).pin_memory()
+    ctx.layer_forward(graph, X_h, Yf, W=wl.W.cuda(), **{k: v for k, v in kw.items() if k not in ("X", "Y")})
+    assert_sum_close(Yf.numpy(), fwd["Y"], fwd["Y_abs"], TOL_F32, "forward after backward")
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("Q,P", [(1, 3), (2, 2), (3, 5)])
 @pytest.mark.parametrize("agg", ["sum", "max"])
 def test_streamed_gated_layer(Q, P, agg):
