@@ -435,6 +435,7 @@ def with_link_ceiling(roofline, torch):
 def bench_streamed_app(args, wl):
     """The gated, CommNet or max-pooling layer with X, Y and the graph in host memory; every transfer is timed."""
     import torch
+    import saga_inputs as si
     import paper_1810_08403_amd as saga
     g = wl.graph
     n, nnz = g.n, g.nnz
@@ -466,16 +467,62 @@ def bench_streamed_app(args, wl):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     tm = ctx.get_timings()
     link = (tm["bytes_h2d"] + tm["bytes_d2h"]) / steps / (ms * 1e-3) / 1e9
-    print(json.dumps({"metric": "fused_saga_layer_throughput", "value": round(nnz / (ms * 1e-3) / 1e9, 4), "unit": "GTEPS", "n_gpus": 1,
-                      "steps": steps, "warmup": 1, "ms_per_step": round(ms, 2), "higher_is_better": True, "scaling": "weak",
-                      "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": wl.name + "_streamed", "n_vertices": n, "nnz": nnz, "edge_op": wl.edge_op, "agg": args.agg,
-                                 "device_budget_bytes": budget, "plan": [tm["plan_dst_intervals"], tm["plan_src_intervals"]],
-                                 "peak_device_bytes": ctx.peak_device_bytes(), "inputs": "pinned host memory, transfers timed"},
-                      "roofline": with_link_ceiling(
-                          {"bound": "host_link", "achieved": round(link, 2), "peak": 128.0, "unit": "GB/s", "frac": round(link / 128.0, 4),
-                           "traffic": None, "h2d_bytes_per_step": tm["bytes_h2d"] // steps, "d2h_bytes_per_step": tm["bytes_d2h"] // steps},
-                          torch)}))
+    out = {"metric": "fused_saga_layer_throughput", "value": round(nnz / (ms * 1e-3) / 1e9, 4), "unit": "GTEPS", "n_gpus": 1,
+           "steps": steps, "warmup": 1, "ms_per_step": round(ms, 2), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl.name + "_streamed", "n_vertices": n, "nnz": nnz, "edge_op": wl.edge_op, "agg": args.agg,
+                      "device_budget_bytes": budget, "plan": [tm["plan_dst_intervals"], tm["plan_src_intervals"]],
+                      "peak_device_bytes": ctx.peak_device_bytes(), "inputs": "pinned host memory, transfers timed"},
+           "roofline": with_link_ceiling(
+               {"bound": "host_link", "achieved": round(link, 2), "peak": 128.0, "unit": "GB/s", "frac": round(link / 128.0, 4),
+                "traffic": None, "h2d_bytes_per_step": tm["bytes_h2d"] // steps, "d2h_bytes_per_step": tm["bytes_d2h"] // steps},
+               torch)}
+    if args.backward:
+        # A and Y of the same layer from a device-resident forward call on a context of its own (the streamed call does
+        # not return the Gather output), moved to pinned host memory; then the streamed backward pass, every transfer timed
+        c2 = saga.Context(0)
+        g2 = c2.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        fm = wl.W.shape[0]
+        Yd, Ad = torch.empty(n, wl.W.shape[1], device="cuda"), torch.empty(n, fm, device="cuda")
+        c2.layer_forward(g2, wl.X.float().cuda(), Yd, accum_out=Ad, **kw)
+        torch.cuda.synchronize()
+        A_h, Y_h = Ad.cpu().pin_memory(), Yd.cpu().pin_memory()
+        g2.destroy()
+        c2.destroy()
+        del Yd, Ad
+        torch.cuda.empty_cache()
+        dY_h = si.normal_features(n, wl.W.shape[1], 55).pin_memory()
+        dX_h = torch.empty(n, X.shape[1]).pin_memory()
+        z = lambda *shape: torch.empty(*shape, device="cuda")
+        gk = dict(dX=dX_h, dbias=z(wl.W.shape[1]))
+        if wl.edge_op == "gated":
+            f = X.shape[1]
+            gk.update(dW_gate=z(f, 2 * f), db_gate=z(f), dW_msg=z(f, f))
+        if wl.edge_op == "pool":
+            gk.update(dW_pool=z(fm, X.shape[1]), db_pool=z(fm))
+        if wl.W_self is not None:
+            gk["dW_self"] = z(*wl.W_self.shape)
+        dW = z(*wl.W.shape)
+        bkw = {k: v for k, v in kw.items() if k != "W"}
+        def bstep():
+            ctx.layer_backward(graph, A_h, dY_h, kw["W"], dW, X=X, Y=Y_h, **bkw, **gk)
+        t0 = time.time()
+        bstep()                                    # builds the edge order by source and its chunk grid
+        torch.cuda.synchronize()
+        t_first = time.time() - t0
+        ctx.reset_timings()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            bstep()
+        torch.cuda.synchronize()
+        msb = (time.perf_counter() - t0) * 1e3 / steps
+        tb = ctx.get_timings()
+        out["backward"] = {"ms_per_step": round(msb, 2), "gteps": round(nnz / (msb * 1e-3) / 1e9, 4), "first_call_s": round(t_first, 2),
+                           "h2d_bytes_per_step": tb["bytes_h2d"] // steps, "d2h_bytes_per_step": tb["bytes_d2h"] // steps,
+                           "link_GBps": round((tb["bytes_h2d"] + tb["bytes_d2h"]) / steps / (msb * 1e-3) / 1e9, 2),
+                           "peak_device_bytes": ctx.peak_device_bytes()}
+    print(json.dumps(out))
 
 
 def bench_streamed(args):

@@ -318,19 +318,29 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const bool same_grid = g->grid && g->grid->wlp.min_edges == wlp.min_edges && g->grid->wlp.cut_degree == wlp.cut_degree &&
                            g->grid->wlp.stripe_rows == wlp.stripe_rows && g->grid->wlp.team == wlp.team &&
                            g->grid->weighted == weighted;
-    if (same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P)) {
+    // what the context holds apart from the schedule's own buffers (packed weights, other graphs) counts too
+    size_t held = ctx->cur_bytes;
+    for (const DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
+                            &ctx->st_partials, &ctx->st_D, &ctx->st_S[0], &ctx->st_S[1]})
+        held -= std::min(held, b->bytes);
+    std::vector<int64_t> nnz, pairs;
+    auto need_for = [&](int q, int p) {
+        count_grid(g, q, p, &nnz, &pairs);
+        return plan_bytes(g, q, p, F, Fw, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs, gated ? Fd : 0, F_self) +
+               (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0) +
+               (extras ? extras->bytes_per_dst_row * (size_t)((n + q - 1) / q) : 0);
+    };
+    // the grid of an earlier call is kept if it was made for the same tunables and, under a budget, this call fits
+    // it too (a backward pass holds more per vertex than the forward pass whose grid it finds)
+    bool reuse = same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P);
+    if (reuse && ctx->budget > 0 && Q == 0 && P == 0 && need_for(g->grid->Q, g->grid->P) + held > ctx->budget) reuse = false;
+    if (reuse) {
         Q = g->grid->Q;
         P = g->grid->P;
     } else if (Q > 0 && P > 0) {
         if (Q > n || P > n) return ctx->fail(SAGA_ERR_INVALID_ARG, "more intervals than vertices");
     } else {
         bool found = false;
-        std::vector<int64_t> nnz, pairs;
-        // what the context holds apart from the schedule's own buffers (packed weights, other graphs) counts too
-        size_t held = ctx->cur_bytes;
-        for (const DevBuf* b : {&ctx->st_A, &ctx->st_V[0], &ctx->st_V[1], &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1],
-                                &ctx->st_partials, &ctx->st_D, &ctx->st_S[0], &ctx->st_S[1]})
-            held -= std::min(held, b->bytes);
         const int qs[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 256, 512, 1024};
         const int ps[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
         for (int q : qs) {
@@ -338,11 +348,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             for (int p : ps) {
                 if ((P > 0 && p != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
-                count_grid(g, q, p, &nnz, &pairs);
-                const size_t need = plan_bytes(g, q, p, F, Fw, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs,
-                                               gated ? Fd : 0, F_self) +
-                                    (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0) +
-                                    (extras ? extras->bytes_per_dst_row * (size_t)((n + q - 1) / q) : 0);
+                const size_t need = need_for(q, p);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
                 if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need + held <= ctx->budget)) {
                     Q = q;
@@ -373,8 +379,10 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         const size_t s_bytes = has_self ? (size_t)y_tile_rows * F_self * 4 : 0;
         const size_t want[NB] = {(size_t)Dq * Fw * 4, (size_t)Sp * F * 4, (size_t)Sp * F * 4, c_bytes, c_bytes, y_bytes, y_bytes,
                                  grid->max_slots > 0 ? (size_t)grid->max_slots * Fw * 4 : 0, gated ? (size_t)Dq * Fd * 4 : 0, s_bytes, s_bytes};
+        // under a budget a buffer left by another plan must not be larger than this plan counted either
         bool fits = true;
-        for (int b = 0; b < NB; ++b) fits = fits && bufs[b]->bytes >= want[b];
+        for (int b = 0; b < NB; ++b)
+            fits = fits && bufs[b]->bytes >= want[b] && (ctx->budget == 0 || bufs[b]->bytes <= round_up(want[b], 256));
         if (!fits) {
             // another plan left its buffers: start from nothing, so that this plan's own sizes are what counts against the budget
             for (DevBuf* b : bufs) ctx->dev_free(b);
