@@ -333,7 +333,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // the grid of an earlier call is kept if it was made for the same tunables and, under a budget, this call fits
     // it too (a backward pass holds more per vertex than the forward pass whose grid it finds)
     bool reuse = same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P);
-    if (reuse && ctx->budget > 0 && Q == 0 && P == 0 && need_for(g->grid->Q, g->grid->P) + held > ctx->budget) reuse = false;
+    if (reuse && ctx->budget > 0 && (Q == 0 || P == 0) && need_for(g->grid->Q, g->grid->P) + held > ctx->budget) reuse = false;
     if (reuse) {
         Q = g->grid->Q;
         P = g->grid->P;
@@ -461,7 +461,10 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         // copy stream: wait until the kernels that last read this buffer pair are done
         if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
         if (load_v) {
-            if (vb != b && used[vb]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[vb], 0));
+            // a source buffer chosen by the caller (destination order innermost) was last read by the kernels of the
+            // interval before the previous one, which may be the step just before this one when an interval had no
+            // edges at all: wait for both buffer pairs then
+            if (used[1 - b] && (vb != b || vbuf >= 0)) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[1 - b], 0));
             if (feed) {
                 if (saga_status fs = feed->fill(s0, srows, static_cast<float*>(ctx->st_V[vb].p), sin, !seen[(size_t)i], &bytes_h2d))
                     return fs;

@@ -380,10 +380,6 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
     return SAGA_OK;
 }
 
-// A streamed layer of any of the four programs. Linear layers go straight to the chunk schedule. Layers whose ApplyEdge has
-// a per-vertex part (Section 3.2) first stream X through that product, tile by tile, into pinned host memory held by
-// the context (the paper's dataflow does the same when the hoisted products of a big graph do not fit the device:
-// they become vertex data of their own), then run the schedule on those rows.
 // The per-vertex products of a gated or pooled layer (Section 3.2) for every vertex of a host-resident X, tile by tile
 // through the device into pinned host memory (ctx->h_hoist, n rows of Fh values): [Ps | M | Pd] (Fh = 3F) or the pooled
 // rows sigmoid(X W_pool^T + b) (Fh = F_pool). Returns after the last copy has arrived.
@@ -434,6 +430,10 @@ saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga
     return SAGA_OK;
 }
 
+// A streamed layer of any of the four programs. Linear layers go straight to the chunk schedule. Layers whose ApplyEdge has
+// a per-vertex part (Section 3.2) first stream X through that product, tile by tile, into pinned host memory held by
+// the context (the paper's dataflow does the same when the hoisted products of a big graph do not fit the device:
+// they become vertex data of their own), then run the schedule on those rows.
 static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
                                   const saga_vertex_params* vp, saga_tensor* Y)
 {

@@ -543,3 +543,30 @@ def test_forward_and_backward_alternate_under_one_budget():
         assert ctx.peak_device_bytes() <= budget, ("backward", rep, ctx.peak_device_bytes(), budget, plans)
     assert all(q * p > 1 for q, p in plans), plans
     ctx.destroy()
+
+
+@pytest.mark.parametrize("schedule", [0, 1, 2])
+def test_source_intervals_without_out_edges(schedule):
+    """Whole source intervals may have no out-edges (the schedule then skips them). With the destination order
+    innermost a source buffer is then reused one step after the kernels that last read it, not two."""
+    import dataclasses
+    wl0 = si.workload(5, scale=12, edge_factor=24, f_in=32, f_out=24)
+    g0 = wl0.graph
+    n, P = g0.n, 8
+    Sp = (n + P - 1) // P
+    dst = g0.dst_of_edges()
+    src = g0.row_idx.long()
+    keep = ~torch.isin(torch.div(src, Sp, rounding_mode="floor"), torch.tensor([2, 4, 7]))
+    g = si.build_csc(n, src[keep], dst[keep])
+    wl = dataclasses.replace(wl0, graph=g, edge_weight=si.gcn_edge_weights(g0)[keep].contiguous())
+    assert g.nnz == int(keep.sum())
+    with new_context(dst_intervals=2, src_intervals=P, schedule=schedule) as ctx:
+        graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+        graph.set_edge_data(wl.edge_weight)
+        for rep in range(2):
+            ref_max = run_oracle(wl, agg="max", with_vertex=False)
+            A = _streamed(ctx, wl, graph, "max", with_vertex=False)
+            assert_bit_equal(A, ref_max["A"], f"max Gather, schedule {schedule}, call {rep}")
+            ref = run_oracle(wl, agg="sum")
+            Y = _streamed(ctx, wl, graph, "sum")
+            assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"sum layer, schedule {schedule}, call {rep}")
