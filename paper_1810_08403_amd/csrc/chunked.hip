@@ -261,18 +261,24 @@ struct Plan {
     size_t bytes;
 };
 
-// Device bytes a Q x P plan needs (upper bound on the chunk payload from the edge counts).
-size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t Fa, int64_t F_out, bool has_w, bool weighted, int64_t min_edges,
-                  int64_t y_tile_rows, const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs, int64_t Fd, int64_t F_self)
+// Upper bounds on the largest chunk payload and the most partial rows of a tiling, from its edge counts.
+void chunk_bounds(const std::vector<int64_t>& nnz, const std::vector<int64_t>& pairs, bool weighted, int64_t min_edges, size_t* max_chunk,
+                  size_t* max_slots)
 {
-    const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
-    size_t max_chunk = 0, max_slots = 0;
+    *max_chunk = *max_slots = 0;
     for (size_t c = 0; c < nnz.size(); ++c) {
         const size_t pieces = (size_t)(pairs[c] + nnz[c] / std::max<int64_t>(min_edges, 1));
         const size_t b = 16 * pieces + 16 * (pieces / 2 + 1) + (weighted ? 8 : 4) * (size_t)nnz[c] + 4 * 256;
-        max_chunk = std::max(max_chunk, b);
-        max_slots = std::max(max_slots, (size_t)(nnz[c] / std::max<int64_t>(min_edges, 1)) + 1);
+        *max_chunk = std::max(*max_chunk, b);
+        *max_slots = std::max(*max_slots, (size_t)(nnz[c] / std::max<int64_t>(min_edges, 1)) + 1);
     }
+}
+
+// Device bytes a Q x P plan needs, given its largest chunk payload and its most partial rows.
+size_t plan_bytes(const saga_graph* g, int Q, int P, int64_t F, int64_t Fa, int64_t F_out, bool has_w, int64_t y_tile_rows, size_t max_chunk,
+                  size_t max_slots, int64_t Fd, int64_t F_self)
+{
+    const int64_t Dq = (g->n + Q - 1) / Q, Sp = (g->n + P - 1) / P;
     size_t total = (size_t)Dq * Fa * 4;                // A_j
     total += (size_t)Dq * Fd * 4;                      // constant rows of the interval's destinations (gated)
     total += 2 * (size_t)Sp * F * 4;                   // V_i, double buffered
@@ -324,16 +330,23 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                             &ctx->st_partials, &ctx->st_D, &ctx->st_S[0], &ctx->st_S[1]})
         held -= std::min(held, b->bytes);
     std::vector<int64_t> nnz, pairs;
-    auto need_for = [&](int q, int p) {
-        count_grid(g, q, p, &nnz, &pairs);
-        return plan_bytes(g, q, p, F, Fw, F_out, has_w, weighted, wlp.min_edges, tile_rows_for(q), nnz, pairs, gated ? Fd : 0, F_self) +
+    auto need_of = [&](int q, int p, size_t max_chunk, size_t max_slots) {
+        return plan_bytes(g, q, p, F, Fw, F_out, has_w, tile_rows_for(q), max_chunk, max_slots, gated ? Fd : 0, F_self) +
                (feed ? feed->bytes_per_row * (size_t)((n + p - 1) / p) : 0) +
                (extras ? extras->bytes_per_dst_row * (size_t)((n + q - 1) / q) : 0);
+    };
+    auto need_for = [&](int q, int p) {  // a tiling that does not exist yet: one pass over the edges for its counts
+        size_t max_chunk, max_slots;
+        count_grid(g, q, p, &nnz, &pairs);
+        chunk_bounds(nnz, pairs, weighted, wlp.min_edges, &max_chunk, &max_slots);
+        return need_of(q, p, max_chunk, max_slots);
     };
     // the grid of an earlier call is kept if it was made for the same tunables and, under a budget, this call fits
     // it too (a backward pass holds more per vertex than the forward pass whose grid it finds)
     bool reuse = same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P);
-    if (reuse && ctx->budget > 0 && (Q == 0 || P == 0) && need_for(g->grid->Q, g->grid->P) + held > ctx->budget) reuse = false;
+    if (reuse && ctx->budget > 0 && (Q == 0 || P == 0) &&
+        need_of(g->grid->Q, g->grid->P, g->grid->max_chunk_bytes, (size_t)g->grid->max_slots) + held > ctx->budget)
+        reuse = false;  // (the existing tiling's payload sizes are known exactly: no pass over the edges on this path)
     if (reuse) {
         Q = g->grid->Q;
         P = g->grid->P;
