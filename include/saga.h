@@ -253,9 +253,8 @@ typedef struct saga_layer_grads {
  * X and A are required; A must be the accum_out of the forward call on the same inputs, or
  * no message will compare equal.
  *
- * Streamed calls (a SAGA_MEM_HOST graph, fp32; sum over COPY / MUL_WEIGHT messages with or
- * without W_self, max over COPY / MUL_WEIGHT messages, sum or max over POOL messages, sum over
- * GATED messages): A, Y, dY,
+ * Streamed calls (a SAGA_MEM_HOST graph, fp32; sum or max over COPY / MUL_WEIGHT messages, sum
+ * or max over POOL messages, sum over GATED messages, each with or without W_self): A, Y, dY,
  * grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST tensors (pinned
  * recommended), the parameters and their gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
  * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
@@ -279,8 +278,11 @@ typedef struct saga_layer_grads {
  * half and of db_gate), then the schedule over the edges clustered by source (rows
  * [Pd | gradient of accum] travel, [Ps | M] are the constants, both source-side sums at once; per
  * interval the shares of dW_gate's left half and of dW_msg; the last product is
- * dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd). Every transfer goes through the context's device
- * budget like in saga_layer_forward.
+ * dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd). In these layers a W_self term is handled like in the
+ * linear ones: dW_self is added tile by tile with dW, and dZ W_self^T is a second operand pair of
+ * the product that ends the last pass (beside the identity for a plain max Gather, W_pool for
+ * pooled rows, and appended to dPd W_gd for gated ones). Every transfer goes through the
+ * context's device budget like in saga_layer_forward.
  *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self, act NONE or
  * RELU): X is not

@@ -16,7 +16,8 @@
 //     gradient of accum passing through pinned host memory between a tile pass and the
 //     schedule, and a per-interval finish on the device; gated layers run the schedule
 //     twice (in-edges, then edges by source), their per-vertex products and gradients
-//     passing through pinned memory as well.
+//     passing through pinned memory as well. In all of them a W_self term adds its
+//     gradient tile by tile and its share of dX inside the schedule's last product.
 #include <cstring>
 
 #include "saga_internal.h"
@@ -769,6 +770,37 @@ static saga_status streamed_param_grads(saga_ctx* ctx, int64_t n, const saga_ten
     return SAGA_OK;
 }
 
+// The second operand rows of a streamed backward pass's last product, for a layer with W_self: tile by tile,
+// [pre | dZ] with dZ formed from the tile's rows of dY (and Y, through the activation's derivative; the Y tile passes
+// through ctx->ws_dz, max_rows x Fo floats, which the caller allocates) and pre an optional block of pre_w columns
+// copied from host rows. The vertex's own partial gradient is then dZ W_self^T inside that product.
+static std::function<saga_status(int64_t, int64_t, float*, hipStream_t, int64_t*)>
+own_rows_fill(saga_ctx* ctx, const saga_tensor* dY, const saga_tensor* Y, int32_t act, int32_t Fo, const float* pre_rows, int64_t ld_pre,
+              int32_t pre_w, int64_t max_rows)
+{
+    return [=](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+        auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
+        const int64_t ldd = (int64_t)pre_w + Fo;
+        if (rows > max_rows) return ctx->fail(SAGA_ERR_INTERNAL, "own-row tile larger than planned");
+        if (pre_w > 0) {
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)ldd, pre_rows + row0 * ld_pre, sizeof(float) * (size_t)ld_pre,
+                                          sizeof(float) * (size_t)pre_w, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)pre_w * 4;
+        }
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst + pre_w, sizeof(float) * (size_t)ldd, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
+                                      sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * (int64_t)Fo * 4;
+        if (act != SAGA_ACT_NONE) {
+            float* tY = static_cast<float*>(ctx->ws_dz.p);
+            HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_of_t(Y, row0), sizeof(float) * (size_t)Y->ld,
+                                          sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)Fo * 4;
+            HIP_TRY(ctx, launch_dz_colsum(dst + pre_w, ldd, tY, Fo, act, dst + pre_w, rows, Fo, nullptr, nullptr, 0, on, ldd));
+        }
+        return SAGA_OK;
+    };
+}
+
 // Streamed backward pass of a layer with the max accumulator (COPY, MUL_WEIGHT or POOL messages) or with pooled messages
 // under the sum accumulator; X, A, Y, dY and dX in host memory. Three passes:
 //   1. tiles of rows: dZ, dW += A^T dZ, dbias (dW_self), and the gradient of accum dZ W^T out to pinned host memory;
@@ -847,12 +879,40 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         rows_t.cols = rows_t.ld = Fm;
     }
     saga_vertex_params vt{};
-    saga_tensor wp{};
+    saga_tensor wp{}, wst_t{};
+    vt.act = SAGA_ACT_NONE;
+    const bool with_self = vp->W_self != nullptr;
+    if (with_self) {
+        // the vertex's own partial gradient dZ W_self^T joins dX as the second operand pair of the schedule's last
+        // product (for a plain max Gather that product is otherwise the identity); its rows dZ are formed tile by tile
+        const int32_t Fo = (int32_t)vp->W->cols;
+        const bool use_y = vp->act != SAGA_ACT_NONE;
+        const int64_t self_tile = std::min<int64_t>(n, std::max<int64_t>(4096, ((int64_t)64 << 20) / ((int64_t)F * 4)));
+        if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * ((size_t)Fo * F + (pool ? 0 : (size_t)F * F))))) return st;
+        float* wst = static_cast<float*>(ctx->ws_wt.p);
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, F, Fo, SAGA_F32, wst, F, 0, s));
+        wst_t.data = wst;
+        wst_t.rows = Fo;
+        wst_t.cols = wst_t.ld = F;
+        wst_t.dtype = SAGA_F32;
+        wst_t.mem = SAGA_MEM_DEVICE;
+        vt.W_self = &wst_t;
+        if (!pool) {
+            HIP_TRY(ctx, launch_pack_bt_rows(nullptr, 0, 0, F, F, wst + (size_t)Fo * F, F, 0, s));  // identity
+            wp = wst_t;
+            wp.data = wst + (size_t)Fo * F;
+            wp.rows = F;
+            vt.W = &wp;
+        }
+        if (use_y)
+            if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)self_tile * Fo))) return st;
+        ex.F_self = Fo;
+        ex.self_fill = own_rows_fill(ctx, dY, Y, vp->act, Fo, nullptr, 0, 0, self_tile);
+    }
     if (pool) {
         // dX = dPre W_pool: W_pool (F_pool x F) is already the "F_in x F_out" matrix of this product
         wp = *ep->W_pool;
         vt.W = &wp;
-        vt.act = SAGA_ACT_NONE;
         ex.bytes_per_dst_row = sizeof(float) * ((size_t)Fm + F);
         {
             // the split workspace for the largest interval there can be, so that nothing is allocated inside the pipeline;
@@ -887,7 +947,7 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         };
     }
     saga_tensor no_dx{};  // pooled layers without dX still need the pass for dW_pool: the schedule then writes nothing out
-    return streamed_forward(ctx, g->tr, &rows_t, &et, SAGA_AGG_SUM, pool ? &vt : nullptr, grads->dX ? grads->dX : &no_dx,
+    return streamed_forward(ctx, g->tr, &rows_t, &et, SAGA_AGG_SUM, (pool || with_self) ? &vt : nullptr, grads->dX ? grads->dX : &no_dx,
                             agg == SAGA_AGG_MAX ? &feed : nullptr, &ex);
 }
 
@@ -923,7 +983,9 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
             ctx->h_grad_bytes = need;
         }
     }
-    if ((st = streamed_param_grads(ctx, n, nullptr, A, Y, dY, vp, grads, n > 0 ? ctx->h_grad : nullptr))) return st;
+    const bool with_self = vp->W_self != nullptr;
+    const int32_t Fo = (int32_t)vp->W->cols;
+    if ((st = streamed_param_grads(ctx, n, with_self ? X : nullptr, A, Y, dY, vp, grads, n > 0 ? ctx->h_grad : nullptr))) return st;
     if (n == 0) {  // sums over nothing
         if ((st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg, lddwg))) return st;
         if ((st = param_grad(ctx, nullptr, 3 * (int64_t)F, F, nullptr, F, F, 0, dWg + F, lddwg))) return st;
@@ -998,12 +1060,20 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     }
 
     // ---- pass 3: source parts and dX, over the edges clustered by source ----
-    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * 2 * (size_t)F * F))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)F * (2 * (size_t)F + (with_self ? (size_t)F + Fo : 0))))) return st;
     float* M1 = static_cast<float*>(ctx->ws_wt.p);  // [W_gs ; W_m] as a 2F x F matrix: row f of W_gs is W_gate[f][0..F)
+    float* M2 = M1 + 2 * (size_t)F * F;             // with W_self: [W_gd ; W_self^T], (F + F_out) x F
     const float* Wg = static_cast<const float*>(ep->W_gate->data);
     HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, M1, F, 0, s));
     HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr, ep->W_msg ? ep->W_msg->ld : 0, 0, F, F,
                                      M1, F, F, s));
+    const int64_t self_tile = std::min<int64_t>(n, std::max<int64_t>(4096, ((int64_t)64 << 20) / ((int64_t)F * 4)));
+    if (with_self) {
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, M2, F, 0, s));
+        HIP_TRY(ctx, launch_pack_bt_transpose(vp->W_self->data, vp->W_self->ld, F, Fo, SAGA_F32, M2 + (size_t)F * F, F, 0, s));
+        if (vp->act != SAGA_ACT_NONE)
+            if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)self_tile * Fo))) return st;
+    }
     HIP_TRY(ctx, hipStreamSynchronize(s));
     saga_tensor rows_t{};
     rows_t.rows = n;
@@ -1027,9 +1097,14 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ex.dst_width = 2 * F;
     ex.dst_rows = H;  // [Ps | M]
     ex.ld_dst = ldh;
-    ex.self_rows = h_dH + 2 * F;  // dPd, the second operand of the last product
-    ex.ld_self = ldh;
-    ex.F_self = F;
+    if (with_self) {  // second operand rows [dPd | dZ]: the vertex's own partial gradient dZ W_self^T rides along
+        ex.F_self = F + Fo;
+        ex.self_fill = own_rows_fill(ctx, dY, Y, vp->act, Fo, h_dH + 2 * F, ldh, F, self_tile);
+    } else {
+        ex.self_rows = h_dH + 2 * F;  // dPd, the second operand of the last product
+        ex.ld_self = ldh;
+        ex.F_self = F;
+    }
     ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
     bool any_done = false;
     ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
@@ -1053,6 +1128,11 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     wgd_t = *ep->W_gate;  // W_gd: the right half of W_gate, F x F with W_gate's row stride
     wgd_t.data = const_cast<float*>(Wg) + F;
     wgd_t.cols = F;
+    if (with_self) {
+        wgd_t.data = M2;
+        wgd_t.rows = F + Fo;
+        wgd_t.ld = F;
+    }
     saga_vertex_params vt{};
     vt.W = &m1_t;
     vt.W_self = &wgd_t;
@@ -1169,20 +1249,6 @@ saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     vt.W_self = &wst_t;
     StreamExtras ex;
     ex.F_self = Fo;
-    ex.self_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
-        auto rows_of_t = [](const saga_tensor* t, int64_t r) { return static_cast<const float*>(t->data) + r * t->ld; };
-        if (rows > self_tile) return ctx->fail(SAGA_ERR_INTERNAL, "own-row tile larger than planned");
-        HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * (size_t)Fo, rows_of_t(dY, row0), sizeof(float) * (size_t)dY->ld,
-                                      sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
-        *h2d += rows * (int64_t)Fo * 4;
-        if (use_y) {
-            float* tY = static_cast<float*>(ctx->ws_dz.p);
-            HIP_TRY(ctx, hipMemcpy2DAsync(tY, sizeof(float) * (size_t)Fo, rows_of_t(Y, row0), sizeof(float) * (size_t)Y->ld,
-                                          sizeof(float) * (size_t)Fo, (size_t)rows, hipMemcpyHostToDevice, on));
-            *h2d += rows * (int64_t)Fo * 4;
-            HIP_TRY(ctx, launch_dz_colsum(dst, Fo, tY, Fo, vp->act, dst, rows, Fo, nullptr, nullptr, 0, on));
-        }
-        return SAGA_OK;
-    };
+    ex.self_fill = own_rows_fill(ctx, dY, Y, vp->act, Fo, nullptr, 0, 0, self_tile);
     return streamed_forward(ctx, g->tr, &dz_t, &et, SAGA_AGG_SUM, &vt, grads->dX, &feed, &ex);
 }

@@ -177,7 +177,8 @@ __device__ __forceinline__ float act_grad(int mode, float g, float y)
 
 template <int VEC, int MODE>
 __global__ __launch_bounds__(256) void k_dz_colsum(const float* __restrict__ dY, int64_t lddy, const float* __restrict__ Y, int64_t ldy,
-                                                   float* __restrict__ dZ, int64_t rows, int F, int64_t R, float* __restrict__ part)
+                                                   float* __restrict__ dZ, int64_t lddz, int64_t rows, int F, int64_t R,
+                                                   float* __restrict__ part)
 {
     __shared__ float red[256 * VEC];
     const int ncg = (F + VEC - 1) / VEC;                  // column groups
@@ -202,13 +203,13 @@ __global__ __launch_bounds__(256) void k_dz_colsum(const float* __restrict__ dY,
                         const float4 y = *reinterpret_cast<const float4*>(Y + r * ldy + c);
                         g[0] = act_grad(MODE, g[0], y.x), g[1] = act_grad(MODE, g[1], y.y);
                         g[2] = act_grad(MODE, g[2], y.z), g[3] = act_grad(MODE, g[3], y.w);
-                        *reinterpret_cast<float4*>(dZ + r * F + c) = make_float4(g[0], g[1], g[2], g[3]);
+                        *reinterpret_cast<float4*>(dZ + r * lddz + c) = make_float4(g[0], g[1], g[2], g[3]);
                     }
                 } else {
                     g[0] = dY[r * lddy + c];
                     if (MODE) {
                         g[0] = act_grad(MODE, g[0], Y[r * ldy + c]);
-                        dZ[r * F + c] = g[0];
+                        dZ[r * lddz + c] = g[0];
                     }
                 }
 #pragma unroll
@@ -321,9 +322,10 @@ hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, int accumu
 int64_t colsum_slabs(int64_t rows) { return std::max<int64_t>(1, std::min<int64_t>(1024, (rows + 127) / 128)); }
 
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, int32_t act, float* dZ, int64_t rows, int32_t F,
-                            float* part, float* dbias, int accumulate, hipStream_t s)
+                            float* part, float* dbias, int accumulate, hipStream_t s, int64_t lddz)
 {
     if (F <= 0) return hipSuccess;
+    if (lddz <= 0) lddz = F;
     if (act == SAGA_ACT_NONE) Y = nullptr;
     if (act != SAGA_ACT_NONE && !Y) return hipErrorInvalidValue;
     if (!Y && !part) return hipSuccess;  // nothing to mask, nothing to sum
@@ -331,21 +333,21 @@ hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64
     const int64_t R = (std::max<int64_t>(rows, 1) + slabs - 1) / slabs;
     const bool mask = Y != nullptr;
     const bool sig = act == SAGA_ACT_SIGMOID;
-    const bool vec4 = F % 4 == 0 && lddy % 4 == 0 && (!mask || ldy % 4 == 0) && (reinterpret_cast<uintptr_t>(dY) & 15u) == 0 &&
+    const bool vec4 = F % 4 == 0 && lddy % 4 == 0 && (!mask || (ldy % 4 == 0 && lddz % 4 == 0)) && (reinterpret_cast<uintptr_t>(dY) & 15u) == 0 &&
                       (!mask || ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (reinterpret_cast<uintptr_t>(dZ) & 15u) == 0));
     const dim3 grid((unsigned)slabs), block(256);
     if (vec4 && mask && sig)
-        hipLaunchKernelGGL((k_dz_colsum<4, 2>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<4, 2>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     else if (vec4 && mask)
-        hipLaunchKernelGGL((k_dz_colsum<4, 1>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<4, 1>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     else if (vec4)
-        hipLaunchKernelGGL((k_dz_colsum<4, 0>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<4, 0>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     else if (mask && sig)
-        hipLaunchKernelGGL((k_dz_colsum<1, 2>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<1, 2>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     else if (mask)
-        hipLaunchKernelGGL((k_dz_colsum<1, 1>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<1, 1>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     else
-        hipLaunchKernelGGL((k_dz_colsum<1, 0>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, rows, F, R, part);
+        hipLaunchKernelGGL((k_dz_colsum<1, 0>), grid, block, 0, s, dY, lddy, Y, ldy, dZ, lddz, rows, F, R, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !part) return e;
     hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((F + 63) / 64)), dim3(256), 0, s, part, (int64_t)F, (int)slabs, F, dbias, (int64_t)F, accumulate);

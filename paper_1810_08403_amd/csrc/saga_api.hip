@@ -1120,8 +1120,6 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
         if (gated_h && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
         const bool max_or_pool = pool_h || (agg == SAGA_AGG_MAX && !gated_h);
-        if ((max_or_pool || gated_h) && vp->W_self)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass covers W_self only with sum over COPY / MUL_WEIGHT messages");
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
         const saga_tensor* W = vp->W;

@@ -300,12 +300,12 @@ struct GemmTnArgs {
 };
 void gemm_tn_plan(int64_t n, int32_t FP, int32_t FQ, int64_t* rows_per_split, int32_t* n_split);
 hipError_t launch_gemm_tn(const GemmTnArgs& a, float* C, int64_t ldc, int accumulate, hipStream_t s);  // accumulate: C += P^T Q
-// One pass over the gradient rows: dZ (rows x F, compact) = dY times the derivative of activation `act` taken from the
-// layer's output Y (ReLU: 1 where Y > 0; sigmoid: Y (1 - Y); SAGA_ACT_NONE: Y is not read, nothing is stored, dZ is
-// dY); with part (colsum_slabs(rows) x F floats), dbias[c] = sum over rows of dZ[r][c].
+// One pass over the gradient rows: dZ (rows x F, row stride lddz, 0 = compact) = dY times the derivative of activation
+// `act` taken from the layer's output Y (ReLU: 1 where Y > 0; sigmoid: Y (1 - Y); SAGA_ACT_NONE: Y is not read, nothing
+// is stored, dZ is dY); with part (colsum_slabs(rows) x F floats), dbias[c] = sum over rows of dZ[r][c].
 int64_t colsum_slabs(int64_t rows);
 hipError_t launch_dz_colsum(const float* dY, int64_t lddy, const float* Y, int64_t ldy, int32_t act, float* dZ, int64_t rows, int32_t F,
-                            float* part, float* dbias, int accumulate, hipStream_t s);  // accumulate: dbias += the sums
+                            float* part, float* dbias, int accumulate, hipStream_t s, int64_t lddz = 0);  // accumulate: dbias += the sums
 // bf16 layers: dZ (rows x F, compact) = dY where Y > 0 (Y NULL: dY), as fp32 and as bf16
 hipError_t launch_dz_bf16(const uint16_t* dY, int64_t lddy, const uint16_t* Y, int64_t ldy, float* dZ32, uint16_t* dZ16, int64_t rows,
                           int32_t F, hipStream_t s);

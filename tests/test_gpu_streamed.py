@@ -570,3 +570,88 @@ def test_source_intervals_without_out_edges(schedule):
             ref = run_oracle(wl, agg="sum")
             Y = _streamed(ctx, wl, graph, "sum")
             assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"sum layer, schedule {schedule}, call {rep}")
+
+
+@pytest.mark.parametrize("edge_op,agg,act,Q,P", [("copy", "max", "relu", 2, 3), ("mul_weight", "max", "sigmoid", 1, 4),
+                                                 ("pool", "max", "relu", 2, 2), ("gated", "sum", "relu", 2, 3),
+                                                 ("gated", "sum", "sigmoid", 1, 2)])
+def test_streamed_backward_own_product_in_every_layer_program(edge_op, agg, act, Q, P):
+    """Y = act(A W + X W_self + b) with a max Gather, pooled or gated messages, backwards from host memory: dW_self is
+    added tile by tile with the other ApplyVertex gradients, and dZ W_self^T joins dX inside the schedule's last
+    product (beside the identity for a plain max Gather, W_pool for pooled rows, [W_gs; W_m] and W_gd for gated ones)."""
+    import oracle
+    import paper_1810_08403_amd as saga
+    pool, gated = edge_op == "pool", edge_op == "gated"
+    if pool:
+        wl = si.mpgcn_workload(scale=11, f_in=16, f_pool=32, f_out=24)
+        wl.X = torch.round(wl.X.clamp(-1, 1) * 4) / 4          # coarse values, see the pooled max test above
+        wl.W_pool = torch.round((wl.W_pool * 4).clamp(-0.5, 0.5) * 8) / 8
+        wl.b_pool = torch.round(wl.b_pool.clamp(-0.5, 0.5) * 8) / 8
+    elif gated:
+        wl = si.workload(4, scale=11, f_in=20, f_out=12)
+    else:
+        wl = si.commnet_workload(scale=11, f_in=40, f_out=24)
+    g = wl.graph
+    n, F = wl.X.shape
+    Fm, Fo = wl.W.shape
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    W_self = si.glorot_uniform(F, Fo, 77)
+    w = si.uniform_pm(g.nnz, 1.0, 17) if edge_op == "mul_weight" else None
+    dY = si.normal_features(n, Fo, 31)
+    bias = si.uniform_pm(Fo, 0.3, 3)
+    okw, kw = {}, dict(edge_op=edge_op, agg=agg, act=act, bias=bias.cuda(), W_self=W_self.cuda())
+    if w is not None:
+        okw["edge_weight"] = w.numpy()
+    if pool:
+        okw.update(W_pool=wl.W_pool.numpy(), b_pool=wl.b_pool.numpy())
+        kw.update(W_pool=wl.W_pool.cuda(), b_pool=wl.b_pool.cuda())
+    if gated:
+        okw.update(W_gate=wl.W_gate.numpy(), b_gate=wl.b_gate.numpy(), W_msg=wl.W_msg.numpy())
+        kw.update(W_gate=wl.W_gate.cuda(), b_gate=wl.b_gate.cuda(), W_msg=wl.W_msg.cuda())
+    fwd = oracle.layer(cp, ri, wl.X.numpy(), edge_op, agg=agg, W=wl.W.numpy(), W_self=W_self.numpy(), bias=bias.numpy(), act=act, **okw)
+    if gated:
+        bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), fwd["A"], dY.numpy(), wl.W.numpy(), bias=bias.numpy(), act=act,
+                                    W_self=W_self.numpy(), **okw)
+    else:
+        bwd = oracle.max_backward(cp, ri, wl.X.numpy(), dY.numpy(), wl.W.numpy(), edge_op, bias=bias.numpy(), act=act,
+                                  W_self=W_self.numpy(), **okw)
+    ctx = saga.Context(0)
+    for name, val in (("dst_intervals", Q), ("src_intervals", P), ("bwd_tile_rows", 600)):
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+    if w is not None:
+        graph.set_edge_data(w)
+    X_h = wl.X.clone().pin_memory()
+    Y_h, A_h = torch.empty(n, Fo).pin_memory(), torch.empty(n, Fm).pin_memory()
+    if pool:   # the device's own pooled rows decide the maxima (see the pooled max test above)
+        with new_context() as c2:
+            g2 = c2.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+            Yd, Ad = torch.empty(n, Fo, device="cuda"), torch.empty(n, Fm, device="cuda")
+            c2.layer_forward(g2, wl.X.cuda(), Yd, W=wl.W.cuda(), accum_out=Ad, **kw)
+            torch.cuda.synchronize()
+            A_h.copy_(Ad.cpu())
+            Y_h.copy_(Yd.cpu())
+            g2.destroy()
+    else:
+        A_h.copy_(torch.as_tensor(fwd["A"], dtype=torch.float32))
+        Y_h.copy_(torch.as_tensor(fwd["Y"], dtype=torch.float32))
+    dY_h = dY.clone().pin_memory()
+    dX_h = torch.full((n, F), float("nan")).pin_memory()
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    out = dict(dW=nan(Fm, Fo), dbias=nan(Fo), dW_self=nan(F, Fo))
+    if pool:
+        out.update(dW_pool=nan(Fm, F), db_pool=nan(Fm))
+    if gated:
+        out.update(dW_gate=nan(F, 2 * F), db_gate=nan(F), dW_msg=nan(F, F))
+    for rep, want_dx in enumerate([True, False, True]):
+        for t in out.values():
+            t.fill_(float("nan"))
+        dX_h.fill_(float("nan"))
+        rest = {k: v for k, v in out.items() if k != "dW"}
+        ctx.layer_backward(graph, A_h, dY_h, wl.W.cuda(), out["dW"], X=X_h, Y=Y_h, dX=dX_h if want_dx else None, **rest, **kw)
+        what = f"streamed backward with W_self, {edge_op} {agg} {act} {Q}x{P} call {rep}"
+        for name, got in out.items():
+            assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " " + name)
+        if want_dx:
+            assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
+    ctx.destroy()
