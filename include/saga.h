@@ -284,10 +284,11 @@ typedef struct saga_layer_grads {
  * pooled rows, and appended to dPd W_gd for gated ones). Every transfer goes through the
  * context's device budget like in saga_layer_forward.
  *
- * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, no W_self, act NONE or
- * RELU): X is not
- * needed, Y, dY and grads->dX are bf16 like W, A stays the fp32 accum_out of the forward
- * call, parameter gradients are fp32. dZ's bf16 values are used as they are; the rows that
+ * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, with or without W_self,
+ * act NONE or RELU): X is needed only with W_self (bf16, like W_self); Y, dY and grads->dX are
+ * bf16 like W, A stays the fp32 accum_out of the forward call, parameter gradients are fp32
+ * (dW_self = X^T dZ from the rows of X widened to fp32; dZ W_self^T is a second operand pair of
+ * the bf16 product that makes dX, which then always follows the propagation). dZ's bf16 values are used as they are; the rows that
  * travel over the edges and the product that makes dX are bf16 with fp32 accumulation and
  * one rounding to bf16 each, like the forward pass; dW and dbias are fp32 products and sums.
  * Sums are deterministic run to run.

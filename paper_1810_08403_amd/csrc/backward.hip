@@ -533,9 +533,11 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
 
 // bf16 layers (sum over COPY / MUL_WEIGHT messages): the rows that travel over the edges and through the dX product
 // are bf16 with fp32 accumulation, like the forward pass; the parameter gradients are fp32 products of the fp32 Gather
-// output with dZ (whose bf16 values are exact in fp32).
-saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
-                                   const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+// output (for dW_self: of X widened to fp32) with dZ, whose bf16 values are exact in fp32. With W_self the propagation
+// always runs first and dX = [T dZ | dZ] [W ; W_self]^T is one product with two operand pairs.
+saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
+                                   const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                                   const saga_layer_grads* grads)
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
@@ -557,24 +559,38 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
     if ((st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ32, Fo, Fo, n, static_cast<float*>(grads->dW->data),
                          grads->dW->ld)))
         return st;
+    const bool with_self = vp->W_self != nullptr;
+    if (with_self) {  // dW_self = X^T dZ, with the rows of X widened to fp32 in the buffer the Gather output uses in forward calls
+        if ((st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)std::max<int64_t>(n, 1) * F))) return st;
+        float* X32 = static_cast<float*>(ctx->ws_accum.p);
+        HIP_TRY(ctx, launch_dz_bf16(static_cast<const uint16_t*>(X->data), X->ld, nullptr, 0, X32, nullptr, n, F, s));
+        if ((st = param_grad(ctx, X32, F, F, dZ32, Fo, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld))) return st;
+    }
     if (!grads->dX || n == 0) return SAGA_OK;
     if ((st = ensure_transposed(ctx, g))) return st;
     const float* w_t = nullptr;
     if ((st = transposed_weights(ctx, g, ep, &w_t))) return st;
 
-    // rows x K (bf16) times W^T, W given as F x F_out: C[rows x F] bf16
-    auto times_wt16 = [&](const uint16_t* rows16, int64_t ld, uint16_t* C, int64_t ldc) -> saga_status {
+    // rows x K (bf16) times W^T, W given as F x F_out: C[rows x F] bf16; own: the second operand pair (dZ, W_self)
+    auto times_wt16 = [&](const uint16_t* rows16, int64_t ld, uint16_t* C, int64_t ldc, bool own) -> saga_status {
         int64_t n_pad, k_pad;
         bt_padded_shape(F, Fo, SAGA_BF16, &n_pad, &k_pad);
-        if (saga_status e = ctx->dev_alloc(&ctx->ws_bt, sizeof(uint16_t) * (size_t)(n_pad * k_pad))) return e;
+        const int64_t ldbt = own ? 2 * k_pad : k_pad;
+        if (saga_status e = ctx->dev_alloc(&ctx->ws_bt, sizeof(uint16_t) * (size_t)(n_pad * ldbt))) return e;
         uint16_t* bt = static_cast<uint16_t*>(ctx->ws_bt.p);
-        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(uint16_t) * (size_t)(n_pad * k_pad), s));
-        HIP_TRY(ctx, launch_pack_bt_rows_bf16(static_cast<const uint16_t*>(vp->W->data), vp->W->ld, F, Fo, bt, k_pad, s));
+        HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(uint16_t) * (size_t)(n_pad * ldbt), s));
+        HIP_TRY(ctx, launch_pack_bt_rows_bf16(static_cast<const uint16_t*>(vp->W->data), vp->W->ld, F, Fo, bt, ldbt, s));
         GemmArgs gm{};
+        if (own) {
+            HIP_TRY(ctx, launch_pack_bt_rows_bf16(static_cast<const uint16_t*>(vp->W_self->data), vp->W_self->ld, F, Fo, bt + k_pad, ldbt, s));
+            gm.A2 = dZ16;
+            gm.lda2 = Fo;
+            gm.K2 = Fo;
+        }
         gm.A = rows16;
         gm.lda = ld;
         gm.Bt = bt;
-        gm.ldbt = k_pad;
+        gm.ldbt = ldbt;
         gm.C = C;
         gm.ldc = ldc;
         gm.M = n;
@@ -626,14 +642,15 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
 
     uint16_t* dX = static_cast<uint16_t*>(grads->dX->data);
     const int64_t lddx = grads->dX->ld;
-    const int32_t wmid = Fo <= F ? Fo : F;
+    const bool first = Fo <= F || with_self;  // propagate dZ, then the product
+    const int32_t wmid = first ? Fo : F;
     if ((st = ctx->dev_alloc(&ctx->ws_grad, sizeof(uint16_t) * (size_t)n * wmid))) return st;
     uint16_t* mid = static_cast<uint16_t*>(ctx->ws_grad.p);
-    if (Fo <= F) {
-        if ((st = propagate16(dZ16, Fo, Fo, mid, Fo))) return st;   // the narrower rows travel
-        return times_wt16(mid, Fo, dX, lddx);
+    if (first) {
+        if ((st = propagate16(dZ16, Fo, Fo, mid, Fo))) return st;   // the narrower rows travel (with W_self: always dZ)
+        return times_wt16(mid, Fo, dX, lddx, with_self);
     }
-    if ((st = times_wt16(dZ16, Fo, mid, F))) return st;
+    if ((st = times_wt16(dZ16, Fo, mid, F, false))) return st;
     return propagate16(mid, F, F, dX, lddx);
 }
 

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void k_dz_bf16(const uint16_t* __restrict__ dY
             const bool pos = (y & 0x7fffu) != 0 && (y & 0x8000u) == 0 && (y & 0x7fffu) <= 0x7f80u;  // y > 0, not NaN
             g = pos ? g : (uint16_t)0;
         }
-        dZ16[i] = g;
+        if (dZ16) dZ16[i] = g;  // NULL: only the fp32 copy is wanted (the rows of X for dW_self)
         dZ32[i] = __uint_as_float((uint32_t)g << 16);
     }
 }

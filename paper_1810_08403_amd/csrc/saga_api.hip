@@ -1206,8 +1206,8 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (tensor_ok(W) && W->dtype == SAGA_BF16) {
         // bf16 layers: X, W, Y, dY, dX in bf16; A and the parameter gradients in fp32
         auto dev_bf16 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_BF16; };
-        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT) || vp->W_self)
-            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers sum over COPY / MUL_WEIGHT messages without W_self");
+        if (agg != SAGA_AGG_SUM || (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT))
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers sum over COPY / MUL_WEIGHT messages");
         if (vp->act == SAGA_ACT_SIGMOID)  // a derivative y (1 - y) from an 8-bit y is not worth having
             return ctx->fail(SAGA_ERR_UNSUPPORTED, "the bf16 backward pass covers activations NONE and RELU only");
         if (!dev_bf16(W) || W->rows > (1 << 20) || W->cols > (1 << 20)) return ctx->fail(SAGA_ERR_INVALID_ARG, "malformed W");
@@ -1223,12 +1223,22 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dbias must be F_out fp32 values on the device");
         if (grads->dX && (!dev_bf16(grads->dX) || grads->dX->rows != n || grads->dX->cols != F))
             return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dX must be a device n x F_in bf16 tensor");
-        if (grads->dW_self || grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
+        if (vp->W_self) {
+            if (!dev_bf16(vp->W_self) || vp->W_self->rows != F || vp->W_self->cols != Fo)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self must be a device F_in x F_out bf16 tensor, like W");
+            if (!X || !dev_bf16(X) || X->rows != n || X->cols != F)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self needs X as a device n x F_in bf16 tensor");
+            if (!grads->dW_self || !dev_f32(grads->dW_self) || grads->dW_self->rows != F || grads->dW_self->cols != Fo)
+                return ctx->fail(SAGA_ERR_INVALID_ARG, "W_self is given: grads->dW_self must be a device F_in x F_out fp32 tensor");
+        } else if (grads->dW_self) {
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "grads->dW_self is given but W_self is not");
+        }
+        if (grads->dW_gate || grads->db_gate || grads->dW_msg || grads->dW_pool || grads->db_pool)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "this layer has no such parameter gradients");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
         DeviceGuard guard16(ctx->device);
-        return resident_backward_bf16(ctx, const_cast<saga_graph*>(g), A, Y, dY, ep, vp, grads);
+        return resident_backward_bf16(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
     }
     if (!dev_f32(W) || W->rows > (1 << 20) || W->cols > (1 << 20))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device Fm x F_out fp32 tensor");

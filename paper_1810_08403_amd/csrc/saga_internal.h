@@ -324,7 +324,7 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                               const saga_layer_grads* grads);
-saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
+saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y, const saga_tensor* dY,
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 // backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
 saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,

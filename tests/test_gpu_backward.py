@@ -500,18 +500,20 @@ def test_pool_backward_with_own_product_and_sigmoid_activation(ctx):
 # bf16 layers
 # --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("f_in,f_out,edge_op,act", [(128, 48, "mul_weight", "relu"), (48, 128, "copy", "none"), (512, 256, "mul_weight", "relu"),
-                                                    (20, 7, "copy", "relu"), (64, 64, "mul_weight", "none")])
-def test_bf16_backward_matches_oracle(ctx, f_in, f_out, edge_op, act):
+@pytest.mark.parametrize("f_in,f_out,edge_op,act,with_self", [(128, 48, "mul_weight", "relu", False), (48, 128, "copy", "none", False),
+                                                              (512, 256, "mul_weight", "relu", False), (20, 7, "copy", "relu", False),
+                                                              (64, 64, "mul_weight", "none", False), (128, 48, "copy", "relu", True),
+                                                              (48, 128, "mul_weight", "none", True), (20, 7, "copy", "relu", True)])
+def test_bf16_backward_matches_oracle(ctx, f_in, f_out, edge_op, act, with_self):
     from helpers import TOL_BF16
     wl = si.commnet_workload(scale=11, f_in=f_in, f_out=f_out)
-    wl.edge_op, wl.W_self = edge_op, None
+    wl.edge_op = edge_op
     if edge_op == "mul_weight":
         wl.edge_weight = si.gcn_edge_weights(wl.graph)
-    wl.X, wl.W = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W)
+    wl.X, wl.W, wl.W_self = si.round_to_bf16(wl.X), si.round_to_bf16(wl.W), si.round_to_bf16(wl.W_self)
     n = wl.graph.n
     dY = si.round_to_bf16(si.normal_features(n, f_out, 99))
-    fwd, bwd = _oracle_pair(wl, act, None, False, dY)
+    fwd, bwd = _oracle_pair(wl, act, None, with_self, dY)
     graph = make_graph(ctx, wl.graph)
     dev = "cuda"
     b16 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).to(dev).to(torch.bfloat16)
@@ -519,9 +521,14 @@ def test_bf16_backward_matches_oracle(ctx, f_in, f_out, edge_op, act):
     dW, db = torch.full((f_in, f_out), float("nan"), device=dev), torch.full((f_out,), float("nan"), device=dev)
     dX = torch.full((n, f_in), float("nan"), device=dev, dtype=torch.bfloat16)
     kw = dict(edge_weight=wl.edge_weight.to(dev)) if edge_op == "mul_weight" else {}
+    dWs = torch.full((f_in, f_out), float("nan"), device=dev)
+    if with_self:   # Y = act(A W + X W_self): dW_self from X widened to fp32, dZ W_self^T inside the dX product
+        kw.update(X=b16(wl.X), W_self=b16(wl.W_self), dW_self=dWs)
     ctx.layer_backward(graph, A, b16(dY), b16(wl.W), dW, Y=b16(fwd["Y"]), edge_op=edge_op, act=act, dX=dX, dbias=db, **kw)
     torch.cuda.synchronize()
-    what = f"bf16 {f_in}->{f_out} {edge_op} {act}"
+    what = f"bf16 {f_in}->{f_out} {edge_op} {act}" + (" with W_self" if with_self else "")
+    if with_self:
+        assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], bwd["dW_self_abs"], TOL_F32, what + " dW_self")
     # the parameter gradients are fp32 products of exactly representable inputs: the fp32 bar applies
     assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
     dZ = dY * torch.as_tensor(fwd["Y"] > 0) if act == "relu" else dY
