@@ -243,6 +243,27 @@ def main():
     copy_gbps = device_copy_ceiling(ctx, torch)
     out["roofline"]["measured_copy_ceiling"] = {"GBps": round(copy_gbps, 1), "frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
                                                 "kernel": "k_copy_u128, 1 GiB read + 1 GiB written"}
+    # the dense products of the layer (the per-vertex products hoisted out of ApplyEdge, and ApplyVertex) against the MFMA
+    # peak of their dtype, and against the bytes they have to move: at these widths they sit between the two
+    ms_dense = out["stages_ms"]["hoist"] + out["stages_ms"]["apply_vertex"]
+    if ms_dense > 0 and not args.transform_first:
+        flops = 0.0
+        bytes_dense = 0.0
+        if wl.edge_op == "gated":
+            flops += 2.0 * n * f_in * 3 * f_in
+            bytes_dense += n * f_in * es + n * 3 * f_in * 4
+        if wl.edge_op == "pool":
+            flops += 2.0 * n * f_in * f_msg
+            bytes_dense += n * f_in * es + n * f_msg * 4
+        if has_w:
+            flops += 2.0 * n * f_msg * f_out + (2.0 * n * f_in * f_out if wl.W_self is not None else 0.0)
+            bytes_dense += n * f_msg * es + (n * f_in * es if wl.W_self is not None else 0) + n * f_out * es
+        peak_tf = 2500.0 if wl.dtype == "bf16" else 157.3
+        tf = flops / (ms_dense * 1e-3) / 1e12
+        out["dense_products"] = {"bound": "mfma", "kernel": "k_gemm_nt", "achieved": round(tf, 1), "peak": peak_tf, "unit": "TFLOP/s",
+                                 "frac": round(tf / peak_tf, 4), "ms": round(ms_dense, 4), "flops": flops,
+                                 "bytes": bytes_dense, "GBps": round(bytes_dense / (ms_dense * 1e-3) / 1e9, 1),
+                                 "frac_of_hbm_peak": round(bytes_dense / (ms_dense * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
 
     if (not args.transform_first and not args.hip_graph and has_w and wl.W_self is None and args.agg == "sum"
             and wl.edge_op in ("copy", "mul_weight") and f_out < f_in):

@@ -5,9 +5,10 @@
 //
 // C[M x N] = act(A[M x K] * Bt[N x K]^T + bias). Both operands are read
 // K-contiguous: A as given, the weights from a packed, zero-padded transpose
-// Bt. A K tile is 64 bytes per row (16 fp32 or 32 bf16). In LDS a row takes
-// 80 bytes, so the 16-byte fragment reads of 32 consecutive rows spread over
-// all banks. Each lane reads 16 bytes of its row: for bf16 that is exactly one
+// Bt. A K tile is 64 bytes per row for fp32 (16 elements) and 128 bytes for
+// bf16 (64 elements). In LDS a row takes 16 bytes more, so the 16-byte
+// fragment reads of consecutive rows spread over all banks. Each lane reads
+// 16 bytes of its row per step: for bf16 that is exactly one
 // 32x32x16 MFMA operand; for fp32 it feeds four 32x32x2 MFMAs (lane halves
 // supply k and k+4 instead of k and k+1, the same on both operands, which
 // only permutes the order of the K sum).
@@ -30,8 +31,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte fragment as a first-class vector value
 
-constexpr int kRowBytes = 64;    // bytes of K per tile row
-constexpr int kLdsStride = 80;   // LDS bytes per tile row
+// bytes of K per tile row: 64 for fp32 (16 elements, 16 MFMAs of 64 cycles per wave and 32 x 32 tile), 128 for bf16
+// (64 elements: with 64 bytes a wave had 256 cycles of MFMA work between two barriers, less than the barrier, the LDS
+// round trip and the address arithmetic around it cost)
+template <typename T>
+constexpr int row_bytes()
+{
+    return sizeof(T) == 4 ? 64 : 128;
+}
+constexpr int kLdsPad = 16;      // LDS bytes added to a tile row: 16-byte reads of 16 consecutive rows then cover all banks
 constexpr int kBtRowPad = 128;   // Bt rows are padded to a multiple of this
 
 __device__ __forceinline__ uint16_t to_bf16(float f)
@@ -75,7 +83,7 @@ template <typename T, int BM, int BN, bool ALIGNED, int ACH, int BCH>
 __device__ __forceinline__ void tile_load(const GemmArgs& a, const T* __restrict__ A, const T* __restrict__ Bt, int64_t m0,
                                           int n0, int kt, int nk, int tid, u32x4 (&ra)[ACH], u32x4 (&rb)[BCH], unsigned& ka)
 {
-    constexpr int KT = kRowBytes / (int)sizeof(T), EPC = 16 / (int)sizeof(T);
+    constexpr int KB = row_bytes<T>(), KT = KB / (int)sizeof(T), EPC = 16 / (int)sizeof(T), CPR = KB / 16;  // chunks per row
     ka = 0;
     const bool past = kt >= nk;
     if (past) kt = nk - 1;
@@ -89,7 +97,7 @@ __device__ __forceinline__ void tile_load(const GemmArgs& a, const T* __restrict
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         const int c = tid + 256 * i;
-        const int row = (c >> 2) < BM ? (c >> 2) : 0, kc = c & 3;
+        const int row = (c / CPR) < BM ? (c / CPR) : 0, kc = c % CPR;
         int64_t gr = m0 + row;
         if (gr >= a.M) gr = a.M - 1;
         const int k = k0 + kc * EPC;
@@ -116,26 +124,27 @@ __device__ __forceinline__ void tile_load(const GemmArgs& a, const T* __restrict
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
         const int c = tid + 256 * i;
-        const int row = (c >> 2) < BN ? (c >> 2) : 0, kc = c & 3;
+        const int row = (c / CPR) < BN ? (c / CPR) : 0, kc = c % CPR;
         rb[i] = *reinterpret_cast<const u32x4*>(Bt + (int64_t)(n0 + row) * a.ldbt + kt * KT + kc * EPC);
     }
 }
-template <int BM, int BN, bool ALIGNED, int ACH, int BCH>
+template <int KB, int BM, int BN, bool ALIGNED, int ACH, int BCH>
 __device__ __forceinline__ void tile_store(unsigned char* buf, int tid, const u32x4 (&ra)[ACH], const u32x4 (&rb)[BCH],
                                            unsigned ka)
 {
+    constexpr int CPR = KB / 16, kLdsStride = KB + kLdsPad;
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         const int c = tid + 256 * i;
         const bool in = !ALIGNED || ((ka >> i) & 1u);
         const u32x4 v = in ? ra[i] : u32x4{0u, 0u, 0u, 0u};
-        if (BM * 4 % 256 == 0 || c < BM * 4) *reinterpret_cast<u32x4*>(buf + (c >> 2) * kLdsStride + (c & 3) * 16) = v;
+        if (BM * CPR % 256 == 0 || c < BM * CPR) *reinterpret_cast<u32x4*>(buf + (c / CPR) * kLdsStride + (c % CPR) * 16) = v;
     }
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
         const int c = tid + 256 * i;
-        if (BN * 4 % 256 == 0 || c < BN * 4)
-            *reinterpret_cast<u32x4*>(buf + (BM + (c >> 2)) * kLdsStride + (c & 3) * 16) = rb[i];
+        if (BN * CPR % 256 == 0 || c < BN * CPR)
+            *reinterpret_cast<u32x4*>(buf + (BM + c / CPR) * kLdsStride + (c % CPR) * 16) = rb[i];
     }
 }
 
@@ -175,9 +184,11 @@ __device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&a
 // with nothing else to do. Layers have short K loops (K = 128: eight K tiles), where that wait and the write-out
 // would otherwise be a third of a tile's time.
 template <typename T, int BM, int BN, int WM, int WN, bool ALIGNED, typename TO>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_gemm_nt(const GemmArgs a, const int n_tiles_n, const int n_tiles)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 4 ? 3 : 2, sizeof(T) == 4 ? 3 : 2))) void k_gemm_nt(
+    const GemmArgs a, const int n_tiles_n, const int n_tiles)
 {
-    constexpr int KT = kRowBytes / (int)sizeof(T);  // elements of K per tile
+    constexpr int KB = row_bytes<T>(), kLdsStride = KB + kLdsPad;
+    constexpr int KT = KB / (int)sizeof(T);  // elements of K per tile
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * kLdsStride];
@@ -198,7 +209,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const int nk = (a.K + KT - 1) / KT + (a.A2 ? (a.K2 + KT - 1) / KT : 0);
     const int nkp = (nk + 1) & ~1;  // the loop takes K tiles in pairs: an odd count is padded with a zero tile
 
-    constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;
+    constexpr int ACH = (BM * (KB / 16) + 255) / 256, BCH = (BN * (KB / 16) + 255) / 256;
     u32x4 ra[ACH], rb[BCH], ra2[ACH], rb2[BCH];
     unsigned ka = 0, ka2 = 0;  // bit i: chunk i of this thread lies inside K
 
@@ -206,7 +217,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 
     auto multiply = [&](const unsigned char* base) {
 #pragma unroll
-        for (int step = 0; step < 2; ++step) {
+        for (int step = 0; step < KB / 32; ++step) {
             u32x4 fa[TM], fb[TN];
             const int chunk = (step * 2 + (lane >> 5)) * 16;
 #pragma unroll
@@ -235,7 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
     };
     load_next(ra, rb, ka);
-    tile_store<BM, BN, ALIGNED>(lds[0], tid, ra, rb, ka);
+    tile_store<KB, BM, BN, ALIGNED>(lds[0], tid, ra, rb, ka);
     load_next(ra, rb, ka);
     __syncthreads();
     for (int ti = 0; ti < count; ++ti) {
@@ -253,13 +264,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs it is meant to overlap
             multiply(lds[0]);
             __builtin_amdgcn_sched_barrier(0);  // ... and the wait for the older loads behind them
-            tile_store<BM, BN, ALIGNED>(lds[1], tid, ra, rb, ka);
+            tile_store<KB, BM, BN, ALIGNED>(lds[1], tid, ra, rb, ka);
             __syncthreads();
             load_next(ra, rb, ka);
             __builtin_amdgcn_sched_barrier(0);
             multiply(lds[1]);
             __builtin_amdgcn_sched_barrier(0);
-            tile_store<BM, BN, ALIGNED>(lds[0], tid, ra2, rb2, ka2);
+            tile_store<KB, BM, BN, ALIGNED>(lds[0], tid, ra2, rb2, ka2);
             __syncthreads();
         }
         // write-out: lane holds column (lane & 31) of 16 rows of each 32 x 32 tile
@@ -307,9 +318,9 @@ hipError_t launch_cfg(const GemmArgs& a, bool aligned, hipStream_t s)
     const int n_tiles_n = (a.N + BN - 1) / BN;
     const int64_t n_tiles = ((a.M + BM - 1) / BM) * n_tiles_n;
     if (n_tiles > 0x7fffffffLL - 8) return hipErrorInvalidValue;
-    // as many workgroups as the 256 compute units hold at once (three each), a multiple of the 8 XCDs; fewer when
-    // there are fewer tiles. Each takes every slots-th tile of its XCD's share.
-    const int64_t blocks = std::min<int64_t>((n_tiles + 7) / 8 * 8, 768);
+    // as many workgroups as the 256 compute units hold at once (three each, two with the wider K tiles of bf16), a
+    // multiple of the 8 XCDs; fewer when there are fewer tiles. Each takes every slots-th tile of its XCD's share.
+    const int64_t blocks = std::min<int64_t>((n_tiles + 7) / 8 * 8, sizeof(T) == 4 ? 768 : 512);
     if (aligned)
         hipLaunchKernelGGL((k_gemm_nt<T, BM, BN, WM, WN, true, TO>), dim3((unsigned)blocks), dim3(256), 0, s, a, n_tiles_n,
                            (int)n_tiles);
@@ -328,15 +339,19 @@ hipError_t launch_typed(const GemmArgs& a, hipStream_t s)
         aligned = aligned && (a.K2 * sizeof(T)) % 16 == 0 && (a.lda2 * sizeof(T)) % 16 == 0 &&
                   (reinterpret_cast<uintptr_t>(a.A2) & 15u) == 0;
     if (a.N > 64) return launch_cfg<T, 128, 128, 2, 2, TO>(a, aligned, s);
-    if (a.N > 32) return launch_cfg<T, 128, 64, 4, 1, TO>(a, aligned, s);
-    return launch_cfg<T, 256, 32, 4, 1, TO>(a, aligned, s);
+    if constexpr (sizeof(T) == 2) {  // bf16: 288 LDS rows of 144 bytes would leave one workgroup per compute unit
+        return launch_cfg<T, 128, 64, 4, 1, TO>(a, aligned, s);
+    } else {
+        if (a.N > 32) return launch_cfg<T, 128, 64, 4, 1, TO>(a, aligned, s);
+        return launch_cfg<T, 256, 32, 4, 1, TO>(a, aligned, s);
+    }
 }
 
 }  // namespace
 
 void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_t* k_pad)
 {
-    const int kt = kRowBytes / (dtype == SAGA_F32 ? 4 : 2);
+    const int kt = dtype == SAGA_F32 ? row_bytes<float>() / 4 : row_bytes<uint16_t>() / 2;
     *n_pad = ((int64_t)N + kBtRowPad - 1) / kBtRowPad * kBtRowPad;
     *k_pad = ((int64_t)K + kt - 1) / kt * kt;
 }
