@@ -44,3 +44,38 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.saga_create(None, 0, None, 0) == 1
     assert lib.saga_last_error(None) == b"null context"
     assert lib.saga_peak_device_bytes(None) == 0
+
+
+def test_header_is_plain_c_and_its_layouts_are_the_binding_s(tmp_path):
+    """include/saga.h must compile as C99 on its own (a C caller has nothing else), and the struct sizes and member
+    offsets a C compiler gives are the ones the ctypes binding marshals to."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the image"
+    inc = os.path.join(ROOT, "include")
+    members = {
+        "saga_tensor": (binding.Tensor, ["data", "rows", "cols", "ld", "dtype", "mem"]),
+        "saga_edge_params": (binding.EdgeParams, ["op", "edge_weight", "W_gate", "b_gate", "W_msg", "W_pool", "b_pool"]),
+        "saga_vertex_params": (binding.VertexParams, ["W", "bias", "act", "W_self"]),
+        "saga_layer_grads": (binding.LayerGrads, ["dX", "dW", "dbias", "dW_self", "dW_gate", "db_gate", "dW_msg", "dW_pool", "db_pool"]),
+    }
+    lines = ['#include "saga.h"', "#include <stddef.h>", "#include <stdio.h>", "int main(void) {"]
+    for name, (_, fields) in members.items():
+        lines.append(f'  printf("{name} %zu\\n", sizeof({name}));')
+        for f in fields:
+            lines.append(f'  printf("{name}.{f} %zu\\n", offsetof({name}, {f}));')
+    lines.append('  printf("saga_timings %zu\\n", sizeof(saga_timings));')
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for name, (cls, fields) in members.items():
+        assert int(got[name]) == ctypes.sizeof(cls), name
+        names = [f[0] for f in cls._fields_ if not f[0].startswith(("reserved", "pad"))]   # explicit padding in the binding
+        assert names == fields, (name, names)
+        for f in fields:
+            assert int(got[f"{name}.{f}"]) == getattr(cls, f).offset, (name, f)
+    assert int(got["saga_timings"]) == ctypes.sizeof(binding.Timings)
