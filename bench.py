@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--mma", type=int, default=None, help="1: bf16 sums accumulate on the matrix unit (library option mma)")
     ap.add_argument("--transform-first", type=int, default=None,
                     help="1: run the ApplyVertex product before the propagation where the layer narrows the rows (see saga_set_option)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="run Scatter, ApplyEdge and Gather as separate stages through a per-edge tensor (library option fused = 0)")
     ap.add_argument("--budget-gib", type=float, default=16.0, help="config5 only: device-memory budget")
     ap.add_argument("--dst-intervals", type=int, default=None, help="config5 only: force the plan")
     ap.add_argument("--src-intervals", type=int, default=None)
@@ -132,7 +134,8 @@ def main():
 
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
-                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first)):
+                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first),
+                      ("fused", 0 if args.unfused else None)):
         if val is not None:
             ctx.set_option(name, val)
     t0 = time.time()
@@ -220,7 +223,7 @@ def main():
         "config": {"workload": wl.name, "n_vertices": n, "nnz": nnz, "f_in": f_in, "f_out": f_out,
                    "edge_op": wl.edge_op, "agg": args.agg, "act": wl.act, "max_in_degree": info["max_in_degree"],
                    "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"],
-                   "hip_graph": bool(args.hip_graph), "transform_first": int(args.transform_first or 0)},
+                   "hip_graph": bool(args.hip_graph), "transform_first": int(args.transform_first or 0), "fused": not args.unfused},
         "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(f"spmm_d{args.density:g}" if args.workload == "spmm" else args.workload, nnz, info["n_work_items"], args.agg),
@@ -265,7 +268,7 @@ def main():
                                  "bytes": bytes_dense, "GBps": round(bytes_dense / (ms_dense * 1e-3) / 1e9, 1),
                                  "frac_of_hbm_peak": round(bytes_dense / (ms_dense * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
 
-    if (not args.transform_first and not args.hip_graph and has_w and wl.W_self is None and args.agg == "sum"
+    if (not args.transform_first and not args.hip_graph and not args.unfused and has_w and wl.W_self is None and args.agg == "sum"
             and wl.edge_op in ("copy", "mul_weight") and f_out < f_in):
         # the same layer with the product before the propagation (option transform_first), timed beside the headline
         ctx.set_option("transform_first", 1)

@@ -332,6 +332,11 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                at F_out values per edge. The same function (the linear stages commute; the operator motion
  *                of Section 3.2 taken one step further), with a different rounding order: sums are taken over
  *                rows of X W rounded to X's dtype. Off by default because it leaves the paper's stage order.
+ *   "fused"      0/1 (default 1): 0 runs Scatter, ApplyEdge and Gather of device-resident COPY / MUL_WEIGHT layers
+ *                as separate stages through a per-edge tensor of n_edges x F fp32 values held by the context
+ *                (the propagation without the fused operator of Section 3.2, the baseline of Section 6.2); other
+ *                messages return SAGA_ERR_UNSUPPORTED in this mode, a tensor above 128 GiB or the budget
+ *                SAGA_ERR_BUDGET. Max results are the same bits as the fused ones, sums differ in rounding order.
  *   "bwd_tile_rows"  streamed backward calls: rows per tile of the backward-ApplyVertex pass (default 0 = as
  *                many as make the widest tile about 64 MiB)
  *   "overlap"    streamed calls: 1 = copies on their own streams, overlapping the kernels

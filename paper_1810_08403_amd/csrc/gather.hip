@@ -968,6 +968,34 @@ __global__ __launch_bounds__(256) void k_f32_to_bf16(const float* in, uint16_t* 
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
         out[i] = f32_to_bf16_rne(in[i]);
 }
+// The stages run one by one, for the comparison with the fused operator (Section 3.2; the paper's baseline without
+// the optimised propagation, Section 6.2): Scatter writes the per-edge tensor S[e] = X[src e] (fp32), ApplyEdge
+// turns it into the messages in place (one fp32 multiply by the edge weight), and Gather then reads the messages
+// as rows of their own (edge e reads row e).
+template <typename T>
+__global__ __launch_bounds__(256) void k_stage_scatter(const T* __restrict__ X, int64_t ldx, const int32_t* __restrict__ src,
+                                                       float* __restrict__ S, int F, int64_t n_edges)
+{
+    const int64_t total = n_edges * F;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t e = i / F;
+        const int f = (int)(i - e * F);
+        const T x = X[(int64_t)src[e] * ldx + f];
+        if constexpr (sizeof(T) == 4)
+            S[i] = x;
+        else
+            S[i] = __uint_as_float((uint32_t)x << 16);
+    }
+}
+__global__ __launch_bounds__(256) void k_stage_apply_edge(float* __restrict__ S, const float* __restrict__ w, int F, int64_t n_edges)
+{
+    const int64_t total = n_edges * F;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) S[i] = w[i / F] * S[i];
+}
+__global__ __launch_bounds__(256) void k_iota_i32(int32_t* p, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = (int32_t)i;
+}
 __global__ __launch_bounds__(256) void k_copy_u128(uint4* dst, const uint4* src, int64_t count)
 {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
@@ -1120,6 +1148,25 @@ hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hip
 {
     if (count <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_f32_to_bf16, dim3(grid_for(count)), dim3(256), 0, s, in, out, count);
+    return hipGetLastError();
+}
+hipError_t launch_stage_scatter_apply(const void* X, int64_t ldx, int32_t dtype, const int32_t* src, const float* edge_w, float* S,
+                                      int32_t* iota, int32_t F, int64_t n_edges, hipStream_t s)
+{
+    if (n_edges <= 0 || F <= 0) return hipSuccess;
+    const int64_t total = n_edges * F;
+    if (dtype == SAGA_F32)
+        hipLaunchKernelGGL(k_stage_scatter<float>, dim3(grid_for(total)), dim3(256), 0, s, static_cast<const float*>(X), ldx, src, S, F, n_edges);
+    else
+        hipLaunchKernelGGL(k_stage_scatter<uint16_t>, dim3(grid_for(total)), dim3(256), 0, s, static_cast<const uint16_t*>(X), ldx, src, S, F,
+                           n_edges);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (edge_w) {
+        hipLaunchKernelGGL(k_stage_apply_edge, dim3(grid_for(total)), dim3(256), 0, s, S, edge_w, F, n_edges);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k_iota_i32, dim3(grid_for(n_edges)), dim3(256), 0, s, iota, n_edges);
     return hipGetLastError();
 }
 hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s)

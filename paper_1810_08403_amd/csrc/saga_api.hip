@@ -598,7 +598,7 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->ws_tile, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->ws_tile, &ctx->ws_edge_msg, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
                       &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials, &ctx->st_D, &ctx->st_S[0],
                       &ctx->st_S[1]})
         ctx->dev_free(b);
@@ -647,6 +647,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "bwd_tile_rows")) {
         if (value < 0 || value > (1LL << 31)) return ctx->fail(SAGA_ERR_INVALID_ARG, "bwd_tile_rows must be in [0, 2^31]");
         ctx->opt_bwd_tile_rows = value;
+    } else if (!strcmp(name, "fused")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "fused must be 0 or 1");
+        ctx->opt_fused = (int)value;
     } else if (!strcmp(name, "transform_first")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "transform_first must be 0 or 1");
         ctx->opt_transform_first = (int)value;
@@ -983,6 +986,27 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     if (g->n_slots > 0) {
         if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * ga.F)) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
+    }
+    if (!ctx->opt_fused) {
+        // the baseline of Section 6.2: the stages one by one through a materialised per-edge tensor, which the fused
+        // operator exists to avoid; Gather then is the same kernel reading message e for edge e
+        if (ep->op != SAGA_EDGE_COPY && ep->op != SAGA_EDGE_MUL_WEIGHT)
+            return ctx->fail(SAGA_ERR_UNSUPPORTED, "option fused = 0 covers COPY and MUL_WEIGHT messages");
+        const size_t msg_bytes = sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1) * ga.F;
+        const size_t all_bytes = (msg_bytes + 255) / 256 * 256 + sizeof(int32_t) * (size_t)std::max<int64_t>(g->nnz, 1);
+        if (all_bytes > ((size_t)128 << 30) || (ctx->budget > 0 && ctx->cur_bytes + all_bytes > ctx->budget))
+            return ctx->fail(SAGA_ERR_BUDGET, "the per-edge tensor of the unfused stages needs %zu bytes", all_bytes);
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_edge_msg, all_bytes)) return st;
+        float* msg = static_cast<float*>(ctx->ws_edge_msg.p);
+        int32_t* iota = reinterpret_cast<int32_t*>(static_cast<char*>(ctx->ws_edge_msg.p) + (msg_bytes + 255) / 256 * 256);
+        HIP_TRY(ctx, launch_stage_scatter_apply(ga.src, ga.ld_src, ga.dtype, ga.row_idx, ga.edge_w, msg, iota, ga.F, g->nnz, s));
+        ga.src = msg;
+        ga.ld_src = ga.F;
+        ga.dtype = SAGA_F32;
+        ga.row_idx = iota;
+        ga.edge_w = nullptr;
+        ga.op = SAGA_EDGE_COPY;
+        ga.mma = 0;
     }
     HIP_TRY(ctx, launch_gather(ga, s));
     if (es) HIP_TRY(ctx, hipEventRecord(es->ev[2], s));

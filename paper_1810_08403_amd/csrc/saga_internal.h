@@ -86,6 +86,7 @@ struct saga_ctx {
     int opt_overlap = 1;   // streamed path: copies on their own streams
     int64_t opt_bwd_tile_rows = 0;  // streamed backward: rows per tile of backward-ApplyVertex (0 = about 64 MiB)
     int opt_transform_first = 0;  // resident linear sum layers with F_out < F_in: Y = act(gather(X W) + bias)
+    int opt_fused = 1;            // 0: resident linear layers run Scatter, ApplyEdge and Gather as separate stages (baseline)
 
     // reusable workspace (grown on demand, never shrunk until destroy)
     DevBuf ws_accum;     // Gather output A (fp32 or bf16) when the caller gives no accum_out
@@ -110,6 +111,7 @@ struct saga_ctx {
     float* h_grad = nullptr;   // streamed backward of max / pooled layers: the gradient of accum of all vertices, pinned
     size_t h_grad_bytes = 0;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
+    DevBuf ws_edge_msg;  // stage-by-stage baseline: the per-edge tensor (n_edges x F fp32) and the edge numbers behind it
     DevBuf ws_tile;      // streamed backward of max / pooled layers: a tile of the gradient of accum, rows of X of an interval
 
     // profiling
@@ -281,6 +283,9 @@ hipError_t launch_pack_bt_rows(const float* Wsrc, int64_t ldw, int64_t col0, int
                                float* Bt, int64_t ldbt, int64_t row0, hipStream_t s);
 // Bt rows [0, R) = Wsrc[r][0 .. K), bf16
 hipError_t launch_pack_bt_rows_bf16(const uint16_t* Wsrc, int64_t ldw, int32_t R, int32_t K, uint16_t* Bt, int64_t ldbt, hipStream_t s);
+// Stage-by-stage baseline: S[e] = fp32(X[src e]) (Scatter), S[e] *= w_e (ApplyEdge, skipped without weights), iota[e] = e
+hipError_t launch_stage_scatter_apply(const void* X, int64_t ldx, int32_t dtype, const int32_t* src, const float* edge_w, float* S,
+                                      int32_t* iota, int32_t F, int64_t n_edges, hipStream_t s);
 hipError_t launch_zero_bytes(void* p, size_t bytes, hipStream_t s);
 
 // C[FP x FQ] = P^T Q over n rows (fp32), the rows divided over n_split ranges of
