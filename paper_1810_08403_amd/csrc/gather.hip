@@ -21,7 +21,9 @@
 // (fewer: several edges side by side in a wavefront), both templates over the
 // per-edge function; k_gather_wide_mma / k_gather_narrow_mma (optional: bf16
 // sums whose multiply-accumulate runs on the matrix unit); k_combine (partial
-// rows of cut columns); small fill / copy / validation kernels.
+// rows of cut columns); k_stage_scatter / k_stage_apply_edge (the stages one by
+// one through a per-edge tensor, the baseline the fused operator is measured
+// against); small fill / copy / validation kernels.
 #include <cmath>
 #include <type_traits>
 
