@@ -282,13 +282,20 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     ga.ld_out2 = ldh;
     if ((st = run_propagation(ctx, g->tr, ga, row_bytes))) return st;
 
-    // ApplyEdge parameter gradients
+    // ApplyEdge parameter gradients: [dPs | dM | dPd]^T X in one product (X is read once instead of three times);
+    // its three F x F blocks are dW_gate's left half, dW_msg and dW_gate's right half
     const float* Xp = static_cast<const float*>(X->data);
     float* dWg = static_cast<float*>(grads->dW_gate->data);
-    if ((st = param_grad(ctx, dH, ldh, F, Xp, X->ld, F, n, dWg, grads->dW_gate->ld))) return st;
-    if ((st = param_grad(ctx, dH + 2 * F, ldh, F, Xp, X->ld, F, n, dWg + F, grads->dW_gate->ld))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * 3 * (size_t)F * F))) return st;
+    float* blocks = static_cast<float*>(ctx->ws_tile.p);
+    if ((st = param_grad(ctx, dH, ldh, 3 * F, Xp, X->ld, F, n, blocks, F))) return st;
+    const size_t row = sizeof(float) * (size_t)F;
+    HIP_TRY(ctx, hipMemcpy2DAsync(dWg, sizeof(float) * (size_t)grads->dW_gate->ld, blocks, row, row, (size_t)F, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(ctx, hipMemcpy2DAsync(dWg + F, sizeof(float) * (size_t)grads->dW_gate->ld, blocks + 2 * (size_t)F * F, row, row, (size_t)F,
+                                  hipMemcpyDeviceToDevice, s));
     if (grads->dW_msg)
-        if ((st = param_grad(ctx, dH + F, ldh, F, Xp, X->ld, F, n, static_cast<float*>(grads->dW_msg->data), grads->dW_msg->ld))) return st;
+        HIP_TRY(ctx, hipMemcpy2DAsync(grads->dW_msg->data, sizeof(float) * (size_t)grads->dW_msg->ld, blocks + (size_t)F * F, row, row,
+                                      (size_t)F, hipMemcpyDeviceToDevice, s));
     if (grads->db_gate) {
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, sizeof(float) * (size_t)colsum_slabs(n) * F))) return st;
         HIP_TRY(ctx, launch_dz_colsum(dH + 2 * F, ldh, nullptr, 0, SAGA_ACT_NONE, nullptr, n, F, static_cast<float*>(ctx->ws_splitk.p),
