@@ -318,3 +318,30 @@ def test_team_mode_gated():
             assert_sum_close(A, ref["A"], ref["A_abs"], TOL_F32, f"team gated F={F}")
             assert_sum_close(Y, ref["Y"], ref["Y_abs"], TOL_F32, f"team gated layer F={F}")
             graph.destroy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_apply_vertex_product_at_ragged_shapes(ctx, dtype):
+    """ApplyVertex alone: on a graph of self-loops the Gather output is X, so Y = act(X W + b) is the dense product
+    kernel by itself. Row counts that end in the middle of a tile, K below, at and just above the K-tile width (odd
+    and even numbers of K tiles: an odd one is padded with a zero tile), N on both sides of every tile-shape switch."""
+    import paper_1810_08403_amd as saga
+    n = 3 * 128 + 77
+    idx = torch.arange(n, dtype=torch.int64)
+    g = si.build_csc(n, idx, idx)
+    graph = make_graph(ctx, g)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    for K, N in [(1, 1), (15, 33), (16, 32), (17, 31), (33, 65), (48, 64), (64, 128), (100, 129), (129, 200), (300, 7), (512, 256), (520, 24)]:
+        X = si.normal_features(n, K, 100 + K)
+        W = si.glorot_uniform(K, N, 200 + N)
+        b = si.uniform_pm(N, 0.5, 300 + N)
+        if dtype == "bf16":
+            X, W = si.round_to_bf16(X), si.round_to_bf16(W)
+        Y = torch.full((n, N), float("nan"), device="cuda", dtype=tdt)
+        ctx.layer_forward(graph, X.cuda().to(tdt), Y, edge_op="copy", W=W.cuda().to(tdt), bias=b.cuda(), act="relu")
+        torch.cuda.synchronize()
+        Zabs = X.double().abs() @ W.double().abs() + b.double().abs()
+        ref = torch.relu(X.double() @ W.double() + b.double())
+        assert_sum_close(Y.float().cpu().numpy(), ref.numpy(), Zabs.numpy(), tol, f"product {n} x {K} x {N} {dtype}")
+    graph.destroy()
