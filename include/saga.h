@@ -171,12 +171,12 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
  * Placement selects the path: all tensors SAGA_MEM_DEVICE with a device graph
  * -> resident; X and Y SAGA_MEM_HOST (pinned recommended) with a host graph ->
  * streamed through the context's budget, parameters still on the device. Streamed calls
- * cover all four layer programs in fp32: GATED and POOL first stream X through their
- * per-vertex products (Section 3.2) into pinned host memory held by the context, tile by
- * tile, and then run the chunk schedule on those rows (for GATED the rows [Ps | M] travel
- * and the destination parts Pd of the resident interval are copied in beside its
- * accumulator); with W_self the interval's own rows of X are copied in tile by tile for
- * the second operand of the ApplyVertex product.
+ * cover all four layer programs in fp32: for GATED and POOL the per-vertex products
+ * (Section 3.2) are formed on the device as the rows of X arrive (a source interval's rows
+ * of X are multiplied into the interval buffer: [Ps | M], or the pooled rows; for GATED the
+ * destination parts Pd of the resident interval are formed beside its accumulator from the
+ * interval's own rows of X), so the host link carries X only; with W_self the interval's own
+ * rows of X are copied in tile by tile for the second operand of the ApplyVertex product.
  *
  * Arithmetic: fp32 accumulation everywhere. BF16: X, W bf16; A is rounded to
  * bf16 (nearest even) once before the ApplyVertex product; Y is rounded to

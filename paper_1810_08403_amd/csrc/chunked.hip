@@ -309,7 +309,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const int64_t F_out = has_w ? vp->W->cols : Fw;
     if (n == 0) return SAGA_OK;
     if (n_out == 2 && (!extras->op || Fd != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "two outputs need a two-row edge function");
-    if (gated && (!extras || !extras->dst_rows || F != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "streamed gated call without its hoisted rows");
+    if (gated && (!extras || (!extras->dst_rows && !extras->dst_fill) || F != 2 * Fa))
+        return ctx->fail(SAGA_ERR_INTERNAL, "streamed gated call without its hoisted rows");
 
     WorkListParams wlp = work_list_params(ctx, F * 4);
     wlp.skip_empty = true;
@@ -452,16 +453,20 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * Fw, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
         if (gated) {  // the destination parts of this interval, once the previous interval's kernels have let go of the buffer
             if (d_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_d_free, 0));
-            const int64_t w1 = extras->dst2_rows ? Fa : Fd;  // columns that come from dst_rows
-            HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_D.p, (size_t)Fd * 4, extras->dst_rows + (int64_t)j * Dq * extras->ld_dst,
-                                          (size_t)extras->ld_dst * 4, (size_t)w1 * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
-            if (extras->dst2_rows)
-                HIP_TRY(ctx, hipMemcpy2DAsync(static_cast<float*>(ctx->st_D.p) + Fa, (size_t)Fd * 4,
-                                              extras->dst2_rows + (int64_t)j * Dq * extras->ld_dst2, (size_t)extras->ld_dst2 * 4,
-                                              (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+            if (extras->dst_fill) {
+                if (saga_status fs = extras->dst_fill((int64_t)j * Dq, rows_of(j), static_cast<float*>(ctx->st_D.p), sin, &bytes_h2d)) return fs;
+            } else {
+                const int64_t w1 = extras->dst2_rows ? Fa : Fd;  // columns that come from dst_rows
+                HIP_TRY(ctx, hipMemcpy2DAsync(ctx->st_D.p, (size_t)Fd * 4, extras->dst_rows + (int64_t)j * Dq * extras->ld_dst,
+                                              (size_t)extras->ld_dst * 4, (size_t)w1 * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+                if (extras->dst2_rows)
+                    HIP_TRY(ctx, hipMemcpy2DAsync(static_cast<float*>(ctx->st_D.p) + Fa, (size_t)Fd * 4,
+                                                  extras->dst2_rows + (int64_t)j * Dq * extras->ld_dst2, (size_t)extras->ld_dst2 * 4,
+                                                  (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
+                bytes_h2d += rows_of(j) * Fd * 4;
+            }
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
             HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
-            bytes_h2d += rows_of(j) * Fd * 4;
         }
         return SAGA_OK;
     };

@@ -430,10 +430,12 @@ saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga
     return SAGA_OK;
 }
 
-// A streamed layer of any of the four programs. Linear layers go straight to the chunk schedule. Layers whose ApplyEdge has
-// a per-vertex part (Section 3.2) first stream X through that product, tile by tile, into pinned host memory held by
-// the context (the paper's dataflow does the same when the hoisted products of a big graph do not fit the device:
-// they become vertex data of their own), then run the schedule on those rows.
+// A streamed layer of any of the four programs. Linear layers go straight to the chunk schedule. Layers whose ApplyEdge
+// has a per-vertex part (Section 3.2) form those products on the device as the rows of X arrive: a source interval's
+// rows of X are copied in and multiplied into the interval buffer ([Ps | M] of a gated layer, the pooled rows of a
+// max-pooling one), and a gated layer's destination parts Pd_j are formed the same way from the destination
+// interval's rows of X. The products therefore never cross the host link: it carries X once per destination
+// interval, like in a linear layer, instead of the two to three times wider hoisted rows there and back.
 static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
                                   const saga_vertex_params* vp, saga_tensor* Y)
 {
@@ -448,29 +450,84 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
         ex.F_self = F;
         use_ex = true;
     }
-    if (!gated && !pool) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
+    if ((!gated && !pool) || n == 0) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
 
-    const int32_t Fh = gated ? 3 * F : (int32_t)ep->W_pool->rows;  // width of the per-vertex rows
-    if (saga_status st = stream_hoist_to_host(ctx, X, ep, n, F, Fh)) return st;
+    hipStream_t s = ctx->stream;
+    const int32_t Fh = gated ? 2 * F : (int32_t)ep->W_pool->rows;  // width of the rows that travel over the edges
+    // packed weights of the per-vertex products, in a buffer of their own (the schedule packs ApplyVertex's into ws_bt):
+    // gated: rows [W_gs ; W_m ; W_gd] with the bias behind W_gd's rows; pooled: W_pool
+    const int32_t n_rows = gated ? 3 * F : Fh;
+    int64_t n_pad, k_pad;
+    bt_padded_shape(n_rows, F, SAGA_F32, &n_pad, &k_pad);
+    n_pad += 128;  // the product over W_gd starts in the middle of the buffer and reads whole tiles of rows
+    saga_status st;
+    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
+    if ((st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)n_rows))) return st;
+    float* bt = static_cast<float*>(ctx->ws_wt.p);
+    float* bias = static_cast<float*>(ctx->ws_bias.p);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)n_rows, s));
+    if (gated) {
+        const float* Wg = static_cast<const float*>(ep->W_gate->data);
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr, ep->W_msg ? ep->W_msg->ld : 0, 0,
+                                         F, F, bt, k_pad, F, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
+        if (ep->b_gate)
+            HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
+    } else {
+        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, Fh, F, bt, k_pad, 0, s));
+        if (ep->b_pool) HIP_TRY(ctx, hipMemcpyAsync(bias, ep->b_pool->data, sizeof(float) * (size_t)Fh, hipMemcpyDeviceToDevice, s));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(s));  // the products below run on the schedule's copy-in stream
+    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_tile}) ctx->dev_free(b);  // sized per interval below
 
-    saga_tensor hx{};
-    hx.data = ctx->h_hoist;
+    // rows [row0, row0 + rows) of X into `tmp`, then tmp x (n_cols rows of the packed weights from row w0 on) into dst
+    auto product = [&](DevBuf* tmp, int64_t row0, int64_t rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, hipStream_t on,
+                       int64_t* h2d) -> saga_status {
+        if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)rows * F)) return e;  // grows once: intervals do not grow
+        HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+        *h2d += rows * (int64_t)F * 4;
+        GemmArgs hg{};
+        hg.A = tmp->p;
+        hg.lda = F;
+        hg.Bt = bt + (int64_t)w0 * k_pad;
+        hg.ldbt = k_pad;
+        hg.bias = bias + w0;
+        hg.C = dst;
+        hg.ldc = n_cols;
+        hg.M = rows;
+        hg.N = n_cols;
+        hg.K = F;
+        hg.dtype = hg.out_dtype = SAGA_F32;
+        hg.act = act;
+        HIP_TRY(ctx, launch_gemm(hg, on));
+        return SAGA_OK;
+    };
+    VertexFeed feed;
+    feed.bytes_per_row = sizeof(float) * (size_t)F;
+    feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
+        return product(&ctx->ws_accum, row0, rows, 0, Fh, pool ? (int32_t)SAGA_ACT_SIGMOID : (int32_t)SAGA_ACT_NONE, dst, on, h2d);
+    };
+    saga_tensor hx{};  // shape of the rows that travel; the feed supplies them
+    hx.data = nullptr;
     hx.rows = n;
+    hx.cols = hx.ld = Fh;
     hx.dtype = SAGA_F32;
     hx.mem = SAGA_MEM_HOST;
-    hx.ld = Fh;
     saga_edge_params e2 = *ep;
     if (pool) {  // the pooled rows are plain vertex data now
-        hx.cols = Fh;
         e2.op = SAGA_EDGE_COPY;
-    } else {     // rows [Ps | M] travel; the destination parts Pd sit behind them in every row
-        hx.cols = 2 * F;
+    } else {     // rows [Ps | M] travel, the destination parts Pd of the resident interval are formed beside its accumulator
         ex.acc_width = F;
-        ex.dst_rows = ctx->h_hoist + 2 * F;
-        ex.ld_dst = Fh;
+        ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
+        ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+            return product(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, on, h2d);
+        };
         use_ex = true;
     }
-    return streamed_forward(ctx, g, &hx, &e2, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
+    return streamed_forward(ctx, g, &hx, &e2, agg, vp, Y, &feed, use_ex ? &ex : nullptr);
 }
 
 extern "C" {

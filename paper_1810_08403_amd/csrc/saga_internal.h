@@ -352,9 +352,10 @@ struct VertexFeed {
     std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, bool first_visit, int64_t* h2d)> fill;
     size_t bytes_per_row = 0;
 };
-// What the streamed schedule needs beyond a linear layer. Gated layers: X is the host array of hoisted rows [Ps | M]
-// (2F wide), the accumulator rows are acc_width = F wide, and the destination parts Pd of every destination interval
-// are made resident from dst_rows while the interval is worked on. W_self layers: the interval's own rows of the
+// What the streamed schedule needs beyond a linear layer. Gated layers: the rows that travel are the hoisted rows
+// [Ps | M] (2F wide; X gives their shape, a feed or a host array the values), the accumulator rows are acc_width = F
+// wide, and the destination parts Pd of every destination interval are made resident from dst_rows, or by dst_fill,
+// while the interval is worked on. W_self layers: the interval's own rows of the
 // layer input are copied in tile by tile for the second operand of the ApplyVertex product.
 struct StreamExtras {
     int32_t acc_width = 0;             // 0: as wide as X's rows
@@ -368,6 +369,9 @@ struct StreamExtras {
     int32_t dst_width = 0;             // 0: acc_width
     const float* dst2_rows = nullptr;  // host, n rows of acc_width values, ld_dst2 elements apart
     int64_t ld_dst2 = 0;
+    // instead of dst_rows: produces the constant rows of destinations [row0, row0 + rows) in dst (dst_width wide,
+    // compact) on stream s and adds the bytes it copies to *h2d (a gated layer forms Pd of the interval from its rows of X)
+    std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, int64_t* h2d)> dst_fill;
     int32_t n_out = 1;                 // 2: the edge function has two outputs; accumulator rows are [out | out2]
     // called once per destination interval after its last chunk, before ApplyVertex, with the interval's accumulator
     // rows on the device (compute stream s): the backward pass of pooled messages goes through the sigmoid there
