@@ -267,12 +267,14 @@ typedef struct saga_layer_grads {
  * pair of the schedule's last product, fed by tiles of dZ formed the same way). Without
  * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Max and pooled layers
  * take three passes: tiles of rows for backward-ApplyVertex, which also send the gradient of accum
- * out to pinned host memory of the library's own (pooled layers stream X through W_pool as their
- * forward call does); the chunk schedule over the edges clustered by source, in which rows
+ * out to pinned host memory of the library's own; the chunk schedule over the edges clustered by source, in which rows
  * [A | gradient of accum] travel and the row of the vertex itself (x_u or its pooled row) sits
  * beside the accumulator for the max decision (sum over pooled rows: the gradient of accum travels
- * as plain vertex data); and per interval, while its sums are on the device, the pooled layers'
- * sigmoid derivative, dW_pool, db_pool and the product dX = dPre W_pool. Gated layers take the
+ * as plain vertex data; pooled rows are formed again on the device from the interval's rows of X);
+ * and per interval, while its sums are on the device, the pooled layers' sigmoid derivative,
+ * dW_pool, db_pool and the product dX = dPre W_pool. Gated layers (whose products Ps, M, Pd
+ * are formed on the device from the rows of X of the interval that needs them, as in the forward
+ * call) take the
  * tile pass, then the schedule over the in-edges (rows [Ps | M] travel, [Pd | gradient of accum]
  * of the resident interval are the constants: dPd, and per interval its share of dW_gate's right
  * half and of db_gate), then the schedule over the edges clustered by source (rows

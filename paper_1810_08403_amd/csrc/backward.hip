@@ -828,7 +828,7 @@ own_rows_fill(saga_ctx* ctx, const saga_tensor* dY, const saga_tensor* Y, int32_
 // Streamed backward pass of a layer with the max accumulator (COPY, MUL_WEIGHT or POOL messages) or with pooled messages
 // under the sum accumulator; X, A, Y, dY and dX in host memory. Three passes:
 //   1. tiles of rows: dZ, dW += A^T dZ, dbias (dW_self), and the gradient of accum dZ W^T out to pinned host memory;
-//      pooled layers also stream X through their per-vertex product (stream_hoist_to_host);
+//      pooled rows are formed again on the device, interval by interval, from the rows of X (VertexProducts);
 //   2. the chunk schedule over the edges clustered by source. Max: rows [A | gradient of accum] of the destination side
 //      travel, the row of the vertex itself (x_u, or its pooled row) sits beside the accumulator, and the edge function
 //      is the max-gradient one of the resident pass; sum over pooled rows: the gradient of accum travels as it is;
@@ -866,14 +866,12 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
     }
     if (!propagate) return SAGA_OK;
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
+    VertexProducts prod;  // pooled rows are formed on the device from the rows of X, interval by interval
     if (pool)
-        if ((st = stream_hoist_to_host(ctx, X, ep, n, F, Fm))) return st;
+        if ((st = prod.init(ctx, X, ep))) return st;
     if ((st = ensure_transposed_host(ctx, g))) return st;
-
-    // the per-vertex part of the message: the pooled rows, or X itself
-    const float* S = pool ? ctx->h_hoist : static_cast<const float*>(X->data);
-    const int64_t lds = pool ? Fm : X->ld;
     const float* h_dA = ctx->h_grad;
+    float* pooled_j = nullptr;  // where dst_fill left the pooled rows of the resident interval (its rows of X are in ws_tile)
     VertexFeed feed;
     StreamExtras ex;
     saga_tensor rows_t{};  // shape of the rows that travel
@@ -896,8 +894,15 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         };
         ex.op = kGatherOpMaxGrad;
         ex.acc_width = Fm;
-        ex.dst_rows = S;
-        ex.ld_dst = lds;
+        if (pool) {  // the vertex's own pooled row beside its accumulator
+            ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+                pooled_j = dst;
+                return prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_SIGMOID, dst, Fm, on, h2d);
+            };
+        } else {
+            ex.dst_rows = static_cast<const float*>(X->data);
+            ex.ld_dst = X->ld;
+        }
     } else {
         rows_t.data = ctx->h_grad;  // sum over pooled rows: the gradient of accum travels unchanged
         rows_t.cols = rows_t.ld = Fm;
@@ -949,15 +954,15 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         }
         bool any_done = false;
         ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
-            // the interval's pooled rows and its rows of X, on the compute stream (its kernels wait for them anyway)
-            if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fm)) return e;  // intervals do not grow
-            if (saga_status e = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * (size_t)rows * F)) return e;
-            float* tS = static_cast<float*>(ctx->ws_hoist.p);
-            float* tX = static_cast<float*>(ctx->ws_tile.p);
-            HIP_TRY(ctx, hipMemcpyAsync(tS, ctx->h_hoist + row0 * Fm, sizeof(float) * (size_t)rows * Fm, hipMemcpyHostToDevice, on));
-            HIP_TRY(ctx, hipMemcpy2DAsync(tX, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
-                                          sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
-            *h2d += rows * (int64_t)(Fm + F) * 4;
+            // the interval's pooled rows and its rows of X: left by dst_fill (max), or formed here, on the compute stream
+            // (sum: there are no constant rows, and the kernels that follow wait for them anyway)
+            float* tS = pooled_j;
+            if (agg != SAGA_AGG_MAX) {
+                if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fm)) return e;  // intervals do not grow
+                tS = static_cast<float*>(ctx->ws_hoist.p);
+                if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_SIGMOID, tS, Fm, on, h2d)) return e;
+            }
+            const float* tX = static_cast<const float*>(ctx->ws_tile.p);
             HIP_TRY(ctx, launch_sigmoid_grad(acc, tS, rows * (int64_t)Fm, on));
             if (saga_status e = param_grad(ctx, acc, Fm, Fm, tX, F, F, rows, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld,
                                            any_done ? 1 : 0, on, false))
@@ -976,10 +981,9 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
 }
 
 // Streamed backward pass of a gated layer (sum accumulator); X, A, Y, dY and dX in host memory. The per-vertex products
-// [Ps | M | Pd] of all vertices and the per-vertex gradients [dPs | dM | dPd] pass through pinned host memory of the
-// library's own, as the forward call's products do:
-//   1. tiles of rows: dZ, dW += A^T dZ, dbias, and the gradient of accum dZ W^T out to pinned memory; X through the
-//      per-vertex products (stream_hoist_to_host);
+// [Ps | M | Pd] are formed on the device from the rows of X of the interval that needs them, as in the forward call;
+// the gradient of accum and the per-vertex gradients [dPs | dM | dPd] pass through pinned host memory of the library's own:
+//   1. tiles of rows: dZ, dW += A^T dZ, dbias, and the gradient of accum dZ W^T out to pinned memory;
 //   2. the chunk schedule over the in-edges: rows [Ps | M] travel, [Pd | gradient of accum] of the resident interval sit
 //      beside its accumulator, edge function "gate gradient": dPd_j. Per interval: dW_gd += dPd_j^T X_j, db += sums;
 //      dPd_j goes out to pinned memory;
@@ -1021,9 +1025,10 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
         return SAGA_OK;
     }
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
-    if ((st = stream_hoist_to_host(ctx, X, ep, n, F, 3 * F))) return st;
+    VertexProducts prod;  // [Ps | M] and Pd of an interval are formed on the device from its rows of X, which stay in
+                          // ws_tile (resident interval) for the parameter gradients added up per interval
+    if ((st = prod.init(ctx, X, ep))) return st;
     if ((st = ensure_transposed_host(ctx, g))) return st;
-    const float* H = ctx->h_hoist;                 // [Ps | M | Pd], 3F per vertex
     const float* h_dA = ctx->h_grad;               // F per vertex
     float* h_dH = ctx->h_grad + (size_t)n * F;     // [dPs | dM | dPd], 3F per vertex
     const int64_t ldh = 3 * (int64_t)F;
@@ -1036,43 +1041,41 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
         const size_t need = std::max(sizeof(float) * (size_t)nsp * F * F, sizeof(float) * (size_t)colsum_slabs(n) * F);
         if ((st = ctx->dev_alloc(&ctx->ws_splitk, need))) return st;
     }
-    // an interval's rows of X on the device, for the parameter gradients both schedules add up per interval
-    auto x_rows = [&](int64_t row0, int64_t rows, hipStream_t on, int64_t* h2d, float** tX) -> saga_status {
-        if (saga_status e = ctx->dev_alloc(&ctx->ws_tile, sizeof(float) * (size_t)rows * F)) return e;  // intervals do not grow
-        *tX = static_cast<float*>(ctx->ws_tile.p);
-        HIP_TRY(ctx, hipMemcpy2DAsync(*tX, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
-                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
-        *h2d += rows * (int64_t)F * 4;
-        return SAGA_OK;
-    };
     saga_edge_params et{};
     et.op = SAGA_EDGE_COPY;  // the chunks carry no edge data; the edge function is named in the extras
 
     // ---- pass 2: destination parts, over the in-edges ----
     {
-        saga_tensor rows_t{};
-        rows_t.data = const_cast<float*>(H);
+        saga_tensor rows_t{};  // shape of the rows that travel, [Ps | M]: the feed forms them from the interval's rows of X
         rows_t.rows = n;
-        rows_t.cols = 2 * F;
-        rows_t.ld = ldh;
+        rows_t.cols = rows_t.ld = 2 * F;
         rows_t.dtype = SAGA_F32;
         rows_t.mem = SAGA_MEM_HOST;
         saga_tensor out_t = rows_t;
         out_t.data = h_dH + 2 * F;
         out_t.cols = F;
+        out_t.ld = ldh;
+        VertexFeed feed;
+        feed.bytes_per_row = sizeof(float) * (size_t)F;
+        feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
+            return prod.rows(&ctx->ws_accum, row0, rows, 0, 2 * F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d);
+        };
         StreamExtras ex;
         ex.op = kGatherOpGateGrad;
         ex.acc_width = F;
         ex.dst_width = 2 * F;
-        ex.dst_rows = H + 2 * F;
-        ex.ld_dst = ldh;
-        ex.dst2_rows = h_dA;
-        ex.ld_dst2 = F;
+        ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+            // [Pd | gradient of accum] of the resident interval; its rows of X stay in ws_tile for after_gather
+            if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d)) return e;
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * 2 * (size_t)F, h_dA + row0 * F, sizeof(float) * (size_t)F,
+                                          sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)F * 4;
+            return SAGA_OK;
+        };
         ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
         bool any_done = false;
-        ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
-            float* tX = nullptr;
-            if (saga_status e = x_rows(row0, rows, on, h2d, &tX)) return e;
+        ex.after_gather = [&, any_done](int64_t, int64_t rows, float* acc, hipStream_t on, int64_t*) mutable -> saga_status {
+            const float* tX = static_cast<const float*>(ctx->ws_tile.p);
             if (saga_status e = param_grad(ctx, acc, F, F, tX, F, F, rows, dWg + F, lddwg, any_done ? 1 : 0, on, false)) return e;
             if (grads->db_gate)
                 HIP_TRY(ctx, launch_dz_colsum(acc, F, nullptr, 0, SAGA_ACT_NONE, nullptr, rows, F, static_cast<float*>(ctx->ws_splitk.p),
@@ -1080,7 +1083,7 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
             any_done = true;
             return SAGA_OK;
         };
-        if ((st = streamed_forward(ctx, g, &rows_t, &et, SAGA_AGG_SUM, nullptr, &out_t, nullptr, &ex))) return st;
+        if ((st = streamed_forward(ctx, g, &rows_t, &et, SAGA_AGG_SUM, nullptr, &out_t, &feed, &ex))) return st;
     }
 
     // ---- pass 3: source parts and dX, over the edges clustered by source ----
@@ -1105,13 +1108,13 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     rows_t.dtype = SAGA_F32;
     rows_t.mem = SAGA_MEM_HOST;
     VertexFeed feed;
+    feed.bytes_per_row = sizeof(float) * (size_t)F;
     feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
         // [the destination part of the gate's argument | the gradient of accum] of the vertices at the far end of the out-edges
-        HIP_TRY(ctx, hipMemcpy2DAsync(dst, sizeof(float) * 2 * (size_t)F, H + row0 * ldh + 2 * F, sizeof(float) * (size_t)ldh,
-                                      sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+        if (saga_status e = prod.rows(&ctx->ws_accum, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d)) return e;
         HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * 2 * (size_t)F, h_dA + row0 * F, sizeof(float) * (size_t)F,
                                       sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
-        *h2d += rows * 2 * (int64_t)F * 4;
+        *h2d += rows * (int64_t)F * 4;
         return SAGA_OK;
     };
     StreamExtras ex;
@@ -1119,8 +1122,10 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ex.acc_width = F;
     ex.n_out = 2;
     ex.dst_width = 2 * F;
-    ex.dst_rows = H;  // [Ps | M]
-    ex.ld_dst = ldh;
+    ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+        // [Ps | M] of the resident interval; its rows of X stay in ws_tile for after_gather
+        return prod.rows(&ctx->ws_tile, row0, rows, 0, 2 * F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d);
+    };
     if (with_self) {  // second operand rows [dPd | dZ]: the vertex's own partial gradient dZ W_self^T rides along
         ex.F_self = F + Fo;
         ex.self_fill = own_rows_fill(ctx, dY, Y, vp->act, Fo, h_dH + 2 * F, ldh, F, self_tile);
@@ -1131,9 +1136,8 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     }
     ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
     bool any_done = false;
-    ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
-        float* tX = nullptr;
-        if (saga_status e = x_rows(row0, rows, on, h2d, &tX)) return e;
+    ex.after_gather = [&, any_done](int64_t, int64_t rows, float* acc, hipStream_t on, int64_t*) mutable -> saga_status {
+        const float* tX = static_cast<const float*>(ctx->ws_tile.p);
         if (saga_status e = param_grad(ctx, acc, 2 * (int64_t)F, F, tX, F, F, rows, dWg, lddwg, any_done ? 1 : 0, on, false)) return e;
         if (grads->dW_msg)
             if (saga_status e = param_grad(ctx, acc + F, 2 * (int64_t)F, F, tX, F, F, rows, static_cast<float*>(grads->dW_msg->data),

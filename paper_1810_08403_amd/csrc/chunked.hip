@@ -354,27 +354,44 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     } else if (Q > 0 && P > 0) {
         if (Q > n || P > n) return ctx->fail(SAGA_ERR_INVALID_ARG, "more intervals than vertices");
     } else {
+        int best_q = 0, best_p = 0;
+        // For every number of destination intervals, the fewest source intervals that fit. Every destination interval
+        // re-reads all vertex data over the link, so fewer of them is better, unless what is left of the budget then
+        // only fits slivers of source intervals: each (destination, source) step costs a fixed time on top of its
+        // bytes (taken as the time of 2 MiB on the link), so a plan with a few more destination intervals and far
+        // fewer steps can be cheaper. The search goes on past the first fit while that fit is this fine-grained.
         bool found = false;
+        double best_cost = 0.0;
+        int further = 0;
         const int qs[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 256, 512, 1024};
         const int ps[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
         for (int q : qs) {
             if ((Q > 0 && q != Q) || q > n) continue;
+            int fit_p = 0;
             for (int p : ps) {
                 if ((P > 0 && p != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
                 const size_t need = need_for(q, p);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
                 if ((ctx->budget == 0 && small_enough) || (ctx->budget > 0 && need + held <= ctx->budget)) {
-                    Q = q;
-                    P = p;
-                    found = true;
+                    fit_p = p;
                     break;
                 }
             }
-            if (found) break;
+            if (!fit_p) continue;
+            const double cost = (double)q * (double)n * F * 4 + (double)q * fit_p * (double)(2 << 20);
+            if (!found || cost < best_cost) {
+                found = true;
+                best_cost = cost;
+                best_q = q;
+                best_p = fit_p;
+            }
+            if (fit_p <= 32 || ++further > 3) break;
         }
         if (!found)
             return ctx->fail(SAGA_ERR_BUDGET, "no vertex-interval x edge-chunk plan fits %zu bytes of device memory", ctx->budget);
+        Q = best_q;
+        P = best_p;
     }
     y_tile_rows = tile_rows_for(Q);
     if (!(same_grid && g->grid->Q == Q && g->grid->P == P))
@@ -563,13 +580,14 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     // ApplyVertex on the resident A_j (or A_j itself when there is none) and its way back to the host
     auto apply_and_drain = [&](int j) -> saga_status {
         const int64_t v0 = (int64_t)j * Dq, rows = rows_of(j);
-        if (gated) {  // every kernel that reads the destination parts of this interval has been enqueued
-            HIP_TRY(ctx, hipEventRecord(grid->ev_d_free, sc));
-            d_busy = true;
-        }
         if (agg == SAGA_AGG_MAX) HIP_TRY(ctx, launch_neg_inf_to_zero(A, rows * Fw, sc));
         if (extras && extras->after_gather)
             if (saga_status hs = extras->after_gather(v0, rows, A, sc, &bytes_h2d)) return hs;
+        if (gated) {  // every kernel that reads the destination parts of this interval (or what dst_fill left beside them,
+                      // which after_gather may use) has been enqueued
+            HIP_TRY(ctx, hipEventRecord(grid->ev_d_free, sc));
+            d_busy = true;
+        }
         if (!Yh) {  // nobody wants the rows (a backward pass that only needs what after_gather adds up)
             HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
             a_busy = true;

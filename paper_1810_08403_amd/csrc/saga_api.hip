@@ -380,53 +380,60 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
     return SAGA_OK;
 }
 
-// The per-vertex products of a gated or pooled layer (Section 3.2) for every vertex of a host-resident X, tile by tile
-// through the device into pinned host memory (ctx->h_hoist, n rows of Fh values): [Ps | M | Pd] (Fh = 3F) or the pooled
-// rows sigmoid(X W_pool^T + b) (Fh = F_pool). Returns after the last copy has arrived.
-saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fh)
+saga_status VertexProducts::init(saga_ctx* c, const saga_tensor* x, const saga_edge_params* ep)
 {
-    const bool gated = ep->op == SAGA_EDGE_GATED;
-    const size_t need = sizeof(float) * (size_t)std::max<int64_t>(n, 1) * Fh;
-    if (ctx->h_hoist_bytes < need) {
-        if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
-        ctx->h_hoist = nullptr;
-        ctx->h_hoist_bytes = 0;
-        HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_hoist), need, hipHostMallocDefault));
-        ctx->h_hoist_bytes = need;
-    }
-    // tiles of about 64 MiB of per-vertex rows; smaller when that is what the budget leaves beside the schedule's
-    // buffers of an earlier call (giving those up and allocating them again costs more than smaller tiles do)
-    int64_t T = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(n, 1), std::max<int64_t>(4096, ((int64_t)64 << 20) / (4 * (int64_t)Fh))));
-    const size_t fixed = sizeof(float) * (size_t)(Fh + 128) * (F + 64) + (1 << 20);  // packed weights, slack
-    const size_t per_row = sizeof(float) * ((size_t)F + Fh);
-    if (ctx->budget > 0 && ctx->cur_bytes + fixed + per_row * (size_t)T > ctx->budget) {
-        auto left = [&]() { return ctx->budget > ctx->cur_bytes + fixed ? ctx->budget - ctx->cur_bytes - fixed : (size_t)0; };
-        if (left() / per_row < 2048) ctx->make_room(fixed + per_row * (size_t)T);
-        T = std::max<int64_t>(64, std::min<int64_t>(T, (int64_t)(left() / per_row)));
-    }
-    if (saga_status st = ctx->dev_alloc(&ctx->ws_accum, sizeof(float) * (size_t)T * F)) return st;
+    ctx = c;
+    X = x;
+    F = (int32_t)x->cols;
     hipStream_t s = ctx->stream;
-    int64_t h2d = 0, d2h = 0;
-    for (int64_t r0 = 0; r0 < n; r0 += T) {
-        const int64_t rows = std::min(T, n - r0);
-        HIP_TRY(ctx, hipMemcpy2DAsync(ctx->ws_accum.p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + r0 * X->ld,
-                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, s));
-        saga_tensor xt{};
-        xt.data = ctx->ws_accum.p;
-        xt.rows = rows;
-        xt.cols = F;
-        xt.ld = F;
-        xt.dtype = SAGA_F32;
-        xt.mem = SAGA_MEM_DEVICE;
-        if (saga_status st = gated ? hoist_gated(ctx, &xt, ep, rows, F) : hoist_pool(ctx, &xt, ep, rows, F, Fh)) return st;
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->h_hoist + r0 * Fh, ctx->ws_hoist.p, sizeof(float) * (size_t)rows * Fh, hipMemcpyDeviceToHost, s));
-        h2d += rows * (int64_t)F * 4;
-        d2h += rows * (int64_t)Fh * 4;
+    const bool gated = ep->op == SAGA_EDGE_GATED;
+    const int32_t n_rows = gated ? 3 * F : (int32_t)ep->W_pool->rows;
+    int64_t n_pad;
+    bt_padded_shape(n_rows, F, SAGA_F32, &n_pad, &k_pad);
+    n_pad += 128;  // a product may start in the middle of the buffer (W_gd) and reads whole tiles of rows
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_prod, sizeof(float) * (size_t)(n_pad * k_pad))) return st;
+    if (saga_status st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)n_rows)) return st;
+    bt = static_cast<float*>(ctx->ws_prod.p);
+    bias = static_cast<float*>(ctx->ws_bias.p);
+    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
+    HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)n_rows, s));
+    if (gated) {
+        const float* Wg = static_cast<const float*>(ep->W_gate->data);
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr, ep->W_msg ? ep->W_msg->ld : 0, 0,
+                                         F, F, bt, k_pad, F, s));
+        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
+        if (ep->b_gate)
+            HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
+    } else {
+        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, n_rows, F, bt, k_pad, 0, s));
+        if (ep->b_pool) HIP_TRY(ctx, hipMemcpyAsync(bias, ep->b_pool->data, sizeof(float) * (size_t)n_rows, hipMemcpyDeviceToDevice, s));
     }
-    HIP_TRY(ctx, hipStreamSynchronize(s));
-    ctx->acc.bytes_h2d += h2d;
-    ctx->acc.bytes_d2h += d2h;
-    for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_hoist}) ctx->dev_free(b);  // make room under the budget
+    HIP_TRY(ctx, hipStreamSynchronize(s));  // the products run on other streams of the schedule
+    return SAGA_OK;
+}
+
+saga_status VertexProducts::rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
+                                 hipStream_t on, int64_t* h2d) const
+{
+    if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)n_rows * F)) return e;  // grows once: intervals do not grow
+    HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                  sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)n_rows, hipMemcpyHostToDevice, on));
+    *h2d += n_rows * (int64_t)F * 4;
+    GemmArgs hg{};
+    hg.A = tmp->p;
+    hg.lda = F;
+    hg.Bt = bt + (int64_t)w0 * k_pad;
+    hg.ldbt = k_pad;
+    hg.bias = bias + w0;
+    hg.C = dst;
+    hg.ldc = ldc;
+    hg.M = n_rows;
+    hg.N = n_cols;
+    hg.K = F;
+    hg.dtype = hg.out_dtype = SAGA_F32;
+    hg.act = act;
+    HIP_TRY(ctx, launch_gemm(hg, on));
     return SAGA_OK;
 }
 
@@ -452,63 +459,14 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
     }
     if ((!gated && !pool) || n == 0) return streamed_forward(ctx, g, X, ep, agg, vp, Y, nullptr, use_ex ? &ex : nullptr);
 
-    hipStream_t s = ctx->stream;
     const int32_t Fh = gated ? 2 * F : (int32_t)ep->W_pool->rows;  // width of the rows that travel over the edges
-    // packed weights of the per-vertex products, in a buffer of their own (the schedule packs ApplyVertex's into ws_bt):
-    // gated: rows [W_gs ; W_m ; W_gd] with the bias behind W_gd's rows; pooled: W_pool
-    const int32_t n_rows = gated ? 3 * F : Fh;
-    int64_t n_pad, k_pad;
-    bt_padded_shape(n_rows, F, SAGA_F32, &n_pad, &k_pad);
-    n_pad += 128;  // the product over W_gd starts in the middle of the buffer and reads whole tiles of rows
-    saga_status st;
-    if ((st = ctx->dev_alloc(&ctx->ws_wt, sizeof(float) * (size_t)(n_pad * k_pad)))) return st;
-    if ((st = ctx->dev_alloc(&ctx->ws_bias, sizeof(float) * (size_t)n_rows))) return st;
-    float* bt = static_cast<float*>(ctx->ws_wt.p);
-    float* bias = static_cast<float*>(ctx->ws_bias.p);
-    HIP_TRY(ctx, launch_zero_bytes(bt, sizeof(float) * (size_t)(n_pad * k_pad), s));
-    HIP_TRY(ctx, launch_zero_bytes(bias, sizeof(float) * (size_t)n_rows, s));
-    if (gated) {
-        const float* Wg = static_cast<const float*>(ep->W_gate->data);
-        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, 0, F, F, bt, k_pad, 0, s));
-        HIP_TRY(ctx, launch_pack_bt_rows(ep->W_msg ? static_cast<const float*>(ep->W_msg->data) : nullptr, ep->W_msg ? ep->W_msg->ld : 0, 0,
-                                         F, F, bt, k_pad, F, s));
-        HIP_TRY(ctx, launch_pack_bt_rows(Wg, ep->W_gate->ld, F, F, F, bt, k_pad, 2 * (int64_t)F, s));
-        if (ep->b_gate)
-            HIP_TRY(ctx, hipMemcpyAsync(bias + 2 * F, ep->b_gate->data, sizeof(float) * (size_t)F, hipMemcpyDeviceToDevice, s));
-    } else {
-        HIP_TRY(ctx, launch_pack_bt_rows(static_cast<const float*>(ep->W_pool->data), ep->W_pool->ld, 0, Fh, F, bt, k_pad, 0, s));
-        if (ep->b_pool) HIP_TRY(ctx, hipMemcpyAsync(bias, ep->b_pool->data, sizeof(float) * (size_t)Fh, hipMemcpyDeviceToDevice, s));
-    }
-    HIP_TRY(ctx, hipStreamSynchronize(s));  // the products below run on the schedule's copy-in stream
+    VertexProducts prod;
+    if (saga_status st = prod.init(ctx, X, ep)) return st;
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_tile}) ctx->dev_free(b);  // sized per interval below
-
-    // rows [row0, row0 + rows) of X into `tmp`, then tmp x (n_cols rows of the packed weights from row w0 on) into dst
-    auto product = [&](DevBuf* tmp, int64_t row0, int64_t rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, hipStream_t on,
-                       int64_t* h2d) -> saga_status {
-        if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)rows * F)) return e;  // grows once: intervals do not grow
-        HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
-                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
-        *h2d += rows * (int64_t)F * 4;
-        GemmArgs hg{};
-        hg.A = tmp->p;
-        hg.lda = F;
-        hg.Bt = bt + (int64_t)w0 * k_pad;
-        hg.ldbt = k_pad;
-        hg.bias = bias + w0;
-        hg.C = dst;
-        hg.ldc = n_cols;
-        hg.M = rows;
-        hg.N = n_cols;
-        hg.K = F;
-        hg.dtype = hg.out_dtype = SAGA_F32;
-        hg.act = act;
-        HIP_TRY(ctx, launch_gemm(hg, on));
-        return SAGA_OK;
-    };
     VertexFeed feed;
     feed.bytes_per_row = sizeof(float) * (size_t)F;
     feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
-        return product(&ctx->ws_accum, row0, rows, 0, Fh, pool ? (int32_t)SAGA_ACT_SIGMOID : (int32_t)SAGA_ACT_NONE, dst, on, h2d);
+        return prod.rows(&ctx->ws_accum, row0, rows, 0, Fh, pool ? (int32_t)SAGA_ACT_SIGMOID : (int32_t)SAGA_ACT_NONE, dst, Fh, on, h2d);
     };
     saga_tensor hx{};  // shape of the rows that travel; the feed supplies them
     hx.data = nullptr;
@@ -523,7 +481,7 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
         ex.acc_width = F;
         ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
         ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
-            return product(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, on, h2d);
+            return prod.rows(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, F, on, h2d);
         };
         use_ex = true;
     }
@@ -655,11 +613,10 @@ saga_status saga_destroy(saga_ctx* ctx)
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias,
-                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->ws_tile, &ctx->ws_edge_msg, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
+                      &ctx->ws_flag, &ctx->ws_dz, &ctx->ws_grad, &ctx->ws_splitk, &ctx->ws_edge_t, &ctx->ws_dh, &ctx->ws_dz16, &ctx->ws_wt, &ctx->ws_tile, &ctx->ws_edge_msg, &ctx->ws_prod, &ctx->st_A, &ctx->st_V[0], &ctx->st_V[1],
                       &ctx->st_C[0], &ctx->st_C[1], &ctx->st_Y[0], &ctx->st_Y[1], &ctx->st_partials, &ctx->st_D, &ctx->st_S[0],
                       &ctx->st_S[1]})
         ctx->dev_free(b);
-    if (ctx->h_hoist) (void)hipHostFree(ctx->h_hoist);
     if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);

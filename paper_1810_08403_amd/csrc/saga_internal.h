@@ -106,11 +106,10 @@ struct saga_ctx {
     // streamed calls: accumulator interval, two vertex intervals, two chunk payloads, two output tiles, partial rows
     DevBuf st_A, st_V[2], st_C[2], st_Y[2], st_partials;
     DevBuf st_D, st_S[2];  // gated: destination parts of the resident interval; W_self: tiles of the interval's own rows
-    float* h_hoist = nullptr;  // streamed gated / pooled layers: the per-vertex products of all vertices in pinned host memory
-    size_t h_hoist_bytes = 0;
     float* h_grad = nullptr;   // streamed backward of max / pooled layers: the gradient of accum of all vertices, pinned
     size_t h_grad_bytes = 0;
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
+    DevBuf ws_prod;      // streamed gated / pooled layers: packed weights of the per-vertex products (VertexProducts)
     DevBuf ws_edge_msg;  // stage-by-stage baseline: the per-edge tensor (n_edges x F fp32) and the edge numbers behind it
     DevBuf ws_tile;      // streamed backward of max / pooled layers: a tile of the gradient of accum, rows of X of an interval
 
@@ -388,7 +387,22 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                              int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,
                              const StreamExtras* extras = nullptr);
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* grid);
-saga_status stream_hoist_to_host(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fh);
+// The per-vertex products of a gated or pooled ApplyEdge (Section 3.2) formed on the device from rows of a host X, for
+// the streamed calls: init packs the weights (gated: rows [W_gs ; W_m ; W_gd] and the gate bias behind W_gd's rows;
+// pooled: W_pool and its bias) into buffers of the context and waits for that; rows copies rows [row0, row0 + rows) of
+// X into *tmp (grown to rows x F floats once) and writes tmp x (n_cols rows of the packed weights from row w0 on)^T
+// + bias, through `act`, to dst with row stride ldc, all on stream `on`.
+struct VertexProducts {
+    saga_ctx* ctx = nullptr;
+    const saga_tensor* X = nullptr;
+    int32_t F = 0;
+    float* bt = nullptr;
+    float* bias = nullptr;
+    int64_t k_pad = 0;
+    saga_status init(saga_ctx* c, const saga_tensor* x, const saga_edge_params* ep);
+    saga_status rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
+                     hipStream_t on, int64_t* h2d) const;
+};
 void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device
