@@ -15,8 +15,9 @@
 //     with or without W_self), or, for the max accumulator and pooled messages, with the
 //     gradient of accum passing through pinned host memory between a tile pass and the
 //     schedule, and a per-interval finish on the device; gated layers run the schedule
-//     twice (in-edges, then edges by source), their per-vertex products and gradients
-//     passing through pinned memory as well. In all of them a W_self term adds its
+//     twice (in-edges, then edges by source), their per-vertex gradients passing through
+//     pinned memory as well; the per-vertex products of gated and pooled layers are formed
+//     again on the device from the rows of X. In all of them a W_self term adds its
 //     gradient tile by tile and its share of dX inside the schedule's last product.
 #include <cstring>
 
