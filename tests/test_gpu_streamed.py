@@ -473,8 +473,8 @@ def test_streamed_max_pooling_and_commnet_layers(agg):
 
 
 def test_streamed_apps_respect_the_budget_over_repeated_calls():
-    """The per-vertex products of gated and pooled layers are formed outside the chunk schedule; together with the
-    schedule's buffers of the previous call they still have to stay under the budget."""
+    """The per-vertex products of gated and pooled layers are formed on the device inside the chunk schedule, through
+    buffers of their own; together with the schedule's buffers they have to stay under the budget, call after call."""
     import paper_1810_08403_amd as saga
     budget = 8 << 20
     ctx = saga.Context(0, hbm_budget_bytes=budget)
@@ -655,3 +655,35 @@ def test_streamed_backward_own_product_in_every_layer_program(edge_op, agg, act,
         if want_dx:
             assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
     ctx.destroy()
+
+
+@pytest.mark.parametrize("app", ["gated", "pool"])
+def test_streamed_products_never_cross_the_host_link(app):
+    """Gated and pooled layers from host memory: the per-vertex products are formed on the device from the rows of X,
+    so what crosses the link is X once per destination interval (plus, for a gated layer, once more for the
+    destination parts), the edge chunks and Y: not the two to three times wider products."""
+    import paper_1810_08403_amd as saga
+    Q, P = 2, 3
+    if app == "gated":
+        wl = si.workload(4, scale=12, f_in=32, f_out=24)
+        kw = dict(edge_op="gated", W_gate=wl.W_gate.cuda(), b_gate=wl.b_gate.cuda(), W_msg=wl.W_msg.cuda())
+        ref = run_oracle(wl, agg="sum", hoisted=True)
+        x_passes = Q + 1
+    else:
+        wl = si.mpgcn_workload(scale=12, f_in=32, f_pool=96, f_out=24)
+        kw = dict(edge_op="pool", agg="max", W_pool=wl.W_pool.cuda(), b_pool=wl.b_pool.cuda())
+        ref = run_oracle(wl, agg="max", hoisted=True)
+        x_passes = Q
+    g = wl.graph
+    n, F = wl.X.shape
+    with new_context(dst_intervals=Q, src_intervals=P) as ctx:
+        graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+        Y = torch.full((n, 24), float("nan")).pin_memory()
+        ctx.reset_timings()
+        ctx.layer_forward(graph, wl.X.clone().pin_memory(), Y, W=wl.W.cuda(), act=wl.act, **kw)
+        t = ctx.get_timings()
+        assert_sum_close(Y.numpy(), ref["Y"], ref["Y_abs"], TOL_F32, f"streamed {app} layer")
+        x_bytes = n * F * 4
+        chunk_bytes = g.nnz * 4 + 64 * (g.nnz // 16 + n) + Q * P * 4096     # ids, a generous bound on work items, padding
+        assert t["bytes_d2h"] == n * 24 * 4, t
+        assert x_passes * x_bytes <= t["bytes_h2d"] <= x_passes * x_bytes + chunk_bytes, (t["bytes_h2d"], x_bytes, chunk_bytes)
