@@ -79,3 +79,12 @@ def test_header_is_plain_c_and_its_layouts_are_the_binding_s(tmp_path):
         for f in fields:
             assert int(got[f"{name}.{f}"]) == getattr(cls, f).offset, (name, f)
     assert int(got["saga_timings"]) == ctypes.sizeof(binding.Timings)
+
+
+def test_every_option_of_saga_set_option_is_documented_in_the_header():
+    src = open(os.path.join(ROOT, "paper_1810_08403_amd", "csrc", "saga_api.hip")).read()
+    names = set(re.findall(r'!strcmp\(name, "([a-z_0-9]+)"\)', src))
+    assert len(names) >= 10
+    header = open(os.path.join(ROOT, "include", "saga.h")).read()
+    missing = [n for n in sorted(names) if f'"{n}"' not in header]
+    assert not missing, f"options without a line in saga.h: {missing}"
