@@ -321,7 +321,11 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                as two bf16 parts (w = hi + lo to 2^-18 relative); products and sums stay fp32. A
  *                non-finite feature then turns up to 32 features of the destination row into NaN, not one.
  *                Measured: 40 % fewer vector-ALU instructions, the same time (the kernel waits for the L2).
- *   "dst_intervals" / "src_intervals"  streamed plan override, 0 = automatic
+ *   "dst_intervals" / "src_intervals"  streamed plan override, 0 = automatic. k intervals hold
+ *                ceil(n / k) vertices each; where that leaves the last ones empty (7 vertices,
+ *                k = 5) the plan has only the intervals that hold vertices (4), and
+ *                saga_get_timings reports that number. More intervals than vertices:
+ *                SAGA_ERR_INVALID_ARG.
  *   "schedule"   streamed calls: 0 = the paper's schedule (Section 3.1: an accumulator chunk
  *                stays on the device until its ApplyVertex has consumed it); the two baselines
  *                the paper measures against (Section 6.2): 1 = stage by stage (all Gather

@@ -344,6 +344,14 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     };
     // the grid of an earlier call is kept if it was made for the same tunables and, under a budget, this call fits
     // it too (a backward pass holds more per vertex than the forward pass whose grid it finds)
+    // k intervals of ceil(n / k) rows leave the last ones empty when n is small against k * k (7 vertices in 5 intervals
+    // of 2): a grid only ever has the intervals that hold vertices
+    auto whole = [&](int k) {
+        const int64_t rows = (n + k - 1) / k;
+        return (int)((n + rows - 1) / rows);
+    };
+    if (Q > 0 && Q <= n) Q = whole(Q);
+    if (P > 0 && P <= n) P = whole(P);
     bool reuse = same_grid && (Q == 0 || Q == g->grid->Q) && (P == 0 || P == g->grid->P);
     if (reuse && ctx->budget > 0 && (Q == 0 || P == 0) &&
         need_of(g->grid->Q, g->grid->P, g->grid->max_chunk_bytes, (size_t)g->grid->max_slots) + held > ctx->budget)
@@ -366,10 +374,10 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         const int qs[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 256, 512, 1024};
         const int ps[] = {1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096};
         for (int q : qs) {
-            if ((Q > 0 && q != Q) || q > n) continue;
+            if ((Q > 0 && whole(q) != Q) || q > n) continue;
             int fit_p = 0;
             for (int p : ps) {
-                if ((P > 0 && p != P) || p > n || p < q) continue;
+                if ((P > 0 && whole(p) != P) || p > n || p < q) continue;
                 // without a cap, stop growing P once a source interval is below 1 GiB
                 const size_t need = need_for(q, p);
                 const bool small_enough = (size_t)((n + p - 1) / p) * F * 4 <= ((size_t)1 << 30);
@@ -390,8 +398,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         }
         if (!found)
             return ctx->fail(SAGA_ERR_BUDGET, "no vertex-interval x edge-chunk plan fits %zu bytes of device memory", ctx->budget);
-        Q = best_q;
-        P = best_p;
+        Q = whole(best_q);
+        P = whole(best_p);
     }
     y_tile_rows = tile_rows_for(Q);
     if (!(same_grid && g->grid->Q == Q && g->grid->P == P))

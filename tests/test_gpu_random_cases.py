@@ -90,9 +90,9 @@ def test_random_forward_case(seed):
         if agg == "max" and op in ("copy", "mul_weight"):
             assert_bit_equal(A.cpu().numpy(), ref["A"], what + " max Gather")
         else:
-            assert_sum_close(A.cpu().numpy(), ref["A"], ref["A_abs"], TOL_F32, what + " Gather")
+            assert_sum_close(A.cpu().numpy(), ref["A"], ref["A_abs"], TOL_F32, what + " Gather", tiny_outputs=True)
         if n > 0:
-            assert_sum_close(Y.float().cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_BF16 if dtype == "bf16" else TOL_F32, what + " layer")
+            assert_sum_close(Y.float().cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_BF16 if dtype == "bf16" else TOL_F32, what + " layer", tiny_outputs=True)
         graph.destroy()
 
 
@@ -120,11 +120,11 @@ def test_random_linear_backward_case(seed):
                          dX=dX, dbias=db, dW_self=dWs)
         torch.cuda.synchronize()
         what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} self={Ws is not None}"
-        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW")
-        assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX")
-        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias")
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW", tiny_outputs=True)
+        assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX", tiny_outputs=True)
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias", tiny_outputs=True)
         if Ws is not None:
-            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self")
+            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self", tiny_outputs=True)
         graph.destroy()
 
 
@@ -162,7 +162,7 @@ def test_random_gated_and_max_backward_case(seed):
             if Ws is not None:
                 got["dW_self"] = dWs
             for name, v in got.items():
-                assert_sum_close(v.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " gated " + name)
+                assert_sum_close(v.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " gated " + name, tiny_outputs=True)
         else:                                                    # max over weighted messages
             w = t(g.nnz)
             fwd = oracle.layer(cp, ri, X.numpy(), "mul_weight", w.numpy(), agg="max", W=W.numpy(), act=act, W_self=Wsn)
@@ -171,8 +171,117 @@ def test_random_gated_and_max_backward_case(seed):
             c.layer_backward(graph, f32(bwd["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(fwd["Y"]), edge_op="mul_weight", agg="max",
                              edge_weight=w.cuda(), act=act, dX=dX, W_self=Wsd, dW_self=dWs)
             torch.cuda.synchronize()
-            assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " max dW")
-            assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " max dX")
+            assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " max dW", tiny_outputs=True)
+            assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " max dX", tiny_outputs=True)
             if Ws is not None:
-                assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " max dW_self")
+                assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " max dW_self", tiny_outputs=True)
         graph.destroy()
+
+
+def _pinned(a):
+    return torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).clone().pin_memory()
+
+
+@pytest.mark.parametrize("seed", range(max(24, N_CASES // 2)))
+def test_random_streamed_case(seed):
+    """The same kind of random case with X, Y and the graph in host memory: a random grid of intervals or a random
+    budget, a random schedule, forwards against the oracle's layer, then (where the oracle's argmax decisions do not
+    depend on the precision of a sigmoid) backwards against the oracle's gradients, twice on the same handles."""
+    import paper_1810_08403_amd as saga
+    rng, g, F, Fo, op, agg, act, _ = _case(2000 + seed)
+    n = g.n
+    F = min(F, 132)
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    X, W, bias, dY = t(n, F), t(F, Fo, s=0.3), t(Fo, s=0.2), t(n, Fo)
+    Ws = t(F, Fo, s=0.3) if rng.random() < 0.35 else None
+    w = t(g.nnz) if op == "mul_weight" else None
+    kw, okw, Fm = {}, {}, F
+    if op == "gated":
+        Wg, bg, Wm = t(F, 2 * F, s=0.3), t(F, s=0.2), (t(F, F, s=0.3) if rng.random() < 0.6 else None)
+        kw = dict(W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=None if Wm is None else Wm.cuda())
+        okw = dict(W_gate=Wg.numpy(), b_gate=bg.numpy(), W_msg=None if Wm is None else Wm.numpy())
+    if op == "pool":
+        Fm = int(rng.choice([2, 8, 20, 64]))
+        Wp, bp = t(Fm, F, s=0.3), t(Fm, s=0.2)
+        W = t(Fm, Fo, s=0.3)
+        kw = dict(W_pool=Wp.cuda(), b_pool=bp.cuda())
+        okw = dict(W_pool=Wp.numpy(), b_pool=bp.numpy())
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    wn = None if w is None else w.numpy()
+    Wsn, Wsd = (None, None) if Ws is None else (Ws.numpy(), Ws.cuda())
+    fwd = oracle.layer(cp, ri, X.numpy(), op, wn, agg=agg, W=W.numpy(), W_self=Wsn, bias=bias.numpy(), act=act, **okw)
+
+    # the plan: a fixed grid, or a budget a little above what a random grid of this layer would need
+    opts = dict(schedule=int(rng.choice([0, 0, 1, 2])), overlap=int(rng.integers(2)), bwd_tile_rows=int(rng.choice([0, 64, 300, 1000])))
+    budget = 0
+    if rng.random() < 0.6 or n < 8:
+        opts.update(dst_intervals=int(rng.integers(1, min(n, 5) + 1)), src_intervals=int(rng.integers(1, min(n, 7) + 1)))
+    else:
+        budget = int((n * (3 * F + Fm + Fo) * 4 + g.nnz * 8) * rng.uniform(0.25, 1.2)) + (1 << 20)
+    what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fm}->{Fo} {op} {agg} {act} self={Ws is not None} {opts} budget={budget}"
+    print(what, flush=True)
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    for name, val in opts.items():
+        ctx.set_option(name, val)
+    graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)          # host graph
+    if w is not None:
+        graph.set_edge_data(w)
+    X_h = _pinned(X)
+    Y_h = torch.full((n, Fo), float("nan")).pin_memory()
+    for rep in range(2):
+        Y_h.fill_(float("nan"))
+        try:
+            ctx.layer_forward(graph, X_h, Y_h, edge_op=op, agg=agg, W=W.cuda(), W_self=Wsd, bias=bias.cuda(), act=act, **kw)
+        except saga.SagaError as e:
+            assert budget and e.status == 4, what      # SAGA_ERR_BUDGET: a random budget may be below any plan
+            graph.destroy()
+            ctx.destroy()
+            return
+        if n > 0:
+            assert_sum_close(Y_h.numpy(), fwd["Y"], fwd["Y_abs"], TOL_F32, what + f" layer, call {rep}", tiny_outputs=True)
+    if budget:
+        assert ctx.peak_device_bytes() <= budget, what
+        tm = ctx.get_timings()
+        print(f"  plan {tm['plan_dst_intervals']} x {tm['plan_src_intervals']}, peak {ctx.peak_device_bytes()} of {budget}", flush=True)
+    if agg == "max" and op in ("copy", "mul_weight") and Ws is None:
+        A_h = torch.full((n, F), float("nan")).pin_memory()          # without W the call returns the Gather output itself
+        ctx.layer_forward(graph, X_h, A_h, edge_op=op, agg=agg)
+        assert_bit_equal(A_h.numpy(), fwd["A"], what + " max Gather")
+
+    backward = (op in ("copy", "mul_weight")) or (op == "gated" and agg == "sum")
+    if backward and n > 0:
+        if op == "gated":
+            bwd = oracle.gated_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), bias=bias.numpy(), act=act, W_self=Wsn, **okw)
+        elif agg == "max":
+            bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), op, edge_weight=wn, bias=bias.numpy(), act=act, W_self=Wsn)
+        else:
+            bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
+        A_h, Yf_h, dY_h = _pinned(bwd["A"] if agg == "max" else fwd["A"]), _pinned(fwd["Y"]), _pinned(dY)
+        dX_h = torch.full((n, F), float("nan")).pin_memory()
+        nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+        out = dict(dW=nan(Fm, Fo), dbias=nan(Fo))
+        if Ws is not None:
+            out["dW_self"] = nan(F, Fo)
+        if op == "gated":
+            out.update(dW_gate=nan(F, 2 * F), db_gate=nan(F))
+            if okw["W_msg"] is not None:
+                out["dW_msg"] = nan(F, F)
+        for rep, want_dx in enumerate([True, False]):
+            for v in out.values():
+                v.fill_(float("nan"))
+            dX_h.fill_(float("nan"))
+            rest = {k: v for k, v in out.items() if k != "dW"}
+            try:
+                ctx.layer_backward(graph, A_h, dY_h, W.cuda(), out["dW"], X=X_h, Y=Yf_h, dX=dX_h if want_dx else None, edge_op=op, agg=agg,
+                                   bias=bias.cuda(), W_self=Wsd, act=act, **rest, **kw)
+            except saga.SagaError as e:
+                assert budget and e.status == 4, what  # the backward pass holds more per vertex than the forward pass
+                break
+            for name, got in out.items():
+                assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + f" backward {name}, call {rep}", tiny_outputs=True)
+            if want_dx:
+                assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + f" backward dX, call {rep}", tiny_outputs=True)
+        if budget:
+            assert ctx.peak_device_bytes() <= budget, what + " (backward)"
+    graph.destroy()
+    ctx.destroy()
