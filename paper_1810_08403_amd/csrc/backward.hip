@@ -404,9 +404,11 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     float* dS = grads->dX ? static_cast<float*>(grads->dX->data) : nullptr;
     int64_t ldds = grads->dX ? grads->dX->ld : 0;
     if (pool) {
-        if ((st = hoist_pool(ctx, X, ep, n, F, Fm))) return st;
+        // the pooled rows h are what a max Gather compares with; a sum needs only their pre-activations, further down
+        if (agg == SAGA_AGG_MAX)
+            if ((st = hoist_pool(ctx, X, ep, n, F, Fm))) return st;
         if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)n * Fm))) return st;
-        S = static_cast<const float*>(ctx->ws_hoist.p);
+        S = static_cast<const float*>(ctx->ws_hoist.p);  // (read by the max Gather's way back only)
         lds = Fm;
         dS = static_cast<float*>(ctx->ws_dh.p);
         ldds = Fm;
@@ -435,8 +437,11 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     }
     if (!pool) return SAGA_OK;
 
-    // through the sigmoid, then the per-vertex product: dPre = dS (.) h (1 - h), dW_pool = dPre^T X, db_pool, dX = dPre W_pool
-    HIP_TRY(ctx, launch_sigmoid_grad(dS, S, n * (int64_t)Fm, s));
+    // through the sigmoid, then the per-vertex product: dPre = dS (.) sigmoid'(z), dW_pool = dPre^T X, db_pool, dX = dPre W_pool.
+    // The slope comes from the pre-activations z = X W_pool^T + b, formed once more over the pooled rows (which are
+    // done with): h (1 - h) from an fp32 h has lost the slope of a saturated unit.
+    if ((st = hoist_pool(ctx, X, ep, n, F, Fm, SAGA_ACT_NONE))) return st;
+    HIP_TRY(ctx, launch_sigmoid_grad(dS, static_cast<const float*>(ctx->ws_hoist.p), n * (int64_t)Fm, s));
     const float* Xp = static_cast<const float*>(X->data);
     if ((st = param_grad(ctx, dS, Fm, Fm, Xp, X->ld, F, n, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
     if (grads->db_pool) {
@@ -834,7 +839,7 @@ own_rows_fill(saga_ctx* ctx, const saga_tensor* dY, const saga_tensor* Y, int32_
 //      travel, the row of the vertex itself (x_u, or its pooled row) sits beside the accumulator, and the edge function
 //      is the max-gradient one of the resident pass; sum over pooled rows: the gradient of accum travels as it is;
 //   3. per interval, while its sums dS are still on the device: pooled layers go through the sigmoid
-//      (dPre = dS (.) h (1 - h)), add dPre^T X and the column sums of dPre to dW_pool and db_pool, and the schedule's
+//      (dPre = dS (.) sigmoid'(z), the slope formed from the interval's pre-activations), add dPre^T X and the column sums of dPre to dW_pool and db_pool, and the schedule's
 //      ApplyVertex product is dX = dPre W_pool; otherwise dS is dX.
 saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                                        const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
@@ -961,7 +966,11 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
             if (agg != SAGA_AGG_MAX) {
                 if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fm)) return e;  // intervals do not grow
                 tS = static_cast<float*>(ctx->ws_hoist.p);
-                if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_SIGMOID, tS, Fm, on, h2d)) return e;
+                if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_NONE, tS, Fm, on, h2d)) return e;
+            } else {
+                // the pooled rows are done with: their pre-activations take their place (the slope of a saturated unit
+                // cannot be had from an fp32 h), from the interval's rows of X that dst_fill left in ws_tile
+                if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_NONE, tS, Fm, on, h2d, false)) return e;
             }
             const float* tX = static_cast<const float*>(ctx->ws_tile.p);
             HIP_TRY(ctx, launch_sigmoid_grad(acc, tS, rows * (int64_t)Fm, on));

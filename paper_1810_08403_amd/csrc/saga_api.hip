@@ -352,7 +352,7 @@ saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_par
 
 // Figure 11's ApplyEdge depends on the source only: H = sigmoid(X Wp^T + bp) once per vertex (Section 3.2),
 // into ctx->ws_hoist (n x Fm fp32)
-saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm)
+saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm, int32_t act)
 {
     hipStream_t s = ctx->stream;
     int64_t n_pad, k_pad;
@@ -375,7 +375,7 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
     hg.N = Fm;
     hg.K = F;
     hg.dtype = hg.out_dtype = SAGA_F32;
-    hg.act = SAGA_ACT_SIGMOID;
+    hg.act = act;
     HIP_TRY(ctx, launch_gemm(hg, s));
     return SAGA_OK;
 }
@@ -414,12 +414,16 @@ saga_status VertexProducts::init(saga_ctx* c, const saga_tensor* x, const saga_e
 }
 
 saga_status VertexProducts::rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
-                                 hipStream_t on, int64_t* h2d) const
+                                 hipStream_t on, int64_t* h2d, bool upload) const
 {
-    if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)n_rows * F)) return e;  // grows once: intervals do not grow
-    HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
-                                  sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)n_rows, hipMemcpyHostToDevice, on));
-    *h2d += n_rows * (int64_t)F * 4;
+    if (upload) {
+        if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)n_rows * F)) return e;  // grows once: intervals do not grow
+        HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)n_rows, hipMemcpyHostToDevice, on));
+        *h2d += n_rows * (int64_t)F * 4;
+    } else if (!tmp->p || tmp->bytes < sizeof(float) * (size_t)n_rows * F) {
+        return ctx->fail(SAGA_ERR_INTERNAL, "per-vertex product from rows that were never brought in");
+    }
     GemmArgs hg{};
     hg.A = tmp->p;
     hg.lda = F;

@@ -315,7 +315,7 @@ hipError_t launch_dz_bf16(const uint16_t* dY, int64_t lddy, const uint16_t* Y, i
                           int32_t F, hipStream_t s);
 hipError_t launch_permute_f32(const float* in, const int32_t* perm, float* out, int64_t count, hipStream_t s);
 // d[i] *= h[i] * (1 - h[i]): a gradient taken through a sigmoid whose outputs are h (both compact, count elements)
-hipError_t launch_sigmoid_grad(float* d, const float* h, int64_t count, hipStream_t s);
+hipError_t launch_sigmoid_grad(float* d, const float* z, int64_t count, hipStream_t s);  // d *= sigmoid'(z)
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
@@ -323,7 +323,9 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes);
 // per-vertex products of a gated ApplyEdge into ctx->ws_hoist, rows [Ps | M | Pd (+ b)] (saga_api.hip)
 saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F);
 // per-vertex messages of a max-pooling ApplyEdge into ctx->ws_hoist, n x Fm (saga_api.hip)
-saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm);
+// act: SAGA_ACT_SIGMOID for the pooled rows themselves, SAGA_ACT_NONE for their pre-activations (backward pass)
+saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm,
+                       int32_t act = SAGA_ACT_SIGMOID);
 // backward pass of a resident layer (backward.hip)
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
@@ -400,8 +402,9 @@ struct VertexProducts {
     float* bias = nullptr;
     int64_t k_pad = 0;
     saga_status init(saga_ctx* c, const saga_tensor* x, const saga_edge_params* ep);
+    // upload = false: tmp already holds these rows of X (an earlier call for the same rows left them there)
     saga_status rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
-                     hipStream_t on, int64_t* h2d) const;
+                     hipStream_t on, int64_t* h2d, bool upload = true) const;
 };
 void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
 

@@ -178,6 +178,46 @@ def test_random_gated_and_max_backward_case(seed):
         graph.destroy()
 
 
+@pytest.mark.parametrize("seed", range(max(12, N_CASES // 6)))
+def test_random_pooled_max_backward_case(seed):
+    """Figure 11's layer backwards on the device: max over pooled messages, random widths, with saturated units among
+    them (the slope of a sigmoid near 0 or 1 must keep its relative accuracy)."""
+    rng, g, F, Fo, _, _, _, _ = _case(1300 + seed)
+    n = g.n
+    act = ["relu", "none", "sigmoid"][seed % 3]
+    Fm = int(rng.choice([1, 2, 8, 20, 64, 100]))
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    # coarse values: the order of the pooled sigmoids, ties included, is the same in fp32 and in fp64
+    X = torch.round(t(n, F).clamp(-1, 1) * 4) / 4
+    # (pre-activations stay below about 10 in size: from 17 on an fp32 sigmoid is exactly 1 and ties appear that fp64 does not have)
+    Wp = torch.round(t(Fm, F, s=0.3 * min(1.0, 6.0 / F ** 0.5)).clamp(-0.5, 0.5) * 8) / 8
+    bp = torch.round(t(Fm, s=1.5).clamp(-4, 4) * 8) / 8
+    W, dY, bias = t(Fm, Fo, s=0.3), t(n, Fo), t(Fo, s=0.2)
+    Ws = t(F, Fo, s=0.3) if seed % 4 == 1 else None
+    Wsn, Wsd = (None, None) if Ws is None else (Ws.numpy(), Ws.cuda())
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), "pool", W_pool=Wp.numpy(), b_pool=bp.numpy(), bias=bias.numpy(),
+                              act=act, W_self=Wsn)
+    what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fm}->{Fo} {act} self={Ws is not None}"
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    with new_context() as c:
+        graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        kw = dict(edge_op="pool", agg="max", W_pool=Wp.cuda(), b_pool=bp.cuda(), bias=bias.cuda(), act=act, W_self=Wsd)
+        Y, A = nan(n, Fo), nan(n, Fm)
+        c.layer_forward(graph, X.cuda(), Y, W=W.cuda(), accum_out=A, **kw)       # the device's own pooled maxima
+        torch.cuda.synchronize()
+        assert_sum_close(A.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " pooled Gather", tiny_outputs=True)
+        out = dict(dW=nan(Fm, Fo), dbias=nan(Fo), dW_pool=nan(Fm, F), db_pool=nan(Fm), dX=nan(n, F))
+        if Ws is not None:
+            out["dW_self"] = nan(F, Fo)
+        rest = {k: v for k, v in out.items() if k != "dW"}
+        c.layer_backward(graph, A, dY.cuda(), W.cuda(), out["dW"], X=X.cuda(), Y=Y, **rest, **kw)
+        torch.cuda.synchronize()
+        for name, got in out.items():
+            assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " " + name, tiny_outputs=True)
+        graph.destroy()
+
+
 def _pinned(a):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).clone().pin_memory()
 
@@ -204,6 +244,9 @@ def test_random_streamed_case(seed):
         Fm = int(rng.choice([2, 8, 20, 64]))
         Wp, bp = t(Fm, F, s=0.3), t(Fm, s=0.2)
         W = t(Fm, Fo, s=0.3)
+        if agg == "max":   # coarse values: the order of the pooled sigmoids, ties included, is the same in fp32 and in fp64
+            X = torch.round(X.clamp(-1, 1) * 4) / 4
+            Wp, bp = torch.round(Wp.clamp(-0.5, 0.5) * 8) / 8, torch.round(bp.clamp(-0.5, 0.5) * 8) / 8
         kw = dict(W_pool=Wp.cuda(), b_pool=bp.cuda())
         okw = dict(W_pool=Wp.numpy(), b_pool=bp.numpy())
     cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
@@ -248,15 +291,27 @@ def test_random_streamed_case(seed):
         ctx.layer_forward(graph, X_h, A_h, edge_op=op, agg=agg)
         assert_bit_equal(A_h.numpy(), fwd["A"], what + " max Gather")
 
-    backward = (op in ("copy", "mul_weight")) or (op == "gated" and agg == "sum")
+    backward = (op in ("copy", "mul_weight")) or (op == "gated" and agg == "sum") or (op == "pool" and agg == "max")
     if backward and n > 0:
         if op == "gated":
             bwd = oracle.gated_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), bias=bias.numpy(), act=act, W_self=Wsn, **okw)
         elif agg == "max":
-            bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), op, edge_weight=wn, bias=bias.numpy(), act=act, W_self=Wsn)
+            bwd = oracle.max_backward(cp, ri, X.numpy(), dY.numpy(), W.numpy(), op, edge_weight=wn, bias=bias.numpy(), act=act, W_self=Wsn,
+                                      **okw)
         else:
             bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
         A_h, Yf_h, dY_h = _pinned(bwd["A"] if agg == "max" else fwd["A"]), _pinned(fwd["Y"]), _pinned(dY)
+        if op == "pool":
+            # the backward pass recomputes the pooled rows in fp32 and looks for them in A bit for bit: A comes from the
+            # device's own forward pass (resident, a second context), checked against the oracle's before it is used
+            with new_context() as c2:
+                g2 = c2.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+                Yd, Ad = torch.empty(n, Fo, device="cuda"), torch.empty(n, Fm, device="cuda")
+                c2.layer_forward(g2, X.cuda(), Yd, edge_op=op, agg=agg, W=W.cuda(), W_self=Wsd, bias=bias.cuda(), act=act, accum_out=Ad, **kw)
+                torch.cuda.synchronize()
+                g2.destroy()
+            assert_sum_close(Ad.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " pooled Gather")
+            A_h, Yf_h = _pinned(Ad.cpu().numpy()), _pinned(Yd.cpu().numpy())
         dX_h = torch.full((n, F), float("nan")).pin_memory()
         nan = lambda *s: torch.full(s, float("nan"), device="cuda")
         out = dict(dW=nan(Fm, Fo), dbias=nan(Fo))
@@ -266,6 +321,8 @@ def test_random_streamed_case(seed):
             out.update(dW_gate=nan(F, 2 * F), db_gate=nan(F))
             if okw["W_msg"] is not None:
                 out["dW_msg"] = nan(F, F)
+        if op == "pool":
+            out.update(dW_pool=nan(Fm, F), db_pool=nan(Fm))
         for rep, want_dx in enumerate([True, False]):
             for v in out.values():
                 v.fill_(float("nan"))
