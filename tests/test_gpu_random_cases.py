@@ -218,6 +218,44 @@ def test_random_pooled_max_backward_case(seed):
         graph.destroy()
 
 
+@pytest.mark.parametrize("seed", range(max(12, N_CASES // 6)))
+def test_random_bf16_backward_case(seed):
+    """The bf16 layers backwards (sum over COPY / MUL_WEIGHT messages, ReLU or none, with or without W_self): X, W, Y,
+    dY and dX in bf16, A and the parameter gradients in fp32."""
+    rng, g, F, Fo, _, _, _, _ = _case(1700 + seed)
+    n = g.n
+    op = "mul_weight" if seed % 2 else "copy"
+    act = "relu" if seed % 3 else "none"
+    r16 = si.round_to_bf16
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    X, W, bias, dY = r16(t(n, F)), r16(t(F, Fo, s=0.3)), t(Fo, s=0.2), r16(t(n, Fo))
+    Ws = r16(t(F, Fo, s=0.3)) if seed % 4 == 0 else None
+    w = t(g.nnz) if op == "mul_weight" else None
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    wn = None if w is None else w.numpy()
+    Wsn = None if Ws is None else Ws.numpy()
+    fwd = oracle.layer(cp, ri, X.numpy(), op, wn, W=W.numpy(), W_self=Wsn, bias=bias.numpy(), act=act)
+    bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
+    b16 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda().to(torch.bfloat16)
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    with new_context() as c:
+        graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        dX = torch.full((n, F), float("nan"), device="cuda", dtype=torch.bfloat16)
+        dW, db, dWs = nan(F, Fo), nan(Fo), (nan(F, Fo) if Ws is not None else None)
+        kw = dict(X=b16(X), W_self=b16(Ws), dW_self=dWs) if Ws is not None else {}
+        c.layer_backward(graph, torch.as_tensor(fwd["A"], dtype=torch.float32).cuda(), b16(dY), b16(W), dW, Y=b16(fwd["Y"]), edge_op=op,
+                         edge_weight=None if w is None else w.cuda(), bias=bias.cuda(), act=act, dX=dX, dbias=db, **kw)
+        torch.cuda.synchronize()
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} bf16 self={Ws is not None}"
+        # the parameter gradients are fp32 products of inputs the fp32 path would see unchanged: the fp32 bar applies
+        assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW", tiny_outputs=True)
+        assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias", tiny_outputs=True)
+        if Ws is not None:
+            assert_sum_close(dWs.cpu().numpy(), bwd["dW_self"], np.maximum(bwd["dW_self_abs"], 1e-30), TOL_F32, what + " dW_self", tiny_outputs=True)
+        assert_sum_close(dX.float().cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_BF16, what + " dX", tiny_outputs=True)
+        graph.destroy()
+
+
 def _pinned(a):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).clone().pin_memory()
 
