@@ -79,15 +79,25 @@ def test_random_forward_case(seed):
     if rng.random() < 0.5:
         opts = dict(split=int(rng.choice([16, 32, 64])), cut_degree=int(rng.choice([16, 64, 256])), stripe_kb=int(rng.choice([0, 4, 64])),
                     team=int(rng.integers(2)))
+    # the optional code paths: work-group order, the matrix-unit multiply-accumulate, the stages one by one, the product first
+    if rng.random() < 0.4:
+        opts.update(xcd_remap=int(rng.integers(2)), mma=int(rng.integers(2)))
+        if op in ("copy", "mul_weight") and rng.random() < 0.4:
+            opts["fused"] = 0
+        if rng.random() < 0.4:
+            opts["transform_first"] = 1
+    want_accum = not (opts.get("transform_first") and rng.random() < 0.7)   # asking for the Gather output keeps the paper's order
     with new_context(**opts) as c:
         graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
         Y = torch.full((n, Fo), float("nan"), device="cuda", dtype=tdt)
-        A = torch.full((n, Fm), float("nan"), device="cuda")
+        A = torch.full((n, Fm), float("nan"), device="cuda") if want_accum else None
         c.layer_forward(graph, X.cuda().to(tdt), Y, edge_op=op, edge_weight=None if w is None else w.cuda(), agg=agg, W=W.cuda().to(tdt),
                         bias=bias.cuda(), act=act, accum_out=A, **kw)
         torch.cuda.synchronize()
-        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} {dtype} {opts}"
-        if agg == "max" and op in ("copy", "mul_weight"):
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} {dtype} {opts} accum={want_accum}"
+        if not want_accum:
+            pass
+        elif agg == "max" and op in ("copy", "mul_weight"):
             assert_bit_equal(A.cpu().numpy(), ref["A"], what + " max Gather")
         else:
             assert_sum_close(A.cpu().numpy(), ref["A"], ref["A_abs"], TOL_F32, what + " Gather", tiny_outputs=True)
