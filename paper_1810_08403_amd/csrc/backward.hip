@@ -404,11 +404,11 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     float* dS = grads->dX ? static_cast<float*>(grads->dX->data) : nullptr;
     int64_t ldds = grads->dX ? grads->dX->ld : 0;
     if (pool) {
-        // the pooled rows h are what a max Gather compares with; a sum needs only their pre-activations, further down
-        if (agg == SAGA_AGG_MAX)
-            if ((st = hoist_pool(ctx, X, ep, n, F, Fm))) return st;
+        // the pre-activations z = X W_pool^T + b of the pooled rows: the max Gather's way back forms a vertex's pooled row
+        // from them (once per work item), and the slope of the sigmoid comes from them further down
+        if ((st = hoist_pool(ctx, X, ep, n, F, Fm, SAGA_ACT_NONE))) return st;
         if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)n * Fm))) return st;
-        S = static_cast<const float*>(ctx->ws_hoist.p);  // (read by the max Gather's way back only)
+        S = static_cast<const float*>(ctx->ws_hoist.p);
         lds = Fm;
         dS = static_cast<float*>(ctx->ws_dh.p);
         ldds = Fm;
@@ -426,8 +426,9 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
         ga.ld_src = A->ld;
         ga.src2 = dA;          // ... and its gradient
         ga.ld_src2 = Fm;
-        ga.dst = S;            // per item: this vertex's own row
+        ga.dst = S;            // per item: this vertex's own row (pooled: its pre-activations)
         ga.ld_dst = lds;
+        ga.dst_sigmoid = pool ? 1 : 0;
         ga.edge_w = w_t;
         ga.out = dS;
         ga.ld_out = ldds;
@@ -438,10 +439,8 @@ static saga_status max_pool_backward_rest(saga_ctx* ctx, saga_graph* g, const sa
     if (!pool) return SAGA_OK;
 
     // through the sigmoid, then the per-vertex product: dPre = dS (.) sigmoid'(z), dW_pool = dPre^T X, db_pool, dX = dPre W_pool.
-    // The slope comes from the pre-activations z = X W_pool^T + b, formed once more over the pooled rows (which are
-    // done with): h (1 - h) from an fp32 h has lost the slope of a saturated unit.
-    if ((st = hoist_pool(ctx, X, ep, n, F, Fm, SAGA_ACT_NONE))) return st;
-    HIP_TRY(ctx, launch_sigmoid_grad(dS, static_cast<const float*>(ctx->ws_hoist.p), n * (int64_t)Fm, s));
+    // The slope comes from the pre-activations: h (1 - h) from an fp32 h has lost the slope of a saturated unit.
+    HIP_TRY(ctx, launch_sigmoid_grad(dS, S, n * (int64_t)Fm, s));
     const float* Xp = static_cast<const float*>(X->data);
     if ((st = param_grad(ctx, dS, Fm, Fm, Xp, X->ld, F, n, static_cast<float*>(grads->dW_pool->data), grads->dW_pool->ld))) return st;
     if (grads->db_pool) {
@@ -877,7 +876,7 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         if ((st = prod.init(ctx, X, ep))) return st;
     if ((st = ensure_transposed_host(ctx, g))) return st;
     const float* h_dA = ctx->h_grad;
-    float* pooled_j = nullptr;  // where dst_fill left the pooled rows of the resident interval (its rows of X are in ws_tile)
+    float* pooled_j = nullptr;  // where dst_fill left the pre-activations of the resident interval's pooled rows (its rows of X are in ws_tile)
     VertexFeed feed;
     StreamExtras ex;
     saga_tensor rows_t{};  // shape of the rows that travel
@@ -902,9 +901,10 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         ex.acc_width = Fm;
         if (pool) {  // the vertex's own pooled row beside its accumulator
             ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
-                pooled_j = dst;
-                return prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_SIGMOID, dst, Fm, on, h2d);
+                pooled_j = dst;  // as pre-activations: the kernel forms the pooled row, the slope needs z itself
+                return prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_NONE, dst, Fm, on, h2d);
             };
+            ex.dst_sigmoid = true;
         } else {
             ex.dst_rows = static_cast<const float*>(X->data);
             ex.ld_dst = X->ld;
@@ -960,17 +960,13 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
         }
         bool any_done = false;
         ex.after_gather = [&, any_done](int64_t row0, int64_t rows, float* acc, hipStream_t on, int64_t* h2d) mutable -> saga_status {
-            // the interval's pooled rows and its rows of X: left by dst_fill (max), or formed here, on the compute stream
+            // the pre-activations of the interval's pooled rows and its rows of X: left by dst_fill (max), or formed here, on the compute stream
             // (sum: there are no constant rows, and the kernels that follow wait for them anyway)
             float* tS = pooled_j;
             if (agg != SAGA_AGG_MAX) {
                 if (saga_status e = ctx->dev_alloc(&ctx->ws_hoist, sizeof(float) * (size_t)rows * Fm)) return e;  // intervals do not grow
                 tS = static_cast<float*>(ctx->ws_hoist.p);
                 if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_NONE, tS, Fm, on, h2d)) return e;
-            } else {
-                // the pooled rows are done with: their pre-activations take their place (the slope of a saturated unit
-                // cannot be had from an fp32 h), from the interval's rows of X that dst_fill left in ws_tile
-                if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 0, Fm, SAGA_ACT_NONE, tS, Fm, on, h2d, false)) return e;
             }
             const float* tX = static_cast<const float*>(ctx->ws_tile.p);
             HIP_TRY(ctx, launch_sigmoid_grad(acc, tS, rows * (int64_t)Fm, on));

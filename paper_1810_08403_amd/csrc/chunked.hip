@@ -547,6 +547,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ga.src2 = static_cast<const float*>(ctx->st_V[vb].p) + Fa;
             ga.ld_src2 = F;
             ga.dst = static_cast<const float*>(ctx->st_D.p);
+            ga.dst_sigmoid = extras->dst_sigmoid ? 1 : 0;
             ga.ld_dst = Fd;
             if (Fd == 2 * Fa) {
                 ga.dst2 = ga.dst + Fa;

@@ -310,7 +310,9 @@ __device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, 
 //   kEfGateBoth  both of the above at once from the same loads: acc += g (1 - g) * (c2 * m), acc2 += g * m
 //   kEfMaxGrad   acc += w_e * m where w_e * c1 == x, else nothing   (gradient of a max Gather: x is the maximum that
 //                was gathered at the other end of the edge, c1 this vertex's own row, so the test says "this vertex
-//                supplied the maximum"; the product is the same single fp32 multiply that formed the message)
+//                supplied the maximum"; the product is the same single fp32 multiply that formed the message). With
+//                `dst_sigmoid` the constant row is stored as pre-activations z and c1 = sigmoid(z) is formed once per
+//                item, by the function the pooled rows were made with, so that the backward pass keeps z for the slope
 constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3, kEfMaxGrad = 4;
 
 template <int AGG, int EF>
@@ -424,6 +426,11 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 if (ok[c]) f.load(a.dst + (int64_t)it.v * a.ld_dst + col[c]);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) pd[c][j] = f.get(j);
+                if constexpr (EF == kEfMaxGrad)
+                    if (a.dst_sigmoid) {  // the same function of the same fp32 value as the product that made the pooled rows
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) pd[c][j] = sigmoid_f32(pd[c][j]);
+                    }
             }
             if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
                 Frag<float, VEC> f;
@@ -777,6 +784,11 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
         if (colok) f.load(a.dst + (int64_t)it.v * a.ld_dst + col);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) pd[j] = f.get(j);
+        if constexpr (EF == kEfMaxGrad)
+            if (a.dst_sigmoid) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) pd[j] = sigmoid_f32(pd[j]);
+            }
     }
     if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
         Frag<float, VEC> f;

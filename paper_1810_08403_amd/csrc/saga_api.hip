@@ -414,16 +414,12 @@ saga_status VertexProducts::init(saga_ctx* c, const saga_tensor* x, const saga_e
 }
 
 saga_status VertexProducts::rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
-                                 hipStream_t on, int64_t* h2d, bool upload) const
+                                 hipStream_t on, int64_t* h2d) const
 {
-    if (upload) {
-        if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)n_rows * F)) return e;  // grows once: intervals do not grow
-        HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
-                                      sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)n_rows, hipMemcpyHostToDevice, on));
-        *h2d += n_rows * (int64_t)F * 4;
-    } else if (!tmp->p || tmp->bytes < sizeof(float) * (size_t)n_rows * F) {
-        return ctx->fail(SAGA_ERR_INTERNAL, "per-vertex product from rows that were never brought in");
-    }
+    if (saga_status e = ctx->dev_alloc(tmp, sizeof(float) * (size_t)n_rows * F)) return e;  // grows once: intervals do not grow
+    HIP_TRY(ctx, hipMemcpy2DAsync(tmp->p, sizeof(float) * (size_t)F, static_cast<const float*>(X->data) + row0 * X->ld,
+                                  sizeof(float) * (size_t)X->ld, sizeof(float) * (size_t)F, (size_t)n_rows, hipMemcpyHostToDevice, on));
+    *h2d += n_rows * (int64_t)F * 4;
     GemmArgs hg{};
     hg.A = tmp->p;
     hg.lda = F;

@@ -216,6 +216,7 @@ struct GatherArgs {
     int32_t accumulate;      // 1: combine with what `out` already holds (streamed, chunk i > 0)
     int32_t xcd_remap;
     int32_t mma;             // 1: bf16 sums over linear messages may run their multiply-accumulate on the matrix unit
+    int32_t dst_sigmoid;     // kGatherOpMaxGrad: `dst` holds pre-activations, the item's own row is their sigmoid (pooled rows)
     // transform-first layers: the gathered rows are already X W, so ApplyVertex's bias and activation are applied
     // to every finished row (whole-column items here, cut columns in the combine pass); not with `accumulate`
     const float* bias;       // [F] fp32, nullable
@@ -373,6 +374,7 @@ struct StreamExtras {
     // instead of dst_rows: produces the constant rows of destinations [row0, row0 + rows) in dst (dst_width wide,
     // compact) on stream s and adds the bytes it copies to *h2d (a gated layer forms Pd of the interval from its rows of X)
     std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, int64_t* h2d)> dst_fill;
+    bool dst_sigmoid = false;          // the constant rows are pre-activations of pooled rows (GatherArgs::dst_sigmoid)
     int32_t n_out = 1;                 // 2: the edge function has two outputs; accumulator rows are [out | out2]
     // called once per destination interval after its last chunk, before ApplyVertex, with the interval's accumulator
     // rows on the device (compute stream s): the backward pass of pooled messages goes through the sigmoid there
@@ -402,9 +404,8 @@ struct VertexProducts {
     float* bias = nullptr;
     int64_t k_pad = 0;
     saga_status init(saga_ctx* c, const saga_tensor* x, const saga_edge_params* ep);
-    // upload = false: tmp already holds these rows of X (an earlier call for the same rows left them there)
     saga_status rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
-                     hipStream_t on, int64_t* h2d, bool upload = true) const;
+                     hipStream_t on, int64_t* h2d) const;
 };
 void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
 
