@@ -44,19 +44,21 @@ __device__ __forceinline__ float identity()
 }
 
 // Gather's accumulate step. For max the message is formed first by a single
-// multiply (no contraction is possible: there is no addition to fuse with).
+// multiply (no contraction is possible: there is no addition to fuse with), then one
+// maximum instruction takes it in: fmaxf is the larger of two finite values whatever
+// their order, bit for bit what `m > acc ? m : acc` gives (a compare and a select, which
+// made the bf16 max layer of 512-wide rows ALU-bound) except for the sign of a zero maximum.
 template <int AGG>
 __device__ __forceinline__ float accumulate(float acc, float w, float x)
 {
     if (AGG == SAGA_AGG_SUM) return fmaf(w, x, acc);
-    const float m = w * x;
-    return m > acc ? m : acc;
+    return __builtin_fmaxf(w * x, acc);
 }
 template <int AGG>
 __device__ __forceinline__ float combine(float a, float b)
 {
     if (AGG == SAGA_AGG_SUM) return a + b;
-    return b > a ? b : a;
+    return __builtin_fmaxf(b, a);
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
