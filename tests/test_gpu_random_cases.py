@@ -17,6 +17,20 @@ N_CASES = int(os.environ.get("SAGA_RANDOM_CASES", "48"))
 N_BWD_CASES = max(16, N_CASES // 3)
 
 
+def _strided(rows, cols, pad, dtype=torch.float32, src=None, pinned=False):
+    """A rows x cols view into a rows x (cols + pad) buffer of NaN: the row stride the C ABI calls ld."""
+    buf = torch.full((rows, cols + pad), float("nan"), dtype=dtype)
+    buf = buf.pin_memory() if pinned else buf.cuda()
+    view = buf[:, :cols]
+    if src is not None:
+        view.copy_(src)
+    return buf, view
+
+
+def _padding_untouched(buf, cols):
+    return bool(torch.isnan(buf[:, cols:].float()).all())
+
+
 def _case(seed):
     rng = np.random.default_rng(1000 + seed)
     n = int(rng.choice([1, 2, 7, 33, 64, 200, 777, 1500]))
@@ -87,14 +101,17 @@ def test_random_forward_case(seed):
         if rng.random() < 0.4:
             opts["transform_first"] = 1
     want_accum = not (opts.get("transform_first") and rng.random() < 0.7)   # asking for the Gather output keeps the paper's order
+    pads = [int(x) for x in rng.choice([0, 0, 0, 1, 3, 4, 8, 20], 3)]          # row strides beyond the row width
     with new_context(**opts) as c:
         graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
-        Y = torch.full((n, Fo), float("nan"), device="cuda", dtype=tdt)
-        A = torch.full((n, Fm), float("nan"), device="cuda") if want_accum else None
-        c.layer_forward(graph, X.cuda().to(tdt), Y, edge_op=op, edge_weight=None if w is None else w.cuda(), agg=agg, W=W.cuda().to(tdt),
+        Xb, Xd = _strided(n, F, pads[0], tdt, X)
+        Yb, Y = _strided(n, Fo, pads[1], tdt)
+        Ab, A = _strided(n, Fm, pads[2]) if want_accum else (None, None)
+        c.layer_forward(graph, Xd, Y, edge_op=op, edge_weight=None if w is None else w.cuda(), agg=agg, W=W.cuda().to(tdt),
                         bias=bias.cuda(), act=act, accum_out=A, **kw)
         torch.cuda.synchronize()
-        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} {dtype} {opts} accum={want_accum}"
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} {dtype} {opts} accum={want_accum} pads={pads}"
+        assert _padding_untouched(Yb, Fo) and (Ab is None or _padding_untouched(Ab, Fm)), what + ": wrote between the rows"
         if not want_accum:
             pass
         elif agg == "max" and op in ("copy", "mul_weight"):
@@ -122,14 +139,19 @@ def test_random_linear_backward_case(seed):
     bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
     with new_context() as c:
         graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
-        f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda()
+        f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32)
         nan = lambda *s: torch.full(s, float("nan"), device="cuda")
-        dX, dW, db, dWs = nan(n, F), nan(F, Fo), nan(Fo), (nan(F, Fo) if Ws is not None else None)
-        c.layer_backward(graph, f32(fwd["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(fwd["Y"]), edge_op=op,
+        pads = [int(x) for x in rng.choice([0, 0, 0, 1, 3, 4, 8, 20], 6)]      # row strides beyond the row width
+        (_, Ad), (_, dYd), (_, Yd), (_, Xd) = (_strided(n, F, pads[0], src=f32(fwd["A"])), _strided(n, Fo, pads[1], src=dY),
+                                               _strided(n, Fo, pads[2], src=f32(fwd["Y"])), _strided(n, F, pads[3], src=X))
+        (dXb, dX), (dWb, dW) = _strided(n, F, pads[4]), _strided(F, Fo, pads[5])
+        db, dWs = nan(Fo), (nan(F, Fo) if Ws is not None else None)
+        c.layer_backward(graph, Ad, dYd, W.cuda(), dW, X=Xd, Y=Yd, edge_op=op,
                          edge_weight=None if w is None else w.cuda(), bias=bias.cuda(), W_self=None if Ws is None else Ws.cuda(), act=act,
                          dX=dX, dbias=db, dW_self=dWs)
         torch.cuda.synchronize()
-        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} self={Ws is not None}"
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {act} self={Ws is not None} pads={pads}"
+        assert _padding_untouched(dXb, F) and _padding_untouched(dWb, Fo), what + ": wrote between the rows"
         assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW", tiny_outputs=True)
         assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX", tiny_outputs=True)
         assert_sum_close(db.cpu().numpy(), bwd["dbias"], np.maximum(bwd["dbias_abs"], 1e-30), TOL_F32, what + " dbias", tiny_outputs=True)
@@ -317,8 +339,10 @@ def test_random_streamed_case(seed):
     graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)          # host graph
     if w is not None:
         graph.set_edge_data(w)
-    X_h = _pinned(X)
-    Y_h = torch.full((n, Fo), float("nan")).pin_memory()
+    pads = [int(x) for x in rng.choice([0, 0, 0, 1, 3, 4, 8, 20], 3)]          # row strides of the host tensors beyond the row width
+    what += f" pads={pads}"
+    _, X_h = _strided(n, F, pads[0], src=X, pinned=True)
+    Yb_h, Y_h = _strided(n, Fo, pads[1], pinned=True)
     for rep in range(2):
         Y_h.fill_(float("nan"))
         try:
@@ -330,6 +354,7 @@ def test_random_streamed_case(seed):
             return
         if n > 0:
             assert_sum_close(Y_h.numpy(), fwd["Y"], fwd["Y_abs"], TOL_F32, what + f" layer, call {rep}", tiny_outputs=True)
+        assert _padding_untouched(Yb_h, Fo), what + ": wrote between the rows of Y"
     if budget:
         assert ctx.peak_device_bytes() <= budget, what
         tm = ctx.get_timings()
@@ -360,7 +385,7 @@ def test_random_streamed_case(seed):
                 g2.destroy()
             assert_sum_close(Ad.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " pooled Gather")
             A_h, Yf_h = _pinned(Ad.cpu().numpy()), _pinned(Yd.cpu().numpy())
-        dX_h = torch.full((n, F), float("nan")).pin_memory()
+        dXb_h, dX_h = _strided(n, F, pads[2], pinned=True)
         nan = lambda *s: torch.full(s, float("nan"), device="cuda")
         out = dict(dW=nan(Fm, Fo), dbias=nan(Fo))
         if Ws is not None:
@@ -386,6 +411,7 @@ def test_random_streamed_case(seed):
                 assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + f" backward {name}, call {rep}", tiny_outputs=True)
             if want_dx:
                 assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + f" backward dX, call {rep}", tiny_outputs=True)
+            assert _padding_untouched(dXb_h, F), what + ": wrote between the rows of dX"
         if budget:
             assert ctx.peak_device_bytes() <= budget, what + " (backward)"
     graph.destroy()
