@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 import os
 
 # more cases on demand: SAGA_RANDOM_CASES=1000 python -m pytest tests/test_gpu_random_cases.py
-N_CASES = int(os.environ.get("SAGA_RANDOM_CASES", "48"))
+N_CASES = int(os.environ.get("SAGA_RANDOM_CASES", "200"))
 N_BWD_CASES = max(16, N_CASES // 3)
 
 
