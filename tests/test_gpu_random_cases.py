@@ -416,3 +416,70 @@ def test_random_streamed_case(seed):
             assert ctx.peak_device_bytes() <= budget, what + " (backward)"
     graph.destroy()
     ctx.destroy()
+
+
+@pytest.mark.parametrize("seed", range(max(8, N_CASES // 12)))
+def test_random_session_on_one_context(seed):
+    """What a context and its graph handles keep between calls (work lists per row width, the edge order by source,
+    attached edge data and its transposed copy, workspaces that only grow): three graphs on one context, a random
+    sequence of forward and backward calls of changing widths, edge functions, accumulators and dtypes, each call
+    checked against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    with new_context() as c:
+        graphs = []
+        for k in range(3):
+            _, g, *_ = _case(7100 + 10 * seed + k)
+            h = c.graph_create_csc(g.n, g.col_ptr.cuda(), g.row_idx.cuda())
+            attached = None
+            if rng.random() < 0.5:                     # edge data attached to the handle instead of passed per call
+                attached = t(g.nnz)
+                h.set_edge_data(attached.cuda())
+            graphs.append((g, h, attached))
+        for step in range(10):
+            g, h, attached = graphs[int(rng.integers(3))]
+            n, cp, ri = g.n, g.col_ptr.numpy(), g.row_idx.numpy()
+            F = int(rng.choice([1, 4, 7, 16, 48, 64, 100, 128, 260]))
+            Fo = int(rng.choice([1, 5, 16, 64]))
+            op = str(rng.choice(["copy", "mul_weight", "mul_weight", "gated"]))
+            agg = str(rng.choice(["sum", "max"]))
+            act = str(rng.choice(["none", "relu"]))
+            bf16 = op != "gated" and rng.random() < 0.3
+            if op == "gated":
+                F = min(F, 64)
+            r = si.round_to_bf16 if bf16 else (lambda x: x)
+            tdt = torch.bfloat16 if bf16 else torch.float32
+            X, W, bias = r(t(n, F)), r(t(F, Fo, s=0.3)), t(Fo, s=0.2)
+            w_call = None
+            if op == "mul_weight" and (attached is None or rng.random() < 0.3):
+                w_call = t(g.nnz)                      # per-call weights take precedence over attached ones
+            w_used = w_call if w_call is not None else attached
+            kw, okw = {}, {}
+            if op == "gated":
+                Wg, bg = t(F, 2 * F, s=0.3), t(F, s=0.2)
+                kw, okw = dict(W_gate=Wg.cuda(), b_gate=bg.cuda()), dict(W_gate=Wg.numpy(), b_gate=bg.numpy())
+            what = f"seed {seed} step {step}: n={n} nnz={g.nnz} F={F}->{Fo} {op} {agg} {act} bf16={bf16} attached={attached is not None} per_call={w_call is not None}"
+            wn = None if (op != "mul_weight" or w_used is None) else w_used.numpy()
+            ref = oracle.layer(cp, ri, X.numpy(), op, wn, agg=agg, W=W.numpy(), bias=bias.numpy(), act=act, **okw)
+            Y, A = torch.full((n, Fo), float("nan"), device="cuda", dtype=tdt), nan(n, F)
+            c.layer_forward(h, X.cuda().to(tdt), Y, edge_op=op, edge_weight=None if w_call is None else w_call.cuda(), agg=agg,
+                            W=W.cuda().to(tdt), bias=bias.cuda(), act=act, accum_out=A, **kw)
+            torch.cuda.synchronize()
+            if agg == "max" and op != "gated":
+                assert_bit_equal(A.cpu().numpy(), ref["A"], what + " max Gather")
+            else:
+                assert_sum_close(A.cpu().numpy(), ref["A"], ref["A_abs"], TOL_F32, what + " Gather", tiny_outputs=True)
+            assert_sum_close(Y.float().cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_BF16 if bf16 else TOL_F32, what + " layer", tiny_outputs=True)
+            if op != "gated" and agg == "sum" and not bf16 and rng.random() < 0.6:       # the same layer backwards
+                dY = t(n, Fo)
+                bwd = oracle.layer_backward(cp, ri, X.numpy(), ref["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), act=act)
+                f32 = lambda a: torch.as_tensor(np.ascontiguousarray(a), dtype=torch.float32).cuda()
+                dX, dW, db = nan(n, F), nan(F, Fo), nan(Fo)
+                c.layer_backward(h, f32(ref["A"]), dY.cuda(), W.cuda(), dW, X=X.cuda(), Y=f32(ref["Y"]), edge_op=op,
+                                 edge_weight=None if w_call is None else w_call.cuda(), bias=bias.cuda(), act=act, dX=dX, dbias=db)
+                torch.cuda.synchronize()
+                assert_sum_close(dW.cpu().numpy(), bwd["dW"], bwd["dW_abs"], TOL_F32, what + " dW", tiny_outputs=True)
+                assert_sum_close(dX.cpu().numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + " dX", tiny_outputs=True)
+        for _, h, _ in graphs:
+            h.destroy()
