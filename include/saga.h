@@ -244,10 +244,12 @@ typedef struct saga_layer_grads {
  * Max accumulator (Figure 11's layer): the gradient of A[v][f] goes to every in-edge whose
  * message equals the maximum A[v][f] (on a tie every maximal edge receives all of it). The
  * decision is taken by recomputing the message, w_e * x_u[f] with the same single fp32
- * multiply as the forward pass (or the pooled sigmoid row of u, recomputed per vertex by the
- * same product and kernel as in the forward pass), and comparing it with the A the caller
+ * multiply as the forward pass (or the pooled sigmoid row of u: its pre-activations z_u are
+ * recomputed per vertex by the same product as in the forward pass and the sigmoid is taken
+ * by the same function of the same fp32 value), and comparing it with the A the caller
  * kept: one propagation pass over the out-edges. POOL then goes through the sigmoid per
- * vertex: dPre = dS (.) h (.) (1 - h), dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
+ * vertex: dPre = dS (.) sigmoid'(z), the slope formed from z so that a saturated unit keeps
+ * its relative accuracy, dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
  * sums of dPre. With W_self the own partial gradient dZ W_self^T is written into dX before
  * the propagation adds to it (COPY, MUL_WEIGHT) or joins the product dPre W_pool (POOL).
  * X and A are required; A must be the accum_out of the forward call on the same inputs, or
