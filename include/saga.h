@@ -159,6 +159,9 @@ saga_status saga_graph_destroy(saga_graph* g);
  * weights): [n_edges] fp32 in CSC edge order, same placement as the graph.
  * Copied. Used when saga_edge_params.edge_weight is NULL; required for
  * streamed MUL_WEIGHT calls, where it is stored chunk by chunk with the edges.
+ * May be called again at any time between layer calls: a host graph that
+ * already has its tiling (and its edge order by source) keeps both and only the
+ * weights inside their pinned payloads are written again, in place.
  */
 saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
 

@@ -97,7 +97,12 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1810_08403_amd.build` "
                           "(hipcc, gfx950). There is no CPU fallback.")
-    L = ctypes.CDLL(LIB_PATH)
+    _lib = declare_signatures(ctypes.CDLL(LIB_PATH))
+    return _lib
+
+
+def declare_signatures(L: ctypes.CDLL) -> ctypes.CDLL:
+    """Argument and result types of every entry point of include/saga.h on a loaded library."""
     P, I64, I32, SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     L.saga_create.restype = I32
     L.saga_create.argtypes = [ctypes.POINTER(P), ctypes.c_int, P, SZ]
@@ -137,7 +142,6 @@ def load_library() -> ctypes.CDLL:
     L.saga_copy_bytes.argtypes = [P, P, P, SZ]
     L.saga_version.restype = ctypes.c_char_p
     L.saga_version.argtypes = []
-    _lib = L
     return L
 
 

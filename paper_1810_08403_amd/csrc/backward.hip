@@ -711,6 +711,30 @@ static saga_status ensure_transposed_host(saga_ctx* ctx, saga_graph* g)
     return SAGA_OK;
 }
 
+// New edge data on a host graph whose edge order by source exists already: the same counting pass that built the order
+// places every weight again (columns in order keep every group ascending in destination id), then the tiling of that
+// order, if there is one, takes the weights over in place. A twin that was built without edge data gets them now; its
+// tiling, made for unweighted chunks, is then replaced at the next call that needs weights.
+saga_status transposed_host_refresh_weights(saga_ctx* ctx, saga_graph* g)
+{
+    saga_graph* t = g->tr;
+    if (!t || t->where != SAGA_MEM_HOST || g->h_edge_data.empty()) return SAGA_OK;
+    const int64_t n = g->n, nnz = g->nnz;
+    try {
+        t->h_edge_data.resize((size_t)nnz);
+        std::vector<int64_t> fill(t->h_col_ptr.begin(), t->h_col_ptr.begin() + n);
+        const int64_t* cp = g->h_col_ptr.data();
+        const int32_t* src = g->h_row_idx.data();
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = cp[v]; e < cp[v + 1]; ++e) t->h_edge_data[(size_t)fill[(size_t)src[e]]++] = g->h_edge_data[(size_t)e];
+    } catch (...) {
+        transposed_graph_destroy(ctx, g);  // rebuilt, with the new data, by the next backward call
+        return SAGA_OK;
+    }
+    chunk_grid_refresh_weights(t);
+    return SAGA_OK;
+}
+
 // Parameter gradients of a streamed layer without the propagation: backward-ApplyVertex over tiles of rows copied in
 // from host memory on the context's stream (dZ, the bias sums, dW += A^T dZ, tile after tile in a fixed order).
 // h_dA (optional, pinned host, n x F compact): also receives the gradient of accum, dZ W^T, tile by tile.

@@ -38,7 +38,7 @@
 struct ChunkMeta {
     int64_t nnz = 0, n_items = 0, n_team = 0, n_heavy = 0, n_slots = 0;
     size_t off_items = 0, off_heavy = 0, off_ridx = 0, off_w = 0, bytes = 0;
-    char* host = nullptr;  // pinned payload: [items | heavy | row_idx | weights]
+    char* host = nullptr;  // inside the tiling's pinned arena: [items | heavy | row_idx | weights]
 };
 
 struct ChunkGrid {
@@ -49,13 +49,10 @@ struct ChunkGrid {
     std::vector<ChunkMeta> chunks;  // [j * P + i]
     size_t max_chunk_bytes = 0;
     int64_t max_slots = 0;
-    // device side: the buffers themselves belong to the context (one streamed call runs at a time, and the forward
-    // grid of a graph and the grid of its transposed twin must share one budget)
-    hipStream_t s_in = nullptr, s_out = nullptr;
-    hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
-    hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
-    hipEvent_t ev_a_done = nullptr, ev_a_ready = nullptr, ev_a_in = nullptr;
-    hipEvent_t ev_d_free = nullptr, ev_s_ready[2] = {nullptr, nullptr};  // destination parts / own-row tiles (gated, W_self)
+    char* arena = nullptr;    // one pinned allocation that holds every chunk's payload
+    size_t arena_bytes = 0;
+    // device side: the buffers, streams and events belong to the context (one streamed call runs at a time, and the
+    // forward grid of a graph and the grid of its transposed twin must share one budget)
     float* a_host = nullptr;  // pinned home of the accumulators for the swapping baselines
     size_t a_host_bytes = 0;
 };
@@ -63,32 +60,54 @@ struct ChunkGrid {
 void chunk_grid_destroy(saga_ctx* ctx, ChunkGrid* g)
 {
     if (!g) return;
-    for (auto& c : g->chunks)
-        if (c.host) (void)hipHostFree(c.host);
     (void)ctx;
-    for (hipEvent_t e : {g->ev_ready[0], g->ev_ready[1], g->ev_free[0], g->ev_free[1], g->ev_y_ready[0], g->ev_y_ready[1],
-                         g->ev_y_free[0], g->ev_y_free[1], g->ev_a_done, g->ev_a_ready, g->ev_a_in, g->ev_d_free, g->ev_s_ready[0],
-                         g->ev_s_ready[1]})
-        if (e) (void)hipEventDestroy(e);
+    if (g->arena) (void)hipHostFree(g->arena);
     if (g->a_host) (void)hipHostFree(g->a_host);
-    if (g->s_in) (void)hipStreamDestroy(g->s_in);
-    if (g->s_out) (void)hipStreamDestroy(g->s_out);
     delete g;
+}
+
+saga_status saga_ctx::ensure_stream_set()
+{
+    if (st.ready) return SAGA_OK;
+    if (!st.s_in) HIP_TRY(this, hipStreamCreateWithFlags(&st.s_in, hipStreamNonBlocking));
+    if (!st.s_out) HIP_TRY(this, hipStreamCreateWithFlags(&st.s_out, hipStreamNonBlocking));
+    for (hipEvent_t* e : {&st.ev_ready[0], &st.ev_ready[1], &st.ev_free[0], &st.ev_free[1], &st.ev_y_ready[0], &st.ev_y_ready[1],
+                          &st.ev_y_free[0], &st.ev_y_free[1], &st.ev_a_done, &st.ev_a_ready, &st.ev_a_in, &st.ev_d_free, &st.ev_s_ready[0],
+                          &st.ev_s_ready[1]})
+        if (!*e) HIP_TRY(this, hipEventCreateWithFlags(e, hipEventDisableTiming));
+    st.ready = true;
+    return SAGA_OK;
+}
+
+void saga_ctx::destroy_stream_set()
+{
+    for (hipEvent_t* e : {&st.ev_ready[0], &st.ev_ready[1], &st.ev_free[0], &st.ev_free[1], &st.ev_y_ready[0], &st.ev_y_ready[1],
+                          &st.ev_y_free[0], &st.ev_y_free[1], &st.ev_a_done, &st.ev_a_ready, &st.ev_a_in, &st.ev_d_free, &st.ev_s_ready[0],
+                          &st.ev_s_ready[1]}) {
+        if (*e) (void)hipEventDestroy(*e);
+        *e = nullptr;
+    }
+    if (st.s_in) (void)hipStreamDestroy(st.s_in);
+    if (st.s_out) (void)hipStreamDestroy(st.s_out);
+    st.s_in = st.s_out = nullptr;
+    st.ready = false;
 }
 
 // After a streamed call that failed half-way: nothing it enqueued may still be reading or writing the caller's host
 // tensors when the error is returned. Errors of the waits themselves are ignored (the call has failed already).
-void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* g)
+void chunk_grid_drain(saga_ctx* ctx)
 {
-    if (g && g->s_in) (void)hipStreamSynchronize(g->s_in);
+    if (ctx->st.s_in) (void)hipStreamSynchronize(ctx->st.s_in);
     if (ctx->stream) (void)hipStreamSynchronize(ctx->stream);
-    if (g && g->s_out) (void)hipStreamSynchronize(g->s_out);
+    if (ctx->st.s_out) (void)hipStreamSynchronize(ctx->st.s_out);
 }
 
 namespace {
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// fn(i) for i in [0, n) on up to max_threads threads. fn must not throw. If a thread cannot be started the threads that
+// did start (or the caller alone) do all the work: nothing is thrown from here.
 template <typename Fn>
 void parallel_for(int64_t n, int max_threads, Fn fn)
 {
@@ -98,15 +117,21 @@ void parallel_for(int64_t n, int max_threads, Fn fn)
         return;
     }
     std::atomic<int64_t> next{0};
+    auto work = [&] {
+        for (;;) {
+            const int64_t i = next.fetch_add(1);
+            if (i >= n) break;
+            fn(i);
+        }
+    };
     std::vector<std::thread> th;
-    for (int t = 0; t < nt; ++t)
-        th.emplace_back([&] {
-            for (;;) {
-                const int64_t i = next.fetch_add(1);
-                if (i >= n) break;
-                fn(i);
-            }
-        });
+    try {
+        th.reserve((size_t)nt);
+        for (int t = 1; t < nt; ++t) th.emplace_back(work);
+    } catch (...) {
+        // out of threads or memory: carry on with what there is
+    }
+    work();
     for (auto& t : th) t.join();
 }
 
@@ -118,24 +143,45 @@ struct BuiltChunk {
     int64_t n_slots = 0, n_team = 0;
 };
 
-// Chunk C_ij of the host CSC: columns [j*Dq, ...), sources in [i*Sp, (i+1)*Sp), local ids.
-void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, const WorkListParams& wlp, bool weighted,
-                 BuiltChunk* out)
+// Where chunk C_ij's edges sit in the host CSC: columns [j*Dq, ...), sources in [i*Sp, (i+1)*Sp). For local column c,
+// lo[c] is the first such edge of the column and lcp[c + 1] - lcp[c] their number (they are consecutive: a column is
+// ascending in source id).
+void locate_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, std::vector<int64_t>* lcp, std::vector<int64_t>* lo)
 {
     const int64_t v0 = (int64_t)j * Dq, v1 = std::min(g->n, v0 + Dq);
     const int64_t s0 = (int64_t)i * Sp, s1 = std::min(g->n, s0 + Sp);
     const int64_t* cp = g->h_col_ptr.data();
     const int32_t* ri = g->h_row_idx.data();
-    std::vector<int64_t> lcp((size_t)(v1 - v0) + 1, 0);
-    std::vector<int64_t> lo((size_t)(v1 - v0));
+    lcp->assign((size_t)(v1 - v0) + 1, 0);
+    lo->assign((size_t)(v1 - v0), 0);
     for (int64_t v = v0; v < v1; ++v) {
         const int32_t* b = ri + cp[v];
         const int32_t* e = ri + cp[v + 1];
         const int32_t* l = std::lower_bound(b, e, (int32_t)s0);
         const int32_t* h = std::lower_bound(l, e, (int32_t)std::min<int64_t>(s1, 0x7fffffff));
-        lo[v - v0] = l - ri;
-        lcp[v - v0 + 1] = lcp[v - v0] + (h - l);
+        (*lo)[v - v0] = l - ri;
+        (*lcp)[v - v0 + 1] = (*lcp)[v - v0] + (h - l);
     }
+}
+
+// The chunk's edge data in chunk order, from the graph's edge data.
+void fill_chunk_weights(const saga_graph* g, const std::vector<int64_t>& lcp, const std::vector<int64_t>& lo, float* out)
+{
+    for (size_t c = 0; c + 1 < lcp.size(); ++c) {
+        const int64_t cnt = lcp[c + 1] - lcp[c];
+        if (cnt > 0) memcpy(out + lcp[c], g->h_edge_data.data() + lo[c], sizeof(float) * (size_t)cnt);
+    }
+}
+
+// Chunk C_ij of the host CSC, local ids, with its work list.
+void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, const WorkListParams& wlp, bool weighted,
+                 BuiltChunk* out)
+{
+    const int64_t v0 = (int64_t)j * Dq, v1 = std::min(g->n, v0 + Dq);
+    const int64_t s0 = (int64_t)i * Sp;
+    const int32_t* ri = g->h_row_idx.data();
+    std::vector<int64_t> lcp, lo;
+    locate_chunk(g, Dq, Sp, i, j, &lcp, &lo);
     const int64_t nnz = lcp.back();
     out->ridx.resize((size_t)nnz);
     if (weighted) out->w.resize((size_t)nnz);
@@ -143,8 +189,8 @@ void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, cons
         const int64_t cnt = lcp[v - v0 + 1] - lcp[v - v0];
         const int64_t src = lo[v - v0], dst = lcp[v - v0];
         for (int64_t k = 0; k < cnt; ++k) out->ridx[dst + k] = (int32_t)(ri[src + k] - s0);
-        if (weighted) memcpy(out->w.data() + dst, g->h_edge_data.data() + src, sizeof(float) * (size_t)cnt);
     }
+    if (weighted && nnz > 0) fill_chunk_weights(g, lcp, lo, out->w.data());
     WorkList wl;
     build_work_list(lcp.data(), out->ridx.data(), v1 - v0, wlp, &wl);
     out->items.swap(wl.items);
@@ -153,6 +199,8 @@ void build_chunk(const saga_graph* g, int64_t Dq, int64_t Sp, int i, int j, cons
     out->n_team = wl.n_team;
 }
 
+// The Q x P tiling of a host graph, built aside and handed to the graph only when it is complete: a failure on the
+// way (host memory, pinned memory) leaves the graph without a tiling, never with half of one.
 saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkListParams& wlp, bool weighted)
 {
     if (g->grid) {
@@ -161,15 +209,23 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
     }
     ChunkGrid* grid = new (std::nothrow) ChunkGrid();
     if (!grid) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
-    g->grid = grid;
+    auto bail = [&](saga_status st) {
+        chunk_grid_destroy(ctx, grid);
+        return st;
+    };
     grid->Q = Q;
     grid->P = P;
     grid->Dq = (g->n + Q - 1) / Q;
     grid->Sp = (g->n + P - 1) / P;
     grid->wlp = wlp;
     grid->weighted = weighted;
-    grid->chunks.resize((size_t)Q * P);
-    std::vector<BuiltChunk> built((size_t)Q * P);
+    std::vector<BuiltChunk> built;
+    try {
+        grid->chunks.resize((size_t)Q * P);
+        built.resize((size_t)Q * P);
+    } catch (...) {
+        return bail(ctx->fail(SAGA_ERR_INTERNAL, "out of host memory while tiling the graph"));
+    }
     std::atomic<bool> oom{false};
     parallel_for((int64_t)Q * P, 16, [&](int64_t c) {
         try {
@@ -178,7 +234,8 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
             oom = true;
         }
     });
-    if (oom) return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory while tiling the graph");
+    if (oom) return bail(ctx->fail(SAGA_ERR_INTERNAL, "out of host memory while tiling the graph"));
+    size_t total = 0;
     for (size_t c = 0; c < built.size(); ++c) {
         ChunkMeta& m = grid->chunks[c];
         const BuiltChunk& b = built[c];
@@ -199,28 +256,37 @@ saga_status build_grid(saga_ctx* ctx, saga_graph* g, int Q, int P, const WorkLis
         m.bytes = off;
         grid->max_chunk_bytes = std::max(grid->max_chunk_bytes, m.bytes);
         grid->max_slots = std::max(grid->max_slots, m.n_slots);
-        if (m.bytes > 0 && m.nnz > 0) {
-            HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&m.host), m.bytes, hipHostMallocDefault));
+        if (m.nnz > 0) total += m.bytes;
+    }
+    if (total > 0) {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&grid->arena), total, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            grid->arena = nullptr;
+            return bail(ctx->fail(SAGA_ERR_HIP, "hipHostMalloc(%zu) for the tiling's payloads failed: %s", total, hipGetErrorString(e)));
         }
+        grid->arena_bytes = total;
+        size_t at = 0;
+        for (ChunkMeta& m : grid->chunks)
+            if (m.nnz > 0) {
+                m.host = grid->arena + at;
+                at += m.bytes;
+            }
     }
     parallel_for((int64_t)built.size(), 8, [&](int64_t c) {
         ChunkMeta& m = grid->chunks[(size_t)c];
         BuiltChunk& b = built[(size_t)c];
         if (!m.host) return;
-        memcpy(m.host + m.off_items, b.items.data(), sizeof(WorkItem) * b.items.size());
-        memcpy(m.host + m.off_heavy, b.heavy.data(), sizeof(HeavyVertex) * b.heavy.size());
-        memcpy(m.host + m.off_ridx, b.ridx.data(), sizeof(int32_t) * b.ridx.size());
-        memcpy(m.host + m.off_w, b.w.data(), sizeof(float) * b.w.size());
+        // (an empty vector's data() may be null, which memcpy must not be given even for zero bytes)
+        if (!b.items.empty()) memcpy(m.host + m.off_items, b.items.data(), sizeof(WorkItem) * b.items.size());
+        if (!b.heavy.empty()) memcpy(m.host + m.off_heavy, b.heavy.data(), sizeof(HeavyVertex) * b.heavy.size());
+        if (!b.ridx.empty()) memcpy(m.host + m.off_ridx, b.ridx.data(), sizeof(int32_t) * b.ridx.size());
+        if (!b.w.empty()) memcpy(m.host + m.off_w, b.w.data(), sizeof(float) * b.w.size());
         BuiltChunk().items.swap(b.items);
         std::vector<int32_t>().swap(b.ridx);
         std::vector<float>().swap(b.w);
     });
-    HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_in, hipStreamNonBlocking));
-    HIP_TRY(ctx, hipStreamCreateWithFlags(&grid->s_out, hipStreamNonBlocking));
-    for (hipEvent_t* e : {&grid->ev_ready[0], &grid->ev_ready[1], &grid->ev_free[0], &grid->ev_free[1], &grid->ev_y_ready[0],
-                          &grid->ev_y_ready[1], &grid->ev_y_free[0], &grid->ev_y_free[1], &grid->ev_a_done, &grid->ev_a_ready,
-                          &grid->ev_a_in, &grid->ev_d_free, &grid->ev_s_ready[0], &grid->ev_s_ready[1]})
-        HIP_TRY(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
+    g->grid = grid;
     return SAGA_OK;
 }
 
@@ -406,6 +472,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         if (saga_status st = build_grid(ctx, g, Q, P, wlp, weighted)) return st;
     ChunkGrid* grid = g->grid;
     const int64_t Dq = grid->Dq, Sp = grid->Sp;
+    if (saga_status sst = ctx->ensure_stream_set()) return sst;
+    saga_ctx::StreamSet& ss = ctx->st;
 
     // ---- device buffers, all counted against the budget ----
     saga_status st;
@@ -435,7 +503,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
 
     // "overlap" 0 puts every copy on the compute stream: nothing overlaps (the streaming-off baseline)
     hipStream_t sc = ctx->stream;
-    hipStream_t sin = ctx->opt_overlap ? grid->s_in : sc, sout = ctx->opt_overlap ? grid->s_out : sc;
+    hipStream_t sin = ctx->opt_overlap ? ss.s_in : sc, sout = ctx->opt_overlap ? ss.s_out : sc;
     const int schedule = (feed || extras) ? 0 : (has_w || ctx->opt_schedule == 2 ? ctx->opt_schedule : 0);
     std::vector<char> seen(feed ? (size_t)P : 0, 0);  // source intervals the feed has been called for
     const float* Xh = static_cast<const float*>(X->data);
@@ -474,10 +542,10 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
 
     // A_j <- identity of the accumulator, once nobody reads the buffer any more
     auto fill_a = [&](int j) -> saga_status {
-        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_done, 0));
+        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_a_done, 0));
         HIP_TRY(ctx, launch_fill_f32(A, rows_of(j) * Fw, agg == SAGA_AGG_SUM ? 0.f : -__builtin_huge_valf(), sc));
         if (gated) {  // the destination parts of this interval, once the previous interval's kernels have let go of the buffer
-            if (d_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_d_free, 0));
+            if (d_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, ss.ev_d_free, 0));
             if (extras->dst_fill) {
                 if (saga_status fs = extras->dst_fill((int64_t)j * Dq, rows_of(j), static_cast<float*>(ctx->st_D.p), sin, &bytes_h2d)) return fs;
             } else {
@@ -490,8 +558,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                                                   (size_t)Fa * 4, (size_t)rows_of(j), hipMemcpyHostToDevice, sin));
                 bytes_h2d += rows_of(j) * Fd * 4;
             }
-            HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
-            HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_in, sin));
+            HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_a_in, 0));
         }
         return SAGA_OK;
     };
@@ -502,12 +570,12 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
         const int vb = vbuf >= 0 ? vbuf : b;
         const int64_t s0 = (int64_t)i * Sp, srows = std::min(n, s0 + Sp) - s0;
         // copy stream: wait until the kernels that last read this buffer pair are done
-        if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[b], 0));
+        if (used[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, ss.ev_free[b], 0));
         if (load_v) {
             // a source buffer chosen by the caller (destination order innermost) was last read by the kernels of the
             // interval before the previous one, which may be the step just before this one when an interval had no
             // edges at all: wait for both buffer pairs then
-            if (used[1 - b] && (vb != b || vbuf >= 0)) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_free[1 - b], 0));
+            if (used[1 - b] && (vb != b || vbuf >= 0)) HIP_TRY(ctx, hipStreamWaitEvent(sin, ss.ev_free[1 - b], 0));
             if (feed) {
                 if (saga_status fs = feed->fill(s0, srows, static_cast<float*>(ctx->st_V[vb].p), sin, !seen[(size_t)i], &bytes_h2d))
                     return fs;
@@ -519,15 +587,15 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             }
         }
         if (m.nnz == 0) {  // only a feed brings us here: the interval had to be visited, there is nothing to add
-            HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sin));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_free[b], sin));
             used[b] = true;
             ++step;
             return SAGA_OK;
         }
         HIP_TRY(ctx, hipMemcpyAsync(ctx->st_C[b].p, m.host, m.bytes, hipMemcpyHostToDevice, sin));
-        HIP_TRY(ctx, hipEventRecord(grid->ev_ready[b], sin));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_ready[b], sin));
         bytes_h2d += (int64_t)m.bytes;
-        HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_ready[b], 0));
+        HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_ready[b], 0));
         const char* cb = static_cast<const char*>(ctx->st_C[b].p);
         GatherArgs ga{};
         ga.items = reinterpret_cast<const WorkItem*>(cb + m.off_items);
@@ -581,7 +649,7 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                 HIP_TRY(ctx, launch_combine(ca, sc));
             }
         }
-        HIP_TRY(ctx, hipEventRecord(grid->ev_free[b], sc));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_free[b], sc));
         used[b] = true;
         ++step;
         return SAGA_OK;
@@ -594,33 +662,33 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             if (saga_status hs = extras->after_gather(v0, rows, A, sc, &bytes_h2d)) return hs;
         if (gated) {  // every kernel that reads the destination parts of this interval (or what dst_fill left beside them,
                       // which after_gather may use) has been enqueued
-            HIP_TRY(ctx, hipEventRecord(grid->ev_d_free, sc));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_d_free, sc));
             d_busy = true;
         }
         if (!Yh) {  // nobody wants the rows (a backward pass that only needs what after_gather adds up)
-            HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sc));
             a_busy = true;
             return SAGA_OK;
         }
         if (!has_w) {
-            HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
-            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_ready, sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, ss.ev_a_ready, 0));
             HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)Fw * 4, (size_t)Fw * 4, (size_t)rows,
                                           hipMemcpyDeviceToHost, sout));
             bytes_d2h += rows * Fw * 4;
-            HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sout));
             a_busy = true;
             return SAGA_OK;
         }
         for (int64_t r0 = 0; r0 < rows; r0 += y_tile_rows) {
             const int64_t tr = std::min(y_tile_rows, rows - r0);
             const int b = (int)(ystep & 1);
-            if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_y_free[b], 0));
+            if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_y_free[b], 0));
             GemmArgs ge{};
             if (has_self) {
                 // the tile's own rows of the layer input, for the second operand; the staging buffer is free once the
                 // product that last read it has been followed by its copy-out (ev_y_free)
-                if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_y_free[b], 0));
+                if (yused[b]) HIP_TRY(ctx, hipStreamWaitEvent(sin, ss.ev_y_free[b], 0));
                 if (extras->self_fill) {
                     if (saga_status fs = extras->self_fill(v0 + r0, tr, static_cast<float*>(ctx->st_S[b].p), sin, &bytes_h2d)) return fs;
                 } else {
@@ -628,8 +696,8 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
                                                   (size_t)extras->ld_self * 4, (size_t)F_self * 4, (size_t)tr, hipMemcpyHostToDevice, sin));
                     bytes_h2d += tr * F_self * 4;
                 }
-                HIP_TRY(ctx, hipEventRecord(grid->ev_s_ready[b], sin));
-                HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_s_ready[b], 0));
+                HIP_TRY(ctx, hipEventRecord(ss.ev_s_ready[b], sin));
+                HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_s_ready[b], 0));
                 ge.A2 = ctx->st_S[b].p;
                 ge.lda2 = F_self;
                 ge.K2 = (int32_t)F_self;
@@ -647,34 +715,34 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ge.dtype = ge.out_dtype = SAGA_F32;
             ge.act = vp->act;
             HIP_TRY(ctx, launch_gemm(ge, sc));
-            HIP_TRY(ctx, hipEventRecord(grid->ev_y_ready[b], sc));
-            HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_y_ready[b], 0));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_y_ready[b], sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, ss.ev_y_ready[b], 0));
             HIP_TRY(ctx, hipMemcpy2DAsync(Yh + (v0 + r0) * Y->ld, (size_t)Y->ld * 4, ctx->st_Y[b].p, (size_t)F_out * 4,
                                           (size_t)F_out * 4, (size_t)tr, hipMemcpyDeviceToHost, sout));
-            HIP_TRY(ctx, hipEventRecord(grid->ev_y_free[b], sout));
+            HIP_TRY(ctx, hipEventRecord(ss.ev_y_free[b], sout));
             bytes_d2h += tr * F_out * 4;
             yused[b] = true;
             ++ystep;
         }
-        HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sc));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sc));
         a_busy = true;
         return SAGA_OK;
     };
     // the baselines swap the accumulator of interval j between the device and its host home
     auto swap_out = [&](int j) -> saga_status {
-        HIP_TRY(ctx, hipEventRecord(grid->ev_a_ready, sc));
-        HIP_TRY(ctx, hipStreamWaitEvent(sout, grid->ev_a_ready, 0));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_a_ready, sc));
+        HIP_TRY(ctx, hipStreamWaitEvent(sout, ss.ev_a_ready, 0));
         HIP_TRY(ctx, hipMemcpyAsync(grid->a_host + (int64_t)j * Dq * F, A, (size_t)rows_of(j) * F * 4, hipMemcpyDeviceToHost, sout));
-        HIP_TRY(ctx, hipEventRecord(grid->ev_a_done, sout));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sout));
         a_busy = true;
         bytes_d2h += rows_of(j) * F * 4;
         return SAGA_OK;
     };
     auto swap_in = [&](int j) -> saga_status {
-        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, grid->ev_a_done, 0));
+        if (a_busy) HIP_TRY(ctx, hipStreamWaitEvent(sin, ss.ev_a_done, 0));
         HIP_TRY(ctx, hipMemcpyAsync(A, grid->a_host + (int64_t)j * Dq * F, (size_t)rows_of(j) * F * 4, hipMemcpyHostToDevice, sin));
-        HIP_TRY(ctx, hipEventRecord(grid->ev_a_in, sin));
-        HIP_TRY(ctx, hipStreamWaitEvent(sc, grid->ev_a_in, 0));
+        HIP_TRY(ctx, hipEventRecord(ss.ev_a_in, sin));
+        HIP_TRY(ctx, hipStreamWaitEvent(sc, ss.ev_a_in, 0));
         bytes_h2d += rows_of(j) * F * 4;
         return SAGA_OK;
     };
@@ -745,4 +813,35 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     ctx->acc.n_split_vertices = heavy;
     ctx->acc.n_calls += 1;
     return SAGA_OK;
+}
+
+// New edge data on a host graph that already has a tiling: the weights inside the pinned payloads are written again
+// from g->h_edge_data, chunk by chunk. Nothing is allocated or freed; the caller has made sure no streamed call is in
+// flight (every streamed call synchronises its streams before it returns).
+void chunk_grid_refresh_weights(saga_graph* g)
+{
+    ChunkGrid* grid = g->grid;
+    if (!grid || !grid->weighted || g->h_edge_data.empty()) return;
+    parallel_for((int64_t)grid->chunks.size(), 8, [&](int64_t c) {
+        const ChunkMeta& m = grid->chunks[(size_t)c];
+        if (!m.host || m.nnz == 0) return;
+        try {
+            std::vector<int64_t> lcp, lo;
+            locate_chunk(g, grid->Dq, grid->Sp, (int)(c % grid->P), (int)(c / grid->P), &lcp, &lo);
+            fill_chunk_weights(g, lcp, lo, reinterpret_cast<float*>(m.host + m.off_w));
+        } catch (...) {
+            // out of host memory for two small index vectors: fall back to one column at a time
+            const int64_t v0 = (c / grid->P) * grid->Dq, v1 = std::min(g->n, v0 + grid->Dq);
+            const int64_t s0 = (c % grid->P) * grid->Sp, s1 = std::min(g->n, s0 + grid->Sp);
+            float* out = reinterpret_cast<float*>(m.host + m.off_w);
+            const int32_t* ri = g->h_row_idx.data();
+            for (int64_t v = v0; v < v1; ++v) {
+                const int32_t* b = ri + g->h_col_ptr[(size_t)v];
+                const int32_t* e = ri + g->h_col_ptr[(size_t)v + 1];
+                const int32_t* l = std::lower_bound(b, e, (int32_t)s0);
+                const int32_t* h = std::lower_bound(l, e, (int32_t)std::min<int64_t>(s1, 0x7fffffff));
+                for (const int32_t* q = l; q < h; ++q) *out++ = g->h_edge_data[(size_t)(q - ri)];
+            }
+        }
+    });
 }

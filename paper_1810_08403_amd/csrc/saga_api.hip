@@ -4,6 +4,7 @@
 // functions, and argument checking for every entry point.
 #include <algorithm>
 #include <cstring>
+#include <exception>
 
 #include "saga_internal.h"
 
@@ -488,6 +489,22 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
     return streamed_forward(ctx, g, &hx, &e2, agg, vp, Y, &feed, use_ex ? &ex : nullptr);
 }
 
+// No C++ exception may leave an extern "C" entry point: whatever the layer code throws (host memory for a work list,
+// a tiling, a vector of counts) becomes SAGA_ERR_INTERNAL, after everything the call enqueued has been waited for.
+template <typename Fn>
+static saga_status guarded(saga_ctx* ctx, Fn&& fn)
+{
+    try {
+        return fn();
+    } catch (const std::exception& e) {
+        chunk_grid_drain(ctx);
+        return ctx->fail(SAGA_ERR_INTERNAL, "%s", e.what());
+    } catch (...) {
+        chunk_grid_drain(ctx);
+        return ctx->fail(SAGA_ERR_INTERNAL, "unknown exception");
+    }
+}
+
 extern "C" {
 
 const char* saga_version(void) { return kVersion; }
@@ -618,6 +635,7 @@ saga_status saga_destroy(saga_ctx* ctx)
                       &ctx->st_S[1]})
         ctx->dev_free(b);
     if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
+    ctx->destroy_stream_set();
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
@@ -840,12 +858,13 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
         } catch (...) {
             return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
         }
-        if (g->grid) {  // chunk-ordered copy is rebuilt at the next call
-            chunk_grid_destroy(ctx, g->grid);
-            g->grid = nullptr;
-        }
-        transposed_graph_destroy(ctx, g);  // its copy of the edge data, too
-        return SAGA_OK;
+        // A tiling that exists keeps its structure: only the weights inside its pinned payloads are written again (no
+        // streamed call is in flight: each one synchronises its streams before it returns). The same for the edge
+        // order by source and its tiling.
+        return guarded(ctx, [&] {
+            chunk_grid_refresh_weights(g);
+            return transposed_host_refresh_weights(ctx, g);
+        });
     }
     g->tr_edge_data_valid = false;
     if (saga_status st = ctx->dev_alloc(&g->d_edge_data, sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1))) return st;
@@ -1128,8 +1147,8 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
         if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
-        const saga_status sst = streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y);
-        if (sst != SAGA_OK) chunk_grid_drain(ctx, g->grid);  // host tensors are the caller's again when this returns
+        const saga_status sst = guarded(ctx, [&] { return streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y); });
+        if (sst != SAGA_OK) chunk_grid_drain(ctx);  // host tensors are the caller's again when this returns
         return sst;
     }
     if (Y->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
@@ -1140,7 +1159,7 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
     if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
     if (g->n == 0) return SAGA_OK;
-    return resident_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y, accum_out);
+    return guarded(ctx, [&] { return resident_forward(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y, accum_out); });
 }
 
 saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_tensor* A,
@@ -1222,14 +1241,12 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
-        const saga_status sst = gated_h ? streamed_gated_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads)
-                                : max_or_pool
-                                    ? streamed_max_pool_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
-                                    : streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
-        if (sst != SAGA_OK) {  // host tensors are the caller's again when this returns
-            chunk_grid_drain(ctx, g->grid);
-            if (g->tr) chunk_grid_drain(ctx, g->tr->grid);
-        }
+        const saga_status sst = guarded(ctx, [&] {
+            return gated_h ? streamed_gated_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads)
+                   : max_or_pool ? streamed_max_pool_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
+                                 : streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
+        });
+        if (sst != SAGA_OK) chunk_grid_drain(ctx);  // host tensors are the caller's again when this returns
         return sst;
     }
     if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
@@ -1276,7 +1293,7 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && !ep->edge_weight && !g->d_edge_data.p && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "MUL_WEIGHT needs edge_weight or saga_graph_set_edge_data");
         DeviceGuard guard16(ctx->device);
-        return resident_backward_bf16(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
+        return guarded(ctx, [&] { return resident_backward_bf16(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads); });
     }
     if (!dev_f32(W) || W->rows > (1 << 20) || W->cols > (1 << 20))
         return ctx->fail(SAGA_ERR_INVALID_ARG, "W must be a device Fm x F_out fp32 tensor");
@@ -1339,7 +1356,7 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         return ctx->fail(SAGA_ERR_INVALID_ARG, "gate gradients are for GATED layers only");
     }
     DeviceGuard guard(ctx->device);
-    return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads);
+    return guarded(ctx, [&] { return resident_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads); });
 }
 
 }  // extern "C"

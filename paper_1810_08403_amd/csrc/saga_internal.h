@@ -108,6 +108,19 @@ struct saga_ctx {
     DevBuf st_D, st_S[2];  // gated: destination parts of the resident interval; W_self: tiles of the interval's own rows
     float* h_grad = nullptr;   // streamed backward of max / pooled layers: the gradient of accum of all vertices, pinned
     size_t h_grad_bytes = 0;
+    // The copy-in and copy-out streams and the events of the chunk schedule. They belong to the context, are made at the
+    // first streamed call and live until saga_destroy: one streamed call runs at a time, and tilings come and go with
+    // the row width of a call, which must not cost a stream and fourteen events each time.
+    struct StreamSet {
+        hipStream_t s_in = nullptr, s_out = nullptr;
+        hipEvent_t ev_ready[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+        hipEvent_t ev_y_ready[2] = {nullptr, nullptr}, ev_y_free[2] = {nullptr, nullptr};
+        hipEvent_t ev_a_done = nullptr, ev_a_ready = nullptr, ev_a_in = nullptr;
+        hipEvent_t ev_d_free = nullptr, ev_s_ready[2] = {nullptr, nullptr};  // destination parts / own-row tiles (gated, W_self)
+        bool ready = false;
+    } st;
+    saga_status ensure_stream_set();
+    void destroy_stream_set();
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
     DevBuf ws_prod;      // streamed gated / pooled layers: packed weights of the per-vertex products (VertexProducts)
     DevBuf ws_edge_msg;  // stage-by-stage baseline: the per-edge tensor (n_edges x F fp32) and the edge numbers behind it
@@ -343,6 +356,8 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
 saga_status streamed_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g);
+// new edge data on a host graph: carried over into the edge order by source (if it exists) and into that order's tiling
+saga_status transposed_host_refresh_weights(saga_ctx* ctx, saga_graph* g);
 
 // streamed path (chunked.hip)
 // A VertexFeed replaces the plain host-to-device copy of a source interval's rows: fill() enqueues on `s` whatever leaves
@@ -407,7 +422,9 @@ struct VertexProducts {
     saga_status rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
                      hipStream_t on, int64_t* h2d) const;
 };
-void chunk_grid_drain(saga_ctx* ctx, ChunkGrid* grid);  // wait for everything a (failed) streamed call enqueued; grid may be NULL
+void chunk_grid_drain(saga_ctx* ctx);  // wait for everything a (failed) streamed call enqueued
+// new edge data on a host graph whose tiling exists: the weights inside the tiling's pinned payloads are written again
+void chunk_grid_refresh_weights(saga_graph* g);
 
 // shared by api and chunked: ApplyVertex on a block of rows already on the device
 // Xself / ld_self / F_self: the vertices' own rows for vp->W_self (ignored when that is NULL)
