@@ -192,6 +192,28 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
                                const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out);
 
 /*
+ * The resident forward layer for callers that must not allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it. Same arguments, same kernels
+ * and same results as saga_layer_forward, but everything the layer needs beyond its inputs
+ * and outputs (the Gather output, the partial rows of cut columns, the packed weights, the
+ * per-vertex products of gated and pooled layers) lives in one static device array of
+ * 64 MiB (67,108,864 bytes) that the library holds on every GPU it runs on until the
+ * process ends. The call reaches no hipMalloc / hipFree and no other allocating routine,
+ * and records no stage timings.
+ *   - Device tensors and a device graph only (SAGA_ERR_UNSUPPORTED otherwise).
+ *   - The work list for this row width must exist already: call saga_layer_forward once with
+ *     the same shapes first, else SAGA_ERR_UNSUPPORTED (building it allocates).
+ *   - A layer whose scratch needs exceed 64 MiB is refused with SAGA_ERR_BUDGET and a
+ *     message; nothing has been enqueued then.
+ *   - Every call on one GPU, from any context, uses that GPU's one array and finds the last
+ *     call's contents in it (the call overwrites what it reads): calls that overlap on one
+ *     GPU race. Enqueue them on one stream, or wait between them.
+ */
+saga_status saga_layer_forward_noalloc(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,
+                                       const saga_edge_params* ep, int32_t agg,
+                                       const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out);
+
+/*
  * Gradients a backward call writes (each overwritten, not added to). All fp32, device.
  */
 typedef struct saga_layer_grads {

@@ -28,7 +28,7 @@ MEM_DEVICE, MEM_HOST = 0, 1
 
 # every entry point include/saga.h declares
 EXPORTS = ["saga_create", "saga_destroy", "saga_graph_create_csc", "saga_graph_destroy",
-           "saga_graph_set_edge_data", "saga_layer_forward", "saga_layer_backward", "saga_set_profiling", "saga_reset_timings",
+           "saga_graph_set_edge_data", "saga_layer_forward", "saga_layer_forward_noalloc", "saga_layer_backward", "saga_set_profiling", "saga_reset_timings",
            "saga_get_timings", "saga_set_option", "saga_peak_device_bytes", "saga_last_error",
            "saga_graph_info", "saga_plan_work_list", "saga_plan_reencoding", "saga_copy_bytes", "saga_version"]
 
@@ -117,6 +117,8 @@ def declare_signatures(L: ctypes.CDLL) -> ctypes.CDLL:
     L.saga_layer_forward.restype = I32
     L.saga_layer_forward.argtypes = [P, P, ctypes.POINTER(Tensor), ctypes.POINTER(EdgeParams), I32,
                                      ctypes.POINTER(VertexParams), ctypes.POINTER(Tensor), ctypes.POINTER(Tensor)]
+    L.saga_layer_forward_noalloc.restype = I32
+    L.saga_layer_forward_noalloc.argtypes = L.saga_layer_forward.argtypes
     L.saga_layer_backward.restype = I32
     L.saga_layer_backward.argtypes = [P, P, ctypes.POINTER(Tensor), ctypes.POINTER(Tensor), ctypes.POINTER(Tensor),
                                       ctypes.POINTER(Tensor), ctypes.POINTER(EdgeParams), I32,
@@ -250,7 +252,8 @@ class Context:
     def layer_forward(self, g: Graph, X: torch.Tensor, Y: torch.Tensor, edge_op: str = "copy",
                       edge_weight: Optional[torch.Tensor] = None, W_gate=None, b_gate=None, W_msg=None,
                       W_pool=None, b_pool=None, agg: str = "sum", W=None, bias=None, W_self=None, act: str = "none",
-                      accum_out=None):
+                      accum_out=None, no_alloc: bool = False):
+        """saga_layer_forward, or saga_layer_forward_noalloc with no_alloc=True."""
         tx, ty = as_tensor(X), as_tensor(Y)
         twg, tbg, twm = as_tensor(W_gate), as_tensor(b_gate), as_tensor(W_msg)
         twp, tbp, tws = as_tensor(W_pool), as_tensor(b_pool), as_tensor(W_self)
@@ -270,8 +273,8 @@ class Context:
         cur = torch.cuda.current_stream(self.device)
         if cur != self.stream:
             self.stream.wait_stream(cur)
-        self._check(self.lib.saga_layer_forward(self._h, g._h, ctypes.byref(tx), ctypes.byref(ep), AGG[agg],
-                                                ctypes.byref(vp), ctypes.byref(ty), _ref(tacc)))
+        entry = self.lib.saga_layer_forward_noalloc if no_alloc else self.lib.saga_layer_forward
+        self._check(entry(self._h, g._h, ctypes.byref(tx), ctypes.byref(ep), AGG[agg], ctypes.byref(vp), ctypes.byref(ty), _ref(tacc)))
         if cur != self.stream:
             cur.wait_stream(self.stream)
         return Y

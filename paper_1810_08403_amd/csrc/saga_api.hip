@@ -22,8 +22,25 @@ saga_status saga_ctx::fail(saga_status s, const char* fmt, ...)
     return s;
 }
 
+// Scratch memory of saga_layer_forward_noalloc: the Gather output, the partial rows of cut columns, the packed weights
+// and the per-vertex products of one resident layer, for callers that must not allocate. One array per GPU for the
+// life of the process; every call on that GPU shares it.
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 saga_status saga_ctx::dev_alloc(DevBuf* b, size_t bytes)
 {
+    if (arena_active) {
+        if (b->p && b->bytes >= bytes) return SAGA_OK;
+        const size_t rounded = (bytes + 255) / 256 * 256;
+        if (arena_used + rounded > kScratchBytes)
+            return fail(SAGA_ERR_BUDGET, "this layer needs more than the %zu bytes of scratch memory saga_layer_forward_noalloc has",
+                        kScratchBytes);
+        b->p = bytes ? scratch_ptr + arena_used : nullptr;
+        b->bytes = bytes ? rounded : 0;
+        arena_used += bytes ? rounded : 0;
+        return SAGA_OK;
+    }
     if (b->p && b->bytes >= bytes) return SAGA_OK;
     dev_free(b);
     if (bytes == 0) return SAGA_OK;
@@ -43,6 +60,11 @@ saga_status saga_ctx::dev_alloc(DevBuf* b, size_t bytes)
 
 void saga_ctx::dev_free(DevBuf* b)
 {
+    if (arena_active) {  // carved from the static array: nothing to give back
+        b->p = nullptr;
+        b->bytes = 0;
+        return;
+    }
     if (b->p) {
         (void)hipFree(b->p);
         cur_bytes -= b->bytes;
@@ -257,6 +279,8 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
         return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team;
     };
     if (same(p, g->list_params)) return SAGA_OK;
+    if (ctx->arena_active)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "no work list for this row width yet: call saga_layer_forward once with the same shapes first");
     // park the current list, then look for one built earlier with these parameters
     if (g->list_params.min_edges >= 0) {
         if (g->saved_lists.size() >= 8) {
@@ -620,6 +644,15 @@ saga_status saga_create(saga_ctx** out, int device, void* hip_stream, size_t hbm
         }
         c->own_stream = true;
     }
+    // the static scratch array has its own copy, at its own address, on every GPU: ask for this device's, with this device current
+    void* sp = nullptr;
+    if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) {
+        (void)hipGetLastError();
+        if (c->own_stream) (void)hipStreamDestroy(c->stream);
+        delete c;
+        return SAGA_ERR_HIP;
+    }
+    c->scratch_ptr = static_cast<unsigned char*>(sp);
     *out = c;
     return SAGA_OK;
 }
@@ -908,7 +941,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
 
     saga_ctx::EventSet* es = nullptr;
-    if (ctx->profiling) {
+    if (ctx->profiling && !ctx->arena_active) {
         if (ctx->ev_used == ctx->ev_pool.size()) {
             if (ctx->ev_pool.size() >= 512) {
                 if (saga_status st = ctx->drain_events()) return st;
@@ -1078,6 +1111,30 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ctx->acc.n_split_vertices = g->n_heavy;
     ctx->acc.plan_dst_intervals = ctx->acc.plan_src_intervals = 0;
     return SAGA_OK;
+}
+
+saga_status saga_layer_forward_noalloc(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
+                                       int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out)
+{
+    if (!ctx) return SAGA_ERR_INVALID_ARG;
+    if (!g || !X) return ctx->fail(SAGA_ERR_INVALID_ARG, "null argument");
+    if (X->mem != SAGA_MEM_DEVICE || g->where != SAGA_MEM_DEVICE)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "saga_layer_forward_noalloc covers resident layers (device tensors, device graph)");
+    if (ctx->arena_active) return ctx->fail(SAGA_ERR_INVALID_ARG, "saga_layer_forward_noalloc is not re-entrant");
+    // The workspaces an ordinary call would grow are set aside; while arena_active every request is carved from the
+    // static array (or refused), so the layer code below runs unchanged and reaches no allocator.
+    DevBuf* const ws[] = {&ctx->ws_accum, &ctx->ws_accum16, &ctx->ws_partials, &ctx->ws_hoist, &ctx->ws_bt, &ctx->ws_bias, &ctx->ws_edge_msg};
+    DevBuf saved[sizeof(ws) / sizeof(ws[0])];
+    for (size_t i = 0; i < sizeof(ws) / sizeof(ws[0]); ++i) {
+        saved[i] = *ws[i];
+        *ws[i] = DevBuf{};
+    }
+    ctx->arena_used = 0;
+    ctx->arena_active = true;
+    const saga_status st = saga_layer_forward(ctx, g, X, ep, agg, vp, Y, accum_out);
+    ctx->arena_active = false;
+    for (size_t i = 0; i < sizeof(ws) / sizeof(ws[0]); ++i) *ws[i] = saved[i];
+    return st;
 }
 
 saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,

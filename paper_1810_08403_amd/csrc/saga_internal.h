@@ -137,6 +137,12 @@ struct saga_ctx {
     size_t ev_used = 0;
     saga_timings acc{};
 
+    // saga_layer_forward_noalloc: while arena_active, dev_alloc carves from the library's static device array instead of
+    // calling the allocator, dev_free does nothing, and a missing work list is an error instead of being built
+    unsigned char* scratch_ptr = nullptr;  // device address of the static array on this context's device
+    size_t arena_used = 0;
+    bool arena_active = false;
+
     saga_status fail(saga_status s, const char* fmt, ...);
     saga_status dev_alloc(DevBuf* b, size_t bytes);  // frees and reallocates when too small
     void dev_free(DevBuf* b);

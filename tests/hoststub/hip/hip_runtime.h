@@ -54,6 +54,13 @@ hipError_t hipEventDestroy(hipEvent_t e);
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s);
 hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b);
 
+// a `static __device__` array of the library is an ordinary static array here; its "device address" is its address,
+// and from the first request on it is device memory: out of bounds for host code
+#define __device__
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) (static_cast<const void*>(&(x))), sizeof(x)
+hipError_t hipGetSymbolAddress(void** p, const void* symbol, size_t bytes);
+
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t s);
 hipError_t hipMemcpy2DAsync(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height, hipMemcpyKind kind,
                             hipStream_t s);
@@ -65,10 +72,13 @@ extern "C" {
 // 0: every operation runs when it is enqueued; 1: as late as the API allows (at a synchronisation, a free,
 // a stream's destruction); 2: at random points chosen by a generator seeded with `seed`
 void stub_set_mode(int mode, uint64_t seed);
+void stub_device_synchronize(void);
 // live allocations (device + pinned) and live streams / events, for leak checks at the end of a session
 void stub_live_counts(int64_t* allocations, int64_t* bytes, int64_t* streams, int64_t* events);
 // make the n-th allocation from now on fail once (0: never): error paths
 void stub_fail_allocation(int64_t nth);
+// calls of hipMalloc, hipFree, hipHostMalloc, hipHostFree, stream and event creation so far
+int64_t stub_allocator_calls(void);
 // memory of the test driver that stands for device memory during a library call: host code must not touch it
 void stub_register_device(void* p, size_t bytes);
 void stub_unregister_device(void* p);

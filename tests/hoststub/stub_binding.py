@@ -88,6 +88,8 @@ class StubContext:
         self.lib.stub_register_device.restype = None
         self.lib.stub_unregister_device.argtypes = [ctypes.c_void_p]
         self.lib.stub_unregister_device.restype = None
+        self.lib.stub_allocator_calls.argtypes = []
+        self.lib.stub_allocator_calls.restype = ctypes.c_int64
         h = ctypes.c_void_p()
         st = self.lib.saga_create(ctypes.byref(h), 0, None, hbm_budget_bytes)
         if st != B.SAGA_OK:
@@ -96,6 +98,9 @@ class StubContext:
 
     def set_mode(self, mode: int, seed: int = 0):
         self.lib.stub_set_mode(mode, seed)
+
+    def synchronize(self):
+        self.lib.stub_device_synchronize()
 
     def live_counts(self):
         v = [ctypes.c_int64() for _ in range(4)]
@@ -124,15 +129,16 @@ class StubContext:
         return StubGraph(self, g.value, n, ri.numel(), device)
 
     def layer_forward(self, g, X, Y, edge_op="copy", edge_weight=None, W_gate=None, b_gate=None, W_msg=None, W_pool=None, b_pool=None,
-                      agg="sum", W=None, bias=None, W_self=None, act="none", accum_out=None):
+                      agg="sum", W=None, bias=None, W_self=None, act="none", accum_out=None, no_alloc=False):
         keep = [_as_tensor(t) for t in (X, Y, W_gate, b_gate, W_msg, W_pool, b_pool, W, bias, W_self, accum_out)]
         tx, ty, twg, tbg, twm, twp, tbp, tw, tb, tws, tacc = keep
         ew = edge_weight.t if isinstance(edge_weight, Dev) else edge_weight
         ep = B.EdgeParams(B.EDGE_OP[edge_op], ew.data_ptr() if ew is not None else None, _ptr(twg), _ptr(tbg), _ptr(twm), _ptr(twp), _ptr(tbp))
         vp = B.VertexParams(_ptr(tw), _ptr(tb), B.ACT[act], 0, _ptr(tws))
         with _device_scope(self.lib, X, Y, W_gate, b_gate, W_msg, W_pool, b_pool, W, bias, W_self, accum_out, edge_weight):
-            self._check(self.lib.saga_layer_forward(self._h, g._h, ctypes.byref(tx), ctypes.byref(ep), B.AGG[agg], ctypes.byref(vp),
-                                                    ctypes.byref(ty), ctypes.byref(tacc) if tacc is not None else None))
+            entry = self.lib.saga_layer_forward_noalloc if no_alloc else self.lib.saga_layer_forward
+            self._check(entry(self._h, g._h, ctypes.byref(tx), ctypes.byref(ep), B.AGG[agg], ctypes.byref(vp), ctypes.byref(ty),
+                              ctypes.byref(tacc) if tacc is not None else None))
         return Y
 
     def layer_backward(self, g, A, dY, W, dW, X=None, Y=None, edge_op="copy", edge_weight=None, agg="sum", bias=None, W_self=None, act="none",

@@ -66,6 +66,7 @@ void device_close()
 int g_mode = 0;
 uint64_t g_rng = 0x9e3779b97f4a7c15ULL;
 int64_t g_fail_in = 0;
+int64_t g_allocator_calls = 0;
 
 [[noreturn]] void die(const char* what)
 {
@@ -168,6 +169,8 @@ extern "C" void stub_set_mode(int mode, uint64_t seed)
     g_rng = seed * 0x9e3779b97f4a7c15ULL + 12345;
 }
 
+extern "C" void stub_device_synchronize(void) { run_all(); }
+
 extern "C" void stub_live_counts(int64_t* allocations, int64_t* bytes, int64_t* streams, int64_t* events)
 {
     int64_t b = 0, ns = 0, ne = 0;
@@ -205,8 +208,21 @@ hipError_t hipGetDevice(int* d)
 }
 hipError_t hipSetDevice(int d) { return d == 0 ? hipSuccess : hipErrorInvalidValue; }
 
+extern "C" int64_t stub_allocator_calls(void) { return g_allocator_calls; }
+
+hipError_t hipGetSymbolAddress(void** p, const void* symbol, size_t bytes)
+{
+    *p = const_cast<void*>(symbol);
+    if (!g_device.count(*p)) {
+        g_device[*p] = bytes;
+        if (g_device_open == 0) STUB_POISON(*p, bytes);
+    }
+    return hipSuccess;
+}
+
 static hipError_t alloc_any(void** p, size_t bytes, bool device)
 {
+    ++g_allocator_calls;
     *p = alloc_poisoned(bytes);
     if (!*p) return hipErrorOutOfMemory;
     g_allocs[*p] = bytes;
@@ -218,6 +234,7 @@ static hipError_t alloc_any(void** p, size_t bytes, bool device)
 }
 static hipError_t free_any(void* p, bool device)
 {
+    ++g_allocator_calls;
     if (!p) return hipSuccess;
     run_all();  // the real call waits for the device
     auto it = g_allocs.find(p);
@@ -253,6 +270,7 @@ extern "C" void stub_unregister_device(void* p)
 
 hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned)
 {
+    ++g_allocator_calls;
     *s = new StubStream();
     g_streams.push_back(*s);
     return hipSuccess;
@@ -285,6 +303,7 @@ hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned)
 
 hipError_t hipEventCreate(hipEvent_t* e)
 {
+    ++g_allocator_calls;
     *e = new StubEvent();
     g_events.push_back(*e);
     return hipSuccess;

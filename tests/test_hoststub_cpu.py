@@ -47,3 +47,7 @@ def test_random_sessions(stub_lib, mode, new_edge_data):
 
 def test_failed_allocations_come_back_as_errors(stub_lib):
     _run("run_alloc_failures.py", stub_lib)
+
+
+def test_no_alloc_entry_point_reaches_no_allocator(stub_lib):
+    _run("run_no_alloc.py", stub_lib)
