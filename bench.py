@@ -68,6 +68,11 @@ def main():
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--team", type=int, default=None)
     ap.add_argument("--mma", type=int, default=None, help="1: bf16 sums accumulate on the matrix unit (library option mma)")
+    ap.add_argument("--dense-blocks", type=int, default=None, help="0: bf16 sum layers without the dense-block path (library option dense_blocks)")
+    ap.add_argument("--dense-min-edges", type=int, default=None, help="edges from which a 64 x 32 block goes to the matrix cores (0: default)")
+    ap.add_argument("--dense-tile-gain", type=int, default=None)
+    ap.add_argument("--dense-overlap", type=int, default=None, help="0: the dense-block kernel runs before the sparse kernel instead of beside it")
+    ap.add_argument("--dense-chunk", type=int, default=None)
     ap.add_argument("--transform-first", type=int, default=None,
                     help="1: run the ApplyVertex product before the propagation where the layer narrows the rows (see saga_set_option)")
     ap.add_argument("--unfused", action="store_true",
@@ -135,7 +140,8 @@ def main():
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
                       ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first),
-                      ("fused", 0 if args.unfused else None)):
+                      ("dense_blocks", args.dense_blocks), ("dense_min_edges", args.dense_min_edges), ("dense_tile_gain", args.dense_tile_gain),
+                      ("dense_chunk", args.dense_chunk), ("dense_overlap", args.dense_overlap), ("fused", 0 if args.unfused else None)):
         if val is not None:
             ctx.set_option(name, val)
     t0 = time.time()

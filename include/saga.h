@@ -370,6 +370,19 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                (the propagation without the fused operator of Section 3.2, the baseline of Section 6.2); other
  *                messages return SAGA_ERR_UNSUPPORTED in this mode, a tensor above 128 GiB or the budget
  *                SAGA_ERR_BUDGET. Max results are the same bits as the fused ones, sums differ in rounding order.
+ *   "dense_blocks"  0/1 (default 1): device-resident sum layers over COPY / MUL_WEIGHT messages of bf16 rows of a multiple
+ *                of 128 features. Destinations ranked by in-degree and sources by out-degree cut the adjacency matrix
+ *                into 64 x 32 blocks; the well-filled ones (the heavy corner of a power-law graph) are multiplied as
+ *                dense products on the matrix cores, each source row read once per block instead of once per edge, the
+ *                weights as two bf16 parts (2^-17 relative); the other edges stay with the sparse propagation kernel.
+ *                Same function, another rounding order; sums stay reproducible run to run. The plan is built at the
+ *                first call that can use it. The resident backward pass does not use it.
+ *   "dense_min_edges"  edges from which a block goes to the matrix cores (0 = default 256; at most 2048)
+ *   "dense_tile_gain"  edges beyond dense_min_edges, summed over the blocks of a destination tile, from which the tile
+ *                uses the dense path at all (it costs a partial row per destination; -1 = default 512)
+ *   "dense_chunk"  blocks of one destination tile worked by one workgroup (0 = default 128)
+ *   "dense_overlap"  0/1 (default 0): 1 runs the dense kernel on a second stream beside the sparse kernel (measured:
+ *                no gain, the two fill the chip one after the other)
  *   "bwd_tile_rows"  streamed backward calls: rows per tile of the backward-ApplyVertex pass (default 0 = as
  *                many as make the widest tile about 64 MiB)
  *   "overlap"    streamed calls: 1 = copies on their own streams, overlapping the kernels

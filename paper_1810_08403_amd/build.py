@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsaga.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["saga_api.hip", "gather.hip", "gemm.hip", "gemm_tn.hip", "backward.hip", "chunked.hip"]
+SOURCES = ["saga_api.hip", "gather.hip", "hybrid.hip", "gemm.hip", "gemm_tn.hip", "backward.hip", "chunked.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are switched off for every kernel of this library

@@ -106,35 +106,6 @@ namespace {
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// fn(i) for i in [0, n) on up to max_threads threads. fn must not throw. If a thread cannot be started the threads that
-// did start (or the caller alone) do all the work: nothing is thrown from here.
-template <typename Fn>
-void parallel_for(int64_t n, int max_threads, Fn fn)
-{
-    const int nt = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, max_threads), std::thread::hardware_concurrency()));
-    if (nt <= 1) {
-        for (int64_t i = 0; i < n; ++i) fn(i);
-        return;
-    }
-    std::atomic<int64_t> next{0};
-    auto work = [&] {
-        for (;;) {
-            const int64_t i = next.fetch_add(1);
-            if (i >= n) break;
-            fn(i);
-        }
-    };
-    std::vector<std::thread> th;
-    try {
-        th.reserve((size_t)nt);
-        for (int t = 1; t < nt; ++t) th.emplace_back(work);
-    } catch (...) {
-        // out of threads or memory: carry on with what there is
-    }
-    work();
-    for (auto& t : th) t.join();
-}
-
 struct BuiltChunk {
     std::vector<WorkItem> items;
     std::vector<HeavyVertex> heavy;

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <exception>
+#include <new>
 
 #include "saga_internal.h"
 
@@ -120,7 +121,7 @@ saga_status saga_ctx::drain_events()
 // processed by the four wavefronts of one workgroup (team items come first in
 // the list); with team = 1 by one wavefront like a whole light column.
 void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
-                     WorkList* out)
+                     WorkList* out, const int32_t* extra_slots)
 {
     out->items.clear();
     out->heavy.clear();
@@ -141,7 +142,16 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
         const int64_t b = col_ptr[v], e = col_ptr[v + 1];
         const int64_t deg = e - b;
         out->max_degree = std::max(out->max_degree, deg);
-        if (deg == 0 && p.skip_empty) continue;
+        const int32_t extra = extra_slots ? extra_slots[v] : 0;
+        if (deg == 0 && p.skip_empty && extra == 0) continue;
+        if (extra > 0 && deg <= p.cut_degree) {
+            // partial rows written elsewhere come first; what is left of the column is one more partial row (or none)
+            HeavyVertex h{(int32_t)v, (int32_t)out->n_slots, extra + (deg > 0 ? 1 : 0), 0};
+            out->n_slots += extra;
+            if (deg > 0) whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, (int32_t)(out->n_slots++)});
+            out->heavy.push_back(h);
+            continue;
+        }
         if (deg <= p.cut_degree) {
             whole.push_back(WorkItem{(int32_t)v, (int32_t)b, (int32_t)e, -1});
             continue;
@@ -162,6 +172,13 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
             pos = q;
         }
         const size_t n_p = pieces.size() - first_piece;
+        if (extra > 0) {
+            HeavyVertex h{(int32_t)v, (int32_t)out->n_slots, (int32_t)(extra + n_p), 0};
+            out->n_slots += extra;
+            for (size_t i = 0; i < n_p; ++i) pieces[first_piece + i].it.slot = (int32_t)(out->n_slots++);
+            out->heavy.push_back(h);
+            continue;
+        }
         if (n_p == 1) {
             // one piece after all: its result is the vertex's row. A team still takes it
             // (four wavefronts share the edges); without teams it is an ordinary whole column.
@@ -180,6 +197,189 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
     for (const Piece& pc : pieces) out->items.push_back(pc.it);
     out->n_team = team > 1 ? (int64_t)pieces.size() : 0;
     out->items.insert(out->items.end(), whole.begin(), whole.end());
+}
+
+// The dense-block plan of a CSC (see HybridPlan). Two passes over the edges, destination tile by destination tile, on
+// several threads: the first counts the edges of every (destination tile, source tile) block and decides which blocks
+// and tiles go to the matrix cores, the second writes the dense edges block by block and the remainder as a CSC.
+void build_hybrid_plan(const int64_t* col_ptr, const int32_t* row_idx, int64_t n, const HybridParams& hp, HybridPlan* out)
+{
+    *out = HybridPlan{};
+    const int64_t nnz = col_ptr[n];
+    const int64_t n_dt = (n + kDenseM - 1) / kDenseM, n_st = (n + kDenseK - 1) / kDenseK;
+    out->n_dst_tiles = n_dt;
+    out->n_src_tiles = n_st;
+    // ranks: heavy first, ties by id
+    std::vector<int64_t> outdeg((size_t)n, 0);
+    for (int64_t e = 0; e < nnz; ++e) ++outdeg[(size_t)row_idx[e]];
+    std::vector<int32_t> dorder((size_t)n), sorder((size_t)n);
+    for (int64_t v = 0; v < n; ++v) dorder[(size_t)v] = sorder[(size_t)v] = (int32_t)v;
+    std::stable_sort(dorder.begin(), dorder.end(),
+                     [&](int32_t a, int32_t b) { return col_ptr[a + 1] - col_ptr[a] > col_ptr[b + 1] - col_ptr[b]; });
+    std::stable_sort(sorder.begin(), sorder.end(), [&](int32_t a, int32_t b) { return outdeg[(size_t)a] > outdeg[(size_t)b]; });
+    std::vector<int32_t> spos((size_t)n);
+    for (int64_t r = 0; r < n; ++r) spos[(size_t)sorder[(size_t)r]] = (int32_t)r;
+    out->dst_order.assign((size_t)n_dt * kDenseM, -1);
+    out->src_tile_ids.assign((size_t)n_st * kDenseK, 0);
+    for (int64_t r = 0; r < n; ++r) {
+        out->dst_order[(size_t)r] = dorder[(size_t)r];
+        out->src_tile_ids[(size_t)r] = sorder[(size_t)r];
+    }
+    out->extra_slots.assign((size_t)n, 0);
+
+    // pass 1: per destination tile, the dense source tiles (ascending) and their edge counts
+    struct TilePlan {
+        std::vector<int32_t> st;   // dense source tiles
+        std::vector<int32_t> cnt;  // edges of each
+    };
+    std::vector<TilePlan> tp((size_t)n_dt);
+    std::vector<int64_t> rem_deg((size_t)n, 0);
+    const int n_threads = 16;
+    std::atomic<bool> failed{false};
+    parallel_for(n_threads, n_threads, [&](int64_t th) {
+        try {
+            std::vector<int32_t> cnt((size_t)n_st, 0), touched;
+            for (int64_t t = th; t < n_dt; t += n_threads) {
+                touched.clear();
+                for (int m = 0; m < kDenseM; ++m) {
+                    const int32_t v = out->dst_order[(size_t)t * kDenseM + m];
+                    if (v < 0) continue;
+                    for (int64_t e = col_ptr[v]; e < col_ptr[v + 1]; ++e) {
+                        const int32_t st = spos[(size_t)row_idx[e]] / kDenseK;
+                        if (cnt[(size_t)st]++ == 0) touched.push_back(st);
+                    }
+                }
+                int64_t gain = 0;
+                for (int32_t st : touched)
+                    if (cnt[(size_t)st] >= hp.min_block_edges) gain += cnt[(size_t)st] - hp.min_block_edges;
+                if (gain >= hp.min_tile_gain && gain > 0) {
+                    std::sort(touched.begin(), touched.end());
+                    for (int32_t st : touched)
+                        if (cnt[(size_t)st] >= hp.min_block_edges) {
+                            tp[(size_t)t].st.push_back(st);
+                            tp[(size_t)t].cnt.push_back(cnt[(size_t)st]);
+                        }
+                }
+                for (int32_t st : touched) cnt[(size_t)st] = 0;
+            }
+        } catch (...) {
+            failed = true;
+        }
+    });
+    if (failed) throw std::bad_alloc();
+
+    // blocks, chunks and offsets
+    std::vector<int64_t> tile_b0((size_t)n_dt + 1, 0);
+    for (int64_t t = 0; t < n_dt; ++t) tile_b0[(size_t)t + 1] = tile_b0[(size_t)t] + (int64_t)tp[(size_t)t].st.size();
+    const int64_t nb = tile_b0[(size_t)n_dt];
+    if (nb > 0x7fffffffLL - 1) throw std::bad_alloc();
+    out->blk_src_tile.resize((size_t)nb);
+    out->blk_e0.assign((size_t)nb + 1, 0);
+    out->blk_tile.assign((size_t)nb, -1);
+    std::vector<int64_t> blk_t0((size_t)nb + 1, 0);  // offsets of the finished operands' edges in dt_addr / dt_edge
+    int64_t nde = 0, ndt = 0, n_tiles = 0;
+    const int64_t ch = std::max<int64_t>(1, hp.max_chunk_blocks);
+    for (int64_t t = 0; t < n_dt; ++t) {
+        const TilePlan& p = tp[(size_t)t];
+        const int64_t b0 = tile_b0[(size_t)t], k = (int64_t)p.st.size();
+        for (int64_t i = 0; i < k; ++i) {
+            out->blk_src_tile[(size_t)(b0 + i)] = p.st[(size_t)i];
+            out->blk_e0[(size_t)(b0 + i)] = (int32_t)nde;
+            blk_t0[(size_t)(b0 + i)] = ndt;
+            if (p.cnt[(size_t)i] > kDenseListMax) {
+                out->blk_tile[(size_t)(b0 + i)] = (int32_t)n_tiles++;
+                ndt += p.cnt[(size_t)i];
+            } else {
+                nde += p.cnt[(size_t)i];
+            }
+        }
+        if (k == 0) continue;
+        const int64_t n_chunks = (k + ch - 1) / ch;
+        for (int64_t c = 0; c < n_chunks; ++c)
+            out->chunks.push_back(DenseChunk{(int32_t)t, (int32_t)(b0 + c * ch), (int32_t)std::min(b0 + k, b0 + (c + 1) * ch), (int32_t)c});
+        for (int m = 0; m < kDenseM; ++m) {
+            const int32_t v = out->dst_order[(size_t)t * kDenseM + m];
+            if (v >= 0) out->extra_slots[(size_t)v] = (int32_t)n_chunks;
+        }
+    }
+    if (nde > 0x7fffffffLL - 1 || ndt > 0x7fffffffLL - 1 || n_tiles * kDenseTileElems > 0x7fffffffLL - 1) throw std::bad_alloc();
+    out->blk_e0[(size_t)nb] = (int32_t)nde;
+    blk_t0[(size_t)nb] = ndt;
+    out->n_dense_edges = nde + ndt;
+    out->n_tiles = n_tiles;
+    out->de_pos.resize((size_t)nde);
+    out->de_edge.resize((size_t)nde);
+    out->dt_addr.resize((size_t)ndt);
+    out->dt_edge.resize((size_t)ndt);
+
+    // pass 2: dense edges into their blocks; what is left of every column counted, then written
+    std::vector<int64_t> rem_cnt((size_t)n, 0);
+    parallel_for(n_threads, n_threads, [&](int64_t th) {
+        try {
+            std::vector<int32_t> blk_of((size_t)n_st, -1);
+            std::vector<int32_t> cursor;
+            for (int64_t t = th; t < n_dt; t += n_threads) {
+                const TilePlan& p = tp[(size_t)t];
+                const int64_t b0 = tile_b0[(size_t)t];
+                for (size_t i = 0; i < p.st.size(); ++i) blk_of[(size_t)p.st[i]] = (int32_t)i;
+                cursor.assign(p.st.size(), 0);
+                for (int m = 0; m < kDenseM; ++m) {
+                    const int32_t v = out->dst_order[(size_t)t * kDenseM + m];
+                    if (v < 0) continue;
+                    int64_t left = 0;
+                    for (int64_t e = col_ptr[v]; e < col_ptr[v + 1]; ++e) {
+                        const int32_t sp = spos[(size_t)row_idx[e]];
+                        const int32_t bi = blk_of[(size_t)(sp / kDenseK)];
+                        if (bi < 0) {
+                            ++left;
+                            continue;
+                        }
+                        const int k = sp % kDenseK;
+                        // the weight's place in the block's 64 x 32 operand, in the lane order of the 16x16x32 matrix instruction:
+                        // sub-tile of 16 destinations, then lane = (k / 8) * 16 + (m % 16), then k % 8
+                        const int pos = (((m >> 4) * 64 + (k >> 3) * 16 + (m & 15)) << 3) + (k & 7);
+                        const int32_t tile = out->blk_tile[(size_t)(b0 + bi)];
+                        if (tile >= 0) {
+                            const int64_t at = blk_t0[(size_t)(b0 + bi)] + cursor[(size_t)bi]++;
+                            out->dt_addr[(size_t)at] = (int32_t)((int64_t)tile * kDenseTileElems + pos);
+                            out->dt_edge[(size_t)at] = (int32_t)e;
+                        } else {
+                            const int64_t at = (int64_t)out->blk_e0[(size_t)(b0 + bi)] + cursor[(size_t)bi]++;
+                            out->de_pos[(size_t)at] = (uint16_t)pos;
+                            out->de_edge[(size_t)at] = (int32_t)e;
+                        }
+                    }
+                    rem_cnt[(size_t)v] = left;
+                }
+                for (size_t i = 0; i < p.st.size(); ++i) blk_of[(size_t)p.st[i]] = -1;
+            }
+        } catch (...) {
+            failed = true;
+        }
+    });
+    if (failed) throw std::bad_alloc();
+    out->rem_col_ptr.assign((size_t)n + 1, 0);
+    for (int64_t v = 0; v < n; ++v) out->rem_col_ptr[(size_t)v + 1] = out->rem_col_ptr[(size_t)v] + rem_cnt[(size_t)v];
+    const int64_t nrem = out->rem_col_ptr[(size_t)n];
+    out->rem_row_idx.resize((size_t)nrem);
+    out->rem_edge.resize((size_t)nrem);
+    std::vector<int32_t> dpos((size_t)n);
+    for (int64_t r = 0; r < n; ++r) dpos[(size_t)dorder[(size_t)r]] = (int32_t)r;
+    parallel_for(n_threads, n_threads, [&](int64_t th) {
+        // (no allocation in here: a tile's dense source tiles are looked up by binary search)
+        const int64_t v0 = n * th / n_threads, v1 = n * (th + 1) / n_threads;
+        for (int64_t v = v0; v < v1; ++v) {
+            const TilePlan& p = tp[(size_t)(dpos[(size_t)v] / kDenseM)];
+            int64_t at = out->rem_col_ptr[(size_t)v];
+            for (int64_t e = col_ptr[v]; e < col_ptr[v + 1]; ++e) {
+                const int32_t st = spos[(size_t)row_idx[e]] / kDenseK;
+                if (!p.st.empty() && std::binary_search(p.st.begin(), p.st.end(), st)) continue;
+                out->rem_row_idx[(size_t)at] = row_idx[e];
+                out->rem_edge[(size_t)at] = (int32_t)e;
+                ++at;
+            }
+        }
+    });
 }
 
 namespace {
@@ -334,6 +534,106 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
     g->n_heavy = (int64_t)wl.heavy.size();
     g->n_slots = wl.n_slots;
     g->list_params = p;
+    return SAGA_OK;
+}
+
+static void hybrid_free(saga_ctx* ctx, HybridDevice* h)
+{
+    for (DevBuf* b : {&h->chunks, &h->blk_src_tile, &h->blk_e0, &h->blk_tile, &h->de_pos, &h->de_edge, &h->de_w, &h->dt_addr, &h->dt_edge, &h->de_tiles,
+                      &h->src_tile_ids, &h->tile_row_slot0,
+                      &h->rem_row_idx, &h->rem_edge, &h->rem_w, &h->items, &h->heavy})
+        ctx->dev_free(b);
+    *h = HybridDevice{};
+}
+
+static HybridParams hybrid_params(const saga_ctx* ctx)
+{
+    HybridParams hp;
+    if (ctx->opt_dense_min_edges > 0) hp.min_block_edges = ctx->opt_dense_min_edges;
+    if (ctx->opt_dense_tile_gain >= 0) hp.min_tile_gain = ctx->opt_dense_tile_gain;
+    if (ctx->opt_dense_chunk > 0) hp.max_chunk_blocks = (int32_t)ctx->opt_dense_chunk;
+    return hp;
+}
+
+// The dense-block form of a resident graph for rows of `row_bytes` (the remainder's work list depends on the row width
+// like any other): built on the host at the first call that can use it, kept in the graph handle.
+static saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+{
+    HybridDevice& h = g->hyb;
+    const WorkListParams p = work_list_params(ctx, row_bytes);
+    const HybridParams hp = hybrid_params(ctx);
+    auto same = [](const WorkListParams& a, const WorkListParams& b) {
+        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team;
+    };
+    if (h.built && same(p, h.list_params) && hp.min_block_edges == h.hp.min_block_edges && hp.min_tile_gain == h.hp.min_tile_gain &&
+        hp.max_chunk_blocks == h.hp.max_chunk_blocks)
+        return SAGA_OK;
+    if (ctx->arena_active)
+        return ctx->fail(SAGA_ERR_UNSUPPORTED, "no dense-block plan for this row width yet: call saga_layer_forward once with the same shapes first");
+    hybrid_free(ctx, &h);
+    h.list_params = p;
+    h.hp = hp;
+    h.built = true;
+    if (g->nnz == 0 || g->n >= (1LL << 30)) return SAGA_OK;
+    std::vector<int32_t> h_row((size_t)g->nnz);
+    HIP_TRY(ctx, hipMemcpyAsync(h_row.data(), g->d_row_idx.p, sizeof(int32_t) * (size_t)g->nnz, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HybridPlan plan;
+    build_hybrid_plan(g->h_col_ptr.data(), h_row.data(), g->n, hp, &plan);
+    if (plan.chunks.empty()) return SAGA_OK;  // nothing dense enough: the sparse kernel takes the whole graph
+    WorkList wl;
+    build_work_list(plan.rem_col_ptr.data(), plan.rem_row_idx.data(), g->n, p, &wl, plan.extra_slots.data());
+    // first partial row of every destination that has dense blocks, by destination rank
+    std::vector<int32_t> slot0_of((size_t)g->n, -1);
+    for (const HeavyVertex& hv : wl.heavy) slot0_of[(size_t)hv.v] = hv.slot0;
+    std::vector<int32_t> tile_row_slot0(plan.dst_order.size(), -1);
+    for (size_t i = 0; i < plan.dst_order.size(); ++i) {
+        const int32_t v = plan.dst_order[i];
+        if (v >= 0 && plan.extra_slots[(size_t)v] > 0) tile_row_slot0[i] = slot0_of[(size_t)v];
+    }
+    auto up = [&](DevBuf* b, const void* src, size_t bytes) -> saga_status {
+        if (saga_status st = ctx->dev_alloc(b, std::max<size_t>(bytes, 16))) return st;
+        if (bytes) HIP_TRY(ctx, hipMemcpyAsync(b->p, src, bytes, hipMemcpyHostToDevice, ctx->stream));
+        return SAGA_OK;
+    };
+    saga_status st;
+    if ((st = up(&h.chunks, plan.chunks.data(), sizeof(DenseChunk) * plan.chunks.size())) ||
+        (st = up(&h.blk_src_tile, plan.blk_src_tile.data(), 4 * plan.blk_src_tile.size())) ||
+        (st = up(&h.blk_e0, plan.blk_e0.data(), 4 * plan.blk_e0.size())) ||
+        (st = up(&h.blk_tile, plan.blk_tile.data(), 4 * plan.blk_tile.size())) ||
+        (st = up(&h.de_pos, plan.de_pos.data(), 2 * plan.de_pos.size())) ||
+        (st = up(&h.de_edge, plan.de_edge.data(), 4 * plan.de_edge.size())) ||
+        (st = up(&h.dt_addr, plan.dt_addr.data(), 4 * plan.dt_addr.size())) ||
+        (st = up(&h.dt_edge, plan.dt_edge.data(), 4 * plan.dt_edge.size())) ||
+        (st = ctx->dev_alloc(&h.de_tiles, std::max<size_t>(2 * (size_t)plan.n_tiles * kDenseTileElems, 16))) ||
+        (st = up(&h.src_tile_ids, plan.src_tile_ids.data(), 4 * plan.src_tile_ids.size())) ||
+        (st = up(&h.tile_row_slot0, tile_row_slot0.data(), 4 * tile_row_slot0.size())) ||
+        (st = up(&h.rem_row_idx, plan.rem_row_idx.data(), 4 * plan.rem_row_idx.size())) ||
+        (st = up(&h.rem_edge, plan.rem_edge.data(), 4 * plan.rem_edge.size())) ||
+        (st = up(&h.items, wl.items.data(), sizeof(WorkItem) * wl.items.size())) ||
+        (st = up(&h.heavy, wl.heavy.data(), sizeof(HeavyVertex) * wl.heavy.size())) ||
+        (st = ctx->dev_alloc(&h.de_w, std::max<size_t>(4 * plan.de_pos.size(), 16))) ||
+        (st = ctx->dev_alloc(&h.rem_w, std::max<size_t>(4 * plan.rem_row_idx.size(), 16)))) {
+        (void)hipStreamSynchronize(ctx->stream);
+        hybrid_free(ctx, &h);
+        return st;
+    }
+    // the finished operands start as zeros; packing the weights only ever writes the cells that hold an edge
+    if (plan.n_tiles > 0) HIP_TRY(ctx, launch_zero_bytes(h.de_tiles.p, 2 * (size_t)plan.n_tiles * kDenseTileElems, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // the host vectors go out of scope below
+    h.n_list_edges = (int64_t)plan.de_pos.size();
+    h.n_tile_edges = (int64_t)plan.dt_addr.size();
+    h.n_tiles = plan.n_tiles;
+    h.n_chunks = (int64_t)plan.chunks.size();
+    h.n_blocks = (int64_t)plan.blk_src_tile.size();
+    h.n_dense_edges = plan.n_dense_edges;
+    h.n_rem_edges = (int64_t)plan.rem_row_idx.size();
+    h.n_items = (int64_t)wl.items.size();
+    h.n_team = wl.n_team;
+    h.n_heavy = (int64_t)wl.heavy.size();
+    h.n_slots = wl.n_slots;
+    h.weights_state = 0;
+    h.usable = true;
     return SAGA_OK;
 }
 
@@ -557,6 +857,50 @@ saga_status saga_plan_work_list(int64_t n, const int64_t* col_ptr, const int32_t
     return SAGA_OK;
 }
 
+saga_status saga_plan_dense_blocks(int64_t n, const int64_t* col_ptr, const int32_t* row_idx, int64_t min_block_edges, int64_t min_tile_gain,
+                                   int32_t max_chunk_blocks, int64_t* counts, int32_t* chunks_out, int64_t chunk_capacity, int32_t* block_edges_out,
+                                   int64_t block_capacity, int32_t* remainder_row_idx_out, int32_t* remainder_edge_out, int64_t* remainder_col_ptr_out,
+                                   int32_t* dense_edge_out, int32_t* dense_block_of_edge_out)
+{
+    if (n < 0 || !col_ptr || !counts || min_block_edges < 1 || min_tile_gain < 0 || max_chunk_blocks < 1) return SAGA_ERR_INVALID_ARG;
+    if (col_ptr[n] > 0 && !row_idx) return SAGA_ERR_INVALID_ARG;
+    try {
+        HybridPlan plan;
+        HybridParams hp;
+        hp.min_block_edges = min_block_edges;
+        hp.min_tile_gain = min_tile_gain;
+        hp.max_chunk_blocks = max_chunk_blocks;
+        build_hybrid_plan(col_ptr, row_idx, n, hp, &plan);
+        counts[0] = (int64_t)plan.chunks.size();
+        counts[1] = (int64_t)plan.blk_src_tile.size();
+        counts[2] = plan.n_dense_edges;
+        counts[3] = (int64_t)plan.rem_row_idx.size();
+        if (chunks_out) memcpy(chunks_out, plan.chunks.data(), sizeof(DenseChunk) * (size_t)std::min<int64_t>(chunk_capacity, counts[0]));
+        if (block_edges_out)
+            for (int64_t b = 0; b < std::min<int64_t>(block_capacity, counts[1]); ++b)
+                block_edges_out[b] = plan.blk_tile[(size_t)b] >= 0 ? -1 : plan.blk_e0[(size_t)b + 1] - plan.blk_e0[(size_t)b];
+        if (remainder_row_idx_out && counts[3] > 0) memcpy(remainder_row_idx_out, plan.rem_row_idx.data(), 4 * (size_t)counts[3]);
+        if (remainder_edge_out && counts[3] > 0) memcpy(remainder_edge_out, plan.rem_edge.data(), 4 * (size_t)counts[3]);
+        if (remainder_col_ptr_out) memcpy(remainder_col_ptr_out, plan.rem_col_ptr.data(), 8 * ((size_t)n + 1));
+        if (dense_edge_out) {  // list edges first, then the edges of the finished operands
+            if (!plan.de_edge.empty()) memcpy(dense_edge_out, plan.de_edge.data(), 4 * plan.de_edge.size());
+            if (!plan.dt_edge.empty()) memcpy(dense_edge_out + plan.de_edge.size(), plan.dt_edge.data(), 4 * plan.dt_edge.size());
+        }
+        if (dense_block_of_edge_out) {
+            for (int64_t b = 0; b < counts[1]; ++b)
+                for (int32_t e = plan.blk_e0[(size_t)b]; e < plan.blk_e0[(size_t)b + 1]; ++e) dense_block_of_edge_out[e] = (int32_t)b;
+            std::vector<int32_t> block_of_tile((size_t)plan.n_tiles, -1);
+            for (int64_t b = 0; b < counts[1]; ++b)
+                if (plan.blk_tile[(size_t)b] >= 0) block_of_tile[(size_t)plan.blk_tile[(size_t)b]] = (int32_t)b;
+            for (size_t i = 0; i < plan.dt_addr.size(); ++i)
+                dense_block_of_edge_out[plan.de_edge.size() + i] = block_of_tile[(size_t)(plan.dt_addr[i] / kDenseTileElems)];
+        }
+    } catch (...) {
+        return SAGA_ERR_INTERNAL;
+    }
+    return SAGA_OK;
+}
+
 saga_status saga_plan_reencoding(int64_t n, const int64_t* col_ptr, const int32_t* row_idx, int32_t Q, int32_t P, uint64_t seed,
                                  int32_t* new_id, int64_t* before, int64_t* after)
 {
@@ -669,6 +1013,9 @@ saga_status saga_destroy(saga_ctx* ctx)
         ctx->dev_free(b);
     if (ctx->h_grad) (void)hipHostFree(ctx->h_grad);
     ctx->destroy_stream_set();
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    if (ctx->s_dense) (void)hipStreamDestroy(ctx->s_dense);
     for (auto& es : ctx->ev_pool)
         for (auto& e : es.ev) (void)hipEventDestroy(e);
     if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
@@ -712,6 +1059,21 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "bwd_tile_rows")) {
         if (value < 0 || value > (1LL << 31)) return ctx->fail(SAGA_ERR_INVALID_ARG, "bwd_tile_rows must be in [0, 2^31]");
         ctx->opt_bwd_tile_rows = value;
+    } else if (!strcmp(name, "dense_blocks")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "dense_blocks must be 0 or 1");
+        ctx->opt_dense_blocks = (int)value;
+    } else if (!strcmp(name, "dense_overlap")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "dense_overlap must be 0 or 1");
+        ctx->opt_dense_overlap = (int)value;
+    } else if (!strcmp(name, "dense_min_edges")) {
+        if (value < 0 || value > kDenseM * kDenseK) return ctx->fail(SAGA_ERR_INVALID_ARG, "dense_min_edges must be in [0, 2048]");
+        ctx->opt_dense_min_edges = value;
+    } else if (!strcmp(name, "dense_tile_gain")) {
+        if (value < -1 || value > (1LL << 40)) return ctx->fail(SAGA_ERR_INVALID_ARG, "dense_tile_gain must be in [-1, 2^40]");
+        ctx->opt_dense_tile_gain = value;
+    } else if (!strcmp(name, "dense_chunk")) {
+        if (value < 0 || value > (1 << 20)) return ctx->fail(SAGA_ERR_INVALID_ARG, "dense_chunk must be in [0, 2^20]");
+        ctx->opt_dense_chunk = value;
     } else if (!strcmp(name, "fused")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "fused must be 0 or 1");
         ctx->opt_fused = (int)value;
@@ -873,6 +1235,7 @@ saga_status saga_graph_destroy(saga_graph* g)
         ctx->dev_free(&sl.items);
         ctx->dev_free(&sl.heavy);
     }
+    hybrid_free(ctx, &g->hyb);
     if (g->grid) chunk_grid_destroy(ctx, g->grid);
     transposed_graph_destroy(ctx, g);
     delete g;
@@ -900,6 +1263,7 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
         });
     }
     g->tr_edge_data_valid = false;
+    if (g->hyb.weights_state == 1) g->hyb.weights_state = 0;  // the dense-block form packs the new data at its next call
     if (saga_status st = ctx->dev_alloc(&g->d_edge_data, sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1))) return st;
     if (g->nnz > 0) {
         HIP_TRY(ctx, hipMemcpyAsync(g->d_edge_data.p, w, sizeof(float) * (size_t)g->nnz, hipMemcpyDeviceToDevice, ctx->stream));
@@ -938,7 +1302,19 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     const int32_t Fo_tf = tf ? (int32_t)vp->W->cols : 0;
     // bytes one edge gathers: the source row, or two hoisted fp32 rows when gated
     const int64_t row_bytes = ep->op == SAGA_EDGE_GATED ? 2 * (int64_t)F * 4 : (int64_t)(tf ? Fo_tf : Fm) * (bf16 ? 2 : 4);
-    if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
+    // bf16 rows summed over linear messages: the well-filled blocks of the adjacency matrix go to the matrix cores, the
+    // sparse kernel keeps the remainder (rows of a multiple of 128 features, 16-byte aligned: what the dense kernel loads)
+    const int32_t Fg = tf ? Fo_tf : Fm;  // width of the rows the propagation moves
+    const int64_t ld_g = tf ? (int64_t)Fo_tf : X->ld;
+    bool hybrid = ctx->opt_dense_blocks && ctx->opt_fused && !ctx->opt_team && !ctx->opt_mma && bf16 && agg == SAGA_AGG_SUM &&
+                  (ep->op == SAGA_EDGE_COPY || ep->op == SAGA_EDGE_MUL_WEIGHT) && Fg % 128 == 0 && ld_g % 8 == 0 &&
+                  (tf || (reinterpret_cast<uintptr_t>(X->data) & 15u) == 0);
+    if (hybrid) {
+        if (saga_status st = ensure_hybrid(ctx, g, row_bytes)) return st;
+        hybrid = g->hyb.usable;
+    }
+    if (!hybrid)
+        if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
 
     saga_ctx::EventSet* es = nullptr;
     if (ctx->profiling && !ctx->arena_active) {
@@ -958,10 +1334,13 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     }
 
     GatherArgs ga{};
-    ga.items = static_cast<const WorkItem*>(g->d_items.p);
-    ga.n_items = g->n_items;
-    ga.n_team = g->n_team;
-    ga.row_idx = static_cast<const int32_t*>(g->d_row_idx.p);
+    ga.items = static_cast<const WorkItem*>(hybrid ? g->hyb.items.p : g->d_items.p);
+    ga.n_items = hybrid ? g->hyb.n_items : g->n_items;
+    ga.n_team = hybrid ? g->hyb.n_team : g->n_team;
+    ga.row_idx = static_cast<const int32_t*>(hybrid ? g->hyb.rem_row_idx.p : g->d_row_idx.p);
+    const int64_t n_slots = hybrid ? g->hyb.n_slots : g->n_slots;
+    const int64_t n_heavy = hybrid ? g->hyb.n_heavy : g->n_heavy;
+    const HeavyVertex* heavy = static_cast<const HeavyVertex*>(hybrid ? g->hyb.heavy.p : g->d_heavy.p);
     ga.F = Fm;
     ga.agg = agg;
     ga.op = pool ? (int32_t)SAGA_EDGE_COPY : ep->op;
@@ -1049,9 +1428,66 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
             ga.ld_out16 = F;
         }
     }
-    if (g->n_slots > 0) {
-        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)g->n_slots * ga.F)) return st;
+    if (n_slots > 0) {
+        if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)n_slots * ga.F)) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
+    }
+    bool dense_forked = false;
+    if (hybrid) {
+        HybridDevice& h = g->hyb;
+        // The edge data in the two orders the kernels read them: block by block as two-part bf16, and in the remainder's
+        // edge order. Attached data are packed once; data passed with the call are packed every call; COPY packs ones.
+        const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
+        const float* w_src = !weighted ? nullptr : (ep->edge_weight ? ep->edge_weight : static_cast<const float*>(g->d_edge_data.p));
+        const int want_state = !weighted ? 2 : (ep->edge_weight ? 0 : 1);
+        if (want_state == 0 || h.weights_state != want_state) {
+            PackArgs pa{};
+            pa.w = w_src;
+            pa.de_edge = static_cast<const int32_t*>(h.de_edge.p);
+            pa.n_list = h.n_list_edges;
+            pa.de_w = static_cast<uint32_t*>(h.de_w.p);
+            pa.dt_edge = static_cast<const int32_t*>(h.dt_edge.p);
+            pa.dt_addr = static_cast<const int32_t*>(h.dt_addr.p);
+            pa.n_tile = h.n_tile_edges;
+            pa.de_tiles = static_cast<uint16_t*>(h.de_tiles.p);
+            pa.rem_edge = static_cast<const int32_t*>(h.rem_edge.p);
+            pa.n_rem = weighted ? h.n_rem_edges : 0;
+            pa.rem_w = static_cast<float*>(h.rem_w.p);
+            HIP_TRY(ctx, launch_pack_hybrid_weights(pa, s));
+            h.weights_state = want_state;
+        }
+        if (weighted) ga.edge_w = static_cast<const float*>(h.rem_w.p);
+        DenseArgs da{};
+        da.chunks = static_cast<const DenseChunk*>(h.chunks.p);
+        da.n_chunks = h.n_chunks;
+        da.blk_src_tile = static_cast<const int32_t*>(h.blk_src_tile.p);
+        da.blk_e0 = static_cast<const int32_t*>(h.blk_e0.p);
+        da.blk_tile = static_cast<const int32_t*>(h.blk_tile.p);
+        da.de_tiles = static_cast<const uint16_t*>(h.de_tiles.p);
+        da.de_pos = static_cast<const uint16_t*>(h.de_pos.p);
+        da.de_w = static_cast<const uint32_t*>(h.de_w.p);
+        da.src_tile_ids = static_cast<const int32_t*>(h.src_tile_ids.p);
+        da.tile_row_slot0 = static_cast<const int32_t*>(h.tile_row_slot0.p);
+        da.X = static_cast<const uint16_t*>(ga.src);
+        da.ld = ga.ld_src;
+        da.F = ga.F;
+        da.use_low = weighted ? 1 : 0;
+        da.partials = ga.partials;
+        if (ctx->opt_dense_overlap && !ctx->arena_active) {
+            if (!ctx->s_dense) {
+                HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->s_dense, hipStreamNonBlocking));
+                HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+                HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
+            }
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, s));
+            HIP_TRY(ctx, hipStreamWaitEvent(ctx->s_dense, ctx->ev_fork, 0));
+            HIP_TRY(ctx, launch_dense_blocks(da, ctx->s_dense));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->s_dense));
+            dense_forked = true;
+        } else {
+            HIP_TRY(ctx, launch_dense_blocks(da, s));
+        }
+        if (es) es->n_gather_launches = 2;
     }
     if (!ctx->opt_fused) {
         // the baseline of Section 6.2: the stages one by one through a materialised per-edge tensor, which the fused
@@ -1075,12 +1511,13 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         ga.mma = 0;
     }
     HIP_TRY(ctx, launch_gather(ga, s));
+    if (dense_forked) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->ev_join, 0));
     if (es) HIP_TRY(ctx, hipEventRecord(es->ev[2], s));
 
-    if (g->n_heavy > 0) {
+    if (n_heavy > 0) {
         CombineArgs ca{};
-        ca.heavy = static_cast<const HeavyVertex*>(g->d_heavy.p);
-        ca.n_heavy = g->n_heavy;
+        ca.heavy = heavy;
+        ca.n_heavy = n_heavy;
         ca.partials = ga.partials;
         ca.F = ga.F;
         ca.agg = agg;
@@ -1107,8 +1544,8 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         HIP_TRY(ctx, hipEventRecord(es->ev[4], s));
         ctx->ev_used += 1;
     }
-    ctx->acc.n_work_items = g->n_items;
-    ctx->acc.n_split_vertices = g->n_heavy;
+    ctx->acc.n_work_items = hybrid ? g->hyb.n_items : g->n_items;
+    ctx->acc.n_split_vertices = n_heavy;
     ctx->acc.plan_dst_intervals = ctx->acc.plan_src_intervals = 0;
     return SAGA_OK;
 }

@@ -4,14 +4,45 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
 #include <functional>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/saga.h"
+
+// fn(i) for i in [0, n) on up to max_threads threads. fn must not throw. If a thread cannot be started the threads that
+// did start (or the caller alone) do all the work: nothing is thrown from here.
+template <typename Fn>
+inline void parallel_for(int64_t n, int max_threads, Fn fn)
+{
+    const int nt = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, max_threads), std::thread::hardware_concurrency()));
+    if (nt <= 1) {
+        for (int64_t i = 0; i < n; ++i) fn(i);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    auto work = [&] {
+        for (;;) {
+            const int64_t i = next.fetch_add(1);
+            if (i >= n) break;
+            fn(i);
+        }
+    };
+    std::vector<std::thread> th;
+    try {
+        th.reserve((size_t)nt);
+        for (int t = 1; t < nt; ++t) th.emplace_back(work);
+    } catch (...) {
+        // out of threads or memory: carry on with what there is
+    }
+    work();
+    for (auto& t : th) t.join();
+}
 
 // ---------------------------------------------------------------------------
 // work list: the unit a wavefront of the propagation kernel processes
@@ -51,10 +82,62 @@ struct WorkListParams {
 };
 // Build the work list of a CSC block whose arrays are on the host
 // (col_ptr[0] = 0; vertex ids and edge offsets are local to the block).
+// extra_slots (nullable, one per column): partial rows that another kernel writes for the column ahead of
+// its own pieces (the dense blocks below). Such a column is always combined from partial rows: slots
+// [slot0, slot0 + extra) are reserved for the other kernel, its pieces (all of them, even a single one) follow.
 struct saga_ctx;
 WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes);
 void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
-                     WorkList* out);
+                     WorkList* out, const int32_t* extra_slots = nullptr);
+
+// ---------------------------------------------------------------------------
+// dense blocks: the part of the adjacency matrix that is a dense contraction
+// ---------------------------------------------------------------------------
+// Destinations ranked by in-degree and sources ranked by out-degree, grouped 64 and 32 at a time, cut the
+// adjacency matrix into 64 x 32 blocks. In a power-law graph the blocks of heavy destinations and heavy
+// sources are well filled: there the sum over in-edges is a dense product A_block (64 x 32 edge weights)
+// times X_block (32 source rows), which the matrix cores do at a cost that does not depend on how many of
+// the 2,048 cells hold an edge, and every source row is read once for 64 destinations instead of once per
+// edge. Blocks with at least min_block_edges edges go that way (in destination tiles where that pays for
+// the partial rows it costs); all other edges stay with the sparse propagation kernel as a remainder CSC.
+constexpr int kDenseM = 64, kDenseK = 32;
+struct HybridParams {
+    // A block costs the matrix cores the same whatever its fill (64 MFMAs per wavefront: about a microsecond of one compute
+    // unit with two-part weights), an edge whose source row hits in the L2 costs the sparse kernel about 0.02 ns of the whole
+    // chip: measured on the R-MAT 18 workload the layer is fastest with blocks from about 256 edges (an eighth full) on;
+    // 56, 100 and 160 were 8 %, 7 % and 8 % slower, 400 the same.
+    int64_t min_block_edges = 256;
+    int64_t min_tile_gain = 512;    // edges beyond min_block_edges, summed over a destination tile's blocks, that pay for its partial rows
+    int32_t max_chunk_blocks = 128; // blocks of one destination tile worked by one workgroup (one partial row per destination each)
+};
+// A block's weights reach the kernel in one of two forms: as a list of (cell, weight) pairs that the workgroup scatters
+// into a cleared LDS operand (blocks of up to kDenseListMax edges: one pair per thread), or, for fuller blocks, as the
+// finished 64 x 32 operand itself (two bf16 parts, 8 KiB), which is copied into LDS as it is.
+constexpr int kDenseListMax = 256;
+constexpr int kDenseTileElems = 2 * kDenseM * kDenseK;  // bf16 values of a finished operand: high parts, then low parts
+struct DenseChunk {
+    int32_t tile;   // destination tile
+    int32_t b0, b1; // its blocks [b0, b1)
+    int32_t cidx;   // which of the tile's chunks this is: the partial row written for a destination is slot0 + cidx
+};
+struct HybridPlan {
+    int64_t n_dst_tiles = 0, n_src_tiles = 0, n_dense_edges = 0;
+    std::vector<int32_t> dst_order;      // n_dst_tiles * 64: the vertex at each destination rank (-1: none)
+    std::vector<int32_t> src_tile_ids;   // n_src_tiles * 32: the vertex at each source rank (0 where there is none: a valid row, never weighted)
+    std::vector<int32_t> blk_src_tile;   // per block
+    std::vector<int32_t> blk_e0;         // per block + 1: its edges in de_pos / de_edge (none for a block kept as a finished operand)
+    std::vector<int32_t> blk_tile;       // per block: which finished operand is its own, or -1 for a block kept as a list
+    int64_t n_tiles = 0;                 // finished operands
+    std::vector<uint16_t> de_pos;        // list blocks: where the edge's weight sits in the block's 64 x 32 operand (matrix-core lane order)
+    std::vector<int32_t> de_edge;        // the edge's number in the caller's edge order
+    std::vector<int32_t> dt_addr;        // edges of finished operands: operand * kDenseTileElems + cell (the high part; the low part is kDenseM * kDenseK further)
+    std::vector<int32_t> dt_edge;
+    std::vector<DenseChunk> chunks;
+    std::vector<int32_t> extra_slots;    // per vertex: chunks of its destination tile (0: the tile has no dense blocks)
+    std::vector<int64_t> rem_col_ptr;    // the remainder as a CSC of its own (sources ascending inside a column)
+    std::vector<int32_t> rem_row_idx, rem_edge;
+};
+void build_hybrid_plan(const int64_t* col_ptr, const int32_t* row_idx, int64_t n, const HybridParams& hp, HybridPlan* out);
 
 // ---------------------------------------------------------------------------
 // device buffers with accounting
@@ -87,6 +170,8 @@ struct saga_ctx {
     int64_t opt_bwd_tile_rows = 0;  // streamed backward: rows per tile of backward-ApplyVertex (0 = about 64 MiB)
     int opt_transform_first = 0;  // resident linear sum layers with F_out < F_in: Y = act(gather(X W) + bias)
     int opt_fused = 1;            // 0: resident linear layers run Scatter, ApplyEdge and Gather as separate stages (baseline)
+    int opt_dense_blocks = 1;     // bf16 sum layers over COPY / MUL_WEIGHT edges: well-filled blocks of the adjacency matrix on the matrix cores
+    int64_t opt_dense_min_edges = 0, opt_dense_tile_gain = -1, opt_dense_chunk = 0;  // 0 / -1: the defaults of HybridParams
 
     // reusable workspace (grown on demand, never shrunk until destroy)
     DevBuf ws_accum;     // Gather output A (fp32 or bf16) when the caller gives no accum_out
@@ -121,6 +206,12 @@ struct saga_ctx {
     } st;
     saga_status ensure_stream_set();
     void destroy_stream_set();
+    // a second compute stream for the dense-block kernel, which runs beside the sparse propagation kernel (the two are
+    // bound by different things: the matrix cores and memory latency, and the traffic below the L2), with the events that
+    // fork it from and join it to the context's stream; made at the first call that needs it
+    hipStream_t s_dense = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int opt_dense_overlap = 0;  // measured: no gain, the two kernels fill the chip one after the other
     DevBuf ws_wt;        // streamed backward: W transposed, the "ApplyVertex" matrix of the backward propagation
     DevBuf ws_prod;      // streamed gated / pooled layers: packed weights of the per-vertex products (VertexProducts)
     DevBuf ws_edge_msg;  // stage-by-stage baseline: the per-edge tensor (n_edges x F fp32) and the edge numbers behind it
@@ -154,6 +245,19 @@ struct saga_ctx {
 
 struct ChunkGrid;  // streamed representation (chunked.hip)
 
+// The dense-block form of a resident graph on the device (built at the first call that can use it).
+struct HybridDevice {
+    bool built = false, usable = false;   // usable: the graph has dense blocks worth taking
+    WorkListParams list_params{-1, -1, -1, false, 1};
+    HybridParams hp;
+    int64_t n_chunks = 0, n_blocks = 0, n_dense_edges = 0, n_rem_edges = 0;
+    DevBuf chunks, blk_src_tile, blk_e0, blk_tile, de_pos, de_edge, de_w, dt_addr, dt_edge, de_tiles, src_tile_ids, tile_row_slot0;
+    int64_t n_list_edges = 0, n_tile_edges = 0, n_tiles = 0;
+    DevBuf rem_row_idx, rem_edge, rem_w, items, heavy;
+    int64_t n_items = 0, n_team = 0, n_heavy = 0, n_slots = 0;
+    int weights_state = 0;                // 0: de_w / rem_w not packed; 1: packed from the attached edge data; 2: packed as all ones (COPY)
+};
+
 struct saga_graph {
     saga_ctx* ctx = nullptr;
     int64_t n = 0, nnz = 0;
@@ -178,6 +282,7 @@ struct saga_graph {
     // the same edges grouped by source (backward-Scatter gathers over out-edges): built at the
     // first backward call. tr's columns are this graph's sources; perm[e'] is the position in
     // this graph's edge order of the transposed graph's edge e'.
+    HybridDevice hyb;
     saga_graph* tr = nullptr;
     DevBuf d_perm;
     bool tr_edge_data_valid = false;  // tr->d_edge_data holds d_edge_data permuted
@@ -258,6 +363,43 @@ struct CombineArgs {
     int32_t act;
 };
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+
+// The dense blocks of a bf16 sum layer on the matrix cores (hybrid.hip): one workgroup per chunk of blocks of one
+// destination tile; each of its four wavefronts owns 128 of the features; partial rows go to `partials`.
+struct DenseArgs {
+    const DenseChunk* chunks;
+    int64_t n_chunks;
+    const int32_t* blk_src_tile;
+    const int32_t* blk_e0;
+    const int32_t* blk_tile;        // per block: index of its finished operand in de_tiles, or -1 (edge list)
+    const uint16_t* de_tiles;       // finished operands, kDenseTileElems bf16 values each (16-byte aligned)
+    const uint16_t* de_pos;
+    const uint32_t* de_w;           // per list edge: the weight as two bf16 parts, high | low << 16 (w = high + low to 2^-17)
+    const int32_t* src_tile_ids;
+    const int32_t* tile_row_slot0;  // 64 per destination tile: first partial row of that destination, -1 where the tile has no vertex
+    const uint16_t* X;              // bf16 rows
+    int64_t ld;
+    int32_t F;                      // a multiple of 128
+    int32_t use_low;                // 0: the low parts are all zero (COPY) and their products are skipped
+    float* partials;
+};
+hipError_t launch_dense_blocks(const DenseArgs& a, hipStream_t s);
+// de_w[i] = two-part bf16 of w[de_edge[i]], de_tiles[dt_addr[i]] (and kDenseM * kDenseK further) = the two parts of
+// w[dt_edge[i]], rem_w[i] = w[rem_edge[i]]; w NULL stands for all ones (and leaves rem_w alone)
+struct PackArgs {
+    const float* w;
+    const int32_t* de_edge;
+    int64_t n_list;
+    uint32_t* de_w;
+    const int32_t* dt_edge;
+    const int32_t* dt_addr;
+    int64_t n_tile;
+    uint16_t* de_tiles;
+    const int32_t* rem_edge;
+    int64_t n_rem;
+    float* rem_w;
+};
+hipError_t launch_pack_hybrid_weights(const PackArgs& a, hipStream_t s);
 
 // rows x cols fp32 fill / max-identity fix-up for streamed max-Gather
 hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t s);

@@ -114,6 +114,17 @@ class StubContext:
     def set_option(self, name, value):
         self._check(self.lib.saga_set_option(self._h, name.encode(), int(value)))
 
+    def set_profiling(self, on):
+        self._check(self.lib.saga_set_profiling(self._h, 1 if on else 0))
+
+    def reset_timings(self):
+        self._check(self.lib.saga_reset_timings(self._h))
+
+    def get_timings(self):
+        t = B.Timings()
+        self._check(self.lib.saga_get_timings(self._h, ctypes.byref(t)))
+        return t.as_dict()
+
     def peak_device_bytes(self):
         return int(self.lib.saga_peak_device_bytes(self._h))
 

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "saga_internal.h"
 
@@ -196,6 +197,92 @@ hipError_t launch_combine(const CombineArgs& a, hipStream_t s)
     if (a.n_heavy <= 0) return hipSuccess;
     const CombineArgs copy = a;
     stub_enqueue(s, [copy] { combine_cpu(copy); });
+    return hipSuccess;
+}
+
+// The dense blocks: the 64 x 32 operand of every block is rebuilt from its compact edge list exactly as the kernel does
+// (same cell order, same two-part bf16 weights), then multiplied out with plain loops.
+hipError_t launch_dense_blocks(const DenseArgs& a, hipStream_t s)
+{
+    if (a.n_chunks <= 0) return hipSuccess;
+    if (a.F <= 0 || a.F % 128 != 0 || a.ld % 8 != 0) return hipErrorInvalidValue;
+    const DenseArgs d = a;
+    stub_enqueue(s, [d] {
+        std::vector<float> A((size_t)kDenseM * kDenseK);
+        std::vector<double> acc((size_t)kDenseM * d.F);
+        for (int64_t c = 0; c < d.n_chunks; ++c) {
+            const DenseChunk ch = d.chunks[c];
+            std::fill(acc.begin(), acc.end(), 0.0);
+            for (int b = ch.b0; b < ch.b1; ++b) {
+                std::fill(A.begin(), A.end(), 0.f);
+                // undo the lane order: cell = ((sub-tile * 64 + lane) * 8 + k % 8), lane = (k / 8) * 16 + m % 16
+                auto cell_to_mk = [](int pos, int* m, int* k) {
+                    const int j = pos & 7, lane = (pos >> 3) & 63, mt = pos >> 9;
+                    *m = mt * 16 + (lane & 15);
+                    *k = (lane >> 4) * 8 + j;
+                };
+                if (d.blk_tile[b] >= 0) {
+                    if (d.blk_e0[b] != d.blk_e0[b + 1]) die("a block kept as a finished operand has an edge list too");
+                    const uint16_t* t = d.de_tiles + (int64_t)d.blk_tile[b] * kDenseTileElems;
+                    for (int pos = 0; pos < kDenseM * kDenseK; ++pos) {
+                        int m, k;
+                        cell_to_mk(pos, &m, &k);
+                        A[(size_t)m * kDenseK + k] = bf16_to_f32(t[pos]) + (d.use_low ? bf16_to_f32(t[pos + kDenseM * kDenseK]) : 0.f);
+                    }
+                } else {
+                    if (d.blk_e0[b + 1] - d.blk_e0[b] > kDenseListMax || d.blk_e0[b + 1] <= d.blk_e0[b]) die("edge list of a block out of range");
+                    for (int e = d.blk_e0[b]; e < d.blk_e0[b + 1]; ++e) {
+                        const int pos = d.de_pos[e];
+                        if (pos < 0 || pos >= kDenseM * kDenseK) die("dense edge outside its block");
+                        int m, k;
+                        cell_to_mk(pos, &m, &k);
+                        if (A[(size_t)m * kDenseK + k] != 0.f) die("two dense edges in one cell");
+                        const uint32_t w = d.de_w[e];
+                        A[(size_t)m * kDenseK + k] = bf16_to_f32((uint16_t)(w & 0xffffu)) + (d.use_low ? bf16_to_f32((uint16_t)(w >> 16)) : 0.f);
+                    }
+                }
+                const int32_t* ids = d.src_tile_ids + (int64_t)d.blk_src_tile[b] * kDenseK;
+                for (int m = 0; m < kDenseM; ++m)
+                    for (int k = 0; k < kDenseK; ++k) {
+                        const float wmk = A[(size_t)m * kDenseK + k];
+                        if (wmk == 0.f) continue;
+                        for (int f = 0; f < d.F; ++f) acc[(size_t)m * d.F + f] += (double)wmk * bf16_to_f32(d.X[(int64_t)ids[k] * d.ld + f]);
+                    }
+                for (int k = 0; k < kDenseK; ++k) (void)d.X[(int64_t)ids[k] * d.ld];  // every row of the block is read, weighted or not
+            }
+            for (int m = 0; m < kDenseM; ++m) {
+                const int slot0 = d.tile_row_slot0[(int64_t)ch.tile * kDenseM + m];
+                if (slot0 < 0) continue;
+                for (int f = 0; f < d.F; ++f) d.partials[(int64_t)(slot0 + ch.cidx) * d.F + f] = (float)acc[(size_t)m * d.F + f];
+            }
+        }
+    });
+    return hipSuccess;
+}
+
+hipError_t launch_pack_hybrid_weights(const PackArgs& in, hipStream_t s)
+{
+    PackArgs a = in;
+    if (!a.w) a.n_rem = 0;
+    if (a.n_list + a.n_tile + a.n_rem <= 0) return hipSuccess;
+    stub_enqueue(s, [a] {
+        auto split = [&](float x, uint16_t* hi, uint16_t* lo) {
+            *hi = f32_to_bf16(x);
+            *lo = f32_to_bf16(x - bf16_to_f32(*hi));
+        };
+        for (int64_t i = 0; i < a.n_list; ++i) {
+            uint16_t hi, lo;
+            split(a.w ? a.w[a.de_edge[i]] : 1.0f, &hi, &lo);
+            a.de_w[i] = (uint32_t)hi | ((uint32_t)lo << 16);
+        }
+        for (int64_t i = 0; i < a.n_tile; ++i) {
+            uint16_t hi, lo;
+            split(a.w ? a.w[a.dt_edge[i]] : 1.0f, &hi, &lo);
+            a.de_tiles[a.dt_addr[i]] = hi;
+            a.de_tiles[a.dt_addr[i] + kDenseM * kDenseK] = lo;
+        }
+        for (int64_t i = 0; i < a.n_rem; ++i) a.rem_w[i] = a.w[a.rem_edge[i]];
+    });
     return hipSuccess;
 }
 

@@ -51,3 +51,9 @@ def test_failed_allocations_come_back_as_errors(stub_lib):
 
 def test_no_alloc_entry_point_reaches_no_allocator(stub_lib):
     _run("run_no_alloc.py", stub_lib)
+
+
+def test_dense_block_plan_and_schedule(stub_lib):
+    """The dense-block form of a resident graph (ranks, 64 x 32 blocks as edge lists or finished operands, chunks, the
+    partial-row slots shared with the sparse remainder's work list, weight packing) against the oracle."""
+    _run("run_hybrid.py", stub_lib)
