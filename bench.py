@@ -36,18 +36,31 @@ def algorithmic_gather_bytes(nnz, n, f_in, elem_bytes, weighted, gated, n_items)
     return nnz * per_edge + n * per_vertex + n_items * 16
 
 
-def measured_traffic(workload_key, nnz, work_items, agg):
-    """HBM-side bytes per gather launch from the committed rocprofv3 counter summary, if it was
-    taken on this very workload and work list (else None: counters cannot be read from here)."""
+def source_stamp():
+    """Hash of the sources that decide what the propagation kernels read and write: a counter summary taken before
+    any of them changed is stale."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("gather.hip", "hybrid.hip", "saga_api.hip", "saga_internal.h"):
+        with open(os.path.join(ROOT, "paper_1810_08403_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_key, nnz, work_items, dense_edges, agg):
+    """Bytes that crossed below the L2 per launch of the dominant kernel, from the committed rocprofv3 counter summary,
+    if it was taken on this very workload, work list and source version (else None, with the reason)."""
     path = os.path.join(ROOT, "profiles", f"{workload_key}_traffic.json")
     try:
         with open(path) as f:
             d = json.load(f)
     except (OSError, ValueError):
-        return None
-    if d.get("nnz") == nnz and d.get("work_items") == work_items and d.get("agg") == agg:
-        return int(d["traffic_bytes_per_launch"])
-    return None
+        return None, "no counter summary for this workload under profiles/"
+    if d.get("source_stamp") != source_stamp():
+        return None, "the counter summary under profiles/ was taken on other sources"
+    if d.get("nnz") != nnz or d.get("work_items") != work_items or d.get("dense_edges", 0) != dense_edges or d.get("agg") != agg:
+        return None, "the counter summary under profiles/ was taken on another work list"
+    return d, None
 
 
 def main():
@@ -213,14 +226,38 @@ def main():
         assert torch.equal(a[:1024], b[:1024]) and torch.equal(a[-1024:], b[-1024:])
         del a, b
 
-    ms_gather = tm["ms_gather"] / max(tm["n_calls"], 1)
+    calls = max(tm["n_calls"], 1)
+    ms_gather = tm["ms_gather"] / calls            # the whole propagation stage
+    ms_dense = tm["ms_dense_blocks"] / calls       # ... of which the dense-block kernel (0 when the path is not taken)
+    ms_sparse = ms_gather - ms_dense               # ... and the sparse propagation kernel, the dominant launch
+    n_dense_edges, n_dense_blocks = tm["n_dense_edges"], tm["n_dense_blocks"]
     if (args.transform_first and has_w and wl.W_self is None and args.agg == "sum" and wl.edge_op in ("copy", "mul_weight")
             and f_out < f_in):
         f_msg = f_out          # the propagation moves rows of X W
-    alg_bytes = algorithmic_gather_bytes(nnz, n, f_msg, es, wl.edge_op == "mul_weight", wl.edge_op == "gated",
-                                         info["n_work_items"])
-    achieved = alg_bytes / (ms_gather * 1e-3) / 1e9 if ms_gather > 0 else 0.0
-    compulsory = n * f_msg * es + nnz * (8 if wl.edge_op == "mul_weight" else 4) + info["n_work_items"] * 16 + n * f_msg * es
+    weighted, gated = wl.edge_op == "mul_weight", wl.edge_op == "gated"
+    n_items, n_split = tm["n_work_items"], tm["n_split_vertices"]
+    # the sparse kernel's launch: its edges (id, weight, source row), its work items, and one row per item: a finished row
+    # for a column that is not combined from partial rows, an fp32 partial row otherwise
+    e_sparse = nnz - n_dense_edges
+    if n_dense_edges:
+        whole_items = n - n_split
+        alg_bytes = (algorithmic_gather_bytes(e_sparse, 0, f_msg, es, weighted, gated, n_items) + whole_items * f_msg * es +
+                     max(n_items - whole_items, 0) * f_msg * 4)
+    else:
+        alg_bytes = algorithmic_gather_bytes(nnz, n, f_msg, es, weighted, gated, n_items)
+    effective = alg_bytes / (ms_sparse * 1e-3) / 1e9 if ms_sparse > 0 else 0.0
+    compulsory = n * f_msg * es + nnz * (8 if weighted else 4) + n_items * 16 + n * f_msg * es
+    tr, why = measured_traffic(f"spmm_d{args.density:g}" if args.workload == "spmm" else args.workload, nnz, n_items, n_dense_edges, args.agg)
+    if tr is not None and ms_sparse > 0:
+        # bytes that crossed below the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) per launch
+        # of the dominant kernel, over its launch time measured here: no counter of this chip sits below the Infinity
+        # Cache, so this is an upper bound of the HBM rate, and the fraction an upper bound of the HBM fraction
+        achieved = tr["traffic_bytes_per_launch"] / (ms_sparse * 1e-3) / 1e9
+        basis = "counters: bytes below the L2 per launch (HBM or Infinity Cache)"
+    else:
+        # without a valid counter summary: every array once, over the time of the whole propagation stage (a lower bound)
+        achieved = compulsory / (ms_gather * 1e-3) / 1e9 if ms_gather > 0 else 0.0
+        basis = "compulsory bytes (each array once): " + str(why)
     out = {
         "metric": "fused_saga_layer_throughput", "value": round(gteps, 4), "unit": "GTEPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -228,27 +265,37 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "n_vertices": n, "nnz": nnz, "f_in": f_in, "f_out": f_out,
                    "edge_op": wl.edge_op, "agg": args.agg, "act": wl.act, "max_in_degree": info["max_in_degree"],
-                   "work_items": info["n_work_items"], "split_vertices": info["n_split_vertices"],
+                   "work_items": n_items, "split_vertices": n_split, "dense_blocks": n_dense_blocks, "dense_edges": n_dense_edges,
+                   "partial_rows": tm["n_partial_rows"],
                    "hip_graph": bool(args.hip_graph), "transform_first": int(args.transform_first or 0), "fused": not args.unfused},
-        "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "fused Scatter-ApplyEdge-Gather, sparse kernel (k_gather_*)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(f"spmm_d{args.density:g}" if args.workload == "spmm" else args.workload, nnz, info["n_work_items"], args.agg),
+                     "achieved_basis": basis,
+                     "traffic": int(tr["traffic_bytes_per_launch"]) if tr is not None else None,
                      "algorithmic_bytes_per_launch": alg_bytes,
-                     "compulsory_bytes_per_launch": compulsory,
+                     "effective_GBps": round(effective, 1),
+                     "compulsory_bytes_per_layer": compulsory,
                      "compulsory_frac": round(compulsory / (ms_gather * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if ms_gather > 0 else None,
-                     "ms_per_launch": round(ms_gather, 4)},
-        "stages_ms": {"hoist": round(tm["ms_hoist"] / max(tm["n_calls"], 1), 4), "gather": round(ms_gather, 4),
-                      "combine": round(tm["ms_combine"] / max(tm["n_calls"], 1), 4),
-                      "apply_vertex": round(tm["ms_apply_vertex"] / max(tm["n_calls"], 1), 4),
-                      "events_total": round(tm["ms_total"] / max(tm["n_calls"], 1), 4)},
+                     "ms_per_launch": round(ms_sparse, 4), "edges_per_launch": e_sparse},
+        "stages_ms": {"hoist": round(tm["ms_hoist"] / calls, 4), "gather": round(ms_gather, 4), "dense_blocks": round(ms_dense, 4),
+                      "combine": round(tm["ms_combine"] / calls, 4),
+                      "apply_vertex": round(tm["ms_apply_vertex"] / calls, 4),
+                      "events_total": round(tm["ms_total"] / calls, 4)},
         "gather_gflops": round(2.0 * nnz * f_in / (ms_gather * 1e-3) / 1e9, 1) if ms_gather > 0 else None,
         "setup_s": {"generate": round(t_gen, 2), "ingest": round(t_ingest, 3), "first_call": round(t_first, 3)},
     }
-    if out["roofline"]["traffic"] and ms_gather > 0:
-        # the measured bytes below the L2 per launch over the launch time measured here: the "achieved HBM GB/s vs peak" figure
-        tr_gbps = out["roofline"]["traffic"] / (ms_gather * 1e-3) / 1e9
-        out["roofline"]["traffic_GBps"] = round(tr_gbps, 1)
-        out["roofline"]["traffic_frac"] = round(tr_gbps / HBM_PEAK_GBPS, 4)
+    if tr is not None:
+        out["roofline"]["l2_hit_rate"] = tr.get("l2_hit_rate")
+    if n_dense_blocks and ms_dense > 0:
+        # the dense-block kernel against the matrix cores: what it executes (every cell of every block, two weight parts
+        # when the edges are weighted) and the part of that which is edges
+        parts = 2 if weighted else 1
+        executed = 2.0 * n_dense_blocks * 64 * 32 * f_msg * parts
+        useful = 2.0 * n_dense_edges * f_msg
+        out["dense_blocks"] = {"bound": "mfma", "kernel": "k_dense_blocks", "achieved": round(executed / (ms_dense * 1e-3) / 1e12, 1),
+                               "peak": 2500.0, "unit": "TFLOP/s", "frac": round(executed / (ms_dense * 1e-3) / 1e12 / 2500.0, 4),
+                               "useful_TFLOPs": round(useful / (ms_dense * 1e-3) / 1e12, 1), "ms": round(ms_dense, 4),
+                               "blocks": n_dense_blocks, "edges": n_dense_edges, "weight_parts": parts}
     copy_gbps = device_copy_ceiling(ctx, torch)
     out["roofline"]["measured_copy_ceiling"] = {"GBps": round(copy_gbps, 1), "frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4),
                                                 "kernel": "k_copy_u128, 1 GiB read + 1 GiB written"}

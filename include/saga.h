@@ -126,6 +126,9 @@ typedef struct saga_timings {
     int32_t plan_dst_intervals, plan_src_intervals; /* last streamed plan (0 = resident) */
     int32_t reserved;
     int64_t n_work_items, n_split_vertices; /* of the last graph used */
+    double ms_dense_blocks;  /* the part of ms_gather spent in the dense-block kernel (option "dense_blocks") */
+    int64_t n_dense_blocks, n_dense_edges; /* of the last layer that used the dense-block path, else 0 */
+    int64_t n_partial_rows;  /* partial rows (of the row width, fp32) the last layer wrote and combined */
 } saga_timings;
 
 /*

@@ -159,6 +159,7 @@ struct saga_ctx {
 
     // tunables
     int64_t opt_split = 64;        // minimum edges per piece of a cut column
+    bool opt_split_set = false;    // the caller has chosen it (the dense-block path otherwise cuts its remainder finer)
     int64_t opt_cut_degree = 0;    // 0 = 2 * split
     int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
     int opt_xcd_remap = 1;
@@ -221,7 +222,8 @@ struct saga_ctx {
     bool profiling = false;
     struct EventSet {
         hipEvent_t ev[5];
-        bool has_hoist, has_combine, has_apply;
+        hipEvent_t ev_dense;  // after the dense-block kernel, before the sparse one (same stream)
+        bool has_hoist, has_combine, has_apply, has_dense;
         int n_gather_launches;
     };
     std::vector<EventSet> ev_pool;
