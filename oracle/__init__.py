@@ -97,6 +97,8 @@ def lib():
         L.saga_oracle_gated_backward.argtypes = [ctypes.POINTER(_GBwdArgs)]
         L.saga_oracle_gated_backward_sample.restype = ctypes.c_int
         L.saga_oracle_gated_backward_sample.argtypes = [ctypes.POINTER(_GBwdArgs), _I64, _P, _P, _P]
+        L.saga_oracle_max_backward_sample.restype = ctypes.c_int
+        L.saga_oracle_max_backward_sample.argtypes = [ctypes.POINTER(_MBwdArgs), _I64, _P, _P, _P]
         L.saga_oracle_backward_sample.restype = ctypes.c_int
         L.saga_oracle_backward_sample.argtypes = [ctypes.POINTER(_BwdArgs), _I64, _P, _P, _P, _I64, _P, _P, _P, _P]
         _lib = L
@@ -362,4 +364,32 @@ def max_backward(col_ptr, row_idx, X, dY, W, edge_op="copy", edge_weight=None, W
     rc = lib().saga_oracle_max_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_max_backward rejected its arguments")
+    return out
+
+
+def max_backward_sample(col_ptr, row_idx, X, dY, W, ulist, edge_op="copy", edge_weight=None, W_pool=None, b_pool=None, bias=None,
+                        act="none", W_self=None):
+    """max_backward's definitions evaluated only for the rows dX[ulist] (distinct source vertices), from those vertices'
+    out-edges and the whole columns of the destinations they reach, for graphs too large to do whole. Returns dict dX,
+    dX_abs (len(ulist) x F)."""
+    col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
+    row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
+    Xv, Wv, dYv = _f32(X), _f32(W), _f32(dY)
+    n, F = Xv.shape
+    Wp, bp, w, bv, Ws = _f32(W_pool), _f32(b_pool), _f32(edge_weight), _f32(bias), _f32(W_self)
+    Fp = Wp.shape[0] if edge_op == "pool" else 0
+    Fm = Fp if edge_op == "pool" else F
+    F_out = Wv.shape[1]
+    assert Wv.shape == (Fm, F_out) and dYv.shape == (n, F_out)
+    assert Ws is None or Ws.shape == (F, F_out)
+    assert edge_op != "pool" or Wp.shape == (Fp, F)
+    ul = np.ascontiguousarray(np.asarray(ulist, dtype=np.int64))
+    assert len(set(ul.tolist())) == len(ul)
+    out = {"dX": np.zeros((len(ul), F)), "dX_abs": np.zeros((len(ul), F))}
+    a = _MBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, EDGE_OPS[edge_op], ACTS[act], _ptr(w), _ptr(Wp), _ptr(bp), Fp,
+                  _ptr(Wv), _ptr(bv), F_out, _ptr(dYv), None, None, None, None, None, None, None, None, None, None,
+                  _ptr(Ws), None, None, None)
+    rc = lib().saga_oracle_max_backward_sample(ctypes.byref(a), len(ul), _ptr(ul), _ptr(out["dX"]), _ptr(out["dX_abs"]))
+    if rc != 0:
+        raise ValueError("saga_oracle_max_backward_sample rejected its arguments")
     return out

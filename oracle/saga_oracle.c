@@ -26,7 +26,8 @@
  *     Section 2.2) as the chain rule of the forward definitions: linear layers
  *     (whole graph and sampled), the gated layer (whole graph, and sampled
  *     rows of the input gradient), the max accumulator with
- *     COPY / MUL_WEIGHT / max-pooling messages (further down in this file).
+ *     COPY / MUL_WEIGHT / max-pooling messages (whole graph, and sampled rows
+ *     of the input gradient; further down in this file).
  *
  * Every function is pinned by tests/test_oracle_pins.py against something
  * other than itself (dense matrix forms, finite differences of the forward
@@ -1249,5 +1250,180 @@ int saga_oracle_max_backward(const saga_oracle_mbwd_args* p)
         p->db_pool_abs[c] = bsa;
     }
     free(buf);
+    return 0;
+}
+
+/*
+ * saga_oracle_max_backward's definitions evaluated only for the rows dX[ulist] (n_u distinct source
+ * vertices), for graphs too large to do whole. A row dX[u] needs: the messages of u's out-edges; for
+ * every destination v of such an edge the maximum A[v] over all of v's in-edges (the whole column is
+ * walked), the pre-activation of v and from it dZ[v] and dA[v] = dZ[v] W^T; for POOL the pooled row of
+ * every source (one product per vertex, all of them) and the sigmoid's slope at u; with W_self the
+ * vertex's own partial gradient dZ[u] W_self^T, which needs A[u] as well. Every quantity is formed by the
+ * same expressions, in the same order inside a row, as in the whole-graph function; nothing is shared
+ * with it but act_backward and sigmoid. Outputs dX_rows, dX_rows_abs: n_u x F.
+ */
+int saga_oracle_max_backward_sample(const saga_oracle_mbwd_args* p, int64_t n_u, const int64_t* ulist, double* dX_rows,
+                                    double* dX_rows_abs)
+{
+    if (!p || !p->col_ptr || !p->X || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (n_u < 0 || (n_u > 0 && (!ulist || !dX_rows || !dX_rows_abs))) return 1;
+    const int op = p->edge_op;
+    if (op != EDGE_COPY && op != EDGE_MUL_WEIGHT && op != EDGE_POOL) return 1;
+    if (op == EDGE_MUL_WEIGHT && !p->edge_w) return 1;
+    if (op == EDGE_POOL && (!p->W_pool || p->F_pool <= 0)) return 1;
+    if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
+    const int64_t n = p->n, F = p->F, Fo = p->F_out, Fm = op == EDGE_POOL ? p->F_pool : F;
+    if (n_u == 0) return 0;
+
+    /* which sample a vertex is, and which destinations the rows depend on */
+    int64_t* sample_of = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+    int64_t* slot_of = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+    if (!sample_of || !slot_of) { free(sample_of); free(slot_of); return 2; }
+    for (int64_t v = 0; v < n; ++v) sample_of[v] = slot_of[v] = -1;
+    for (int64_t i = 0; i < n_u; ++i) {
+        if (ulist[i] < 0 || ulist[i] >= n || sample_of[ulist[i]] >= 0) { free(sample_of); free(slot_of); return 1; }
+        sample_of[ulist[i]] = i;
+    }
+    int64_t n_t = 0; /* destinations whose A, dZ and dA are needed */
+    for (int64_t v = 0; v < n; ++v) {
+        int need = p->W_self && sample_of[v] >= 0;
+        for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1] && !need; ++e) need = sample_of[p->row_idx[e]] >= 0;
+        if (need) slot_of[v] = n_t++;
+    }
+    int64_t* tlist = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n_t > 0 ? n_t : 1));
+    const size_t tm = (size_t)(n_t > 0 ? n_t : 1) * (size_t)Fm, tz = (size_t)(n_t > 0 ? n_t : 1) * (size_t)Fo;
+    const size_t um = (size_t)n_u * (size_t)Fm;
+    double* T = (double*)calloc(3 * tm + 2 * tz + 2 * um, sizeof(double));
+    double *H = NULL, *Hz = NULL;
+    if (op == EDGE_POOL) {
+        H = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)Fm);
+        Hz = (double*)malloc(sizeof(double) * um);
+    }
+    if (!tlist || !T || (op == EDGE_POOL && (!H || !Hz))) {
+        free(sample_of); free(slot_of); free(tlist); free(T); free(H); free(Hz);
+        return 2;
+    }
+    double *A = T, *dA = A + tm, *dAa = dA + tm, *dZ = dAa + tm, *dZa = dZ + tz, *dS = dZa + tz, *dSa = dS + um;
+    for (int64_t v = 0; v < n; ++v)
+        if (slot_of[v] >= 0) tlist[slot_of[v]] = v;
+
+    /* POOL: the pooled row of every vertex (any of them may supply a maximum); the absolute-term sum of the
+     * sigmoid's argument only where the slope is taken, at the sampled vertices */
+    if (op == EDGE_POOL) {
+#pragma omp parallel for schedule(static)
+        for (int64_t u = 0; u < n; ++u)
+            for (int64_t c = 0; c < Fm; ++c) {
+                double z = p->b_pool ? (double)p->b_pool[c] : 0.0, za = fabs(z);
+                for (int64_t k = 0; k < F; ++k) {
+                    const double t = (double)p->W_pool[c * F + k] * (double)p->X[u * F + k];
+                    z += t;
+                    za += fabs(t);
+                }
+                H[u * Fm + c] = sigmoid(z);
+                if (sample_of[u] >= 0) Hz[sample_of[u] * Fm + c] = za;
+            }
+    }
+
+    /* Gather and backward-ApplyVertex at the destinations that matter */
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t t = 0; t < n_t; ++t) {
+        const int64_t v = tlist[t];
+        for (int64_t c = 0; c < Fm; ++c) {
+            double best = 0.0;
+            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                const int64_t u = p->row_idx[e];
+                double m;
+                if (op == EDGE_POOL) m = H[u * Fm + c];
+                else if (op == EDGE_MUL_WEIGHT) { const float pr = p->edge_w[e] * p->X[u * F + c]; m = (double)pr; }
+                else m = (double)p->X[u * F + c];
+                if (e == p->col_ptr[v] || m > best) best = m;
+            }
+            A[t * Fm + c] = best;
+        }
+        for (int64_t o = 0; o < Fo; ++o) {
+            double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);
+            for (int64_t c = 0; c < Fm; ++c) {
+                const double tt = A[t * Fm + c] * (double)p->W[c * Fo + o];
+                z += tt;
+                za += fabs(tt);
+            }
+            if (p->W_self)
+                for (int64_t k = 0; k < F; ++k) {
+                    const double tt = (double)p->X[v * F + k] * (double)p->W_self[k * Fo + o];
+                    z += tt;
+                    za += fabs(tt);
+                }
+            act_backward(p->act, z, za, (double)p->dY[v * Fo + o], &dZ[t * Fo + o], &dZa[t * Fo + o]);
+        }
+        for (int64_t c = 0; c < Fm; ++c) {
+            double s = 0.0, sa = 0.0;
+            for (int64_t o = 0; o < Fo; ++o) {
+                s += dZ[t * Fo + o] * (double)p->W[c * Fo + o];
+                sa += dZa[t * Fo + o] * fabs((double)p->W[c * Fo + o]);
+            }
+            dA[t * Fm + c] = s;
+            dAa[t * Fm + c] = sa;
+        }
+    }
+
+    /* backward-Gather, the edge factor and backward-Scatter for the sampled sources: one feature per
+     * iteration, destinations and their edges in stored order */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t c = 0; c < Fm; ++c)
+        for (int64_t t = 0; t < n_t; ++t) {
+            const int64_t v = tlist[t];
+            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                const int64_t u = p->row_idx[e], i = sample_of[u];
+                if (i < 0) continue;
+                double m, w = 1.0;
+                if (op == EDGE_POOL) m = H[u * Fm + c];
+                else if (op == EDGE_MUL_WEIGHT) { const float pr = p->edge_w[e] * p->X[u * F + c]; m = (double)pr; w = (double)p->edge_w[e]; }
+                else m = (double)p->X[u * F + c];
+                if (m == A[t * Fm + c]) {
+                    dS[i * Fm + c] += w * dA[t * Fm + c];
+                    dSa[i * Fm + c] += fabs(w) * dAa[t * Fm + c];
+                }
+            }
+        }
+
+    for (int64_t i = 0; i < n_u; ++i) {
+        const int64_t u = ulist[i];
+        if (op == EDGE_POOL) {
+            /* through the sigmoid, then the per-vertex product */
+            for (int64_t c = 0; c < Fm; ++c) {
+                const double h = H[u * Fm + c], d1 = h * (1.0 - h);
+                dSa[i * Fm + c] = dSa[i * Fm + c] * d1 + fabs(dS[i * Fm + c]) * d1 * fabs(1.0 - 2.0 * h) * Hz[i * Fm + c];
+                dS[i * Fm + c] = dS[i * Fm + c] * d1;
+            }
+            for (int64_t k = 0; k < F; ++k) {
+                double s = 0.0, sa = 0.0;
+                for (int64_t c = 0; c < Fm; ++c) {
+                    s += dS[i * Fm + c] * (double)p->W_pool[c * F + k];
+                    sa += dSa[i * Fm + c] * fabs((double)p->W_pool[c * F + k]);
+                }
+                dX_rows[i * F + k] = s;
+                dX_rows_abs[i * F + k] = sa;
+            }
+        } else {
+            for (int64_t k = 0; k < F; ++k) {
+                dX_rows[i * F + k] = dS[i * F + k];
+                dX_rows_abs[i * F + k] = dSa[i * F + k];
+            }
+        }
+        if (p->W_self) {
+            const int64_t t = slot_of[u];
+            for (int64_t k = 0; k < F; ++k) {
+                double s = 0.0, sa = 0.0;
+                for (int64_t o = 0; o < Fo; ++o) {
+                    s += dZ[t * Fo + o] * (double)p->W_self[k * Fo + o];
+                    sa += dZa[t * Fo + o] * fabs((double)p->W_self[k * Fo + o]);
+                }
+                dX_rows[i * F + k] += s;
+                dX_rows_abs[i * F + k] += sa;
+            }
+        }
+    }
+    free(sample_of); free(slot_of); free(tlist); free(T); free(H); free(Hz);
     return 0;
 }

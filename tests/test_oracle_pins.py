@@ -718,6 +718,59 @@ def test_max_backward_equals_autograd_of_the_dense_form(edge_op, act, with_self)
         assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name
 
 
+@pytest.mark.parametrize("edge_op", ["copy", "mul_weight", "pool"])
+@pytest.mark.parametrize("act,with_self", [("none", False), ("relu", False), ("sigmoid", True), ("relu", True)])
+def test_sampled_max_backward_equals_the_whole_graph_form_and_autograd(edge_op, act, with_self):
+    """Rows of dX from the sampled form: the same numbers as the whole-graph form (itself pinned to autograd above), and
+    directly the gradient autograd gives for those rows of the dense formulation."""
+    import torch
+    g, X, w, Wp, bp, b, rng = _max_bwd_setup(seed=8, n=60, m=400)
+    n, F = X.shape
+    Fm = Wp.shape[0] if edge_op == "pool" else F
+    W = rng.standard_normal((Fm, 3)).astype(np.float32)
+    dY = rng.standard_normal((n, 3)).astype(np.float32)
+    Ws = rng.standard_normal((F, 3)).astype(np.float32) if with_self else None
+    kw = dict(edge_weight=w) if edge_op == "mul_weight" else (dict(W_pool=Wp, b_pool=bp) if edge_op == "pool" else {})
+    whole = oracle.max_backward(*_np(g), X, dY, W, edge_op, bias=b, act=act, W_self=Ws, **kw)
+    od = np.bincount(g.row_idx.numpy(), minlength=n)
+    deg = np.diff(g.col_ptr.numpy())
+    ul = sorted({0, n - 1, 13, 41, int(od.argmax()), int(od.argmin()), int(deg.argmax()), int(deg.argmin())})
+    part = oracle.max_backward_sample(*_np(g), X, dY, W, ul, edge_op, bias=b, act=act, W_self=Ws, **kw)
+    assert np.allclose(part["dX"], whole["dX"][ul], rtol=1e-12, atol=1e-13)
+    assert np.allclose(part["dX_abs"], whole["dX_abs"][ul], rtol=1e-12, atol=1e-13)
+    assert np.abs(whole["dX"][ul]).max() > 0.05
+    t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
+    Xt = t(X)
+    Adj = torch.tensor(_dense_adj(g)) > 0
+    if edge_op == "pool":
+        S = torch.sigmoid(Xt @ torch.tensor(Wp, dtype=torch.float64).T + torch.tensor(bp, dtype=torch.float64))[None, :, :].expand(n, n, Fm)
+    elif edge_op == "mul_weight":
+        S = torch.tensor(_dense_adj(g, w))[:, :, None] * Xt[None, :, :]
+    else:
+        S = Xt[None, :, :].expand(n, n, F)
+    masked = torch.where(Adj[:, :, None], S, torch.tensor(-np.inf, dtype=torch.float64))
+    A = torch.where(Adj.any(1)[:, None], masked.amax(1), torch.zeros(n, Fm, dtype=torch.float64))
+    Z = A @ torch.tensor(W, dtype=torch.float64) + torch.tensor(b, dtype=torch.float64)
+    if with_self:
+        Z = Z + Xt @ torch.tensor(Ws, dtype=torch.float64)
+    Y = torch.relu(Z) if act == "relu" else (torch.sigmoid(Z) if act == "sigmoid" else Z)
+    (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
+    tol = dict(rtol=1e-6, atol=1e-7) if edge_op == "mul_weight" else dict(rtol=1e-10, atol=1e-11)
+    assert np.allclose(part["dX"], Xt.grad.numpy()[ul], **tol)
+
+
+def test_sampled_max_backward_on_ties_and_rejected_arguments():
+    g = si.csc_from_lists(3, [(0, 2), (1, 2)])
+    X = np.array([[2.0, 1.0], [2.0, 5.0], [0.0, 0.0]], np.float32)
+    W = np.eye(2, dtype=np.float32)
+    dY = np.array([[0, 0], [0, 0], [3.0, 7.0]], np.float32)
+    part = oracle.max_backward_sample(*_np(g), X, dY, W, [1, 0, 2], "copy")
+    assert np.array_equal(part["dX"], [[3, 7], [3, 0], [0, 0]])            # rows in the order asked for; the tie gives both 3
+    assert oracle.max_backward_sample(*_np(g), X, dY, W, [], "copy")["dX"].shape == (0, 2)
+    with pytest.raises(ValueError):
+        oracle.max_backward_sample(*_np(g), X, dY, W, [3], "copy")
+
+
 def test_max_backward_sends_the_whole_gradient_to_every_tied_source():
     # vertex 2 has in-edges from 0 and 1 with equal features in column 0 and distinct ones in column 1
     g = si.csc_from_lists(3, [(0, 2), (1, 2)])
