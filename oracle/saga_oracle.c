@@ -1329,17 +1329,16 @@ int saga_oracle_max_backward_sample(const saga_oracle_mbwd_args* p, int64_t n_u,
 #pragma omp parallel for schedule(dynamic, 4)
     for (int64_t t = 0; t < n_t; ++t) {
         const int64_t v = tlist[t];
-        for (int64_t c = 0; c < Fm; ++c) {
-            double best = 0.0;
-            for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
-                const int64_t u = p->row_idx[e];
+        /* the running maximum of every feature sits in A's row (zero-filled: the value without in-edges) */
+        for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+            const int64_t u = p->row_idx[e];
+            for (int64_t c = 0; c < Fm; ++c) {
                 double m;
                 if (op == EDGE_POOL) m = H[u * Fm + c];
                 else if (op == EDGE_MUL_WEIGHT) { const float pr = p->edge_w[e] * p->X[u * F + c]; m = (double)pr; }
                 else m = (double)p->X[u * F + c];
-                if (e == p->col_ptr[v] || m > best) best = m;
+                if (e == p->col_ptr[v] || m > A[t * Fm + c]) A[t * Fm + c] = m;
             }
-            A[t * Fm + c] = best;
         }
         for (int64_t o = 0; o < Fo; ++o) {
             double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);

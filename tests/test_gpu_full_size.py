@@ -23,6 +23,34 @@ def _sample(g, count, seed):
     return np.array(sorted(picks), dtype=np.int64)
 
 
+def _source_sample(g, count, seed):
+    """Random source vertices plus the one with most out-edges, the one with most in-edges, one without out-edges, the
+    first and the last."""
+    n = g.n
+    od = torch.bincount(g.row_idx.long(), minlength=n).cpu().numpy()
+    ind = g.in_degree().cpu().numpy()
+    rng = np.random.default_rng(seed)
+    picks = set(rng.choice(n, size=count, replace=False).tolist()) | {int(od.argmax()), int(ind.argmax()), 0, n - 1}
+    picks.add(int(np.nonzero(od == 0)[0][0]))
+    assert od.max() > 10_000
+    return np.array(sorted(picks), dtype=np.int64)
+
+
+def _mpgcn_rmat20_exact_preactivations(device):
+    """The max-pooling workload bench.py times (R-MAT 20, 128 -> pool 128 -> 128) with X, W_pool and b_pool on coarse grids
+    (multiples of 1/4, 1/8, 1/8): every pooled pre-activation is then a multiple of 1/32 below 9 in magnitude, exact in
+    fp32 in any order of summation, and two different ones give sigmoids 3.8e-6 apart or more, so that the fp32 sigmoids
+    on the GPU and the fp64 ones in the oracle rank the messages alike, ties included (the maximum is a decision, and
+    both sides have to take it on the same values)."""
+    wl = si.mpgcn_workload(scale=20, edge_factor=32, f_in=128, f_pool=128, f_out=128, device=device)
+    wl.X = torch.round(wl.X.clamp(-1, 1) * 4) / 4
+    wl.W_pool = torch.round((wl.W_pool * 8).clamp(-1, 1)) / 8
+    wl.b_pool = torch.round(wl.b_pool.clamp(-0.5, 0.5) * 8) / 8
+    z = wl.X.double() @ wl.W_pool.double().T + wl.b_pool.double()
+    assert z.abs().max().item() <= 9.0 and z.std().item() > 0.5
+    return wl
+
+
 def _oracle_rows(wl, vl, agg, W=None, act=None, X=None, with_vertex=True):
     g = wl.graph
     kw = dict(edge_op=wl.edge_op, agg=agg, vlist=vl)
@@ -253,13 +281,15 @@ def test_commnet_rmat20_forward_and_backward():
     ctx.destroy()
 
 
-def test_mpgcn_rmat20_forward_and_backward_properties():
-    """The max-pooling GCN layer bench.py times (R-MAT 20, 128 -> pool 128 -> 128, max): sampled rows from the oracle
-    (max over sigmoids: the Gather output to the fp32 bar, because the sigmoid is evaluated in fp32), and for the
-    backward pass at this size what holds at any size: the same bits with and without dX, exact doubling, and no
-    gradient for a vertex without out-edges."""
+def test_mpgcn_rmat20_forward_and_backward():
+    """The max-pooling GCN layer bench.py times (R-MAT 20, 128 -> pool 128 -> 128, max), with pre-activations exact in fp32:
+    sampled rows of the forward pass from the oracle; backwards, sampled rows of dX from the oracle's sampled form (which
+    recomputes the maxima of every destination those sources reach), dW and dbias against the same sums in fp64, and
+    for dW_pool and db_pool, sums over a million vertices the oracle cannot do in seconds, what holds at any size: the
+    same bits with and without dX, exact doubling. The stored output handed to the backward pass is synthetic (only its
+    sign is used, for ReLU's derivative), so that the oracle can be given the same mask."""
     import paper_1810_08403_amd as saga
-    wl = si.mpgcn_workload(scale=20, edge_factor=32, f_in=128, f_pool=128, f_out=128, device="cuda")
+    wl = _mpgcn_rmat20_exact_preactivations("cuda")
     g = wl.graph
     n = g.n
     cp, ri = g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy()
@@ -275,10 +305,11 @@ def test_mpgcn_rmat20_forward_and_backward_properties():
     assert_sum_close(A[vl].cpu().numpy(), r["A"], r["A_abs"], TOL_F32, "MP-GCN R-MAT 20 Gather")
     assert_sum_close(Y[vl].cpu().numpy(), r["Y"], r["Y_abs"], TOL_F32, "MP-GCN R-MAT 20 layer")
     dY = si.normal_features(n, 128, 78, device="cuda")
+    Y_in = si.normal_features(n, 128, 79, device="cuda")
     z = lambda *s: torch.full(s, float("nan"), device="cuda")
     def run(dy, want_dx=True):
         out = dict(dW=z(128, 128), dX=z(n, 128) if want_dx else None, dW_pool=z(128, 128), db_pool=z(128), dbias=z(128))
-        ctx.layer_backward(graph, A, dy, wl.W, out["dW"], X=wl.X, Y=Y, dX=out["dX"], dW_pool=out["dW_pool"], db_pool=out["db_pool"],
+        ctx.layer_backward(graph, A, dy, wl.W, out["dW"], X=wl.X, Y=Y_in, dX=out["dX"], dW_pool=out["dW_pool"], db_pool=out["db_pool"],
                            dbias=out["dbias"], **kw)
         torch.cuda.synchronize()
         return out
@@ -288,8 +319,14 @@ def test_mpgcn_rmat20_forward_and_backward_properties():
         assert torch.equal(r1[name], r2[name]), name
         assert torch.equal(r3[name], r1[name] * 2.0), name
     assert torch.equal(r3["dX"], r1["dX"] * 2.0)
+    dZ = dY * (Y_in > 0)
+    ul = _source_sample(g, 60, 12)
+    ref = oracle.max_backward_sample(cp, ri, wl.X.cpu().numpy(), dZ.cpu().numpy(), wl.W.cpu().numpy(), ul, "pool",
+                                     W_pool=wl.W_pool.cpu().numpy(), b_pool=wl.b_pool.cpu().numpy(), act="none")
+    assert np.abs(ref["dX"]).max() > 1.0
+    assert_sum_close(r1["dX"][ul].cpu().numpy(), ref["dX"], np.maximum(ref["dX_abs"], 1e-30), TOL_F32, "MP-GCN R-MAT 20, sampled rows of dX")
     # dW = A^T dZ and dbias against the same sums in fp64 on the device
-    dz64 = (dY * (Y > 0)).double()
+    dz64 = dZ.double()
     assert_sum_close(r1["dW"].cpu().numpy(), (A.double().T @ dz64).cpu().numpy(), (A.double().abs().T @ dz64.abs()).cpu().numpy(), TOL_F32,
                      "MP-GCN R-MAT 20 dW")
     assert_sum_close(r1["dbias"].cpu().numpy(), dz64.sum(0).cpu().numpy(), dz64.abs().sum(0).cpu().numpy(), TOL_F32, "MP-GCN R-MAT 20 dbias")
@@ -337,9 +374,12 @@ def test_streamed_applications_under_one_gib_at_full_size(app):
     ctx.destroy()
 
 
-def test_config4_streamed_gated_backward_under_two_gib_equals_the_resident_one():
-    """Configuration 4's gated layer backwards from host memory through a 2 GiB device budget, against the device-resident
-    backward pass of the same layer (itself checked against the oracle's sampled rows above)."""
+def test_config4_streamed_gated_backward_under_two_gib():
+    """Configuration 4's gated layer backwards from host memory through a 2 GiB device budget: sampled rows of dX against
+    the oracle's sampled form, element by element at the fp32 bar; the parameter gradients (sums over all million
+    vertices) against the device-resident backward pass of the same layer, whose sampled rows the oracle checks above.
+    The stored output handed to both passes is synthetic (only its sign is used, for ReLU's derivative), so that the
+    oracle is given the same mask."""
     import paper_1810_08403_amd as saga
     wl = si.workload(4, device="cuda")
     g = wl.graph
@@ -352,15 +392,17 @@ def test_config4_streamed_gated_backward_under_two_gib_equals_the_resident_one()
     Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
     ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
     dY = si.normal_features(n, 128, 31).cuda()
+    Y_in = si.normal_features(n, 128, 32).cuda()
     ref = dict(dW=z(F, 128), dbias=z(128), dW_gate=z(F, 2 * F), db_gate=z(F), dW_msg=z(F, F), dX=z(n, F))
-    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y, dX=ref["dX"], dbias=ref["dbias"], dW_gate=ref["dW_gate"],
+    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y_in, dX=ref["dX"], dbias=ref["dbias"], dW_gate=ref["dW_gate"],
                        db_gate=ref["db_gate"], dW_msg=ref["dW_msg"], **kw)
     torch.cuda.synchronize()
-    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y, dY=dY).items()}
+    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y_in, dY=dY).items()}
     ref = {k: v.cpu() for k, v in ref.items()}
+    ul = _source_sample(g, 60, 12)
     graph.destroy()
     ctx.destroy()
-    del Y, A, dY
+    del Y, A, dY, Y_in
     torch.cuda.empty_cache()
     budget = 2 << 30
     ctx = saga.Context(0, hbm_budget_bytes=budget)
@@ -372,6 +414,11 @@ def test_config4_streamed_gated_backward_under_two_gib_equals_the_resident_one()
                        dbias=got["dbias"], dW_gate=got["dW_gate"], db_gate=got["db_gate"], dW_msg=got["dW_msg"], **kw)
     torch.cuda.synchronize()
     assert ctx.peak_device_bytes() <= budget
+    dZ = (host["dY"] * (host["Y"] > 0)).numpy()
+    smp = oracle.gated_backward_sample(g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), host["X"].numpy(), dZ, wl.W.cpu().numpy(),
+                                       wl.W_gate.cpu().numpy(), ul, b_gate=wl.b_gate.cpu().numpy(), W_msg=wl.W_msg.cpu().numpy())
+    assert_sum_close(dX_h[ul].numpy(), smp["dX"], np.maximum(smp["dX_abs"], 1e-30), TOL_F32, "configuration 4 streamed under 2 GiB, sampled rows of dX")
+    assert_sum_close(ref["dX"][ul].numpy(), smp["dX"], np.maximum(smp["dX_abs"], 1e-30), TOL_F32, "configuration 4 resident with ReLU, sampled rows of dX")
     for name in names:   # the same sums in another grouping: close in the norm of each tensor
         err = (got[name].cpu().double() - ref[name].double()).abs().max().item()
         assert err <= 1e-4 * ref[name].abs().max().item(), (name, err)
@@ -383,12 +430,14 @@ def test_config4_streamed_gated_backward_under_two_gib_equals_the_resident_one()
     ctx.destroy()
 
 
-def test_mpgcn_rmat20_streamed_backward_under_two_gib_equals_the_resident_one():
-    """The max-pooling layer's backward pass from host memory through a 2 GiB device budget at R-MAT 20, against the
-    device-resident backward pass of the same layer (whose maxima decisions it must reproduce: both recompute the pooled
-    rows with the same kernels), and the peak stays under the budget."""
+def test_mpgcn_rmat20_streamed_backward_under_two_gib():
+    """The max-pooling layer's backward pass from host memory through a 2 GiB device budget at R-MAT 20 (pre-activations
+    exact in fp32, synthetic stored output for ReLU's mask): sampled rows of dX against the oracle's sampled form, element
+    by element at the fp32 bar; dW and dbias against the same sums in fp64; dW_pool and db_pool against the
+    device-resident backward pass; a vertex gets a gradient exactly where the resident pass gives it one; and the peak
+    stays under the budget."""
     import paper_1810_08403_amd as saga
-    wl = si.mpgcn_workload(scale=20, edge_factor=32, f_in=128, f_pool=128, f_out=128, device="cuda")
+    wl = _mpgcn_rmat20_exact_preactivations("cuda")
     g = wl.graph
     n = g.n
     kw = dict(edge_op="pool", agg="max", W_pool=wl.W_pool, b_pool=wl.b_pool, act="relu")
@@ -398,15 +447,17 @@ def test_mpgcn_rmat20_streamed_backward_under_two_gib_equals_the_resident_one():
     Y, A = torch.empty(n, 128, device="cuda"), torch.empty(n, 128, device="cuda")
     ctx.layer_forward(graph, wl.X, Y, W=wl.W, accum_out=A, **kw)
     dY = si.normal_features(n, 128, 78, device="cuda")
+    Y_in = si.normal_features(n, 128, 79, device="cuda")
     ref = dict(dW=z(128, 128), dX=z(n, 128), dW_pool=z(128, 128), db_pool=z(128), dbias=z(128))
-    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y, dX=ref["dX"], dW_pool=ref["dW_pool"], db_pool=ref["db_pool"],
+    ctx.layer_backward(graph, A, dY, wl.W, ref["dW"], X=wl.X, Y=Y_in, dX=ref["dX"], dW_pool=ref["dW_pool"], db_pool=ref["db_pool"],
                        dbias=ref["dbias"], **kw)
     torch.cuda.synchronize()
-    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y, dY=dY).items()}
+    host = {k: v.cpu() for k, v in dict(X=wl.X, A=A, Y=Y_in, dY=dY).items()}
     ref = {k: v.cpu() for k, v in ref.items()}
+    ul = _source_sample(g, 60, 12)
     graph.destroy()
     ctx.destroy()
-    del Y, A, dY
+    del Y, A, dY, Y_in
     torch.cuda.empty_cache()
     budget = 2 << 30
     ctx = saga.Context(0, hbm_budget_bytes=budget)
@@ -418,6 +469,14 @@ def test_mpgcn_rmat20_streamed_backward_under_two_gib_equals_the_resident_one():
                        dW_pool=got["dW_pool"], db_pool=got["db_pool"], dbias=got["dbias"], **kw)
     torch.cuda.synchronize()
     assert ctx.peak_device_bytes() <= budget
+    dZ = host["dY"] * (host["Y"] > 0)
+    smp = oracle.max_backward_sample(g.col_ptr.cpu().numpy(), g.row_idx.cpu().numpy(), host["X"].numpy(), dZ.numpy(), wl.W.cpu().numpy(), ul,
+                                     "pool", W_pool=wl.W_pool.cpu().numpy(), b_pool=wl.b_pool.cpu().numpy(), act="none")
+    assert np.abs(smp["dX"]).max() > 1.0
+    assert_sum_close(dX_h[ul].numpy(), smp["dX"], np.maximum(smp["dX_abs"], 1e-30), TOL_F32, "MP-GCN streamed under 2 GiB, sampled rows of dX")
+    dz64, A64 = dZ.double(), host["A"].double()
+    assert_sum_close(got["dW"].cpu().numpy(), (A64.T @ dz64).numpy(), (A64.abs().T @ dz64.abs()).numpy(), TOL_F32, "MP-GCN streamed dW")
+    assert_sum_close(got["dbias"].cpu().numpy(), dz64.sum(0).numpy(), dz64.abs().sum(0).numpy(), TOL_F32, "MP-GCN streamed dbias")
     # the same sums in another grouping: close in the norm of each tensor
     for name in ("dW", "dW_pool", "db_pool", "dbias"):
         err = (got[name].cpu().double() - ref[name].double()).abs().max().item()
