@@ -59,11 +59,11 @@ class _GBwdArgs(ctypes.Structure):
     """Mirror of saga_oracle_gbwd_args in saga_oracle.c."""
     _fields_ = [("n", _I64), ("col_ptr", _P), ("row_idx", _P), ("X", _P), ("F", _I64),
                 ("W_gate", _P), ("b_gate", _P), ("W_msg", _P), ("A", _P), ("W", _P), ("bias", _P),
-                ("F_out", _I64), ("act", _I32), ("pad_", _I32), ("dY", _P),
+                ("F_out", _I64), ("act", _I32), ("agg", _I32), ("dY", _P),
                 ("dX", _P), ("dX_abs", _P), ("dW", _P), ("dW_abs", _P), ("dbias", _P),
                 ("dW_gate", _P), ("dW_gate_abs", _P), ("db_gate", _P), ("db_gate_abs", _P),
                 ("dW_msg", _P), ("dW_msg_abs", _P),
-                ("W_self", _P), ("dW_self", _P), ("dW_self_abs", _P), ("dbias_abs", _P)]
+                ("W_self", _P), ("dW_self", _P), ("dW_self_abs", _P), ("dbias_abs", _P), ("A_max", _P)]
 
 
 class _MBwdArgs(ctypes.Structure):
@@ -281,19 +281,24 @@ def backward_sample(col_ptr, row_idx, X, A, dY, W, ulist, w_entries, edge_op="co
     return out
 
 
-def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=None, bias=None, act="none", W_self=None):
-    """Gradients of one gated layer with the sum accumulator (Example 2.1 / Figure 2, Section 2.2's backward stages).
+def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=None, bias=None, act="none", W_self=None, agg="sum"):
+    """Gradients of one gated layer (Example 2.1 / Figure 2, Section 2.2's backward stages).
 
-    A is the forward Gather output (fp64). Returns fp64 arrays dX, dW, dbias, dW_gate (F x 2F), db_gate, dW_msg
-    (with respect to an explicit identity when W_msg is None), dW_self when W_self is given, and their *_abs error
-    scales."""
+    agg "sum": A is the forward Gather output (fp64). agg "max": A is not read (pass None); the Gather output is
+    recomputed and returned as "A", and only the edges that supplied a maximum carry gradient. Returns fp64 arrays dX,
+    dW, dbias, dW_gate (F x 2F), db_gate, dW_msg (with respect to an explicit identity when W_msg is None), dW_self
+    when W_self is given, and their *_abs error scales."""
     col_ptr = np.ascontiguousarray(np.asarray(col_ptr, dtype=np.int64))
     row_idx = np.ascontiguousarray(np.asarray(row_idx, dtype=np.int32))
     Xv, Wv, dYv, Wg = _f32(X), _f32(W), _f32(dY), _f32(W_gate)
-    A = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
     n, F = Xv.shape
     F_out = Wv.shape[1]
-    assert A.shape == (n, F) and Wv.shape == (F, F_out) and dYv.shape == (n, F_out) and Wg.shape == (F, 2 * F)
+    if agg == "sum":
+        A = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
+        assert A.shape == (n, F)
+    else:
+        assert agg == "max" and A is None
+    assert Wv.shape == (F, F_out) and dYv.shape == (n, F_out) and Wg.shape == (F, 2 * F)
     bg, Wm, bv, Ws = _f32(b_gate), _f32(W_msg), _f32(bias), _f32(W_self)
     assert Wm is None or Wm.shape == (F, F)
     out = {"dX": np.empty((n, F)), "dX_abs": np.empty((n, F)), "dW": np.empty((F, F_out)), "dW_abs": np.empty((F, F_out)),
@@ -302,11 +307,13 @@ def gated_backward(col_ptr, row_idx, X, A, dY, W, W_gate, b_gate=None, W_msg=Non
     if Ws is not None:
         assert Ws.shape == (F, F_out)
         out.update(dW_self=np.empty((F, F_out)), dW_self_abs=np.empty((F, F_out)))
+    if agg == "max":
+        out["A"] = np.empty((n, F))
     a = _GBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, _ptr(Wg), _ptr(bg), _ptr(Wm), _ptr(A), _ptr(Wv), _ptr(bv),
-                  F_out, ACTS[act], 0, _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]), _ptr(out["dW_abs"]),
+                  F_out, ACTS[act], AGGS[agg], _ptr(dYv), _ptr(out["dX"]), _ptr(out["dX_abs"]), _ptr(out["dW"]), _ptr(out["dW_abs"]),
                   _ptr(out["dbias"]), _ptr(out["dW_gate"]), _ptr(out["dW_gate_abs"]), _ptr(out["db_gate"]),
                   _ptr(out["db_gate_abs"]), _ptr(out["dW_msg"]), _ptr(out["dW_msg_abs"]),
-                  _ptr(Ws), _ptr(out.get("dW_self")), _ptr(out.get("dW_self_abs")), _ptr(out["dbias_abs"]))
+                  _ptr(Ws), _ptr(out.get("dW_self")), _ptr(out.get("dW_self_abs")), _ptr(out["dbias_abs"]), _ptr(out.get("A")))
     rc = lib().saga_oracle_gated_backward(ctypes.byref(a))
     if rc != 0:
         raise ValueError("saga_oracle_gated_backward rejected its arguments")
@@ -327,7 +334,7 @@ def gated_backward_sample(col_ptr, row_idx, X, dZ, W, W_gate, ulist, b_gate=None
     assert len(set(ul.tolist())) == len(ul)
     out = {"dX": np.zeros((len(ul), F)), "dX_abs": np.zeros((len(ul), F))}
     a = _GBwdArgs(n, _ptr(col_ptr), _ptr(row_idx), _ptr(Xv), F, _ptr(Wg), _ptr(bg), _ptr(Wm), None, _ptr(Wv), None,
-                  F_out, ACTS["none"], 0, _ptr(dZv), *([None] * 11), None, None, None, None)
+                  F_out, ACTS["none"], AGGS["sum"], _ptr(dZv), *([None] * 11), None, None, None, None, None)
     rc = lib().saga_oracle_gated_backward_sample(ctypes.byref(a), len(ul), _ptr(ul), _ptr(out["dX"]), _ptr(out["dX_abs"]))
     if rc != 0:
         raise ValueError("saga_oracle_gated_backward_sample rejected its arguments")

@@ -684,6 +684,13 @@ int saga_oracle_backward_sample(const saga_oracle_bwd_args* p, int64_t n_u, cons
  * dW_msg is the gradient with respect to an explicit identity matrix.
  * Every *_abs output is the first-order error scale of its value: all sums with absolute
  * terms, and for each use of g the rounding of its argument propagated through g' = g (1 - g).
+ *
+ * Max accumulator (agg = AGG_MAX; A[v][f] = max of m_e[f] over in-edges, 0 without in-edges): the
+ * Gather output is recomputed here from the hoisted products (p->A is not read) so that
+ * backward-Gather can ask, per edge and feature, whether the message equals the maximum; an edge
+ * whose message does receives dm_e[f] = dA[v][f] whole (ties: every maximal edge, as for the other
+ * max layers), every other edge receives nothing for that feature. Everything else is unchanged.
+ * The recomputed Gather output is returned in A_max (n x F, nullable).
  */
 typedef struct saga_oracle_gbwd_args {
     int64_t n;
@@ -695,30 +702,52 @@ typedef struct saga_oracle_gbwd_args {
     const double* A;
     const float *W, *bias;
     int64_t F_out;
-    int32_t act, pad_;
+    int32_t act, agg;    /* agg: AGG_SUM, or AGG_MAX (see below) */
     const float* dY;
     double *dX, *dX_abs, *dW, *dW_abs, *dbias;
     double *dW_gate, *dW_gate_abs, *db_gate, *db_gate_abs, *dW_msg, *dW_msg_abs;
     const float* W_self;                        /* F x F_out, nullable: Z = A W + X W_self + bias */
     double *dW_self, *dW_self_abs, *dbias_abs;  /* nullable (dW_self with W_self only) */
+    double *A_max;                              /* n x F out, nullable (AGG_MAX only) */
 } saga_oracle_gbwd_args;
 
 int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
 {
-    if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->A || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
+    if (p->agg != AGG_SUM && p->agg != AGG_MAX) return 1;
+    if (p->agg == AGG_SUM && !p->A) return 1;
     if (p->act != ACT_NONE && p->act != ACT_RELU && p->act != ACT_SIGMOID) return 1;
     if (!p->dX || !p->dX_abs || !p->dW || !p->dW_abs || !p->dbias || !p->dW_gate || !p->dW_gate_abs || !p->db_gate ||
         !p->db_gate_abs || !p->dW_msg || !p->dW_msg_abs)
         return 1;
     if (p->dW_self && !p->W_self) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out;
+    const int is_max = p->agg == AGG_MAX;
     const size_t nf = (size_t)(n > 0 ? n : 1) * (size_t)F, nz = (size_t)(n > 0 ? n : 1) * (size_t)Fo;
-    double* buf = (double*)calloc(14 * nf + 2 * nz, sizeof(double));
+    double* buf = (double*)calloc(15 * nf + 2 * nz, sizeof(double));
     if (!buf) return 2;
     double *Ps = buf, *Pd = Ps + nf, *M = Pd + nf, *Psa = M + nf, *Pda = Psa + nf, *Ma = Pda + nf;
     double *dA = Ma + nf, *dAa = dA + nf, *dPs = dAa + nf, *dPd = dPs + nf, *dM = dPd + nf;
-    double *dPsa = dM + nf, *dPda = dPsa + nf, *dMa = dPda + nf, *dZ = dMa + nf, *dZa = dZ + nz;
+    double *dPsa = dM + nf, *dPda = dPsa + nf, *dMa = dPda + nf, *Amax = dMa + nf, *dZ = Amax + nf, *dZa = dZ + nz;
     if (saga_oracle_hoist(n, p->X, F, p->W_gate, p->W_msg, Ps, Pd, M, Psa, Pda, Ma)) { free(buf); return 1; }
+    const double* Ain = p->A;
+    if (is_max) {
+        /* Gather with the max accumulator, the message formed exactly as in backward-Gather below */
+#pragma omp parallel for schedule(dynamic, 16)
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t f = 0; f < F; ++f) {
+                const double b = p->b_gate ? (double)p->b_gate[f] : 0.0;
+                double best = 0.0;
+                for (int64_t e = p->col_ptr[v]; e < p->col_ptr[v + 1]; ++e) {
+                    const int64_t u = p->row_idx[e];
+                    const double m = sigmoid(Ps[u * F + f] + Pd[v * F + f] + b) * M[u * F + f];
+                    if (e == p->col_ptr[v] || m > best) best = m;
+                }
+                Amax[v * F + f] = best;
+            }
+        Ain = Amax;
+        if (p->A_max) memcpy(p->A_max, Amax, sizeof(double) * (size_t)n * (size_t)F);
+    }
 
     /* backward-ApplyVertex */
 #pragma omp parallel for schedule(static)
@@ -726,7 +755,7 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
         for (int64_t o = 0; o < Fo; ++o) {
             double z = p->bias ? (double)p->bias[o] : 0.0, za = fabs(z);
             for (int64_t f = 0; f < F; ++f) {
-                const double t = p->A[v * F + f] * (double)p->W[f * Fo + o];
+                const double t = Ain[v * F + f] * (double)p->W[f * Fo + o];
                 z += t;
                 za += fabs(t);
             }
@@ -756,7 +785,7 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
         for (int64_t f = 0; f < F; ++f) {
             for (int64_t o = 0; o < 4 * Fo; ++o) row[o] = 0.0;
             for (int64_t v = 0; v < n; ++v) {
-                const double a = p->A[v * F + f], x = (double)p->X[v * F + f];
+                const double a = Ain[v * F + f], x = (double)p->X[v * F + f];
                 for (int64_t o = 0; o < Fo; ++o) {
                     row[o] += a * dZ[v * Fo + o];
                     row[Fo + o] += fabs(a) * dZa[v * Fo + o];
@@ -796,6 +825,7 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
                     const double s = Ps[u * F + f] + Pd[v * F + f] + b;
                     const double Za = Psa[u * F + f] + Pda[v * F + f] + fabs(b);
                     const double g = sigmoid(s), t = M[u * F + f], Ta = Ma[u * F + f];
+                    if (is_max && g * t != Amax[v * F + f]) continue; /* this edge did not supply the maximum of feature f */
                     const double da = dA[v * F + f], daa = dAa[v * F + f];
                     dM[u * F + f] += g * da;
                     dMa[u * F + f] += g * (daa + fabs(da) * (1.0 - g) * Za);
@@ -877,14 +907,14 @@ int saga_oracle_gated_backward(const saga_oracle_gbwd_args* p)
  * The gated backward definitions evaluated only for the rows dX[ulist] (n_u distinct vertices), for graphs
  * too large to do whole. A sampled vertex u needs dPs[u], dM[u] (sums over its out-edges) and dPd[u] (a sum
  * over its in-edges), hence the per-vertex products of u and of its neighbours only; those are formed here
- * exactly as in the whole-graph form. No activation and no W_self: p->dY is taken as dZ (p->act must be
+ * exactly as in the whole-graph form. Sum accumulator, no activation and no W_self: p->dY is taken as dZ (p->act must be
  * ACT_NONE, p->A and the parameter-gradient outputs are not used). Outputs n_u x F.
  */
 int saga_oracle_gated_backward_sample(const saga_oracle_gbwd_args* p, int64_t n_u, const int64_t* ulist, double* dX_rows,
                                       double* dX_rows_abs)
 {
     if (!p || !p->col_ptr || !p->X || !p->W_gate || !p->W || !p->dY || p->F <= 0 || p->F_out <= 0 || p->n < 0) return 1;
-    if (p->act != ACT_NONE || p->W_self || n_u < 0 || (n_u > 0 && (!ulist || !dX_rows || !dX_rows_abs))) return 1;
+    if (p->act != ACT_NONE || p->agg != AGG_SUM || p->W_self || n_u < 0 || (n_u > 0 && (!ulist || !dX_rows || !dX_rows_abs))) return 1;
     const int64_t n = p->n, F = p->F, Fo = p->F_out, nnz = p->col_ptr[n];
     if (n_u == 0) return 0;
     /* the edges grouped by source */

@@ -619,6 +619,68 @@ def test_gated_backward_equals_autograd_of_the_dense_form(act, with_self, with_m
         assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name    # a scale bounds its value
 
 
+@pytest.mark.parametrize("act,with_self", [("none", False), ("relu", False), ("sigmoid", True), ("relu", True)])
+@pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
+def test_gated_max_backward_equals_autograd_of_the_dense_form(act, with_self, with_msg, with_b):
+    """Max over gated messages: the recomputed Gather output is the forward oracle's, and every gradient is what autograd
+    gives for the dense formulation (amax over a masked [v, u, f] tensor; no two messages of a column tie here)."""
+    import torch
+    g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(seed=4, n=40, m=90, with_msg=with_msg, with_b=with_b)
+    n, F = X.shape
+    deg = np.diff(g.col_ptr.numpy())
+    assert (deg == 0).any() and (deg > 3).any()
+    Ws = (np.round(np.random.default_rng(78).standard_normal(W.shape) * 32) / 32).astype(np.float32) if with_self else None
+    fwd = oracle.layer(*_np(g), X, "gated", agg="max", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act, W_self=Ws)
+    bwd = oracle.gated_backward(*_np(g), X, None, dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act, W_self=Ws, agg="max")
+    assert np.allclose(bwd["A"], fwd["A"], rtol=1e-12, atol=1e-13)
+    t = lambda a: torch.tensor(np.asarray(a, np.float64), requires_grad=True)
+    Xt, Wgt, Wt, bt = t(X), t(Wg), t(W), t(b)
+    Wst = t(Ws if with_self else np.zeros(W.shape))
+    bgt = t(bg if with_b else np.zeros(F))
+    Wmt = t(Wm if with_msg else np.eye(F))
+    Adj = torch.tensor(_dense_adj(g)) > 0                                 # [v, u]
+    Ps, Pd, M = Xt @ Wgt[:, :F].T, Xt @ Wgt[:, F:].T, Xt @ Wmt.T
+    msg = torch.sigmoid(Ps[None, :, :] + Pd[:, None, :] + bgt) * M[None, :, :]      # [v, u, f]
+    masked = torch.where(Adj[:, :, None], msg, torch.tensor(-np.inf, dtype=torch.float64))
+    A = torch.where(Adj.any(1)[:, None], masked.amax(1), torch.zeros(n, F, dtype=torch.float64))
+    Z = A @ Wt + Xt @ Wst + bt
+    Y = torch.relu(Z) if act == "relu" else (torch.sigmoid(Z) if act == "sigmoid" else Z)
+    assert np.allclose(Y.detach().numpy(), fwd["Y"], rtol=1e-12, atol=1e-12)
+    (Y * torch.tensor(dY.astype(np.float64))).sum().backward()
+    for name, ref in [("dX", Xt.grad), ("dW", Wt.grad), ("dbias", bt.grad), ("dW_gate", Wgt.grad), ("db_gate", bgt.grad),
+                      ("dW_msg", Wmt.grad)] + ([("dW_self", Wst.grad)] if with_self else []):
+        assert np.allclose(bwd[name], ref.numpy(), rtol=1e-10, atol=1e-11), name
+        assert np.abs(ref.numpy()).max() > 1e-3, name
+    for name in ["dX", "dW", "dW_gate", "db_gate", "dW_msg", "dbias"] + (["dW_self"] if with_self else []):
+        assert (bwd[name + "_abs"] >= np.abs(bwd[name]) * (1 - 1e-12)).all(), name
+    # it is not the sum layer's gradient: with more than one in-edge somewhere, most edges carry nothing
+    sum_fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, b_gate=bg, W_msg=Wm, W=W, bias=b, act=act, W_self=Ws)
+    sum_bwd = oracle.gated_backward(*_np(g), X, sum_fwd["A"], dY, W, Wg, b_gate=bg, W_msg=Wm, bias=b, act=act, W_self=Ws)
+    assert not np.allclose(sum_bwd["dW_gate"], bwd["dW_gate"], rtol=1e-3, atol=1e-6)
+
+
+def test_gated_max_backward_on_a_tie_and_on_a_single_edge():
+    # vertices 0 and 1 carry the same features: their messages to vertex 2 tie in every feature, both get the whole gradient;
+    # vertex 3 has the single in-edge 2 -> 3, where max and sum are the same layer
+    g = si.csc_from_lists(4, [(0, 2), (1, 2), (2, 3)])
+    X = np.array([[0.5, -1.0], [0.5, -1.0], [0.25, 2.0], [1.0, 1.0]], np.float32)
+    Wg = np.array([[0.5, 0.25, -0.5, 1.0], [1.0, -0.75, 0.25, 0.5]], np.float32)
+    W = np.array([[1.0, 0.5], [-0.5, 2.0]], np.float32)
+    dY = np.array([[0, 0], [0, 0], [3.0, 7.0], [-2.0, 0.5]], np.float32)
+    mx = oracle.gated_backward(*_np(g), X, None, dY, W, Wg, agg="max")
+    fwd = oracle.layer(*_np(g), X, "gated", W_gate=Wg, W=W)
+    sm = oracle.gated_backward(*_np(g), X, fwd["A"], dY, W, Wg)
+    assert np.allclose(mx["A"][3], fwd["A"][3], rtol=1e-14) and np.allclose(mx["A"][2], fwd["A"][2] / 2, rtol=1e-14)
+    assert np.array_equal(mx["dX"][0], mx["dX"][1]) and np.abs(mx["dX"][0]).max() > 0
+    # per edge the two layers send back the same thing when both edges of vertex 2 are maximal: the sum layer's dA[2] is
+    # dZ[2] W^T as well, so the rows of the two tied sources agree between the layers, and so does everything at vertex 3
+    assert np.allclose(mx["dX"][0], sm["dX"][0], rtol=1e-13, atol=1e-15)
+    assert np.allclose(mx["dW_gate"], sm["dW_gate"], rtol=1e-13, atol=1e-15)
+    assert np.allclose(mx["dW_msg"], sm["dW_msg"], rtol=1e-13, atol=1e-15)
+    # dW = A^T dZ differs: the max layer's A[2] is one message, the sum layer's two
+    assert not np.allclose(mx["dW"], sm["dW"])
+
+
 @pytest.mark.parametrize("with_msg,with_b", [(True, True), (False, False)])
 def test_sampled_gated_backward_equals_the_whole_graph_form(with_msg, with_b):
     g, X, Wg, bg, Wm, W, b, dY = _gated_bwd_setup(seed=6, n=70, m=600, F=5, Fo=4, with_msg=with_msg, with_b=with_b)
