@@ -236,9 +236,12 @@ typedef struct saga_layer_grads {
 /*
  * One layer backward (the backward stages of Section 2.2, run in reverse order of the
  * forward ones): fp32, ApplyVertex Y = act(A W + X W_self + bias) with act NONE, RELU or
- * SIGMOID, everything device-resident. Covered: sum accumulator with COPY, MUL_WEIGHT, GATED
- * or POOL messages; max accumulator with COPY, MUL_WEIGHT or POOL messages; each with or
- * without W_self. Max over GATED messages returns SAGA_ERR_UNSUPPORTED.
+ * SIGMOID, everything device-resident. Covered: sum and max accumulator, each with COPY,
+ * MUL_WEIGHT, GATED or POOL messages, each with or without W_self. Under the max accumulator
+ * an edge carries gradient for the features whose maximum it supplied (every maximal edge
+ * on a tie, the whole gradient each); the messages are recomputed by the forward pass's own
+ * expressions and compared with A bit for bit, so A must be that pass's accum_out. (From host
+ * memory, max over GATED messages returns SAGA_ERR_UNSUPPORTED.)
  *
  *   backward-ApplyVertex   dZ = dY (.) act'(Z), the derivative taken from the stored output
  *                          (ReLU: 1 where Y > 0; sigmoid: Y (1 - Y), whose error is that of

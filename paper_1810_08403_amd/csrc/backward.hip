@@ -117,7 +117,7 @@ static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs g
     ga.agg = SAGA_AGG_SUM;
     ga.xcd_remap = ctx->opt_xcd_remap;
     ga.mma = ctx->opt_mma;
-    const bool two = ga.op == kGatherOpGateBoth;
+    const bool two = ga.op == kGatherOpGateBoth || ga.op == kGatherOpGateBothMax;
     if (view->n_slots > 0) {
         if (saga_status st = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * ga.F * (two ? 2 : 1))) return st;
         ga.partials = static_cast<float*>(ctx->ws_partials.p);
@@ -225,8 +225,13 @@ static saga_status param_grad(saga_ctx* ctx, const float* P, int64_t ldp, int32_
 // Everything of a gated layer's backward pass after backward-ApplyVertex's parameter gradients: the gradient of
 // accum, the three per-vertex sums of backward-ApplyEdge (gates recomputed from the hoisted products), and the dense
 // products that turn them into dX and the ApplyEdge parameter gradients.
+// With the max accumulator (`A_max` = the forward Gather output, else NULL) an edge carries gradient only for the
+// features whose maximum at its destination it supplied: the two propagation passes then also compare the recomputed
+// message with that maximum (a third constant row in the pass over the in-edges, a third row per edge in the pass
+// over the out-edges).
 static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const float* dZ, int64_t lddz,
-                                       const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads)
+                                       const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads,
+                                       const saga_tensor* A_max)
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)vp->W->rows, Fo = (int32_t)vp->W->cols;
@@ -260,21 +265,30 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     ga.F = F;
     ga.ld_src = ga.ld_dst = ga.ld_out = ldh;
     // destination part: dPd[v] = sum over in-edges of dA[v] (.) M[u] (.) g (1 - g), g = sigmoid(Ps[u] + Pd[v])
-    ga.op = kGatherOpGateGrad;
+    ga.op = A_max ? kGatherOpGateGradMax : kGatherOpGateGrad;
     ga.src = H;
     ga.src2 = H + F;
     ga.ld_src2 = ldh;
     ga.dst = H + 2 * F;
     ga.dst2 = dA;
     ga.ld_dst2 = F;
+    if (A_max) {
+        ga.dst3 = static_cast<const float*>(A_max->data);
+        ga.ld_dst3 = A_max->ld;
+    }
     ga.out = dH + 2 * F;
     if ((st = run_propagation(ctx, g, ga, row_bytes))) return st;
     // source parts, both from one pass over the out-edges (the same two rows are loaded per edge):
     //   dPs[u] = sum of dA[v] (.) M[u] (.) g (1 - g),  dM[u] = sum of g (.) dA[v],  g = sigmoid(Pd[v] + Ps[u])
-    ga.op = kGatherOpGateBoth;
+    ga.op = A_max ? kGatherOpGateBothMax : kGatherOpGateBoth;
+    ga.dst3 = nullptr;
     ga.src = H + 2 * F;
     ga.src2 = dA;
     ga.ld_src2 = F;
+    if (A_max) {
+        ga.src3 = A_max->data;
+        ga.ld_src3 = A_max->ld;
+    }
     ga.dst = H;
     ga.dst2 = H + F;
     ga.ld_dst2 = ldh;
@@ -516,7 +530,7 @@ saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X
     if (saga_status st = param_grad(ctx, static_cast<const float*>(A->data), A->ld, F, dZ, lddz, Fo, n, static_cast<float*>(grads->dW->data), grads->dW->ld)) return st;
     if (grads->dW_self)  // X is as wide as the messages except for POOL
         if (saga_status st = param_grad(ctx, static_cast<const float*>(X->data), X->ld, (int32_t)X->cols, dZ, lddz, Fo, n, static_cast<float*>(grads->dW_self->data), grads->dW_self->ld)) return st;
-    if (ep->op == SAGA_EDGE_GATED) return gated_backward_rest(ctx, g, X, dZ, lddz, ep, vp, grads);
+    if (ep->op == SAGA_EDGE_GATED) return gated_backward_rest(ctx, g, X, dZ, lddz, ep, vp, grads, agg == SAGA_AGG_MAX ? A : nullptr);
     if (ep->op == SAGA_EDGE_POOL || agg == SAGA_AGG_MAX) return max_pool_backward_rest(ctx, g, X, A, dZ, lddz, ep, agg, vp, grads);
     if (!grads->dX || n == 0) return SAGA_OK;
 

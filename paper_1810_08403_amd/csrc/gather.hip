@@ -315,16 +315,28 @@ __device__ __forceinline__ void fetch_ids(const_i32_ptr ridx, const_f32_ptr ew, 
 //                supplied the maximum"; the product is the same single fp32 multiply that formed the message). With
 //                `dst_sigmoid` the constant row is stored as pre-activations z and c1 = sigmoid(z) is formed once per
 //                item, by the function the pooled rows were made with, so that the backward pass keeps z for the slope
-constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3, kEfMaxGrad = 4;
+//   kEfGateGradMax / kEfGateBothMax  the two gradient forms for a gated layer under the max accumulator: the edge
+//                contributes only where its message equals the maximum that was gathered at the edge's destination,
+//                sigmoid(x + c1) * m == c3 with c3 a third constant row (in-edge pass: the item is the destination), or
+//                sigmoid(x + c1) * c2 == t with t a third row per edge (out-edge pass: the message's m is this item's
+//                constant row c2, the destination's maximum travels with the edge). The message is formed by the very
+//                expression of kEfGate (sigmoid_f32 of one fp32 sum, one multiply), so the comparison is bit for bit.
+constexpr int kEfLinear = 0, kEfGate = 1, kEfGateGrad = 2, kEfGateBoth = 3, kEfMaxGrad = 4, kEfGateGradMax = 5, kEfGateBothMax = 6;
+constexpr bool ef_is_grad(int ef) { return ef == kEfGateGrad || ef == kEfGateBoth || ef == kEfGateGradMax || ef == kEfGateBothMax; }
+constexpr bool ef_is_both(int ef) { return ef == kEfGateBoth || ef == kEfGateBothMax; }
+constexpr bool ef_third_row(int ef) { return ef == kEfGateBothMax; }    // a third row per edge
+constexpr bool ef_third_const(int ef) { return ef == kEfGateGradMax; }  // a third constant row per item
 
 template <int AGG, int EF>
-__device__ __forceinline__ float edge_step(float acc, float w, float x, float m, float c1, float c2)
+__device__ __forceinline__ float edge_step(float acc, float w, float x, float m, float c1, float c2, float c3)
 {
     if constexpr (EF == kEfGate) return accumulate<AGG>(acc, sigmoid_f32(x + c1), m);
-    if constexpr (EF == kEfGateGrad) {
+    if constexpr (EF == kEfGateGrad || EF == kEfGateGradMax) {
         float g, slope;
         sigmoid_and_slope_f32(x + c1, g, slope);
-        return fmaf(slope, c2 * m, acc);
+        const float r = fmaf(slope, c2 * m, acc);
+        if constexpr (EF == kEfGateGradMax) return sigmoid_f32(x + c1) * m == c3 ? r : acc;
+        return r;
     }
     if constexpr (EF == kEfMaxGrad) {
         const float msg = w * c1;
@@ -332,38 +344,50 @@ __device__ __forceinline__ float edge_step(float acc, float w, float x, float m,
     }
     return accumulate<AGG>(acc, w, x);
 }
-__device__ __forceinline__ void edge_step_both(float& acc, float& acc2, float x, float m, float c1, float c2)
+template <int EF>
+__device__ __forceinline__ void edge_step_both(float& acc, float& acc2, float x, float m, float c1, float c2, float t)
 {
     float g, slope;
     sigmoid_and_slope_f32(x + c1, g, slope);
-    acc = fmaf(slope, c2 * m, acc);
-    acc2 = fmaf(g, m, acc2);
+    const float r = fmaf(slope, c2 * m, acc), r2 = fmaf(g, m, acc2);
+    if constexpr (EF == kEfGateBothMax) {
+        const bool hit = sigmoid_f32(x + c1) * c2 == t;
+        acc = hit ? r : acc;
+        acc2 = hit ? r2 : acc2;
+    } else {
+        acc = r;
+        acc2 = r2;
+    }
 }
 
 // One group of up to U edges: issue every row load first, then consume.
 // TAIL guards each edge with the wave-uniform predicate e + k < e1.
 template <typename T, int VEC, int RC, int AGG, int EF, int U, bool TAIL>
 __device__ __forceinline__ void wide_group(const T* __restrict__ X, const int64_t ld, const T* __restrict__ X2, const int64_t ld2,
-                                           const int (&u)[U], const int e, const int e1, const int (&col)[RC],
-                                           Frag<T, VEC> (&x)[U][RC], Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1])
+                                           const T* __restrict__ X3, const int64_t ld3, const int (&u)[U], const int e, const int e1,
+                                           const int (&col)[RC], Frag<T, VEC> (&x)[U][RC], Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1],
+                                           Frag<T, VEC> (&t3)[ef_third_row(EF) ? U : 1][ef_third_row(EF) ? RC : 1])
 {
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         if (TAIL && e + k >= e1) continue;
         const T* row = X + (int64_t)u[k] * ld;
         const T* row2 = X2 + (int64_t)u[k] * ld2;
+        const T* row3 = X3 + (int64_t)u[k] * ld3;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
             x[k][c].load(row + col[c]);
             if constexpr (EF != kEfLinear) m[k][c].load(row2 + col[c]);
+            if constexpr (ef_third_row(EF)) t3[k][c].load(row3 + col[c]);
         }
     }
 }
 template <typename T, int VEC, int RC, int AGG, int EF, int U, bool TAIL>
 __device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, const int e1, const float (&c1)[RC][VEC],
-                                             const float (&c2)[RC][VEC], float (&acc)[RC][VEC],
-                                             float (&acc2)[EF == kEfGateBoth ? RC : 1][VEC], const Frag<T, VEC> (&x)[U][RC],
-                                             const Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1])
+                                             const float (&c2)[RC][VEC], const float (&c3)[RC][VEC], float (&acc)[RC][VEC],
+                                             float (&acc2)[ef_is_both(EF) ? RC : 1][VEC], const Frag<T, VEC> (&x)[U][RC],
+                                             const Frag<T, VEC> (&m)[EF ? U : 1][EF ? RC : 1],
+                                             const Frag<T, VEC> (&t3)[ef_third_row(EF) ? U : 1][ef_third_row(EF) ? RC : 1])
 {
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -372,12 +396,13 @@ __device__ __forceinline__ void wide_consume(const float (&w)[U], const int e, c
         for (int c = 0; c < RC; ++c)
 #pragma unroll
             for (int jj = 0; jj < VEC; ++jj) {
-                float mv = 0.f;
+                float mv = 0.f, tv = 0.f;
                 if constexpr (EF != kEfLinear) mv = m[k][c].get(jj);
-                if constexpr (EF == kEfGateBoth)
-                    edge_step_both(acc[c][jj], acc2[c][jj], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
+                if constexpr (ef_third_row(EF)) tv = t3[k][c].get(jj);
+                if constexpr (ef_is_both(EF))
+                    edge_step_both<EF>(acc[c][jj], acc2[c][jj], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj], tv);
                 else
-                    acc[c][jj] = edge_step<AGG, EF>(acc[c][jj], w[k], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj]);
+                    acc[c][jj] = edge_step<AGG, EF>(acc[c][jj], w[k], x[k][c].get(jj), mv, c1[c][jj], c2[c][jj], c3[c][jj]);
             }
     }
 }
@@ -391,22 +416,25 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
     const int F = a.F;
     const int nvec = (F + VEC - 1) / VEC;
     constexpr bool GATED = EF != kEfLinear;
-    constexpr int LOADS_PER_EDGE = RC * (GATED ? 2 : 1);
+    constexpr bool ROW3 = ef_third_row(EF);
+    constexpr int LOADS_PER_EDGE = RC * (ROW3 ? 3 : GATED ? 2 : 1);
     constexpr int U = (kInFlight / LOADS_PER_EDGE) > 0 ? (kInFlight / LOADS_PER_EDGE) : 1;
     const T* __restrict__ X = static_cast<const T*>(a.src);
     const T* __restrict__ X2 = GATED ? static_cast<const T*>(a.src2) : X;
     const int64_t ld2 = GATED ? a.ld_src2 : 0;
+    const T* __restrict__ X3 = ROW3 ? static_cast<const T*>(a.src3) : X;
+    const int64_t ld3 = ROW3 ? a.ld_src3 : 0;
     const const_i32_ptr ridx = (const_i32_ptr)(uintptr_t)a.row_idx;
     const const_f32_ptr ew = (GATED && EF != kEfMaxGrad) ? (const_f32_ptr)0 : (const_f32_ptr)(uintptr_t)a.edge_w;
     __shared__ float red[(kWavesPerBlock - 1) * 64 * RC * VEC];
 
     for (int cb = 0; cb < nvec; cb += 64 * RC) {
         float acc[RC][VEC];
-        float acc2[EF == kEfGateBoth ? RC : 1][VEC];
-        float pd[RC][VEC], c2[RC][VEC];
+        float acc2[ef_is_both(EF) ? RC : 1][VEC];
+        float pd[RC][VEC], c2[RC][VEC], c3[RC][VEC];
         bool ok[RC];
 #pragma unroll
-        for (int c = 0; c < (EF == kEfGateBoth ? RC : 1); ++c)
+        for (int c = 0; c < (ef_is_both(EF) ? RC : 1); ++c)
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc2[c][j] = 0.f;
         int col[RC];
@@ -421,6 +449,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 acc[c][j] = identity<AGG>();
                 pd[c][j] = 0.f;
                 c2[c][j] = 0.f;
+                c3[c][j] = 0.f;
             }
             if constexpr (GATED) {
                 Frag<float, VEC> f;
@@ -434,16 +463,24 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                         for (int j = 0; j < VEC; ++j) pd[c][j] = sigmoid_f32(pd[c][j]);
                     }
             }
-            if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
+            if constexpr (ef_is_grad(EF)) {
                 Frag<float, VEC> f;
                 f.zero();
                 if (ok[c]) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col[c]);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) c2[c][j] = f.get(j);
             }
+            if constexpr (ef_third_const(EF)) {
+                Frag<float, VEC> f;
+                f.zero();
+                if (ok[c]) f.load(a.dst3 + (int64_t)it.v * a.ld_dst3 + col[c]);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) c3[c][j] = f.get(j);
+            }
         }
         Frag<T, VEC> x[U][RC];
         Frag<T, VEC> m[GATED ? U : 1][GATED ? RC : 1];
+        Frag<T, VEC> t3[ROW3 ? U : 1][ROW3 ? RC : 1];
         int u[U], un[U];
         float w[U], wn[U];
         int e = it.e0;
@@ -454,15 +491,15 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                 u[k] = un[k];
                 w[k] = wn[k];
             }
-            wide_group<T, VEC, RC, AGG, EF, U, false>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
+            wide_group<T, VEC, RC, AGG, EF, U, false>(X, a.ld_src, X2, ld2, X3, ld3, u, e, it.e1, ldcol, x, m, t3);
             // ids of the next full group travel while this group's rows do
             if (e + 2 * U <= it.e1) fetch_ids<U, false>(ridx, ew, e + U, it.e1, un, wn);
-            wide_consume<T, VEC, RC, AGG, EF, U, false>(w, e, it.e1, pd, c2, acc, acc2, x, m);
+            wide_consume<T, VEC, RC, AGG, EF, U, false>(w, e, it.e1, pd, c2, c3, acc, acc2, x, m, t3);
         }
         if (e < it.e1) {
             fetch_ids<U, true>(ridx, ew, e, it.e1, u, w);
-            wide_group<T, VEC, RC, AGG, EF, U, true>(X, a.ld_src, X2, ld2, u, e, it.e1, ldcol, x, m);
-            wide_consume<T, VEC, RC, AGG, EF, U, true>(w, e, it.e1, pd, c2, acc, acc2, x, m);
+            wide_group<T, VEC, RC, AGG, EF, U, true>(X, a.ld_src, X2, ld2, X3, ld3, u, e, it.e1, ldcol, x, m, t3);
+            wide_consume<T, VEC, RC, AGG, EF, U, true>(w, e, it.e1, pd, c2, c3, acc, acc2, x, m, t3);
         }
         if (it.team) {  // the same for every wavefront of the block, so the barriers are uniform
 #pragma unroll
@@ -476,7 +513,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
                         store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, false);
                     }
             }
-            if constexpr (EF == kEfGateBoth) {  // the second row through the same LDS space
+            if constexpr (ef_is_both(EF)) {  // the second row through the same LDS space
                 __syncthreads();
 #pragma unroll
                 for (int c = 0; c < RC; ++c) team_park<VEC>(red, 64 * RC * VEC, c * 64 + lane, ok[c], acc2[c]);
@@ -496,7 +533,7 @@ __global__ __launch_bounds__(256) void k_gather_wide(const GatherArgs a)
             for (int c = 0; c < RC; ++c)
                 if (ok[c]) {
                     store_row<VEC>(a, it.v, it.slot, col[c], acc[c], AGG, it.empty_item);
-                    if constexpr (EF == kEfGateBoth) store_row2<VEC>(a, it.v, it.slot, col[c], acc2[c]);
+                    if constexpr (ef_is_both(EF)) store_row2<VEC>(a, it.v, it.slot, col[c], acc2[c]);
                 }
         }
     }
@@ -758,27 +795,33 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
     const bool colok = sub < nvec;
     const int col = sub * VEC;
     const int ldcol = colok ? col : 0;
-    constexpr int U = GATED ? kInFlight / 2 : kInFlight;
+    constexpr bool ROW3 = ef_third_row(EF);
+    constexpr int U = ROW3 ? kInFlight / 3 : GATED ? kInFlight / 2 : kInFlight;
     const T* __restrict__ X = static_cast<const T*>(a.src);
     const T* __restrict__ X2 = GATED ? static_cast<const T*>(a.src2) : X;
     const int64_t ld2 = GATED ? a.ld_src2 : 0;
+    const T* __restrict__ X3 = ROW3 ? static_cast<const T*>(a.src3) : X;
+    const int64_t ld3 = ROW3 ? a.ld_src3 : 0;
     const int32_t* __restrict__ ridx = a.row_idx;
     const float* __restrict__ ew = a.edge_w;
     // row address = this lane's fragment of row 0 + id * bytes per row: one 32 x 32 -> 64-bit multiply-add
     // (the launcher checks that a row stride fits 32 bits)
     const char* const xbase = reinterpret_cast<const char*>(X + ldcol);
     const char* const xbase2 = reinterpret_cast<const char*>(X2 + ldcol);
+    const char* const xbase3 = reinterpret_cast<const char*>(X3 + ldcol);
     const uint32_t ldb = (uint32_t)(a.ld_src * (int64_t)sizeof(T));
     const uint32_t ldb2 = (uint32_t)(ld2 * (int64_t)sizeof(T));
+    const uint32_t ldb3 = (uint32_t)(ld3 * (int64_t)sizeof(T));
     const int grp4 = grp << 2;
 
-    float acc[VEC], acc2[VEC], pd[VEC], c2[VEC];
+    float acc[VEC], acc2[VEC], pd[VEC], c2[VEC], c3[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
         acc[j] = identity<AGG>();
         acc2[j] = 0.f;
         pd[j] = 0.f;
         c2[j] = 0.f;
+        c3[j] = 0.f;
     }
     if constexpr (GATED) {
         Frag<float, VEC> f;
@@ -792,12 +835,19 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                 for (int j = 0; j < VEC; ++j) pd[j] = sigmoid_f32(pd[j]);
             }
     }
-    if constexpr (EF == kEfGateGrad || EF == kEfGateBoth) {
+    if constexpr (ef_is_grad(EF)) {
         Frag<float, VEC> f;
         f.zero();
         if (colok) f.load(a.dst2 + (int64_t)it.v * a.ld_dst2 + col);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) c2[j] = f.get(j);
+    }
+    if constexpr (ef_third_const(EF)) {
+        Frag<float, VEC> f;
+        f.zero();
+        if (colok) f.load(a.dst3 + (int64_t)it.v * a.ld_dst3 + col);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) c3[j] = f.get(j);
     }
 
     // ids and weights of a batch of 64 edges, one per lane; the next batch's travel while this one's rows do
@@ -826,6 +876,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
             constexpr bool CHECK = decltype(check_tag)::value;
             Frag<T, VEC> x[U];
             Frag<T, VEC> m[GATED ? U : 1];
+            Frag<T, VEC> t3[ROW3 ? U : 1];
             float w[U];
             bool ok[U];
 #pragma unroll
@@ -840,6 +891,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                     w[k] = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(wt)));
                     x[k].load(reinterpret_cast<const T*>(xbase + (uint64_t)u * ldb));
                     if constexpr (GATED) m[k].load(reinterpret_cast<const T*>(xbase2 + (uint64_t)u * ldb2));
+                    if constexpr (ROW3) t3[k].load(reinterpret_cast<const T*>(xbase3 + (uint64_t)u * ldb3));
                 }
             }
 #pragma unroll
@@ -847,15 +899,16 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
                 if (k < count) {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) {
-                        float mv = 0.f;
+                        float mv = 0.f, tv = 0.f;
                         if constexpr (GATED) mv = m[k].get(j);
-                        if constexpr (EF == kEfGateBoth) {
+                        if constexpr (ROW3) tv = t3[k].get(j);
+                        if constexpr (ef_is_both(EF)) {
                             float r = acc[j], r2 = acc2[j];
-                            edge_step_both(r, r2, x[k].get(j), mv, pd[j], c2[j]);
+                            edge_step_both<EF>(r, r2, x[k].get(j), mv, pd[j], c2[j], tv);
                             acc[j] = (!CHECK || ok[k]) ? r : acc[j];
                             acc2[j] = (!CHECK || ok[k]) ? r2 : acc2[j];
                         } else {
-                            const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j]);
+                            const float r = edge_step<AGG, EF>(acc[j], w[k], x[k].get(j), mv, pd[j], c2[j], c3[j]);
                             acc[j] = (!CHECK || ok[k]) ? r : acc[j];
                         }
                     }
@@ -872,7 +925,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
             acc[j] = combine<AGG>(acc[j], __shfl_xor(acc[j], off));
-            if constexpr (EF == kEfGateBoth) acc2[j] += __shfl_xor(acc2[j], off);
+            if constexpr (ef_is_both(EF)) acc2[j] += __shfl_xor(acc2[j], off);
         }
     if (it.team) {
         __shared__ float red[(kWavesPerBlock - 1) * 32 * VEC];
@@ -882,7 +935,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
             team_collect<AGG, VEC>(red, 32 * VEC, sub, acc);
             store_row<VEC>(a, it.v, it.slot, col, acc, AGG, false);
         }
-        if constexpr (EF == kEfGateBoth) {
+        if constexpr (ef_is_both(EF)) {
             __syncthreads();
             team_park<VEC>(red, 32 * VEC, sub, grp == 0 && colok, acc2);
             __syncthreads();
@@ -893,7 +946,7 @@ __global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const
         }
     } else if (grp == 0 && colok) {
         store_row<VEC>(a, it.v, it.slot, col, acc, AGG, it.empty_item);
-        if constexpr (EF == kEfGateBoth) store_row2<VEC>(a, it.v, it.slot, col, acc2);
+        if constexpr (ef_is_both(EF)) store_row2<VEC>(a, it.v, it.slot, col, acc2);
     }
 }
 
@@ -1075,6 +1128,8 @@ hipError_t launch_op(const GatherArgs& a, hipStream_t s)
         if (a.op == kGatherOpGateGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateGrad>(a, s);
         if (a.op == kGatherOpGateBoth) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateBoth>(a, s);
         if (a.op == kGatherOpMaxGrad) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfMaxGrad>(a, s);
+        if (a.op == kGatherOpGateGradMax) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateGradMax>(a, s);
+        if (a.op == kGatherOpGateBothMax) return launch_shape<T, VEC, SAGA_AGG_SUM, kEfGateBothMax>(a, s);
     }
     return a.agg == SAGA_AGG_SUM ? launch_shape<T, VEC, SAGA_AGG_SUM, kEfLinear>(a, s)
                                  : launch_shape<T, VEC, SAGA_AGG_MAX, kEfLinear>(a, s);
@@ -1096,14 +1151,23 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if ((a.bias || a.act != SAGA_ACT_NONE) && a.accumulate) return hipErrorInvalidValue;
     if (a.ld_src < 0 || a.ld_src >= (1LL << 30) || a.ld_src2 < 0 || a.ld_src2 >= (1LL << 30))
         return hipErrorInvalidValue;  // the kernels form row offsets in bytes with 32-bit row strides
-    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
+    const bool both = a.op == kGatherOpGateBoth || a.op == kGatherOpGateBothMax;
+    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateGradMax || both;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {
         if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM))) return hipErrorInvalidValue;
         if (a.op == kGatherOpMaxGrad && a.agg != SAGA_AGG_SUM) return hipErrorInvalidValue;
         vec_ok = vec_ok && (a.ld_dst * 4) % 16 == 0 && aligned16(a.dst) && (a.ld_src2 * 4) % 16 == 0 && aligned16(a.src2);
         if (grad) vec_ok = vec_ok && (a.ld_dst2 * 4) % 16 == 0 && aligned16(a.dst2);
-        if (a.op == kGatherOpGateBoth) {
+        if (a.op == kGatherOpGateGradMax) {
+            if (!a.dst3) return hipErrorInvalidValue;
+            vec_ok = vec_ok && (a.ld_dst3 * 4) % 16 == 0 && aligned16(a.dst3);
+        }
+        if (a.op == kGatherOpGateBothMax) {
+            if (!a.src3 || a.ld_src3 < 0 || a.ld_src3 >= (1LL << 30)) return hipErrorInvalidValue;
+            vec_ok = vec_ok && (a.ld_src3 * 4) % 16 == 0 && aligned16(a.src3);
+        }
+        if (both) {
             if (!a.out || !a.out2 || a.out16 || (a.partials && !a.partials2)) return hipErrorInvalidValue;
             vec_ok = vec_ok && (a.ld_out2 * 4) % 16 == 0 && aligned16(a.out2) && (!a.partials2 || aligned16(a.partials2));
         }

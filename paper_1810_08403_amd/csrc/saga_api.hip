@@ -1693,7 +1693,7 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
         const bool pool_h = ep->op == SAGA_EDGE_POOL, gated_h = ep->op == SAGA_EDGE_GATED;
         if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
-        if (gated_h && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
+        if (gated_h && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass does not cover max over gated messages (the resident one does)");
         const bool max_or_pool = pool_h || (agg == SAGA_AGG_MAX && !gated_h);
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
@@ -1770,7 +1770,6 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
     if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
     const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
     if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
-    if (gated && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the backward pass does not cover max over gated messages");
     if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
         return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
     auto dev_f32 = [](const saga_tensor* t) { return tensor_ok(t) && t->mem == SAGA_MEM_DEVICE && t->dtype == SAGA_F32; };

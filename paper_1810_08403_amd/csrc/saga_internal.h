@@ -308,6 +308,11 @@ constexpr int32_t kGatherOpGateGrad = 100;
 constexpr int32_t kGatherOpGateBoth = 101;
 // gradient of a max Gather: a vertex receives w_e * (gradient at the other end) over the edges whose maximum it supplied
 constexpr int32_t kGatherOpMaxGrad = 102;
+// the two gate gradients of a gated layer under the max accumulator: only where the edge's message is the maximum that
+// was gathered at its destination (kGatherOpGateGrad with a third constant row `dst3` = that maximum; kGatherOpGateBoth
+// with a third row per edge `src3`)
+constexpr int32_t kGatherOpGateGradMax = 103;
+constexpr int32_t kGatherOpGateBothMax = 104;
 
 struct GatherArgs {
     const WorkItem* items;
@@ -327,6 +332,10 @@ struct GatherArgs {
     int64_t ld_dst;
     const float* dst2;       // kGatherOpGateGrad only
     int64_t ld_dst2;
+    const float* dst3;       // kGatherOpGateGradMax only
+    int64_t ld_dst3;
+    const void* src3;        // kGatherOpGateBothMax only
+    int64_t ld_src3;
     int32_t F;
     int32_t dtype;           // saga_dtype of src (GATED: F32)
     int32_t op;              // saga_edge_op

@@ -153,9 +153,9 @@ def test_backward_rejects_what_it_does_not_cover(ctx):
     Fo = wl.W.shape[1]
     A, dY, W, dW = (torch.zeros(n, F, device="cuda"), torch.zeros(n, Fo, device="cuda"), wl.W.cuda(), torch.zeros(F, Fo, device="cuda"))
     X = wl.X.cuda()
-    with pytest.raises(saga.SagaError) as e:                      # max over gated messages
+    with pytest.raises(saga.SagaError) as e:                      # max over gated messages without the gate's parameters
         ctx.layer_backward(graph, A, dY, W, dW, X=X, agg="max", edge_op="gated")
-    assert e.value.status == 3
+    assert e.value.status == 1
     with pytest.raises(saga.SagaError) as e:                      # an activation without Y
         ctx.layer_backward(graph, A, dY, W, dW, act="sigmoid")
     assert e.value.status == 1
@@ -369,6 +369,85 @@ def test_gated_backward_configuration_4_at_scale_16(ctx):
     assert info["n_split_vertices"] > 0
     for name in ["dW", "dX", "dW_gate", "db_gate", "dW_msg"]:
         assert_sum_close(res[name], bwd[name], bwd[name + "_abs"], TOL_F32, "configuration 4 at scale 16, " + name)
+    graph.destroy()
+
+
+def _coarse_gated_workload(scale, F, Fo):
+    """Configuration 4's layer shape with X, W_gate, b_gate and W_msg on coarse grids (multiples of 1/4 and 1/8): the
+    hoisted products are then exact in fp32 in any order of summation, so the GPU's fp32 messages sigmoid(z) * m and the
+    oracle's fp64 ones are formed from the same z and m and rank alike, ties included (two different (z, m) pairs give
+    messages that differ by far more than the 1e-7 the two sigmoids differ by)."""
+    wl = si.workload(4, scale=scale, f_in=F, f_out=Fo)
+    q = lambda t, lim, s: torch.round(t.clamp(-lim, lim) * s) / s
+    wl.X = q(wl.X, 1.0, 4)
+    wl.W_gate, wl.b_gate, wl.W_msg = q(wl.W_gate, 1.0, 8), q(wl.b_gate, 0.5, 8), q(wl.W_msg, 1.0, 8)
+    Xd = wl.X.double()
+    z = (Xd @ wl.W_gate[:, :F].double().T).abs().max() + (Xd @ wl.W_gate[:, F:].double().T).abs().max() + 0.5
+    assert z.item() <= 12.0 and (wl.W_gate != 0).float().mean().item() > 0.2
+    return wl
+
+
+@pytest.mark.parametrize("F,Fo,act,with_b,with_msg,with_self", [
+    (8, 8, "relu", True, True, False),
+    (64, 32, "relu", True, True, False),
+    (128, 128, "none", True, True, False),       # configuration 4's widths: the narrow kernel at its widest
+    (160, 24, "relu", True, True, False),        # wide kernel, one fragment per lane
+    (260, 16, "relu", False, True, False),       # wide kernel, two fragments per lane
+    (70, 8, "none", True, True, False),          # rows that do not allow 16-byte fragments
+    (20, 12, "relu", True, False, False),        # identity message matrix
+    (64, 48, "sigmoid", True, True, True),       # sigmoid activation and the vertex's own product
+    (20, 12, "relu", True, False, True),
+])
+def test_gated_max_backward_matches_oracle(ctx, F, Fo, act, with_b, with_msg, with_self):
+    """Max over gated messages backwards. The Gather output handed to the backward pass is the forward pass's own (its
+    maxima are compared bit for bit with the recomputed messages); the stored output is synthetic, only the activation's
+    derivative is taken from it, and the oracle is given the same dZ."""
+    wl = _coarse_gated_workload(10, F, Fo)
+    g = wl.graph
+    n = g.n
+    dev = "cuda"
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    deg = np.diff(cp)
+    assert deg.max() > 128 and (deg == 0).any()                      # cut columns and empty ones
+    Ws = si.glorot_uniform(F, Fo, 41) if with_self else None
+    bg = wl.b_gate if with_b else None
+    Wm = wl.W_msg if with_msg else None
+    opt = lambda t: None if t is None else t.to(dev)
+    graph = make_graph(ctx, g)
+    A = torch.full((n, F), float("nan"), device=dev)
+    Yf = torch.empty(n, Fo, device=dev)
+    ctx.layer_forward(graph, wl.X.to(dev), Yf, edge_op="gated", agg="max", W_gate=wl.W_gate.to(dev), b_gate=opt(bg), W_msg=opt(Wm),
+                      W=wl.W.to(dev), W_self=opt(Ws), act="none", accum_out=A)
+    dY = si.normal_features(n, Fo, 99)
+    Y_in = si.normal_features(n, Fo, 98)
+    if act == "sigmoid":
+        Y_in = torch.sigmoid(Y_in)
+    slope = {"none": torch.ones_like(Y_in.double()), "relu": (Y_in > 0).double(), "sigmoid": Y_in.double() * (1 - Y_in.double())}[act]
+    dZ = (dY.double() * slope).float()
+    okw = dict(W_gate=wl.W_gate.numpy(), b_gate=None if bg is None else bg.numpy(), W_msg=None if Wm is None else Wm.numpy(),
+               W_self=None if Ws is None else Ws.numpy())
+    bwd = oracle.gated_backward(cp, ri, wl.X.numpy(), None, dZ.numpy(), wl.W.numpy(), act="none", agg="max", **okw)
+    what = f"gated max {F}->{Fo} {act}"
+    assert_sum_close(A.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " A")
+    nan = lambda *shape: torch.full(shape, float("nan"), device=dev)
+    def run(want_dx=True):
+        out = dict(dW=nan(F, Fo), dX=nan(n, F) if want_dx else None, dbias=nan(Fo), dW_gate=nan(F, 2 * F),
+                   db_gate=nan(F) if with_b else None, dW_msg=nan(F, F) if with_msg else None, dW_self=nan(F, Fo) if with_self else None)
+        ctx.layer_backward(graph, A, dY.to(dev), wl.W.to(dev), out["dW"], X=wl.X.to(dev), Y=Y_in.to(dev), edge_op="gated", agg="max", act=act,
+                           dX=out["dX"], dbias=out["dbias"], W_gate=wl.W_gate.to(dev), b_gate=opt(bg), W_msg=opt(Wm),
+                           dW_gate=out["dW_gate"], db_gate=out["db_gate"], dW_msg=out["dW_msg"], W_self=opt(Ws), dW_self=out["dW_self"])
+        torch.cuda.synchronize()
+        return {k: v.cpu().numpy() for k, v in out.items() if v is not None}
+    res = run()
+    for name in res:
+        assert np.abs(bwd[name]).max() > 0, name
+        assert_sum_close(res[name], bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, f"{what} {name}")
+    # a source that supplies no maximum gets nothing through the edges: its row of [dPs | dM] is zero, and without
+    # in-edges dPd as well, so dX is exactly the vertex's own partial gradient (zero without W_self)
+    if not with_self:
+        assert ((bwd["dX_abs"] == 0) <= (res["dX"] == 0)).all()
+    res2 = run(want_dx=False)
+    assert np.array_equal(res2["dW_gate"], res["dW_gate"]) and np.array_equal(res2["dW"], res["dW"])
     graph.destroy()
 
 
