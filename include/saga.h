@@ -262,70 +262,68 @@ typedef struct saga_layer_grads {
  * rows of dZ are propagated first and multiplied by W^T afterwards (the operator motion of
  * Section 3.2 applied to the backward pass); the result is the same up to rounding order.
  *
- * GATED (Example 2.1 / Figure 2): with s_e = W_gs x_u + W_gd x_v + b, g_e = sigmoid(s_e),
- * t_u = W_m x_u, backward-ApplyEdge gives every edge dt_e = g_e (.) dA[v] and
- * ds_e = dA[v] (.) t_u (.) g_e (.) (1 - g_e). The gates are recomputed from the hoisted
- * per-vertex products (Section 3.2), not stored per edge. Three propagation passes collect
- * them per vertex: sum of ds_e over in-edges (destination part), sum of ds_e and of dt_e over
- * out-edges (source parts); dense products then give dX = [dPs | dM | dPd] [W_gs ; W_m ; W_gd],
- * dW_gate = [dPs^T X | dPd^T X], db_gate = column sums of dPd, dW_msg = dM^T X.
- * With W_self the own partial gradient dZ W_self^T joins dX as a second operand pair of that
- * product. X is required.
+ * What the propagation part does, by layer (u -> v an edge, dA = gradient of accum):
  *
- * Max accumulator (Figure 11's layer): the gradient of A[v][f] goes to every in-edge whose
- * message equals the maximum A[v][f] (on a tie every maximal edge receives all of it). The
- * decision is taken by recomputing the message, w_e * x_u[f] with the same single fp32
- * multiply as the forward pass (or the pooled sigmoid row of u: its pre-activations z_u are
- * recomputed per vertex by the same product as in the forward pass and the sigmoid is taken
- * by the same function of the same fp32 value), and comparing it with the A the caller
- * kept: one propagation pass over the out-edges. POOL then goes through the sigmoid per
- * vertex: dPre = dS (.) sigmoid'(z), the slope formed from z so that a saturated unit keeps
- * its relative accuracy, dX = dPre W_pool, dW_pool = dPre^T X, db_pool = column
- * sums of dPre. With W_self the own partial gradient dZ W_self^T is written into dX before
- * the propagation adds to it (COPY, MUL_WEIGHT) or joins the product dPre W_pool (POOL).
- * X and A are required; A must be the accum_out of the forward call on the same inputs, or
- * no message will compare equal.
+ *   layer                  per edge                                    passes over the edges          then, per vertex                          needs
+ *   ---------------------  ------------------------------------------  -----------------------------  ----------------------------------------  ---------
+ *   sum, COPY/MUL_WEIGHT   dX[u] += w_e dA[v]                          out-edges, once                (own partial gradient joins dX)           A
+ *   sum, GATED             s_e = W_gs x_u + W_gd x_v + b, g_e =        in-edges: dPd[v] += ds_e;      dX = [dPs|dM|dPd] [W_gs;W_m;W_gd]         A, X
+ *   (Example 2.1, Fig. 2)  sigmoid(s_e), t_u = W_m x_u;                out-edges: dPs[u] += ds_e and  (+ dZ W_self^T as a second operand        
+ *                          dt_e = g_e (.) dA[v],                       dM[u] += dt_e in one pass;     pair), dW_gate = [dPs^T X | dPd^T X],     
+ *                          ds_e = dA[v] (.) t_u (.) g_e (.) (1 - g_e)  gates recomputed from the      db_gate = column sums of dPd,             
+ *                                                                      hoisted products (Sec. 3.2)    dW_msg = dM^T X                           
+ *   max, COPY/MUL_WEIGHT   dX[u][f] += w_e dA[v][f] where the message  out-edges, once                (own partial gradient written into dX     A, X
+ *   (Figure 11's Gather)   w_e x_u[f], one fp32 multiply as in the                                    before the propagation adds to it)        
+ *                          forward pass, equals A[v][f]                                                                                          
+ *   max or sum, POOL       as above on the pooled rows h_u =           out-edges, once                dPre = dS (.) sigmoid'(z), slope formed   A, X
+ *   (Figure 11)            sigmoid(z_u); z_u = W_pool x_u + b is                                      from z (a saturated unit keeps its        
+ *                          recomputed per vertex by the forward                                       relative accuracy); dX = dPre W_pool      
+ *                          pass's product and sigmoid                                                 (+ dZ W_self^T), dW_pool = dPre^T X,      
+ *                                                                                                     db_pool = column sums of dPre             
+ *   max, GATED             the GATED rows, only for the features f     as sum, GATED; A[v] travels    as sum, GATED                             A, X
+ *                          where g_e[f] t_u[f] equals A[v][f]          as a third row                                                           
  *
- * Streamed calls (a SAGA_MEM_HOST graph, fp32; sum or max over COPY / MUL_WEIGHT messages, sum
- * or max over POOL messages, sum over GATED messages, each with or without W_self): A, Y, dY,
- * grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST tensors (pinned
- * recommended), the parameters and their gradients stay on the device. The propagation dX = (sum over out-edges of w_e dZ[v]) W^T is
- * the forward chunk schedule of Section 3.1 run on the chunks of edges clustered by source
- * (the CSR side of the paper's chunk layout), with dZ as the vertex data and W^T as the
- * ApplyVertex matrix; the transposed chunk grid is built at the first such call. dZ is formed
- * on the way in: a vertex interval's rows of dY (and Y with an activation) are copied to the
- * device and turned into dZ in place, and the first time an interval comes by, its rows of A are copied too and
- * its share of dW and dbias is added (interval by interval in a fixed order; with W_self its
- * rows of X come too, for dW_self, and the own partial gradient dZ W_self^T is the second operand
- * pair of the schedule's last product, fed by tiles of dZ formed the same way). Without
- * grads->dX only that backward-ApplyVertex part runs, over tiles of rows. Max and pooled layers
- * take three passes: tiles of rows for backward-ApplyVertex, which also send the gradient of accum
- * out to pinned host memory of the library's own; the chunk schedule over the edges clustered by source, in which rows
- * [A | gradient of accum] travel and the row of the vertex itself (x_u or its pooled row) sits
- * beside the accumulator for the max decision (sum over pooled rows: the gradient of accum travels
- * as plain vertex data; pooled rows are formed again on the device from the interval's rows of X);
- * and per interval, while its sums are on the device, the pooled layers' sigmoid derivative,
- * dW_pool, db_pool and the product dX = dPre W_pool. Gated layers (whose products Ps, M, Pd
- * are formed on the device from the rows of X of the interval that needs them, as in the forward
- * call) take the
- * tile pass, then the schedule over the in-edges (rows [Ps | M] travel, [Pd | gradient of accum]
- * of the resident interval are the constants: dPd, and per interval its share of dW_gate's right
- * half and of db_gate), then the schedule over the edges clustered by source (rows
- * [Pd | gradient of accum] travel, [Ps | M] are the constants, both source-side sums at once; per
- * interval the shares of dW_gate's left half and of dW_msg; the last product is
- * dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd). In these layers a W_self term is handled like in the
- * linear ones: dW_self is added tile by tile with dW, and dZ W_self^T is a second operand pair of
- * the product that ends the last pass (beside the identity for a plain max Gather, W_pool for
- * pooled rows, and appended to dPd W_gd for gated ones). Every transfer goes through the
- * context's device budget like in saga_layer_forward.
+ * Under the max accumulator a tie gives every maximal edge the whole gradient, and A must be
+ * the accum_out of the forward call on the same inputs, or no message will compare equal.
+ *
+ * Streamed calls (a SAGA_MEM_HOST graph, fp32; every layer of the table except max over
+ * GATED): A, Y, dY, grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST
+ * tensors (pinned recommended), the parameters and their gradients stay on the device. Every
+ * transfer goes through the context's device budget like in saga_layer_forward. The passes:
+ *
+ *   layer                  passes
+ *   ---------------------  --------------------------------------------------------------------------------------------
+ *   sum, COPY/MUL_WEIGHT   one: the forward chunk schedule of Section 3.1 on the chunks of edges clustered by source
+ *                          (the CSR side of the paper's chunk layout, built at the first such call), dZ as vertex data,
+ *                          W^T as the ApplyVertex matrix. dZ is formed on the way in (an interval's rows of dY, and of Y
+ *                          with an activation, turned into dZ in place); the first time an interval comes by, its rows
+ *                          of A (and of X with W_self) come too and its share of dW, dbias (dW_self) is added, interval
+ *                          by interval in a fixed order; dZ W_self^T is the second operand pair of the last product.
+ *                          Without grads->dX only this backward-ApplyVertex part runs, over tiles of rows.
+ *   max; POOL              three: tiles of rows for backward-ApplyVertex, which also send dA out to pinned host memory of
+ *                          the library's own; the schedule over the edges clustered by source, in which rows [A | dA]
+ *                          travel and the vertex's own row (x_u, or its pooled row formed on the device from the
+ *                          interval's rows of X) sits beside the accumulator for the max decision (sum over pooled rows:
+ *                          dA travels as plain vertex data); per interval, while its sums are on the device, the
+ *                          sigmoid's slope, dW_pool, db_pool and dX = dPre W_pool.
+ *   sum, GATED             three: the tile pass; the schedule over the in-edges (rows [Ps | M] travel, [Pd | dA] of the
+ *                          resident interval are the constants: dPd, and per interval its share of dW_gate's right half
+ *                          and of db_gate); the schedule over the edges clustered by source (rows [Pd | dA] travel,
+ *                          [Ps | M] are the constants, both source-side sums at once; per interval the shares of
+ *                          dW_gate's left half and of dW_msg; the last product is dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd).
+ *                          Ps, M, Pd are formed on the device from the rows of X of the interval that needs them.
+ *   W_self in the above    dW_self is added tile by tile with dW; dZ W_self^T is a second operand pair of the product
+ *                          that ends the last pass (beside the identity for a plain max Gather, W_pool for pooled rows,
+ *                          appended to dPd W_gd for gated ones).
  *
  * BF16 layers (W in SAGA_BF16; sum over COPY / MUL_WEIGHT messages, with or without W_self,
  * act NONE or RELU): X is needed only with W_self (bf16, like W_self); Y, dY and grads->dX are
  * bf16 like W, A stays the fp32 accum_out of the forward call, parameter gradients are fp32
  * (dW_self = X^T dZ from the rows of X widened to fp32; dZ W_self^T is a second operand pair of
- * the bf16 product that makes dX, which then always follows the propagation). dZ's bf16 values are used as they are; the rows that
- * travel over the edges and the product that makes dX are bf16 with fp32 accumulation and
- * one rounding to bf16 each, like the forward pass; dW and dbias are fp32 products and sums.
+ * the bf16 product that makes dX, which then always follows the propagation). dZ's bf16 values
+ * are used as they are; the rows that travel over the edges and the product that makes dX are
+ * bf16 with fp32 accumulation and one rounding to bf16 each, like the forward pass; dW and
+ * dbias are fp32 products and sums.
  * Sums are deterministic run to run.
  */
 saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_tensor* X,
