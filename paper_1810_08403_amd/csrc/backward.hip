@@ -30,6 +30,7 @@ void transposed_graph_destroy(saga_ctx* ctx, saga_graph* g)
     saga_graph* t = g->tr;
     if (t->grid) chunk_grid_destroy(ctx, t->grid);
     for (DevBuf* b : {&t->d_row_idx, &t->d_items, &t->d_heavy, &t->d_edge_data}) ctx->dev_free(b);
+    hybrid_free(ctx, &t->hyb);
     for (auto& sl : t->saved_lists) {
         ctx->dev_free(&sl.items);
         ctx->dev_free(&sl.heavy);
@@ -636,26 +637,41 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
         ga.op = w_t ? SAGA_EDGE_MUL_WEIGHT : SAGA_EDGE_COPY;
         ga.out16 = out16;
         ga.ld_out16 = ld_out;
-        // run_propagation sets dtype to fp32: give the bf16 view its own few lines
+        // run_propagation sets dtype to fp32: give the bf16 view its own few lines. As in the forward pass, the well-filled
+        // blocks of the adjacency matrix (here of its transpose: sources ranked by out-degree are the rows) go to the
+        // matrix cores where the rows allow it, and the sparse kernel keeps the remainder.
         saga_graph* view = g->tr;
-        if (saga_status e = ensure_work_list(ctx, view, (int64_t)width * 2)) return e;
-        ga.items = static_cast<const WorkItem*>(view->d_items.p);
-        ga.n_items = view->n_items;
-        ga.n_team = view->n_team;
-        ga.row_idx = static_cast<const int32_t*>(view->d_row_idx.p);
+        bool hybrid = hybrid_applies(ctx, width, ld, src);
+        if (hybrid) {
+            if (saga_status e = ensure_hybrid(ctx, view, (int64_t)width * 2)) return e;
+            hybrid = view->hyb.usable;
+        }
+        if (!hybrid)
+            if (saga_status e = ensure_work_list(ctx, view, (int64_t)width * 2)) return e;
+        const HybridDevice& h = view->hyb;
+        ga.items = static_cast<const WorkItem*>(hybrid ? h.items.p : view->d_items.p);
+        ga.n_items = hybrid ? h.n_items : view->n_items;
+        ga.n_team = hybrid ? h.n_team : view->n_team;
+        ga.row_idx = static_cast<const int32_t*>(hybrid ? h.rem_row_idx.p : view->d_row_idx.p);
+        const int64_t n_slots = hybrid ? h.n_slots : view->n_slots, n_heavy = hybrid ? h.n_heavy : view->n_heavy;
         ga.dtype = SAGA_BF16;
         ga.agg = SAGA_AGG_SUM;
         ga.xcd_remap = ctx->opt_xcd_remap;
         ga.mma = ctx->opt_mma;
-        if (view->n_slots > 0) {
-            if (saga_status e = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)view->n_slots * width)) return e;
+        if (n_slots > 0) {
+            if (saga_status e = ctx->dev_alloc(&ctx->ws_partials, sizeof(float) * (size_t)n_slots * width)) return e;
             ga.partials = static_cast<float*>(ctx->ws_partials.p);
         }
+        bool forked = false;
+        if (hybrid)  // the weights in the edge order by source: the view's own copy of attached data, or this call's permuted ones
+            if (saga_status e = hybrid_dense_launch(ctx, view, &ga, w_t != nullptr, w_t, w_t != nullptr && !ep->edge_weight, nullptr, &forked))
+                return e;
         HIP_TRY(ctx, launch_gather(ga, s));
-        if (view->n_heavy > 0) {
+        if (forked) HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->ev_join, 0));
+        if (n_heavy > 0) {
             CombineArgs ca{};
-            ca.heavy = static_cast<const HeavyVertex*>(view->d_heavy.p);
-            ca.n_heavy = view->n_heavy;
+            ca.heavy = static_cast<const HeavyVertex*>(hybrid ? h.heavy.p : view->d_heavy.p);
+            ca.n_heavy = n_heavy;
             ca.partials = ga.partials;
             ca.F = width;
             ca.agg = SAGA_AGG_SUM;

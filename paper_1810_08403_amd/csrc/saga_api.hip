@@ -541,7 +541,7 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
     return SAGA_OK;
 }
 
-static void hybrid_free(saga_ctx* ctx, HybridDevice* h)
+void hybrid_free(saga_ctx* ctx, HybridDevice* h)
 {
     for (DevBuf* b : {&h->chunks, &h->blk_src_tile, &h->blk_e0, &h->blk_tile, &h->de_pos, &h->de_edge, &h->de_w, &h->dt_addr, &h->dt_edge, &h->de_tiles,
                       &h->src_tile_ids, &h->tile_row_slot0,
@@ -561,7 +561,7 @@ static HybridParams hybrid_params(const saga_ctx* ctx)
 
 // The dense-block form of a resident graph for rows of `row_bytes` (the remainder's work list depends on the row width
 // like any other): built on the host at the first call that can use it, kept in the graph handle.
-static saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
 {
     HybridDevice& h = g->hyb;
     WorkListParams p = work_list_params(ctx, row_bytes);
@@ -644,6 +644,80 @@ static saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes
     h.n_slots = wl.n_slots;
     h.weights_state = 0;
     h.usable = true;
+    return SAGA_OK;
+}
+
+bool hybrid_applies(const saga_ctx* ctx, int32_t F, int64_t ld, const void* rows)
+{
+    return ctx->opt_dense_blocks && ctx->opt_fused && !ctx->opt_team && !ctx->opt_mma && F % 128 == 0 && ld % 8 == 0 &&
+           (reinterpret_cast<uintptr_t>(rows) & 15u) == 0;
+}
+
+// The dense-block half of a bf16 sum propagation over `view` (the graph, or its edge order by source), whose plan
+// ensure_hybrid has built. ga carries the rows (src, ld_src, F) and the partial rows; on return it reads the remainder's
+// weights. The edge data in the two orders the kernels read them (block by block as two-part bf16, and in the
+// remainder's edge order) are packed here: attached data (`w_attached`: w_src is the view's own copy, which
+// saga_graph_set_edge_data invalidates) once, data passed with the call every call, COPY packs ones once.
+// *forked: the kernel went to the context's second stream and the caller waits for ev_join after its own launch.
+saga_status hybrid_dense_launch(saga_ctx* ctx, saga_graph* view, GatherArgs* ga, bool weighted, const float* w_src, bool w_attached,
+                                saga_ctx::EventSet* es, bool* forked)
+{
+    hipStream_t s = ctx->stream;
+    HybridDevice& h = view->hyb;
+    *forked = false;
+    const int want_state = !weighted ? 2 : (w_attached ? 1 : 0);
+    if (want_state == 0 || h.weights_state != want_state) {
+        PackArgs pa{};
+        pa.w = w_src;
+        pa.de_edge = static_cast<const int32_t*>(h.de_edge.p);
+        pa.n_list = h.n_list_edges;
+        pa.de_w = static_cast<uint32_t*>(h.de_w.p);
+        pa.dt_edge = static_cast<const int32_t*>(h.dt_edge.p);
+        pa.dt_addr = static_cast<const int32_t*>(h.dt_addr.p);
+        pa.n_tile = h.n_tile_edges;
+        pa.de_tiles = static_cast<uint16_t*>(h.de_tiles.p);
+        pa.rem_edge = static_cast<const int32_t*>(h.rem_edge.p);
+        pa.n_rem = weighted ? h.n_rem_edges : 0;
+        pa.rem_w = static_cast<float*>(h.rem_w.p);
+        HIP_TRY(ctx, launch_pack_hybrid_weights(pa, s));
+        h.weights_state = want_state;
+    }
+    if (weighted) ga->edge_w = static_cast<const float*>(h.rem_w.p);
+    DenseArgs da{};
+    da.chunks = static_cast<const DenseChunk*>(h.chunks.p);
+    da.n_chunks = h.n_chunks;
+    da.blk_src_tile = static_cast<const int32_t*>(h.blk_src_tile.p);
+    da.blk_e0 = static_cast<const int32_t*>(h.blk_e0.p);
+    da.blk_tile = static_cast<const int32_t*>(h.blk_tile.p);
+    da.de_tiles = static_cast<const uint16_t*>(h.de_tiles.p);
+    da.de_pos = static_cast<const uint16_t*>(h.de_pos.p);
+    da.de_w = static_cast<const uint32_t*>(h.de_w.p);
+    da.src_tile_ids = static_cast<const int32_t*>(h.src_tile_ids.p);
+    da.tile_row_slot0 = static_cast<const int32_t*>(h.tile_row_slot0.p);
+    da.X = static_cast<const uint16_t*>(ga->src);
+    da.ld = ga->ld_src;
+    da.F = ga->F;
+    da.use_low = weighted ? 1 : 0;
+    da.partials = ga->partials;
+    if (ctx->opt_dense_overlap && !ctx->arena_active) {
+        if (!ctx->s_dense) {
+            HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->s_dense, hipStreamNonBlocking));
+            HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+            HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
+        }
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, s));
+        HIP_TRY(ctx, hipStreamWaitEvent(ctx->s_dense, ctx->ev_fork, 0));
+        HIP_TRY(ctx, launch_dense_blocks(da, ctx->s_dense));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->s_dense));
+        *forked = true;
+    } else {
+        HIP_TRY(ctx, launch_dense_blocks(da, s));
+        if (es) {
+            HIP_TRY(ctx, hipEventRecord(es->ev_dense, s));
+            es->has_dense = true;
+        }
+    }
+    if (es) es->n_gather_launches = 2;
     return SAGA_OK;
 }
 
@@ -1280,6 +1354,7 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* w)
     }
     g->tr_edge_data_valid = false;
     if (g->hyb.weights_state == 1) g->hyb.weights_state = 0;  // the dense-block form packs the new data at its next call
+    if (g->tr && g->tr->hyb.weights_state == 1) g->tr->hyb.weights_state = 0;
     if (saga_status st = ctx->dev_alloc(&g->d_edge_data, sizeof(float) * (size_t)std::max<int64_t>(g->nnz, 1))) return st;
     if (g->nnz > 0) {
         HIP_TRY(ctx, hipMemcpyAsync(g->d_edge_data.p, w, sizeof(float) * (size_t)g->nnz, hipMemcpyDeviceToDevice, ctx->stream));
@@ -1322,9 +1397,8 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     // sparse kernel keeps the remainder (rows of a multiple of 128 features, 16-byte aligned: what the dense kernel loads)
     const int32_t Fg = tf ? Fo_tf : Fm;  // width of the rows the propagation moves
     const int64_t ld_g = tf ? (int64_t)Fo_tf : X->ld;
-    bool hybrid = ctx->opt_dense_blocks && ctx->opt_fused && !ctx->opt_team && !ctx->opt_mma && bf16 && agg == SAGA_AGG_SUM &&
-                  (ep->op == SAGA_EDGE_COPY || ep->op == SAGA_EDGE_MUL_WEIGHT) && Fg % 128 == 0 && ld_g % 8 == 0 &&
-                  (tf || (reinterpret_cast<uintptr_t>(X->data) & 15u) == 0);
+    bool hybrid = bf16 && agg == SAGA_AGG_SUM && (ep->op == SAGA_EDGE_COPY || ep->op == SAGA_EDGE_MUL_WEIGHT) &&
+                  hybrid_applies(ctx, Fg, ld_g, tf ? nullptr : X->data);
     if (hybrid) {
         if (saga_status st = ensure_hybrid(ctx, g, row_bytes)) return st;
         hybrid = g->hyb.usable;
@@ -1451,64 +1525,9 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     }
     bool dense_forked = false;
     if (hybrid) {
-        HybridDevice& h = g->hyb;
-        // The edge data in the two orders the kernels read them: block by block as two-part bf16, and in the remainder's
-        // edge order. Attached data are packed once; data passed with the call are packed every call; COPY packs ones.
         const bool weighted = ep->op == SAGA_EDGE_MUL_WEIGHT;
         const float* w_src = !weighted ? nullptr : (ep->edge_weight ? ep->edge_weight : static_cast<const float*>(g->d_edge_data.p));
-        const int want_state = !weighted ? 2 : (ep->edge_weight ? 0 : 1);
-        if (want_state == 0 || h.weights_state != want_state) {
-            PackArgs pa{};
-            pa.w = w_src;
-            pa.de_edge = static_cast<const int32_t*>(h.de_edge.p);
-            pa.n_list = h.n_list_edges;
-            pa.de_w = static_cast<uint32_t*>(h.de_w.p);
-            pa.dt_edge = static_cast<const int32_t*>(h.dt_edge.p);
-            pa.dt_addr = static_cast<const int32_t*>(h.dt_addr.p);
-            pa.n_tile = h.n_tile_edges;
-            pa.de_tiles = static_cast<uint16_t*>(h.de_tiles.p);
-            pa.rem_edge = static_cast<const int32_t*>(h.rem_edge.p);
-            pa.n_rem = weighted ? h.n_rem_edges : 0;
-            pa.rem_w = static_cast<float*>(h.rem_w.p);
-            HIP_TRY(ctx, launch_pack_hybrid_weights(pa, s));
-            h.weights_state = want_state;
-        }
-        if (weighted) ga.edge_w = static_cast<const float*>(h.rem_w.p);
-        DenseArgs da{};
-        da.chunks = static_cast<const DenseChunk*>(h.chunks.p);
-        da.n_chunks = h.n_chunks;
-        da.blk_src_tile = static_cast<const int32_t*>(h.blk_src_tile.p);
-        da.blk_e0 = static_cast<const int32_t*>(h.blk_e0.p);
-        da.blk_tile = static_cast<const int32_t*>(h.blk_tile.p);
-        da.de_tiles = static_cast<const uint16_t*>(h.de_tiles.p);
-        da.de_pos = static_cast<const uint16_t*>(h.de_pos.p);
-        da.de_w = static_cast<const uint32_t*>(h.de_w.p);
-        da.src_tile_ids = static_cast<const int32_t*>(h.src_tile_ids.p);
-        da.tile_row_slot0 = static_cast<const int32_t*>(h.tile_row_slot0.p);
-        da.X = static_cast<const uint16_t*>(ga.src);
-        da.ld = ga.ld_src;
-        da.F = ga.F;
-        da.use_low = weighted ? 1 : 0;
-        da.partials = ga.partials;
-        if (ctx->opt_dense_overlap && !ctx->arena_active) {
-            if (!ctx->s_dense) {
-                HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->s_dense, hipStreamNonBlocking));
-                HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
-                HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
-            }
-            HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, s));
-            HIP_TRY(ctx, hipStreamWaitEvent(ctx->s_dense, ctx->ev_fork, 0));
-            HIP_TRY(ctx, launch_dense_blocks(da, ctx->s_dense));
-            HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->s_dense));
-            dense_forked = true;
-        } else {
-            HIP_TRY(ctx, launch_dense_blocks(da, s));
-            if (es) {
-                HIP_TRY(ctx, hipEventRecord(es->ev_dense, s));
-                es->has_dense = true;
-            }
-        }
-        if (es) es->n_gather_launches = 2;
+        if (saga_status st = hybrid_dense_launch(ctx, g, &ga, weighted, w_src, weighted && !ep->edge_weight, es, &dense_forked)) return st;
     }
     if (!ctx->opt_fused) {
         // the baseline of Section 6.2: the stages one by one through a materialised per-edge tensor, which the fused

@@ -444,6 +444,16 @@ struct GemmArgs {
     int32_t act;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+// The dense-block form of a bf16 sum propagation (hybrid.hip) over one edge order of a graph: the plan and its device
+// copy (ensure_hybrid; view->hyb.usable says whether the graph has blocks worth it), whether a call qualifies
+// (hybrid_applies: options, rows of a multiple of 128 bf16 values, 16-byte aligned), the launch of the dense half
+// (hybrid_dense_launch) and the release of the plan.
+saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* view, int64_t row_bytes);
+bool hybrid_applies(const saga_ctx* ctx, int32_t F, int64_t ld, const void* rows);
+saga_status hybrid_dense_launch(saga_ctx* ctx, saga_graph* view, GatherArgs* ga, bool weighted, const float* w_src, bool w_attached,
+                                saga_ctx::EventSet* es, bool* forked);
+void hybrid_free(saga_ctx* ctx, HybridDevice* h);
+
 // Size (elements) of a padded Bt for N x K.
 void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_t* k_pad);
 // Bt[n][col0 + k] = W[k][n] for n < N, k < K (W is K x N row-major with ldw). Writes only those

@@ -345,3 +345,28 @@ def test_apply_vertex_product_at_ragged_shapes(ctx, dtype):
         ref = torch.relu(X.double() @ W.double() + b.double())
         assert_sum_close(Y.float().cpu().numpy(), ref.numpy(), Zabs.numpy(), tol, f"product {n} x {K} x {N} {dtype}")
     graph.destroy()
+
+
+def test_apply_vertex_product_at_layer_widths_over_many_rows(ctx):
+    """fp32 products with K = 32 ... 128 over some 37,000 rows (the shapes of the hoisted products and of ApplyVertex in the
+    128-wide applications: every workgroup walks several output tiles). ApplyVertex alone on a graph of self-loops, as
+    above: a row count that ends inside a tile, N below, at and above the 32-column slices and 128-column tiles, with and
+    without bias, all three activations."""
+    n = 32768 + 4096 + 19
+    idx = torch.arange(n, dtype=torch.int64)
+    g = si.build_csc(n, idx, idx)
+    graph = make_graph(ctx, g)
+    cases = [(32, 1, "relu", True), (64, 40, "none", False), (96, 128, "sigmoid", True), (128, 129, "relu", True), (128, 384, "none", True),
+             (128, 200, "relu", False), (64, 32, "relu", True), (128, 512, "relu", True), (100, 128, "relu", True)]
+    for K, N, act, with_b in cases:
+        X = si.normal_features(n, K, 100 + K)
+        W = si.glorot_uniform(K, N, 200 + N)
+        b = si.uniform_pm(N, 0.5, 300 + N) if with_b else None
+        Y = torch.full((n, N), float("nan"), device="cuda")
+        ctx.layer_forward(graph, X.cuda(), Y, edge_op="copy", W=W.cuda(), bias=None if b is None else b.cuda(), act=act)
+        torch.cuda.synchronize()
+        Z = X.double() @ W.double() + (0 if b is None else b.double())
+        Zabs = X.double().abs() @ W.double().abs() + (0 if b is None else b.double().abs())
+        ref = {"relu": torch.relu, "sigmoid": torch.sigmoid, "none": lambda t: t}[act](Z)
+        assert_sum_close(Y.cpu().numpy(), ref.numpy(), Zabs.numpy(), TOL_F32, f"product {n} x {K} x {N} {act}")
+    graph.destroy()
