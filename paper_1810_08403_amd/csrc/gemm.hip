@@ -284,6 +284,132 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(T) =
     }
 }
 
+// ---------------------------------------------------------------------------
+// fp32 products with K = 128 (the layer width of the gated, CommNet and max-pooling applications: their hoisted
+// per-vertex products and ApplyVertex) with the weights resident in LDS. A workgroup owns 128 columns: their rows of Bt
+// (64 KiB) are brought into LDS once; then it walks 64-row tiles of A, each copied from memory straight into one of two
+// 32 KiB LDS buffers (global_load_lds: no registers, no store instructions) while the previous tile is multiplied. One
+// barrier per tile, 64 MFMAs (4,096 cycles) per wavefront between two barriers; the results of a tile are written out
+// after the barrier and complete under the MFMAs of the next tile. A wave-wide copy lands as 1 KiB of consecutive LDS
+// bytes, so rows cannot be padded; instead the 16-byte chunks of a row are stored permuted (chunk c of row r at position
+// c ^ (r & 15)), which spreads the operand reads of 16 consecutive rows over all banks. One workgroup of eight
+// wavefronts per compute unit (128 KiB of LDS), two wavefronts per SIMD, each with one 32 x 32 accumulator tile (four
+// wavefronts with two tiles each, one per SIMD, were slower: 94 against 100 TFLOP/s on 1,048,576 x 128 x 384).
+// ---------------------------------------------------------------------------
+constexpr int kWldsK = 128, kWldsBM = 64, kWldsBN = 128;
+
+template <bool CHECK>
+__device__ __forceinline__ void wlds_store(const GemmArgs& a, const floatx16& acc, int64_t row0, int col, float bias)
+{
+    float* __restrict__ C = static_cast<float*>(a.C);
+    if (CHECK && col >= a.N) return;
+    float* p = C + row0 * a.ldc + col;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int dr = (r >> 2) * 8 + (r & 3);
+        if (CHECK && row0 + dr >= a.M) continue;
+        float y = acc[r] + bias;
+        if (a.act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
+        if (a.act == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
+        p[dr * a.ldc] = y;
+    }
+}
+
+__global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n_cg, const int wg_per_cg, const int n_tiles_m)
+{
+    // three separate arrays: the compiler makes an LDS read wait for the copies in flight (they count as memory
+    // operations that write LDS) unless it can tell that they go to another array than the one being read
+    __shared__ __attribute__((aligned(16))) float Bs[kWldsBN * kWldsK];
+    __shared__ __attribute__((aligned(16))) float As0[kWldsBM * kWldsK];
+    __shared__ __attribute__((aligned(16))) float As1[kWldsBM * kWldsK];
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int wm = wave & 1, wn = wave >> 1;
+    // blockIdx = ((j / 8) * n_cg + cg) * 8 + j % 8: workgroup j of every column group on XCD j % 8, so that the column
+    // groups that read the same rows of A at the same time share them in one L2
+    const int cg = (int)((blockIdx.x >> 3) % (unsigned)n_cg);
+    const int j = (int)((blockIdx.x >> 3) / (unsigned)n_cg) * 8 + (int)(blockIdx.x & 7);
+    if (j >= n_tiles_m) return;
+    const int count = (n_tiles_m - j + wg_per_cg - 1) / wg_per_cg;  // tiles j, j + wg_per_cg, ...
+    const float* __restrict__ A = static_cast<const float*>(a.A);
+    const float* __restrict__ Bt = static_cast<const float*>(a.Bt);
+
+    // a wave-wide copy: rows 2 idx and 2 idx + 1 of a tile, lane l the chunk that belongs at position l & 31 of row
+    // 2 idx + (l >> 5), i.e. chunk (l & 31) ^ (row & 15) of the row in memory. A wavefront makes eight per tile.
+    const int crow = lane >> 5, cpos = lane & 31;
+    auto copy_one = [&](int tile, float (&buf)[kWldsBM * kWldsK], int i) {
+        const int idx = wave * 4 + i, row = 2 * idx + crow;
+        int64_t gr = (int64_t)tile * kWldsBM + row;
+        if (gr >= a.M) gr = a.M - 1;  // rows past the end are copies of the last row; their results are not stored
+        const float* src = A + gr * a.lda + ((cpos ^ (row & 15)) << 2);
+        __builtin_amdgcn_global_load_lds(src, (lds_ptr)(&buf[idx * 256]), 16, 0, 0);
+    };
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int idx = wave * 8 + i, row = 2 * idx + crow;
+        const float* src = Bt + (int64_t)(cg * kWldsBN + row) * a.ldbt + ((cpos ^ (row & 15)) << 2);  // Bt is padded to 128 rows
+        __builtin_amdgcn_global_load_lds(src, (lds_ptr)(&Bs[idx * 256]), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) copy_one(j, As0, i);
+    const int col0 = cg * kWldsBN + wn * 32 + m;
+    const float bias = (a.bias && col0 < a.N) ? a.bias[col0] : 0.f;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's copies have landed
+    __syncthreads();
+
+    // operand addresses: row r of a buffer, chunk 2 s + h at position (2 s + h) ^ (r & 15); r & 15 == m & 15 for both operands
+    const int ra = (wm * 32 + m) * kWldsK;
+    const int rb0 = (wn * 32 + m) * kWldsK;
+    const int sw = m & 15;
+    // One tile: the next one's copies first, then 16 steps of three operand reads (requested a step ahead) and eight
+    // MFMAs; the wait for the copies, the barrier, and the write-out, which the hardware completes under the next
+    // tile's MFMAs. (Spreading the copies and the previous tile's write-out, from a second accumulator set, between
+    // the MFMAs of the steps was slower: 1.28 against 1.11 ms on 1,048,576 x 128 x 384.)
+    auto do_tile = [&](int t, const float (&cur)[kWldsBM * kWldsK], float (&nxt)[kWldsBM * kWldsK]) {
+        const int tile = j + t * wg_per_cg;
+        if (t + 1 < count) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) copy_one(tile + wg_per_cg, nxt, i);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the copies start before the MFMAs they run under
+        floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        u32x4 fa, fb0;
+        auto fetch = [&](int s_, u32x4& xa, u32x4& xb0) {
+            const int pos = ((2 * s_ + h) ^ sw) << 2;
+            xa = *reinterpret_cast<const u32x4*>(&cur[ra + pos]);
+            xb0 = *reinterpret_cast<const u32x4*>(&Bs[rb0 + pos]);
+        };
+        fetch(0, fa, fb0);
+#pragma unroll
+        for (int s_ = 0; s_ < kWldsK / 8; ++s_) {
+            u32x4 na = fa, nb0 = fb0;
+            if (s_ + 1 < kWldsK / 8) fetch(s_ + 1, na, nb0);
+            __builtin_amdgcn_sched_barrier(0);  // the next step's reads are on their way while this step multiplies
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c]), __uint_as_float(fb0[c]), acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            fa = na;
+            fb0 = nb0;
+        }
+        // the next tile's copies (and the previous tile's stores) were issued a whole tile ago
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();  // every wavefront is done with this buffer, and sees the next one
+        const int64_t row0 = (int64_t)tile * kWldsBM + wm * 32 + h * 4;
+        if ((int64_t)tile * kWldsBM + kWldsBM <= a.M && cg * kWldsBN + kWldsBN <= a.N)
+            wlds_store<false>(a, acc, row0, col0, bias);
+        else
+            wlds_store<true>(a, acc, row0, col0, bias);
+    };
+    for (int t = 0; t < count; t += 2) {
+        do_tile(t, As0, As1);
+        if (t + 1 < count) do_tile(t + 1, As1, As0);
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_pack_bt_transpose(const T* W, int64_t ldw, int K, int N, T* Bt, int64_t ldbt, int64_t col0)
 {
@@ -356,12 +482,29 @@ void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_
     *k_pad = ((int64_t)K + kt - 1) / kt * kt;
 }
 
+// the weights-in-LDS kernel where it applies (fp32, one operand, K = 128, rows in 16-byte fragments, enough rows to give
+// every compute unit several tiles); false: not applicable
+static bool launch_wlds(const GemmArgs& a, hipStream_t s, hipError_t* err)
+{
+    if (a.A2 || a.K != kWldsK || a.lda % 4 != 0 || (reinterpret_cast<uintptr_t>(a.A) & 15u) || a.M < 16 * 1024) return false;
+    if (a.ldbt % 4 != 0 || a.ldbt < kWldsK || (reinterpret_cast<uintptr_t>(a.Bt) & 15u)) return false;
+    const int n_cg = (a.N + kWldsBN - 1) / kWldsBN;
+    const int64_t n_tiles_m = (a.M + kWldsBM - 1) / kWldsBM;
+    if (n_cg > 32 || n_tiles_m > 0x7fffffffLL) return false;
+    const int wg_per_cg = std::max(8, 256 / n_cg / 8 * 8);  // one workgroup per compute unit, a multiple of the 8 XCDs per column group
+    hipLaunchKernelGGL(k_gemm_wlds, dim3((unsigned)(wg_per_cg * n_cg)), dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    *err = hipGetLastError();
+    return true;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (a.K <= 0 || (a.A2 && a.K2 <= 0)) return hipErrorInvalidValue;
     if (a.dtype == SAGA_F32) {
         if (a.out_dtype != SAGA_F32) return hipErrorInvalidValue;
+        hipError_t e = hipSuccess;
+        if (launch_wlds(a, s, &e)) return e;
         return launch_typed<float, float>(a, s);
     }
     if (a.out_dtype == SAGA_F32) return launch_typed<uint16_t, float>(a, s);
