@@ -216,6 +216,55 @@ def test_random_gated_and_max_backward_case(seed):
 
 
 @pytest.mark.parametrize("seed", range(max(12, N_CASES // 6)))
+def test_random_gated_max_backward_case(seed):
+    """Max over gated messages backwards on random small graphs and widths. X and the gate's parameters sit on coarse
+    grids (multiples of 1/4 and 1/8), so that the hoisted products are exact in fp32 and the GPU's fp32 messages and the
+    oracle's fp64 ones rank alike, ties included; the Gather output handed to the backward pass is the forward pass's own;
+    the stored output is synthetic (only the activation's derivative is taken from it) and the oracle gets the same dZ."""
+    rng, g, F, Fo, _, _, _, _ = _case(1700 + seed)
+    F = min(F, 96)
+    n = g.n
+    act = ["none", "relu", "sigmoid", "relu"][seed % 4]
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    q = lambda x, lim, k: torch.round(x.clamp(-lim, lim) * k) / k
+    X, W, dY = q(t(n, F), 1.0, 4), t(F, Fo, s=0.3), t(n, Fo)
+    sc = 1.5 / max(F, 1) ** 0.5
+    Wg, bg = q(t(F, 2 * F, s=sc), 1.0, 8), q(t(F, s=0.3), 0.5, 8)
+    Wm = q(t(F, F, s=sc), 1.0, 8) if seed % 3 != 1 else None
+    Ws = t(F, Fo, s=0.3) if seed % 5 < 2 else None
+    z = (X.double() @ Wg[:, :F].double().T).abs().max() + (X.double() @ Wg[:, F:].double().T).abs().max() + 0.5
+    assert z.item() <= 14.0
+    Y_in = t(n, Fo)
+    if act == "sigmoid":
+        Y_in = torch.sigmoid(Y_in)
+    slope = {"none": torch.ones(n, Fo, dtype=torch.float64), "relu": (Y_in > 0).double(), "sigmoid": Y_in.double() * (1 - Y_in.double())}[act]
+    dZ = (dY.double() * slope).float()
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    opt = lambda v: None if v is None else v.cuda()
+    npo = lambda v: None if v is None else v.numpy()
+    bwd = oracle.gated_backward(cp, ri, X.numpy(), None, dZ.numpy(), W.numpy(), W_gate=Wg.numpy(), b_gate=bg.numpy(), W_msg=npo(Wm), act="none",
+                                W_self=npo(Ws), agg="max")
+    nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+    with new_context() as c:
+        graph = c.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
+        what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {act} msg={Wm is not None} self={Ws is not None}"
+        A, Yf = nan(n, F), nan(n, Fo)
+        c.layer_forward(graph, X.cuda(), Yf, edge_op="gated", agg="max", W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=opt(Wm), W=W.cuda(), W_self=opt(Ws),
+                        act="none", accum_out=A)
+        assert_sum_close(A.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " A", tiny_outputs=True)
+        out = dict(dX=nan(n, F), dW=nan(F, Fo), dW_gate=nan(F, 2 * F), db_gate=nan(F), dW_msg=nan(F, F) if Wm is not None else None,
+                   dW_self=nan(F, Fo) if Ws is not None else None)
+        c.layer_backward(graph, A, dY.cuda(), W.cuda(), out["dW"], X=X.cuda(), Y=Y_in.cuda(), edge_op="gated", agg="max", act=act, dX=out["dX"],
+                         W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=opt(Wm), dW_gate=out["dW_gate"], db_gate=out["db_gate"], dW_msg=out["dW_msg"],
+                         W_self=opt(Ws), dW_self=out["dW_self"])
+        torch.cuda.synchronize()
+        for name, v in out.items():
+            if v is not None:
+                assert_sum_close(v.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + " " + name, tiny_outputs=True)
+        graph.destroy()
+
+
+@pytest.mark.parametrize("seed", range(max(12, N_CASES // 6)))
 def test_random_pooled_max_backward_case(seed):
     """Figure 11's layer backwards on the device: max over pooled messages, random widths, with saturated units among
     them (the slope of a sigmoid near 0 or 1 must keep its relative accuracy)."""
