@@ -78,6 +78,7 @@ def main():
     ap.add_argument("--split", type=int, default=None, help="work-list tunable (see saga_set_option)")
     ap.add_argument("--cut-degree", type=int, default=None)
     ap.add_argument("--stripe-kb", type=int, default=None)
+    ap.add_argument("--piece-order", type=int, default=None, help="0: pieces by first band and column (library option piece_order)")
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--team", type=int, default=None)
     ap.add_argument("--mma", type=int, default=None, help="1: bf16 sums accumulate on the matrix unit (library option mma)")
@@ -152,7 +153,7 @@ def main():
 
     ctx = saga.Context(0)
     for name, val in (("split", args.split), ("cut_degree", args.cut_degree), ("stripe_kb", args.stripe_kb),
-                      ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first),
+                      ("piece_order", args.piece_order), ("xcd_remap", args.xcd_remap), ("team", args.team), ("mma", args.mma), ("transform_first", args.transform_first),
                       ("dense_blocks", args.dense_blocks), ("dense_min_edges", args.dense_min_edges), ("dense_tile_gain", args.dense_tile_gain),
                       ("dense_chunk", args.dense_chunk), ("dense_overlap", args.dense_overlap), ("fused", 0 if args.unfused else None)):
         if val is not None:

@@ -338,11 +338,16 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
 
 /* Tunables, for measurement. They shape the work list, which is (re)built at the next
  * saga_layer_forward that finds them changed:
- *   "split"      minimum edges in one piece of a cut column (default 64)
+ *   "split"      minimum edges in one piece of a cut column (default 64; until the caller sets it, layers whose
+ *                propagation writes rows of fewer than 512 features use 32)
  *   "cut_degree" columns with more in-edges than this are cut (default 0 = 2 * split)
  *   "stripe_kb"  pieces end where the source rows cross a multiple of this many KiB of
  *                feature rows, and pieces are processed band by band (default 1024;
  *                0 = cut by edge count only)
+ *   "piece_order" 0/1 (default 1): the order of the pieces inside the list. 0: by the band of a piece's
+ *                first source, then by column. 1: by the band of its first source, then the band of its last
+ *                one, then by column, so that the pieces that run at the same time reach over the same rows.
+ *                Results do not depend on it.
  *   "team"       0/1, a piece of a cut column is worked by a whole workgroup whose four
  *                wavefronts reduce through LDS, and holds at least 4 * split edges (default 0:
  *                fewer partial rows, but measured slower than one wavefront per piece)

@@ -109,7 +109,7 @@ static saga_status ensure_transposed(saga_ctx* ctx, saga_graph* g)
 static saga_status run_propagation(saga_ctx* ctx, saga_graph* view, GatherArgs ga, int64_t row_bytes)
 {
     hipStream_t s = ctx->stream;
-    if (saga_status st = ensure_work_list(ctx, view, row_bytes)) return st;
+    if (saga_status st = ensure_work_list(ctx, view, row_bytes, ga.F)) return st;
     ga.items = static_cast<const WorkItem*>(view->d_items.p);
     ga.n_items = view->n_items;
     ga.n_team = view->n_team;
@@ -643,11 +643,11 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
         saga_graph* view = g->tr;
         bool hybrid = hybrid_applies(ctx, width, ld, src);
         if (hybrid) {
-            if (saga_status e = ensure_hybrid(ctx, view, (int64_t)width * 2)) return e;
+            if (saga_status e = ensure_hybrid(ctx, view, (int64_t)width * 2, width)) return e;
             hybrid = view->hyb.usable;
         }
         if (!hybrid)
-            if (saga_status e = ensure_work_list(ctx, view, (int64_t)width * 2)) return e;
+            if (saga_status e = ensure_work_list(ctx, view, (int64_t)width * 2, width)) return e;
         const HybridDevice& h = view->hyb;
         ga.items = static_cast<const WorkItem*>(hybrid ? h.items.p : view->d_items.p);
         ga.n_items = hybrid ? h.n_items : view->n_items;

@@ -134,8 +134,14 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
     out->max_degree = 0;
     std::vector<WorkItem> whole;
     whole.reserve((size_t)n_cols);
+    // A piece's place in the list: the band of its first source, then the band of its last one, then its column. The
+    // wavefronts that run at the same time take neighbouring pieces; a piece of a column with few edges per band reaches
+    // over many bands, and with the pieces of one first band in column order a band's rows were shared with pieces that
+    // reach anywhere between one band and fifty further. Next to pieces with the same reach the window of rows the
+    // neighbours read is the same one (an LRU model of the L2s that reproduces the measured miss rate of the remainder of
+    // the R-MAT 18 workload, 27 %, gives 17 % for this order; order 0 is the old one).
     struct Piece {
-        int64_t key;  // (first stripe, vertex)
+        int64_t first, last;  // stripes
         WorkItem it;
     };
     std::vector<Piece> pieces;
@@ -172,7 +178,8 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
             }
             if (e - q < min_piece / 2) q = e;  // do not leave a sliver behind
             const int64_t stripe = R > 0 ? (int64_t)row_idx[pos] / R : (pos - b) / min_piece;
-            pieces.push_back(Piece{stripe * n_cols + v, WorkItem{(int32_t)v, (int32_t)pos, (int32_t)q, -1}});
+            const int64_t last = (R > 0 && p.order == 1) ? (int64_t)row_idx[q - 1] / R : 0;
+            pieces.push_back(Piece{stripe, last, WorkItem{(int32_t)v, (int32_t)pos, (int32_t)q, -1}});
             pos = q;
         }
         const size_t n_p = pieces.size() - first_piece;
@@ -196,7 +203,12 @@ void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_c
         for (size_t i = 0; i < n_p; ++i) pieces[first_piece + i].it.slot = (int32_t)(out->n_slots++);
         out->heavy.push_back(h);
     }
-    std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.key < b.key; });
+    std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) {
+        if (a.first != b.first) return a.first < b.first;
+        if (a.last != b.last) return a.last < b.last;
+        if (a.it.v != b.it.v) return a.it.v < b.it.v;
+        return a.it.e0 < b.it.e0;
+    });
     out->items.reserve(pieces.size() + whole.size());
     for (const Piece& pc : pieces) out->items.push_back(pc.it);
     out->n_team = team > 1 ? (int64_t)pieces.size() : 0;
@@ -465,22 +477,28 @@ static int64_t pow2_floor(int64_t x)
     return p;
 }
 
-WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes)
+WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes, int32_t width)
 {
     WorkListParams p;
     p.min_edges = ctx->opt_split;
-    p.cut_degree = ctx->opt_cut_degree > 0 ? ctx->opt_cut_degree : 2 * ctx->opt_split;
+    // A piece costs one partial row written and read again (8 bytes per feature) on top of the rows it gathers. Where the
+    // caller has not chosen, narrow outputs get finer pieces: measured with 128 fp32 features (512-byte partial rows, the
+    // gated layer on R-MAT 20: 4.06 ms at 64 edges, 3.93 at 32, 4.01 at 16; CommNet 2.09 / 2.05 / 2.15) against 64 for
+    // the 2 KiB partial rows of the R-MAT 18 workload (4.45 ms at 64, 4.57 at 48, 4.86 at 32, 4.71 at 80).
+    if (!ctx->opt_split_set && width > 0 && width * 4 < 2048) p.min_edges = 32;
+    p.cut_degree = ctx->opt_cut_degree > 0 ? ctx->opt_cut_degree : 2 * p.min_edges;
     p.stripe_rows = 0;
     if (ctx->opt_stripe_kb > 0) p.stripe_rows = std::max<int64_t>(64, pow2_floor(ctx->opt_stripe_kb * 1024 / std::max<int64_t>(row_bytes, 1)));
     p.team = ctx->opt_team ? 4 : 1;
+    p.order = ctx->opt_piece_order;
     return p;
 }
 
-saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width)
 {
-    const WorkListParams p = work_list_params(ctx, row_bytes);
+    const WorkListParams p = work_list_params(ctx, row_bytes, width);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
-        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team;
+        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team && a.order == b.order;
     };
     if (same(p, g->list_params)) return SAGA_OK;
     if (ctx->arena_active)
@@ -495,7 +513,7 @@ saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
         g->saved_lists.push_back(saga_graph::SavedList{g->list_params, g->d_items, g->d_heavy, g->n_items, g->n_team, g->n_heavy, g->n_slots});
         g->d_items = DevBuf{};
         g->d_heavy = DevBuf{};
-        g->list_params = WorkListParams{-1, -1, -1, false, 1};
+        g->list_params = WorkListParams{-1, -1, -1, false, 1, 1};
     }
     for (size_t i = 0; i < g->saved_lists.size(); ++i) {
         if (!same(p, g->saved_lists[i].params)) continue;
@@ -561,19 +579,16 @@ static HybridParams hybrid_params(const saga_ctx* ctx)
 
 // The dense-block form of a resident graph for rows of `row_bytes` (the remainder's work list depends on the row width
 // like any other): built on the host at the first call that can use it, kept in the graph handle.
-saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes)
+saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width)
 {
     HybridDevice& h = g->hyb;
-    WorkListParams p = work_list_params(ctx, row_bytes);
-    if (!ctx->opt_split_set) {
-        // what is left of the heavy columns once their full blocks are gone is worth cutting finer: measured on the R-MAT 18
-        // workload, pieces of at least 48 edges (gather 4.29 + combine 0.51 ms) against 64 (4.69 + 0.40) and 32 (4.15 + 0.71)
-        p.min_edges = 48;
-        if (ctx->opt_cut_degree == 0) p.cut_degree = 96;
-    }
+    // The remainder keeps the general piece size at any width: its columns have lost their heavy blocks, and finer pieces
+    // cost more than they spread (backward pass of the R-MAT 18 workload, 128 bf16 features: 3.65 ms at 64, 3.98 at 32).
+    (void)width;
+    WorkListParams p = work_list_params(ctx, row_bytes, 0);
     const HybridParams hp = hybrid_params(ctx);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
-        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team;
+        return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team && a.order == b.order;
     };
     if (h.built && same(p, h.list_params) && hp.min_block_edges == h.hp.min_block_edges && hp.min_tile_gain == h.hp.min_tile_gain &&
         hp.max_chunk_blocks == h.hp.max_chunk_blocks)
@@ -1125,6 +1140,9 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "stripe_kb")) {
         if (value < 0 || value > (1 << 22)) return ctx->fail(SAGA_ERR_INVALID_ARG, "stripe_kb must be in [0, 2^22]");
         ctx->opt_stripe_kb = value;
+    } else if (!strcmp(name, "piece_order")) {
+        if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "piece_order must be 0 or 1");
+        ctx->opt_piece_order = (int)value;
     } else if (!strcmp(name, "team")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "team must be 0 or 1");
         ctx->opt_team = (int)value;
@@ -1400,11 +1418,11 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     bool hybrid = bf16 && agg == SAGA_AGG_SUM && (ep->op == SAGA_EDGE_COPY || ep->op == SAGA_EDGE_MUL_WEIGHT) &&
                   hybrid_applies(ctx, Fg, ld_g, tf ? nullptr : X->data);
     if (hybrid) {
-        if (saga_status st = ensure_hybrid(ctx, g, row_bytes)) return st;
+        if (saga_status st = ensure_hybrid(ctx, g, row_bytes, Fg)) return st;
         hybrid = g->hyb.usable;
     }
     if (!hybrid)
-        if (saga_status st = ensure_work_list(ctx, g, row_bytes)) return st;
+        if (saga_status st = ensure_work_list(ctx, g, row_bytes, Fg)) return st;
 
     saga_ctx::EventSet* es = nullptr;
     if (ctx->profiling && !ctx->arena_active) {

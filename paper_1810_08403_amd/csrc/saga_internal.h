@@ -79,6 +79,7 @@ struct WorkListParams {
     int64_t stripe_rows;  // pieces end on multiples of this many source rows (0: cut by count only)
     bool skip_empty = false;  // leave columns without edges out (streamed chunks: nothing to add)
     int32_t team = 1;         // wavefronts that share one piece of a cut column (1 or 4)
+    int32_t order = 1;        // pieces in the list: 0 by first band and column, 1 by first band, last band and column
 };
 // Build the work list of a CSC block whose arrays are on the host
 // (col_ptr[0] = 0; vertex ids and edge offsets are local to the block).
@@ -86,7 +87,8 @@ struct WorkListParams {
 // its own pieces (the dense blocks below). Such a column is always combined from partial rows: slots
 // [slot0, slot0 + extra) are reserved for the other kernel, its pieces (all of them, even a single one) follow.
 struct saga_ctx;
-WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes);
+// width: features of the rows the propagation writes (0: not known), see the definition
+WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes, int32_t width = 0);
 void build_work_list(const int64_t* col_ptr, const int32_t* row_idx, int64_t n_cols, const WorkListParams& p,
                      WorkList* out, const int32_t* extra_slots = nullptr);
 
@@ -159,9 +161,10 @@ struct saga_ctx {
 
     // tunables
     int64_t opt_split = 64;        // minimum edges per piece of a cut column
-    bool opt_split_set = false;    // the caller has chosen it (the dense-block path otherwise cuts its remainder finer)
+    bool opt_split_set = false;    // the caller has chosen it (narrow rows otherwise get finer pieces, see work_list_params)
     int64_t opt_cut_degree = 0;    // 0 = 2 * split
     int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
+    int opt_piece_order = 1;       // see WorkListParams::order
     int opt_xcd_remap = 1;
     int opt_mma = 0;               // 1: bf16 sum propagation with the multiply-accumulate on the matrix unit (measured: a tie)
     int opt_team = 0;              // 1: a piece of a cut column is worked by a whole workgroup (measured slower)
@@ -448,7 +451,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 // copy (ensure_hybrid; view->hyb.usable says whether the graph has blocks worth it), whether a call qualifies
 // (hybrid_applies: options, rows of a multiple of 128 bf16 values, 16-byte aligned), the launch of the dense half
 // (hybrid_dense_launch) and the release of the plan.
-saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* view, int64_t row_bytes);
+saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* view, int64_t row_bytes, int32_t width = 0);
 bool hybrid_applies(const saga_ctx* ctx, int32_t F, int64_t ld, const void* rows);
 saga_status hybrid_dense_launch(saga_ctx* ctx, saga_graph* view, GatherArgs* ga, bool weighted, const float* w_src, bool w_attached,
                                 saga_ctx::EventSet* es, bool* forked);
@@ -502,7 +505,7 @@ hipError_t launch_sigmoid_grad(float* d, const float* z, int64_t count, hipStrea
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
-saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes);
+saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width = 0);
 // per-vertex products of a gated ApplyEdge into ctx->ws_hoist, rows [Ps | M | Pd (+ b)] (saga_api.hip)
 saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F);
 // per-vertex messages of a max-pooling ApplyEdge into ctx->ws_hoist, n x Fm (saga_api.hip)
