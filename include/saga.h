@@ -386,7 +386,7 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
  *                weights as two bf16 parts (2^-17 relative); the other edges stay with the sparse propagation kernel.
  *                Same function, another rounding order; sums stay reproducible run to run. The plan is built at the
  *                first call that can use it. The resident backward pass does not use it.
- *   "dense_min_edges"  edges from which a block goes to the matrix cores (0 = default 256; at most 2048)
+ *   "dense_min_edges"  edges from which a block goes to the matrix cores (0 = default 200; at most 2048)
  *   "dense_tile_gain"  edges beyond dense_min_edges, summed over the blocks of a destination tile, from which the tile
  *                uses the dense path at all (it costs a partial row per destination; -1 = default 512)
  *   "dense_chunk"  blocks of one destination tile worked by one workgroup (0 = default 128)
