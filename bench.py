@@ -317,7 +317,8 @@ def main():
             bytes_dense += n * f_msg * es + (n * f_in * es if wl.W_self is not None else 0) + n * f_out * es
         peak_tf = 2500.0 if wl.dtype == "bf16" else 157.3
         tf = flops / (ms_dense * 1e-3) / 1e12
-        out["dense_products"] = {"bound": "mfma", "kernel": "k_gemm_wlds" if (wl.dtype == "f32" and f_msg == 128 and f_in == 128 and wl.W_self is None) else "k_gemm_nt", "achieved": round(tf, 1), "peak": peak_tf, "unit": "TFLOP/s",
+        out["dense_products"] = {"bound": "mfma", "kernel": ("k_gemm_wlds" if (wl.dtype == "f32" and f_msg == 128 and f_in == 128 and wl.W_self is None) else
+                                                           "k_gemm_wreg16" if (wl.dtype == "bf16" and f_msg in (256, 512) and f_out % 16 == 0 and n >= 32768 and wl.W_self is None) else "k_gemm_nt"), "achieved": round(tf, 1), "peak": peak_tf, "unit": "TFLOP/s",
                                  "frac": round(tf / peak_tf, 4), "ms": round(ms_dense, 4), "flops": flops,
                                  "bytes": bytes_dense, "GBps": round(bytes_dense / (ms_dense * 1e-3) / 1e9, 1),
                                  "frac_of_hbm_peak": round(bytes_dense / (ms_dense * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}

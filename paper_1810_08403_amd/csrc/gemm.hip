@@ -22,12 +22,14 @@
 // without the write-out 0.30 ms. A write-out with 16-byte stores from
 // transposed accumulators (32 bytes per row and instruction) was slower than
 // the 4-byte stores that fill two whole 128-byte lines per instruction.
+#include <type_traits>
 #include "device_math.h"
 #include "saga_internal.h"
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte fragment as a first-class vector value
 
@@ -410,6 +412,192 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
     }
 }
 
+// ---------------------------------------------------------------------------
+// bf16 products with K = 256 or 512 and many rows (ApplyVertex of the wide GCN layers, the transform-first product and
+// dZ W^T of their backward pass) with the weights resident in registers. These products are bound by memory (512 -> 256:
+// 0.4 GB against 69 GFLOP), and the 256 KiB of a 512 x 256 bf16 weight matrix fit no LDS; they do fit the registers of
+// one workgroup: each of its eight wavefronts keeps 32 columns for all of K (128 registers per lane at K = 512),
+// already in the layout of the 16x16x32 matrix instruction's first operand, for the whole kernel. The product is
+// taken transposed, C^T = W^T A^T: the rows of A are the instruction's second operand (read from LDS, 16 bytes per
+// lane and instruction) and a lane ends up with four consecutive columns of one row, which it stores as 8 bytes.
+// The workgroup walks 32-row tiles of A, copied from memory straight into one of three LDS buffers
+// (global_load_lds, chunks permuted within a row as in k_gemm_wlds) two tiles ahead of the multiplication, so that two
+// tiles (64 KiB at K = 512) are in flight per compute unit all the time. Every row of A is read from memory once
+// and no weight is read again after the first microsecond.
+// Waiting for a tile: a wavefront's copies complete in the order they were issued, its stores in an order of their
+// own. s_waitcnt vmcnt(n), n = the copies of the one tile that may still be in flight, is therefore enough whatever
+// the stores do: if a copy of an earlier tile were outstanding, so would all n of the later one be.
+// Measured on 262,144 x 512 x 256 (MI355X; the stage also packs the weights): 153 us with k_gemm_nt, 94 us here
+// (4.3 TB/s). What the steps cost, from runs with parts taken out: the copies alone 56 us; with the operand reads and
+// MFMAs 78 us (every wavefront reads the whole tile from LDS: 256 KiB per tile and compute unit with eight
+// wavefronts; sixteen wavefronts of 16 columns read twice that and took 108 us); an epilogue of its own before the
+// steps, 100 us (113 us before the chip's bf16 conversion instruction replaced the integer rounding and the
+// activation became a branch per group instead of a select per value: two wavefronts per SIMD in the same phase
+// hide no vector instructions), spread between the steps of the next tile as it is now, 94 us.
+// ---------------------------------------------------------------------------
+constexpr int kWregTR = 32;  // rows of a tile
+
+// NW wavefronts per workgroup, each with 256 / NW columns (CH groups of 16): the fewer wavefronts, the fewer times a tile
+// of A is read from LDS (once per wavefront), the more registers the weights take per lane (4 CH K / 32).
+template <int KS, int NW, typename TO>
+__global__ __launch_bounds__(NW * 64) void k_gemm_wreg16(const GemmArgs a, const int n_cg, const int wg_per_cg, const int n_tiles_m)
+{
+    constexpr int K = 32 * KS;                         // 512 or 256
+    constexpr int CH = 16 / NW;                        // 16-column groups of a wavefront
+    constexpr int kTile = kWregTR * K;                 // bf16 elements of a tile
+    constexpr int kCopies = kTile * 2 / 1024 / NW;     // wave-wide copies (1 KiB) per wavefront and tile
+    constexpr int kRowsPerCopy = 1024 / (K * 2);       // 1 or 2
+    constexpr int kChunks = K / 8;                     // 16-byte chunks of a row: 64 or 32
+    static_assert(kCopies >= 1 && kCopies < 16, "the wait below counts the copies of one tile in four bits");
+    __shared__ __attribute__((aligned(16))) uint16_t As0[kTile];
+    __shared__ __attribute__((aligned(16))) uint16_t As1[kTile];
+    __shared__ __attribute__((aligned(16))) uint16_t As2[kTile];
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to be: addresses built from it stay in scalar registers
+    const int n = lane & 15, g = lane >> 4;
+    const int cg = (int)((blockIdx.x >> 3) % (unsigned)n_cg);
+    const int j = (int)((blockIdx.x >> 3) / (unsigned)n_cg) * 8 + (int)(blockIdx.x & 7);
+    if (j >= n_tiles_m) return;
+    const int count = (n_tiles_m - j + wg_per_cg - 1) / wg_per_cg;  // tiles j, j + wg_per_cg, ...
+    const uint16_t* __restrict__ A = static_cast<const uint16_t*>(a.A);
+    const uint16_t* __restrict__ Bt = static_cast<const uint16_t*>(a.Bt);
+    const int c0 = cg * 256 + wave * 16 * CH;  // this wavefront's columns: [c0, c0 + 16 CH); N is a multiple of 16
+
+    // lane l of a copy brings the chunk that belongs at position l % kChunks of its row, chunk (l % kChunks) ^ (row & 15)
+    const int crow = lane / kChunks, cpos = lane % kChunks;
+    auto copy_tile = [&](int tile, uint16_t (&buf)[kTile]) {
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) {
+            const int idx = wave * kCopies + i, row = idx * kRowsPerCopy + crow;
+            int64_t gr = (int64_t)tile * kWregTR + row;
+            if (gr >= a.M) gr = a.M - 1;  // rows past the end are copies of the last row; their results are not stored
+            const uint16_t* src = A + gr * a.lda + ((cpos ^ (row & 15)) << 3);
+            __builtin_amdgcn_global_load_lds(src, (lds_ptr)(&buf[idx * 512]), 16, 0, 0);
+        }
+    };
+    copy_tile(j, As0);
+    if (count > 1) copy_tile(j + wg_per_cg, As1);
+
+    // the weights: column c0 + 16 h + n, the eight k at 32 s + 8 g, for every group h and step s (groups past N: column 0,
+    // their results are not stored)
+    u32x4 w[CH][KS];
+    float bias[CH][4];
+#pragma unroll
+    for (int h = 0; h < CH; ++h) {
+        const bool has = c0 + 16 * h < a.N;
+        const uint16_t* wp = Bt + (int64_t)(has ? c0 + 16 * h + n : 0) * a.ldbt + 8 * g;
+#pragma unroll
+        for (int s_ = 0; s_ < KS; ++s_) w[h][s_] = *reinterpret_cast<const u32x4*>(wp + 32 * s_);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bias[h][q] = (a.bias && has) ? a.bias[c0 + 16 * h + 4 * g + q] : 0.f;
+    }
+
+    // bias, activation, rounding and store of one 16 x 16 group of results: columns c0 + 16 h ..., rows 16 hh ... of the tile
+    auto store_act = [&](int tile, const floatx4& r, int h, int hh, auto act_c) {
+        constexpr int ACT = decltype(act_c)::value;
+        TO* __restrict__ C = static_cast<TO*>(a.C);
+        const int64_t row = (int64_t)tile * kWregTR + hh * 16 + n;
+        if (c0 + 16 * h >= a.N || row >= a.M) return;
+        float y[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            y[q] = r[q] + bias[h][q];
+            if (ACT == SAGA_ACT_RELU) y[q] = y[q] > 0.f ? y[q] : 0.f;
+            if (ACT == SAGA_ACT_SIGMOID) y[q] = sigmoid_f32(y[q]);
+        }
+        TO* p = C + row * a.ldc + c0 + 16 * h + 4 * g;
+        if (sizeof(TO) == 4) {
+            *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+        } else {
+            // the conversion instruction of this chip (round to nearest even, two values at a time)
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            uint2 v;
+            v.x = __builtin_bit_cast(uint32_t, (bf16x2){(__bf16)y[0], (__bf16)y[1]});
+            v.y = __builtin_bit_cast(uint32_t, (bf16x2){(__bf16)y[2], (__bf16)y[3]});
+            *reinterpret_cast<uint2*>(p) = v;
+        }
+    };
+    // one branch on the activation per group instead of a select per value (the sigmoid's exponential would otherwise be
+    // computed for every value of every layer)
+    const int act = __builtin_amdgcn_readfirstlane(a.act);
+    auto store_group = [&](int tile, const floatx4& r, int h, int hh) {
+        if (act == SAGA_ACT_RELU)
+            store_act(tile, r, h, hh, std::integral_constant<int, SAGA_ACT_RELU>{});
+        else if (act == SAGA_ACT_SIGMOID)
+            store_act(tile, r, h, hh, std::integral_constant<int, SAGA_ACT_SIGMOID>{});
+        else
+            store_act(tile, r, h, hh, std::integral_constant<int, SAGA_ACT_NONE>{});
+    };
+    // A tile's results move to pacc at the next tile's barrier and are stored group by group between the steps of that
+    // tile: with two wavefronts per SIMD, both in the same phase, an epilogue of its own would leave the matrix cores idle.
+    floatx4 acc[CH][2], pacc[CH][2];
+#pragma unroll
+    for (int h = 0; h < CH; ++h)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[h][0][q] = acc[h][1][q] = 0.f;
+    // Operand reads: row hh * 16 + n of the buffer, chunk 4 s + g at position (4 s + g) ^ n, i.e. byte
+    // n * 2 K + ((g ^ (n & 3)) << 4) + ((s ^ (n >> 2)) << 6), and 32 K bytes further for the second half of the rows.
+    // They are written as instructions: for an LDS read it can see, the compiler waits for every copy in flight that
+    // it cannot prove to go to another array, and after unrolling it could not for one tile in three. The wait for a
+    // read is lgkmcnt(0) on the registers it fills, placed before the next step's reads are issued, so a read has the
+    // MFMAs of one step to arrive in.
+    const uint32_t rd = (uint32_t)(n * 2 * K + ((g ^ (n & 3)) << 4)), nb = (uint32_t)(n >> 2);
+    auto lds_base = [](const uint16_t* p) { return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint16_t*)p; };
+    auto fetch = [&](uint32_t base, int s_, u32x4& x0, u32x4& x1) {
+        const uint32_t addr = base + rd + (((uint32_t)s_ ^ nb) << 6);
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3" : "=&v"(x0), "=&v"(x1) : "v"(addr), "n"(32 * K) : "memory");
+    };
+    auto arrived = [](u32x4& x0, u32x4& x1) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x0), "+v"(x1)::"memory"); };
+    auto do_tile = [&](int t, const uint16_t (&cur)[kTile], uint16_t (&nxt2)[kTile]) {
+        const int tile = j + t * wg_per_cg;
+        // this wavefront's copies of tile t have landed (those of tile t + 1 may be in flight), then everybody's have
+        if (t + 1 < count)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | kCopies);
+        else
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        // the bare barrier instruction: __syncthreads(), and a fence on LDS alone too, would make the compiler wait for the
+        // copies of tile t + 1 as well (they write LDS). What has to be ordered is ordered by hand: the copies of tile t by
+        // the wait above, this wavefront's operand reads of tile t - 1 by the waits that precede the MFMAs using them.
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int h = 0; h < CH; ++h)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                pacc[h][hh] = acc[h][hh];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[h][hh][q] = 0.f;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 2 < count) copy_tile(tile + 2 * wg_per_cg, nxt2);
+        const uint32_t base = lds_base(cur);
+        u32x4 f[2][2];
+        fetch(base, 0, f[0][0], f[0][1]);
+#pragma unroll
+        for (int s_ = 0; s_ < KS; ++s_) {
+            u32x4(&fc)[2] = f[s_ & 1];
+            arrived(fc[0], fc[1]);
+            if (s_ + 1 < KS) fetch(base, s_ + 1, f[(s_ + 1) & 1][0], f[(s_ + 1) & 1][1]);
+#pragma unroll
+            for (int h = 0; h < CH; ++h) {
+                const bf16x8 wv = __builtin_bit_cast(bf16x8, w[h][s_]);
+                acc[h][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, __builtin_bit_cast(bf16x8, fc[0]), acc[h][0], 0, 0, 0);
+                acc[h][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, __builtin_bit_cast(bf16x8, fc[1]), acc[h][1], 0, 0, 0);
+            }
+            if (t > 0 && (s_ & 1) && s_ / 2 < 2 * CH) store_group(tile - wg_per_cg, pacc[(s_ / 2) >> 1][(s_ / 2) & 1], (s_ / 2) >> 1, (s_ / 2) & 1);
+        }
+    };
+    for (int t = 0; t < count; t += 3) {
+        do_tile(t, As0, As2);
+        if (t + 1 < count) do_tile(t + 1, As1, As0);
+        if (t + 2 < count) do_tile(t + 2, As2, As1);
+    }
+#pragma unroll
+    for (int h = 0; h < CH; ++h)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) store_group(j + (count - 1) * wg_per_cg, acc[h][hh], h, hh);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_pack_bt_transpose(const T* W, int64_t ldw, int K, int N, T* Bt, int64_t ldbt, int64_t col0)
 {
@@ -497,6 +685,29 @@ static bool launch_wlds(const GemmArgs& a, hipStream_t s, hipError_t* err)
     return true;
 }
 
+// the weights-in-registers kernel where it applies (bf16, one operand, K = 256 or 512, N a multiple of 16, rows and
+// outputs in 16-byte / 8-byte fragments, enough rows to give every compute unit several tiles); false: not applicable
+template <typename TO>
+static bool launch_wreg16(const GemmArgs& a, hipStream_t s, hipError_t* err)
+{
+    if (a.A2 || (a.K != 256 && a.K != 512) || a.N % 16 != 0 || a.M < 32 * 1024) return false;
+    if (a.lda % 8 != 0 || (reinterpret_cast<uintptr_t>(a.A) & 15u) || a.ldbt % 8 != 0 || a.ldbt < a.K ||
+        (reinterpret_cast<uintptr_t>(a.Bt) & 15u) || a.ldc % 4 != 0 || (reinterpret_cast<uintptr_t>(a.C) & 15u))
+        return false;
+    const int n_cg = (a.N + 255) / 256;
+    const int64_t n_tiles_m = (a.M + kWregTR - 1) / kWregTR;
+    if (n_cg > 32 || n_tiles_m > 0x7fffffffLL) return false;
+    const int wg_per_cg = std::max(8, 256 / n_cg / 8 * 8);  // one workgroup per compute unit, a multiple of the 8 XCDs per column group
+    const dim3 grid((unsigned)(wg_per_cg * n_cg));
+    constexpr int NW = 8;
+    if (a.K == 512)
+        hipLaunchKernelGGL((k_gemm_wreg16<16, NW, TO>), grid, dim3(NW * 64), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    else
+        hipLaunchKernelGGL((k_gemm_wreg16<8, NW, TO>), grid, dim3(NW * 64), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    *err = hipGetLastError();
+    return true;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
@@ -507,7 +718,12 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         if (launch_wlds(a, s, &e)) return e;
         return launch_typed<float, float>(a, s);
     }
-    if (a.out_dtype == SAGA_F32) return launch_typed<uint16_t, float>(a, s);
+    hipError_t e = hipSuccess;
+    if (a.out_dtype == SAGA_F32) {
+        if (launch_wreg16<float>(a, s, &e)) return e;
+        return launch_typed<uint16_t, float>(a, s);
+    }
+    if (launch_wreg16<uint16_t>(a, s, &e)) return e;
     return launch_typed<uint16_t, uint16_t>(a, s);
 }
 

@@ -347,6 +347,32 @@ def test_apply_vertex_product_at_ragged_shapes(ctx, dtype):
     graph.destroy()
 
 
+def test_bf16_product_at_wide_layer_widths_over_many_rows(ctx):
+    """bf16 products with K = 256 and 512 over some 37,000 rows (ApplyVertex of the wide GCN layers: every workgroup walks
+    several 32-row tiles with the weights held in registers). ApplyVertex alone on a graph of self-loops: a row count that
+    ends inside a tile, N one wavefront's 16 columns, part of a 256-column group, a whole one and two, with and without
+    bias, all three activations; K = 128 and N = 40 take the general kernel over the same rows."""
+    n = 32768 + 4096 + 19
+    idx = torch.arange(n, dtype=torch.int64)
+    g = si.build_csc(n, idx, idx)
+    graph = make_graph(ctx, g)
+    cases = [(512, 256, "relu", True), (256, 512, "none", False), (512, 16, "sigmoid", True), (256, 48, "relu", True),
+             (512, 272, "none", True), (256, 256, "relu", False), (512, 40, "relu", True), (128, 256, "relu", True)]
+    for K, N, act, with_b in cases:
+        X = si.round_to_bf16(si.normal_features(n, K, 100 + K))
+        W = si.round_to_bf16(si.glorot_uniform(K, N, 200 + N))
+        b = si.uniform_pm(N, 0.5, 300 + N) if with_b else None
+        Y = torch.full((n, N), float("nan"), device="cuda", dtype=torch.bfloat16)
+        ctx.layer_forward(graph, X.cuda().to(torch.bfloat16), Y, edge_op="copy", W=W.cuda().to(torch.bfloat16),
+                          bias=None if b is None else b.cuda(), act=act)
+        torch.cuda.synchronize()
+        Z = X.double() @ W.double() + (0 if b is None else b.double())
+        Zabs = X.double().abs() @ W.double().abs() + (0 if b is None else b.double().abs())
+        ref = {"relu": torch.relu, "sigmoid": torch.sigmoid, "none": lambda t: t}[act](Z)
+        assert_sum_close(Y.float().cpu().numpy(), ref.numpy(), Zabs.numpy(), TOL_BF16, f"bf16 product {n} x {K} x {N} {act}")
+    graph.destroy()
+
+
 def test_apply_vertex_product_at_layer_widths_over_many_rows(ctx):
     """fp32 products with K = 32 ... 128 over some 37,000 rows (the shapes of the hoisted products and of ApplyVertex in the
     128-wide applications: every workgroup walks several output tiles). ApplyVertex alone on a graph of self-loops, as
