@@ -292,7 +292,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(T) =
 // (64 KiB) are brought into LDS once; then it walks 64-row tiles of A, each copied from memory straight into one of two
 // 32 KiB LDS buffers (global_load_lds: no registers, no store instructions) while the previous tile is multiplied. One
 // barrier per tile, 64 MFMAs (4,096 cycles) per wavefront between two barriers; the results of a tile are written out
-// after the barrier and complete under the MFMAs of the next tile. A wave-wide copy lands as 1 KiB of consecutive LDS
+// between the first steps of the next tile and complete under its MFMAs. A wave-wide copy lands as 1 KiB of consecutive LDS
 // bytes, so rows cannot be padded; instead the 16-byte chunks of a row are stored permuted (chunk c of row r at position
 // c ^ (r & 15)), which spreads the operand reads of 16 consecutive rows over all banks. One workgroup of eight
 // wavefronts per compute unit (128 KiB of LDS), two wavefronts per SIMD, each with one 32 x 32 accumulator tile (four
@@ -300,23 +300,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(T) =
 // ---------------------------------------------------------------------------
 constexpr int kWldsK = 128, kWldsBM = 64, kWldsBN = 128;
 
-template <bool CHECK>
-__device__ __forceinline__ void wlds_store(const GemmArgs& a, const floatx16& acc, int64_t row0, int col, float bias)
+// bias, activation and store of value r of a lane's 32 x 32 accumulator tile (row row0 + (r / 4) * 8 + r % 4)
+template <int ACT, bool CHECK>
+__device__ __forceinline__ void wlds_store_one(const GemmArgs& a, float v, int r, int64_t row0, int col, float bias)
 {
-    float* __restrict__ C = static_cast<float*>(a.C);
-    if (CHECK && col >= a.N) return;
-    float* p = C + row0 * a.ldc + col;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int dr = (r >> 2) * 8 + (r & 3);
-        if (CHECK && row0 + dr >= a.M) continue;
-        float y = acc[r] + bias;
-        if (a.act == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
-        if (a.act == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
-        p[dr * a.ldc] = y;
-    }
+    const int dr = (r >> 2) * 8 + (r & 3);
+    if (CHECK && (col >= a.N || row0 + dr >= a.M)) return;
+    float y = v + bias;
+    if (ACT == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
+    if (ACT == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
+    static_cast<float*>(a.C)[(row0 + dr) * a.ldc + col] = y;
 }
-
+// The activation is a parameter of the kernel: as a run-time select per value it made every product compute the sigmoid's
+// exponential for every value.
+template <int ACT>
 __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n_cg, const int wg_per_cg, const int n_tiles_m)
 {
     // three separate arrays: the compiler makes an LDS read wait for the copies in flight (they count as memory
@@ -364,11 +361,16 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
     const int ra = (wm * 32 + m) * kWldsK;
     const int rb0 = (wn * 32 + m) * kWldsK;
     const int sw = m & 15;
-    // One tile: the next one's copies first, then 16 steps of three operand reads (requested a step ahead) and eight
-    // MFMAs; the wait for the copies, the barrier, and the write-out, which the hardware completes under the next
-    // tile's MFMAs. (Spreading the copies and the previous tile's write-out, from a second accumulator set, between
-    // the MFMAs of the steps was slower: 1.28 against 1.11 ms on 1,048,576 x 128 x 384.)
-    auto do_tile = [&](int t, const float (&cur)[kWldsBM * kWldsK], float (&nxt)[kWldsBM * kWldsK]) {
+    // One tile: the next one's copies first, then 16 steps of two operand reads (requested a step ahead) and four
+    // MFMAs; the wait for the copies and the barrier. The results of a tile are written out between the first eight
+    // steps of the next tile, two values per step: with two wavefronts per SIMD that leave the barrier together, a
+    // write-out of its own (16 values per lane with their address arithmetic) kept the matrix cores waiting.
+    // (Spreading the copies between the steps as well was slower: 1.28 against 1.11 ms on 1,048,576 x 128 x 384.)
+    floatx16 pacc;
+    int64_t prow0 = 0;
+    bool pfull = false;
+    auto do_tile = [&](int t, const float (&cur)[kWldsBM * kWldsK], float (&nxt)[kWldsBM * kWldsK], auto pchk) __attribute__((always_inline)) {
+        constexpr bool PCHECK = decltype(pchk)::value;  // the previous tile ends past M or N
         const int tile = j + t * wg_per_cg;
         if (t + 1 < count) {
 #pragma unroll
@@ -393,23 +395,33 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c]), __uint_as_float(fb0[c]), acc, 0, 0, 0);
+            if (s_ < 8 && t > 0) {
+                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_], 2 * s_, prow0, col0, bias);
+                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_ + 1], 2 * s_ + 1, prow0, col0, bias);
+            }
             __builtin_amdgcn_sched_barrier(0);
             fa = na;
             fb0 = nb0;
         }
-        // the next tile's copies (and the previous tile's stores) were issued a whole tile ago
+        // the next tile's copies were issued a whole tile ago, the previous tile's stores at least half a tile ago
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();  // every wavefront is done with this buffer, and sees the next one
-        const int64_t row0 = (int64_t)tile * kWldsBM + wm * 32 + h * 4;
-        if ((int64_t)tile * kWldsBM + kWldsBM <= a.M && cg * kWldsBN + kWldsBN <= a.N)
-            wlds_store<false>(a, acc, row0, col0, bias);
+        pacc = acc;
+        prow0 = (int64_t)tile * kWldsBM + wm * 32 + h * 4;
+        pfull = (int64_t)tile * kWldsBM + kWldsBM <= a.M && cg * kWldsBN + kWldsBN <= a.N;
+    };
+    auto tile_of = [&](int t, const float (&cur)[kWldsBM * kWldsK], float (&nxt)[kWldsBM * kWldsK]) __attribute__((always_inline)) {
+        if (pfull || t == 0)
+            do_tile(t, cur, nxt, std::false_type{});
         else
-            wlds_store<true>(a, acc, row0, col0, bias);
+            do_tile(t, cur, nxt, std::true_type{});
     };
     for (int t = 0; t < count; t += 2) {
-        do_tile(t, As0, As1);
-        if (t + 1 < count) do_tile(t + 1, As1, As0);
+        tile_of(t, As0, As1);
+        if (t + 1 < count) tile_of(t + 1, As1, As0);
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) wlds_store_one<ACT, true>(a, pacc[r], r, prow0, col0, bias);
 }
 
 // ---------------------------------------------------------------------------
@@ -680,7 +692,13 @@ static bool launch_wlds(const GemmArgs& a, hipStream_t s, hipError_t* err)
     const int64_t n_tiles_m = (a.M + kWldsBM - 1) / kWldsBM;
     if (n_cg > 32 || n_tiles_m > 0x7fffffffLL) return false;
     const int wg_per_cg = std::max(8, 256 / n_cg / 8 * 8);  // one workgroup per compute unit, a multiple of the 8 XCDs per column group
-    hipLaunchKernelGGL(k_gemm_wlds, dim3((unsigned)(wg_per_cg * n_cg)), dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    const dim3 grid((unsigned)(wg_per_cg * n_cg));
+    if (a.act == SAGA_ACT_RELU)
+        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_RELU>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    else if (a.act == SAGA_ACT_SIGMOID)
+        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_SIGMOID>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    else
+        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_NONE>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
     *err = hipGetLastError();
     return true;
 }
