@@ -582,10 +582,15 @@ static HybridParams hybrid_params(const saga_ctx* ctx)
 saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width)
 {
     HybridDevice& h = g->hyb;
-    // The remainder keeps the general piece size at any width: its columns have lost their heavy blocks, and finer pieces
-    // cost more than they spread (backward pass of the R-MAT 18 workload, 128 bf16 features: 3.65 ms at 64, 3.98 at 32).
+    // The remainder's piece size goes by the bytes of a source row, not by the narrow-row rule of the general list: its
+    // columns have lost their heavy blocks. Rows of 256 and 512 bytes keep 64 edges per piece (backward pass of the R-MAT
+    // 18 workload, 128 bf16 features: 3.65 ms at 64, 3.98 at 32; 256 features: 3.42 at 64, 3.46 at 48); rows of 1 KiB take
+    // 48 (forward layer of the same workload, 512 bf16 features: 4.11 ms at 48, 4.21 at 40, 4.23 at 56 and 64, 4.32 at
+    // 32, 4.73 at 80: longer pieces reach over more bands of source rows, shorter ones cost k_combine more than the
+    // sparse kernel gains). Columns are cut from 128 edges on either way.
     (void)width;
     WorkListParams p = work_list_params(ctx, row_bytes, 0);
+    if (!ctx->opt_split_set && row_bytes >= 1024) p.min_edges = 48;
     const HybridParams hp = hybrid_params(ctx);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
         return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team && a.order == b.order;

@@ -106,9 +106,9 @@ constexpr int kDenseM = 64, kDenseK = 32;
 struct HybridParams {
     // A block costs the matrix cores the same whatever its fill (64 MFMAs per wavefront: about a microsecond of one compute
     // unit with two-part weights), an edge whose source row hits in the L2 costs the sparse kernel about 0.02 ns of the whole
-    // chip. Measured on the R-MAT 18 workload (512 bf16 features) the layer takes 4.29 ms with blocks from 200 edges on
-    // (a tenth full), 4.33 at 208, 4.43 at 216 and at 256, 4.44 at 176 and 192, 4.57 at 128 and at 100; the backward pass
-    // of the same layer (256 features) 3.43 ms at 192, 3.51 at 208, 3.66 at 256.
+    // chip. Measured on the R-MAT 18 workload (512 bf16 features) the layer takes 4.11 ms with blocks from 200 edges on
+    // (a tenth full), 4.14 at 192, 4.16 at 208, 4.27 at 160, 4.36 at 144, 4.48 at 256; the backward pass of the same layer
+    // (256 features) 3.43 ms at 192, 3.51 at 208, 3.66 at 256.
     int64_t min_block_edges = 200;
     int64_t min_tile_gain = 512;    // edges beyond min_block_edges, summed over a destination tile's blocks, that pay for its partial rows
     int32_t max_chunk_blocks = 128; // blocks of one destination tile worked by one workgroup (one partial row per destination each)
