@@ -170,9 +170,9 @@ def test_split_threshold_and_xcd_remap_do_not_change_max(ctx):
     wl = si.workload(5, scale=11, edge_factor=32, f_in=32, f_out=8)
     ref = run_oracle(wl, agg="max", with_vertex=False)
     refs = run_oracle(wl, agg="sum", with_vertex=False)
-    for split, remap, team, stripe in ((64, 1, 1, 1024), (300, 0, 0, 0), (1 << 20, 1, 1, 64), (16, 1, 1, 16), (32, 0, 0, 256),
-                                       (16, 1, 0, 1024)):
-        with new_context(split=split, xcd_remap=remap, team=team, stripe_kb=stripe) as c:
+    for split, remap, team, stripe, order in ((64, 1, 1, 1024, 1), (300, 0, 0, 0, 1), (1 << 20, 1, 1, 64, 0), (16, 1, 1, 16, 1), (32, 0, 0, 256, 0),
+                                              (16, 1, 0, 1024, 1), (16, 1, 0, 16, 0)):
+        with new_context(split=split, xcd_remap=remap, team=team, stripe_kb=stripe, piece_order=order) as c:
             graph = make_graph(c, wl.graph)
             _, A = run_gpu(c, wl, graph, agg="max", with_vertex=False)
             assert_bit_equal(A, ref["A"], f"split={split}")

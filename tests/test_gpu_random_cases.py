@@ -100,7 +100,7 @@ def test_random_forward_case(seed):
                     team=int(rng.integers(2)))
     # the optional code paths: work-group order, the matrix-unit multiply-accumulate, the stages one by one, the product first
     if rng.random() < 0.4:
-        opts.update(xcd_remap=int(rng.integers(2)), mma=int(rng.integers(2)))
+        opts.update(xcd_remap=int(rng.integers(2)), mma=int(rng.integers(2)), piece_order=int(rng.integers(2)))
         if op in ("copy", "mul_weight") and rng.random() < 0.4:
             opts["fused"] = 0
         if rng.random() < 0.4:

@@ -69,6 +69,9 @@ def test_work_list_partitions_the_edges(kw):
         pieces = is_team if kw["team"] == 4 else ~whole
         first_stripe = ri[e0[pieces]] // R
         assert (np.diff(first_stripe) >= 0).all()                       # pieces come stripe by stripe
+        last_stripe = ri[e1[pieces] - 1] // R                             # ... and within a stripe by the stripe they reach
+        same_first = np.diff(first_stripe) == 0
+        assert (np.diff(last_stripe)[same_first] >= 0).all()
     if kw["team"] == 1:
         assert whole[np.argmax(whole):].all()                           # whole columns follow the pieces
 
