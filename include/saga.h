@@ -339,7 +339,8 @@ saga_status saga_get_timings(saga_ctx* ctx, saga_timings* out); /* synchronises 
 /* Tunables, for measurement. They shape the work list, which is (re)built at the next
  * saga_layer_forward that finds them changed:
  *   "split"      minimum edges in one piece of a cut column (default 64; until the caller sets it, layers whose
- *                propagation writes rows of fewer than 512 features use 32, and the sparse remainder of the
+ *                propagation writes rows of fewer than 512 features, and whose source rows do not all fit the L2s,
+ *                use 32, and the sparse remainder of the
  *                dense-block path uses 48 for source rows of 1 KiB or more)
  *   "cut_degree" columns with more in-edges than this are cut (default 0 = 2 * split)
  *   "stripe_kb"  pieces end where the source rows cross a multiple of this many KiB of

@@ -496,7 +496,10 @@ WorkListParams work_list_params(const saga_ctx* ctx, int64_t row_bytes, int32_t 
 
 saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width)
 {
-    const WorkListParams p = work_list_params(ctx, row_bytes, width);
+    // source rows that all fit the L2s together (8 x 4 MiB) are not what finer pieces are for: there is no miss to save,
+    // only partial rows to add
+    const bool table_in_l2 = g->n * std::max<int64_t>(row_bytes, 1) <= (32ll << 20);
+    const WorkListParams p = work_list_params(ctx, row_bytes, table_in_l2 ? 0 : width);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
         return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team && a.order == b.order;
     };
