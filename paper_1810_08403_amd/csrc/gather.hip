@@ -778,8 +778,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(6, 8))) voi
 // sit side by side in one wave-wide load; a butterfly over the lane groups
 // finishes the reduction.
 // ---------------------------------------------------------------------------
+// Eight wavefronts per SIMD (64 registers) where the variant fits them without spilling: on graphs of many light columns
+// a wavefront's life is one chain of three memory round trips (work item, source ids, rows) for a dozen edges, and the
+// throughput is the number of resident wavefronts over that chain (CommNet on R-MAT 20: 19 wavefronts per compute unit
+// on average at six per SIMD, propagation 1.24 ms; 1.18 ms at eight). The gate-gradient variants and the bf16 maximum
+// need more registers: five and six.
+constexpr int narrow_min_waves(int elem_bytes, int agg, int ef)
+{
+    return ef_is_grad(ef) ? 5 : (elem_bytes == 2 && agg == SAGA_AGG_MAX) ? 6 : 8;
+}
 template <typename T, int VEC, int AGG, int EF>
-__global__ __launch_bounds__(256) void k_gather_narrow(const GatherArgs a, const int lpr_log2)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(narrow_min_waves(sizeof(T), AGG, EF), 8))) void k_gather_narrow(
+    const GatherArgs a, const int lpr_log2)
 {
     constexpr bool GATED = EF != kEfLinear;
     ItemView it;
