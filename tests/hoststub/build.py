@@ -1,5 +1,6 @@
 """Build the host translation units of libsaga against the CPU stand-in of the HIP runtime (g++, no GPU code):
-tests/hoststub/_build/libsaga_hoststub_asan.so with AddressSanitizer and UBSan. Test infrastructure only."""
+tests/hoststub/_build/libsaga_hoststub_asan.so with AddressSanitizer and UBSan, libsaga_hoststub_tsan.so with
+ThreadSanitizer. Test infrastructure only."""
 import os
 import subprocess
 import sys
@@ -13,7 +14,8 @@ STUB_UNITS = ["stub_runtime.cpp", "stub_kernels.cpp"]
 
 
 def lib_path(sanitize=True):
-    return os.path.join(OUT_DIR, "libsaga_hoststub_asan.so" if sanitize else "libsaga_hoststub.so")
+    name = {True: "libsaga_hoststub_asan.so", False: "libsaga_hoststub.so", "thread": "libsaga_hoststub_tsan.so"}[sanitize]
+    return os.path.join(OUT_DIR, name)
 
 
 def build(sanitize=True, force=False):
@@ -24,7 +26,9 @@ def build(sanitize=True, force=False):
     if not force and os.path.exists(out) and all(os.path.getmtime(out) >= os.path.getmtime(d) for d in deps):
         return out
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-pthread", "-fno-omit-frame-pointer", f"-I{HERE}", f"-I{CSRC}"]
-    if sanitize:
+    if sanitize == "thread":
+        cmd += ["-fsanitize=thread"]
+    elif sanitize:
         cmd += ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
     cmd += ["-x", "c++"] + srcs + ["-o", out]
     subprocess.run(cmd, check=True)
@@ -33,6 +37,10 @@ def build(sanitize=True, force=False):
 
 def asan_runtime():
     return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+
+
+def tsan_runtime():
+    return subprocess.run(["gcc", "-print-file-name=libtsan.so"], check=True, capture_output=True, text=True).stdout.strip()
 
 
 if __name__ == "__main__":

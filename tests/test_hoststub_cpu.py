@@ -45,6 +45,21 @@ def test_random_sessions(stub_lib, mode, new_edge_data):
     _run("run_sessions.py", stub_lib, mode, 1000 + 100 * mode, 25, new_edge_data)
 
 
+def test_sessions_under_thread_sanitizer():
+    """The same host code built with ThreadSanitizer (tilings are built on several threads): the recorded session and its
+    neighbours, operations executed at seeded random points. The oracle runs on one thread here: its OpenMP runtime is
+    not instrumented and would be reported for races it does not have."""
+    lib = hoststub_build.build(sanitize="thread")
+    env = dict(os.environ)
+    env["LD_PRELOAD"] = (hoststub_build.tsan_runtime() + " " + env.get("LD_PRELOAD", "")).strip()
+    env["TSAN_OPTIONS"] = "halt_on_error=0:report_signal_unsafe=0:history_size=4"
+    env["OMP_NUM_THREADS"] = "1"
+    r = subprocess.run([sys.executable, os.path.join(HERE, "hoststub", "run_sessions.py"), lib, "2", "474", "8", "1"], env=env,
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, f"exit {r.returncode}\n{r.stdout[-3000:]}\n{r.stderr[-6000:]}"
+    assert "ok:" in r.stdout and "ThreadSanitizer" not in r.stderr and "ThreadSanitizer" not in r.stdout, r.stderr[-6000:]
+
+
 def test_failed_allocations_come_back_as_errors(stub_lib):
     _run("run_alloc_failures.py", stub_lib)
 
