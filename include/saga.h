@@ -172,7 +172,10 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
  * One layer forward. X is n x F_in (SAGA_F32, or SAGA_BF16 for COPY /
  * MUL_WEIGHT). Y is n x F_out in X's dtype (n x Fm when vp->W is NULL).
  * accum_out, if given, receives the Gather output A as n x Fm fp32 before
- * ApplyVertex (device path only).
+ * ApplyVertex: a SAGA_MEM_DEVICE tensor on the resident path, a SAGA_MEM_HOST one on the
+ * streamed path (every destination interval's rows are copied out after the interval's
+ * ApplyVertex products have been enqueued; the call then follows the paper's schedule whatever
+ * the "schedule" option says).
  *
  * Placement selects the path: all tensors SAGA_MEM_DEVICE with a device graph
  * -> resident; X and Y SAGA_MEM_HOST (pinned recommended) with a host graph ->
@@ -240,8 +243,10 @@ typedef struct saga_layer_grads {
  * MUL_WEIGHT, GATED or POOL messages, each with or without W_self. Under the max accumulator
  * an edge carries gradient for the features whose maximum it supplied (every maximal edge
  * on a tie, the whole gradient each); the messages are recomputed by the forward pass's own
- * expressions and compared with A bit for bit, so A must be that pass's accum_out. (From host
- * memory, max over GATED messages returns SAGA_ERR_UNSUPPORTED.)
+ * expressions and compared with A bit for bit, so A must be that pass's accum_out: of a
+ * resident forward call for a resident backward call, of a streamed one for a streamed one
+ * (the per-vertex products of GATED and POOL layers are formed by different kernels on the two
+ * paths, whose sums may differ in the last bit).
  *
  *   backward-ApplyVertex   dZ = dY (.) act'(Z), the derivative taken from the stored output
  *                          (ReLU: 1 where Y > 0; sigmoid: Y (1 - Y), whose error is that of
@@ -286,8 +291,7 @@ typedef struct saga_layer_grads {
  * Under the max accumulator a tie gives every maximal edge the whole gradient, and A must be
  * the accum_out of the forward call on the same inputs, or no message will compare equal.
  *
- * Streamed calls (a SAGA_MEM_HOST graph, fp32; every layer of the table except max over
- * GATED): A, Y, dY, grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST
+ * Streamed calls (a SAGA_MEM_HOST graph, fp32; every layer of the table): A, Y, dY, grads->dX (and X, where the resident call reads it) are SAGA_MEM_HOST
  * tensors (pinned recommended), the parameters and their gradients stay on the device. Every
  * transfer goes through the context's device budget like in saga_layer_forward. The passes:
  *
@@ -312,6 +316,10 @@ typedef struct saga_layer_grads {
  *                          [Ps | M] are the constants, both source-side sums at once; per interval the shares of
  *                          dW_gate's left half and of dW_msg; the last product is dX = [dPs | dM] [W_gs ; W_m] + dPd W_gd).
  *                          Ps, M, Pd are formed on the device from the rows of X of the interval that needs them.
+ *   max, GATED             as sum, GATED, with the rows of A beside the rows of dA wherever those go: [Pd | dA | A] of the
+ *                          resident interval over the in-edges, [Pd | dA | A] travelling over the out-edges. Ps, M, Pd
+ *                          come from the same product kernel as in the streamed forward call, whatever the interval
+ *                          size, so the messages formed again are that call's bits.
  *   W_self in the above    dW_self is added tile by tile with dW; dZ W_self^T is a second operand pair of the product
  *                          that ends the last pass (beside the identity for a plain max Gather, W_pool for pooled rows,
  *                          appended to dPd W_gd for gated ones).

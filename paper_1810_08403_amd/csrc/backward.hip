@@ -926,6 +926,7 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
     if (!propagate) return SAGA_OK;
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
     VertexProducts prod;  // pooled rows are formed on the device from the rows of X, interval by interval
+    prod.one_kernel = agg == SAGA_AGG_MAX;
     if (pool)
         if ((st = prod.init(ctx, X, ep))) return st;
     if ((st = ensure_transposed_host(ctx, g))) return st;
@@ -1052,9 +1053,14 @@ saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_
 //      dW_gs += dPs^T X_J, dW_m += dM^T X_J; the schedule's last product is
 //      dX_J = [dPs | dM] [W_gs ; W_m] + dPd_J W_gd, the second pair fed from what pass 2 left in pinned memory.
 saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
-                                    const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                                    const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                                     const saga_layer_grads* grads)
 {
+    // Under the max accumulator an edge passes gradient on only where its message is the maximum that was gathered at its
+    // destination (A, the forward pass's Gather output, which the caller hands in): the rows of A ride along, as a third
+    // constant row of the destination in the in-edge pass and as a third row per edge in the out-edge pass, and the edge
+    // functions compare the recomputed message with them bit for bit, as on the resident path.
+    const bool is_max = agg == SAGA_AGG_MAX;
     const int64_t n = g->n;
     const int32_t F = (int32_t)X->cols;
     hipStream_t s = ctx->stream;
@@ -1087,6 +1093,7 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_grad, &ctx->ws_hoist, &ctx->ws_dz, &ctx->ws_dh, &ctx->ws_tile}) ctx->dev_free(b);
     VertexProducts prod;  // [Ps | M] and Pd of an interval are formed on the device from its rows of X, which stay in
                           // ws_tile (resident interval) for the parameter gradients added up per interval
+    prod.one_kernel = is_max;
     if ((st = prod.init(ctx, X, ep))) return st;
     if ((st = ensure_transposed_host(ctx, g))) return st;
     const float* h_dA = ctx->h_grad;               // F per vertex
@@ -1121,18 +1128,24 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
             return prod.rows(&ctx->ws_accum, row0, rows, 0, 2 * F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d);
         };
         StreamExtras ex;
-        ex.op = kGatherOpGateGrad;
+        ex.op = is_max ? kGatherOpGateGradMax : kGatherOpGateGrad;
         ex.acc_width = F;
-        ex.dst_width = 2 * F;
-        ex.dst_fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
-            // [Pd | gradient of accum] of the resident interval; its rows of X stay in ws_tile for after_gather
-            if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d)) return e;
-            HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * 2 * (size_t)F, h_dA + row0 * F, sizeof(float) * (size_t)F,
+        const int64_t dw = (is_max ? 3 : 2) * (int64_t)F;  // [Pd | gradient of accum] and, under max, the maxima
+        ex.dst_width = (int32_t)dw;
+        ex.dst_fill = [&, dw](int64_t row0, int64_t rows, float* dst, hipStream_t on, int64_t* h2d) -> saga_status {
+            // [Pd | gradient of accum ( | A )] of the resident interval; its rows of X stay in ws_tile for after_gather
+            if (saga_status e = prod.rows(&ctx->ws_tile, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, dw, on, h2d)) return e;
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * (size_t)dw, h_dA + row0 * F, sizeof(float) * (size_t)F,
                                           sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
             *h2d += rows * (int64_t)F * 4;
+            if (is_max) {
+                HIP_TRY(ctx, hipMemcpy2DAsync(dst + 2 * F, sizeof(float) * (size_t)dw, static_cast<const float*>(A->data) + row0 * A->ld,
+                                              sizeof(float) * (size_t)A->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+                *h2d += rows * (int64_t)F * 4;
+            }
             return SAGA_OK;
         };
-        ex.bytes_per_dst_row = sizeof(float) * (size_t)F;
+        ex.bytes_per_dst_row = sizeof(float) * (size_t)F * (is_max ? 2 : 1);
         bool any_done = false;
         ex.after_gather = [&, any_done](int64_t, int64_t rows, float* acc, hipStream_t on, int64_t*) mutable -> saga_status {
             const float* tX = static_cast<const float*>(ctx->ws_tile.p);
@@ -1162,23 +1175,30 @@ saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_ten
             if ((st = ctx->dev_alloc(&ctx->ws_dz, sizeof(float) * (size_t)self_tile * Fo))) return st;
     }
     HIP_TRY(ctx, hipStreamSynchronize(s));
+    const int64_t tw = (is_max ? 3 : 2) * (int64_t)F;  // width of the rows that travel
     saga_tensor rows_t{};
     rows_t.rows = n;
-    rows_t.cols = rows_t.ld = 2 * F;
+    rows_t.cols = rows_t.ld = tw;
     rows_t.dtype = SAGA_F32;
     rows_t.mem = SAGA_MEM_HOST;
     VertexFeed feed;
-    feed.bytes_per_row = sizeof(float) * (size_t)F;
-    feed.fill = [&](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
-        // [the destination part of the gate's argument | the gradient of accum] of the vertices at the far end of the out-edges
-        if (saga_status e = prod.rows(&ctx->ws_accum, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, 2 * (int64_t)F, on, h2d)) return e;
-        HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * 2 * (size_t)F, h_dA + row0 * F, sizeof(float) * (size_t)F,
+    feed.bytes_per_row = sizeof(float) * (size_t)F * (is_max ? 2 : 1);
+    feed.fill = [&, tw](int64_t row0, int64_t rows, float* dst, hipStream_t on, bool, int64_t* h2d) -> saga_status {
+        // [the destination part of the gate's argument | the gradient of accum ( | the maxima )] of the vertices at the far end
+        // of the out-edges
+        if (saga_status e = prod.rows(&ctx->ws_accum, row0, rows, 2 * F, F, SAGA_ACT_NONE, dst, tw, on, h2d)) return e;
+        HIP_TRY(ctx, hipMemcpy2DAsync(dst + F, sizeof(float) * (size_t)tw, h_dA + row0 * F, sizeof(float) * (size_t)F,
                                       sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
         *h2d += rows * (int64_t)F * 4;
+        if (is_max) {
+            HIP_TRY(ctx, hipMemcpy2DAsync(dst + 2 * F, sizeof(float) * (size_t)tw, static_cast<const float*>(A->data) + row0 * A->ld,
+                                          sizeof(float) * (size_t)A->ld, sizeof(float) * (size_t)F, (size_t)rows, hipMemcpyHostToDevice, on));
+            *h2d += rows * (int64_t)F * 4;
+        }
         return SAGA_OK;
     };
     StreamExtras ex;
-    ex.op = kGatherOpGateBoth;
+    ex.op = is_max ? kGatherOpGateBothMax : kGatherOpGateBoth;
     ex.acc_width = F;
     ex.n_out = 2;
     ex.dst_width = 2 * F;

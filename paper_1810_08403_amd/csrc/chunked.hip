@@ -346,8 +346,12 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
     const int64_t F_out = has_w ? vp->W->cols : Fw;
     if (n == 0) return SAGA_OK;
     if (n_out == 2 && (!extras->op || Fd != 2 * Fa)) return ctx->fail(SAGA_ERR_INTERNAL, "two outputs need a two-row edge function");
-    if (gated && (!extras || (!extras->dst_rows && !extras->dst_fill) || F != 2 * Fa))
+    // rows [x | m] travel, or [x | m | t] for the out-edge gradient under the max accumulator (t: the maximum gathered at the
+    // edge's far end)
+    const bool third_row = op == kGatherOpGateBothMax;
+    if (gated && (!extras || (!extras->dst_rows && !extras->dst_fill) || F != (third_row ? 3 : 2) * Fa))
         return ctx->fail(SAGA_ERR_INTERNAL, "streamed gated call without its hoisted rows");
+    if (op == kGatherOpGateGradMax && Fd != 3 * Fa) return ctx->fail(SAGA_ERR_INTERNAL, "the in-edge gradient under max needs three constant rows");
 
     WorkListParams wlp = work_list_params(ctx, F * 4);
     wlp.skip_empty = true;
@@ -588,9 +592,17 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             ga.dst = static_cast<const float*>(ctx->st_D.p);
             ga.dst_sigmoid = extras->dst_sigmoid ? 1 : 0;
             ga.ld_dst = Fd;
-            if (Fd == 2 * Fa) {
+            if (Fd >= 2 * Fa) {
                 ga.dst2 = ga.dst + Fa;
                 ga.ld_dst2 = Fd;
+            }
+            if (Fd == 3 * Fa) {  // third constant row: the maximum gathered at this destination
+                ga.dst3 = ga.dst + 2 * Fa;
+                ga.ld_dst3 = Fd;
+            }
+            if (third_row) {
+                ga.src3 = static_cast<const float*>(ctx->st_V[vb].p) + 2 * Fa;
+                ga.ld_src3 = F;
             }
         }
         ga.partials = static_cast<float*>(ctx->st_partials.p);
@@ -641,12 +653,22 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             a_busy = true;
             return SAGA_OK;
         }
+        // the Gather output itself, for a caller that keeps it for back-propagation (on the outbound stream)
+        auto accum_to_host = [&]() -> saga_status {
+            HIP_TRY(ctx, hipMemcpy2DAsync(extras->accum_rows + v0 * extras->ld_accum, (size_t)extras->ld_accum * 4, A, (size_t)Fw * 4,
+                                          (size_t)Fa * 4, (size_t)rows, hipMemcpyDeviceToHost, sout));
+            bytes_d2h += rows * Fa * 4;
+            return SAGA_OK;
+        };
+        const bool want_accum = extras && extras->accum_rows;
         if (!has_w) {
             HIP_TRY(ctx, hipEventRecord(ss.ev_a_ready, sc));
             HIP_TRY(ctx, hipStreamWaitEvent(sout, ss.ev_a_ready, 0));
             HIP_TRY(ctx, hipMemcpy2DAsync(Yh + v0 * Y->ld, (size_t)Y->ld * 4, A, (size_t)Fw * 4, (size_t)Fw * 4, (size_t)rows,
                                           hipMemcpyDeviceToHost, sout));
             bytes_d2h += rows * Fw * 4;
+            if (want_accum)
+                if (saga_status as = accum_to_host()) return as;
             HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sout));
             a_busy = true;
             return SAGA_OK;
@@ -695,7 +717,14 @@ saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X,
             yused[b] = true;
             ++ystep;
         }
-        HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sc));
+        if (want_accum) {  // A_j is free again when the products that read it are done and its copy has left
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_ready, sc));
+            HIP_TRY(ctx, hipStreamWaitEvent(sout, ss.ev_a_ready, 0));
+            if (saga_status as = accum_to_host()) return as;
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sout));
+        } else {
+            HIP_TRY(ctx, hipEventRecord(ss.ev_a_done, sc));
+        }
         a_busy = true;
         return SAGA_OK;
     };

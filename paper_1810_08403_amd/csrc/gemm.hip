@@ -733,7 +733,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     if (a.dtype == SAGA_F32) {
         if (a.out_dtype != SAGA_F32) return hipErrorInvalidValue;
         hipError_t e = hipSuccess;
-        if (launch_wlds(a, s, &e)) return e;
+        if (!a.tiled_only && launch_wlds(a, s, &e)) return e;
         return launch_typed<float, float>(a, s);
     }
     hipError_t e = hipSuccess;

@@ -865,6 +865,7 @@ saga_status VertexProducts::rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int3
     hg.K = F;
     hg.dtype = hg.out_dtype = SAGA_F32;
     hg.act = act;
+    hg.tiled_only = one_kernel ? 1 : 0;
     HIP_TRY(ctx, launch_gemm(hg, on));
     return SAGA_OK;
 }
@@ -876,13 +877,18 @@ saga_status VertexProducts::rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int3
 // interval's rows of X. The products therefore never cross the host link: it carries X once per destination
 // interval, like in a linear layer, instead of the two to three times wider hoisted rows there and back.
 static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep, int32_t agg,
-                                  const saga_vertex_params* vp, saga_tensor* Y)
+                                  const saga_vertex_params* vp, saga_tensor* Y, saga_tensor* accum_out)
 {
     const int64_t n = g->n;
     const int32_t F = (int32_t)X->cols;
     const bool gated = ep->op == SAGA_EDGE_GATED, pool = ep->op == SAGA_EDGE_POOL;
     StreamExtras ex;
     bool use_ex = false;
+    if (accum_out) {
+        ex.accum_rows = static_cast<float*>(accum_out->data);
+        ex.ld_accum = accum_out->ld;
+        use_ex = true;
+    }
     if (vp && vp->W_self) {
         ex.self_rows = static_cast<const float*>(X->data);
         ex.ld_self = X->ld;
@@ -893,6 +899,7 @@ static saga_status streamed_layer(saga_ctx* ctx, saga_graph* g, const saga_tenso
 
     const int32_t Fh = gated ? 2 * F : (int32_t)ep->W_pool->rows;  // width of the rows that travel over the edges
     VertexProducts prod;
+    prod.one_kernel = agg == SAGA_AGG_MAX;
     if (saga_status st = prod.init(ctx, X, ep)) return st;
     for (DevBuf* b : {&ctx->ws_accum, &ctx->ws_tile}) ctx->dev_free(b);  // sized per interval below
     VertexFeed feed;
@@ -1706,11 +1713,13 @@ saga_status saga_layer_forward(saga_ctx* ctx, const saga_graph* g, const saga_te
     if (streamed) {
         if (Y->mem != SAGA_MEM_HOST || g->where != SAGA_MEM_HOST)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed calls need X, Y and the graph in host memory");
-        if (accum_out) return ctx->fail(SAGA_ERR_UNSUPPORTED, "accum_out is not available on the streamed path");
+        if (accum_out && (!tensor_ok(accum_out) || accum_out->mem != SAGA_MEM_HOST || accum_out->dtype != SAGA_F32 ||
+                          accum_out->rows != g->n || accum_out->cols != Fm))
+            return ctx->fail(SAGA_ERR_INVALID_ARG, "accum_out of a streamed call must be a host n x Fm fp32 tensor");
         if (X->dtype != SAGA_F32) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed path is fp32 only");
         if (ep->op == SAGA_EDGE_MUL_WEIGHT && g->h_edge_data.empty() && g->nnz > 0)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
-        const saga_status sst = guarded(ctx, [&] { return streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y); });
+        const saga_status sst = guarded(ctx, [&] { return streamed_layer(ctx, const_cast<saga_graph*>(g), X, ep, agg, vp, Y, accum_out); });
         if (sst != SAGA_OK) chunk_grid_drain(ctx);  // host tensors are the caller's again when this returns
         return sst;
     }
@@ -1738,7 +1747,6 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
         if (agg != SAGA_AGG_SUM && agg != SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad accumulator");
         const bool pool_h = ep->op == SAGA_EDGE_POOL, gated_h = ep->op == SAGA_EDGE_GATED;
         if (ep->op < SAGA_EDGE_COPY || ep->op > SAGA_EDGE_POOL) return ctx->fail(SAGA_ERR_INVALID_ARG, "bad edge op");
-        if (gated_h && agg == SAGA_AGG_MAX) return ctx->fail(SAGA_ERR_UNSUPPORTED, "the streamed backward pass does not cover max over gated messages (the resident one does)");
         const bool max_or_pool = pool_h || (agg == SAGA_AGG_MAX && !gated_h);
         if (vp->act != SAGA_ACT_NONE && vp->act != SAGA_ACT_RELU && vp->act != SAGA_ACT_SIGMOID)
             return ctx->fail(SAGA_ERR_INVALID_ARG, "bad activation");
@@ -1805,7 +1813,7 @@ saga_status saga_layer_backward(saga_ctx* ctx, const saga_graph* g, const saga_t
             return ctx->fail(SAGA_ERR_INVALID_ARG, "streamed MUL_WEIGHT needs saga_graph_set_edge_data");
         DeviceGuard guard_h(ctx->device);
         const saga_status sst = guarded(ctx, [&] {
-            return gated_h ? streamed_gated_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads)
+            return gated_h ? streamed_gated_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
                    : max_or_pool ? streamed_max_pool_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, agg, vp, grads)
                                  : streamed_backward(ctx, const_cast<saga_graph*>(g), X, A, Y, dY, ep, vp, grads);
         });

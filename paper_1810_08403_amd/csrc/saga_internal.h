@@ -435,7 +435,7 @@ struct GemmArgs {
     const void* A2;     // optional second operand, M x K2: C = act(A Bt[:, :Kp]^T + A2 Bt[:, Kp:]^T + bias),
     int64_t lda2;       // Kp = K padded to the K tile (bt_padded_shape)
     int32_t K2;
-    int32_t pad_;
+    int32_t tiled_only;  // 1: always k_gemm_nt, whatever M: rows of one product formed in calls of different sizes are then the same bits
     const void* Bt;     // Npad x Kpad, dtype, row n = column n of the weight matrix
     int64_t ldbt;       // = Kpad
     const float* bias;  // [N] fp32, nullable
@@ -521,7 +521,7 @@ saga_status resident_backward_bf16(saga_ctx* ctx, saga_graph* g, const saga_tens
                                    const saga_edge_params* ep, const saga_vertex_params* vp, const saga_layer_grads* grads);
 // backward pass of a streamed layer: tensors in host memory, host graph (backward.hip)
 saga_status streamed_gated_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
-                                    const saga_tensor* dY, const saga_edge_params* ep, const saga_vertex_params* vp,
+                                    const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
                                     const saga_layer_grads* grads);
 saga_status streamed_max_pool_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                                        const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,
@@ -574,6 +574,10 @@ struct StreamExtras {
     // instead of self_rows: produces rows [row0, row0 + rows) of the second operand (F_self wide, compact) in dst on
     // stream s and adds the bytes it copies to *h2d (the streamed backward pass forms the interval's own dZ there)
     std::function<saga_status(int64_t row0, int64_t rows, float* dst, hipStream_t s, int64_t* h2d)> self_fill;
+    // the caller's accum_out: host, n rows of acc_width values, ld_accum elements apart; every destination interval's Gather
+    // output is copied there on the outbound stream once its ApplyVertex products have been enqueued
+    float* accum_rows = nullptr;
+    int64_t ld_accum = 0;
 };
 saga_status streamed_forward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_edge_params* ep,
                              int32_t agg, const saga_vertex_params* vp, saga_tensor* Y, const VertexFeed* feed = nullptr,
@@ -591,6 +595,9 @@ struct VertexProducts {
     float* bt = nullptr;
     float* bias = nullptr;
     int64_t k_pad = 0;
+    // under the max accumulator: one product kernel for every interval size, because the backward pass forms these rows
+    // again, in intervals of its own, and compares the messages made from them with the forward pass's maxima bit for bit
+    bool one_kernel = false;
     saga_status init(saga_ctx* c, const saga_tensor* x, const saga_edge_params* ep);
     saga_status rows(DevBuf* tmp, int64_t row0, int64_t n_rows, int32_t w0, int32_t n_cols, int32_t act, float* dst, int64_t ldc,
                      hipStream_t on, int64_t* h2d) const;

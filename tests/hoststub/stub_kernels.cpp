@@ -64,10 +64,11 @@ void store_finished(const GatherArgs& a, float* out, int64_t ld_out, int64_t v, 
 
 void gather_cpu(const GatherArgs a)
 {
-    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
+    const bool under_max = a.op == kGatherOpGateGradMax || a.op == kGatherOpGateBothMax;  // only maximal edges count
+    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth || under_max;
     const bool maxgrad = a.op == kGatherOpMaxGrad;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || maxgrad;
-    const bool both = a.op == kGatherOpGateBoth;
+    const bool both = a.op == kGatherOpGateBoth || a.op == kGatherOpGateBothMax;
     const int agg = (grad || maxgrad) ? SAGA_AGG_SUM : a.agg;
     const float* w = (!gated || maxgrad) ? a.edge_w : nullptr;
     for (int64_t i = 0; i < a.n_items; ++i) {
@@ -81,6 +82,7 @@ void gather_cpu(const GatherArgs a)
                 if (maxgrad && a.dst_sigmoid) c1 = sigmoid(c1);
             }
             if (grad) c2 = a.dst2[(int64_t)it.v * a.ld_dst2 + f];
+            const float c3 = a.op == kGatherOpGateGradMax ? a.dst3[(int64_t)it.v * a.ld_dst3 + f] : 0.f;
             for (int32_t e = it.e0; e < it.e1; ++e) {
                 const int64_t u = a.row_idx[e];
                 if (u < 0) die("negative source id reached the propagation kernel");
@@ -91,6 +93,13 @@ void gather_cpu(const GatherArgs a)
                     const double msg = (double)sigmoid(x + c1) * m;
                     acc = agg == SAGA_AGG_SUM ? acc + msg : (msg > acc ? msg : acc);
                 } else if (grad) {
+                    if (under_max) {  // the forward stand-in's message, formed again and compared with the kept maximum
+                        // over the in-edges the message matrix's row travels (m) and the maximum is the item's third constant
+                        // row; over the out-edges that row is the item's own (c2) and the maximum travels as a third row
+                        const bool in_edges = a.op == kGatherOpGateGradMax;
+                        const float kept = in_edges ? c3 : static_cast<const float*>(a.src3)[u * a.ld_src3 + f];
+                        if ((float)((double)sigmoid(x + c1) * (in_edges ? m : c2)) != kept) continue;
+                    }
                     const double g = 1.0 / (1.0 + std::exp(-((double)x + c1)));
                     acc += g * (1.0 - g) * ((double)c2 * m);
                     if (both) acc2 += g * m;
@@ -179,12 +188,15 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     if (a.n_items <= 0) return hipSuccess;
     if ((a.bias || a.act != SAGA_ACT_NONE) && a.accumulate) return hipErrorInvalidValue;
     if (a.ld_src < 0 || a.ld_src >= (1LL << 30) || a.ld_src2 < 0 || a.ld_src2 >= (1LL << 30)) return hipErrorInvalidValue;
-    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateBoth;
+    const bool both_any = a.op == kGatherOpGateBoth || a.op == kGatherOpGateBothMax;
+    const bool grad = a.op == kGatherOpGateGrad || a.op == kGatherOpGateGradMax || both_any;
     const bool gated = a.op == SAGA_EDGE_GATED || grad || a.op == kGatherOpMaxGrad;
     if (gated) {
         if (!a.src2 || !a.dst || (grad && (!a.dst2 || a.agg != SAGA_AGG_SUM))) return hipErrorInvalidValue;
         if (a.op == kGatherOpMaxGrad && a.agg != SAGA_AGG_SUM) return hipErrorInvalidValue;
-        if (a.op == kGatherOpGateBoth && (!a.out || !a.out2 || a.out16 || (a.partials && !a.partials2))) return hipErrorInvalidValue;
+        if (both_any && (!a.out || !a.out2 || a.out16 || (a.partials && !a.partials2))) return hipErrorInvalidValue;
+        if (a.op == kGatherOpGateGradMax && !a.dst3) return hipErrorInvalidValue;
+        if (a.op == kGatherOpGateBothMax && !a.src3) return hipErrorInvalidValue;
         if (a.dtype != SAGA_F32) return hipErrorInvalidValue;
     }
     const GatherArgs copy = a;

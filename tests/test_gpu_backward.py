@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import saga_inputs as si
-from helpers import TOL_F32, assert_sum_close, make_graph, new_context
+from helpers import TOL_F32, assert_sum_close, coarse_gated_workload, make_graph, new_context
 
 pytestmark = pytest.mark.gpu
 
@@ -372,21 +372,6 @@ def test_gated_backward_configuration_4_at_scale_16(ctx):
     graph.destroy()
 
 
-def _coarse_gated_workload(scale, F, Fo):
-    """Configuration 4's layer shape with X, W_gate, b_gate and W_msg on coarse grids (multiples of 1/4 and 1/8): the
-    hoisted products are then exact in fp32 in any order of summation, so the GPU's fp32 messages sigmoid(z) * m and the
-    oracle's fp64 ones are formed from the same z and m and rank alike, ties included (two different (z, m) pairs give
-    messages that differ by far more than the 1e-7 the two sigmoids differ by)."""
-    wl = si.workload(4, scale=scale, f_in=F, f_out=Fo)
-    q = lambda t, lim, s: torch.round(t.clamp(-lim, lim) * s) / s
-    wl.X = q(wl.X, 1.0, 4)
-    wl.W_gate, wl.b_gate, wl.W_msg = q(wl.W_gate, 1.0, 8), q(wl.b_gate, 0.5, 8), q(wl.W_msg, 1.0, 8)
-    Xd = wl.X.double()
-    z = (Xd @ wl.W_gate[:, :F].double().T).abs().max() + (Xd @ wl.W_gate[:, F:].double().T).abs().max() + 0.5
-    assert z.item() <= 12.0 and (wl.W_gate != 0).float().mean().item() > 0.2
-    return wl
-
-
 @pytest.mark.parametrize("F,Fo,act,with_b,with_msg,with_self", [
     (8, 8, "relu", True, True, False),
     (64, 32, "relu", True, True, False),
@@ -402,7 +387,7 @@ def test_gated_max_backward_matches_oracle(ctx, F, Fo, act, with_b, with_msg, wi
     """Max over gated messages backwards. The Gather output handed to the backward pass is the forward pass's own (its
     maxima are compared bit for bit with the recomputed messages); the stored output is synthetic, only the activation's
     derivative is taken from it, and the oracle is given the same dZ."""
-    wl = _coarse_gated_workload(10, F, Fo)
+    wl = coarse_gated_workload(10, F, Fo)
     g = wl.graph
     n = g.n
     dev = "cuda"

@@ -72,3 +72,9 @@ def test_dense_block_plan_and_schedule(stub_lib):
     """The dense-block form of a resident graph (ranks, 64 x 32 blocks as edge lists or finished operands, chunks, the
     partial-row slots shared with the sparse remainder's work list, weight packing) against the oracle."""
     _run("run_hybrid.py", stub_lib)
+
+
+def test_max_over_gated_messages_from_host_memory(stub_lib):
+    """The streamed forward call keeps its Gather output (accum_out in host memory) and the streamed backward call of max
+    over gated messages carries those maxima through both chunk schedules as a third row per vertex."""
+    _run("run_gated_max.py", stub_lib)
