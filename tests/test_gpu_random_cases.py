@@ -434,16 +434,13 @@ def test_random_streamed_case(seed):
             bwd = oracle.layer_backward(cp, ri, X.numpy(), fwd["A"], dY.numpy(), W.numpy(), op, wn, bias=bias.numpy(), W_self=Wsn, act=act)
         A_h, Yf_h, dY_h = _pinned(bwd["A"] if agg == "max" else fwd["A"]), _pinned(fwd["Y"]), _pinned(dY)
         if op == "pool":
-            # the backward pass recomputes the pooled rows in fp32 and looks for them in A bit for bit: A comes from the
-            # device's own forward pass (resident, a second context), checked against the oracle's before it is used
-            with new_context() as c2:
-                g2 = c2.graph_create_csc(n, g.col_ptr.cuda(), g.row_idx.cuda())
-                Yd, Ad = torch.empty(n, Fo, device="cuda"), torch.empty(n, Fm, device="cuda")
-                c2.layer_forward(g2, X.cuda(), Yd, edge_op=op, agg=agg, W=W.cuda(), W_self=Wsd, bias=bias.cuda(), act=act, accum_out=Ad, **kw)
-                torch.cuda.synchronize()
-                g2.destroy()
-            assert_sum_close(Ad.cpu().numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " pooled Gather")
-            A_h = _pinned(Ad.cpu().numpy())     # (Y stays the oracle's: ReLU's mask is then the same on both sides)
+            # the backward pass recomputes the pooled rows in fp32 and looks for them in A bit for bit: A is the Gather output
+            # the streamed forward call keeps (accum_out), checked against the oracle's before it is used
+            Ab_h, A_h = _strided(n, Fm, pads[1], pinned=True)
+            ctx.layer_forward(graph, X_h, Y_h, edge_op=op, agg=agg, W=W.cuda(), W_self=Wsd, bias=bias.cuda(), act=act, accum_out=A_h, **kw)
+            assert_sum_close(A_h.numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " pooled Gather")
+            assert _padding_untouched(Ab_h, Fm), what + ": wrote between the rows of accum_out"
+            # (Y stays the oracle's: ReLU's mask is then the same on both sides)
         dXb_h, dX_h = _strided(n, F, pads[2], pinned=True)
         nan = lambda *s: torch.full(s, float("nan"), device="cuda")
         out = dict(dW=nan(Fm, Fo), dbias=nan(Fo))
@@ -475,6 +472,91 @@ def test_random_streamed_case(seed):
             assert ctx.peak_device_bytes() <= budget, what + " (backward)"
     graph.destroy()
     ctx.destroy()
+
+
+@pytest.mark.parametrize("seed", range(max(12, N_CASES // 6)))
+def test_random_streamed_gated_max_backward_case(seed):
+    """Max over gated messages from host memory, forwards and backwards, on random small graphs, widths, grids of
+    intervals or budgets: the forward call keeps its Gather output in a pinned tensor whose rows lie further apart than
+    they are wide, and the backward call finds its maxima there. Coarse X and gate parameters as in the resident test."""
+    import paper_1810_08403_amd as saga
+    rng, g, F, Fo, _, _, _, _ = _case(2600 + seed)
+    F = min(F, 96)
+    n = g.n
+    act = ["relu", "none", "sigmoid", "relu"][seed % 4]
+    t = lambda *shape, s=1.0: torch.as_tensor((rng.standard_normal(shape) * s).astype(np.float32))
+    q = lambda x, lim, k: torch.round(x.clamp(-lim, lim) * k) / k
+    X, W, dY = q(t(n, F), 1.0, 4), t(F, Fo, s=0.3), t(n, Fo)
+    sc = 1.5 / max(F, 1) ** 0.5
+    Wg, bg = q(t(F, 2 * F, s=sc), 1.0, 8), q(t(F, s=0.3), 0.5, 8)
+    Wm = q(t(F, F, s=sc), 1.0, 8) if seed % 3 != 1 else None
+    Ws = t(F, Fo, s=0.3) if seed % 5 < 2 else None
+    Y_in = t(n, Fo)
+    if act == "sigmoid":
+        Y_in = torch.sigmoid(Y_in)
+    slope = {"none": torch.ones(n, Fo, dtype=torch.float64), "relu": (Y_in > 0).double(), "sigmoid": Y_in.double() * (1 - Y_in.double())}[act]
+    dZ = (dY.double() * slope).float()
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    opt = lambda v: None if v is None else v.cuda()
+    npo = lambda v: None if v is None else v.numpy()
+    bwd = oracle.gated_backward(cp, ri, X.numpy(), None, dZ.numpy(), W.numpy(), W_gate=Wg.numpy(), b_gate=bg.numpy(), W_msg=npo(Wm), act="none",
+                                W_self=npo(Ws), agg="max")
+    opts = dict(bwd_tile_rows=int(rng.choice([0, 64, 300, 1000])))
+    budget = 0
+    if rng.random() < 0.6 or n < 8:
+        opts.update(dst_intervals=int(rng.integers(1, min(n, 5) + 1)), src_intervals=int(rng.integers(1, min(n, 7) + 1)))
+    else:
+        budget = int((n * (8 * F + Fo) * 4 + g.nnz * 8) * rng.uniform(0.3, 1.2)) + (1 << 20)
+    pads = [int(x) for x in rng.choice([0, 0, 1, 4, 20], 3)]
+    what = f"seed {seed}: n={n} nnz={g.nnz} F={F}->{Fo} {act} msg={Wm is not None} self={Ws is not None} {opts} budget={budget} pads={pads}"
+    print(what, flush=True)
+    ctx = saga.Context(0, hbm_budget_bytes=budget)
+    try:
+        for name, val in opts.items():
+            ctx.set_option(name, val)
+        graph = ctx.graph_create_csc(n, g.col_ptr, g.row_idx)
+        _, X_h = _strided(n, F, pads[0], src=X, pinned=True)
+        Ab_h, A_h = _strided(n, F, pads[1], pinned=True)
+        dXb_h, dX_h = _strided(n, F, pads[2], pinned=True)
+        Yf_h, Y_h, dY_h = torch.empty(n, Fo).pin_memory(), _pinned(Y_in.numpy()), _pinned(dY.numpy())
+        gate = dict(edge_op="gated", agg="max", W_gate=Wg.cuda(), b_gate=bg.cuda(), W_msg=opt(Wm), W_self=opt(Ws))
+        A_h.fill_(float("nan"))
+        try:
+            ctx.layer_forward(graph, X_h, Yf_h, W=W.cuda(), act="none", accum_out=A_h, **gate)
+        except saga.SagaError as e:
+            assert budget and e.status == 4, what
+            return
+        if n > 0:
+            assert_sum_close(A_h.numpy(), bwd["A"], np.maximum(np.abs(bwd["A"]), 1e-30), TOL_F32, what + " A", tiny_outputs=True)
+        assert _padding_untouched(Ab_h, F), what + ": wrote between the rows of accum_out"
+        nan = lambda *s: torch.full(s, float("nan"), device="cuda")
+        out = dict(dW=nan(F, Fo), dW_gate=nan(F, 2 * F), db_gate=nan(F))
+        if Wm is not None:
+            out["dW_msg"] = nan(F, F)
+        if Ws is not None:
+            out["dW_self"] = nan(F, Fo)
+        for rep, want_dx in enumerate([True, False]):
+            for v in out.values():
+                v.fill_(float("nan"))
+            dX_h.fill_(float("nan"))
+            rest = {k: v for k, v in out.items() if k != "dW"}
+            try:
+                ctx.layer_backward(graph, A_h, dY_h, W.cuda(), out["dW"], X=X_h, Y=Y_h, act=act, dX=dX_h if want_dx else None, **rest, **gate)
+            except saga.SagaError as e:
+                assert budget and e.status == 4, what   # the backward pass holds more per vertex than the forward pass
+                break
+            if n == 0:
+                continue
+            for name, got in out.items():
+                assert_sum_close(got.cpu().numpy(), bwd[name], np.maximum(bwd[name + "_abs"], 1e-30), TOL_F32, what + f" {name}, call {rep}", tiny_outputs=True)
+            if want_dx:
+                assert_sum_close(dX_h.numpy(), bwd["dX"], bwd["dX_abs"], TOL_F32, what + f" dX, call {rep}", tiny_outputs=True)
+            assert _padding_untouched(dXb_h, F), what + ": wrote between the rows of dX"
+        if budget:
+            assert ctx.peak_device_bytes() <= budget, what
+        graph.destroy()
+    finally:
+        ctx.destroy()
 
 
 @pytest.mark.parametrize("seed", range(max(8, N_CASES // 12)))
