@@ -588,12 +588,18 @@ saga_status ensure_hybrid(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32
     // The remainder's piece size goes by the bytes of a source row, not by the narrow-row rule of the general list: its
     // columns have lost their heavy blocks. Rows of 256 and 512 bytes keep 64 edges per piece (backward pass of the R-MAT
     // 18 workload, 128 bf16 features: 3.65 ms at 64, 3.98 at 32; 256 features: 3.42 at 64, 3.46 at 48); rows of 1 KiB take
-    // 48 (forward layer of the same workload, 512 bf16 features: 4.11 ms at 48, 4.21 at 40, 4.23 at 56 and 64, 4.32 at
-    // 32, 4.73 at 80: longer pieces reach over more bands of source rows, shorter ones cost k_combine more than the
-    // sparse kernel gains). Columns are cut from 128 edges on either way.
+    // fewer (forward layer of the same workload, 512 bf16 features, bands of 1 MiB: 4.11 ms at 48, 4.21 at 40, 4.23 at 56
+    // and 64, 4.32 at 32, 4.73 at 80: longer pieces reach over more bands of source rows, shorter ones cost k_combine more
+    // than the sparse kernel gains). Columns are cut from 128 edges on either way.
     (void)width;
     WorkListParams p = work_list_params(ctx, row_bytes, 0);
-    if (!ctx->opt_split_set && row_bytes >= 1024) p.min_edges = 48;
+    // Rows of 1 KiB also take bands of 2 MiB of them instead of 1 MiB, and with those pieces of 40 edges: what is left of a
+    // column after its well-filled blocks have gone has few edges per band, and a piece then ends at the next band
+    // boundary sooner than it is worth (same workload, one session: 4.25 ms per layer with bands of 1 MiB and 48 edges;
+    // with 2 MiB 4.16 at 48, 4.17 at 44, 4.11 at 40, 4.18 at 36, 4.22 at 32; with 4 MiB 4.32 at 48, 4.18 at 40, 4.17 at 32).
+    const bool wide_rows = row_bytes >= 1024;
+    if (!ctx->opt_split_set && wide_rows) p.min_edges = (!ctx->opt_stripe_set && p.stripe_rows > 0) ? 40 : 48;
+    if (!ctx->opt_stripe_set && wide_rows && p.stripe_rows > 0) p.stripe_rows *= 2;
     const HybridParams hp = hybrid_params(ctx);
     auto same = [](const WorkListParams& a, const WorkListParams& b) {
         return a.min_edges == b.min_edges && a.cut_degree == b.cut_degree && a.stripe_rows == b.stripe_rows && a.team == b.team && a.order == b.order;
@@ -1155,6 +1161,7 @@ saga_status saga_set_option(saga_ctx* ctx, const char* name, int64_t value)
     } else if (!strcmp(name, "stripe_kb")) {
         if (value < 0 || value > (1 << 22)) return ctx->fail(SAGA_ERR_INVALID_ARG, "stripe_kb must be in [0, 2^22]");
         ctx->opt_stripe_kb = value;
+        ctx->opt_stripe_set = true;
     } else if (!strcmp(name, "piece_order")) {
         if (value != 0 && value != 1) return ctx->fail(SAGA_ERR_INVALID_ARG, "piece_order must be 0 or 1");
         ctx->opt_piece_order = (int)value;

@@ -165,6 +165,7 @@ struct saga_ctx {
     bool opt_split_set = false;    // the caller has chosen it (narrow rows otherwise get finer pieces, see work_list_params)
     int64_t opt_cut_degree = 0;    // 0 = 2 * split
     int64_t opt_stripe_kb = 1024;  // source-row band one piece may span, in KiB of feature rows (0 = cut by count)
+    bool opt_stripe_set = false;   // the caller has chosen it (the remainder of the dense-block path otherwise takes wider bands for 1 KiB rows)
     int opt_piece_order = 1;       // see WorkListParams::order
     int opt_xcd_remap = 1;
     int opt_mma = 0;               // 1: bf16 sum propagation with the multiply-accumulate on the matrix unit (measured: a tie)
