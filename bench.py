@@ -306,12 +306,12 @@ def main():
     if ms_dense > 0 and not args.transform_first:
         flops = 0.0
         bytes_dense = 0.0
-        if wl.edge_op == "gated":
-            flops += 2.0 * n * f_in * 3 * f_in
-            bytes_dense += n * f_in * es + n * 3 * f_in * 4
-        if wl.edge_op == "pool":
-            flops += 2.0 * n * f_in * f_msg
-            bytes_dense += n * f_in * es + n * f_msg * 4
+        # rows x columns of per-vertex products the library formed (it leaves out the rows of vertices that are no edge's
+        # endpoint where its product kernel takes a list of rows); the rows of X those products read are counted whole
+        hoisted = tm["n_hoist_row_cols"]
+        if wl.edge_op in ("gated", "pool"):
+            flops += 2.0 * f_in * hoisted
+            bytes_dense += n * f_in * es + hoisted * 4
         if has_w:
             flops += 2.0 * n * f_msg * f_out + (2.0 * n * f_in * f_out if wl.W_self is not None else 0.0)
             bytes_dense += n * f_msg * es + (n * f_in * es if wl.W_self is not None else 0) + n * f_out * es

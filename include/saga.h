@@ -129,6 +129,8 @@ typedef struct saga_timings {
     double ms_dense_blocks;  /* the part of ms_gather spent in the dense-block kernel (option "dense_blocks") */
     int64_t n_dense_blocks, n_dense_edges; /* of the last layer that used the dense-block path, else 0 */
     int64_t n_partial_rows;  /* partial rows (of the row width, fp32) the last layer wrote and combined */
+    int64_t n_hoist_row_cols; /* rows x columns of per-vertex products (Section 3.2) the last gated or pooled resident layer
+                                 formed: below n x 3F (n x F_pool) where rows of vertices that are no edge's endpoint were left out */
 } saga_timings;
 
 /*

@@ -69,7 +69,8 @@ class Timings(ctypes.Structure):
                 ("ms_wall_streamed", ctypes.c_double), ("plan_dst_intervals", ctypes.c_int32),
                 ("plan_src_intervals", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("n_work_items", ctypes.c_int64), ("n_split_vertices", ctypes.c_int64), ("ms_dense_blocks", ctypes.c_double),
-                ("n_dense_blocks", ctypes.c_int64), ("n_dense_edges", ctypes.c_int64), ("n_partial_rows", ctypes.c_int64)]
+                ("n_dense_blocks", ctypes.c_int64), ("n_dense_edges", ctypes.c_int64), ("n_partial_rows", ctypes.c_int64),
+                ("n_hoist_row_cols", ctypes.c_int64)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}

@@ -254,7 +254,7 @@ static saga_status gated_backward_rest(saga_ctx* ctx, saga_graph* g, const saga_
     float* dA = static_cast<float*>(ctx->ws_grad.p);
     if ((st = rows_times_wt(ctx, dZ, lddz, Fo, vp->W, nullptr, 0, 0, nullptr, n, F, dA, F))) return st;
     // the per-vertex products the gates are made of
-    if ((st = hoist_gated(ctx, X, ep, n, F))) return st;
+    if ((st = hoist_gated(ctx, X, ep, n, F, g))) return st;
     if ((st = ctx->dev_alloc(&ctx->ws_dh, sizeof(float) * (size_t)n * 3 * F))) return st;
     const float* H = static_cast<const float*>(ctx->ws_hoist.p);
     float* dH = static_cast<float*>(ctx->ws_dh.p);

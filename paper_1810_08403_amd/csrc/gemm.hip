@@ -301,19 +301,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(T) =
 constexpr int kWldsK = 128, kWldsBM = 64, kWldsBN = 128;
 
 // bias, activation and store of value r of a lane's 32 x 32 accumulator tile (row row0 + (r / 4) * 8 + r % 4)
+// out_row: the row of C the value goes to (row0 + dr itself, or what the row list names for it)
 template <int ACT, bool CHECK>
-__device__ __forceinline__ void wlds_store_one(const GemmArgs& a, float v, int r, int64_t row0, int col, float bias)
+__device__ __forceinline__ void wlds_store_one(const GemmArgs& a, float v, int r, int64_t row0, int64_t out_row, int col, float bias)
 {
     const int dr = (r >> 2) * 8 + (r & 3);
     if (CHECK && (col >= a.N || row0 + dr >= a.M)) return;
     float y = v + bias;
     if (ACT == SAGA_ACT_RELU) y = y > 0.f ? y : 0.f;
     if (ACT == SAGA_ACT_SIGMOID) y = sigmoid_f32(y);
-    static_cast<float*>(a.C)[(row0 + dr) * a.ldc + col] = y;
+    static_cast<float*>(a.C)[out_row * a.ldc + col] = y;
 }
 // The activation is a parameter of the kernel: as a run-time select per value it made every product compute the sigmoid's
 // exponential for every value.
-template <int ACT>
+// IDS: the product is taken over the rows a.row_ids names (row i of the product reads row row_ids[i] of A and writes row
+// row_ids[i] of C; the list is padded to whole tiles with its last entry). The ids a tile's copies need are read a tile
+// before the copies are issued and the ids its results go to at the tile's start, so that no step waits for them: every
+// wait for memory in the loop is the one at the end of a tile.
+template <int ACT, bool IDS>
 __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n_cg, const int wg_per_cg, const int n_tiles_m)
 {
     // three separate arrays: the compiler makes an LDS read wait for the copies in flight (they count as memory
@@ -337,10 +342,21 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
     // a wave-wide copy: rows 2 idx and 2 idx + 1 of a tile, lane l the chunk that belongs at position l & 31 of row
     // 2 idx + (l >> 5), i.e. chunk (l & 31) ^ (row & 15) of the row in memory. A wavefront makes eight per tile.
     const int crow = lane >> 5, cpos = lane & 31;
+    const int32_t* __restrict__ ids = a.row_ids;
+    int nid[4] = {0, 0, 0, 0};  // IDS: the rows of A this lane copies for the tile after the one being copied
+    auto load_ids = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) nid[i] = ids[(int64_t)tile * kWldsBM + 2 * (wave * 4 + i) + crow];
+    };
     auto copy_one = [&](int tile, float (&buf)[kWldsBM * kWldsK], int i) {
         const int idx = wave * 4 + i, row = 2 * idx + crow;
-        int64_t gr = (int64_t)tile * kWldsBM + row;
-        if (gr >= a.M) gr = a.M - 1;  // rows past the end are copies of the last row; their results are not stored
+        int64_t gr;
+        if constexpr (IDS) {
+            gr = nid[i];
+        } else {
+            gr = (int64_t)tile * kWldsBM + row;
+            if (gr >= a.M) gr = a.M - 1;  // rows past the end are copies of the last row; their results are not stored
+        }
         const float* src = A + gr * a.lda + ((cpos ^ (row & 15)) << 2);
         __builtin_amdgcn_global_load_lds(src, (lds_ptr)(&buf[idx * 256]), 16, 0, 0);
     };
@@ -350,8 +366,12 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
         const float* src = Bt + (int64_t)(cg * kWldsBN + row) * a.ldbt + ((cpos ^ (row & 15)) << 2);  // Bt is padded to 128 rows
         __builtin_amdgcn_global_load_lds(src, (lds_ptr)(&Bs[idx * 256]), 16, 0, 0);
     }
+    if constexpr (IDS) load_ids(j);
 #pragma unroll
     for (int i = 0; i < 4; ++i) copy_one(j, As0, i);
+    if constexpr (IDS) {
+        if (count > 1) load_ids(j + wg_per_cg);
+    }
     const int col0 = cg * kWldsBN + wn * 32 + m;
     const float bias = (a.bias && col0 < a.N) ? a.bias[col0] : 0.f;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's copies have landed
@@ -369,12 +389,27 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
     floatx16 pacc;
     int64_t prow0 = 0;
     bool pfull = false;
+    int4 oid[4], poid[4];  // IDS: the rows of C this lane's 16 results of the current / the previous tile go to
+    auto out_row = [&](int r) -> int64_t {
+        if constexpr (IDS) {
+            const int4 q = poid[r >> 2];
+            return (r & 3) == 0 ? q.x : (r & 3) == 1 ? q.y : (r & 3) == 2 ? q.z : q.w;
+        } else {
+            return prow0 + (r >> 2) * 8 + (r & 3);
+        }
+    };
     auto do_tile = [&](int t, const float (&cur)[kWldsBM * kWldsK], float (&nxt)[kWldsBM * kWldsK], auto pchk) __attribute__((always_inline)) {
         constexpr bool PCHECK = decltype(pchk)::value;  // the previous tile ends past M or N
         const int tile = j + t * wg_per_cg;
         if (t + 1 < count) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) copy_one(tile + wg_per_cg, nxt, i);
+        }
+        if constexpr (IDS) {
+            if (t + 2 < count) load_ids(tile + 2 * wg_per_cg);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                oid[q] = *reinterpret_cast<const int4*>(ids + (int64_t)tile * kWldsBM + wm * 32 + h * 4 + 8 * q);
         }
         __builtin_amdgcn_sched_barrier(0);  // the copies start before the MFMAs they run under
         floatx16 acc;
@@ -396,8 +431,8 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
             for (int c = 0; c < 4; ++c)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c]), __uint_as_float(fb0[c]), acc, 0, 0, 0);
             if (s_ < 8 && t > 0) {
-                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_], 2 * s_, prow0, col0, bias);
-                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_ + 1], 2 * s_ + 1, prow0, col0, bias);
+                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_], 2 * s_, prow0, out_row(2 * s_), col0, bias);
+                wlds_store_one<ACT, PCHECK>(a, pacc[2 * s_ + 1], 2 * s_ + 1, prow0, out_row(2 * s_ + 1), col0, bias);
             }
             __builtin_amdgcn_sched_barrier(0);
             fa = na;
@@ -407,6 +442,10 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();  // every wavefront is done with this buffer, and sees the next one
         pacc = acc;
+        if constexpr (IDS) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) poid[q] = oid[q];
+        }
         prow0 = (int64_t)tile * kWldsBM + wm * 32 + h * 4;
         pfull = (int64_t)tile * kWldsBM + kWldsBM <= a.M && cg * kWldsBN + kWldsBN <= a.N;
     };
@@ -421,7 +460,7 @@ __global__ __launch_bounds__(512) void k_gemm_wlds(const GemmArgs a, const int n
         if (t + 1 < count) tile_of(t + 1, As1, As0);
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) wlds_store_one<ACT, true>(a, pacc[r], r, prow0, col0, bias);
+    for (int r = 0; r < 16; ++r) wlds_store_one<ACT, true>(a, pacc[r], r, prow0, out_row(r), col0, bias);
 }
 
 // ---------------------------------------------------------------------------
@@ -684,21 +723,39 @@ void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_
 
 // the weights-in-LDS kernel where it applies (fp32, one operand, K = 128, rows in 16-byte fragments, enough rows to give
 // every compute unit several tiles); false: not applicable
-static bool launch_wlds(const GemmArgs& a, hipStream_t s, hipError_t* err)
+static bool wlds_applies(const GemmArgs& a)
 {
+    if (a.dtype != SAGA_F32 || a.out_dtype != SAGA_F32 || a.tiled_only) return false;
     if (a.A2 || a.K != kWldsK || a.lda % 4 != 0 || (reinterpret_cast<uintptr_t>(a.A) & 15u) || a.M < 16 * 1024) return false;
+    if (a.row_ids && (reinterpret_cast<uintptr_t>(a.row_ids) & 15u)) return false;
     if (a.ldbt % 4 != 0 || a.ldbt < kWldsK || (reinterpret_cast<uintptr_t>(a.Bt) & 15u)) return false;
     const int n_cg = (a.N + kWldsBN - 1) / kWldsBN;
     const int64_t n_tiles_m = (a.M + kWldsBM - 1) / kWldsBM;
-    if (n_cg > 32 || n_tiles_m > 0x7fffffffLL) return false;
+    return n_cg <= 32 && n_tiles_m <= 0x7fffffffLL;
+}
+
+bool gemm_takes_row_list(const GemmArgs& a) { return a.row_ids && wlds_applies(a); }
+
+static bool launch_wlds(const GemmArgs& a, hipStream_t s, hipError_t* err)
+{
+    if (!wlds_applies(a)) return false;
+    const int n_cg = (a.N + kWldsBN - 1) / kWldsBN;
+    const int64_t n_tiles_m = (a.M + kWldsBM - 1) / kWldsBM;
     const int wg_per_cg = std::max(8, 256 / n_cg / 8 * 8);  // one workgroup per compute unit, a multiple of the 8 XCDs per column group
     const dim3 grid((unsigned)(wg_per_cg * n_cg));
-    if (a.act == SAGA_ACT_RELU)
-        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_RELU>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    if (a.row_ids) {
+        if (a.act == SAGA_ACT_RELU)
+            hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_RELU, true>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+        else if (a.act == SAGA_ACT_SIGMOID)
+            hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_SIGMOID, true>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+        else
+            hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_NONE, true>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+    } else if (a.act == SAGA_ACT_RELU)
+        hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_RELU, false>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
     else if (a.act == SAGA_ACT_SIGMOID)
-        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_SIGMOID>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+        hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_SIGMOID, false>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
     else
-        hipLaunchKernelGGL(k_gemm_wlds<SAGA_ACT_NONE>, grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
+        hipLaunchKernelGGL((k_gemm_wlds<SAGA_ACT_NONE, false>), grid, dim3(512), 0, s, a, n_cg, wg_per_cg, (int)n_tiles_m);
     *err = hipGetLastError();
     return true;
 }
@@ -733,9 +790,11 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     if (a.dtype == SAGA_F32) {
         if (a.out_dtype != SAGA_F32) return hipErrorInvalidValue;
         hipError_t e = hipSuccess;
-        if (!a.tiled_only && launch_wlds(a, s, &e)) return e;
+        if (launch_wlds(a, s, &e)) return e;
+        if (a.row_ids) return hipErrorInvalidValue;  // the tiled kernel takes whole ranges of rows only
         return launch_typed<float, float>(a, s);
     }
+    if (a.row_ids) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
     if (a.out_dtype == SAGA_F32) {
         if (launch_wreg16<float>(a, s, &e)) return e;

@@ -750,9 +750,68 @@ saga_status hybrid_dense_launch(saga_ctx* ctx, saga_graph* view, GatherArgs* ga,
     return SAGA_OK;
 }
 
-// Section 3.2: H = X [Wgs^T | Wm^T | Wgd^T] (+ [0 | 0 | b]) once per vertex, into ctx->ws_hoist (n x 3F fp32)
-saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F)
+// The per-vertex products of Section 3.2 are read through edges only: the source parts by an edge's source, the
+// destination part by its destination. In a directed power-law graph many vertices are neither (R-MAT 20 with 32 edges
+// per vertex: 38 % have no out-edge, 38 % no in-edge), so the graph keeps the two lists of vertices that are, and the
+// products are taken over those rows. Built on the host at the first call that can use them.
+saga_status ensure_endpoints(saga_ctx* ctx, saga_graph* g)
 {
+    if (g->endpoints_built || ctx->arena_active) return SAGA_OK;  // (a call that must not allocate uses them if they are there)
+    const int64_t n = g->n;
+    std::vector<int32_t> h_row, src_rows, dst_rows;
+    try {
+        h_row.resize((size_t)std::max<int64_t>(g->nnz, 1));
+    } catch (...) {
+        return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    }
+    if (g->nnz > 0) {
+        HIP_TRY(ctx, hipMemcpyAsync(h_row.data(), g->d_row_idx.p, sizeof(int32_t) * (size_t)g->nnz, hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    try {
+        std::vector<uint8_t> has_out((size_t)std::max<int64_t>(n, 1), 0);
+        for (int64_t e = 0; e < g->nnz; ++e) has_out[(size_t)h_row[(size_t)e]] = 1;
+        for (int64_t v = 0; v < n; ++v) {
+            if (has_out[(size_t)v]) src_rows.push_back((int32_t)v);
+            if (g->h_col_ptr[(size_t)v + 1] > g->h_col_ptr[(size_t)v]) dst_rows.push_back((int32_t)v);
+        }
+        g->n_src_rows = (int64_t)src_rows.size();
+        g->n_dst_rows = (int64_t)dst_rows.size();
+        for (std::vector<int32_t>* l : {&src_rows, &dst_rows})
+            while (!l->empty() && l->size() % 64 != 0) l->push_back(l->back());
+    } catch (...) {
+        return ctx->fail(SAGA_ERR_INTERNAL, "out of host memory");
+    }
+    for (auto pr : {std::make_pair(&g->d_src_rows, &src_rows), std::make_pair(&g->d_dst_rows, &dst_rows)}) {
+        if (saga_status st = ctx->dev_alloc(pr.first, sizeof(int32_t) * std::max<size_t>(pr.second->size(), 64))) return st;
+        if (!pr.second->empty())
+            HIP_TRY(ctx, hipMemcpyAsync(pr.first->p, pr.second->data(), sizeof(int32_t) * pr.second->size(), hipMemcpyHostToDevice, ctx->stream));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // the vectors go out of scope below
+    g->endpoints_built = true;
+    return SAGA_OK;
+}
+
+// The product `hg` over the graph's listed rows (sources or destinations): the arguments with the list in place if the list
+// leaves out enough rows to pay for it and the product kernel takes lists for this shape, else unchanged (all hg.M rows).
+static GemmArgs over_endpoints(const GemmArgs& hg, const saga_graph* g, bool source_side, bool* listed)
+{
+    *listed = false;
+    if (!g || !g->endpoints_built) return hg;
+    const int64_t rows = source_side ? g->n_src_rows : g->n_dst_rows;
+    GemmArgs sub = hg;
+    sub.row_ids = static_cast<const int32_t*>(source_side ? g->d_src_rows.p : g->d_dst_rows.p);
+    sub.M = rows;
+    if (rows * 8 > hg.M * 7 || !gemm_takes_row_list(sub)) return hg;
+    *listed = true;
+    return sub;
+}
+
+// Section 3.2: H = X [Wgs^T | Wm^T | Wgd^T] (+ [0 | 0 | b]) once per vertex, into ctx->ws_hoist (n x 3F fp32)
+saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, saga_graph* g)
+{
+    if (g)
+        if (saga_status est = ensure_endpoints(ctx, g)) return est;
     hipStream_t s = ctx->stream;
     int64_t n_pad, k_pad;
     bt_padded_shape(3 * F, F, SAGA_F32, &n_pad, &k_pad);
@@ -784,14 +843,37 @@ saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_par
     hg.K = F;
     hg.dtype = hg.out_dtype = SAGA_F32;
     hg.act = SAGA_ACT_NONE;
+    // [Ps | M] for the vertices with out-edges, Pd (+ b) for those with in-edges, as two products, where at least one of
+    // them can go over a list (the product kernel that takes lists has K = 128: the packed weights then hold whole
+    // 128-row groups for either product)
+    GemmArgs src = hg, dst = hg;
+    src.N = 2 * F;
+    src.bias = nullptr;  // (its 2F entries are zeros)
+    dst.N = F;
+    dst.Bt = bt + 2 * (int64_t)F * k_pad;
+    dst.bias = bias + 2 * F;
+    dst.C = static_cast<float*>(ctx->ws_hoist.p) + 2 * F;
+    bool src_listed = false, dst_listed = false;
+    src = over_endpoints(src, g, true, &src_listed);
+    dst = over_endpoints(dst, g, false, &dst_listed);
+    if (src_listed || dst_listed) {
+        HIP_TRY(ctx, launch_gemm(src, s));
+        HIP_TRY(ctx, launch_gemm(dst, s));
+        ctx->acc.n_hoist_row_cols = src.M * src.N + dst.M * dst.N;
+        return SAGA_OK;
+    }
     HIP_TRY(ctx, launch_gemm(hg, s));
+    ctx->acc.n_hoist_row_cols = hg.M * hg.N;
     return SAGA_OK;
 }
 
 // Figure 11's ApplyEdge depends on the source only: H = sigmoid(X Wp^T + bp) once per vertex (Section 3.2),
 // into ctx->ws_hoist (n x Fm fp32)
-saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm, int32_t act)
+saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm, int32_t act,
+                       saga_graph* g)
 {
+    if (g)
+        if (saga_status est = ensure_endpoints(ctx, g)) return est;
     hipStream_t s = ctx->stream;
     int64_t n_pad, k_pad;
     bt_padded_shape(Fm, F, SAGA_F32, &n_pad, &k_pad);
@@ -814,7 +896,10 @@ saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_para
     hg.K = F;
     hg.dtype = hg.out_dtype = SAGA_F32;
     hg.act = act;
+    bool listed = false;
+    hg = over_endpoints(hg, g, true, &listed);  // pooled rows are read through an edge's source
     HIP_TRY(ctx, launch_gemm(hg, s));
+    ctx->acc.n_hoist_row_cols = hg.M * hg.N;
     return SAGA_OK;
 }
 
@@ -1248,6 +1333,7 @@ saga_status saga_reset_timings(saga_ctx* ctx)
     ctx->acc.n_dense_blocks = keep.n_dense_blocks;
     ctx->acc.n_dense_edges = keep.n_dense_edges;
     ctx->acc.n_partial_rows = keep.n_partial_rows;
+    ctx->acc.n_hoist_row_cols = keep.n_hoist_row_cols;
     return SAGA_OK;
 }
 
@@ -1360,7 +1446,7 @@ saga_status saga_graph_destroy(saga_graph* g)
     saga_ctx* ctx = g->ctx;
     DeviceGuard guard(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    for (DevBuf* b : {&g->d_row_idx, &g->d_items, &g->d_heavy, &g->d_edge_data}) ctx->dev_free(b);
+    for (DevBuf* b : {&g->d_row_idx, &g->d_items, &g->d_heavy, &g->d_edge_data, &g->d_src_rows, &g->d_dst_rows}) ctx->dev_free(b);
     for (auto& sl : g->saved_lists) {
         ctx->dev_free(&sl.items);
         ctx->dev_free(&sl.heavy);
@@ -1480,7 +1566,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
     ga.accumulate = 0;
 
     if (ep->op == SAGA_EDGE_GATED) {
-        if (saga_status st = hoist_gated(ctx, X, ep, n, F)) return st;
+        if (saga_status st = hoist_gated(ctx, X, ep, n, F, g)) return st;
         ga.src = ctx->ws_hoist.p;
         ga.ld_src = 3 * (int64_t)F;
         ga.src2 = static_cast<const float*>(ctx->ws_hoist.p) + F;
@@ -1491,7 +1577,7 @@ static saga_status resident_forward(saga_ctx* ctx, saga_graph* g, const saga_ten
         if (es) es->has_hoist = true;
     } else if (pool) {
         // then the propagation kernel gathers rows of H
-        if (saga_status st = hoist_pool(ctx, X, ep, n, F, Fm)) return st;
+        if (saga_status st = hoist_pool(ctx, X, ep, n, F, Fm, SAGA_ACT_SIGMOID, g)) return st;
         ga.src = ctx->ws_hoist.p;
         ga.ld_src = Fm;
         ga.dtype = SAGA_F32;

@@ -289,6 +289,12 @@ struct saga_graph {
     // the same edges grouped by source (backward-Scatter gathers over out-edges): built at the
     // first backward call. tr's columns are this graph's sources; perm[e'] is the position in
     // this graph's edge order of the transposed graph's edge e'.
+    // the vertices with out-edges and those with in-edges, ascending, each list padded to a multiple of 64 entries with its
+    // last one: the per-vertex products of a gated or pooled ApplyEdge (Section 3.2) are needed for edge endpoints only
+    // (ensure_endpoints; built at the first call that can use them)
+    DevBuf d_src_rows, d_dst_rows;
+    int64_t n_src_rows = 0, n_dst_rows = 0;
+    bool endpoints_built = false;
     HybridDevice hyb;
     saga_graph* tr = nullptr;
     DevBuf d_perm;
@@ -447,8 +453,13 @@ struct GemmArgs {
     int32_t dtype;      // of A and Bt
     int32_t out_dtype;  // of C
     int32_t act;
+    // optional: the product over a list of M rows. Row i of the product reads row row_ids[i] of A and writes row
+    // row_ids[i] of C. The list is 16-byte aligned device memory of M rounded up to a multiple of 64 entries, the last
+    // entry repeated. Only where gemm_takes_row_list says so (the fp32 kernel with the weights resident in LDS).
+    const int32_t* row_ids;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+bool gemm_takes_row_list(const GemmArgs& a);  // a with row_ids set: would launch_gemm run it?
 // The dense-block form of a bf16 sum propagation (hybrid.hip) over one edge order of a graph: the plan and its device
 // copy (ensure_hybrid; view->hyb.usable says whether the graph has blocks worth it), whether a call qualifies
 // (hybrid_applies: options, rows of a multiple of 128 bf16 values, 16-byte aligned), the launch of the dense half
@@ -509,11 +520,14 @@ hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream
 // resident graph: make the work list for rows of `row_bytes` current (saga_api.hip)
 saga_status ensure_work_list(saga_ctx* ctx, saga_graph* g, int64_t row_bytes, int32_t width = 0);
 // per-vertex products of a gated ApplyEdge into ctx->ws_hoist, rows [Ps | M | Pd (+ b)] (saga_api.hip)
-saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F);
+// g (nullable): the resident graph whose edges will read the rows; with it, rows of vertices that are no edge's endpoint
+// are left unwritten where the product kernel can take a list of rows
+saga_status hoist_gated(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, saga_graph* g = nullptr);
+saga_status ensure_endpoints(saga_ctx* ctx, saga_graph* g);
 // per-vertex messages of a max-pooling ApplyEdge into ctx->ws_hoist, n x Fm (saga_api.hip)
 // act: SAGA_ACT_SIGMOID for the pooled rows themselves, SAGA_ACT_NONE for their pre-activations (backward pass)
 saga_status hoist_pool(saga_ctx* ctx, const saga_tensor* X, const saga_edge_params* ep, int64_t n, int32_t F, int32_t Fm,
-                       int32_t act = SAGA_ACT_SIGMOID);
+                       int32_t act = SAGA_ACT_SIGMOID, saga_graph* g = nullptr);
 // backward pass of a resident layer (backward.hip)
 saga_status resident_backward(saga_ctx* ctx, saga_graph* g, const saga_tensor* X, const saga_tensor* A, const saga_tensor* Y,
                               const saga_tensor* dY, const saga_edge_params* ep, int32_t agg, const saga_vertex_params* vp,

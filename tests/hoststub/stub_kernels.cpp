@@ -166,7 +166,16 @@ void gemm_cpu(const GemmArgs a)
             const bool inside = n < a.N && (k < a.K || (k >= kp && k < kp + a.K2));
             if (n < a.N && !inside && !(b == b && std::fabs(b) < 3e38f)) die("padding of the packed weights is not finite");
         }
-    for (int64_t m = 0; m < a.M; ++m)
+    if (a.row_ids) {  // the list is padded to whole tiles of 64 rows with its last entry, ascending before that
+        if (a.A2 || a.dtype != SAGA_F32) die("a row list on a product that does not take one");
+        const int64_t padded = (a.M + 63) / 64 * 64;
+        for (int64_t i = 0; i < padded; ++i) {
+            if (a.row_ids[i] < 0) die("negative row in a row list");
+            if (i > 0 && (i < a.M ? a.row_ids[i] <= a.row_ids[i - 1] : a.row_ids[i] != a.row_ids[a.M - 1])) die("row list out of order or badly padded");
+        }
+    }
+    for (int64_t i = 0; i < a.M; ++i) {
+        const int64_t m = a.row_ids ? a.row_ids[i] : i;
         for (int32_t n = 0; n < a.N; ++n) {
             double s = 0.0;
             for (int32_t k = 0; k < a.K; ++k) s += (double)load_elem(a.A, m * a.lda + k, a.dtype) * load_elem(a.Bt, (int64_t)n * a.ldbt + k, a.dtype);
@@ -179,6 +188,7 @@ void gemm_cpu(const GemmArgs a)
             else
                 static_cast<uint16_t*>(a.C)[m * a.ldc + n] = f32_to_bf16(y);
         }
+    }
 }
 
 }  // namespace
@@ -343,9 +353,21 @@ void bt_padded_shape(int32_t N, int32_t K, int32_t dtype, int64_t* n_pad, int64_
     *k_pad = ((int64_t)K + kt - 1) / kt * kt;
 }
 
+static int64_t g_row_list_launches = 0;
+extern "C" int64_t stub_row_list_launches() { return g_row_list_launches; }
+
+// the real product kernel that takes row lists wants K = 128 and at least 16,384 rows; the stand-in takes lists from 64 rows
+// on, so that small graphs reach the host code that builds and hands over the lists
+bool gemm_takes_row_list(const GemmArgs& a)
+{
+    return a.row_ids && a.dtype == SAGA_F32 && a.out_dtype == SAGA_F32 && !a.tiled_only && !a.A2 && a.K == 128 && a.M >= 64;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (a.row_ids && !gemm_takes_row_list(a)) return hipErrorInvalidValue;
+    if (a.row_ids) ++g_row_list_launches;
     if (a.K <= 0 || (a.A2 && a.K2 <= 0)) return hipErrorInvalidValue;
     if (a.dtype == SAGA_F32 && a.out_dtype != SAGA_F32) return hipErrorInvalidValue;
     const GemmArgs copy = a;

@@ -34,7 +34,7 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(binding.EdgeParams) == 7 * 8
     assert ctypes.sizeof(binding.VertexParams) == 4 * 8
     assert ctypes.sizeof(binding.LayerGrads) == 9 * 8
-    assert ctypes.sizeof(binding.Timings) == 8 + 5 * 8 + 3 * 8 + 8 + 3 * 4 + 4 + 2 * 8 + 8 + 3 * 8
+    assert ctypes.sizeof(binding.Timings) == 8 + 5 * 8 + 3 * 8 + 8 + 3 * 4 + 4 + 2 * 8 + 8 + 4 * 8
 
 
 def test_null_arguments_are_rejected_without_a_gpu():

@@ -78,3 +78,9 @@ def test_max_over_gated_messages_from_host_memory(stub_lib):
     """The streamed forward call keeps its Gather output (accum_out in host memory) and the streamed backward call of max
     over gated messages carries those maxima through both chunk schedules as a third row per vertex."""
     _run("run_gated_max.py", stub_lib)
+
+
+def test_products_over_endpoint_lists(stub_lib):
+    """Gated and pooled layers on a directed graph with many vertices without in- or out-edges: the per-vertex products
+    go over the graph's lists of edge endpoints (forward, backward, the call that must not allocate)."""
+    _run("run_endpoints.py", stub_lib)
