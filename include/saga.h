@@ -188,6 +188,10 @@ saga_status saga_graph_set_edge_data(saga_graph* g, const float* edge_weight);
  * destination parts Pd of the resident interval are formed beside its accumulator from the
  * interval's own rows of X), so the host link carries X only; with W_self the interval's own
  * rows of X are copied in tile by tile for the second operand of the ApplyVertex product.
+ * Resident calls form the per-vertex products for edge endpoints only where that saves at least
+ * an eighth of them (the source parts for vertices with out-edges, the destination part for
+ * vertices with in-edges; the lists are built at the first GATED or POOL call on the graph,
+ * which synchronises the stream).
  *
  * Arithmetic: fp32 accumulation everywhere. BF16: X, W bf16; A is rounded to
  * bf16 (nearest even) once before the ApplyVertex product; Y is rounded to

@@ -161,3 +161,40 @@ def test_stage_by_stage_propagation_equals_the_fused_operator(dtype, edge_op, ag
             run_gpu(c0, wg, gg)
         assert e.value.status == 3
         gg.destroy()
+
+
+@pytest.mark.parametrize("op", ["gated", "pool"])
+def test_per_vertex_products_over_the_edge_endpoints_only(ctx, op):
+    """Configuration 4's directed graph at R-MAT 16 with rows of 128 features: a third of the vertices have no out-edge,
+    a third no in-edge, and the per-vertex products of the gated and of the pooled ApplyEdge (Section 3.2) are formed for
+    edge endpoints only (the two lists end in ragged tiles). The whole layer against the oracle, the number of products
+    formed against the degree counts, and a second call on the same handle gives the same bits."""
+    import oracle
+    wl = si.workload(4, scale=16)
+    g = wl.graph
+    n, F = wl.X.shape
+    cp, ri = g.col_ptr.numpy(), g.row_idx.numpy()
+    n_dst, n_src = int((np.diff(cp) > 0).sum()), int((np.bincount(ri, minlength=n) > 0).sum())
+    assert n_dst % 64 and n_src % 64 and 16384 <= n_dst <= n * 7 // 8 and 16384 <= n_src <= n * 7 // 8
+    if op == "gated":
+        kw = dict(edge_op="gated", W_gate=wl.W_gate.cuda(), b_gate=wl.b_gate.cuda(), W_msg=wl.W_msg.cuda())
+        ref = oracle.layer(cp, ri, wl.X.numpy(), "gated", W=wl.W.numpy(), act="relu", b_gate=wl.b_gate.numpy(),
+                           hoisted=oracle.hoist(wl.X.numpy(), wl.W_gate.numpy(), wl.W_msg.numpy()))
+        formed = n_src * 2 * F + n_dst * F
+    else:
+        Wp, bp = si.glorot_uniform(F, F, 71).T.contiguous(), si.uniform_pm(F, 0.2, 72)
+        kw = dict(edge_op="pool", W_pool=Wp.cuda(), b_pool=bp.cuda())
+        ref = oracle.layer(cp, ri, wl.X.numpy(), "pool", agg="sum", W=wl.W.numpy(), act="relu", W_pool=Wp.numpy(), b_pool=bp.numpy())
+        formed = n_src * F
+    graph = make_graph(ctx, g)
+    X, W = wl.X.cuda(), wl.W.cuda()
+    Y = torch.full((n, wl.W.shape[1]), float("nan"), device="cuda")
+    ctx.layer_forward(graph, X, Y, W=W, act="relu", **kw)
+    torch.cuda.synchronize()
+    assert ctx.get_timings()["n_hoist_row_cols"] == formed
+    assert_sum_close(Y.cpu().numpy(), ref["Y"], ref["Y_abs"], TOL_F32, f"{op} layer at R-MAT 16")
+    Y2 = torch.full_like(Y, float("nan"))
+    ctx.layer_forward(graph, X, Y2, W=W, act="relu", **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+    graph.destroy()
